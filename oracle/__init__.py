@@ -1,0 +1,186 @@
+"""CPU oracle (fp64, plain C) -- TEST INFRASTRUCTURE ONLY.
+
+Thin numpy front-end over ``tma_oracle.c``.  Nothing here is imported by the
+product package; only ``tests/``, the smoke check and the benchmark's
+``cpu_baseline`` leg use it.  It never imports the HIP binding.
+
+Every function converts its floating-point arguments to fp64 and returns fp64.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+import subprocess
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "tma_oracle.c")
+_LIB = os.path.join(_HERE, "libtma_oracle.so")
+
+
+def build(force: bool = False) -> str:
+    """Compile the C oracle with gcc (host only)."""
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+        subprocess.check_call(
+            ["gcc", "-O2", "-std=c11", "-Wall", "-Wextra", "-shared", "-fPIC",
+             "-o", _LIB, _SRC, "-lm"])
+    return _LIB
+
+
+_lib = None
+
+
+def lib():
+    global _lib
+    if _lib is None:
+        _lib = C.CDLL(build())
+        _lib.orc_mix64.restype = C.c_uint64
+        _lib.orc_mix64.argtypes = [C.c_uint64, C.c_uint64]
+        _lib.orc_softmax_ce.restype = C.c_double
+        _lib.orc_sigmoid_l2.restype = C.c_double
+    return _lib
+
+
+def _p(a):
+    return None if a is None else a.ctypes.data_as(C.c_void_p)
+
+
+def _f64(a):
+    return np.ascontiguousarray(a, dtype=np.float64)
+
+
+def _i32(a):
+    return np.ascontiguousarray(a, dtype=np.int32)
+
+
+def _i64(a):
+    return np.ascontiguousarray(a, dtype=np.int64)
+
+
+# ---------------------------------------------------------------- partition
+def mix64(seed: int, idx: int) -> int:
+    return int(lib().orc_mix64(C.c_uint64(seed), C.c_uint64(idx)))
+
+
+def partition(n_nodes: int, K: int, seed: int, cluster=None) -> np.ndarray:
+    """part[v] in [0,K): RandomTMA (cluster None) or SuperTMA (Sec. 3.2.2)."""
+    part = np.empty(n_nodes, dtype=np.int32)
+    cl = None if cluster is None else _i32(cluster)
+    lib().orc_partition(C.c_int64(n_nodes), _p(cl), C.c_int32(K), C.c_uint64(seed), _p(part))
+    return part
+
+
+# ---------------------------------------------------------- induced subgraph
+def induced_subgraph(rowptr, colidx, part, p: int):
+    """Node-induced subgraph of partition p (Preliminaries).
+
+    Returns dict(g2l, l2g, rowptr, colidx, inv_deg) in the canonical local
+    numbering (rank by global id, neighbour order kept).
+    """
+    rowptr, colidx, part = _i64(rowptr), _i32(colidx), _i32(part)
+    n = rowptr.shape[0] - 1
+    n_loc, nnz_loc = C.c_int64(0), C.c_int64(0)
+    lib().orc_induced_count(C.c_int64(n), _p(rowptr), _p(colidx), _p(part), C.c_int32(p),
+                            C.byref(n_loc), C.byref(nnz_loc))
+    n_loc, nnz_loc = n_loc.value, nnz_loc.value
+    g2l = np.empty(n, dtype=np.int32)
+    l2g = np.empty(n_loc, dtype=np.int32)
+    rp = np.empty(n_loc + 1, dtype=np.int32)
+    ci = np.empty(nnz_loc, dtype=np.int32)
+    inv = np.empty(n_loc, dtype=np.float64)
+    lib().orc_induced_fill(C.c_int64(n), _p(rowptr), _p(colidx), _p(part), C.c_int32(p),
+                           _p(g2l), _p(l2g), _p(rp), _p(ci), _p(inv))
+    return dict(g2l=g2l, l2g=l2g, rowptr=rp, colidx=ci, inv_deg=inv)
+
+
+# -------------------------------------------------------------- aggregation
+def mean_aggregate(rowptr, colidx, H) -> np.ndarray:
+    rowptr, colidx, H = _i32(rowptr), _i32(colidx), _f64(H)
+    n, F = H.shape
+    M = np.empty_like(H)
+    lib().orc_mean_aggregate(C.c_int64(n), _p(rowptr), _p(colidx), _p(H), C.c_int64(F), _p(M))
+    return M
+
+
+def mean_aggregate_T(rowptr, colidx, G) -> np.ndarray:
+    rowptr, colidx, G = _i32(rowptr), _i32(colidx), _f64(G)
+    n, F = G.shape
+    out = np.empty_like(G)
+    lib().orc_mean_aggregate_T(C.c_int64(n), _p(rowptr), _p(colidx), _p(G), C.c_int64(F), _p(out))
+    return out
+
+
+# -------------------------------------------------------------------- layer
+ACT_NONE, ACT_RELU = 0, 1
+
+
+def sage_layer_fwd(rowptr, colidx, H, W_self, W_neigh, bias, act: int):
+    """Returns (M, Z, Hnext) of one mean-SAGE layer."""
+    rowptr, colidx = _i32(rowptr), _i32(colidx)
+    H, W_self, W_neigh, bias = _f64(H), _f64(W_self), _f64(W_neigh), _f64(bias)
+    n, F_in = H.shape
+    F_out = W_self.shape[1]
+    assert W_self.shape == (F_in, F_out) and W_neigh.shape == (F_in, F_out) and bias.shape == (F_out,)
+    M = np.empty((n, F_in))
+    Z = np.empty((n, F_out))
+    Hn = np.empty((n, F_out))
+    lib().orc_sage_layer_fwd(C.c_int64(n), _p(rowptr), _p(colidx), _p(H), C.c_int64(F_in),
+                             _p(W_self), _p(W_neigh), _p(bias), C.c_int64(F_out), C.c_int(act),
+                             _p(M), _p(Z), _p(Hn))
+    return M, Z, Hn
+
+
+def sage_layer_bwd(rowptr, colidx, H, M, Z, dHnext, W_self, W_neigh, act: int, need_dH=True):
+    """Returns (dW_self, dW_neigh, dbias, dH or None)."""
+    rowptr, colidx = _i32(rowptr), _i32(colidx)
+    H, M, Z, dHnext = _f64(H), _f64(M), _f64(Z), _f64(dHnext)
+    W_self, W_neigh = _f64(W_self), _f64(W_neigh)
+    n, F_in = H.shape
+    F_out = W_self.shape[1]
+    dWs = np.empty((F_in, F_out))
+    dWn = np.empty((F_in, F_out))
+    db = np.empty(F_out)
+    dH = np.empty((n, F_in)) if need_dH else None
+    sM = np.empty((n, F_in))
+    sZ = np.empty((n, F_out))
+    lib().orc_sage_layer_bwd(C.c_int64(n), _p(rowptr), _p(colidx), _p(H), _p(M), _p(Z), _p(dHnext),
+                             _p(W_self), _p(W_neigh), C.c_int64(F_in), C.c_int64(F_out), C.c_int(act),
+                             _p(dWs), _p(dWn), _p(db), _p(dH), _p(sM), _p(sZ))
+    return dWs, dWn, db, dH
+
+
+# ------------------------------------------------------------------- losses
+def softmax_ce(logits, labels, need_grad=True):
+    logits, labels = _f64(logits), _i32(labels)
+    n, Cc = logits.shape
+    d = np.empty_like(logits) if need_grad else None
+    loss = lib().orc_softmax_ce(C.c_int64(n), C.c_int64(Cc), _p(logits), _p(labels), _p(d))
+    return float(loss), d
+
+
+def sigmoid_l2(G, Y, need_grad=True):
+    G, Y = _f64(G), _f64(Y)
+    n, Cc = G.shape
+    d = np.empty_like(G) if need_grad else None
+    loss = lib().orc_sigmoid_l2(C.c_int64(n), C.c_int64(Cc), _p(G), _p(Y), _p(d))
+    return float(loss), d
+
+
+# ------------------------------------------------------ optimizer / averaging
+def sgd_step(W, dW, lr: float) -> np.ndarray:
+    W = _f64(W).copy()
+    dW = _f64(dW)
+    lib().orc_sgd_step(C.c_int64(W.size), _p(W), _p(dW), C.c_double(lr))
+    return W
+
+
+def average(W_stack, active_mask: int | None = None):
+    """phi = mean over active trainers.  W_stack [M, P] -> (W_after [M,P], W_global [P])."""
+    W = _f64(W_stack).copy()
+    M, P = W.shape
+    if active_mask is None:
+        active_mask = (1 << M) - 1
+    Wg = np.zeros(P)
+    lib().orc_average(C.c_int32(M), C.c_int64(P), C.c_uint64(active_mask), _p(W), _p(Wg))
+    return W, Wg

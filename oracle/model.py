@@ -1,0 +1,109 @@
+"""Oracle compositions: the L-layer local trainer step and the TMA loops.
+
+TEST INFRASTRUCTURE ONLY (see ``oracle/__init__.py``).  Built from the layer
+functions of the C oracle, in fp64, in the order the paper's Alg. 2 gives for
+one trainer iteration: forward on the local subgraph, loss, backward, optimizer
+step; and, for several trainers, Alg. 1's aggregate-and-overwrite.
+"""
+from __future__ import annotations
+
+import numpy as np
+
+from . import (ACT_NONE, ACT_RELU, average, sage_layer_bwd, sage_layer_fwd,
+               sgd_step, softmax_ce)
+
+
+def forward(rowptr, colidx, X, params):
+    """ReLU between layers, identity on the last.  Returns (logits, saved)."""
+    H = np.asarray(X, dtype=np.float64)
+    saved = []
+    L = len(params)
+    for l, (Ws, Wn, b) in enumerate(params):
+        act = ACT_RELU if l < L - 1 else ACT_NONE
+        M, Z, Hn = sage_layer_fwd(rowptr, colidx, H, Ws, Wn, b, act)
+        saved.append((H, M, Z, act))
+        H = Hn
+    return H, saved
+
+
+def loss_and_grads(rowptr, colidx, X, y, params):
+    """Mean softmax-CE over all local nodes and d(loss)/d(params)."""
+    logits, saved = forward(rowptr, colidx, X, params)
+    loss, d = softmax_ce(logits, y)
+    grads = [None] * len(params)
+    for l in range(len(params) - 1, -1, -1):
+        H, M, Z, act = saved[l]
+        Ws, Wn, _ = params[l]
+        dWs, dWn, db, dH = sage_layer_bwd(rowptr, colidx, H, M, Z, d, Ws, Wn, act, need_dH=l > 0)
+        grads[l] = (dWs, dWn, db)
+        d = dH
+    return loss, grads, logits, saved
+
+
+def train_step(rowptr, colidx, X, y, params, lr):
+    """One Alg. 2 iteration on the full local subgraph; returns (loss, new params)."""
+    loss, grads, _, _ = loss_and_grads(rowptr, colidx, X, y, params)
+    new = [tuple(sgd_step(w, g, lr).reshape(np.shape(w)) for w, g in zip(pl, gl))
+           for pl, gl in zip(params, grads)]
+    return loss, new
+
+
+def flatten(params) -> np.ndarray:
+    """Flat parameter vector, layer by layer: W_self, W_neigh, b."""
+    return np.concatenate([np.asarray(t, dtype=np.float64).ravel() for layer in params for t in layer])
+
+
+def unflatten(flat, like):
+    out, o = [], 0
+    for layer in like:
+        cur = []
+        for t in layer:
+            sz = int(np.prod(np.shape(t)))
+            cur.append(np.asarray(flat[o:o + sz]).reshape(np.shape(t)))
+            o += sz
+        out.append(tuple(cur))
+    return out
+
+
+def aggregate(params_per_trainer, active_mask=None):
+    """Alg. 1 aggregation line + Alg. 2 overwrite, on structured parameters."""
+    stack = np.stack([flatten(p) for p in params_per_trainer])
+    after, w_global = average(stack, active_mask)
+    return [unflatten(after[i], params_per_trainer[i]) for i in range(len(params_per_trainer))], w_global
+
+
+def tma_schedule(step_time, n_trainers: int, dt_int: float, dt_train: float):
+    """Idealised timeline of Alg. 1 (server) and Alg. 2 (trainers).
+
+    ``step_time(i, k)`` is the duration of trainer i's k-th optimizer call.
+    The server raises the aggregation flag once ``now - T_agg >= dt_int``; a
+    trainer sees the flag only after finishing the step it is in, then blocks
+    until the averaged weights come back, which happens when the slowest
+    trainer has delivered.  Reading taken where the listing is silent: T_agg is
+    reset to the time the broadcast completes (otherwise every poll after the
+    first interval would aggregate).  The stop flag is raised once
+    ``now - T_start > dt_train``; a trainer checks it at the top of its loop.
+
+    Returns (rounds, final_steps): rounds[r][i] = steps trainer i had finished
+    when round r's weights were collected.
+    """
+    t = [0.0] * n_trainers
+    steps = [0] * n_trainers
+    t_agg = 0.0
+    rounds = []
+    while t_agg + dt_int <= dt_train:
+        t_flag = t_agg + dt_int
+        for i in range(n_trainers):
+            while True:
+                t[i] += step_time(i, steps[i])
+                steps[i] += 1
+                if t[i] >= t_flag:
+                    break
+        t_agg = max(t)
+        t = [t_agg] * n_trainers
+        rounds.append(list(steps))
+    for i in range(n_trainers):
+        while t[i] <= dt_train:
+            t[i] += step_time(i, steps[i])
+            steps[i] += 1
+    return rounds, steps

@@ -1,0 +1,303 @@
+/*
+ * CPU oracle for one TMA trainer's local training path.
+ *
+ * TEST INFRASTRUCTURE ONLY.  This file is the slow, plain definition of what
+ * the GPU library computes.  It shares no code, header, table or helper with
+ * the HIP sources; nothing in the product path may call it.  Only the test
+ * suite, the smoke check and the benchmark's CPU-baseline leg load it.
+ *
+ * Everything floating point is fp64, single-threaded, written as the
+ * definition reads: adjacency scanned entry by entry, matrix products as
+ * triple loops, no blocking, no fusion.
+ *
+ * Passages of the paper each function follows are named in its comment
+ * (Preliminaries = the paragraph defining alpha, alpha^-1 and the node-induced
+ * subgraph; Sec. 3.2.2 = the two randomized partition schemes; Thm. 1 and its
+ * proof in App. B = the row-normalised one-layer model, its L2 loss and the
+ * chain rule; Alg. 1/2 = server and trainer loops).
+ *
+ * Pins (see tests/test_oracle_*.py): published SplitMix64 test vector,
+ * partition invariants and the 1/M kept-edge ratio the paper prints, brute
+ * force edge filtering, dense-matrix products, the closed-form initial
+ * gradient from the proof of Thm. 1, the expected neighbour mean
+ * [(1-h), h], central finite differences and the adjoint identity.
+ * The composed multi-layer training step has no value printed in the paper:
+ * it is pinned only through its parts plus finite differences.
+ */
+#include <math.h>
+#include <stddef.h>
+#include <stdint.h>
+#include <string.h>
+
+/* ------------------------------------------------------------------------
+ * Random assignment (Sec. 3.2.2): every node, or every super-node, goes
+ * independently and uniformly to one of K partitions.  The paper fixes no
+ * generator; this build's written spec is
+ *     z    = SplitMix64 output number (id+1) of the stream seeded with `seed`
+ *     part = floor(z * K / 2^64)
+ * SplitMix64 (Steele, Lea, Flood 2014): state += 0x9E3779B97F4A7C15 per draw,
+ * output = finaliser(state).
+ * ---------------------------------------------------------------------- */
+uint64_t orc_mix64(uint64_t seed, uint64_t id)
+{
+    uint64_t z = seed + (id + 1u) * 0x9E3779B97F4A7C15ull;
+    z = (z ^ (z >> 30)) * 0xBF58476D1CE4E5B9ull;
+    z = (z ^ (z >> 27)) * 0x94D049BB133111EBull;
+    return z ^ (z >> 31);
+}
+
+static int32_t uniform_k(uint64_t seed, uint64_t id, int32_t K)
+{
+    unsigned __int128 wide = (unsigned __int128)orc_mix64(seed, id) * (uint64_t)K;
+    return (int32_t)(wide >> 64);
+}
+
+/* cluster == NULL: RandomTMA, the unit of randomness is the node.
+ * cluster != NULL: SuperTMA, the unit is the super-node cluster[v]; a node
+ * inherits the partition of its super-node. */
+void orc_partition(int64_t n_nodes, const int32_t *cluster, int32_t K,
+                   uint64_t seed, int32_t *part)
+{
+    for (int64_t v = 0; v < n_nodes; ++v) {
+        uint64_t unit = cluster ? (uint64_t)cluster[v] : (uint64_t)v;
+        part[v] = uniform_k(seed, unit, K);
+    }
+}
+
+/* ------------------------------------------------------------------------
+ * Node-induced subgraph of partition p (Preliminaries):
+ *   V^(p) = { v : part[v] = p },  E^(p) = { (u,v) in E : u, v in V^(p) }.
+ * Canonical form so that the result is unique: local id = rank of the global
+ * id inside V^(p); neighbours keep the order of the input row.
+ * ---------------------------------------------------------------------- */
+void orc_induced_count(int64_t n_nodes, const int64_t *rowptr, const int32_t *colidx,
+                       const int32_t *part, int32_t p,
+                       int64_t *n_loc, int64_t *nnz_loc)
+{
+    int64_t nl = 0, el = 0;
+    for (int64_t v = 0; v < n_nodes; ++v) {
+        if (part[v] != p) continue;
+        ++nl;
+        for (int64_t e = rowptr[v]; e < rowptr[v + 1]; ++e)
+            if (part[colidx[e]] == p) ++el;
+    }
+    *n_loc = nl;
+    *nnz_loc = el;
+}
+
+void orc_induced_fill(int64_t n_nodes, const int64_t *rowptr, const int32_t *colidx,
+                      const int32_t *part, int32_t p,
+                      int32_t *g2l,        /* [n_nodes], -1 outside the part */
+                      int32_t *l2g,        /* [n_loc] */
+                      int32_t *rowptr_loc, /* [n_loc+1] */
+                      int32_t *colidx_loc, /* [nnz_loc] */
+                      double *inv_deg)     /* [n_loc], 0 for isolated nodes */
+{
+    int32_t nl = 0;
+    for (int64_t v = 0; v < n_nodes; ++v) {
+        if (part[v] == p) { g2l[v] = nl; l2g[nl] = (int32_t)v; ++nl; }
+        else g2l[v] = -1;
+    }
+    int32_t el = 0;
+    rowptr_loc[0] = 0;
+    for (int32_t i = 0; i < nl; ++i) {
+        int64_t v = l2g[i];
+        for (int64_t e = rowptr[v]; e < rowptr[v + 1]; ++e) {
+            int32_t u = colidx[e];
+            if (part[u] == p) colidx_loc[el++] = g2l[u];
+        }
+        rowptr_loc[i + 1] = el;
+        int32_t d = rowptr_loc[i + 1] - rowptr_loc[i];
+        inv_deg[i] = d > 0 ? 1.0 / (double)d : 0.0;
+    }
+}
+
+/* ------------------------------------------------------------------------
+ * Mean aggregation with the row-normalised adjacency (Thm. 1 and the first
+ * equation of its proof): m_v = sum_{u in N'(v)} x_u / d_v, over the
+ * effective (local) neighbourhood.  A node with no local neighbour gets 0.
+ * ---------------------------------------------------------------------- */
+void orc_mean_aggregate(int64_t n, const int32_t *rowptr, const int32_t *colidx,
+                        const double *H, int64_t F, double *M)
+{
+    for (int64_t v = 0; v < n; ++v) {
+        double *m = M + v * F;
+        for (int64_t f = 0; f < F; ++f) m[f] = 0.0;
+        int32_t d = rowptr[v + 1] - rowptr[v];
+        if (d == 0) continue;
+        for (int32_t e = rowptr[v]; e < rowptr[v + 1]; ++e) {
+            const double *h = H + (int64_t)colidx[e] * F;
+            for (int64_t f = 0; f < F; ++f) m[f] += h[f];
+        }
+        for (int64_t f = 0; f < F; ++f) m[f] /= (double)d;
+    }
+}
+
+/* Transposed operator: out = Abar^T G, i.e. every entry (v,u) of the CSR
+ * sends G_v / d_v to row u.  Written as a scatter so that it does not rely on
+ * the graph being symmetric. */
+void orc_mean_aggregate_T(int64_t n, const int32_t *rowptr, const int32_t *colidx,
+                          const double *G, int64_t F, double *out)
+{
+    memset(out, 0, (size_t)(n * F) * sizeof(double));
+    for (int64_t v = 0; v < n; ++v) {
+        int32_t d = rowptr[v + 1] - rowptr[v];
+        if (d == 0) continue;
+        const double *g = G + v * F;
+        for (int32_t e = rowptr[v]; e < rowptr[v + 1]; ++e) {
+            double *o = out + (int64_t)colidx[e] * F;
+            for (int64_t f = 0; f < F; ++f) o[f] += g[f] / (double)d;
+        }
+    }
+}
+
+/* ------------------------------------------------------------------------
+ * One mean-aggregation GraphSAGE layer.  The paper names the encoder and, in
+ * Thm. 1, writes its aggregation as Abar X W; the layer used here is
+ *     M = Abar H,  Z = H W_self + M W_neigh + 1 b^T,  H' = act(Z)
+ * with act = identity (0) or ReLU (1).  W_* are [F_in, F_out] row-major.
+ * ---------------------------------------------------------------------- */
+void orc_sage_layer_fwd(int64_t n, const int32_t *rowptr, const int32_t *colidx,
+                        const double *H, int64_t F_in,
+                        const double *W_self, const double *W_neigh, const double *bias,
+                        int64_t F_out, int act,
+                        double *M, double *Z, double *Hnext)
+{
+    orc_mean_aggregate(n, rowptr, colidx, H, F_in, M);
+    for (int64_t v = 0; v < n; ++v) {
+        double *z = Z + v * F_out;
+        for (int64_t o = 0; o < F_out; ++o) z[o] = bias[o];
+        for (int64_t k = 0; k < F_in; ++k) {
+            double h = H[v * F_in + k], m = M[v * F_in + k];
+            for (int64_t o = 0; o < F_out; ++o)
+                z[o] += h * W_self[k * F_out + o] + m * W_neigh[k * F_out + o];
+        }
+        for (int64_t o = 0; o < F_out; ++o)
+            Hnext[v * F_out + o] = (act == 1) ? (z[o] > 0.0 ? z[o] : 0.0) : z[o];
+    }
+}
+
+/* Chain rule through the layer (the proof of Thm. 1 writes the one-layer
+ * instance: dL/dw = dL/dz * dz/dg * dg/dw):
+ *   dZ = dH' (.) act'(Z)
+ *   dW_self = H^T dZ,  dW_neigh = M^T dZ,  db = column sums of dZ
+ *   dH = dZ W_self^T + Abar^T (dZ W_neigh^T)        (skipped when dH == NULL)
+ * scratch: n*F_in doubles. */
+void orc_sage_layer_bwd(int64_t n, const int32_t *rowptr, const int32_t *colidx,
+                        const double *H, const double *M, const double *Z,
+                        const double *dHnext,
+                        const double *W_self, const double *W_neigh,
+                        int64_t F_in, int64_t F_out, int act,
+                        double *dW_self, double *dW_neigh, double *dbias,
+                        double *dH, double *scratch_dM, double *scratch_dZ)
+{
+    double *dZ = scratch_dZ;
+    for (int64_t i = 0; i < n * F_out; ++i)
+        dZ[i] = (act == 1) ? (Z[i] > 0.0 ? dHnext[i] : 0.0) : dHnext[i];
+
+    for (int64_t i = 0; i < F_in * F_out; ++i) dW_self[i] = dW_neigh[i] = 0.0;
+    for (int64_t o = 0; o < F_out; ++o) dbias[o] = 0.0;
+    for (int64_t v = 0; v < n; ++v) {       /* sums over nodes, one node at a time */
+        const double *g = dZ + v * F_out;
+        for (int64_t k = 0; k < F_in; ++k) {
+            double h = H[v * F_in + k], m = M[v * F_in + k];
+            for (int64_t o = 0; o < F_out; ++o) {
+                dW_self[k * F_out + o] += h * g[o];
+                dW_neigh[k * F_out + o] += m * g[o];
+            }
+        }
+        for (int64_t o = 0; o < F_out; ++o) dbias[o] += g[o];
+    }
+    if (!dH) return;
+
+    double *dM = scratch_dM;
+    for (int64_t v = 0; v < n; ++v)
+        for (int64_t k = 0; k < F_in; ++k) {
+            double s = 0.0, t = 0.0;
+            for (int64_t o = 0; o < F_out; ++o) {
+                s += dZ[v * F_out + o] * W_self[k * F_out + o];
+                t += dZ[v * F_out + o] * W_neigh[k * F_out + o];
+            }
+            dH[v * F_in + k] = s;
+            dM[v * F_in + k] = t;
+        }
+    /* dH += Abar^T dM, as a scatter */
+    for (int64_t v = 0; v < n; ++v) {
+        int32_t d = rowptr[v + 1] - rowptr[v];
+        if (d == 0) continue;
+        for (int32_t e = rowptr[v]; e < rowptr[v + 1]; ++e) {
+            double *o = dH + (int64_t)colidx[e] * F_in;
+            for (int64_t k = 0; k < F_in; ++k) o[k] += dM[v * F_in + k] / (double)d;
+        }
+    }
+}
+
+/* ------------------------------------------------------------------------
+ * Losses.
+ * Softmax cross-entropy, mean over the n local nodes (this build's reading
+ * for workloads that carry class labels; the paper's own task head is out of
+ * scope).  dlogits = (softmax - onehot) / n.
+ * ---------------------------------------------------------------------- */
+double orc_softmax_ce(int64_t n, int64_t C, const double *logits,
+                      const int32_t *labels, double *dlogits)
+{
+    double loss = 0.0;
+    for (int64_t v = 0; v < n; ++v) {
+        const double *z = logits + v * C;
+        double mx = z[0];
+        for (int64_t c = 1; c < C; ++c) if (z[c] > mx) mx = z[c];
+        double se = 0.0;
+        for (int64_t c = 0; c < C; ++c) se += exp(z[c] - mx);
+        double lse = mx + log(se);
+        loss += lse - z[labels[v]];
+        if (dlogits)
+            for (int64_t c = 0; c < C; ++c)
+                dlogits[v * C + c] =
+                    (exp(z[c] - lse) - (c == labels[v] ? 1.0 : 0.0)) / (double)n;
+    }
+    return loss / (double)n;
+}
+
+/* The loss of Thm. 1: z = sigmoid(g), L = 1/2 ||y - z||^2 summed over nodes
+ * and outputs; dL/dg = (z - y) z (1 - z)  (proof of Thm. 1, gradient
+ * equations). */
+double orc_sigmoid_l2(int64_t n, int64_t C, const double *G, const double *Y, double *dG)
+{
+    double loss = 0.0;
+    for (int64_t i = 0; i < n * C; ++i) {
+        double z = 1.0 / (1.0 + exp(-G[i]));
+        double r = z - Y[i];
+        loss += 0.5 * r * r;
+        if (dG) dG[i] = r * z * (1.0 - z);
+    }
+    return loss;
+}
+
+/* ------------------------------------------------------------------------
+ * Optimizer step (Alg. 2, the `optimizer` call; read as plain SGD) and the
+ * aggregation operator phi = arithmetic mean of the trainers' parameters
+ * (Sec. 3.1; Alg. 1 aggregation line), followed by the overwrite of every
+ * participating trainer's weights (Alg. 2).  Trainers whose bit in `active`
+ * is clear take no part and are left untouched (failure experiment, Sec. 4.4).
+ * W is [M][P] row-major.
+ * ---------------------------------------------------------------------- */
+void orc_sgd_step(int64_t P, double *W, const double *dW, double lr)
+{
+    for (int64_t i = 0; i < P; ++i) W[i] -= lr * dW[i];
+}
+
+void orc_average(int32_t M, int64_t P, uint64_t active, double *W, double *W_global)
+{
+    int cnt = 0;
+    for (int32_t i = 0; i < M; ++i) if ((active >> i) & 1u) ++cnt;
+    if (cnt == 0) return;
+    for (int64_t j = 0; j < P; ++j) {
+        double s = 0.0;
+        for (int32_t i = 0; i < M; ++i)
+            if ((active >> i) & 1u) s += W[(int64_t)i * P + j];
+        s /= (double)cnt;
+        if (W_global) W_global[j] = s;
+        for (int32_t i = 0; i < M; ++i)
+            if ((active >> i) & 1u) W[(int64_t)i * P + j] = s;
+    }
+}
