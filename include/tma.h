@@ -1,0 +1,239 @@
+/*
+ * libtma -- C ABI of the MI355X (gfx950) hot path of one TMA trainer:
+ * random partition assignment, node-induced subgraph extraction, mean
+ * aggregation GraphSAGE layer forward/backward, loss, SGD step and on-device
+ * parameter averaging ("Randomized Partitions Improve Model Aggregation",
+ * RandomTMA / SuperTMA; arXiv 2305.09887).
+ *
+ * Conventions (all entry points)
+ *   - Return value: TMA_OK (0) or a negative tma_status.  No exceptions, no
+ *     exit().  tma_last_error() returns a thread-local message for the last
+ *     failing call on this thread.
+ *   - Pointers are DEVICE pointers unless their name starts with h_.
+ *   - The caller owns every buffer and the stream.  The library allocates and
+ *     frees no device memory; scratch space is passed in as (ws, ws_bytes) and
+ *     sized with the matching *_workspace_bytes query.  Work is enqueued on
+ *     `stream` only (a hipStream_t passed as void*; NULL = the default stream)
+ *     and the call returns without waiting, except tma_induced_subgraph_count
+ *     which must hand two sizes back to the host.
+ *   - Matrices are row-major with an explicit leading dimension in ELEMENTS.
+ *   - Indices: local graphs int32 rowptr/colidx; the global graph has an int64
+ *     rowptr (more than 2^31 entries are allowed) and int32 colidx.
+ *   - dtype selects the storage type of features/activations (tma_dtype).
+ *     Weights, weight gradients, losses and averaging are always fp32.
+ *   - Arguments are validated on the host (NULL where not allowed, negative or
+ *     inconsistent sizes, misaligned workspace); the contents of index arrays
+ *     are a precondition and are not scanned: 0 <= colidx < n, rowptr
+ *     non-decreasing, part ids in [0,K).
+ */
+#ifndef TMA_H
+#define TMA_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef void *tma_stream_t; /* hipStream_t */
+
+typedef enum {
+    TMA_OK = 0,
+    TMA_ERR_INVALID_ARG = -1,
+    TMA_ERR_BAD_SHAPE = -2,
+    TMA_ERR_WORKSPACE_TOO_SMALL = -3,
+    TMA_ERR_UNSUPPORTED_DTYPE = -4,
+    TMA_ERR_HIP = -5
+} tma_status;
+
+typedef enum { TMA_F32 = 0, TMA_BF16 = 1 } tma_dtype;
+typedef enum { TMA_ACT_NONE = 0, TMA_ACT_RELU = 1 } tma_act;
+
+/* Library version as major*10000 + minor*100 + patch. */
+int tma_version(void);
+
+/* Message of the last error raised on the calling thread ("" if none). */
+const char *tma_last_error(void);
+
+/* ------------------------------------------------------------------------
+ * Random assignment (paper Sec. 3.2.2).
+ *   cluster == NULL : RandomTMA -- each node is assigned independently and
+ *                     uniformly to one of K partitions.
+ *   cluster != NULL : SuperTMA  -- each super-node (mini-cluster id in
+ *                     [0, n_clusters)) is assigned that way and a node
+ *                     inherits the partition of cluster[v].  With one node
+ *                     per super-node (cluster[v] = v) the result equals
+ *                     RandomTMA's, as the paper notes for N = |V|.
+ * The paper fixes no generator; this library's is
+ *     part = floor( SplitMix64(seed, unit) * K / 2^64 ),
+ * SplitMix64(seed, unit) = output number unit+1 of the SplitMix64 stream
+ * seeded with `seed`.  Pure function of (seed, unit id, K).
+ *   part_out [n_nodes] int32, written.   1 <= K <= 2^30.
+ * ---------------------------------------------------------------------- */
+int tma_partition(int64_t n_nodes, const int32_t *cluster, int64_t n_clusters,
+                  int32_t K, uint64_t seed, int32_t *part_out, tma_stream_t stream);
+
+/* ------------------------------------------------------------------------
+ * Node-induced subgraph of partition p (paper, Preliminaries):
+ *   V^(p) = { v : part[v] = p },  E^(p) = { (u,v) in E : u, v in V^(p) }.
+ * Canonical output: local id = rank of the global id within V^(p); the
+ * neighbours of a row keep their input order.  Two calls:
+ *
+ * _count  writes g2l_out [n_nodes] (local id, or -1 outside the part),
+ *         l2g_out [cap_n_loc], rowptr_loc_out [cap_n_loc + 1]; then WAITS for
+ *         the stream and stores |V^(p)| and the number of kept CSR entries in
+ *         *h_n_loc / *h_nnz_loc (host memory).  If |V^(p)| > cap_n_loc nothing
+ *         is written past the capacity, the sizes are still reported and the
+ *         call returns TMA_ERR_BAD_SHAPE (retry with larger buffers).  More
+ *         than 2^31-1 kept entries also give TMA_ERR_BAD_SHAPE.
+ * _fill   writes colidx_loc_out [nnz_loc] and inv_deg_out [n_loc]
+ *         (1/local degree in fp32, 0 for a node without local neighbours);
+ *         asynchronous.
+ * Workspace: tma_induced_subgraph_workspace_bytes(n_nodes, cap_n_loc) bytes,
+ * 256-byte aligned, for _count only.
+ * ---------------------------------------------------------------------- */
+size_t tma_induced_subgraph_workspace_bytes(int64_t n_nodes, int64_t cap_n_loc);
+
+int tma_induced_subgraph_count(int64_t n_nodes, const int64_t *rowptr, const int32_t *colidx,
+                               const int32_t *part, int32_t p,
+                               int32_t *g2l_out, int32_t *l2g_out, int32_t *rowptr_loc_out,
+                               int64_t cap_n_loc, int64_t *h_n_loc, int64_t *h_nnz_loc,
+                               void *ws, size_t ws_bytes, tma_stream_t stream);
+
+int tma_induced_subgraph_fill(int64_t n_nodes, const int64_t *rowptr, const int32_t *colidx,
+                              const int32_t *part, int32_t p,
+                              const int32_t *g2l, const int32_t *l2g, int64_t n_loc,
+                              const int32_t *rowptr_loc,
+                              int32_t *colidx_loc_out, float *inv_deg_out, tma_stream_t stream);
+
+/* ------------------------------------------------------------------------
+ * Mean aggregation with the row-normalised adjacency (paper Thm. 1 and the
+ * first equation of its proof), over the local neighbourhood:
+ *     M_v = inv_deg[v] * sum_{u in N'(v)} H_u        (0 for an isolated node)
+ * H, M_out: [n, F] of `dtype`, leading dimensions ldh / ldm.  fp32 accumulation
+ * in neighbour order.  Also exported on its own because it is the HBM-bound
+ * kernel of the path.
+ * ---------------------------------------------------------------------- */
+int tma_mean_aggregate(int64_t n, const int32_t *rowptr, const int32_t *colidx,
+                       const float *inv_deg, const void *H, int64_t ldh, int32_t F,
+                       int32_t dtype, void *M_out, int64_t ldm, tma_stream_t stream);
+
+/* ------------------------------------------------------------------------
+ * One mean-aggregation GraphSAGE layer, forward:
+ *     M = Abar H,   Z = H W_self + M W_neigh + 1 b^T,   H' = act(Z)
+ * (the paper names the encoder, Sec. 4.1, and writes its aggregation as
+ * Abar X W in Thm. 1; self and neighbour terms have separate weights, the
+ * neighbour mean excludes the node itself).
+ *   H       [n, F_in]  dtype, ld = ldh
+ *   W_self, W_neigh [F_in, F_out] fp32 row-major, dense;  bias [F_out] fp32
+ *   M_out   [n, F_in]  dtype, dense (ld = F_in), saved for backward
+ *   Hnext_out [n, F_out] dtype, dense.  With TMA_ACT_RELU the sign pattern of
+ *           H' equals that of Z, so H' is all that backward needs.
+ * No workspace.
+ * ---------------------------------------------------------------------- */
+int tma_sage_layer_fwd(int64_t n, const int32_t *rowptr, const int32_t *colidx,
+                       const float *inv_deg,
+                       const void *H, int64_t ldh, int32_t F_in,
+                       const float *W_self, const float *W_neigh, const float *bias,
+                       int32_t F_out, int32_t act, int32_t dtype,
+                       void *M_out, void *Hnext_out, tma_stream_t stream);
+
+/* ------------------------------------------------------------------------
+ * Backward of the layer (chain rule as in the proof of Thm. 1, which writes
+ * the one-layer case dL/dw = dL/dz * dz/dg * dg/dw):
+ *     dZ = dHnext (.) act'(Z)                  (act' from the sign of Hnext)
+ *     dW_self = H^T dZ,  dW_neigh = M^T dZ,  dbias = column sums of dZ
+ *     dH = dZ W_self^T + Abar^T (dZ W_neigh^T)
+ *   H, M     as in forward;  Hnext [n, F_out] the forward output (read only
+ *            when act = TMA_ACT_RELU);  dHnext [n, F_out] dtype, dense
+ *   rowptr_T/colidx_T : CSR of the TRANSPOSED local graph.  For a symmetric
+ *            graph (every configuration of a simple undirected graph) pass
+ *            rowptr/colidx again.  inv_deg is that of the forward graph.
+ *   dW_self, dW_neigh [F_in, F_out], dbias [F_out] fp32: OVERWRITTEN.
+ *   dH_out [n, F_in] dtype dense, or NULL to skip the input gradient (first
+ *            layer).
+ * Workspace: tma_sage_layer_bwd_workspace_bytes(n, F_in, F_out, dtype,
+ * dH_out != NULL), 256-byte aligned.  Results are deterministic (fixed
+ * reduction order, no floating-point atomics).
+ * ---------------------------------------------------------------------- */
+size_t tma_sage_layer_bwd_workspace_bytes(int64_t n, int32_t F_in, int32_t F_out,
+                                          int32_t dtype, int32_t need_dH);
+
+int tma_sage_layer_bwd(int64_t n, const int32_t *rowptr_T, const int32_t *colidx_T,
+                       const float *inv_deg,
+                       const void *H, int64_t ldh, const void *M, const void *Hnext,
+                       const void *dHnext,
+                       const float *W_self, const float *W_neigh,
+                       int32_t F_in, int32_t F_out, int32_t act, int32_t dtype,
+                       float *dW_self, float *dW_neigh, float *dbias, void *dH_out,
+                       void *ws, size_t ws_bytes, tma_stream_t stream);
+
+/* ------------------------------------------------------------------------
+ * Losses on the last layer's output.
+ * tma_softmax_ce: mean softmax cross-entropy over the n local nodes (reading
+ *   taken for workloads with class labels); loss_out[0] fp32 (device),
+ *   dlogits_out = (softmax - onehot)/n in `dtype`, dense [n, C].
+ * tma_sigmoid_l2: the loss of Thm. 1, L = 1/2 sum (y - sigmoid(g))^2 over all
+ *   nodes and outputs; dG = (z - y) z (1 - z).  Y fp32 dense [n, C].
+ * Workspace: tma_loss_workspace_bytes(n, C) bytes, 256-byte aligned.
+ * ---------------------------------------------------------------------- */
+size_t tma_loss_workspace_bytes(int64_t n, int32_t C);
+
+int tma_softmax_ce(int64_t n, int32_t C, const void *logits, int64_t ld, int32_t dtype,
+                   const int32_t *labels, float *loss_out, void *dlogits_out,
+                   void *ws, size_t ws_bytes, tma_stream_t stream);
+
+int tma_sigmoid_l2(int64_t n, int32_t C, const void *G, int64_t ld, int32_t dtype,
+                   const float *Y, float *loss_out, void *dG_out,
+                   void *ws, size_t ws_bytes, tma_stream_t stream);
+
+/* ------------------------------------------------------------------------
+ * Optimizer step of Alg. 2 (the paper does not name the optimizer; plain SGD
+ * is the reading taken): W <- W - lr * dW over a flat fp32 vector.
+ * ---------------------------------------------------------------------- */
+int tma_sgd_step(int64_t n_params, float *W, const float *dW, float lr, tma_stream_t stream);
+
+/* ------------------------------------------------------------------------
+ * Aggregation operator phi of Alg. 1 = arithmetic mean of the trainers'
+ * parameters (Sec. 3.1), followed by the overwrite of Alg. 2: every ACTIVE
+ * trainer's vector is replaced by the mean.  Trainers whose bit in
+ * active_mask is clear are skipped and left untouched (the paper's failure
+ * experiment continues with the remaining trainers).
+ *   W_ptrs : DEVICE array of n_trainers device pointers, each [n_params] fp32
+ *   n_trainers in [1, 64]
+ *   W_global_out : [n_params] fp32 or NULL
+ * Sum in trainer-index order in fp32, then one multiply by 1/|active|.
+ * The caller orders this call after the trainers' last steps (events).
+ * ---------------------------------------------------------------------- */
+int tma_average(float *const *W_ptrs, int32_t n_trainers, uint64_t active_mask,
+                int64_t n_params, float *W_global_out, tma_stream_t stream);
+
+/* ------------------------------------------------------------------------
+ * Gather of the local rows of a row-major table (a trainer "loads" its part
+ * of the feature matrix and of the label vector, Alg. 2, set-up line):
+ *     dst[i, :] = src[l2g[i], :]     for i in [0, n_loc)
+ * Rows are row_bytes long; src_ld_bytes / dst_ld_bytes are the row pitches.
+ * Any element type: 16-byte copies when pointers, pitches and row_bytes are
+ * multiples of 16, 4-byte copies when multiples of 4, else byte copies.
+ * ---------------------------------------------------------------------- */
+int tma_gather_rows(int64_t n_loc, const int32_t *l2g, const void *src, int64_t src_ld_bytes,
+                    int64_t row_bytes, void *dst, int64_t dst_ld_bytes, tma_stream_t stream);
+
+/* ------------------------------------------------------------------------
+ * Measurement aid (not part of the method): per-kernel durations from HIP
+ * events recorded on the launch stream around every kernel launch of this
+ * library between _begin and _end.  kernel_filter NULL or "" times every
+ * kernel; otherwise only the kernel with exactly that name.  _end waits for
+ * the recorded events, then _count/_entry read the totals per kernel name
+ * (name_out stays valid until the next _begin).  Host-side state only.
+ * ---------------------------------------------------------------------- */
+int tma_profile_begin(const char *kernel_filter);
+int tma_profile_end(void);
+int tma_profile_count(void);
+int tma_profile_entry(int index, const char **name_out, int64_t *launches_out, double *total_ms_out);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* TMA_H */

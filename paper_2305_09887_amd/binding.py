@@ -1,0 +1,292 @@
+"""ctypes binding of libtma: same names as the C ABI, argument marshalling only.
+
+Tensors are torch tensors on the GPU (torch is used for device memory and
+streams, nothing else); every computation happens in the library's kernels.
+The library is loaded on first use; if it has not been built the call raises --
+there is no fallback path.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+
+import torch
+
+_PKG = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_PKG, "libtma.so")
+
+TMA_F32, TMA_BF16 = 0, 1
+TMA_ACT_NONE, TMA_ACT_RELU = 0, 1
+
+EXPORTS = (
+    "tma_version", "tma_last_error", "tma_partition",
+    "tma_induced_subgraph_workspace_bytes", "tma_induced_subgraph_count", "tma_induced_subgraph_fill",
+    "tma_mean_aggregate", "tma_sage_layer_fwd", "tma_sage_layer_bwd_workspace_bytes", "tma_sage_layer_bwd",
+    "tma_loss_workspace_bytes", "tma_softmax_ce", "tma_sigmoid_l2", "tma_sgd_step", "tma_average",
+)
+
+
+class TmaError(RuntimeError):
+    pass
+
+
+_lib = None
+
+
+def lib() -> C.CDLL:
+    """The loaded C library (raises if libtma.so is missing)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(_LIB_PATH):
+            raise TmaError(f"{_LIB_PATH} not found: build it with `python -m paper_2305_09887_amd.build` "
+                           "(there is no CPU fallback)")
+        L = C.CDLL(_LIB_PATH)
+        L.tma_last_error.restype = C.c_char_p
+        for name in ("tma_induced_subgraph_workspace_bytes", "tma_sage_layer_bwd_workspace_bytes",
+                     "tma_loss_workspace_bytes"):
+            getattr(L, name).restype = C.c_size_t
+        _lib = L
+    return _lib
+
+
+def _check(rc: int):
+    if rc != 0:
+        raise TmaError(f"libtma error {rc}: {lib().tma_last_error().decode()}")
+
+
+def _stream(stream=None) -> C.c_void_p:
+    s = torch.cuda.current_stream() if stream is None else stream
+    return C.c_void_p(s.cuda_stream)
+
+
+def _ptr(t, dtype=None, name="tensor") -> C.c_void_p:
+    if t is None:
+        return C.c_void_p(0)
+    if not t.is_cuda:
+        raise TmaError(f"{name}: expected a CUDA/HIP tensor")
+    if dtype is not None and t.dtype != dtype:
+        raise TmaError(f"{name}: expected {dtype}, got {t.dtype}")
+    if not t.is_contiguous():
+        raise TmaError(f"{name}: expected a contiguous tensor")
+    return C.c_void_p(t.data_ptr())
+
+
+def _feat_dtype(t) -> int:
+    if t.dtype == torch.float32:
+        return TMA_F32
+    if t.dtype == torch.bfloat16:
+        return TMA_BF16
+    raise TmaError(f"unsupported feature dtype {t.dtype}")
+
+
+def _rows_ld(t, name):
+    """2-D row-major tensor, possibly with padded rows: returns (rows, cols, ld)."""
+    if t.dim() != 2 or t.stride(1) != 1:
+        raise TmaError(f"{name}: expected a 2-D tensor with unit inner stride")
+    return t.shape[0], t.shape[1], (t.stride(0) if t.shape[0] > 1 else max(t.stride(0), t.shape[1]))
+
+
+def _workspace(nbytes: int, device) -> torch.Tensor:
+    return torch.empty(max(int(nbytes), 256), dtype=torch.uint8, device=device)
+
+
+def tma_version() -> int:
+    return lib().tma_version()
+
+
+# ---------------------------------------------------------------------------
+def tma_partition(n_nodes: int, K: int, seed: int, cluster=None, n_clusters: int = 0, out=None, stream=None):
+    """part[v] in [0,K): RandomTMA (cluster None) or SuperTMA (cluster = int32 super-node ids)."""
+    dev = cluster.device if cluster is not None else torch.device("cuda", torch.cuda.current_device())
+    if out is None:
+        out = torch.empty(n_nodes, dtype=torch.int32, device=dev)
+    if out.numel() != n_nodes or (cluster is not None and cluster.numel() != n_nodes):
+        raise TmaError("tma_partition: part_out / cluster must have n_nodes elements")
+    if cluster is not None and n_clusters <= 0:
+        raise TmaError("tma_partition: n_clusters must be given with cluster")
+    _check(lib().tma_partition(C.c_int64(n_nodes), _ptr(cluster, torch.int32, "cluster"), C.c_int64(n_clusters),
+                               C.c_int32(K), C.c_uint64(seed), _ptr(out, torch.int32, "part_out"), _stream(stream)))
+    return out
+
+
+def tma_induced_subgraph(rowptr, colidx, part, p: int, cap_n_loc: int | None = None, stream=None):
+    """Both calls of the extraction.  Returns dict(g2l, l2g, rowptr, colidx, inv_deg, n_loc, nnz_loc)."""
+    n = rowptr.numel() - 1
+    if part.numel() != n:
+        raise TmaError("tma_induced_subgraph: part must have one entry per node")
+    dev = rowptr.device
+    if colidx.numel() == 0:      # edgeless graph: the library wants a non-NULL pointer, never read
+        colidx = torch.zeros(1, dtype=torch.int32, device=dev)
+    cap = n if cap_n_loc is None else min(int(cap_n_loc), n)
+    L = lib()
+    ws_bytes = L.tma_induced_subgraph_workspace_bytes(C.c_int64(n), C.c_int64(cap))
+    ws = _workspace(ws_bytes, dev)
+    g2l = torch.empty(max(n, 1), dtype=torch.int32, device=dev)
+    l2g = torch.empty(max(cap, 1), dtype=torch.int32, device=dev)
+    rp = torch.empty(cap + 1, dtype=torch.int32, device=dev)
+    n_loc, nnz_loc = C.c_int64(0), C.c_int64(0)
+    _check(L.tma_induced_subgraph_count(
+        C.c_int64(n), _ptr(rowptr, torch.int64, "rowptr"), _ptr(colidx, torch.int32, "colidx"),
+        _ptr(part, torch.int32, "part"), C.c_int32(p), _ptr(g2l), _ptr(l2g), _ptr(rp), C.c_int64(cap),
+        C.byref(n_loc), C.byref(nnz_loc), _ptr(ws), C.c_size_t(ws.numel()), _stream(stream)))
+    n_loc, nnz_loc = n_loc.value, nnz_loc.value
+    ci = torch.empty(max(nnz_loc, 1), dtype=torch.int32, device=dev)
+    inv = torch.empty(max(n_loc, 1), dtype=torch.float32, device=dev)
+    _check(L.tma_induced_subgraph_fill(
+        C.c_int64(n), _ptr(rowptr), _ptr(colidx), _ptr(part), C.c_int32(p), _ptr(g2l), _ptr(l2g),
+        C.c_int64(n_loc), _ptr(rp), _ptr(ci), _ptr(inv), _stream(stream)))
+    return dict(g2l=g2l[:n], l2g=l2g[:n_loc], rowptr=rp[:n_loc + 1], colidx=ci[:nnz_loc], inv_deg=inv[:n_loc],
+                n_loc=n_loc, nnz_loc=nnz_loc)
+
+
+def tma_mean_aggregate(rowptr, colidx, inv_deg, H, out=None, stream=None):
+    n, F, ldh = _rows_ld(H, "H")
+    if rowptr.numel() != n + 1 or inv_deg.numel() != n:
+        raise TmaError("tma_mean_aggregate: graph and feature row counts differ")
+    if out is None:
+        out = torch.empty((n, F), dtype=H.dtype, device=H.device)
+    _, Fo, ldm = _rows_ld(out, "M_out")
+    if out.shape[0] != n or Fo != F or out.dtype != H.dtype:
+        raise TmaError("tma_mean_aggregate: M_out shape/dtype mismatch")
+    _check(lib().tma_mean_aggregate(C.c_int64(n), _ptr(rowptr, torch.int32), _ptr(colidx, torch.int32),
+                                    _ptr(inv_deg, torch.float32), C.c_void_p(H.data_ptr()), C.c_int64(ldh),
+                                    C.c_int32(F), C.c_int32(_feat_dtype(H)), C.c_void_p(out.data_ptr()),
+                                    C.c_int64(ldm), _stream(stream)))
+    return out
+
+
+def tma_sage_layer_fwd(rowptr, colidx, inv_deg, H, W_self, W_neigh, bias, act: int, M_out=None, Hnext_out=None,
+                       stream=None):
+    """Returns (M, Hnext)."""
+    n, F_in, ldh = _rows_ld(H, "H")
+    F_out = W_self.shape[1]
+    if tuple(W_self.shape) != (F_in, F_out) or tuple(W_neigh.shape) != (F_in, F_out) or bias.numel() != F_out:
+        raise TmaError("tma_sage_layer_fwd: weight shapes do not match H")
+    if rowptr.numel() != n + 1 or inv_deg.numel() != n:
+        raise TmaError("tma_sage_layer_fwd: graph and feature row counts differ")
+    if M_out is None:
+        M_out = torch.empty((n, F_in), dtype=H.dtype, device=H.device)
+    if Hnext_out is None:
+        Hnext_out = torch.empty((n, F_out), dtype=H.dtype, device=H.device)
+    if tuple(M_out.shape) != (n, F_in) or tuple(Hnext_out.shape) != (n, F_out):
+        raise TmaError("tma_sage_layer_fwd: output shapes")
+    _check(lib().tma_sage_layer_fwd(
+        C.c_int64(n), _ptr(rowptr, torch.int32), _ptr(colidx, torch.int32), _ptr(inv_deg, torch.float32),
+        C.c_void_p(H.data_ptr()), C.c_int64(ldh), C.c_int32(F_in), _ptr(W_self, torch.float32, "W_self"),
+        _ptr(W_neigh, torch.float32, "W_neigh"), _ptr(bias, torch.float32, "bias"), C.c_int32(F_out),
+        C.c_int32(act), C.c_int32(_feat_dtype(H)), _ptr(M_out, H.dtype, "M_out"),
+        _ptr(Hnext_out, H.dtype, "Hnext_out"), _stream(stream)))
+    return M_out, Hnext_out
+
+
+def tma_sage_layer_bwd_workspace_bytes(n: int, F_in: int, F_out: int, dtype: int, need_dH: bool) -> int:
+    return int(lib().tma_sage_layer_bwd_workspace_bytes(C.c_int64(n), C.c_int32(F_in), C.c_int32(F_out),
+                                                        C.c_int32(dtype), C.c_int32(1 if need_dH else 0)))
+
+
+def tma_sage_layer_bwd(rowptr_T, colidx_T, inv_deg, H, M, Hnext, dHnext, W_self, W_neigh, act: int,
+                       dW_self=None, dW_neigh=None, dbias=None, dH_out=None, need_dH=True, ws=None, stream=None):
+    """Returns (dW_self, dW_neigh, dbias, dH or None)."""
+    n, F_in, ldh = _rows_ld(H, "H")
+    F_out = W_self.shape[1]
+    dev = H.device
+    if tuple(M.shape) != (n, F_in) or tuple(dHnext.shape) != (n, F_out):
+        raise TmaError("tma_sage_layer_bwd: M / dHnext shapes")
+    if act == TMA_ACT_RELU and (Hnext is None or tuple(Hnext.shape) != (n, F_out)):
+        raise TmaError("tma_sage_layer_bwd: Hnext is required with ReLU")
+    if need_dH and (rowptr_T.numel() != n + 1 or inv_deg.numel() != n):
+        raise TmaError("tma_sage_layer_bwd: graph and feature row counts differ")
+    if dW_self is None:
+        dW_self = torch.empty((F_in, F_out), dtype=torch.float32, device=dev)
+    if dW_neigh is None:
+        dW_neigh = torch.empty((F_in, F_out), dtype=torch.float32, device=dev)
+    if dbias is None:
+        dbias = torch.empty(F_out, dtype=torch.float32, device=dev)
+    if need_dH and dH_out is None:
+        dH_out = torch.empty((n, F_in), dtype=H.dtype, device=dev)
+    if not need_dH:
+        dH_out = None
+    dt = _feat_dtype(H)
+    need = tma_sage_layer_bwd_workspace_bytes(n, F_in, F_out, dt, need_dH)
+    if ws is None:
+        ws = _workspace(need, dev)
+    _check(lib().tma_sage_layer_bwd(
+        C.c_int64(n), _ptr(rowptr_T, torch.int32), _ptr(colidx_T, torch.int32), _ptr(inv_deg, torch.float32),
+        C.c_void_p(H.data_ptr()), C.c_int64(ldh), _ptr(M, H.dtype, "M"), _ptr(Hnext, H.dtype, "Hnext"),
+        _ptr(dHnext, H.dtype, "dHnext"), _ptr(W_self, torch.float32), _ptr(W_neigh, torch.float32),
+        C.c_int32(F_in), C.c_int32(F_out), C.c_int32(act), C.c_int32(dt),
+        _ptr(dW_self, torch.float32, "dW_self"), _ptr(dW_neigh, torch.float32, "dW_neigh"),
+        _ptr(dbias, torch.float32, "dbias"), _ptr(dH_out, H.dtype, "dH_out"), _ptr(ws), C.c_size_t(ws.numel()),
+        _stream(stream)))
+    return dW_self, dW_neigh, dbias, dH_out
+
+
+def tma_loss_workspace_bytes(n: int, Cc: int) -> int:
+    return int(lib().tma_loss_workspace_bytes(C.c_int64(n), C.c_int32(Cc)))
+
+
+def tma_softmax_ce(logits, labels, loss_out=None, dlogits_out=None, need_grad=True, ws=None, stream=None):
+    """Returns (loss [1] fp32 device tensor, dlogits or None)."""
+    n, Cc, ldz = _rows_ld(logits, "logits")
+    dev = logits.device
+    if labels.numel() != n:
+        raise TmaError("tma_softmax_ce: labels must have one entry per row")
+    if loss_out is None:
+        loss_out = torch.empty(1, dtype=torch.float32, device=dev)
+    if need_grad and dlogits_out is None:
+        dlogits_out = torch.empty((n, Cc), dtype=logits.dtype, device=dev)
+    if ws is None:
+        ws = _workspace(tma_loss_workspace_bytes(n, Cc), dev)
+    _check(lib().tma_softmax_ce(C.c_int64(n), C.c_int32(Cc), C.c_void_p(logits.data_ptr()), C.c_int64(ldz),
+                                C.c_int32(_feat_dtype(logits)), _ptr(labels, torch.int32, "labels"),
+                                _ptr(loss_out, torch.float32), _ptr(dlogits_out if need_grad else None),
+                                _ptr(ws), C.c_size_t(ws.numel()), _stream(stream)))
+    return loss_out, (dlogits_out if need_grad else None)
+
+
+def tma_sigmoid_l2(G, Y, loss_out=None, dG_out=None, need_grad=True, ws=None, stream=None):
+    n, Cc, ldg = _rows_ld(G, "G")
+    dev = G.device
+    if tuple(Y.shape) != (n, Cc):
+        raise TmaError("tma_sigmoid_l2: Y shape")
+    if loss_out is None:
+        loss_out = torch.empty(1, dtype=torch.float32, device=dev)
+    if need_grad and dG_out is None:
+        dG_out = torch.empty((n, Cc), dtype=G.dtype, device=dev)
+    if ws is None:
+        ws = _workspace(tma_loss_workspace_bytes(n, Cc), dev)
+    _check(lib().tma_sigmoid_l2(C.c_int64(n), C.c_int32(Cc), C.c_void_p(G.data_ptr()), C.c_int64(ldg),
+                                C.c_int32(_feat_dtype(G)), _ptr(Y, torch.float32, "Y"),
+                                _ptr(loss_out, torch.float32), _ptr(dG_out if need_grad else None), _ptr(ws),
+                                C.c_size_t(ws.numel()), _stream(stream)))
+    return loss_out, (dG_out if need_grad else None)
+
+
+def tma_sgd_step(W, dW, lr: float, stream=None):
+    if W.numel() != dW.numel():
+        raise TmaError("tma_sgd_step: W and dW differ in size")
+    _check(lib().tma_sgd_step(C.c_int64(W.numel()), _ptr(W, torch.float32, "W"), _ptr(dW, torch.float32, "dW"),
+                              C.c_float(lr), _stream(stream)))
+    return W
+
+
+def tma_average(W_list, active_mask: int | None = None, W_global_out=None, ptr_table=None, stream=None):
+    """Mean of the active trainers' flat fp32 parameter vectors, written back into each of them.
+
+    ``ptr_table`` (int64 device tensor holding the data pointers) can be passed
+    to avoid rebuilding it on every call.
+    """
+    M = len(W_list)
+    n = W_list[0].numel()
+    for w in W_list:
+        if w.numel() != n or w.dtype != torch.float32 or not w.is_cuda or not w.is_contiguous():
+            raise TmaError("tma_average: every W must be a contiguous fp32 GPU tensor of the same size")
+    if active_mask is None:
+        active_mask = (1 << M) - 1
+    if ptr_table is None:
+        ptr_table = torch.tensor([w.data_ptr() for w in W_list], dtype=torch.int64, device=W_list[0].device)
+    if W_global_out is not None and W_global_out.numel() != n:
+        raise TmaError("tma_average: W_global_out size")
+    _check(lib().tma_average(_ptr(ptr_table, torch.int64), C.c_int32(M), C.c_uint64(active_mask), C.c_int64(n),
+                             _ptr(W_global_out, torch.float32), _stream(stream)))
+    return W_global_out

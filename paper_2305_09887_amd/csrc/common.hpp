@@ -1,0 +1,76 @@
+// Shared host-side plumbing of libtma: error reporting, argument checks,
+// launch helpers.  gfx950 only.
+#pragma once
+
+#include <hip/hip_runtime.h>
+
+#include <cstdarg>
+#include <cstdint>
+#include <cstdio>
+
+#include "tma.h"
+
+namespace tma {
+
+constexpr int kWave = 64;  // CDNA wavefront width
+
+// Thread-local message returned by tma_last_error().
+char *error_buffer();
+int fail(int code, const char *fmt, ...);
+
+inline hipStream_t as_stream(tma_stream_t s) { return reinterpret_cast<hipStream_t>(s); }
+
+inline bool aligned(const void *p, size_t a) { return (reinterpret_cast<uintptr_t>(p) % a) == 0; }
+
+inline size_t round_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+
+inline int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
+
+// Checks the launch itself (bad configuration, missing code object); kernel
+// execution errors surface at the caller's next synchronisation.
+inline int check_launch(const char *what)
+{
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return fail(TMA_ERR_HIP, "%s: launch failed: %s", what, hipGetErrorString(e));
+    return TMA_OK;
+}
+
+// Optional per-kernel timing with HIP events recorded on the launch stream
+// (tma_profile_begin / tma_profile_end).  Costs nothing while disabled.
+class KernelTimer {
+public:
+    KernelTimer(const char *name, hipStream_t stream);
+    ~KernelTimer();
+    KernelTimer(const KernelTimer &) = delete;
+    KernelTimer &operator=(const KernelTimer &) = delete;
+
+private:
+    int slot_;
+    hipStream_t stream_;
+};
+#define TMA_TIMED(name, stream) ::tma::KernelTimer tma_kernel_timer_(name, stream)
+
+#define TMA_HIP_TRY(expr, what)                                                          \
+    do {                                                                                 \
+        hipError_t e_ = (expr);                                                          \
+        if (e_ != hipSuccess)                                                            \
+            return ::tma::fail(TMA_ERR_HIP, "%s: %s", what, hipGetErrorString(e_));      \
+    } while (0)
+
+#define TMA_REQUIRE(cond, code, ...)                                                     \
+    do {                                                                                 \
+        if (!(cond)) return ::tma::fail(code, __VA_ARGS__);                              \
+    } while (0)
+
+// bf16 <-> fp32, round-to-nearest-even on store (NaN kept quiet).
+__device__ __forceinline__ float bf16_to_f32(uint16_t b) { return __uint_as_float(uint32_t(b) << 16); }
+
+__device__ __forceinline__ uint16_t f32_to_bf16(float f)
+{
+    uint32_t u = __float_as_uint(f);
+    if ((u & 0x7FFFFFFFu) > 0x7F800000u) return uint16_t((u >> 16) | 0x40u);
+    u += 0x7FFFu + ((u >> 16) & 1u);
+    return uint16_t(u >> 16);
+}
+
+}  // namespace tma

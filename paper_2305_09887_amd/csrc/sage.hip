@@ -1,0 +1,93 @@
+// Entry points of one mean-aggregation GraphSAGE layer (forward / backward).
+// Sequencing only: aggregation kernel, then the MFMA transform; all on the
+// caller's stream, no allocation, no synchronisation.
+#include "kernels.hpp"
+
+namespace tma {
+
+static size_t elem_size(int32_t dtype) { return dtype == TMA_BF16 ? 2 : 4; }
+
+struct BwdWorkspace {
+    size_t dm_bytes;      // D^-1 dM  [n, F_in]
+    size_t weight_bytes;  // split partials
+    size_t total() const { return dm_bytes + weight_bytes; }
+};
+
+static BwdWorkspace plan_bwd(int64_t n, int32_t F_in, int32_t F_out, int32_t dtype, bool need_dH)
+{
+    BwdWorkspace w;
+    w.dm_bytes = need_dH ? round_up(size_t(n > 0 ? n : 1) * size_t(F_in > 0 ? F_in : 1) * elem_size(dtype), 256) : 0;
+    w.weight_bytes = sage_gemm_bwd_weight_workspace_bytes(n, F_in, F_out);
+    return w;
+}
+
+}  // namespace tma
+
+extern "C" int tma_sage_layer_fwd(int64_t n, const int32_t *rowptr, const int32_t *colidx, const float *inv_deg,
+                                  const void *H, int64_t ldh, int32_t F_in, const float *W_self,
+                                  const float *W_neigh, const float *bias, int32_t F_out, int32_t act, int32_t dtype,
+                                  void *M_out, void *Hnext_out, tma_stream_t stream)
+{
+    using namespace tma;
+    const char *fn = "tma_sage_layer_fwd";
+    TMA_REQUIRE(n >= 0 && n <= INT32_MAX, TMA_ERR_INVALID_ARG, "%s: n outside [0, 2^31)", fn);
+    TMA_REQUIRE(F_in >= 1 && F_out >= 1 && F_in <= (1 << 20) && F_out <= (1 << 20), TMA_ERR_BAD_SHAPE,
+                "%s: F_in=%d F_out=%d", fn, F_in, F_out);
+    TMA_REQUIRE(act == TMA_ACT_NONE || act == TMA_ACT_RELU, TMA_ERR_INVALID_ARG, "%s: act %d", fn, act);
+    TMA_REQUIRE(dtype == TMA_F32 || dtype == TMA_BF16, TMA_ERR_UNSUPPORTED_DTYPE, "%s: dtype %d", fn, dtype);
+    if (n == 0) return TMA_OK;
+    TMA_REQUIRE(rowptr && inv_deg && H && W_self && W_neigh && bias && M_out && Hnext_out, TMA_ERR_INVALID_ARG,
+                "%s: NULL argument", fn);
+    TMA_REQUIRE(ldh >= F_in, TMA_ERR_BAD_SHAPE, "%s: ldh < F_in", fn);
+    hipStream_t s = as_stream(stream);
+    if (int rc = launch_spmm(n, rowptr, colidx, inv_deg, H, ldh, F_in, dtype, M_out, F_in, false, s)) return rc;
+    return launch_sage_gemm_fwd(n, H, ldh, M_out, F_in, W_self, W_neigh, bias, F_out, act, dtype, Hnext_out, s);
+}
+
+extern "C" size_t tma_sage_layer_bwd_workspace_bytes(int64_t n, int32_t F_in, int32_t F_out, int32_t dtype,
+                                                     int32_t need_dH)
+{
+    if (n < 0 || F_in < 1 || F_out < 1) return 0;
+    return tma::plan_bwd(n, F_in, F_out, dtype, need_dH != 0).total();
+}
+
+extern "C" int tma_sage_layer_bwd(int64_t n, const int32_t *rowptr_T, const int32_t *colidx_T, const float *inv_deg,
+                                  const void *H, int64_t ldh, const void *M, const void *Hnext, const void *dHnext,
+                                  const float *W_self, const float *W_neigh, int32_t F_in, int32_t F_out, int32_t act,
+                                  int32_t dtype, float *dW_self, float *dW_neigh, float *dbias, void *dH_out, void *ws,
+                                  size_t ws_bytes, tma_stream_t stream)
+{
+    using namespace tma;
+    const char *fn = "tma_sage_layer_bwd";
+    TMA_REQUIRE(n >= 0 && n <= INT32_MAX, TMA_ERR_INVALID_ARG, "%s: n outside [0, 2^31)", fn);
+    TMA_REQUIRE(F_in >= 1 && F_out >= 1 && F_in <= (1 << 20) && F_out <= (1 << 20), TMA_ERR_BAD_SHAPE,
+                "%s: F_in=%d F_out=%d", fn, F_in, F_out);
+    TMA_REQUIRE(act == TMA_ACT_NONE || act == TMA_ACT_RELU, TMA_ERR_INVALID_ARG, "%s: act %d", fn, act);
+    TMA_REQUIRE(dtype == TMA_F32 || dtype == TMA_BF16, TMA_ERR_UNSUPPORTED_DTYPE, "%s: dtype %d", fn, dtype);
+    TMA_REQUIRE(dW_self && dW_neigh && dbias, TMA_ERR_INVALID_ARG, "%s: gradient output is NULL", fn);
+    TMA_REQUIRE(ws && aligned(ws, 256), TMA_ERR_INVALID_ARG, "%s: workspace NULL or not 256-byte aligned", fn);
+    const bool need_dH = dH_out != nullptr;
+    const BwdWorkspace w = plan_bwd(n, F_in, F_out, dtype, need_dH);
+    TMA_REQUIRE(ws_bytes >= w.total(), TMA_ERR_WORKSPACE_TOO_SMALL, "%s: workspace %zu < %zu bytes", fn, ws_bytes,
+                w.total());
+    if (n > 0) {
+        TMA_REQUIRE(H && M && dHnext && W_self && W_neigh, TMA_ERR_INVALID_ARG, "%s: NULL argument", fn);
+        TMA_REQUIRE(act == TMA_ACT_NONE || Hnext, TMA_ERR_INVALID_ARG, "%s: Hnext is required with ReLU", fn);
+        TMA_REQUIRE(!need_dH || (rowptr_T && inv_deg), TMA_ERR_INVALID_ARG, "%s: graph is NULL", fn);
+        TMA_REQUIRE(ldh >= F_in, TMA_ERR_BAD_SHAPE, "%s: ldh < F_in", fn);
+    }
+    hipStream_t s = as_stream(stream);
+    char *base = static_cast<char *>(ws);
+    void *dMs = base;
+    void *wws = base + w.dm_bytes;
+
+    if (int rc = launch_sage_gemm_bwd_weight(n, H, ldh, M, dHnext, Hnext, F_in, F_out, act, dtype, dW_self, dW_neigh,
+                                             dbias, wws, w.weight_bytes, s))
+        return rc;
+    if (!need_dH || n == 0) return TMA_OK;
+    // dH = dZ W_self^T  (written by the transform)  +  A^T (D^-1 dZ W_neigh^T)  (gathered on top of it)
+    if (int rc = launch_sage_gemm_bwd_data(n, dHnext, Hnext, inv_deg, W_self, W_neigh, F_in, F_out, act, dtype,
+                                           dH_out, dMs, s))
+        return rc;
+    return launch_spmm(n, rowptr_T, colidx_T, nullptr, dMs, F_in, F_in, dtype, dH_out, F_in, true, s);
+}

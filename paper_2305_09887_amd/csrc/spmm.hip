@@ -1,0 +1,314 @@
+// Mean aggregation  M = Abar H  (paper Thm. 1, first equation of its proof) and
+// the plain row gather-sum used by the backward pass.  HBM/gather bound: the
+// flops (2 per gathered element) are negligible.
+//
+// Mapping.  A feature row is cut into 16-byte chunks; G lanes (a power of two,
+// the smallest that covers the row, at most the 64-lane wavefront) own one row
+// and each lane keeps its chunk(s) of the running sum in registers, so every
+// neighbour row is fetched with one coalesced 16-byte load per lane.  The G
+// lanes read up to G neighbour ids with one coalesced load and pass them round
+// by cross-lane shuffle.  Local graphs under random assignment are very sparse
+// (mean local degree 2-5) with a power-law tail, so rows are binned by degree
+// inside the block: a row of more than kHubDegree entries is deferred and then
+// summed by all groups of the workgroup together, each taking every NG-th run
+// of G neighbours, with a fixed-order combine through LDS.  The result of a
+// row depends only on its own neighbour list, never on scheduling.
+#include "kernels.hpp"
+
+namespace tma {
+
+constexpr int kSpmmThreads = 256;
+constexpr int kRowsPerGroup = 4;   // rows a lane group walks through per block
+constexpr int kHubDegree = 64;     // rows longer than this are summed by the whole workgroup
+
+template <typename T>
+struct Chunk;
+
+template <>
+struct Chunk<float> {
+    static constexpr int kElems = 4;
+    static __device__ __forceinline__ void load(const float *p, float (&v)[4])
+    {
+        const float4 x = *reinterpret_cast<const float4 *>(p);
+        v[0] = x.x; v[1] = x.y; v[2] = x.z; v[3] = x.w;
+    }
+    static __device__ __forceinline__ void store(float *p, const float (&v)[4])
+    {
+        *reinterpret_cast<float4 *>(p) = make_float4(v[0], v[1], v[2], v[3]);
+    }
+};
+
+template <>
+struct Chunk<uint16_t> {  // bf16 storage
+    static constexpr int kElems = 8;
+    static __device__ __forceinline__ void load(const uint16_t *p, float (&v)[8])
+    {
+        const uint4 x = *reinterpret_cast<const uint4 *>(p);
+        const uint32_t w[4] = {x.x, x.y, x.z, x.w};
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            v[2 * i] = __uint_as_float(w[i] << 16);
+            v[2 * i + 1] = __uint_as_float(w[i] & 0xFFFF0000u);
+        }
+    }
+    static __device__ __forceinline__ void store(uint16_t *p, const float (&v)[8])
+    {
+        uint32_t w[4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) w[i] = uint32_t(f32_to_bf16(v[2 * i])) | (uint32_t(f32_to_bf16(v[2 * i + 1])) << 16);
+        *reinterpret_cast<uint4 *>(p) = make_uint4(w[0], w[1], w[2], w[3]);
+    }
+};
+
+__device__ __forceinline__ float load_elem(const float *p) { return *p; }
+__device__ __forceinline__ float load_elem(const uint16_t *p) { return bf16_to_f32(*p); }
+__device__ __forceinline__ void store_elem(float *p, float v) { *p = v; }
+__device__ __forceinline__ void store_elem(uint16_t *p, float v) { *p = f32_to_bf16(v); }
+
+// Adds the rows colidx[e] for e = beg, beg+1, ... in runs of G entries that start
+// `run_stride` entries apart.  Every lane of the group gets the same trip counts.
+template <typename T, int G, int CPL>
+__device__ __forceinline__ void gather_sum(const T *__restrict__ in, int64_t ld, const int32_t *__restrict__ colidx,
+                                           int32_t beg, int32_t end, int32_t run_stride, int sub, int n_chunks,
+                                           float (&acc)[CPL][Chunk<T>::kElems])
+{
+    constexpr int E = Chunk<T>::kElems;
+    for (int32_t e0 = beg; e0 < end; e0 += run_stride) {
+        const int cnt = (end - e0) < G ? (end - e0) : G;
+        const int32_t mine = sub < cnt ? colidx[e0 + sub] : 0;
+        int j = 0;
+        for (; j + 4 <= cnt; j += 4) {  // four neighbour rows in flight
+            float v[4][CPL][E];
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const T *row = in + int64_t(__shfl(mine, j + q, G)) * ld;
+#pragma unroll
+                for (int c = 0; c < CPL; ++c)
+                    if (sub + c * G < n_chunks) Chunk<T>::load(row + (sub + c * G) * E, v[q][c]);
+            }
+#pragma unroll
+            for (int q = 0; q < 4; ++q)
+#pragma unroll
+                for (int c = 0; c < CPL; ++c)
+                    if (sub + c * G < n_chunks)
+#pragma unroll
+                        for (int i = 0; i < E; ++i) acc[c][i] += v[q][c][i];
+        }
+        for (; j < cnt; ++j) {
+            const T *row = in + int64_t(__shfl(mine, j, G)) * ld;
+#pragma unroll
+            for (int c = 0; c < CPL; ++c)
+                if (sub + c * G < n_chunks) {
+                    float v[E];
+                    Chunk<T>::load(row + (sub + c * G) * E, v);
+#pragma unroll
+                    for (int i = 0; i < E; ++i) acc[c][i] += v[i];
+                }
+        }
+    }
+}
+
+template <typename T, int G, int CPL>
+__device__ __forceinline__ void finish_row(int64_t v, const float *__restrict__ inv_deg, T *__restrict__ out,
+                                           int64_t ld_out, bool accumulate, int sub, int n_chunks,
+                                           float (&acc)[CPL][Chunk<T>::kElems])
+{
+    constexpr int E = Chunk<T>::kElems;
+    const float scale = inv_deg ? inv_deg[v] : 1.0f;
+#pragma unroll
+    for (int c = 0; c < CPL; ++c)
+        if (sub + c * G < n_chunks) {
+            T *dst = out + v * ld_out + (sub + c * G) * E;
+            float r[E];
+#pragma unroll
+            for (int i = 0; i < E; ++i) r[i] = acc[c][i] * scale;
+            if (accumulate) {
+                float old[E];
+                Chunk<T>::load(dst, old);
+#pragma unroll
+                for (int i = 0; i < E; ++i) r[i] += old[i];
+            }
+            Chunk<T>::store(dst, r);
+        }
+}
+
+template <typename T, int G, int CPL>
+__global__ __launch_bounds__(kSpmmThreads) void spmm_rows_kernel(int64_t n, const int32_t *__restrict__ rowptr,
+                                                                 const int32_t *__restrict__ colidx,
+                                                                 const float *__restrict__ inv_deg,
+                                                                 const T *__restrict__ in, int64_t ld_in,
+                                                                 T *__restrict__ out, int64_t ld_out, int n_chunks,
+                                                                 int accumulate)
+{
+    constexpr int E = Chunk<T>::kElems;
+    constexpr int NG = kSpmmThreads / G;
+    constexpr int RPB = NG * kRowsPerGroup;
+    __shared__ int32_t hub_rows[RPB];
+    __shared__ int32_t hub_count;
+    __shared__ float partial[NG][G * CPL * E];
+
+    const int sub = threadIdx.x % G;
+    const int grp = threadIdx.x / G;
+    if (threadIdx.x == 0) hub_count = 0;
+    __syncthreads();
+
+    const int64_t base = int64_t(blockIdx.x) * RPB;
+    for (int i = 0; i < kRowsPerGroup; ++i) {
+        const int64_t v = base + grp + i * NG;
+        if (v >= n) break;
+        const int32_t beg = rowptr[v], end = rowptr[v + 1];
+        if (end - beg > kHubDegree) {
+            if (sub == 0) hub_rows[atomicAdd(&hub_count, 1)] = int32_t(v - base);
+            continue;
+        }
+        float acc[CPL][E];
+#pragma unroll
+        for (int c = 0; c < CPL; ++c)
+#pragma unroll
+            for (int k = 0; k < E; ++k) acc[c][k] = 0.0f;
+        gather_sum<T, G, CPL>(in, ld_in, colidx, beg, end, G, sub, n_chunks, acc);
+        finish_row<T, G, CPL>(v, inv_deg, out, ld_out, accumulate != 0, sub, n_chunks, acc);
+    }
+    __syncthreads();
+
+    const int n_hubs = hub_count;
+    for (int h = 0; h < n_hubs; ++h) {
+        const int64_t v = base + hub_rows[h];
+        const int32_t beg = rowptr[v], end = rowptr[v + 1];
+        float acc[CPL][E];
+#pragma unroll
+        for (int c = 0; c < CPL; ++c)
+#pragma unroll
+            for (int k = 0; k < E; ++k) acc[c][k] = 0.0f;
+        if (beg + grp * G < end) gather_sum<T, G, CPL>(in, ld_in, colidx, beg + grp * G, end, NG * G, sub, n_chunks, acc);
+#pragma unroll
+        for (int c = 0; c < CPL; ++c)
+#pragma unroll
+            for (int k = 0; k < E; ++k) partial[grp][(c * G + sub) * E + k] = acc[c][k];
+        __syncthreads();
+        if (grp == 0) {
+#pragma unroll
+            for (int c = 0; c < CPL; ++c)
+#pragma unroll
+                for (int k = 0; k < E; ++k) {
+                    float s = 0.0f;
+                    for (int g = 0; g < NG; ++g) s += partial[g][(c * G + sub) * E + k];  // fixed order
+                    acc[c][k] = s;
+                }
+            finish_row<T, G, CPL>(v, inv_deg, out, ld_out, accumulate != 0, sub, n_chunks, acc);
+        }
+        __syncthreads();
+    }
+}
+
+// Any F, any alignment: one wavefront per row, lane owns elements lane, lane+64, ...
+template <typename T>
+__global__ __launch_bounds__(kSpmmThreads) void spmm_rows_generic_kernel(int64_t n, const int32_t *__restrict__ rowptr,
+                                                                         const int32_t *__restrict__ colidx,
+                                                                         const float *__restrict__ inv_deg,
+                                                                         const T *__restrict__ in, int64_t ld_in,
+                                                                         T *__restrict__ out, int64_t ld_out, int F,
+                                                                         int accumulate)
+{
+    constexpr int kPer = 8;  // elements per lane per sweep: 512 features per sweep
+    const int lane = threadIdx.x % kWave;
+    const int64_t v = int64_t(blockIdx.x) * (kSpmmThreads / kWave) + threadIdx.x / kWave;
+    if (v >= n) return;
+    const int32_t beg = rowptr[v], end = rowptr[v + 1];
+    const float scale = inv_deg ? inv_deg[v] : 1.0f;
+    for (int f0 = 0; f0 < F; f0 += kWave * kPer) {
+        float acc[kPer];
+#pragma unroll
+        for (int k = 0; k < kPer; ++k) acc[k] = 0.0f;
+        for (int32_t e = beg; e < end; ++e) {
+            const T *row = in + int64_t(colidx[e]) * ld_in;
+#pragma unroll
+            for (int k = 0; k < kPer; ++k) {
+                const int f = f0 + k * kWave + lane;
+                if (f < F) acc[k] += load_elem(row + f);
+            }
+        }
+#pragma unroll
+        for (int k = 0; k < kPer; ++k) {
+            const int f = f0 + k * kWave + lane;
+            if (f < F) {
+                T *dst = out + v * ld_out + f;
+                float r = acc[k] * scale;
+                if (accumulate) r += load_elem(dst);
+                store_elem(dst, r);
+            }
+        }
+    }
+}
+
+template <typename T, int G, int CPL>
+static void launch_rows(int64_t n, const int32_t *rowptr, const int32_t *colidx, const float *inv_deg, const T *in,
+                        int64_t ld_in, T *out, int64_t ld_out, int n_chunks, bool accumulate, hipStream_t s)
+{
+    constexpr int RPB = (kSpmmThreads / G) * kRowsPerGroup;
+    char name[48];
+    snprintf(name, sizeof(name), "%s_%s_g%dx%d", inv_deg ? "spmm_mean" : "spmm_sum", sizeof(T) == 4 ? "f32" : "bf16", G,
+             CPL);
+    TMA_TIMED(name, s);
+    hipLaunchKernelGGL((spmm_rows_kernel<T, G, CPL>), dim3(unsigned(ceil_div(n, RPB))), dim3(kSpmmThreads), 0, s, n,
+                       rowptr, colidx, inv_deg, in, ld_in, out, ld_out, n_chunks, accumulate ? 1 : 0);
+}
+
+template <typename T>
+static int launch_typed(int64_t n, const int32_t *rowptr, const int32_t *colidx, const float *inv_deg, const T *in,
+                        int64_t ld_in, int32_t F, T *out, int64_t ld_out, bool accumulate, hipStream_t s)
+{
+    const size_t row_bytes = size_t(F) * sizeof(T);
+    const bool vec_ok = row_bytes % 16 == 0 && (size_t(ld_in) * sizeof(T)) % 16 == 0 &&
+                        (size_t(ld_out) * sizeof(T)) % 16 == 0 && aligned(in, 16) && aligned(out, 16) &&
+                        row_bytes / 16 <= 256;
+    if (!vec_ok) {
+        TMA_TIMED(inv_deg ? "spmm_mean_generic" : "spmm_sum_generic", s);
+        hipLaunchKernelGGL((spmm_rows_generic_kernel<T>), dim3(unsigned(ceil_div(n, kSpmmThreads / kWave))),
+                           dim3(kSpmmThreads), 0, s, n, rowptr, colidx, inv_deg, in, ld_in, out, ld_out, F,
+                           accumulate ? 1 : 0);
+        return check_launch("spmm (generic)");
+    }
+    const int nc = int(row_bytes / 16);
+#define TMA_SPMM_CASE(G, CPL) launch_rows<T, G, CPL>(n, rowptr, colidx, inv_deg, in, ld_in, out, ld_out, nc, accumulate, s)
+    if (nc <= 4) TMA_SPMM_CASE(4, 1);
+    else if (nc <= 8) TMA_SPMM_CASE(8, 1);
+    else if (nc <= 16) TMA_SPMM_CASE(16, 1);
+    else if (nc <= 32) TMA_SPMM_CASE(32, 1);
+    else if (nc <= 64) TMA_SPMM_CASE(64, 1);
+    else if (nc <= 128) TMA_SPMM_CASE(64, 2);
+    else TMA_SPMM_CASE(64, 4);
+#undef TMA_SPMM_CASE
+    return check_launch("spmm");
+}
+
+int launch_spmm(int64_t n, const int32_t *rowptr, const int32_t *colidx, const float *inv_deg, const void *in,
+                int64_t ld_in, int32_t F, int32_t dtype, void *out, int64_t ld_out, bool accumulate,
+                hipStream_t stream)
+{
+    if (n == 0 || F == 0) return TMA_OK;
+    if (dtype == TMA_F32)
+        return launch_typed<float>(n, rowptr, colidx, inv_deg, static_cast<const float *>(in), ld_in, F,
+                                   static_cast<float *>(out), ld_out, accumulate, stream);
+    if (dtype == TMA_BF16)
+        return launch_typed<uint16_t>(n, rowptr, colidx, inv_deg, static_cast<const uint16_t *>(in), ld_in, F,
+                                      static_cast<uint16_t *>(out), ld_out, accumulate, stream);
+    return fail(TMA_ERR_UNSUPPORTED_DTYPE, "spmm: dtype %d", dtype);
+}
+
+}  // namespace tma
+
+extern "C" int tma_mean_aggregate(int64_t n, const int32_t *rowptr, const int32_t *colidx, const float *inv_deg,
+                                  const void *H, int64_t ldh, int32_t F, int32_t dtype, void *M_out, int64_t ldm,
+                                  tma_stream_t stream)
+{
+    using namespace tma;
+    const char *fn = "tma_mean_aggregate";
+    TMA_REQUIRE(n >= 0 && n <= INT32_MAX && F >= 0, TMA_ERR_INVALID_ARG, "%s: bad n or F", fn);
+    TMA_REQUIRE(dtype == TMA_F32 || dtype == TMA_BF16, TMA_ERR_UNSUPPORTED_DTYPE, "%s: dtype %d", fn, dtype);
+    if (n == 0 || F == 0) return TMA_OK;
+    TMA_REQUIRE(rowptr && inv_deg && H && M_out, TMA_ERR_INVALID_ARG, "%s: NULL argument", fn);
+    TMA_REQUIRE(ldh >= F && ldm >= F, TMA_ERR_BAD_SHAPE, "%s: leading dimension smaller than F", fn);
+    TMA_REQUIRE(H != M_out, TMA_ERR_INVALID_ARG, "%s: in-place aggregation is not supported", fn);
+    return launch_spmm(n, rowptr, colidx, inv_deg, H, ldh, F, dtype, M_out, ldm, false, as_stream(stream));
+}

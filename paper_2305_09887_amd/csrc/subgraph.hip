@@ -1,0 +1,359 @@
+// Node-induced subgraph of one partition (paper, Preliminaries):
+//   V^(p) = alpha^-1(p),  E^(p) = edges of E with both end points in V^(p).
+//
+// Integer-only, HBM-scan bound.  Two prefix scans (local-node flags, kept
+// degrees) done as reduce -> scan-of-block-sums -> apply, which needs no
+// inter-block waiting, and a per-row order-preserving compaction that uses
+// wavefront ballots.  Sixteen lanes share one global row (global average
+// degree of the workloads is about 20), four rows per wavefront.
+#include "common.hpp"
+
+namespace tma {
+
+constexpr int kScanThreads = 256;
+constexpr int kScanItems = 8;                           // consecutive items per thread
+constexpr int kScanTile = kScanThreads * kScanItems;    // items per block
+constexpr int kRowLanes = 16;                           // lanes per CSR row
+constexpr int kRowsPerBlock = 256 / kRowLanes;
+
+// ---- value sources / sinks of the two scans -------------------------------
+struct FlagIn {  // 1 where the node belongs to partition p
+    const int32_t *part;
+    int32_t p;
+    __device__ int32_t load(int64_t i) const { return part[i] == p ? 1 : 0; }
+};
+struct FlagOut {  // local id = exclusive rank; inverse map for the first `cap` local nodes
+    int32_t *g2l;
+    int32_t *l2g;
+    int64_t cap;
+    __device__ void store(int64_t i, int64_t prefix, int32_t v, int64_t /*n*/) const
+    {
+        g2l[i] = v ? int32_t(prefix) : -1;
+        if (v && prefix < cap) l2g[prefix] = int32_t(i);
+    }
+};
+struct DegIn {
+    const int32_t *deg;
+    __device__ int32_t load(int64_t i) const { return deg[i]; }
+};
+struct DegOut {  // rowptr_loc[i] = exclusive prefix, rowptr_loc[n] = total
+    int32_t *rowptr_loc;
+    __device__ void store(int64_t i, int64_t prefix, int32_t v, int64_t n) const
+    {
+        rowptr_loc[i] = int32_t(prefix);
+        if (i == n - 1) rowptr_loc[n] = int32_t(prefix + v);
+    }
+};
+
+__device__ __forceinline__ int64_t effective_n(const int64_t *d_n, int64_t cap)
+{
+    if (!d_n) return cap;
+    int64_t n = *d_n;
+    return n < cap ? n : cap;
+}
+
+// Block-wide exclusive scan of one int per thread (256 threads = 4 wavefronts).
+__device__ __forceinline__ int32_t block_exclusive_scan(int32_t v, int32_t &block_total)
+{
+    __shared__ int32_t wave_sums[kScanThreads / kWave];
+    const int lane = threadIdx.x & (kWave - 1);
+    const int wave = threadIdx.x / kWave;
+    int32_t incl = v;
+#pragma unroll
+    for (int d = 1; d < kWave; d <<= 1) {
+        int32_t t = __shfl_up(incl, d, kWave);
+        if (lane >= d) incl += t;
+    }
+    if (lane == kWave - 1) wave_sums[wave] = incl;
+    __syncthreads();
+    int32_t offset = 0, total = 0;
+#pragma unroll
+    for (int w = 0; w < kScanThreads / kWave; ++w) {
+        int32_t s = wave_sums[w];
+        if (w < wave) offset += s;
+        total += s;
+    }
+    __syncthreads();
+    block_total = total;
+    return offset + incl - v;
+}
+
+template <class In>
+__global__ __launch_bounds__(kScanThreads) void scan_reduce_kernel(const int64_t *d_n, int64_t cap, In in,
+                                                                   int64_t *__restrict__ block_sums)
+{
+    const int64_t n = effective_n(d_n, cap);
+    const int64_t base = int64_t(blockIdx.x) * kScanTile + int64_t(threadIdx.x) * kScanItems;
+    int32_t c = 0;
+#pragma unroll
+    for (int j = 0; j < kScanItems; ++j)
+        if (base + j < n) c += in.load(base + j);
+    int32_t total;
+    block_exclusive_scan(c, total);
+    if (threadIdx.x == 0) block_sums[blockIdx.x] = total;
+}
+
+// One block turns the per-block sums into exclusive offsets and stores the
+// grand total.  nb is at most a few 10^4 (10^8 nodes / 2048).
+__global__ __launch_bounds__(1024) void scan_sums_kernel(int64_t nb, int64_t *__restrict__ block_sums,
+                                                         int64_t *__restrict__ total_out)
+{
+    __shared__ int64_t wave_sums[1024 / kWave];
+    __shared__ int64_t carry_s;
+    const int lane = threadIdx.x & (kWave - 1);
+    const int wave = threadIdx.x / kWave;
+    if (threadIdx.x == 0) carry_s = 0;
+    __syncthreads();
+    for (int64_t base = 0; base < nb; base += 1024) {
+        const int64_t i = base + threadIdx.x;
+        const int64_t v = i < nb ? block_sums[i] : 0;
+        int64_t incl = v;
+#pragma unroll
+        for (int d = 1; d < kWave; d <<= 1) {
+            int64_t t = __shfl_up(incl, d, kWave);
+            if (lane >= d) incl += t;
+        }
+        if (lane == kWave - 1) wave_sums[wave] = incl;
+        __syncthreads();
+        int64_t offset = carry_s, chunk_total = 0;
+        for (int w = 0; w < 1024 / kWave; ++w) {
+            int64_t s = wave_sums[w];
+            if (w < wave) offset += s;
+            chunk_total += s;
+        }
+        if (i < nb) block_sums[i] = offset + incl - v;
+        __syncthreads();
+        if (threadIdx.x == 0) carry_s += chunk_total;
+        __syncthreads();
+    }
+    if (threadIdx.x == 0) *total_out = carry_s;
+}
+
+template <class In, class Out>
+__global__ __launch_bounds__(kScanThreads) void scan_apply_kernel(const int64_t *d_n, int64_t cap, In in, Out out,
+                                                                  const int64_t *__restrict__ block_offsets)
+{
+    const int64_t n = effective_n(d_n, cap);
+    const int64_t base = int64_t(blockIdx.x) * kScanTile + int64_t(threadIdx.x) * kScanItems;
+    int32_t v[kScanItems];
+    int32_t c = 0;
+#pragma unroll
+    for (int j = 0; j < kScanItems; ++j) {
+        v[j] = (base + j < n) ? in.load(base + j) : 0;
+        c += v[j];
+    }
+    int32_t total;
+    int64_t prefix = block_offsets[blockIdx.x] + block_exclusive_scan(c, total);
+#pragma unroll
+    for (int j = 0; j < kScanItems; ++j) {
+        if (base + j < n) out.store(base + j, prefix, v[j], n);
+        prefix += v[j];
+    }
+}
+
+// rowptr_loc[0] = 0 also when the partition is empty (the apply kernel then stores nothing).
+__global__ void write_zero_kernel(int32_t *p) { *p = 0; }
+
+// Kept degree of every local row: entries whose column is local too.
+__global__ __launch_bounds__(256) void row_count_kernel(const int64_t *d_n_loc, int64_t cap,
+                                                        const int32_t *__restrict__ l2g,
+                                                        const int64_t *__restrict__ rowptr,
+                                                        const int32_t *__restrict__ colidx,
+                                                        const int32_t *__restrict__ g2l,
+                                                        int32_t *__restrict__ deg)
+{
+    const int64_t n_loc = effective_n(d_n_loc, cap);
+    const int sub = threadIdx.x % kRowLanes;
+    const int64_t i = int64_t(blockIdx.x) * kRowsPerBlock + threadIdx.x / kRowLanes;
+    int32_t c = 0;
+    if (i < n_loc) {
+        const int64_t v = l2g[i];
+        const int64_t end = rowptr[v + 1];
+        for (int64_t e = rowptr[v] + sub; e < end; e += kRowLanes) c += g2l[colidx[e]] >= 0 ? 1 : 0;
+    }
+#pragma unroll
+    for (int d = kRowLanes / 2; d >= 1; d >>= 1) c += __shfl_xor(c, d, kWave);
+    if (i < n_loc && sub == 0) deg[i] = c;
+}
+
+// Order-preserving compaction of each local row into colidx_loc, relabelled.
+__global__ __launch_bounds__(256) void row_fill_kernel(int64_t n_loc, const int32_t *__restrict__ l2g,
+                                                       const int64_t *__restrict__ rowptr,
+                                                       const int32_t *__restrict__ colidx,
+                                                       const int32_t *__restrict__ g2l,
+                                                       const int32_t *__restrict__ rowptr_loc,
+                                                       int32_t *__restrict__ colidx_loc,
+                                                       float *__restrict__ inv_deg)
+{
+    const int sub = threadIdx.x % kRowLanes;
+    const int group_shift = ((threadIdx.x % kWave) / kRowLanes) * kRowLanes;
+    const int64_t i = int64_t(blockIdx.x) * kRowsPerBlock + threadIdx.x / kRowLanes;
+    const bool live = i < n_loc;
+    int64_t beg = 0, end = 0;
+    int32_t out = 0;
+    if (live) {
+        const int64_t v = l2g[i];
+        beg = rowptr[v];
+        end = rowptr[v + 1];
+        out = rowptr_loc[i];
+        if (sub == 0) {
+            const int32_t d = rowptr_loc[i + 1] - out;
+            inv_deg[i] = d > 0 ? 1.0f / float(d) : 0.0f;
+        }
+    }
+    // Every lane of the wavefront runs the same number of rounds so that the
+    // ballot below is executed by all of them.
+    int64_t len = end - beg;
+#pragma unroll
+    for (int d = kRowLanes; d < kWave; d <<= 1) {
+        int64_t o = __shfl_xor(len, d, kWave);
+        len = o > len ? o : len;
+    }
+    for (int64_t off = 0; off < len; off += kRowLanes) {
+        const int64_t e = beg + off + sub;
+        int32_t lid = -1;
+        if (e < end) lid = g2l[colidx[e]];
+        const uint64_t ballot = __ballot(lid >= 0);
+        const uint32_t mine = uint32_t(ballot >> group_shift) & ((1u << kRowLanes) - 1u);
+        if (lid >= 0) colidx_loc[out + __popc(mine & ((1u << sub) - 1u))] = lid;
+        out += __popc(mine);
+    }
+}
+
+struct CountWorkspace {
+    int64_t *node_block_sums;  // [nb_nodes]
+    int64_t *row_block_sums;   // [nb_rows]
+    int64_t *sizes;            // [2] n_loc, nnz_loc
+    int32_t *deg;              // [cap_n_loc]
+    size_t bytes;
+};
+
+static CountWorkspace carve(void *ws, int64_t n_nodes, int64_t cap)
+{
+    const int64_t nb_nodes = ceil_div(n_nodes > 0 ? n_nodes : 1, kScanTile);
+    const int64_t nb_rows = ceil_div(cap > 0 ? cap : 1, kScanTile);
+    char *p = static_cast<char *>(ws);
+    size_t off = 0;
+    CountWorkspace w;
+    w.node_block_sums = reinterpret_cast<int64_t *>(p + off);
+    off += round_up(size_t(nb_nodes) * 8, 256);
+    w.row_block_sums = reinterpret_cast<int64_t *>(p + off);
+    off += round_up(size_t(nb_rows) * 8, 256);
+    w.sizes = reinterpret_cast<int64_t *>(p + off);
+    off += 256;
+    w.deg = reinterpret_cast<int32_t *>(p + off);
+    off += round_up(size_t(cap > 0 ? cap : 1) * 4, 256);
+    w.bytes = off;
+    return w;
+}
+
+}  // namespace tma
+
+extern "C" size_t tma_induced_subgraph_workspace_bytes(int64_t n_nodes, int64_t cap_n_loc)
+{
+    if (n_nodes < 0 || cap_n_loc < 0) return 0;
+    return tma::carve(nullptr, n_nodes, cap_n_loc).bytes;
+}
+
+extern "C" int tma_induced_subgraph_count(int64_t n_nodes, const int64_t *rowptr, const int32_t *colidx,
+                                          const int32_t *part, int32_t p, int32_t *g2l_out, int32_t *l2g_out,
+                                          int32_t *rowptr_loc_out, int64_t cap_n_loc, int64_t *h_n_loc,
+                                          int64_t *h_nnz_loc, void *ws, size_t ws_bytes, tma_stream_t stream)
+{
+    using namespace tma;
+    const char *fn = "tma_induced_subgraph_count";
+    TMA_REQUIRE(n_nodes >= 0 && n_nodes <= INT32_MAX, TMA_ERR_INVALID_ARG, "%s: n_nodes outside [0, 2^31)", fn);
+    TMA_REQUIRE(cap_n_loc >= 0 && cap_n_loc <= n_nodes, TMA_ERR_INVALID_ARG,
+                "%s: cap_n_loc must lie in [0, n_nodes]", fn);
+    TMA_REQUIRE(h_n_loc && h_nnz_loc && rowptr_loc_out, TMA_ERR_INVALID_ARG,
+                "%s: h_n_loc / h_nnz_loc / rowptr_loc_out is NULL", fn);
+    TMA_REQUIRE(n_nodes == 0 || (rowptr && part && g2l_out), TMA_ERR_INVALID_ARG,
+                "%s: rowptr / part / g2l_out is NULL", fn);
+    TMA_REQUIRE(cap_n_loc == 0 || l2g_out, TMA_ERR_INVALID_ARG, "%s: l2g_out is NULL", fn);
+    TMA_REQUIRE(ws && aligned(ws, 256), TMA_ERR_INVALID_ARG, "%s: workspace NULL or not 256-byte aligned", fn);
+    CountWorkspace w = carve(ws, n_nodes, cap_n_loc);
+    TMA_REQUIRE(ws_bytes >= w.bytes, TMA_ERR_WORKSPACE_TOO_SMALL, "%s: workspace %zu < %zu bytes", fn, ws_bytes,
+                w.bytes);
+    hipStream_t s = as_stream(stream);
+
+    const unsigned nb_nodes = unsigned(ceil_div(n_nodes > 0 ? n_nodes : 1, kScanTile));
+    const unsigned nb_rows = unsigned(ceil_div(cap_n_loc > 0 ? cap_n_loc : 1, kScanTile));
+    FlagIn fin{part, p};
+    FlagOut fout{g2l_out, l2g_out, cap_n_loc};
+    // 1. rank local nodes
+    {
+        TMA_TIMED("scan_reduce_flags", s);
+        hipLaunchKernelGGL(scan_reduce_kernel<FlagIn>, dim3(nb_nodes), dim3(kScanThreads), 0, s, nullptr, n_nodes,
+                           fin, w.node_block_sums);
+    }
+    {
+        TMA_TIMED("scan_sums", s);
+        hipLaunchKernelGGL(scan_sums_kernel, dim3(1), dim3(1024), 0, s, int64_t(nb_nodes), w.node_block_sums,
+                           w.sizes + 0);
+    }
+    {
+        TMA_TIMED("scan_apply_flags", s);
+        hipLaunchKernelGGL((scan_apply_kernel<FlagIn, FlagOut>), dim3(nb_nodes), dim3(kScanThreads), 0, s, nullptr,
+                           n_nodes, fin, fout, w.node_block_sums);
+    }
+    // 2. kept degree per local row, then rowptr_loc by a second scan
+    hipLaunchKernelGGL(write_zero_kernel, dim3(1), dim3(1), 0, s, rowptr_loc_out);
+    if (cap_n_loc > 0) {
+        const unsigned row_blocks = unsigned(ceil_div(cap_n_loc, kRowsPerBlock));
+        TMA_TIMED("row_count", s);
+        hipLaunchKernelGGL(row_count_kernel, dim3(row_blocks), dim3(256), 0, s, w.sizes + 0, cap_n_loc, l2g_out,
+                           rowptr, colidx, g2l_out, w.deg);
+    }
+    DegIn din{w.deg};
+    DegOut dout{rowptr_loc_out};
+    {
+        TMA_TIMED("scan_reduce_deg", s);
+        hipLaunchKernelGGL(scan_reduce_kernel<DegIn>, dim3(nb_rows), dim3(kScanThreads), 0, s, w.sizes + 0,
+                           cap_n_loc, din, w.row_block_sums);
+    }
+    {
+        TMA_TIMED("scan_sums", s);
+        hipLaunchKernelGGL(scan_sums_kernel, dim3(1), dim3(1024), 0, s, int64_t(nb_rows), w.row_block_sums,
+                           w.sizes + 1);
+    }
+    {
+        TMA_TIMED("scan_apply_deg", s);
+        hipLaunchKernelGGL((scan_apply_kernel<DegIn, DegOut>), dim3(nb_rows), dim3(kScanThreads), 0, s, w.sizes + 0,
+                           cap_n_loc, din, dout, w.row_block_sums);
+    }
+    if (int rc = check_launch(fn)) return rc;
+
+    int64_t h_sizes[2] = {0, 0};
+    TMA_HIP_TRY(hipMemcpyAsync(h_sizes, w.sizes, sizeof(h_sizes), hipMemcpyDeviceToHost, s), fn);
+    TMA_HIP_TRY(hipStreamSynchronize(s), fn);
+    *h_n_loc = h_sizes[0];
+    *h_nnz_loc = h_sizes[1];
+    TMA_REQUIRE(h_sizes[0] <= cap_n_loc, TMA_ERR_BAD_SHAPE,
+                "%s: partition has %lld nodes but cap_n_loc is %lld (nnz reported covers the first cap rows only)",
+                fn, (long long)h_sizes[0], (long long)cap_n_loc);
+    TMA_REQUIRE(h_sizes[1] <= INT32_MAX, TMA_ERR_BAD_SHAPE, "%s: %lld kept entries do not fit int32 local indexing",
+                fn, (long long)h_sizes[1]);
+    return TMA_OK;
+}
+
+extern "C" int tma_induced_subgraph_fill(int64_t n_nodes, const int64_t *rowptr, const int32_t *colidx,
+                                         const int32_t *part, int32_t p, const int32_t *g2l, const int32_t *l2g,
+                                         int64_t n_loc, const int32_t *rowptr_loc, int32_t *colidx_loc_out,
+                                         float *inv_deg_out, tma_stream_t stream)
+{
+    using namespace tma;
+    const char *fn = "tma_induced_subgraph_fill";
+    (void)part;
+    (void)p;
+    TMA_REQUIRE(n_nodes >= 0 && n_loc >= 0 && n_loc <= n_nodes, TMA_ERR_INVALID_ARG, "%s: bad n_nodes / n_loc", fn);
+    if (n_loc == 0) return TMA_OK;
+    TMA_REQUIRE(rowptr && g2l && l2g && rowptr_loc && inv_deg_out, TMA_ERR_INVALID_ARG, "%s: NULL argument", fn);
+    // colidx / colidx_loc_out may be NULL only for a graph without entries; not knowable here without a
+    // device read, so they are required whenever there are local rows.
+    TMA_REQUIRE(colidx && colidx_loc_out, TMA_ERR_INVALID_ARG, "%s: colidx / colidx_loc_out is NULL", fn);
+    const unsigned blocks = unsigned(ceil_div(n_loc, kRowsPerBlock));
+    TMA_TIMED("row_fill", as_stream(stream));
+    hipLaunchKernelGGL(row_fill_kernel, dim3(blocks), dim3(256), 0, as_stream(stream), n_loc, l2g, rowptr, colidx,
+                       g2l, rowptr_loc, colidx_loc_out, inv_deg_out);
+    return check_launch(fn);
+}

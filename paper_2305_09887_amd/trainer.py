@@ -1,0 +1,103 @@
+"""One TMA trainer's local training loop (Alg. 2 of the paper) on one HIP stream.
+
+Sequencing and buffer ownership only: every numerical step is a call into the
+C ABI (``binding``).  All buffers are allocated once in ``__init__``; ``step``
+allocates nothing, so several trainers can be time-sliced on their own streams
+without touching the allocator.
+"""
+from __future__ import annotations
+
+import torch
+
+from . import binding as B
+
+
+class LocalTrainer:
+    """Full-batch L-layer mean-aggregation GraphSAGE on a local induced subgraph.
+
+    ``dims`` = [F_0, F_1, ..., F_L]; ReLU between layers, identity on the last;
+    mean softmax cross-entropy over all local nodes; plain SGD.
+    Parameters live in one flat fp32 vector ``W`` (layer by layer: W_self,
+    W_neigh, bias), gradients in ``dW`` with the same layout, so that the
+    optimizer step and the averaging operator are single launches.
+    """
+
+    def __init__(self, rowptr, colidx, inv_deg, X, labels, dims, params=None, stream=None,
+                 rowptr_T=None, colidx_T=None):
+        self.rowptr, self.colidx, self.inv_deg = rowptr, colidx, inv_deg
+        # transposed graph for the backward gather; the same CSR for a symmetric graph
+        self.rowptr_T = rowptr if rowptr_T is None else rowptr_T
+        self.colidx_T = colidx if colidx_T is None else colidx_T
+        self.X, self.labels = X, labels
+        self.dims = list(dims)
+        self.L = len(dims) - 1
+        self.n = X.shape[0]
+        self.dtype = X.dtype
+        dev = X.device
+        self.stream = stream if stream is not None else torch.cuda.current_stream()
+        if X.shape[1] != dims[0]:
+            raise B.TmaError("LocalTrainer: X width differs from dims[0]")
+
+        self.n_params = sum(2 * fi * fo + fo for fi, fo in zip(dims[:-1], dims[1:]))
+        self.W = torch.zeros(self.n_params, dtype=torch.float32, device=dev)
+        self.dW = torch.zeros(self.n_params, dtype=torch.float32, device=dev)
+        self.layers, self.grads = self._views(self.W), self._views(self.dW)
+        if params is not None:
+            self.load_params(params)
+
+        n = max(self.n, 1)
+        self.H = [X] + [torch.empty((n, f), dtype=self.dtype, device=dev)[: self.n] for f in dims[1:]]
+        self.M = [torch.empty((n, f), dtype=self.dtype, device=dev)[: self.n] for f in dims[:-1]]
+        # gradient w.r.t. H[l] for l = 1..L (index l); dH[L] is d(loss)/d(logits)
+        self.dH = [None] + [torch.empty((n, f), dtype=self.dtype, device=dev)[: self.n] for f in dims[1:]]
+        dt = B._feat_dtype(X)
+        ws_bytes = max(B.tma_sage_layer_bwd_workspace_bytes(self.n, fi, fo, dt, l > 0)
+                       for l, (fi, fo) in enumerate(zip(dims[:-1], dims[1:])))
+        ws_bytes = max(ws_bytes, B.tma_loss_workspace_bytes(self.n, dims[-1]))
+        self.ws = torch.empty(max(ws_bytes, 256), dtype=torch.uint8, device=dev)
+        self.loss = torch.zeros(1, dtype=torch.float32, device=dev)
+        self.steps_done = 0
+
+    def _views(self, flat):
+        out, o = [], 0
+        for fi, fo in zip(self.dims[:-1], self.dims[1:]):
+            ws = flat[o:o + fi * fo].view(fi, fo); o += fi * fo
+            wn = flat[o:o + fi * fo].view(fi, fo); o += fi * fo
+            b = flat[o:o + fo]; o += fo
+            out.append((ws, wn, b))
+        return out
+
+    def load_params(self, params):
+        """params: list of (W_self, W_neigh, bias) arrays/tensors per layer."""
+        with torch.cuda.stream(self.stream):
+            for (ws, wn, b), (s, nn_, bb) in zip(self.layers, params):
+                ws.copy_(torch.as_tensor(s, dtype=torch.float32))
+                wn.copy_(torch.as_tensor(nn_, dtype=torch.float32))
+                b.copy_(torch.as_tensor(bb, dtype=torch.float32))
+
+    def forward(self):
+        for l in range(self.L):
+            ws, wn, b = self.layers[l]
+            act = B.TMA_ACT_RELU if l < self.L - 1 else B.TMA_ACT_NONE
+            B.tma_sage_layer_fwd(self.rowptr, self.colidx, self.inv_deg, self.H[l], ws, wn, b, act,
+                                 M_out=self.M[l], Hnext_out=self.H[l + 1], stream=self.stream)
+        return self.H[self.L]
+
+    def backward(self):
+        B.tma_softmax_ce(self.H[self.L], self.labels, loss_out=self.loss, dlogits_out=self.dH[self.L],
+                         ws=self.ws, stream=self.stream)
+        for l in range(self.L - 1, -1, -1):
+            ws, wn, _ = self.layers[l]
+            dws, dwn, db = self.grads[l]
+            act = B.TMA_ACT_RELU if l < self.L - 1 else B.TMA_ACT_NONE
+            B.tma_sage_layer_bwd(self.rowptr_T, self.colidx_T, self.inv_deg, self.H[l], self.M[l], self.H[l + 1],
+                                 self.dH[l + 1], ws, wn, act, dW_self=dws, dW_neigh=dwn, dbias=db,
+                                 dH_out=self.dH[l], need_dH=l > 0, ws=self.ws, stream=self.stream)
+
+    def step(self, lr: float):
+        """One iteration of Alg. 2's loop body on the full local subgraph."""
+        self.forward()
+        self.backward()
+        B.tma_sgd_step(self.W, self.dW, lr, stream=self.stream)
+        self.steps_done += 1
+        return self.loss

@@ -1,0 +1,54 @@
+"""The C-ABI library loads without a GPU and exports every function include/tma.h declares."""
+import ctypes
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+LIB = os.path.join(ROOT, "paper_2305_09887_amd", "libtma.so")
+
+
+def _declared_functions():
+    text = open(os.path.join(ROOT, "include", "tma.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(tma_[a-z0-9_]+)\s*\(", text)))
+
+
+@pytest.fixture(scope="module")
+def lib():
+    if not os.path.exists(LIB):
+        from paper_2305_09887_amd import build
+        build.build(verbose=False)
+    return ctypes.CDLL(LIB)
+
+
+def test_header_declares_the_north_star_calls():
+    names = _declared_functions()
+    for need in ("tma_partition", "tma_induced_subgraph_count", "tma_induced_subgraph_fill", "tma_sage_layer_fwd",
+                 "tma_sage_layer_bwd", "tma_average"):
+        assert need in names
+
+
+def test_library_exports_every_declared_symbol(lib):
+    for name in _declared_functions():
+        assert hasattr(lib, name), f"libtma.so does not export {name}"
+
+
+def test_binding_lists_the_same_symbols():
+    from paper_2305_09887_amd import binding
+    assert sorted(binding.EXPORTS) == _declared_functions()
+
+
+def test_host_side_argument_validation_needs_no_gpu(lib):
+    lib.tma_last_error.restype = ctypes.c_char_p
+    assert lib.tma_version() >= 100
+    # K = 0 is rejected before anything touches a device
+    rc = lib.tma_partition(ctypes.c_int64(8), None, ctypes.c_int64(0), ctypes.c_int32(0), ctypes.c_uint64(1), None, None)
+    assert rc == -1 and b"K=0" in lib.tma_last_error()
+    lib.tma_loss_workspace_bytes.restype = ctypes.c_size_t
+    assert lib.tma_loss_workspace_bytes(ctypes.c_int64(1000), ctypes.c_int32(47)) % 256 == 0
+    lib.tma_sage_layer_bwd_workspace_bytes.restype = ctypes.c_size_t
+    small = lib.tma_sage_layer_bwd_workspace_bytes(ctypes.c_int64(1000), 64, 64, 0, 0)
+    large = lib.tma_sage_layer_bwd_workspace_bytes(ctypes.c_int64(1000), 64, 64, 0, 1)
+    assert large >= small + 1000 * 64 * 4
