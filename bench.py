@@ -1,0 +1,193 @@
+#!/usr/bin/env python3
+"""Benchmark of the TMA trainer hot path on one MI355X.
+
+One "step" = one pass of the whole path on the configs[1] workload, inputs
+already resident in HBM: random K-way node assignment of the 1M-node global
+graph, extraction of one partition's induced subgraph, gather of its feature
+rows and labels, full-batch forward + backward + SGD step of the 2-layer
+mean-aggregation GraphSAGE model on it, and the averaging of K parameter
+vectors.  Prints ONE JSON line (metric, roofline of the dominant kernel, CPU
+oracle baseline).
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+# MI355X published peaks
+PEAK_HBM_GBS = 8000.0
+PEAK_MFMA_F32_TFLOPS = 157.3
+
+WORKLOAD = dict(n_nodes=1_000_000, avg_degree=20, gamma=2.1, K=8, part=0, F=128, hidden=256, classes=47,
+                seeds=dict(graph=11, feat=12, label=13, part=14, weights=15), lr=1e-3)
+
+# HBM bytes per launch of the dominant kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this
+# workload (see profiles/); None until measured.
+MEASURED_TRAFFIC_BYTES = {}
+
+
+def kernel_work(name, n, nnz, dims):
+    """Algorithmic work of one launch of kernel `name` in this workload: ("mfma", flops) or ("hbm", bytes)."""
+    F0, F1, C = dims
+    s = 4
+    gemm = {
+        "gemm_fwd_128x128": 2.0 * n * (2 * F0) * F1,
+        "gemm_fwd_128x64": 2.0 * n * (2 * F1) * C,
+        "gemm_bwd_weight_128x128": 2.0 * n * (2 * F0) * F1,
+        "gemm_bwd_weight_128x64": 2.0 * n * (2 * F1) * C,
+        "gemm_bwd_data_128x128": 2.0 * n * C * (2 * F1),
+    }
+    if name in gemm:
+        return "mfma", gemm[name]
+    spmm = {  # each distinct input row once + indices + output row + rowptr/inv_deg
+        "spmm_mean_f32_g32x1": n * F0 * s + nnz * 4 + n * (F0 * s + 8),
+        "spmm_mean_f32_g64x1": n * F1 * s + nnz * 4 + n * (F1 * s + 8),
+        "spmm_sum_f32_g64x1": n * F1 * s + nnz * 4 + n * (2 * F1 * s + 4),
+    }
+    if name in spmm:
+        return "hbm", float(spmm[name])
+    return None, 0.0
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py: this build runs on ONE GPU only (trainers are independent; nothing is sharded "
+                 "across GPUs). Use --gpus 1.")
+
+    import numpy as np
+    import torch
+    from paper_2305_09887_amd import binding as B, synth
+    from paper_2305_09887_amd.trainer import LocalTrainer
+
+    if not torch.cuda.is_available():
+        sys.exit("bench.py needs a GPU")
+    B.lib()
+    w = WORKLOAD
+    N, K, p = w["n_nodes"], w["K"], w["part"]
+    dims = [w["F"], w["hidden"], w["classes"]]
+    L = len(dims) - 1
+    sd = w["seeds"]
+
+    t0 = time.time()
+    rowptr, colidx = synth.chung_lu_graph(N, w["avg_degree"], w["gamma"], seed=sd["graph"])
+    X = synth.features(N, dims[0], seed=sd["feat"])
+    y = synth.labels(N, dims[-1], seed=sd["label"])
+    params = synth.sage_params(dims, seed=sd["weights"])
+    print(f"[bench] inputs generated in {time.time() - t0:.1f}s: nnz={int(rowptr[-1])}", file=sys.stderr, flush=True)
+
+    dev = torch.device("cuda:0")
+    d_rowptr, d_colidx = torch.as_tensor(rowptr).to(dev), torch.as_tensor(colidx).to(dev)
+    d_X, d_y = torch.as_tensor(X).to(dev), torch.as_tensor(y).to(dev)
+    part = torch.empty(N, dtype=torch.int32, device=dev)
+
+    # set-up pass: learn the local sizes, allocate every persistent buffer
+    B.tma_partition(N, K, sd["part"], out=part)
+    sub = B.tma_induced_subgraph(d_rowptr, d_colidx, part, p)
+    n_loc, nnz_loc = sub["n_loc"], sub["nnz_loc"]
+    Xl = torch.empty((n_loc, dims[0]), dtype=torch.float32, device=dev)
+    yl = torch.empty(n_loc, dtype=torch.int32, device=dev)
+    tr = LocalTrainer(sub["rowptr"], sub["colidx"], sub["inv_deg"], Xl, yl, dims, params=params)
+    peers = [tr.W.clone() for _ in range(K - 1)]      # the other K-1 trainers' parameter vectors
+    W_all = [tr.W] + peers
+    ptrs = torch.tensor([t.data_ptr() for t in W_all], dtype=torch.int64, device=dev)
+    W_global = torch.empty_like(tr.W)
+    cap = n_loc + n_loc // 8 + 1024
+
+    def step():
+        B.tma_partition(N, K, sd["part"], out=part)
+        s = B.tma_induced_subgraph(d_rowptr, d_colidx, part, p, cap_n_loc=cap)
+        B.tma_gather_rows(s["l2g"], d_X, out=Xl)
+        B.tma_gather_rows(s["l2g"], d_y, out=yl)
+        tr.set_graph(s["rowptr"], s["colidx"], s["inv_deg"])
+        tr.step(w["lr"])
+        B.tma_average(W_all, W_global_out=W_global, ptr_table=ptrs)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+
+    # which kernel dominates: every kernel timed with events over three untimed steps
+    B.tma_profile_begin(None)
+    for _ in range(3):
+        step()
+    torch.cuda.synchronize()
+    prof = B.tma_profile_end()
+    per_step = {k: v[1] / 3.0 for k, v in prof.items()}
+    dominant = max(per_step, key=per_step.get)
+
+    # timed region; the dominant kernel alone carries events
+    B.tma_profile_begin(dominant)
+    torch.cuda.synchronize()
+    t_start = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t_start
+    dom = B.tma_profile_end().get(dominant, (0, 0.0))
+    ms_per_step = elapsed * 1e3 / args.steps
+    loss = float(tr.loss.item())
+
+    bound, work = kernel_work(dominant, n_loc, nnz_loc, dims)
+    avg_ms = dom[1] / max(dom[0], 1)
+    if bound == "mfma":
+        achieved, peak, unit = work / (avg_ms * 1e-3) / 1e12, PEAK_MFMA_F32_TFLOPS, "TFLOP/s"
+    else:
+        bound = "hbm"
+        achieved, peak, unit = work / (avg_ms * 1e-3) / 1e9, PEAK_HBM_GBS, "GB/s"
+    roofline = dict(bound=bound, kernel=dominant, achieved=round(achieved, 3), peak=peak, unit=unit,
+                    frac=round(achieved / peak, 4), traffic=MEASURED_TRAFFIC_BYTES.get(dominant),
+                    avg_launch_ms=round(avg_ms, 5), launches=dom[0],
+                    algorithmic_work_per_launch=work)
+
+    value = L * nnz_loc / (ms_per_step * 1e-3)
+    train_ms = sum(v for k, v in per_step.items() if k.startswith(("spmm", "gemm", "reduce", "softmax", "finish", "sgd")))
+    out = {
+        "metric": "trainer edges/sec per SAGE layer fwd+bwd; achieved HBM GB/s vs peak",
+        "value": round(value, 1), "unit": "edges/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32", "data": "synthetic",
+        "config": {"workload": "configs[1]: Chung-Lu power-law graph (gamma 2.1), 1M nodes, avg degree 20, 128-d fp32 "
+                               "features, 47 classes; K=8 random node partitions; whole path per step = partition + "
+                               "induced-subgraph extraction of part 0 + row gather + 2-layer mean-SAGE (hidden 256) "
+                               "full-batch fwd+bwd+SGD + 8-way parameter averaging",
+                   "n_nodes": N, "nnz_global": int(rowptr[-1]), "K": K, "n_loc": n_loc, "nnz_loc": nnz_loc,
+                   "layers": L, "dims": dims, "edge_definition": "directed local CSR entry; value = layers*nnz_loc/step time"},
+        "roofline": roofline,
+        "kernel_ms_per_step": {k: round(v, 5) for k, v in sorted(per_step.items(), key=lambda kv: -kv[1])},
+        "train_only_edges_per_s": round(L * nnz_loc / (train_ms * 1e-3), 1) if train_ms > 0 else None,
+        "final_loss": loss,
+    }
+
+    if not args.no_cpu_baseline:
+        import oracle
+        from oracle import model as omodel
+        t_cpu = time.perf_counter()
+        part_o = oracle.partition(N, K, seed=sd["part"])
+        sub_o = oracle.induced_subgraph(rowptr, colidx, part_o, p)
+        Xo, yo = X[sub_o["l2g"]], y[sub_o["l2g"]]
+        p_o = [tuple(np.asarray(t, dtype=np.float64) for t in l) for l in params]
+        _, p_new = omodel.train_step(sub_o["rowptr"], sub_o["colidx"], Xo, yo, p_o, w["lr"])
+        omodel.aggregate([p_new] + [p_o] * (K - 1))
+        t_cpu = time.perf_counter() - t_cpu
+        out["cpu_baseline"] = {"value": round(L * len(sub_o["colidx"]) / t_cpu, 1), "unit": "edges/s", "cores": 1,
+                               "kind": "oracle",
+                               "sample": f"one full step of the same workload at full size (n_loc={len(sub_o['l2g'])}, "
+                                         f"nnz_loc={len(sub_o['colidx'])}), {t_cpu:.1f} s single-threaded fp64"}
+    print(json.dumps(out), flush=True)
+
+
+if __name__ == "__main__":
+    main()

@@ -23,6 +23,7 @@ EXPORTS = (
     "tma_induced_subgraph_workspace_bytes", "tma_induced_subgraph_count", "tma_induced_subgraph_fill",
     "tma_mean_aggregate", "tma_sage_layer_fwd", "tma_sage_layer_bwd_workspace_bytes", "tma_sage_layer_bwd",
     "tma_loss_workspace_bytes", "tma_softmax_ce", "tma_sigmoid_l2", "tma_sgd_step", "tma_average",
+    "tma_gather_rows", "tma_profile_begin", "tma_profile_end", "tma_profile_count", "tma_profile_entry",
 )
 
 
@@ -290,3 +291,39 @@ def tma_average(W_list, active_mask: int | None = None, W_global_out=None, ptr_t
     _check(lib().tma_average(_ptr(ptr_table, torch.int64), C.c_int32(M), C.c_uint64(active_mask), C.c_int64(n),
                              _ptr(W_global_out, torch.float32), _stream(stream)))
     return W_global_out
+
+
+def tma_gather_rows(l2g, src, out=None, stream=None):
+    """out[i] = src[l2g[i]] for a 1-D or 2-D row-major table (features, labels)."""
+    n_loc = l2g.numel()
+    if src.dim() == 1:
+        row_bytes, src_ld = src.element_size(), src.element_size()
+        shape = (n_loc,)
+    else:
+        _, cols, ld = _rows_ld(src, "src")
+        row_bytes, src_ld = cols * src.element_size(), ld * src.element_size()
+        shape = (n_loc, cols)
+    if out is None:
+        out = torch.empty(shape, dtype=src.dtype, device=src.device)
+    if tuple(out.shape) != shape or out.dtype != src.dtype or not out.is_contiguous():
+        raise TmaError("tma_gather_rows: out must be a contiguous tensor of the gathered shape")
+    _check(lib().tma_gather_rows(C.c_int64(n_loc), _ptr(l2g, torch.int32, "l2g"), C.c_void_p(src.data_ptr()),
+                                 C.c_int64(src_ld), C.c_int64(row_bytes), C.c_void_p(out.data_ptr()),
+                                 C.c_int64(row_bytes), _stream(stream)))
+    return out
+
+
+def tma_profile_begin(kernel_filter: str | None = None):
+    _check(lib().tma_profile_begin(None if not kernel_filter else kernel_filter.encode()))
+
+
+def tma_profile_end() -> dict:
+    """Stops the event timing and returns {kernel name: (launches, total_ms)}."""
+    L = lib()
+    _check(L.tma_profile_end())
+    out = {}
+    for i in range(L.tma_profile_count()):
+        name, cnt, ms = C.c_char_p(), C.c_int64(0), C.c_double(0.0)
+        _check(L.tma_profile_entry(C.c_int(i), C.byref(name), C.byref(cnt), C.byref(ms)))
+        out[name.value.decode()] = (cnt.value, ms.value)
+    return out

@@ -1,0 +1,59 @@
+// Row gather  dst[i,:] = src[l2g[i],:]  -- how a trainer takes its part of the
+// feature matrix and the label vector (Alg. 2, set-up line).  Pure data
+// movement, HBM bound: row_bytes read + row_bytes written per local node.
+#include "common.hpp"
+
+namespace tma {
+
+// W = copy word (uint4: 16 B, uint32_t: 4 B, uint8_t: 1 B).  Consecutive
+// threads copy consecutive words of a row; a block walks several rows.
+template <typename W>
+__global__ __launch_bounds__(256) void gather_rows_kernel(int64_t n_loc, const int32_t *__restrict__ l2g,
+                                                          const char *__restrict__ src, int64_t src_ld,
+                                                          int64_t words_per_row, char *__restrict__ dst,
+                                                          int64_t dst_ld)
+{
+    const int64_t total = n_loc * words_per_row;
+    const int64_t stride = int64_t(gridDim.x) * 256;
+    for (int64_t idx = int64_t(blockIdx.x) * 256 + threadIdx.x; idx < total; idx += stride) {
+        const int64_t i = idx / words_per_row;
+        const int64_t w = idx - i * words_per_row;
+        const W *s = reinterpret_cast<const W *>(src + int64_t(l2g[i]) * src_ld) + w;
+        W *d = reinterpret_cast<W *>(dst + i * dst_ld) + w;
+        *d = *s;
+    }
+}
+
+template <typename W>
+static void launch_gather(int64_t n_loc, const int32_t *l2g, const void *src, int64_t src_ld, int64_t row_bytes,
+                          void *dst, int64_t dst_ld, hipStream_t s)
+{
+    const int64_t words = row_bytes / int64_t(sizeof(W));
+    int64_t blocks = ceil_div(n_loc * words, 256);
+    if (blocks > 256 * 64) blocks = 256 * 64;
+    TMA_TIMED("gather_rows", s);
+    hipLaunchKernelGGL(gather_rows_kernel<W>, dim3(unsigned(blocks)), dim3(256), 0, s, n_loc, l2g,
+                       static_cast<const char *>(src), src_ld, words, static_cast<char *>(dst), dst_ld);
+}
+
+}  // namespace tma
+
+extern "C" int tma_gather_rows(int64_t n_loc, const int32_t *l2g, const void *src, int64_t src_ld_bytes,
+                               int64_t row_bytes, void *dst, int64_t dst_ld_bytes, tma_stream_t stream)
+{
+    using namespace tma;
+    const char *fn = "tma_gather_rows";
+    TMA_REQUIRE(n_loc >= 0 && row_bytes >= 0, TMA_ERR_INVALID_ARG, "%s: negative size", fn);
+    if (n_loc == 0 || row_bytes == 0) return TMA_OK;
+    TMA_REQUIRE(l2g && src && dst, TMA_ERR_INVALID_ARG, "%s: NULL argument", fn);
+    TMA_REQUIRE(src_ld_bytes >= row_bytes && dst_ld_bytes >= row_bytes, TMA_ERR_BAD_SHAPE, "%s: pitch < row_bytes", fn);
+    hipStream_t s = as_stream(stream);
+    auto mult = [&](int64_t a) {
+        return row_bytes % a == 0 && src_ld_bytes % a == 0 && dst_ld_bytes % a == 0 && aligned(src, size_t(a)) &&
+               aligned(dst, size_t(a));
+    };
+    if (mult(16)) launch_gather<uint4>(n_loc, l2g, src, src_ld_bytes, row_bytes, dst, dst_ld_bytes, s);
+    else if (mult(4)) launch_gather<uint32_t>(n_loc, l2g, src, src_ld_bytes, row_bytes, dst, dst_ld_bytes, s);
+    else launch_gather<uint8_t>(n_loc, l2g, src, src_ld_bytes, row_bytes, dst, dst_ld_bytes, s);
+    return check_launch(fn);
+}

@@ -58,6 +58,14 @@ class LocalTrainer:
         self.loss = torch.zeros(1, dtype=torch.float32, device=dev)
         self.steps_done = 0
 
+    def set_graph(self, rowptr, colidx, inv_deg, rowptr_T=None, colidx_T=None):
+        """Point the trainer at a freshly extracted subgraph with the same node count."""
+        if rowptr.numel() != self.n + 1 or inv_deg.numel() != self.n:
+            raise B.TmaError("LocalTrainer.set_graph: node count differs from the allocated buffers")
+        self.rowptr, self.colidx, self.inv_deg = rowptr, colidx, inv_deg
+        self.rowptr_T = rowptr if rowptr_T is None else rowptr_T
+        self.colidx_T = colidx if colidx_T is None else colidx_T
+
     def _views(self, flat):
         out, o = [], 0
         for fi, fo in zip(self.dims[:-1], self.dims[1:]):

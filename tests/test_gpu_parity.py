@@ -374,3 +374,36 @@ def test_tiny_config_training_steps_match_oracle(B):
         assert_close(tr.W.cpu().numpy(), omodel.flatten(p_o), what=f"weights after step {step}")
         losses.append(loss_g)
     assert losses[2] < losses[0]
+
+
+# ------------------------------------------------------------ gather, profiler
+@pytest.mark.parametrize("cols,dtype", [(128, np.float32), (100, np.float32), (3, np.int16), (1, np.uint8)])
+def test_gather_rows_is_an_exact_row_copy(B, cols, dtype):
+    rng = np.random.default_rng(cols)
+    src = (rng.standard_normal((5000, cols)) * 100).astype(dtype)
+    l2g = np.sort(rng.choice(5000, 1234, replace=False)).astype(np.int32)
+    got = B.tma_gather_rows(dev(l2g), dev(src))
+    assert np.array_equal(got.cpu().numpy(), src[l2g])       # definition of the gather: bit-exact copy
+    lab = rng.integers(0, 47, 5000).astype(np.int32)
+    assert np.array_equal(B.tma_gather_rows(dev(l2g), dev(lab)).cpu().numpy(), lab[l2g])
+    assert B.tma_gather_rows(dev(l2g[:0]), dev(lab)).numel() == 0
+
+
+def test_event_profiler_counts_launches(B):
+    sub = _local_graph(3000, 12_000, seed=1)
+    n = len(sub["l2g"])
+    H = dev(synth.features(n, 64, seed=1))
+    args = (dev(sub["rowptr"]), dev(sub["colidx"]), dev(sub["inv_deg"], torch.float32), H)
+    B.tma_profile_begin(None)
+    for _ in range(3):
+        B.tma_mean_aggregate(*args)
+    B.tma_sgd_step(torch.zeros(10, device="cuda"), torch.zeros(10, device="cuda"), 0.1)
+    prof = B.tma_profile_end()
+    assert prof["spmm_mean_f32_g16x1"][0] == 3 and prof["sgd"][0] == 1
+    assert all(ms > 0 for _, ms in prof.values())
+    B.tma_profile_begin("sgd")
+    B.tma_mean_aggregate(*args)
+    B.tma_sgd_step(torch.zeros(10, device="cuda"), torch.zeros(10, device="cuda"), 0.1)
+    assert list(B.tma_profile_end()) == ["sgd"]
+    B.tma_mean_aggregate(*args)                               # disabled again: nothing recorded
+    assert B.tma_profile_end() == {}
