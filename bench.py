@@ -44,6 +44,7 @@ def kernel_work(name, n, nnz, dims):
         "gemm_bwd_weight_128x64": 2.0 * n * (2 * F1) * C,
         "gemm_bwd_data_128x128": 2.0 * n * C * (2 * F1),
     }
+    name = name.replace("_generic", "")
     if name in gemm:
         return "mfma", gemm[name]
     spmm = {  # each distinct input row once + indices + output row + rowptr/inv_deg

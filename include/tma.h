@@ -128,8 +128,12 @@ int tma_mean_aggregate(int64_t n, const int32_t *rowptr, const int32_t *colidx,
  *   H       [n, F_in]  dtype, ld = ldh
  *   W_self, W_neigh [F_in, F_out] fp32 row-major, dense;  bias [F_out] fp32
  *   M_out   [n, F_in]  dtype, dense (ld = F_in), saved for backward
- *   Hnext_out [n, F_out] dtype, dense.  With TMA_ACT_RELU the sign pattern of
+ *   Hnext_out [n, F_out] dtype, leading dimension ld_next >= F_out; padding
+ *           columns are not written.  With TMA_ACT_RELU the sign pattern of
  *           H' equals that of Z, so H' is all that backward needs.
+ * The 16-byte vector paths need 16-byte aligned pointers and leading
+ * dimensions that are multiples of 4 elements (pad rows for widths such as
+ * 47); anything else takes a slower element-wise path with the same result.
  * No workspace.
  * ---------------------------------------------------------------------- */
 int tma_sage_layer_fwd(int64_t n, const int32_t *rowptr, const int32_t *colidx,
@@ -137,7 +141,7 @@ int tma_sage_layer_fwd(int64_t n, const int32_t *rowptr, const int32_t *colidx,
                        const void *H, int64_t ldh, int32_t F_in,
                        const float *W_self, const float *W_neigh, const float *bias,
                        int32_t F_out, int32_t act, int32_t dtype,
-                       void *M_out, void *Hnext_out, tma_stream_t stream);
+                       void *M_out, void *Hnext_out, int64_t ld_next, tma_stream_t stream);
 
 /* ------------------------------------------------------------------------
  * Backward of the layer (chain rule as in the proof of Thm. 1, which writes
@@ -146,13 +150,14 @@ int tma_sage_layer_fwd(int64_t n, const int32_t *rowptr, const int32_t *colidx,
  *     dW_self = H^T dZ,  dW_neigh = M^T dZ,  dbias = column sums of dZ
  *     dH = dZ W_self^T + Abar^T (dZ W_neigh^T)
  *   H, M     as in forward;  Hnext [n, F_out] the forward output (read only
- *            when act = TMA_ACT_RELU);  dHnext [n, F_out] dtype, dense
+ *            when act = TMA_ACT_RELU);  dHnext [n, F_out] dtype; both with
+ *            leading dimension ld_next (padding columns are ignored)
  *   rowptr_T/colidx_T : CSR of the TRANSPOSED local graph.  For a symmetric
  *            graph (every configuration of a simple undirected graph) pass
  *            rowptr/colidx again.  inv_deg is that of the forward graph.
  *   dW_self, dW_neigh [F_in, F_out], dbias [F_out] fp32: OVERWRITTEN.
- *   dH_out [n, F_in] dtype dense, or NULL to skip the input gradient (first
- *            layer).
+ *   dH_out [n, F_in] dtype with the leading dimension of H (ldh), or NULL to
+ *            skip the input gradient (first layer).
  * Workspace: tma_sage_layer_bwd_workspace_bytes(n, F_in, F_out, dtype,
  * dH_out != NULL), 256-byte aligned.  Results are deterministic (fixed
  * reduction order, no floating-point atomics).
@@ -163,7 +168,7 @@ size_t tma_sage_layer_bwd_workspace_bytes(int64_t n, int32_t F_in, int32_t F_out
 int tma_sage_layer_bwd(int64_t n, const int32_t *rowptr_T, const int32_t *colidx_T,
                        const float *inv_deg,
                        const void *H, int64_t ldh, const void *M, const void *Hnext,
-                       const void *dHnext,
+                       const void *dHnext, int64_t ld_next,
                        const float *W_self, const float *W_neigh,
                        int32_t F_in, int32_t F_out, int32_t act, int32_t dtype,
                        float *dW_self, float *dW_neigh, float *dbias, void *dH_out,
@@ -173,9 +178,11 @@ int tma_sage_layer_bwd(int64_t n, const int32_t *rowptr_T, const int32_t *colidx
  * Losses on the last layer's output.
  * tma_softmax_ce: mean softmax cross-entropy over the n local nodes (reading
  *   taken for workloads with class labels); loss_out[0] fp32 (device),
- *   dlogits_out = (softmax - onehot)/n in `dtype`, dense [n, C].
+ *   dlogits_out = (softmax - onehot)/n in `dtype`, [n, C] with the leading
+ *   dimension of the logits (ld); may be NULL.
  * tma_sigmoid_l2: the loss of Thm. 1, L = 1/2 sum (y - sigmoid(g))^2 over all
- *   nodes and outputs; dG = (z - y) z (1 - z).  Y fp32 dense [n, C].
+ *   nodes and outputs; dG = (z - y) z (1 - z), laid out like G (ld).
+ *   Y fp32 dense [n, C].
  * Workspace: tma_loss_workspace_bytes(n, C) bytes, 256-byte aligned.
  * ---------------------------------------------------------------------- */
 size_t tma_loss_workspace_bytes(int64_t n, int32_t C);

@@ -87,6 +87,20 @@ def _rows_ld(t, name):
     return t.shape[0], t.shape[1], (t.stride(0) if t.shape[0] > 1 else max(t.stride(0), t.shape[1]))
 
 
+def _padded(n: int, cols: int, dtype, device) -> torch.Tensor:
+    """[n, cols] view of a buffer whose rows are padded to a multiple of 16 bytes (vector-path friendly)."""
+    per16 = 16 // torch.empty(0, dtype=dtype).element_size()
+    ld = (cols + per16 - 1) // per16 * per16
+    return torch.empty((max(n, 1), ld), dtype=dtype, device=device)[:n, :cols]
+
+
+def _same_ld(a, b, what):
+    if a is None or b is None:
+        return
+    if a.stride(0) != b.stride(0) and a.shape[0] > 1:
+        raise TmaError(f"{what}: tensors must share one leading dimension")
+
+
 def _workspace(nbytes: int, device) -> torch.Tensor:
     return torch.empty(max(int(nbytes), 256), dtype=torch.uint8, device=device)
 
@@ -168,15 +182,16 @@ def tma_sage_layer_fwd(rowptr, colidx, inv_deg, H, W_self, W_neigh, bias, act: i
     if M_out is None:
         M_out = torch.empty((n, F_in), dtype=H.dtype, device=H.device)
     if Hnext_out is None:
-        Hnext_out = torch.empty((n, F_out), dtype=H.dtype, device=H.device)
+        Hnext_out = _padded(n, F_out, H.dtype, H.device)
     if tuple(M_out.shape) != (n, F_in) or tuple(Hnext_out.shape) != (n, F_out):
         raise TmaError("tma_sage_layer_fwd: output shapes")
+    _, _, ld_next = _rows_ld(Hnext_out, "Hnext_out")
     _check(lib().tma_sage_layer_fwd(
         C.c_int64(n), _ptr(rowptr, torch.int32), _ptr(colidx, torch.int32), _ptr(inv_deg, torch.float32),
         C.c_void_p(H.data_ptr()), C.c_int64(ldh), C.c_int32(F_in), _ptr(W_self, torch.float32, "W_self"),
         _ptr(W_neigh, torch.float32, "W_neigh"), _ptr(bias, torch.float32, "bias"), C.c_int32(F_out),
         C.c_int32(act), C.c_int32(_feat_dtype(H)), _ptr(M_out, H.dtype, "M_out"),
-        _ptr(Hnext_out, H.dtype, "Hnext_out"), _stream(stream)))
+        C.c_void_p(Hnext_out.data_ptr()), C.c_int64(ld_next), _stream(stream)))
     return M_out, Hnext_out
 
 
@@ -204,21 +219,28 @@ def tma_sage_layer_bwd(rowptr_T, colidx_T, inv_deg, H, M, Hnext, dHnext, W_self,
     if dbias is None:
         dbias = torch.empty(F_out, dtype=torch.float32, device=dev)
     if need_dH and dH_out is None:
-        dH_out = torch.empty((n, F_in), dtype=H.dtype, device=dev)
+        dH_out = torch.empty((max(n, 1), ldh), dtype=H.dtype, device=dev)[:n, :F_in]
     if not need_dH:
         dH_out = None
+    if dH_out is not None:
+        if tuple(dH_out.shape) != (n, F_in) or _rows_ld(dH_out, "dH_out")[2] != ldh:
+            raise TmaError("tma_sage_layer_bwd: dH_out must have the shape and leading dimension of H")
+    _, _, ld_next = _rows_ld(dHnext, "dHnext")
+    if act == TMA_ACT_RELU:
+        _same_ld(Hnext, dHnext, "tma_sage_layer_bwd: Hnext / dHnext")
     dt = _feat_dtype(H)
     need = tma_sage_layer_bwd_workspace_bytes(n, F_in, F_out, dt, need_dH)
     if ws is None:
         ws = _workspace(need, dev)
     _check(lib().tma_sage_layer_bwd(
         C.c_int64(n), _ptr(rowptr_T, torch.int32), _ptr(colidx_T, torch.int32), _ptr(inv_deg, torch.float32),
-        C.c_void_p(H.data_ptr()), C.c_int64(ldh), _ptr(M, H.dtype, "M"), _ptr(Hnext, H.dtype, "Hnext"),
-        _ptr(dHnext, H.dtype, "dHnext"), _ptr(W_self, torch.float32), _ptr(W_neigh, torch.float32),
+        C.c_void_p(H.data_ptr()), C.c_int64(ldh), _ptr(M, H.dtype, "M"),
+        C.c_void_p(Hnext.data_ptr() if Hnext is not None else 0), C.c_void_p(dHnext.data_ptr()), C.c_int64(ld_next),
+        _ptr(W_self, torch.float32), _ptr(W_neigh, torch.float32),
         C.c_int32(F_in), C.c_int32(F_out), C.c_int32(act), C.c_int32(dt),
         _ptr(dW_self, torch.float32, "dW_self"), _ptr(dW_neigh, torch.float32, "dW_neigh"),
-        _ptr(dbias, torch.float32, "dbias"), _ptr(dH_out, H.dtype, "dH_out"), _ptr(ws), C.c_size_t(ws.numel()),
-        _stream(stream)))
+        _ptr(dbias, torch.float32, "dbias"), C.c_void_p(dH_out.data_ptr() if dH_out is not None else 0), _ptr(ws),
+        C.c_size_t(ws.numel()), _stream(stream)))
     return dW_self, dW_neigh, dbias, dH_out
 
 
@@ -235,12 +257,15 @@ def tma_softmax_ce(logits, labels, loss_out=None, dlogits_out=None, need_grad=Tr
     if loss_out is None:
         loss_out = torch.empty(1, dtype=torch.float32, device=dev)
     if need_grad and dlogits_out is None:
-        dlogits_out = torch.empty((n, Cc), dtype=logits.dtype, device=dev)
+        dlogits_out = torch.empty((max(n, 1), ldz), dtype=logits.dtype, device=dev)[:n, :Cc]
+    if need_grad and (tuple(dlogits_out.shape) != (n, Cc) or _rows_ld(dlogits_out, "dlogits_out")[2] != ldz):
+        raise TmaError("tma_softmax_ce: dlogits_out must have the shape and leading dimension of logits")
     if ws is None:
         ws = _workspace(tma_loss_workspace_bytes(n, Cc), dev)
     _check(lib().tma_softmax_ce(C.c_int64(n), C.c_int32(Cc), C.c_void_p(logits.data_ptr()), C.c_int64(ldz),
                                 C.c_int32(_feat_dtype(logits)), _ptr(labels, torch.int32, "labels"),
-                                _ptr(loss_out, torch.float32), _ptr(dlogits_out if need_grad else None),
+                                _ptr(loss_out, torch.float32),
+                                C.c_void_p(dlogits_out.data_ptr() if need_grad else 0),
                                 _ptr(ws), C.c_size_t(ws.numel()), _stream(stream)))
     return loss_out, (dlogits_out if need_grad else None)
 
@@ -253,13 +278,15 @@ def tma_sigmoid_l2(G, Y, loss_out=None, dG_out=None, need_grad=True, ws=None, st
     if loss_out is None:
         loss_out = torch.empty(1, dtype=torch.float32, device=dev)
     if need_grad and dG_out is None:
-        dG_out = torch.empty((n, Cc), dtype=G.dtype, device=dev)
+        dG_out = torch.empty((max(n, 1), ldg), dtype=G.dtype, device=dev)[:n, :Cc]
+    if need_grad and (tuple(dG_out.shape) != (n, Cc) or _rows_ld(dG_out, "dG_out")[2] != ldg):
+        raise TmaError("tma_sigmoid_l2: dG_out must have the shape and leading dimension of G")
     if ws is None:
         ws = _workspace(tma_loss_workspace_bytes(n, Cc), dev)
     _check(lib().tma_sigmoid_l2(C.c_int64(n), C.c_int32(Cc), C.c_void_p(G.data_ptr()), C.c_int64(ldg),
                                 C.c_int32(_feat_dtype(G)), _ptr(Y, torch.float32, "Y"),
-                                _ptr(loss_out, torch.float32), _ptr(dG_out if need_grad else None), _ptr(ws),
-                                C.c_size_t(ws.numel()), _stream(stream)))
+                                _ptr(loss_out, torch.float32), C.c_void_p(dG_out.data_ptr() if need_grad else 0),
+                                _ptr(ws), C.c_size_t(ws.numel()), _stream(stream)))
     return loss_out, (dG_out if need_grad else None)
 
 

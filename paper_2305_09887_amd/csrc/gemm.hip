@@ -8,401 +8,669 @@
 //
 // fp32 storage uses v_mfma_f32_32x32x2_f32 (fp32 in, fp32 accumulate), so the
 // 1e-4 parity bound holds without any reduced-precision pass.  One kernel
-// template serves the three products: operands are described by small loader
+// template serves the three products: operands are described by small "view"
 // structs that present the concatenations [H | M] / [W_self ; W_neigh], the
-// ReLU mask and the transposes as plain A[m][k], B[k][n] views, and by an
-// epilogue struct.  Tiles are staged through LDS in k-major order so that the
-// 32 lanes of an MFMA operand read 32 consecutive words.
+// ReLU mask and the transposes as plain A[m][k], B[k][n], and by an epilogue
+// struct.
+//
+// Tiling.  128 x BN block tile, 4 wavefronts, each owning a (BM/WM) x (BN/WN)
+// patch of 32x32 MFMA tiles; k is consumed in slabs of BK through two LDS
+// buffers (one barrier per slab) while the next slab's global loads are in
+// flight in registers.  Every operand keeps in LDS the orientation it has in
+// HBM, so all global->LDS traffic is 16-byte loads and 16-byte LDS writes:
+//   k-contiguous operand : LDS [mn][BK+4]; a lane fetches 4 k-values of its row
+//                          with one ds_read_b128 and feeds 4 MFMAs from it;
+//   mn-contiguous operand: LDS [BK][MN+4]; a lane reads one word per MFMA.
+// Within a group of 8 k-values MFMA j takes k = 4*(lane/32) + j from both
+// operands (any bijection of k is allowed as long as A and B agree).
+// Blocks are numbered so that the tiles sharing operand rows (the n-tiles of a
+// row block, the output tiles of one node split) land on the same XCD and hit
+// its L2.
 #include "kernels.hpp"
+
+#include <type_traits>
 
 namespace tma {
 
 typedef float floatx16 __attribute__((ext_vector_type(16)));
 
-constexpr int kPad = 4;  // LDS row padding (words); keeps rows 16-byte aligned
+constexpr int kPad = 4;   // LDS row padding in words: keeps 16-byte alignment, spreads banks
+constexpr int kXcds = 8;  // MI355X: 8 accelerator dies, workgroups are dealt round-robin to them
+
+__device__ __forceinline__ float4 zero4() { return make_float4(0.0f, 0.0f, 0.0f, 0.0f); }
 
 // ---------------------------------------------------------------------------
-// Operand views.  load4(mn, k) returns four consecutive elements along the
-// view's contiguous direction (k when kContigK, else m/n), zero outside.
+// Operand views.  A view presents its operand as X[mn][k].  Per thread and
+// load slot the kernel calls prepare(mn) once per tile (everything that does
+// not depend on k: row pointers, which half of a concatenation, validity), then
+// load(lane, k) once per k-slab, which returns four consecutive elements along
+// the view's contiguous direction (k when kContigK, else mn) as a Raw value,
+// zero outside the operand; resolve(raw) turns it into operand values.  The
+// split lets the kernel issue the loads of the next slab before the MFMAs of
+// the current one and touch the loaded registers (ReLU mask, ragged tails)
+// only afterwards, so no wait on global memory sits in front of the matrix work.
+// V = the vector path is legal (16-byte aligned bases and leading dimensions,
+// inner extents multiple of 4); otherwise element-wise guarded loads.
 // ---------------------------------------------------------------------------
+// The vector loads are branch-free: an out-of-range position is clamped to a valid
+// address and the loaded value is discarded by resolve() through the `ok` flag, so
+// that a k-slab's loads, its MFMAs and the LDS traffic form one basic block the
+// instruction scheduler can interleave.
+struct Raw4 {
+    float4 v;
+    bool ok;
+};
+__device__ __forceinline__ float4 keep_if(const Raw4 &r)
+{
+    return make_float4(r.ok ? r.v.x : 0.0f, r.ok ? r.v.y : 0.0f, r.ok ? r.v.z : 0.0f, r.ok ? r.v.w : 0.0f);
+}
+
+template <bool V>
 struct CatRows {  // A[m][k] = k < F ? H[m][k] : M[m][k-F]          (contiguous along k)
     static constexpr bool kContigK = true;
+    typedef Raw4 Raw;
+    struct Lane {
+        const float *p0, *p1;  // row pointers such that element k is p0[k] (k < F) or p1[k] (k >= F)
+        bool ok;
+    };
     const float *H;
     int64_t ldh;
     const float *Mx;
     int F;
     int64_t rows;
-    bool vec;
-    __device__ __forceinline__ float at(int64_t m, int k) const
+    static __device__ __forceinline__ float4 resolve(const Raw &r) { return keep_if(r); }
+    __device__ __forceinline__ Lane prepare(int64_t m) const
     {
-        if (k < F) return H[m * ldh + k];
-        if (k < 2 * F) return Mx[m * int64_t(F) + (k - F)];
-        return 0.0f;
+        const int64_t mm = m < rows ? m : 0;
+        return Lane{H + mm * ldh, Mx + mm * int64_t(F) - F, m < rows};
     }
-    __device__ __forceinline__ float4 load4(int64_t m, int64_t k64) const
+    __device__ __forceinline__ float at(const Lane &l, int k) const
+    {
+        return k < F ? l.p0[k] : (k < 2 * F ? l.p1[k] : 0.0f);
+    }
+    __device__ __forceinline__ Raw load(const Lane &l, int64_t k64) const
     {
         const int k = int(k64);
-        if (m >= rows) return make_float4(0, 0, 0, 0);
-        if (vec) {
-            if (k < F) return *reinterpret_cast<const float4 *>(H + m * ldh + k);
-            if (k < 2 * F) return *reinterpret_cast<const float4 *>(Mx + m * int64_t(F) + (k - F));
-            return make_float4(0, 0, 0, 0);
+        Raw r;
+        r.ok = l.ok && k < 2 * F;
+        if (V) {
+            const int kc = k < 2 * F ? k : 0;
+            r.v = *reinterpret_cast<const float4 *>((kc < F ? l.p0 : l.p1) + kc);
+        } else {
+            r.v = r.ok ? make_float4(at(l, k), at(l, k + 1), at(l, k + 2), at(l, k + 3)) : zero4();
         }
-        return make_float4(at(m, k), at(m, k + 1), at(m, k + 2), at(m, k + 3));
+        return r;
     }
 };
 
+template <bool V>
 struct CatRowsT {  // A[m][k] = (m < F ? H[k][m] : M[k][m-F])          (contiguous along m); k = node
     static constexpr bool kContigK = false;
+    typedef Raw4 Raw;
+    struct Lane {
+        const float *p;  // column pointer: element of node k is p[k * ld]
+        int64_t ld;
+        int m;
+        bool ok;
+    };
     const float *H;
     int64_t ldh;
     const float *Mx;
     int F;
     int64_t rows;
-    bool vec;
+    static __device__ __forceinline__ float4 resolve(const Raw &r) { return keep_if(r); }
+    __device__ __forceinline__ Lane prepare(int64_t m64) const
+    {
+        const int m = int(m64);
+        if (m < F) return Lane{H + m, ldh, m, true};
+        return Lane{Mx + (m < 2 * F ? m - F : 0), int64_t(F), m, m < 2 * F};
+    }
     __device__ __forceinline__ float at(int64_t node, int m) const
     {
         if (m < F) return H[node * ldh + m];
         if (m < 2 * F) return Mx[node * int64_t(F) + (m - F)];
         return 0.0f;
     }
-    __device__ __forceinline__ float4 load4(int64_t m64, int64_t node) const
+    __device__ __forceinline__ Raw load(const Lane &l, int64_t node) const
     {
-        const int m = int(m64);
-        if (node >= rows) return make_float4(0, 0, 0, 0);
-        if (vec) {
-            if (m < F) return *reinterpret_cast<const float4 *>(H + node * ldh + m);
-            if (m < 2 * F) return *reinterpret_cast<const float4 *>(Mx + node * int64_t(F) + (m - F));
-            return make_float4(0, 0, 0, 0);
+        Raw r;
+        r.ok = l.ok && node < rows;
+        if (V) {
+            r.v = *reinterpret_cast<const float4 *>(l.p + (node < rows ? node : 0) * l.ld);
+        } else {
+            r.v = r.ok ? make_float4(at(node, l.m), at(node, l.m + 1), at(node, l.m + 2), at(node, l.m + 3)) : zero4();
         }
-        return make_float4(at(node, m), at(node, m + 1), at(node, m + 2), at(node, m + 3));
+        return r;
     }
 };
 
+template <bool V>
 struct CatWeights {  // B[k][n] = k < F ? W_self[k][n] : W_neigh[k-F][n]  (contiguous along n)
     static constexpr bool kContigK = false;
+    typedef Raw4 Raw;
+    struct Lane {
+        int n;
+    };
     const float *Ws;
     const float *Wn;
     int F;
     int N;
-    bool vec;
-    __device__ __forceinline__ float4 load4(int64_t n64, int64_t k64) const
+    static __device__ __forceinline__ float4 resolve(const Raw &r) { return keep_if(r); }
+    __device__ __forceinline__ Lane prepare(int64_t n) const { return Lane{int(n)}; }
+    __device__ __forceinline__ Raw load(const Lane &l, int64_t k64) const
     {
-        const int n = int(n64), k = int(k64);
-        if (k >= 2 * F) return make_float4(0, 0, 0, 0);
-        const float *row = k < F ? Ws + int64_t(k) * N : Wn + int64_t(k - F) * N;
-        if (vec && n + 3 < N) return *reinterpret_cast<const float4 *>(row + n);
-        float4 r;
-        r.x = n + 0 < N ? row[n + 0] : 0.0f;
-        r.y = n + 1 < N ? row[n + 1] : 0.0f;
-        r.z = n + 2 < N ? row[n + 2] : 0.0f;
-        r.w = n + 3 < N ? row[n + 3] : 0.0f;
+        const int n = l.n, k = int(k64);
+        Raw r;
+        r.ok = k < 2 * F && n < N;
+        const int kc = k < 2 * F ? k : 0;
+        const float *row = kc < F ? Ws + int64_t(kc) * N : Wn + int64_t(kc - F) * N;
+        if (V) {
+            r.v = *reinterpret_cast<const float4 *>(row + (n < N ? n : 0));
+        } else if (r.ok) {
+            r.v.x = row[n];
+            r.v.y = n + 1 < N ? row[n + 1] : 0.0f;
+            r.v.z = n + 2 < N ? row[n + 2] : 0.0f;
+            r.v.w = n + 3 < N ? row[n + 3] : 0.0f;
+        } else {
+            r.v = zero4();
+        }
         return r;
     }
 };
 
+template <bool V>
 struct CatWeightsT {  // B[k][n] = n < F ? W_self[n][k] : W_neigh[n-F][k]  (contiguous along k); k = output feature
     static constexpr bool kContigK = true;
+    typedef Raw4 Raw;
+    struct Lane {
+        const float *row;
+        bool ok;
+    };
     const float *Ws;
     const float *Wn;
     int F;
     int Fo;
-    bool vec;
-    __device__ __forceinline__ float4 load4(int64_t n64, int64_t k64) const
+    static __device__ __forceinline__ float4 resolve(const Raw &r) { return keep_if(r); }
+    __device__ __forceinline__ Lane prepare(int64_t n64) const
     {
-        const int n = int(n64), k = int(k64);
-        if (n >= 2 * F) return make_float4(0, 0, 0, 0);
-        const float *row = n < F ? Ws + int64_t(n) * Fo : Wn + int64_t(n - F) * Fo;
-        if (vec && k + 3 < Fo) return *reinterpret_cast<const float4 *>(row + k);
-        float4 r;
-        r.x = k + 0 < Fo ? row[k + 0] : 0.0f;
-        r.y = k + 1 < Fo ? row[k + 1] : 0.0f;
-        r.z = k + 2 < Fo ? row[k + 2] : 0.0f;
-        r.w = k + 3 < Fo ? row[k + 3] : 0.0f;
+        const int n = int(n64);
+        if (n < F) return Lane{Ws + int64_t(n) * Fo, true};
+        return Lane{Wn + int64_t(n < 2 * F ? n - F : 0) * Fo, n < 2 * F};
+    }
+    __device__ __forceinline__ Raw load(const Lane &l, int64_t k64) const
+    {
+        const int k = int(k64);
+        Raw r;
+        r.ok = l.ok && k < Fo;
+        if (V) {
+            r.v = *reinterpret_cast<const float4 *>(l.row + (k < Fo ? k : 0));
+        } else if (r.ok) {
+            r.v.x = l.row[k];
+            r.v.y = k + 1 < Fo ? l.row[k + 1] : 0.0f;
+            r.v.z = k + 2 < Fo ? l.row[k + 2] : 0.0f;
+            r.v.w = k + 3 < Fo ? l.row[k + 3] : 0.0f;
+        } else {
+            r.v = zero4();
+        }
         return r;
     }
 };
 
-// dZ = dHnext (.) [Hnext > 0] (ReLU) or dHnext (identity); rows = nodes, dense [rows, Fo].
+// dZ = dHnext (.) [Hnext > 0] (ReLU) or dHnext (identity); rows = nodes, [rows, Fo] with leading dimension ld.
 // kAsA: used as A[m=node][k=o] (contiguous along k).  Otherwise as B[k=node][n=o] (contiguous along n).
-template <bool kAsA>
+// The vector path may read up to three padding elements past Fo inside a row (ld is a multiple of 4);
+// resolve() discards them.
+template <bool kAsA, bool V>
 struct MaskedGrad {
     static constexpr bool kContigK = kAsA;
+    struct Raw {
+        float4 g, h;
+        int nv;  // leading elements that are inside the operand (<= 0: none)
+    };
+    struct Lane {
+        int64_t off;  // kAsA: node * ld ; else: o
+        bool ok;
+    };
     const float *dHn;
     const float *Hn;  // forward output; read only when relu
     int Fo;
+    int64_t ld;
     int64_t rows;
     bool relu;
-    bool vec;
-    __device__ __forceinline__ float at(int64_t node, int o) const
+    static __device__ __forceinline__ float4 resolve(const Raw &r)
     {
-        if (o >= Fo) return 0.0f;
-        float g = dHn[node * Fo + o];
-        if (relu && !(Hn[node * Fo + o] > 0.0f)) g = 0.0f;
-        return g;
+        return make_float4((r.nv > 0 && r.h.x > 0.0f) ? r.g.x : 0.0f, (r.nv > 1 && r.h.y > 0.0f) ? r.g.y : 0.0f,
+                           (r.nv > 2 && r.h.z > 0.0f) ? r.g.z : 0.0f, (r.nv > 3 && r.h.w > 0.0f) ? r.g.w : 0.0f);
     }
-    __device__ __forceinline__ float4 load4(int64_t a, int64_t b) const
+    __device__ __forceinline__ Lane prepare(int64_t mn) const
     {
-        const int64_t node = kAsA ? a : b;
-        const int o = int(kAsA ? b : a);
-        if (node >= rows) return make_float4(0, 0, 0, 0);
-        if (vec && o + 3 < Fo) {
-            float4 g = *reinterpret_cast<const float4 *>(dHn + node * Fo + o);
-            if (relu) {
-                const float4 h = *reinterpret_cast<const float4 *>(Hn + node * Fo + o);
-                g.x = h.x > 0.0f ? g.x : 0.0f;
-                g.y = h.y > 0.0f ? g.y : 0.0f;
-                g.z = h.z > 0.0f ? g.z : 0.0f;
-                g.w = h.w > 0.0f ? g.w : 0.0f;
-            }
-            return g;
+        if (kAsA) return Lane{(mn < rows ? mn : 0) * ld, mn < rows};
+        return Lane{mn < Fo ? mn : 0, mn < Fo};
+    }
+    __device__ __forceinline__ Raw load(const Lane &l, int64_t k) const
+    {
+        Raw r;
+        r.h = make_float4(1.0f, 1.0f, 1.0f, 1.0f);  // identity activation: mask always open
+        const int o = int(kAsA ? k : l.off);
+        const bool inside = kAsA ? (l.ok && o < Fo) : (l.ok && k < rows);
+        r.nv = inside ? Fo - o : 0;
+        if (V) {
+            const int64_t e = kAsA ? l.off + (o < Fo ? o : 0) : (k < rows ? k : 0) * ld + o;
+            r.g = *reinterpret_cast<const float4 *>(dHn + e);
+            if (relu) r.h = *reinterpret_cast<const float4 *>(Hn + e);
+            return r;
         }
-        return make_float4(at(node, o), at(node, o + 1), at(node, o + 2), at(node, o + 3));
+        r.g = zero4();
+        if (!inside) return r;
+        const int64_t e = kAsA ? l.off + o : k * ld + o;
+        r.g.x = dHn[e];
+        if (o + 1 < Fo) r.g.y = dHn[e + 1];
+        if (o + 2 < Fo) r.g.z = dHn[e + 2];
+        if (o + 3 < Fo) r.g.w = dHn[e + 3];
+        if (relu) {
+            r.h.x = Hn[e];
+            if (o + 1 < Fo) r.h.y = Hn[e + 1];
+            if (o + 2 < Fo) r.h.z = Hn[e + 2];
+            if (o + 3 < Fo) r.h.w = Hn[e + 3];
+        }
+        return r;
     }
 };
 
 // ---------------------------------------------------------------------------
-// Epilogues
+// Epilogues.  col_aux / row_aux are fetched once per tile column / row with a
+// clamped (always valid) index; value() is pure arithmetic on registers.
 // ---------------------------------------------------------------------------
 struct FwdEpilogue {  // H' = act(acc + b)
+    static constexpr bool kColAux = true, kRowAux = false;
     float *out;
+    int64_t ld;
     const float *bias;
-    int N;
     bool relu;
-    __device__ __forceinline__ void operator()(int64_t row, int col, float v, int /*split*/) const
+    __device__ __forceinline__ float col_aux(int col) const { return bias[col]; }
+    __device__ __forceinline__ float row_aux(int64_t) const { return 0.0f; }
+    __device__ __forceinline__ float value(float v, float caux, float, int) const
     {
-        v += bias[col];
+        v += caux;
         if (relu) v = v > 0.0f ? v : 0.0f;
-        out[row * N + col] = v;
+        return v;
     }
+    __device__ __forceinline__ void store(int64_t row, int col, float v, int) const { out[row * ld + col] = v; }
 };
 
-struct BwdDataEpilogue {  // columns [0,F): dH_self ; [F,2F): inv_deg[row] * dM
+struct BwdDataEpilogue {  // columns [0,F): dH_self (leading dimension ldh) ; [F,2F): inv_deg[row] * dM (dense)
+    static constexpr bool kColAux = false, kRowAux = true;
     float *dH;
+    int64_t ldh;
     float *dMs;
     const float *inv_deg;
     int F;
-    __device__ __forceinline__ void operator()(int64_t row, int col, float v, int /*split*/) const
+    __device__ __forceinline__ float col_aux(int) const { return 0.0f; }
+    __device__ __forceinline__ float row_aux(int64_t row) const { return inv_deg[row]; }
+    __device__ __forceinline__ float value(float v, float, float raux, int col) const { return col < F ? v : v * raux; }
+    __device__ __forceinline__ void store(int64_t row, int col, float v, int) const
     {
-        if (col < F) dH[row * F + col] = v;
-        else dMs[row * F + (col - F)] = v * inv_deg[row];
+        if (col < F) dH[row * ldh + col] = v;
+        else dMs[row * F + (col - F)] = v;
     }
 };
 
 struct SplitEpilogue {  // partial products, one slab per split
+    static constexpr bool kColAux = false, kRowAux = false;
     float *partial;
     int64_t Mtot;
     int N;
-    __device__ __forceinline__ void operator()(int64_t row, int col, float v, int split) const
+    __device__ __forceinline__ float col_aux(int) const { return 0.0f; }
+    __device__ __forceinline__ float row_aux(int64_t) const { return 0.0f; }
+    __device__ __forceinline__ float value(float v, float, float, int) const { return v; }
+    __device__ __forceinline__ void store(int64_t row, int col, float v, int split) const
     {
         partial[(int64_t(split) * Mtot + row) * N + col] = v;
     }
 };
 
 // ---------------------------------------------------------------------------
-// C[M,N] = A[M,K] B[K,N] over k in [split*k_per_split, ...), fp32 MFMA.
-// Grid: x = m-tile * n_tiles + n-tile (n fastest, so the blocks that share an
-// A row block run together), y = split.
+// C[M,N] = A[M,K] B[K,N], k split into ranges of k_per_split, fp32 MFMA.
+// Work item = (split, m-tile, n-tile), numbered split-major then m then n.
+// Persistent blocks: the grid is 8 x (blocks per die); the block with id b sits
+// on die b % 8 and walks the work items  die*per_die + b/8, + blocks_per_die, ...
+// so that at any time the blocks of a die work on neighbouring items (the n-tiles
+// of one row block, the output tiles of one node range) and share them in its L2.
+// A block that has issued the stores of one tile goes straight on to the loads
+// of its next one.
 // ---------------------------------------------------------------------------
 template <int BM, int BN, int BK, int WM, int WN, bool kColSum, class AL, class BL, class Epi>
-__global__ __launch_bounds__(WM *WN * 64) void gemm_f32_kernel(AL a, BL b, Epi epi, int64_t M, int N, int64_t K,
-                                                              int64_t k_per_split, int n_tiles,
-                                                              float *__restrict__ colsum_partial)
+__global__ __launch_bounds__(WM *WN * 64, 2) void gemm_f32_kernel(AL a, BL b, Epi epi, int64_t M, int N, int64_t K,
+                                                                 int64_t k_per_split, int n_tiles,
+                                                                 int64_t tiles_per_split, int64_t total_work,
+                                                                 float *__restrict__ colsum_partial)
 {
     constexpr int NT = WM * WN * 64;
     constexpr int TM = BM / WM / 32;
     constexpr int TN = BN / WN / 32;
     constexpr int A_V = BM * BK / 4 / NT;
     constexpr int B_V = BN * BK / 4 / NT;
-    static_assert(BM % (WM * 32) == 0 && BN % (WN * 32) == 0 && BK % 4 == 0, "tile shape");
+    constexpr int KG = BK / 8;  // groups of 8 k-values = 4 MFMAs
+    constexpr int A_LD = AL::kContigK ? BK + kPad : BM + kPad;
+    constexpr int B_LD = BL::kContigK ? BK + kPad : BN + kPad;
+    constexpr int A_WORDS = AL::kContigK ? BM * A_LD : BK * A_LD;
+    constexpr int B_WORDS = BL::kContigK ? BN * B_LD : BK * B_LD;
+    static_assert(BM % (WM * 32) == 0 && BN % (WN * 32) == 0 && BK % 8 == 0, "tile shape");
     static_assert((BM * BK / 4) % NT == 0 && (BN * BK / 4) % NT == 0, "loader shape");
+    static_assert(!kColSum || !BL::kContigK, "column sums are taken from a [k][n] tile");
+    static_assert(A_WORDS >= BN && B_WORDS >= BM, "epilogue staging fits");
 
-    __shared__ __attribute__((aligned(16))) float As[BK][BM + kPad];
-    __shared__ __attribute__((aligned(16))) float Bs[BK][BN + kPad];
+    __shared__ __attribute__((aligned(16))) float As[2][A_WORDS];
+    __shared__ __attribute__((aligned(16))) float Bs[2][B_WORDS];
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
+    const int l31 = lane & 31;
+    const int hi = lane >> 5;
     const int wave = tid >> 6;
     const int wm0 = (wave / WN) * (BM / WM);
     const int wn0 = (wave % WN) * (BN / WN);
-    const int64_t m0 = int64_t(blockIdx.x / n_tiles) * BM;
-    const int n0 = int(blockIdx.x % n_tiles) * BN;
-    const int split = blockIdx.y;
-    const int64_t k_begin = int64_t(split) * k_per_split;
-    int64_t k_end = k_begin + k_per_split;
-    if (k_end > K) k_end = K;
 
-    floatx16 acc[TM][TN];
+    // loop-invariant positions of this thread's load slots inside a tile, and their LDS word offsets
+    int a_mn[A_V], a_k[A_V], a_lds[A_V], b_mn[B_V], b_k[B_V], b_lds[B_V];
 #pragma unroll
-    for (int i = 0; i < TM; ++i)
+    for (int i = 0; i < A_V; ++i) {
+        const int idx = tid + i * NT;
+        a_mn[i] = AL::kContigK ? idx / (BK / 4) : (idx % (BM / 4)) * 4;
+        a_k[i] = AL::kContigK ? (idx % (BK / 4)) * 4 : idx / (BM / 4);
+        a_lds[i] = AL::kContigK ? a_mn[i] * A_LD + a_k[i] : a_k[i] * A_LD + a_mn[i];
+    }
 #pragma unroll
-        for (int j = 0; j < TN; ++j)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.0f;
+    for (int i = 0; i < B_V; ++i) {
+        const int idx = tid + i * NT;
+        b_mn[i] = BL::kContigK ? idx / (BK / 4) : (idx % (BN / 4)) * 4;
+        b_k[i] = BL::kContigK ? (idx % (BK / 4)) * 4 : idx / (BN / 4);
+        b_lds[i] = BL::kContigK ? b_mn[i] * B_LD + b_k[i] : b_k[i] * B_LD + b_mn[i];
+    }
 
-    float4 areg[A_V], breg[B_V];
-    float colsum = 0.0f;
+    const int64_t blocks_per_die = gridDim.x / kXcds;
+    const int64_t per_die = (total_work + kXcds - 1) / kXcds;
+    const int64_t die = blockIdx.x % kXcds;
+    int64_t die_end = (die + 1) * per_die;
+    if (die_end > total_work) die_end = total_work;
 
-    auto fetch = [&](int64_t kt) {
-#pragma unroll
-        for (int i = 0; i < A_V; ++i) {
-            const int idx = tid + i * NT;
-            if (AL::kContigK) areg[i] = a.load4(m0 + idx / (BK / 4), kt + (idx % (BK / 4)) * 4);
-            else areg[i] = a.load4(m0 + (idx % (BM / 4)) * 4, kt + idx / (BM / 4));
-        }
-#pragma unroll
-        for (int i = 0; i < B_V; ++i) {
-            const int idx = tid + i * NT;
-            if (BL::kContigK) breg[i] = b.load4(n0 + idx / (BK / 4), kt + (idx % (BK / 4)) * 4);
-            else breg[i] = b.load4(n0 + (idx % (BN / 4)) * 4, kt + idx / (BN / 4));
-        }
-    };
-    auto stage = [&]() {
-#pragma unroll
-        for (int i = 0; i < A_V; ++i) {
-            const int idx = tid + i * NT;
-            if (AL::kContigK) {
-                const int m = idx / (BK / 4), k = (idx % (BK / 4)) * 4;
-                As[k + 0][m] = areg[i].x;
-                As[k + 1][m] = areg[i].y;
-                As[k + 2][m] = areg[i].z;
-                As[k + 3][m] = areg[i].w;
-            } else {
-                *reinterpret_cast<float4 *>(&As[idx / (BM / 4)][(idx % (BM / 4)) * 4]) = areg[i];
-            }
-        }
-#pragma unroll
-        for (int i = 0; i < B_V; ++i) {
-            const int idx = tid + i * NT;
-            if (BL::kContigK) {
-                const int n = idx / (BK / 4), k = (idx % (BK / 4)) * 4;
-                Bs[k + 0][n] = breg[i].x;
-                Bs[k + 1][n] = breg[i].y;
-                Bs[k + 2][n] = breg[i].z;
-                Bs[k + 3][n] = breg[i].w;
-            } else {
-                *reinterpret_cast<float4 *>(&Bs[idx / (BN / 4)][(idx % (BN / 4)) * 4]) = breg[i];
-            }
-        }
-    };
+    for (int64_t work = die * per_die + blockIdx.x / kXcds; work < die_end; work += blocks_per_die) {
+        const int split = int(work / tiles_per_split);
+        const int64_t tile = work % tiles_per_split;
+        const int64_t m0 = (tile / n_tiles) * BM;
+        const int n0 = int(tile % n_tiles) * BN;
+        const int64_t k_begin = int64_t(split) * k_per_split;
+        int64_t k_end = k_begin + k_per_split;
+        if (k_end > K) k_end = K;
 
-    if (k_begin < k_end) {
+        typename AL::Lane alane[A_V];
+        typename BL::Lane blane[B_V];
+#pragma unroll
+        for (int i = 0; i < A_V; ++i) alane[i] = a.prepare(m0 + a_mn[i]);
+#pragma unroll
+        for (int i = 0; i < B_V; ++i) blane[i] = b.prepare(n0 + b_mn[i]);
+
+        floatx16 acc[TM][TN];
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+            for (int j = 0; j < TN; ++j)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.0f;
+
+        typename AL::Raw areg[A_V];
+        typename BL::Raw breg[B_V];
+        float colsum = 0.0f;
+
+        auto fetch = [&](int64_t kt) {
+#pragma unroll
+            for (int i = 0; i < A_V; ++i) areg[i] = a.load(alane[i], kt + a_k[i]);
+#pragma unroll
+            for (int i = 0; i < B_V; ++i) breg[i] = b.load(blane[i], kt + b_k[i]);
+        };
+        auto stage = [&](int buf) {
+#pragma unroll
+            for (int i = 0; i < A_V; ++i) *reinterpret_cast<float4 *>(&As[buf][a_lds[i]]) = AL::resolve(areg[i]);
+#pragma unroll
+            for (int i = 0; i < B_V; ++i) *reinterpret_cast<float4 *>(&Bs[buf][b_lds[i]]) = BL::resolve(breg[i]);
+        };
+        // The four k-values (4*hi + 0..3 of group g) of this lane's row/column, for the 4 MFMAs of the group.
+        auto frag_a = [&](int buf, int g, int i) -> float4 {
+            const int mn = wm0 + i * 32 + l31;
+            const int k = g * 8 + 4 * hi;
+            if (AL::kContigK) return *reinterpret_cast<const float4 *>(&As[buf][mn * A_LD + k]);
+            return make_float4(As[buf][(k + 0) * A_LD + mn], As[buf][(k + 1) * A_LD + mn],
+                               As[buf][(k + 2) * A_LD + mn], As[buf][(k + 3) * A_LD + mn]);
+        };
+        auto frag_b = [&](int buf, int g, int j) -> float4 {
+            const int mn = wn0 + j * 32 + l31;
+            const int k = g * 8 + 4 * hi;
+            if (BL::kContigK) return *reinterpret_cast<const float4 *>(&Bs[buf][mn * B_LD + k]);
+            return make_float4(Bs[buf][(k + 0) * B_LD + mn], Bs[buf][(k + 1) * B_LD + mn],
+                               Bs[buf][(k + 2) * B_LD + mn], Bs[buf][(k + 3) * B_LD + mn]);
+        };
+
+        __syncthreads();  // the previous tile's epilogue has finished reading LDS
         fetch(k_begin);
-        stage();
-    }
-    __syncthreads();
-    for (int64_t kt = k_begin; kt < k_end; kt += BK) {
-        const bool more = kt + BK < k_end;
-        if (more) fetch(kt + BK);
-#pragma unroll
-        for (int kk = 0; kk < BK; kk += 2) {
-            float af[TM], bf[TN];
-#pragma unroll
-            for (int i = 0; i < TM; ++i) af[i] = As[kk + (lane >> 5)][wm0 + i * 32 + (lane & 31)];
-#pragma unroll
-            for (int j = 0; j < TN; ++j) bf[j] = Bs[kk + (lane >> 5)][wn0 + j * 32 + (lane & 31)];
-#pragma unroll
-            for (int i = 0; i < TM; ++i)
-#pragma unroll
-                for (int j = 0; j < TN; ++j)
-                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(af[i], bf[j], acc[i][j], 0, 0, 0);
-        }
-        if (kColSum && m0 == 0 && tid < BN) {
-#pragma unroll
-            for (int k = 0; k < BK; ++k) colsum += Bs[k][tid];
-        }
+        stage(0);
         __syncthreads();
-        if (more) stage();
-        __syncthreads();
-    }
+        int buf = 0;
+        for (int64_t kt = k_begin; kt < k_end; kt += BK) {
+            const bool more = kt + BK < k_end;
+            if (more) fetch(kt + BK);  // in flight while this slab is multiplied
 
-    // MFMA 32x32 result layout: register r of lane l holds row 8*(r/4) + 4*(l/32) + r%4, column l%32.
+            float4 fa[2][TM], fb[2][TN];
 #pragma unroll
-    for (int i = 0; i < TM; ++i)
+            for (int i = 0; i < TM; ++i) fa[0][i] = frag_a(buf, 0, i);
 #pragma unroll
-        for (int j = 0; j < TN; ++j) {
-            const int col = n0 + wn0 + j * 32 + (lane & 31);
+            for (int j = 0; j < TN; ++j) fb[0][j] = frag_b(buf, 0, j);
 #pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                const int64_t row = m0 + wm0 + i * 32 + 8 * (r / 4) + 4 * (lane >> 5) + (r % 4);
-                if (row < M && col < N) epi(row, col, acc[i][j][r], split);
+            for (int g = 0; g < KG; ++g) {
+                const int cur = g & 1, nxt = cur ^ 1;
+                if (g + 1 < KG) {  // next group's fragments are in flight while this group's MFMAs run
+#pragma unroll
+                    for (int i = 0; i < TM; ++i) fa[nxt][i] = frag_a(buf, g + 1, i);
+#pragma unroll
+                    for (int j = 0; j < TN; ++j) fb[nxt][j] = frag_b(buf, g + 1, j);
+                }
+#pragma unroll
+                for (int q = 0; q < 4; ++q)
+#pragma unroll
+                    for (int i = 0; i < TM; ++i)
+#pragma unroll
+                        for (int j = 0; j < TN; ++j) {
+                            const float av = q == 0 ? fa[cur][i].x : q == 1 ? fa[cur][i].y : q == 2 ? fa[cur][i].z : fa[cur][i].w;
+                            const float bv = q == 0 ? fb[cur][j].x : q == 1 ? fb[cur][j].y : q == 2 ? fb[cur][j].z : fb[cur][j].w;
+                            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(av, bv, acc[i][j], 0, 0, 0);
+                        }
+            }
+            if (kColSum && m0 == 0 && tid < BN) {
+#pragma unroll
+                for (int k = 0; k < BK; ++k) colsum += Bs[buf][k * B_LD + tid];
+            }
+            if (more) stage(buf ^ 1);  // the other buffer was last read before the previous barrier
+            __syncthreads();
+            buf ^= 1;
+        }
+
+        // Per-column / per-row epilogue inputs (bias, 1/deg) go through LDS: they are loaded from
+        // global memory once, here, before any store is in flight.  Fetched into registers directly they
+        // would make the compiler guard every store below with a wait on the memory counter, which
+        // also waits for the earlier stores and serialises the whole write-out.
+        if (Epi::kColAux && tid < BN) As[0][tid] = epi.col_aux(n0 + tid < N ? n0 + tid : N - 1);
+        if (Epi::kRowAux && tid < BM) Bs[0][tid] = epi.row_aux(m0 + tid < M ? m0 + tid : M - 1);
+        if (Epi::kColAux || Epi::kRowAux) __syncthreads();
+
+        // MFMA 32x32 result layout: register r of lane l holds row 8*(r/4) + 4*(l/32) + r%4, column l%32.
+        float caux[TN];
+#pragma unroll
+        for (int j = 0; j < TN; ++j) caux[j] = Epi::kColAux ? As[0][wn0 + j * 32 + l31] : 0.0f;
+#pragma unroll
+        for (int i = 0; i < TM; ++i) {
+            float raux[16];
+#pragma unroll
+            for (int r = 0; r < 16; ++r)
+                raux[r] = Epi::kRowAux ? Bs[0][wm0 + i * 32 + 8 * (r / 4) + 4 * hi + (r % 4)] : 0.0f;
+#pragma unroll
+            for (int j = 0; j < TN; ++j) {
+                const int col = n0 + wn0 + j * 32 + l31;
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    const int64_t row = m0 + wm0 + i * 32 + 8 * (r / 4) + 4 * hi + (r % 4);
+                    const float val = epi.value(acc[i][j][r], caux[j], raux[r], col);
+                    if (row < M && col < N) epi.store(row, col, val, split);
+                }
             }
         }
-    if (kColSum && m0 == 0 && tid < BN && n0 + tid < N) colsum_partial[int64_t(split) * N + n0 + tid] = colsum;
+        if (kColSum && m0 == 0 && tid < BN && n0 + tid < N) colsum_partial[int64_t(split) * N + n0 + tid] = colsum;
+    }
 }
 
-// Second stage of the split reduction: fixed order over the splits.
+// Second stage of the split reduction, fixed order.  A block owns 64 groups of
+// four consecutive outputs; its four wavefronts each add up a quarter of the
+// splits (16-byte loads, eight in flight), then the quarters are combined in
+// wavefront order through LDS.
 __global__ __launch_bounds__(256) void reduce_splits_kernel(const float *__restrict__ partial,
                                                             const float *__restrict__ colsum_partial, int n_splits,
                                                             int F, int N, float *__restrict__ dW_self,
                                                             float *__restrict__ dW_neigh, float *__restrict__ dbias)
 {
-    const int64_t total = int64_t(2) * F * N;
-    const int64_t idx = int64_t(blockIdx.x) * blockDim.x + threadIdx.x;
-    if (idx < total) {
-        float s = 0.0f;
-        for (int sp = 0; sp < n_splits; ++sp) s += partial[int64_t(sp) * total + idx];
+    __shared__ float4 part[4][64];
+    const int64_t total = int64_t(2) * F * N;      // weight-gradient entries; then N bias entries
+    const int64_t total_all = total + N;
+    const int lane = threadIdx.x & 63, q = threadIdx.x >> 6;
+    const int64_t e0 = (int64_t(blockIdx.x) * 64 + lane) * 4;
+    const int per = (n_splits + 3) / 4;
+    const int s_begin = q * per, s_end = (s_begin + per < n_splits) ? s_begin + per : n_splits;
+    float4 s = zero4();
+    if (e0 < total_all) {
+        const bool vec = (e0 + 3 < total) && (total % 4 == 0);
+        if (vec) {
+#pragma unroll 8
+            for (int sp = s_begin; sp < s_end; ++sp) {
+                const float4 v = *reinterpret_cast<const float4 *>(partial + int64_t(sp) * total + e0);
+                s.x += v.x; s.y += v.y; s.z += v.z; s.w += v.w;
+            }
+        } else {
+            float t[4] = {0.0f, 0.0f, 0.0f, 0.0f};
+            for (int sp = s_begin; sp < s_end; ++sp)
+#pragma unroll
+                for (int c = 0; c < 4; ++c) {
+                    const int64_t e = e0 + c;
+                    if (e < total) t[c] += partial[int64_t(sp) * total + e];
+                    else if (e < total_all) t[c] += colsum_partial[int64_t(sp) * N + (e - total)];
+                }
+            s = make_float4(t[0], t[1], t[2], t[3]);
+        }
+    }
+    part[q][lane] = s;
+    __syncthreads();
+    if (q == 0 && e0 < total_all) {
+        float r[4] = {0.0f, 0.0f, 0.0f, 0.0f};
+#pragma unroll
+        for (int w = 0; w < 4; ++w) {
+            const float4 v = part[w][lane];
+            r[0] += v.x; r[1] += v.y; r[2] += v.z; r[3] += v.w;
+        }
         const int64_t half = int64_t(F) * N;
-        if (idx < half) dW_self[idx] = s;
-        else dW_neigh[idx - half] = s;
-    } else if (idx < total + N) {
-        const int n = int(idx - total);
-        float s = 0.0f;
-        for (int sp = 0; sp < n_splits; ++sp) s += colsum_partial[int64_t(sp) * N + n];
-        dbias[n] = s;
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+            const int64_t e = e0 + c;
+            if (e < half) dW_self[e] = r[c];
+            else if (e < total) dW_neigh[e - half] = r[c];
+            else if (e < total_all) dbias[e - total] = r[c];
+        }
     }
 }
 
 static bool vec4_ok(const void *p, int64_t ld) { return aligned(p, 16) && ld % 4 == 0; }
 
-template <int BM, int BN, int WM, int WN, bool kColSum, class AL, class BL, class Epi>
+template <int BM, int BN, int BK, int WM, int WN, bool kColSum, class AL, class BL, class Epi>
 static void launch_gemm(const char *name, const AL &a, const BL &b, const Epi &e, int64_t M, int N, int64_t K,
                         int64_t k_per_split, int n_splits, float *colsum_partial, hipStream_t s)
 {
-    constexpr int BK = 16;
-    TMA_TIMED(name, s);
     const int n_tiles = int(ceil_div(N, BN));
-    const int64_t m_tiles = ceil_div(M, BM);
-    hipLaunchKernelGGL((gemm_f32_kernel<BM, BN, BK, WM, WN, kColSum, AL, BL, Epi>),
-                       dim3(unsigned(m_tiles * n_tiles), unsigned(n_splits)), dim3(WM * WN * 64), 0, s, a, b, e, M, N,
-                       K, k_per_split, n_tiles, colsum_partial);
+    const int64_t tiles = ceil_div(M, BM) * n_tiles;
+    const int64_t total = tiles * n_splits;
+    // two resident blocks per compute unit (LDS and register budget of the kernel), 256 units in 8 dies
+    int64_t blocks_per_die = ceil_div(total, kXcds);
+    if (blocks_per_die > 64) blocks_per_die = 64;
+    TMA_TIMED(name, s);
+    hipLaunchKernelGGL((gemm_f32_kernel<BM, BN, BK, WM, WN, kColSum, AL, BL, Epi>), dim3(unsigned(blocks_per_die * kXcds)),
+                       dim3(WM * WN * 64), 0, s, a, b, e, M, N, K, k_per_split, n_tiles, tiles, total, colsum_partial);
+}
+
+// ---- forward ----------------------------------------------------------------
+template <bool VA, bool VB>
+static void fwd_dispatch(int64_t n, const float *H, int64_t ldh, const float *M, int F_in, const float *W_self,
+                         const float *W_neigh, const FwdEpilogue &e, int F_out, hipStream_t s)
+{
+    constexpr bool V = VA && VB;
+    CatRows<VA> a{H, ldh, M, F_in, n};
+    CatWeights<VB> b{W_self, W_neigh, F_in, F_out};
+    const int64_t K = 2 * int64_t(F_in);
+    const int64_t kps = int64_t(round_up(size_t(K), 32));
+    if (F_out <= 64) launch_gemm<128, 64, 32, 4, 1, false>(V ? "gemm_fwd_128x64" : "gemm_fwd_128x64_generic", a, b, e, n, F_out, K, kps, 1, nullptr, s);
+    else launch_gemm<128, 128, 32, 2, 2, false>(V ? "gemm_fwd_128x128" : "gemm_fwd_128x128_generic", a, b, e, n, F_out, K, kps, 1, nullptr, s);
 }
 
 int launch_sage_gemm_fwd(int64_t n, const void *H, int64_t ldh, const void *M, int32_t F_in, const float *W_self,
                          const float *W_neigh, const float *bias, int32_t F_out, int32_t act, int32_t dtype,
-                         void *Hnext, hipStream_t stream)
+                         void *Hnext, int64_t ld_next, hipStream_t stream)
 {
     if (dtype != TMA_F32) return fail(TMA_ERR_UNSUPPORTED_DTYPE, "sage gemm fwd: dtype %d not built yet", dtype);
     if (n == 0 || F_out == 0) return TMA_OK;
     const float *Hf = static_cast<const float *>(H), *Mf = static_cast<const float *>(M);
-    CatRows a{Hf, ldh, Mf, F_in, n, vec4_ok(Hf, ldh) && vec4_ok(Mf, F_in) && F_in % 4 == 0};
-    CatWeights b{W_self, W_neigh, F_in, F_out, vec4_ok(W_self, F_out) && vec4_ok(W_neigh, F_out)};
-    FwdEpilogue e{static_cast<float *>(Hnext), bias, F_out, act == TMA_ACT_RELU};
-    const int64_t K = 2 * int64_t(F_in);
-    const int64_t kps = round_up(size_t(K), 16);
-    if (F_out <= 64) launch_gemm<128, 64, 4, 1, false>("gemm_fwd_128x64", a, b, e, n, F_out, K, kps, 1, nullptr, stream);
-    else launch_gemm<128, 128, 2, 2, false>("gemm_fwd_128x128", a, b, e, n, F_out, K, kps, 1, nullptr, stream);
+    FwdEpilogue e{static_cast<float *>(Hnext), ld_next, bias, act == TMA_ACT_RELU};
+    const bool va = vec4_ok(Hf, ldh) && vec4_ok(Mf, F_in);
+    const bool vb = vec4_ok(W_self, F_out) && vec4_ok(W_neigh, F_out);
+    if (va && vb) fwd_dispatch<true, true>(n, Hf, ldh, Mf, F_in, W_self, W_neigh, e, F_out, stream);
+    else if (va) fwd_dispatch<true, false>(n, Hf, ldh, Mf, F_in, W_self, W_neigh, e, F_out, stream);
+    else if (vb) fwd_dispatch<false, true>(n, Hf, ldh, Mf, F_in, W_self, W_neigh, e, F_out, stream);
+    else fwd_dispatch<false, false>(n, Hf, ldh, Mf, F_in, W_self, W_neigh, e, F_out, stream);
     return check_launch("sage gemm fwd");
 }
 
-int launch_sage_gemm_bwd_data(int64_t n, const void *dHnext, const void *Hnext, const float *inv_deg,
-                              const float *W_self, const float *W_neigh, int32_t F_in, int32_t F_out, int32_t act,
-                              int32_t dtype, void *dH_self_out, void *dM_scaled_out, hipStream_t stream)
+// ---- backward: data ---------------------------------------------------------
+template <bool VA, bool VB>
+static void bwd_data_dispatch(int64_t n, const float *g, const float *h, int64_t ld_next, bool relu,
+                              const float *W_self, const float *W_neigh, int F_in, int F_out,
+                              const BwdDataEpilogue &e, hipStream_t s)
+{
+    constexpr bool V = VA && VB;
+    MaskedGrad<true, VA> a{g, h, F_out, ld_next, n, relu};
+    CatWeightsT<VB> b{W_self, W_neigh, F_in, F_out};
+    const int N = 2 * F_in;
+    const int64_t K = F_out;
+    if (K <= 48) {  // short reduction: 16-wide slabs waste less of the last one
+        const int64_t kps = int64_t(round_up(size_t(K), 16));
+        launch_gemm<128, 128, 16, 2, 2, false>(V ? "gemm_bwd_data_128x128" : "gemm_bwd_data_128x128_generic", a, b, e, n, N, K, kps, 1, nullptr, s);
+    } else {
+        const int64_t kps = int64_t(round_up(size_t(K), 32));
+        launch_gemm<128, 128, 32, 2, 2, false>(V ? "gemm_bwd_data_128x128" : "gemm_bwd_data_128x128_generic", a, b, e, n, N, K, kps, 1, nullptr, s);
+    }
+}
+
+int launch_sage_gemm_bwd_data(int64_t n, const void *dHnext, const void *Hnext, int64_t ld_next,
+                              const float *inv_deg, const float *W_self, const float *W_neigh, int32_t F_in,
+                              int32_t F_out, int32_t act, int32_t dtype, void *dH_self_out, int64_t ldh,
+                              void *dM_scaled_out, hipStream_t stream)
 {
     if (dtype != TMA_F32) return fail(TMA_ERR_UNSUPPORTED_DTYPE, "sage gemm bwd: dtype %d not built yet", dtype);
     if (n == 0 || F_in == 0) return TMA_OK;
     const float *g = static_cast<const float *>(dHnext), *h = static_cast<const float *>(Hnext);
     const bool relu = act == TMA_ACT_RELU;
-    MaskedGrad<true> a{g, h, F_out, n, relu, vec4_ok(g, F_out) && (!relu || vec4_ok(h, F_out))};
-    CatWeightsT b{W_self, W_neigh, F_in, F_out, vec4_ok(W_self, F_out) && vec4_ok(W_neigh, F_out)};
-    BwdDataEpilogue e{static_cast<float *>(dH_self_out), static_cast<float *>(dM_scaled_out), inv_deg, F_in};
-    const int N = 2 * F_in;
-    const int64_t K = F_out;
-    const int64_t kps = round_up(size_t(K), 16);
-    launch_gemm<128, 128, 2, 2, false>("gemm_bwd_data_128x128", a, b, e, n, N, K, kps, 1, nullptr, stream);
+    BwdDataEpilogue e{static_cast<float *>(dH_self_out), ldh, static_cast<float *>(dM_scaled_out), inv_deg, F_in};
+    const bool va = vec4_ok(g, ld_next) && (!relu || vec4_ok(h, ld_next));
+    const bool vb = vec4_ok(W_self, F_out) && vec4_ok(W_neigh, F_out);
+    if (va && vb) bwd_data_dispatch<true, true>(n, g, h, ld_next, relu, W_self, W_neigh, F_in, F_out, e, stream);
+    else if (va) bwd_data_dispatch<true, false>(n, g, h, ld_next, relu, W_self, W_neigh, F_in, F_out, e, stream);
+    else if (vb) bwd_data_dispatch<false, true>(n, g, h, ld_next, relu, W_self, W_neigh, F_in, F_out, e, stream);
+    else bwd_data_dispatch<false, false>(n, g, h, ld_next, relu, W_self, W_neigh, F_in, F_out, e, stream);
     return check_launch("sage gemm bwd data");
 }
 
+// ---- backward: weights ------------------------------------------------------
 struct WeightSplit {
     int n_splits;
     int64_t k_per_split;
@@ -414,11 +682,11 @@ static WeightSplit plan_weight_split(int64_t n, int32_t F_in, int32_t F_out)
     const int bn = F_out <= 64 ? 64 : 128;
     const int64_t tiles = ceil_div(2 * int64_t(F_in), 128) * ceil_div(F_out, bn);
     int64_t want = ceil_div(512, tiles > 0 ? tiles : 1);
-    const int64_t max_useful = ceil_div(n > 0 ? n : 1, 64);
+    const int64_t max_useful = ceil_div(n > 0 ? n : 1, 128);
     if (want > max_useful) want = max_useful;
     if (want < 1) want = 1;
     WeightSplit w;
-    w.k_per_split = int64_t(round_up(size_t(ceil_div(n > 0 ? n : 1, want)), 16));
+    w.k_per_split = int64_t(round_up(size_t(ceil_div(n > 0 ? n : 1, want)), 32));
     w.n_splits = int(ceil_div(n > 0 ? n : 1, w.k_per_split));
     w.partial_bytes = round_up(size_t(w.n_splits) * 2 * size_t(F_in) * size_t(F_out) * 4, 256);
     w.colsum_bytes = round_up(size_t(w.n_splits) * size_t(F_out) * 4, 256);
@@ -431,8 +699,24 @@ size_t sage_gemm_bwd_weight_workspace_bytes(int64_t n, int32_t F_in, int32_t F_o
     return w.partial_bytes + w.colsum_bytes;
 }
 
+template <bool VA, bool VB>
+static void bwd_weight_dispatch(int64_t n, const float *H, int64_t ldh, const float *M, const float *g,
+                                const float *h, int64_t ld_next, bool relu, int F_in, int F_out,
+                                const WeightSplit &w, const SplitEpilogue &e, float *colsum, hipStream_t s)
+{
+    constexpr bool V = VA && VB;
+    CatRowsT<VA> a{H, ldh, M, F_in, n};
+    MaskedGrad<false, VB> b{g, h, F_out, ld_next, n, relu};
+    const int64_t Mtot = 2 * int64_t(F_in);
+    if (F_out <= 64)
+        launch_gemm<128, 64, 32, 4, 1, true>(V ? "gemm_bwd_weight_128x64" : "gemm_bwd_weight_128x64_generic", a, b, e, Mtot, F_out, n, w.k_per_split, w.n_splits, colsum, s);
+    else
+        launch_gemm<128, 128, 32, 2, 2, true>(V ? "gemm_bwd_weight_128x128" : "gemm_bwd_weight_128x128_generic", a, b, e, Mtot, F_out, n, w.k_per_split, w.n_splits, colsum, s);
+}
+
 int launch_sage_gemm_bwd_weight(int64_t n, const void *H, int64_t ldh, const void *M, const void *dHnext,
-                                const void *Hnext, int32_t F_in, int32_t F_out, int32_t act, int32_t dtype,
+                                const void *Hnext, int64_t ld_next, int32_t F_in, int32_t F_out, int32_t act,
+                                int32_t dtype,
                                 float *dW_self, float *dW_neigh, float *dbias, void *ws, size_t ws_bytes,
                                 hipStream_t stream)
 {
@@ -447,18 +731,20 @@ int launch_sage_gemm_bwd_weight(int64_t n, const void *H, int64_t ldh, const voi
     const float *Hf = static_cast<const float *>(H), *Mf = static_cast<const float *>(M);
     const float *g = static_cast<const float *>(dHnext), *h = static_cast<const float *>(Hnext);
     const bool relu = act == TMA_ACT_RELU;
-    CatRowsT a{Hf, ldh, Mf, F_in, n, vec4_ok(Hf, ldh) && vec4_ok(Mf, F_in) && F_in % 4 == 0};
-    MaskedGrad<false> b{g, h, F_out, n, relu, vec4_ok(g, F_out) && (!relu || vec4_ok(h, F_out))};
     const int64_t Mtot = 2 * int64_t(F_in);
     SplitEpilogue e{partial, Mtot, F_out};
     if (F_in > 0) {
-        if (F_out <= 64) launch_gemm<128, 64, 4, 1, true>("gemm_bwd_weight_128x64", a, b, e, Mtot, F_out, n, w.k_per_split, w.n_splits, colsum, stream);
-        else launch_gemm<128, 128, 2, 2, true>("gemm_bwd_weight_128x128", a, b, e, Mtot, F_out, n, w.k_per_split, w.n_splits, colsum, stream);
+        const bool va = vec4_ok(Hf, ldh) && vec4_ok(Mf, F_in);
+        const bool vb = vec4_ok(g, ld_next) && (!relu || vec4_ok(h, ld_next));
+        if (va && vb) bwd_weight_dispatch<true, true>(n, Hf, ldh, Mf, g, h, ld_next, relu, F_in, F_out, w, e, colsum, stream);
+        else if (va) bwd_weight_dispatch<true, false>(n, Hf, ldh, Mf, g, h, ld_next, relu, F_in, F_out, w, e, colsum, stream);
+        else if (vb) bwd_weight_dispatch<false, true>(n, Hf, ldh, Mf, g, h, ld_next, relu, F_in, F_out, w, e, colsum, stream);
+        else bwd_weight_dispatch<false, false>(n, Hf, ldh, Mf, g, h, ld_next, relu, F_in, F_out, w, e, colsum, stream);
         if (int rc = check_launch("sage gemm bwd weight")) return rc;
     }
-    const int64_t total = Mtot * F_out + F_out;
+    const int64_t total_all = Mtot * F_out + F_out;
     TMA_TIMED("reduce_splits", stream);
-    hipLaunchKernelGGL(reduce_splits_kernel, dim3(unsigned(ceil_div(total, 256))), dim3(256), 0, stream, partial,
+    hipLaunchKernelGGL(reduce_splits_kernel, dim3(unsigned(ceil_div(total_all, 256))), dim3(256), 0, stream, partial,
                        colsum, F_in > 0 ? w.n_splits : 0, F_in, F_out, dW_self, dW_neigh, dbias);
     return check_launch("sage gemm bwd weight reduce");
 }

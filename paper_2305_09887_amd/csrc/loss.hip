@@ -24,27 +24,39 @@ __device__ __forceinline__ float block_sum_256(float v)
     return s;
 }
 
-// One node per thread: log-sum-exp, loss term, gradient (softmax - onehot)/n.
+// Sixteen lanes per node (coalesced row reads): log-sum-exp, loss term,
+// gradient (softmax - onehot)/n.  The row is read three times; it stays in L1.
+constexpr int kCeLanes = 16;
+constexpr int kCeRows = 256 / kCeLanes;
+
 template <typename T>
 __global__ __launch_bounds__(256) void softmax_ce_kernel(int64_t n, int C, const T *__restrict__ logits, int64_t ld_in,
                                                          const int32_t *__restrict__ labels,
                                                          T *__restrict__ dlogits, float *__restrict__ block_loss)
 {
-    const int64_t v = int64_t(blockIdx.x) * 256 + threadIdx.x;
+    const int sub = threadIdx.x % kCeLanes;
+    const int64_t v = int64_t(blockIdx.x) * kCeRows + threadIdx.x / kCeLanes;
     float term = 0.0f;
-    if (v < n) {
-        const T *z = logits + v * ld_in;
-        float mx = ld(z);
-        for (int c = 1; c < C; ++c) mx = fmaxf(mx, ld(z + c));
-        float se = 0.0f;
-        for (int c = 0; c < C; ++c) se += expf(ld(z + c) - mx);
+    const bool live = v < n;
+    const T *z = logits + (live ? v : 0) * ld_in;
+    float mx = -INFINITY;
+    if (live)
+        for (int c = sub; c < C; c += kCeLanes) mx = fmaxf(mx, ld(z + c));
+#pragma unroll
+    for (int d = kCeLanes / 2; d >= 1; d >>= 1) mx = fmaxf(mx, __shfl_xor(mx, d, kWave));
+    float se = 0.0f;
+    if (live)
+        for (int c = sub; c < C; c += kCeLanes) se += expf(ld(z + c) - mx);
+#pragma unroll
+    for (int d = kCeLanes / 2; d >= 1; d >>= 1) se += __shfl_xor(se, d, kWave);
+    if (live) {
         const float lse = mx + logf(se);
         const int y = labels[v];
-        term = lse - ld(z + y);
+        if (sub == 0) term = lse - ld(z + y);
         if (dlogits) {
             const float inv_n = 1.0f / float(n);
-            for (int c = 0; c < C; ++c)
-                st(dlogits + v * C + c, (expf(ld(z + c) - lse) - (c == y ? 1.0f : 0.0f)) * inv_n);
+            for (int c = sub; c < C; c += kCeLanes)
+                st(dlogits + v * ld_in + c, (expf(ld(z + c) - lse) - (c == y ? 1.0f : 0.0f)) * inv_n);
         }
     }
     const float s = block_sum_256(term);
@@ -66,7 +78,7 @@ __global__ __launch_bounds__(256) void sigmoid_l2_kernel(int64_t n, int C, const
         const float z = 1.0f / (1.0f + expf(-ld(G + v * ld_in + c)));
         const float r = z - Y[i];
         term = 0.5f * r * r;
-        if (dG) st(dG + i, r * z * (1.0f - z));
+        if (dG) st(dG + v * ld_in + c, r * z * (1.0f - z));
     }
     const float s = block_sum_256(term);
     if (threadIdx.x == 0) block_loss[blockIdx.x] = s;
@@ -122,8 +134,13 @@ static int check_loss_args(const char *fn, int64_t n, int32_t C, const void *in,
 extern "C" size_t tma_loss_workspace_bytes(int64_t n, int32_t C)
 {
     if (n < 0 || C < 1) return 0;
-    const int64_t items = n * int64_t(C);  // the element-wise loss runs one thread per (node, output)
-    return tma::round_up(size_t(tma::ceil_div(items > 0 ? items : 1, 256)) * 4, 256);
+    // one partial sum per block: the element-wise loss runs one thread per (node, output),
+    // the softmax loss sixteen lanes per node
+    const int64_t items = n * int64_t(C);
+    int64_t blocks = tma::ceil_div(items > 0 ? items : 1, 256);
+    const int64_t ce_blocks = tma::ceil_div(n > 0 ? n : 1, tma::kCeRows);
+    if (ce_blocks > blocks) blocks = ce_blocks;
+    return tma::round_up(size_t(blocks) * 4, 256);
 }
 
 extern "C" int tma_softmax_ce(int64_t n, int32_t C, const void *logits, int64_t ldz, int32_t dtype,
@@ -136,7 +153,7 @@ extern "C" int tma_softmax_ce(int64_t n, int32_t C, const void *logits, int64_t 
     TMA_REQUIRE(n == 0 || labels, TMA_ERR_INVALID_ARG, "%s: labels is NULL", fn);
     hipStream_t s = as_stream(stream);
     float *block_loss = static_cast<float *>(ws);
-    const int64_t nb = n > 0 ? ceil_div(n, 256) : 0;
+    const int64_t nb = n > 0 ? ceil_div(n, kCeRows) : 0;
     if (nb > 0) {
         TMA_TIMED("softmax_ce", s);
         if (dtype == TMA_F32)

@@ -26,7 +26,7 @@ static BwdWorkspace plan_bwd(int64_t n, int32_t F_in, int32_t F_out, int32_t dty
 extern "C" int tma_sage_layer_fwd(int64_t n, const int32_t *rowptr, const int32_t *colidx, const float *inv_deg,
                                   const void *H, int64_t ldh, int32_t F_in, const float *W_self,
                                   const float *W_neigh, const float *bias, int32_t F_out, int32_t act, int32_t dtype,
-                                  void *M_out, void *Hnext_out, tma_stream_t stream)
+                                  void *M_out, void *Hnext_out, int64_t ld_next, tma_stream_t stream)
 {
     using namespace tma;
     const char *fn = "tma_sage_layer_fwd";
@@ -38,10 +38,11 @@ extern "C" int tma_sage_layer_fwd(int64_t n, const int32_t *rowptr, const int32_
     if (n == 0) return TMA_OK;
     TMA_REQUIRE(rowptr && inv_deg && H && W_self && W_neigh && bias && M_out && Hnext_out, TMA_ERR_INVALID_ARG,
                 "%s: NULL argument", fn);
-    TMA_REQUIRE(ldh >= F_in, TMA_ERR_BAD_SHAPE, "%s: ldh < F_in", fn);
+    TMA_REQUIRE(ldh >= F_in && ld_next >= F_out, TMA_ERR_BAD_SHAPE, "%s: ldh < F_in or ld_next < F_out", fn);
     hipStream_t s = as_stream(stream);
     if (int rc = launch_spmm(n, rowptr, colidx, inv_deg, H, ldh, F_in, dtype, M_out, F_in, false, s)) return rc;
-    return launch_sage_gemm_fwd(n, H, ldh, M_out, F_in, W_self, W_neigh, bias, F_out, act, dtype, Hnext_out, s);
+    return launch_sage_gemm_fwd(n, H, ldh, M_out, F_in, W_self, W_neigh, bias, F_out, act, dtype, Hnext_out, ld_next,
+                                s);
 }
 
 extern "C" size_t tma_sage_layer_bwd_workspace_bytes(int64_t n, int32_t F_in, int32_t F_out, int32_t dtype,
@@ -53,7 +54,7 @@ extern "C" size_t tma_sage_layer_bwd_workspace_bytes(int64_t n, int32_t F_in, in
 
 extern "C" int tma_sage_layer_bwd(int64_t n, const int32_t *rowptr_T, const int32_t *colidx_T, const float *inv_deg,
                                   const void *H, int64_t ldh, const void *M, const void *Hnext, const void *dHnext,
-                                  const float *W_self, const float *W_neigh, int32_t F_in, int32_t F_out, int32_t act,
+                                  int64_t ld_next, const float *W_self, const float *W_neigh, int32_t F_in, int32_t F_out, int32_t act,
                                   int32_t dtype, float *dW_self, float *dW_neigh, float *dbias, void *dH_out, void *ws,
                                   size_t ws_bytes, tma_stream_t stream)
 {
@@ -74,20 +75,20 @@ extern "C" int tma_sage_layer_bwd(int64_t n, const int32_t *rowptr_T, const int3
         TMA_REQUIRE(H && M && dHnext && W_self && W_neigh, TMA_ERR_INVALID_ARG, "%s: NULL argument", fn);
         TMA_REQUIRE(act == TMA_ACT_NONE || Hnext, TMA_ERR_INVALID_ARG, "%s: Hnext is required with ReLU", fn);
         TMA_REQUIRE(!need_dH || (rowptr_T && inv_deg), TMA_ERR_INVALID_ARG, "%s: graph is NULL", fn);
-        TMA_REQUIRE(ldh >= F_in, TMA_ERR_BAD_SHAPE, "%s: ldh < F_in", fn);
+        TMA_REQUIRE(ldh >= F_in && ld_next >= F_out, TMA_ERR_BAD_SHAPE, "%s: ldh < F_in or ld_next < F_out", fn);
     }
     hipStream_t s = as_stream(stream);
     char *base = static_cast<char *>(ws);
     void *dMs = base;
     void *wws = base + w.dm_bytes;
 
-    if (int rc = launch_sage_gemm_bwd_weight(n, H, ldh, M, dHnext, Hnext, F_in, F_out, act, dtype, dW_self, dW_neigh,
-                                             dbias, wws, w.weight_bytes, s))
+    if (int rc = launch_sage_gemm_bwd_weight(n, H, ldh, M, dHnext, Hnext, ld_next, F_in, F_out, act, dtype, dW_self,
+                                             dW_neigh, dbias, wws, w.weight_bytes, s))
         return rc;
     if (!need_dH || n == 0) return TMA_OK;
     // dH = dZ W_self^T  (written by the transform)  +  A^T (D^-1 dZ W_neigh^T)  (gathered on top of it)
-    if (int rc = launch_sage_gemm_bwd_data(n, dHnext, Hnext, inv_deg, W_self, W_neigh, F_in, F_out, act, dtype,
-                                           dH_out, dMs, s))
+    if (int rc = launch_sage_gemm_bwd_data(n, dHnext, Hnext, ld_next, inv_deg, W_self, W_neigh, F_in, F_out, act, dtype,
+                                           dH_out, ldh, dMs, s))
         return rc;
-    return launch_spmm(n, rowptr_T, colidx_T, nullptr, dMs, F_in, F_in, dtype, dH_out, F_in, true, s);
+    return launch_spmm(n, rowptr_T, colidx_T, nullptr, dMs, F_in, F_in, dtype, dH_out, ldh, true, s);
 }

@@ -132,6 +132,60 @@ __device__ __forceinline__ void finish_row(int64_t v, const float *__restrict__ 
         }
 }
 
+// Adds the rows colidx[e], e in [beg, end), into the accumulators of up to four consecutive
+// CSR rows at once: entry e belongs to row r when bound[r] <= e < bound[r+1].  The entries
+// of consecutive rows are contiguous in colidx, so the group walks them as one list with
+// four independent 16-byte loads in flight, and steers each loaded chunk to its row by
+// predication (adding 0 elsewhere).  At a mean local degree of 2-5 this is what keeps
+// enough bytes in flight; walking the rows one after the other leaves the lanes waiting.
+template <typename T, int G, int R>
+__device__ __forceinline__ void gather_sum_rows(const T *__restrict__ in, int64_t ld,
+                                                const int32_t *__restrict__ colidx, const int32_t (&bound)[R + 1],
+                                                int sub, int n_chunks, float (&acc)[R][Chunk<T>::kElems])
+{
+    constexpr int E = Chunk<T>::kElems;
+    const bool own = sub < n_chunks;
+    const int32_t end = bound[R];
+    for (int32_t e0 = bound[0]; e0 < end; e0 += G) {
+        const int cnt = (end - e0) < G ? (end - e0) : G;
+        const int32_t mine = sub < cnt ? colidx[e0 + sub] : 0;
+        int j = 0;
+        for (; j + 4 <= cnt; j += 4) {
+            float v[4][E];
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const T *row = in + int64_t(__shfl(mine, j + q, G)) * ld;
+                if (own) Chunk<T>::load(row + sub * E, v[q]);
+            }
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const int32_t e = e0 + j + q;
+#pragma unroll
+                for (int r = 0; r < R; ++r) {
+                    const bool hit = e >= bound[r] && e < bound[r + 1];
+                    if (own)
+#pragma unroll
+                        for (int i = 0; i < E; ++i) acc[r][i] += hit ? v[q][i] : 0.0f;
+                }
+            }
+        }
+        for (; j < cnt; ++j) {
+            const T *row = in + int64_t(__shfl(mine, j, G)) * ld;
+            const int32_t e = e0 + j;
+            if (own) {
+                float v[E];
+                Chunk<T>::load(row + sub * E, v);
+#pragma unroll
+                for (int r = 0; r < R; ++r) {
+                    const bool hit = e >= bound[r] && e < bound[r + 1];
+#pragma unroll
+                    for (int i = 0; i < E; ++i) acc[r][i] += hit ? v[i] : 0.0f;
+                }
+            }
+        }
+    }
+}
+
 template <typename T, int G, int CPL>
 __global__ __launch_bounds__(kSpmmThreads) void spmm_rows_kernel(int64_t n, const int32_t *__restrict__ rowptr,
                                                                  const int32_t *__restrict__ colidx,
@@ -142,7 +196,8 @@ __global__ __launch_bounds__(kSpmmThreads) void spmm_rows_kernel(int64_t n, cons
 {
     constexpr int E = Chunk<T>::kElems;
     constexpr int NG = kSpmmThreads / G;
-    constexpr int RPB = NG * kRowsPerGroup;
+    constexpr int R = kRowsPerGroup;
+    constexpr int RPB = NG * R;
     __shared__ int32_t hub_rows[RPB];
     __shared__ int32_t hub_count;
     __shared__ float partial[NG][G * CPL * E];
@@ -152,22 +207,48 @@ __global__ __launch_bounds__(kSpmmThreads) void spmm_rows_kernel(int64_t n, cons
     if (threadIdx.x == 0) hub_count = 0;
     __syncthreads();
 
+    // the group owns R consecutive rows v0 .. v0+R-1
     const int64_t base = int64_t(blockIdx.x) * RPB;
-    for (int i = 0; i < kRowsPerGroup; ++i) {
-        const int64_t v = base + grp + i * NG;
-        if (v >= n) break;
-        const int32_t beg = rowptr[v], end = rowptr[v + 1];
-        if (end - beg > kHubDegree) {
-            if (sub == 0) hub_rows[atomicAdd(&hub_count, 1)] = int32_t(v - base);
-            continue;
+    const int64_t v0 = base + int64_t(grp) * R;
+    int32_t bound[R + 1];
+#pragma unroll
+    for (int r = 0; r <= R; ++r) bound[r] = rowptr[(v0 + r) < n ? (v0 + r) : n];
+    bool any_hub = false;
+#pragma unroll
+    for (int r = 0; r < R; ++r) any_hub = any_hub || (bound[r + 1] - bound[r] > kHubDegree);
+
+    if (CPL == 1 && !any_hub) {
+        float acc[R][E];
+#pragma unroll
+        for (int r = 0; r < R; ++r)
+#pragma unroll
+            for (int k = 0; k < E; ++k) acc[r][k] = 0.0f;
+        gather_sum_rows<T, G, R>(in, ld_in, colidx, bound, sub, n_chunks, acc);
+#pragma unroll
+        for (int r = 0; r < R; ++r)
+            if (v0 + r < n) {
+                float one[1][E];
+#pragma unroll
+                for (int k = 0; k < E; ++k) one[0][k] = acc[r][k];
+                finish_row<T, G, 1>(v0 + r, inv_deg, out, ld_out, accumulate != 0, sub, n_chunks, one);
+            }
+    } else {
+        for (int r = 0; r < R; ++r) {
+            const int64_t v = v0 + r;
+            if (v >= n) break;
+            const int32_t beg = bound[r], end = bound[r + 1];
+            if (end - beg > kHubDegree) {
+                if (sub == 0) hub_rows[atomicAdd(&hub_count, 1)] = int32_t(v - base);
+                continue;
+            }
+            float acc[CPL][E];
+#pragma unroll
+            for (int c = 0; c < CPL; ++c)
+#pragma unroll
+                for (int k = 0; k < E; ++k) acc[c][k] = 0.0f;
+            gather_sum<T, G, CPL>(in, ld_in, colidx, beg, end, G, sub, n_chunks, acc);
+            finish_row<T, G, CPL>(v, inv_deg, out, ld_out, accumulate != 0, sub, n_chunks, acc);
         }
-        float acc[CPL][E];
-#pragma unroll
-        for (int c = 0; c < CPL; ++c)
-#pragma unroll
-            for (int k = 0; k < E; ++k) acc[c][k] = 0.0f;
-        gather_sum<T, G, CPL>(in, ld_in, colidx, beg, end, G, sub, n_chunks, acc);
-        finish_row<T, G, CPL>(v, inv_deg, out, ld_out, accumulate != 0, sub, n_chunks, acc);
     }
     __syncthreads();
 

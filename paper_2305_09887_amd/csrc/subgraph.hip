@@ -154,6 +154,10 @@ __global__ __launch_bounds__(kScanThreads) void scan_apply_kernel(const int64_t 
 // rowptr_loc[0] = 0 also when the partition is empty (the apply kernel then stores nothing).
 __global__ void write_zero_kernel(int32_t *p) { *p = 0; }
 
+// Global rows longer than this are scanned by the whole workgroup instead of 16 lanes
+// (power-law graphs: a few rows hold thousands of entries and would otherwise set the kernel's tail).
+constexpr int kHubRow = 128;
+
 // Kept degree of every local row: entries whose column is local too.
 __global__ __launch_bounds__(256) void row_count_kernel(const int64_t *d_n_loc, int64_t cap,
                                                         const int32_t *__restrict__ l2g,
@@ -162,18 +166,47 @@ __global__ __launch_bounds__(256) void row_count_kernel(const int64_t *d_n_loc, 
                                                         const int32_t *__restrict__ g2l,
                                                         int32_t *__restrict__ deg)
 {
+    __shared__ int32_t hub_rows[kRowsPerBlock];
+    __shared__ int32_t hub_count;
+    __shared__ int32_t wave_part[256 / kWave];
+    if (threadIdx.x == 0) hub_count = 0;
+    __syncthreads();
+
     const int64_t n_loc = effective_n(d_n_loc, cap);
     const int sub = threadIdx.x % kRowLanes;
-    const int64_t i = int64_t(blockIdx.x) * kRowsPerBlock + threadIdx.x / kRowLanes;
+    const int64_t row0 = int64_t(blockIdx.x) * kRowsPerBlock;
+    const int64_t i = row0 + threadIdx.x / kRowLanes;
     int32_t c = 0;
+    bool light = false;
     if (i < n_loc) {
         const int64_t v = l2g[i];
-        const int64_t end = rowptr[v + 1];
-        for (int64_t e = rowptr[v] + sub; e < end; e += kRowLanes) c += g2l[colidx[e]] >= 0 ? 1 : 0;
+        const int64_t beg = rowptr[v], end = rowptr[v + 1];
+        if (end - beg > kHubRow) {
+            if (sub == 0) hub_rows[atomicAdd(&hub_count, 1)] = int32_t(i - row0);
+        } else {
+            light = true;
+            for (int64_t e = beg + sub; e < end; e += kRowLanes) c += g2l[colidx[e]] >= 0 ? 1 : 0;
+        }
     }
 #pragma unroll
     for (int d = kRowLanes / 2; d >= 1; d >>= 1) c += __shfl_xor(c, d, kWave);
-    if (i < n_loc && sub == 0) deg[i] = c;
+    if (light && sub == 0) deg[i] = c;
+    __syncthreads();
+
+    const int n_hubs = hub_count;
+    for (int h = 0; h < n_hubs; ++h) {
+        const int64_t ih = row0 + hub_rows[h];
+        const int64_t v = l2g[ih];
+        const int64_t end = rowptr[v + 1];
+        int32_t ch = 0;
+        for (int64_t e = rowptr[v] + threadIdx.x; e < end; e += 256) ch += g2l[colidx[e]] >= 0 ? 1 : 0;
+#pragma unroll
+        for (int d = kWave / 2; d >= 1; d >>= 1) ch += __shfl_xor(ch, d, kWave);
+        if ((threadIdx.x & (kWave - 1)) == 0) wave_part[threadIdx.x / kWave] = ch;
+        __syncthreads();
+        if (threadIdx.x == 0) deg[ih] = wave_part[0] + wave_part[1] + wave_part[2] + wave_part[3];
+        __syncthreads();
+    }
 }
 
 // Order-preserving compaction of each local row into colidx_loc, relabelled.
@@ -185,13 +218,19 @@ __global__ __launch_bounds__(256) void row_fill_kernel(int64_t n_loc, const int3
                                                        int32_t *__restrict__ colidx_loc,
                                                        float *__restrict__ inv_deg)
 {
+    __shared__ int32_t hub_rows[kRowsPerBlock];
+    __shared__ int32_t hub_count;
+    __shared__ int32_t wave_part[256 / kWave];
+    if (threadIdx.x == 0) hub_count = 0;
+    __syncthreads();
+
     const int sub = threadIdx.x % kRowLanes;
     const int group_shift = ((threadIdx.x % kWave) / kRowLanes) * kRowLanes;
-    const int64_t i = int64_t(blockIdx.x) * kRowsPerBlock + threadIdx.x / kRowLanes;
-    const bool live = i < n_loc;
+    const int64_t row0 = int64_t(blockIdx.x) * kRowsPerBlock;
+    const int64_t i = row0 + threadIdx.x / kRowLanes;
     int64_t beg = 0, end = 0;
     int32_t out = 0;
-    if (live) {
+    if (i < n_loc) {
         const int64_t v = l2g[i];
         beg = rowptr[v];
         end = rowptr[v + 1];
@@ -199,6 +238,10 @@ __global__ __launch_bounds__(256) void row_fill_kernel(int64_t n_loc, const int3
         if (sub == 0) {
             const int32_t d = rowptr_loc[i + 1] - out;
             inv_deg[i] = d > 0 ? 1.0f / float(d) : 0.0f;
+        }
+        if (end - beg > kHubRow) {  // left to the whole workgroup below
+            if (sub == 0) hub_rows[atomicAdd(&hub_count, 1)] = int32_t(i - row0);
+            end = beg;
         }
     }
     // Every lane of the wavefront runs the same number of rounds so that the
@@ -217,6 +260,34 @@ __global__ __launch_bounds__(256) void row_fill_kernel(int64_t n_loc, const int3
         const uint32_t mine = uint32_t(ballot >> group_shift) & ((1u << kRowLanes) - 1u);
         if (lid >= 0) colidx_loc[out + __popc(mine & ((1u << sub) - 1u))] = lid;
         out += __popc(mine);
+    }
+    __syncthreads();
+
+    const int n_hubs = hub_count;
+    const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
+    for (int h = 0; h < n_hubs; ++h) {
+        const int64_t ih = row0 + hub_rows[h];
+        const int64_t v = l2g[ih];
+        const int64_t hbeg = rowptr[v], hend = rowptr[v + 1];
+        int32_t hout = rowptr_loc[ih];
+        for (int64_t off = 0; off < hend - hbeg; off += 256) {   // 256 entries per round, order kept
+            const int64_t e = hbeg + off + threadIdx.x;
+            int32_t lid = -1;
+            if (e < hend) lid = g2l[colidx[e]];
+            const uint64_t ballot = __ballot(lid >= 0);
+            if (lane == 0) wave_part[wave] = __popcll(ballot);
+            __syncthreads();
+            int32_t before = 0, total = 0;
+#pragma unroll
+            for (int w = 0; w < 256 / kWave; ++w) {
+                const int32_t t = wave_part[w];
+                if (w < wave) before += t;
+                total += t;
+            }
+            if (lid >= 0) colidx_loc[hout + before + __popcll(ballot & ((1ull << lane) - 1ull))] = lid;
+            hout += total;
+            __syncthreads();
+        }
     }
 }
 

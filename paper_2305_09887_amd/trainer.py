@@ -46,10 +46,12 @@ class LocalTrainer:
             self.load_params(params)
 
         n = max(self.n, 1)
-        self.H = [X] + [torch.empty((n, f), dtype=self.dtype, device=dev)[: self.n] for f in dims[1:]]
+        # activations and their gradients share one row pitch per layer, padded to 16 bytes so that a
+        # width such as 47 still takes the library's vector paths
+        self.H = [X] + [B._padded(self.n, f, self.dtype, dev) for f in dims[1:]]
         self.M = [torch.empty((n, f), dtype=self.dtype, device=dev)[: self.n] for f in dims[:-1]]
         # gradient w.r.t. H[l] for l = 1..L (index l); dH[L] is d(loss)/d(logits)
-        self.dH = [None] + [torch.empty((n, f), dtype=self.dtype, device=dev)[: self.n] for f in dims[1:]]
+        self.dH = [None] + [B._padded(self.n, f, self.dtype, dev) for f in dims[1:]]
         dt = B._feat_dtype(X)
         ws_bytes = max(B.tma_sage_layer_bwd_workspace_bytes(self.n, fi, fo, dt, l > 0)
                        for l, (fi, fo) in enumerate(zip(dims[:-1], dims[1:])))
