@@ -28,9 +28,19 @@ PEAK_MFMA_F32_TFLOPS = 157.3
 WORKLOAD = dict(n_nodes=1_000_000, avg_degree=20, gamma=2.1, K=8, part=0, F=128, hidden=256, classes=47,
                 seeds=dict(graph=11, feat=12, label=13, part=14, weights=15), lr=1e-3)
 
-# HBM bytes per launch of the dominant kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this
-# workload (see profiles/); None until measured.
-MEASURED_TRAFFIC_BYTES = {}
+# HBM bytes per launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this workload
+# (profiles/bench_configs1_hbm_traffic.txt): (FETCH_SIZE * 2.0 + WRITE_SIZE * 1.0) KiB, the factors being what the
+# same counters read for a plain 1 GiB device copy (FETCH_SIZE reports half the bytes read, WRITE_SIZE all written).
+MEASURED_TRAFFIC_BYTES = {
+    "gemm_bwd_weight_128x128": (208632 * 2.0 + 32639) * 1024,
+    "gemm_fwd_128x128": (68300 * 2.0 + 125237) * 1024,
+    "gemm_bwd_data_128x128": (12988 * 2.0 + 250474) * 1024,
+    "gemm_fwd_128x64": (126468 * 2.0 + 23527) * 1024,
+    "gemm_bwd_weight_128x64": (137408 * 2.0 + 11964) * 1024,
+    "spmm_mean_f32_g64x1": (150540 * 2.0 + 125237) * 1024,
+    "spmm_sum_f32_g64x1": (150540 * 2.0 + 125237) * 1024,
+    "spmm_mean_f32_g32x1": (54110 * 2.0 + 62618) * 1024,
+}
 
 
 def kernel_work(name, n, nnz, dims):
@@ -63,6 +73,8 @@ def main():
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="only run a plain 1 GiB device copy (reference for scaling rocprofv3 FETCH_SIZE/WRITE_SIZE)")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on ONE GPU only (trainers are independent; nothing is sharded "
@@ -76,6 +88,15 @@ def main():
     if not torch.cuda.is_available():
         sys.exit("bench.py needs a GPU")
     B.lib()
+    if args.calibrate_copy:
+        src = torch.ones(1 << 28, dtype=torch.float32, device="cuda:0")       # 1 GiB read + 1 GiB written per copy
+        dst = torch.empty_like(src)
+        for _ in range(5):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        print(json.dumps({"calibrate_copy_bytes_read": src.numel() * 4, "calibrate_copy_bytes_written": src.numel() * 4,
+                          "copies": 5}))
+        return
     w = WORKLOAD
     N, K, p = w["n_nodes"], w["K"], w["part"]
     dims = [w["F"], w["hidden"], w["classes"]]
@@ -149,7 +170,7 @@ def main():
         bound = "hbm"
         achieved, peak, unit = work / (avg_ms * 1e-3) / 1e9, PEAK_HBM_GBS, "GB/s"
     roofline = dict(bound=bound, kernel=dominant, achieved=round(achieved, 3), peak=peak, unit=unit,
-                    frac=round(achieved / peak, 4), traffic=MEASURED_TRAFFIC_BYTES.get(dominant),
+                    frac=round(achieved / peak, 4), traffic=MEASURED_TRAFFIC_BYTES.get(dominant.replace("_generic", "")),
                     avg_launch_ms=round(avg_ms, 5), launches=dom[0],
                     algorithmic_work_per_launch=work)
 

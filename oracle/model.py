@@ -26,13 +26,22 @@ def forward(rowptr, colidx, X, params):
     return H, saved
 
 
-def loss_and_grads(rowptr, colidx, X, y, params):
-    """Mean softmax-CE over all local nodes and d(loss)/d(params)."""
+def loss_and_grads(rowptr, colidx, X, y, params, relu_open=None):
+    """Mean softmax-CE over all local nodes and d(loss)/d(params).
+
+    ``relu_open[l]`` (optional, boolean [n, F_{l+1}]) fixes where layer l's ReLU is open instead of
+    deciding it from this fp64 forward pass.  ReLU' is a yes/no decision taken from a floating-point
+    value; a pre-activation within rounding distance of zero can fall on different sides in fp32 and
+    fp64, which changes one whole term of a weight-gradient sum.  A parity test therefore hands the
+    decision taken in the kernel's precision to both sides; the arithmetic is unchanged.
+    """
     logits, saved = forward(rowptr, colidx, X, params)
     loss, d = softmax_ce(logits, y)
     grads = [None] * len(params)
     for l in range(len(params) - 1, -1, -1):
         H, M, Z, act = saved[l]
+        if relu_open is not None and act == ACT_RELU and relu_open[l] is not None:
+            Z = np.where(np.asarray(relu_open[l]), 1.0, -1.0)   # only the sign of Z is used by the backward pass
         Ws, Wn, _ = params[l]
         dWs, dWn, db, dH = sage_layer_bwd(rowptr, colidx, H, M, Z, d, Ws, Wn, act, need_dH=l > 0)
         grads[l] = (dWs, dWn, db)
@@ -40,9 +49,9 @@ def loss_and_grads(rowptr, colidx, X, y, params):
     return loss, grads, logits, saved
 
 
-def train_step(rowptr, colidx, X, y, params, lr):
+def train_step(rowptr, colidx, X, y, params, lr, relu_open=None):
     """One Alg. 2 iteration on the full local subgraph; returns (loss, new params)."""
-    loss, grads, _, _ = loss_and_grads(rowptr, colidx, X, y, params)
+    loss, grads, _, _ = loss_and_grads(rowptr, colidx, X, y, params, relu_open)
     new = [tuple(sgd_step(w, g, lr).reshape(np.shape(w)) for w, g in zip(pl, gl))
            for pl, gl in zip(params, grads)]
     return loss, new

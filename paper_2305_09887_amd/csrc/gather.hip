@@ -10,30 +10,38 @@ namespace tma {
 template <typename W>
 __global__ __launch_bounds__(256) void gather_rows_kernel(int64_t n_loc, const int32_t *__restrict__ l2g,
                                                           const char *__restrict__ src, int64_t src_ld,
-                                                          int64_t words_per_row, char *__restrict__ dst,
-                                                          int64_t dst_ld)
+                                                          int32_t words_per_row, int32_t rows_per_block,
+                                                          char *__restrict__ dst, int64_t dst_ld)
 {
-    const int64_t total = n_loc * words_per_row;
-    const int64_t stride = int64_t(gridDim.x) * 256;
-    for (int64_t idx = int64_t(blockIdx.x) * 256 + threadIdx.x; idx < total; idx += stride) {
-        const int64_t i = idx / words_per_row;
-        const int64_t w = idx - i * words_per_row;
-        const W *s = reinterpret_cast<const W *>(src + int64_t(l2g[i]) * src_ld) + w;
-        W *d = reinterpret_cast<W *>(dst + i * dst_ld) + w;
-        *d = *s;
+    // a block copies rows_per_block consecutive local rows; thread t starts at word t of that run of rows
+    const int64_t row0 = int64_t(blockIdx.x) * rows_per_block;
+    const int32_t block_words = rows_per_block * words_per_row;
+    for (int32_t t = threadIdx.x; t < block_words; t += 256) {
+        const int32_t r = t / words_per_row;
+        const int32_t w = t - r * words_per_row;
+        const int64_t i = row0 + r;
+        if (i < n_loc) {
+            const W *s = reinterpret_cast<const W *>(src + int64_t(l2g[i]) * src_ld) + w;
+            W *d = reinterpret_cast<W *>(dst + i * dst_ld) + w;
+            *d = *s;
+        }
     }
 }
 
 template <typename W>
-static void launch_gather(int64_t n_loc, const int32_t *l2g, const void *src, int64_t src_ld, int64_t row_bytes,
-                          void *dst, int64_t dst_ld, hipStream_t s)
+static int launch_gather(int64_t n_loc, const int32_t *l2g, const void *src, int64_t src_ld, int64_t row_bytes,
+                         void *dst, int64_t dst_ld, hipStream_t s)
 {
     const int64_t words = row_bytes / int64_t(sizeof(W));
-    int64_t blocks = ceil_div(n_loc * words, 256);
-    if (blocks > 256 * 64) blocks = 256 * 64;
+    if (words > (1 << 24)) return fail(TMA_ERR_BAD_SHAPE, "tma_gather_rows: rows longer than 2^24 words");
+    // about 2048 words (8 per thread) per block
+    int64_t rows_per_block = 2048 / words;
+    if (rows_per_block < 1) rows_per_block = 1;
     TMA_TIMED("gather_rows", s);
-    hipLaunchKernelGGL(gather_rows_kernel<W>, dim3(unsigned(blocks)), dim3(256), 0, s, n_loc, l2g,
-                       static_cast<const char *>(src), src_ld, words, static_cast<char *>(dst), dst_ld);
+    hipLaunchKernelGGL(gather_rows_kernel<W>, dim3(unsigned(ceil_div(n_loc, rows_per_block))), dim3(256), 0, s, n_loc,
+                       l2g, static_cast<const char *>(src), src_ld, int32_t(words), int32_t(rows_per_block),
+                       static_cast<char *>(dst), dst_ld);
+    return TMA_OK;
 }
 
 }  // namespace tma
@@ -52,8 +60,10 @@ extern "C" int tma_gather_rows(int64_t n_loc, const int32_t *l2g, const void *sr
         return row_bytes % a == 0 && src_ld_bytes % a == 0 && dst_ld_bytes % a == 0 && aligned(src, size_t(a)) &&
                aligned(dst, size_t(a));
     };
-    if (mult(16)) launch_gather<uint4>(n_loc, l2g, src, src_ld_bytes, row_bytes, dst, dst_ld_bytes, s);
-    else if (mult(4)) launch_gather<uint32_t>(n_loc, l2g, src, src_ld_bytes, row_bytes, dst, dst_ld_bytes, s);
-    else launch_gather<uint8_t>(n_loc, l2g, src, src_ld_bytes, row_bytes, dst, dst_ld_bytes, s);
+    int rc;
+    if (mult(16)) rc = launch_gather<uint4>(n_loc, l2g, src, src_ld_bytes, row_bytes, dst, dst_ld_bytes, s);
+    else if (mult(4)) rc = launch_gather<uint32_t>(n_loc, l2g, src, src_ld_bytes, row_bytes, dst, dst_ld_bytes, s);
+    else rc = launch_gather<uint8_t>(n_loc, l2g, src, src_ld_bytes, row_bytes, dst, dst_ld_bytes, s);
+    if (rc) return rc;
     return check_launch(fn);
 }

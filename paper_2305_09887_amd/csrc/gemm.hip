@@ -526,21 +526,24 @@ __global__ __launch_bounds__(WM *WN * 64, 2) void gemm_f32_kernel(AL a, BL b, Ep
     }
 }
 
-// Second stage of the split reduction, fixed order.  A block owns 64 groups of
-// four consecutive outputs; its four wavefronts each add up a quarter of the
-// splits (16-byte loads, eight in flight), then the quarters are combined in
-// wavefront order through LDS.
+// Second stage of the split reduction, fixed order.  A block owns 16 groups of four
+// consecutive outputs; its 16 lanes-by-split slices each add up 1/16 of the splits (all
+// their 16-byte loads in flight together), then the slices are combined in slice order
+// through LDS.
+constexpr int kRedCols = 16;    // float4 columns per block
+constexpr int kRedSlices = 16;  // split slices per block
+
 __global__ __launch_bounds__(256) void reduce_splits_kernel(const float *__restrict__ partial,
                                                             const float *__restrict__ colsum_partial, int n_splits,
                                                             int F, int N, float *__restrict__ dW_self,
                                                             float *__restrict__ dW_neigh, float *__restrict__ dbias)
 {
-    __shared__ float4 part[4][64];
+    __shared__ float4 part[kRedSlices][kRedCols];
     const int64_t total = int64_t(2) * F * N;      // weight-gradient entries; then N bias entries
     const int64_t total_all = total + N;
-    const int lane = threadIdx.x & 63, q = threadIdx.x >> 6;
-    const int64_t e0 = (int64_t(blockIdx.x) * 64 + lane) * 4;
-    const int per = (n_splits + 3) / 4;
+    const int col = threadIdx.x % kRedCols, q = threadIdx.x / kRedCols;
+    const int64_t e0 = (int64_t(blockIdx.x) * kRedCols + col) * 4;
+    const int per = (n_splits + kRedSlices - 1) / kRedSlices;
     const int s_begin = q * per, s_end = (s_begin + per < n_splits) ? s_begin + per : n_splits;
     float4 s = zero4();
     if (e0 < total_all) {
@@ -563,13 +566,13 @@ __global__ __launch_bounds__(256) void reduce_splits_kernel(const float *__restr
             s = make_float4(t[0], t[1], t[2], t[3]);
         }
     }
-    part[q][lane] = s;
+    part[q][col] = s;
     __syncthreads();
     if (q == 0 && e0 < total_all) {
         float r[4] = {0.0f, 0.0f, 0.0f, 0.0f};
 #pragma unroll
-        for (int w = 0; w < 4; ++w) {
-            const float4 v = part[w][lane];
+        for (int w = 0; w < kRedSlices; ++w) {
+            const float4 v = part[w][col];
             r[0] += v.x; r[1] += v.y; r[2] += v.z; r[3] += v.w;
         }
         const int64_t half = int64_t(F) * N;
@@ -605,7 +608,7 @@ template <bool VA, bool VB>
 static void fwd_dispatch(int64_t n, const float *H, int64_t ldh, const float *M, int F_in, const float *W_self,
                          const float *W_neigh, const FwdEpilogue &e, int F_out, hipStream_t s)
 {
-    constexpr bool V = VA && VB;
+    constexpr bool V = VA;  // the weights are small: their path does not decide the kernel's speed
     CatRows<VA> a{H, ldh, M, F_in, n};
     CatWeights<VB> b{W_self, W_neigh, F_in, F_out};
     const int64_t K = 2 * int64_t(F_in);
@@ -637,7 +640,7 @@ static void bwd_data_dispatch(int64_t n, const float *g, const float *h, int64_t
                               const float *W_self, const float *W_neigh, int F_in, int F_out,
                               const BwdDataEpilogue &e, hipStream_t s)
 {
-    constexpr bool V = VA && VB;
+    constexpr bool V = VA;
     MaskedGrad<true, VA> a{g, h, F_out, ld_next, n, relu};
     CatWeightsT<VB> b{W_self, W_neigh, F_in, F_out};
     const int N = 2 * F_in;
@@ -744,7 +747,7 @@ int launch_sage_gemm_bwd_weight(int64_t n, const void *H, int64_t ldh, const voi
     }
     const int64_t total_all = Mtot * F_out + F_out;
     TMA_TIMED("reduce_splits", stream);
-    hipLaunchKernelGGL(reduce_splits_kernel, dim3(unsigned(ceil_div(total_all, 256))), dim3(256), 0, stream, partial,
+    hipLaunchKernelGGL(reduce_splits_kernel, dim3(unsigned(ceil_div(total_all, 4 * kRedCols))), dim3(256), 0, stream, partial,
                        colsum, F_in > 0 ? w.n_splits : 0, F_in, F_out, dW_self, dW_neigh, dbias);
     return check_launch("sage gemm bwd weight reduce");
 }

@@ -199,7 +199,13 @@ __global__ __launch_bounds__(256) void row_count_kernel(const int64_t *d_n_loc, 
         const int64_t v = l2g[ih];
         const int64_t end = rowptr[v + 1];
         int32_t ch = 0;
-        for (int64_t e = rowptr[v] + threadIdx.x; e < end; e += 256) ch += g2l[colidx[e]] >= 0 ? 1 : 0;
+        int64_t e = rowptr[v] + threadIdx.x;
+        for (; e + 3 * 256 < end; e += 4 * 256) {  // four independent index -> flag chains in flight
+            const int32_t u0 = colidx[e], u1 = colidx[e + 256], u2 = colidx[e + 512], u3 = colidx[e + 768];
+            const int32_t f0 = g2l[u0], f1 = g2l[u1], f2 = g2l[u2], f3 = g2l[u3];
+            ch += (f0 >= 0) + (f1 >= 0) + (f2 >= 0) + (f3 >= 0);
+        }
+        for (; e < end; e += 256) ch += g2l[colidx[e]] >= 0 ? 1 : 0;
 #pragma unroll
         for (int d = kWave / 2; d >= 1; d >>= 1) ch += __shfl_xor(ch, d, kWave);
         if ((threadIdx.x & (kWave - 1)) == 0) wave_part[threadIdx.x / kWave] = ch;
@@ -270,10 +276,13 @@ __global__ __launch_bounds__(256) void row_fill_kernel(int64_t n_loc, const int3
         const int64_t v = l2g[ih];
         const int64_t hbeg = rowptr[v], hend = rowptr[v + 1];
         int32_t hout = rowptr_loc[ih];
+        int32_t lid_next = -1;
+        if (hbeg + threadIdx.x < hend) lid_next = g2l[colidx[hbeg + threadIdx.x]];
         for (int64_t off = 0; off < hend - hbeg; off += 256) {   // 256 entries per round, order kept
-            const int64_t e = hbeg + off + threadIdx.x;
-            int32_t lid = -1;
-            if (e < hend) lid = g2l[colidx[e]];
+            const int32_t lid = lid_next;
+            const int64_t en = hbeg + off + 256 + threadIdx.x;   // next round's entry is fetched during this one
+            lid_next = -1;
+            if (en < hend) lid_next = g2l[colidx[en]];
             const uint64_t ballot = __ballot(lid >= 0);
             if (lane == 0) wave_part[wave] = __popcll(ballot);
             __syncthreads();

@@ -1,0 +1,71 @@
+"""Parity at the benchmark's full size: configs[1] (1M-node Chung-Lu graph, K = 8, part 0, 128-256-47 model),
+through the same calls and launch configuration bench.py times.
+
+The oracle finishes this size in seconds, so everything is compared in full: partition ids and the local CSR
+bit for bit, logits, loss, every gradient and the updated weights to the fp32 tolerance."""
+import numpy as np
+import pytest
+
+import oracle
+from oracle import model as omodel
+from paper_2305_09887_amd import synth
+
+torch = pytest.importorskip("torch")
+pytestmark = pytest.mark.gpu
+
+TOL = 1e-4
+
+
+def _close(got, want, what, tol=TOL):
+    got, want = np.asarray(got, dtype=np.float64), np.asarray(want, dtype=np.float64)
+    assert got.shape == want.shape, what
+    rel = np.linalg.norm((got - want).ravel()) / np.linalg.norm(want.ravel())
+    mx = np.abs(got - want).max() / np.abs(want).max()
+    assert rel <= tol and mx <= tol, f"{what}: rel fro {rel:.2e}, max abs / max {mx:.2e}"
+
+
+def test_configs1_whole_path_against_oracle():
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    from paper_2305_09887_amd import binding as B
+    from paper_2305_09887_amd.trainer import LocalTrainer
+    N, K, p, dims, lr = 1_000_000, 8, 0, [128, 256, 47], 1e-3
+    rowptr, colidx = synth.chung_lu_graph(N, 20, 2.1, seed=11)
+    X, y = synth.features(N, dims[0], seed=12), synth.labels(N, dims[-1], seed=13)
+    params = synth.sage_params(dims, seed=15)
+    d = lambda a: torch.as_tensor(a).cuda()
+
+    part = B.tma_partition(N, K, seed=14)
+    sub = B.tma_induced_subgraph(d(rowptr), d(colidx), part, p)
+    part_o = oracle.partition(N, K, seed=14)
+    sub_o = oracle.induced_subgraph(rowptr, colidx, part_o, p)
+    assert np.array_equal(part.cpu().numpy(), part_o)
+    for k in ("g2l", "l2g", "rowptr", "colidx"):
+        assert np.array_equal(sub[k].cpu().numpy(), sub_o[k]), k
+    assert np.array_equal(sub["inv_deg"].cpu().numpy(), sub_o["inv_deg"].astype(np.float32))
+    deg = np.diff(sub_o["rowptr"])
+    assert deg.max() > 64 and (deg == 0).mean() > 0.2        # hub rows and many isolated nodes are in the case
+
+    Xl = B.tma_gather_rows(sub["l2g"], d(X))
+    yl = B.tma_gather_rows(sub["l2g"], d(y))
+    assert np.array_equal(Xl.cpu().numpy(), X[sub_o["l2g"]]) and np.array_equal(yl.cpu().numpy(), y[sub_o["l2g"]])
+
+    tr = LocalTrainer(sub["rowptr"], sub["colidx"], sub["inv_deg"], Xl, yl, dims, params=params)
+    loss_g = tr.step(lr).item()
+
+    p_o = [tuple(np.asarray(t, dtype=np.float64) for t in l) for l in params]
+    Xo, yo = X[sub_o["l2g"]], y[sub_o["l2g"]]
+    # the ReLU open/closed decision is taken in the kernel's precision (fp32) on both sides
+    relu_open = [tr.H[1].cpu().numpy() > 0, None]
+    loss_o, grads_o, logits_o, saved = omodel.loss_and_grads(sub_o["rowptr"], sub_o["colidx"], Xo, yo, p_o, relu_open)
+    flips = int((relu_open[0] != (saved[0][2] > 0)).sum())
+    assert flips <= 1e-5 * relu_open[0].size, f"{flips} ReLU decisions differ between fp32 and fp64"
+    assert abs(loss_g - loss_o) <= TOL * abs(loss_o)
+    _close(tr.M[0].cpu().numpy(), saved[0][1], "M layer 0")
+    _close(tr.H[1].cpu().numpy(), saved[1][0], "H layer 1")
+    _close(tr.H[2].cpu().numpy(), logits_o, "logits")
+    for l in range(2):
+        for g, w, name in zip(tr.grads[l], grads_o[l], ("dW_self", "dW_neigh", "dbias")):
+            _close(g.cpu().numpy(), w, f"layer {l} {name}")
+    new_o = [tuple(oracle.sgd_step(w, g, lr).reshape(np.shape(w)) for w, g in zip(pl, gl)) for pl, gl in zip(p_o, grads_o)]
+    _close(tr.W.cpu().numpy(), omodel.flatten(new_o), "weights after the step", tol=1e-6)

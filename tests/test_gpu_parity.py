@@ -365,12 +365,13 @@ def test_tiny_config_training_steps_match_oracle(B):
     losses = []
     for step in range(3):
         loss_g = tr.step(lr).item()
-        loss_o, grads_o, _, _ = omodel.loss_and_grads(sub_o["rowptr"], sub_o["colidx"], Xo, yo, p_o)
+        relu_open = [tr.H[1].cpu().numpy() > 0, None]      # the ReLU decision in the kernel's precision, for both sides
+        loss_o, grads_o, _, _ = omodel.loss_and_grads(sub_o["rowptr"], sub_o["colidx"], Xo, yo, p_o, relu_open)
         assert abs(loss_g - loss_o) <= TOL_F32 * abs(loss_o), f"loss at step {step}"
         for l in range(2):
             for g, w, name in zip(tr.grads[l], grads_o[l], ("dW_self", "dW_neigh", "dbias")):
                 assert_close(g.cpu().numpy(), w, what=f"step {step} layer {l} {name}")
-        _, p_o = omodel.train_step(sub_o["rowptr"], sub_o["colidx"], Xo, yo, p_o, lr)
+        _, p_o = omodel.train_step(sub_o["rowptr"], sub_o["colidx"], Xo, yo, p_o, lr, relu_open)
         assert_close(tr.W.cpu().numpy(), omodel.flatten(p_o), what=f"weights after step {step}")
         losses.append(loss_g)
     assert losses[2] < losses[0]
