@@ -1,0 +1,95 @@
+"""Model aggregation on one GPU: K trainers on K streams, parameter averaging every few steps,
+against the oracle running the same schedule (Alg. 1 aggregation + Alg. 2 overwrite)."""
+import numpy as np
+import pytest
+
+import oracle
+from oracle import model as omodel
+from paper_2305_09887_amd import synth
+
+torch = pytest.importorskip("torch")
+pytestmark = pytest.mark.gpu
+
+
+def _setup(B, N, K, dims, seed):
+    from paper_2305_09887_amd.trainer import LocalTrainer
+    rowptr, colidx = synth.chung_lu_graph(N, 16, 2.1, seed=seed)
+    X, y = synth.features(N, dims[0], seed=seed + 1), synth.labels(N, dims[-1], seed=seed + 2)
+    params = synth.sage_params(dims, seed=seed + 4)
+    d = lambda a: torch.as_tensor(a).cuda()
+    d_rp, d_ci, d_X, d_y = d(rowptr), d(colidx), d(X), d(y)
+    part = B.tma_partition(N, K, seed=seed + 3)
+    part_o = oracle.partition(N, K, seed=seed + 3)
+    trainers, locals_o = [], []
+    for p in range(K):
+        sub = B.tma_induced_subgraph(d_rp, d_ci, part, p)
+        Xl, yl = B.tma_gather_rows(sub["l2g"], d_X), B.tma_gather_rows(sub["l2g"], d_y)
+        trainers.append(LocalTrainer(sub["rowptr"], sub["colidx"], sub["inv_deg"], Xl, yl, dims, params=params,
+                                     stream=torch.cuda.Stream()))
+        so = oracle.induced_subgraph(rowptr, colidx, part_o, p)
+        assert np.array_equal(sub["colidx"].cpu().numpy(), so["colidx"])
+        locals_o.append((so["rowptr"], so["colidx"], X[so["l2g"]], y[so["l2g"]]))
+    p_o = [[tuple(np.asarray(t, dtype=np.float64) for t in l) for l in params] for _ in range(K)]
+    return trainers, locals_o, p_o
+
+
+def test_streams_with_periodic_averaging_match_oracle():
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    from paper_2305_09887_amd import binding as B
+    from paper_2305_09887_amd.aggregation import ModelAggregation
+    K, dims, lr, rounds, every = 4, [32, 48, 8], 0.05, 3, 4
+    trainers, locals_o, p_o = _setup(B, 40_000, K, dims, seed=41)
+    agg = ModelAggregation(trainers)
+    hist = agg.run_rounds(rounds, every, lr)
+    agg.synchronize()
+    assert hist == [[every * (r + 1)] * K for r in range(rounds)]
+    for r in range(rounds):
+        for _ in range(every):
+            for i in range(K):
+                _, p_o[i] = omodel.train_step(*locals_o[i], p_o[i], lr)
+        p_o, wg = omodel.aggregate(p_o)
+    want = omodel.flatten(p_o[0])
+    for i, t in enumerate(trainers):
+        got = t.W.cpu().numpy()
+        assert np.linalg.norm(got - want) <= 1e-4 * np.linalg.norm(want), f"trainer {i}"
+        assert torch.equal(t.W, trainers[0].W)                         # every trainer holds the same mean
+    assert np.linalg.norm(agg.W_global.cpu().numpy() - wg) <= 1e-4 * np.linalg.norm(wg)
+
+
+def test_failed_trainer_is_left_out():
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    from paper_2305_09887_amd import binding as B
+    from paper_2305_09887_amd.aggregation import ModelAggregation
+    K, dims, lr = 3, [16, 16, 4], 0.05
+    trainers, locals_o, p_o = _setup(B, 9000, K, dims, seed=51)
+    w_before = trainers[1].W.clone()
+    agg = ModelAggregation(trainers, active_mask=0b101)                # trainer 1 failed to start
+    agg.run_rounds(2, 3, lr)
+    agg.synchronize()
+    assert trainers[1].steps_done == 0 and torch.equal(trainers[1].W, w_before)
+    for r in range(2):
+        for _ in range(3):
+            for i in (0, 2):
+                _, p_o[i] = omodel.train_step(*locals_o[i], p_o[i], lr)
+        p_o, _ = omodel.aggregate(p_o, active_mask=0b101)
+    want = omodel.flatten(p_o[0])
+    assert np.linalg.norm(trainers[0].W.cpu().numpy() - want) <= 1e-4 * np.linalg.norm(want)
+    assert torch.equal(trainers[0].W, trainers[2].W)
+
+
+def test_timed_trigger_runs_and_preserves_the_mean_property():
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    from paper_2305_09887_amd import binding as B
+    from paper_2305_09887_amd.aggregation import ModelAggregation
+    K, dims, lr = 3, [16, 16, 4], 0.05
+    trainers, _, _ = _setup(B, 30_000, K, dims, seed=61)
+    agg = ModelAggregation(trainers)
+    hist = agg.run_timed(dt_int=0.02, dt_train=0.2, lr=lr)
+    agg.synchronize()
+    assert len(hist) >= 2                                              # several aggregation rounds happened
+    assert all(b >= a for r0, r1 in zip(hist, hist[1:]) for a, b in zip(r0, r1))
+    assert all(s > 0 for s in hist[-1])
+    assert all(torch.isfinite(t.W).all() for t in trainers)
