@@ -6,8 +6,9 @@
 // with dZ = dH' (.) act'(Z) formed while loading (chain rule as in the proof of
 // the paper's Thm. 1).
 //
-// fp32 storage uses v_mfma_f32_32x32x2_f32 (fp32 in, fp32 accumulate), so the
-// 1e-4 parity bound holds without any reduced-precision pass.  One kernel
+// All products use v_mfma_f32_32x32x2_f32 (fp32 in, fp32 accumulate), so the
+// fp32 path's 1e-4 parity bound holds without any reduced-precision pass; bf16
+// storage is widened on the way into LDS and rounded once on the way out.  One kernel
 // template serves the three products: operands are described by small "view"
 // structs that present the concatenations [H | M] / [W_self ; W_neigh], the
 // ReLU mask and the transposes as plain A[m][k], B[k][n], and by an epilogue
@@ -40,45 +41,80 @@ constexpr int kXcds = 8;  // MI355X: 8 accelerator dies, workgroups are dealt ro
 __device__ __forceinline__ float4 zero4() { return make_float4(0.0f, 0.0f, 0.0f, 0.0f); }
 
 // ---------------------------------------------------------------------------
+// Storage types.  T = float (fp32 storage) or uint16_t (bf16 storage).  bf16
+// operands are widened to fp32 while they are written to LDS and multiplied
+// with the fp32 MFMA; results are rounded to bf16 (nearest even) on store.
+// ---------------------------------------------------------------------------
+template <typename T>
+struct Pack4;
+template <>
+struct Pack4<float> {
+    typedef float4 Packed;  // 16 bytes
+    static __device__ __forceinline__ Packed load(const float *p) { return *reinterpret_cast<const float4 *>(p); }
+    static __device__ __forceinline__ float4 widen(const Packed &v) { return v; }
+};
+template <>
+struct Pack4<uint16_t> {
+    typedef uint2 Packed;  // 8 bytes
+    static __device__ __forceinline__ Packed load(const uint16_t *p) { return *reinterpret_cast<const uint2 *>(p); }
+    static __device__ __forceinline__ float4 widen(const Packed &v)
+    {
+        return make_float4(__uint_as_float(v.x << 16), __uint_as_float(v.x & 0xFFFF0000u), __uint_as_float(v.y << 16),
+                           __uint_as_float(v.y & 0xFFFF0000u));
+    }
+};
+__device__ __forceinline__ float widen1(const float *p) { return *p; }
+__device__ __forceinline__ float widen1(const uint16_t *p) { return bf16_to_f32(*p); }
+__device__ __forceinline__ void narrow1(float *p, float v) { *p = v; }
+__device__ __forceinline__ void narrow1(uint16_t *p, float v) { *p = f32_to_bf16(v); }
+
+// ---------------------------------------------------------------------------
 // Operand views.  A view presents its operand as X[mn][k].  Per thread and
 // load slot the kernel calls prepare(mn) once per tile (everything that does
 // not depend on k: row pointers, which half of a concatenation, validity), then
 // load(lane, k) once per k-slab, which returns four consecutive elements along
-// the view's contiguous direction (k when kContigK, else mn) as a Raw value,
-// zero outside the operand; resolve(raw) turns it into operand values.  The
-// split lets the kernel issue the loads of the next slab before the MFMAs of
-// the current one and touch the loaded registers (ReLU mask, ragged tails)
-// only afterwards, so no wait on global memory sits in front of the matrix work.
-// V = the vector path is legal (16-byte aligned bases and leading dimensions,
-// inner extents multiple of 4); otherwise element-wise guarded loads.
+// the view's contiguous direction (k when kContigK, else mn) as a Raw value;
+// resolve(raw) turns it into fp32 operand values, zero outside the operand.
+// The split lets the kernel issue the loads of the next slab before the MFMAs of
+// the current one and touch the loaded registers (widening, ReLU mask, ragged
+// tails) only afterwards, so no wait on global memory sits in front of the
+// matrix work.  V = the vector path is legal (bases aligned to four elements,
+// leading dimensions and inner extents multiples of 4); its loads are
+// branch-free: an out-of-range position is clamped to a valid address and the
+// value is discarded by resolve() through the `ok` flag.  Without V the view
+// loads element by element, guarded.
 // ---------------------------------------------------------------------------
-// The vector loads are branch-free: an out-of-range position is clamped to a valid
-// address and the loaded value is discarded by resolve() through the `ok` flag, so
-// that a k-slab's loads, its MFMAs and the LDS traffic form one basic block the
-// instruction scheduler can interleave.
-struct Raw4 {
+template <typename T, bool V>
+struct RawV {
+    typename Pack4<T>::Packed v;
+    bool ok;
+    __device__ __forceinline__ float4 get() const
+    {
+        const float4 f = Pack4<T>::widen(v);
+        return make_float4(ok ? f.x : 0.0f, ok ? f.y : 0.0f, ok ? f.z : 0.0f, ok ? f.w : 0.0f);
+    }
+};
+template <typename T>
+struct RawV<T, false> {  // element-wise path: already fp32, already zero outside
     float4 v;
     bool ok;
+    __device__ __forceinline__ float4 get() const { return v; }
 };
-__device__ __forceinline__ float4 keep_if(const Raw4 &r)
-{
-    return make_float4(r.ok ? r.v.x : 0.0f, r.ok ? r.v.y : 0.0f, r.ok ? r.v.z : 0.0f, r.ok ? r.v.w : 0.0f);
-}
 
-template <bool V>
+template <typename T, bool V>
 struct CatRows {  // A[m][k] = k < F ? H[m][k] : M[m][k-F]          (contiguous along k)
     static constexpr bool kContigK = true;
-    typedef Raw4 Raw;
+    typedef RawV<T, V> Raw;
     struct Lane {
-        const float *p0, *p1;  // row pointers such that element k is p0[k] (k < F) or p1[k] (k >= F)
+        const T *p0, *p1;  // row pointers such that element k is p0[k] (k < F) or p1[k] (k >= F)
         bool ok;
     };
-    const float *H;
+    const T *H;
     int64_t ldh;
-    const float *Mx;
+    const T *Mx;
     int F;
     int64_t rows;
-    static __device__ __forceinline__ float4 resolve(const Raw &r) { return keep_if(r); }
+    static __device__ __forceinline__ float4 resolve(const Raw &r) { return r.get(); }
     __device__ __forceinline__ Lane prepare(int64_t m) const
     {
         const int64_t mm = m < rows ? m : 0;
@@ -86,16 +122,16 @@ struct CatRows {  // A[m][k] = k < F ? H[m][k] : M[m][k-F]          (contiguous 
     }
     __device__ __forceinline__ float at(const Lane &l, int k) const
     {
-        return k < F ? l.p0[k] : (k < 2 * F ? l.p1[k] : 0.0f);
+        return k < F ? widen1(l.p0 + k) : (k < 2 * F ? widen1(l.p1 + k) : 0.0f);
     }
     __device__ __forceinline__ Raw load(const Lane &l, int64_t k64) const
     {
         const int k = int(k64);
         Raw r;
         r.ok = l.ok && k < 2 * F;
-        if (V) {
+        if constexpr (V) {
             const int kc = k < 2 * F ? k : 0;
-            r.v = *reinterpret_cast<const float4 *>((kc < F ? l.p0 : l.p1) + kc);
+            r.v = Pack4<T>::load((kc < F ? l.p0 : l.p1) + kc);
         } else {
             r.v = r.ok ? make_float4(at(l, k), at(l, k + 1), at(l, k + 2), at(l, k + 3)) : zero4();
         }
@@ -103,22 +139,22 @@ struct CatRows {  // A[m][k] = k < F ? H[m][k] : M[m][k-F]          (contiguous 
     }
 };
 
-template <bool V>
+template <typename T, bool V>
 struct CatRowsT {  // A[m][k] = (m < F ? H[k][m] : M[k][m-F])          (contiguous along m); k = node
     static constexpr bool kContigK = false;
-    typedef Raw4 Raw;
+    typedef RawV<T, V> Raw;
     struct Lane {
-        const float *p;  // column pointer: element of node k is p[k * ld]
+        const T *p;  // column pointer: element of node k is p[k * ld]
         int64_t ld;
         int m;
         bool ok;
     };
-    const float *H;
+    const T *H;
     int64_t ldh;
-    const float *Mx;
+    const T *Mx;
     int F;
     int64_t rows;
-    static __device__ __forceinline__ float4 resolve(const Raw &r) { return keep_if(r); }
+    static __device__ __forceinline__ float4 resolve(const Raw &r) { return r.get(); }
     __device__ __forceinline__ Lane prepare(int64_t m64) const
     {
         const int m = int(m64);
@@ -127,16 +163,16 @@ struct CatRowsT {  // A[m][k] = (m < F ? H[k][m] : M[k][m-F])          (contiguo
     }
     __device__ __forceinline__ float at(int64_t node, int m) const
     {
-        if (m < F) return H[node * ldh + m];
-        if (m < 2 * F) return Mx[node * int64_t(F) + (m - F)];
+        if (m < F) return widen1(H + node * ldh + m);
+        if (m < 2 * F) return widen1(Mx + node * int64_t(F) + (m - F));
         return 0.0f;
     }
     __device__ __forceinline__ Raw load(const Lane &l, int64_t node) const
     {
         Raw r;
         r.ok = l.ok && node < rows;
-        if (V) {
-            r.v = *reinterpret_cast<const float4 *>(l.p + (node < rows ? node : 0) * l.ld);
+        if constexpr (V) {
+            r.v = Pack4<T>::load(l.p + (node < rows ? node : 0) * l.ld);
         } else {
             r.v = r.ok ? make_float4(at(node, l.m), at(node, l.m + 1), at(node, l.m + 2), at(node, l.m + 3)) : zero4();
         }
@@ -145,9 +181,9 @@ struct CatRowsT {  // A[m][k] = (m < F ? H[k][m] : M[k][m-F])          (contiguo
 };
 
 template <bool V>
-struct CatWeights {  // B[k][n] = k < F ? W_self[k][n] : W_neigh[k-F][n]  (contiguous along n)
+struct CatWeights {  // B[k][n] = k < F ? W_self[k][n] : W_neigh[k-F][n]  (contiguous along n); fp32 master weights
     static constexpr bool kContigK = false;
-    typedef Raw4 Raw;
+    typedef RawV<float, V> Raw;
     struct Lane {
         int n;
     };
@@ -155,7 +191,7 @@ struct CatWeights {  // B[k][n] = k < F ? W_self[k][n] : W_neigh[k-F][n]  (conti
     const float *Wn;
     int F;
     int N;
-    static __device__ __forceinline__ float4 resolve(const Raw &r) { return keep_if(r); }
+    static __device__ __forceinline__ float4 resolve(const Raw &r) { return r.get(); }
     __device__ __forceinline__ Lane prepare(int64_t n) const { return Lane{int(n)}; }
     __device__ __forceinline__ Raw load(const Lane &l, int64_t k64) const
     {
@@ -164,7 +200,7 @@ struct CatWeights {  // B[k][n] = k < F ? W_self[k][n] : W_neigh[k-F][n]  (conti
         r.ok = k < 2 * F && n < N;
         const int kc = k < 2 * F ? k : 0;
         const float *row = kc < F ? Ws + int64_t(kc) * N : Wn + int64_t(kc - F) * N;
-        if (V) {
+        if constexpr (V) {
             r.v = *reinterpret_cast<const float4 *>(row + (n < N ? n : 0));
         } else if (r.ok) {
             r.v.x = row[n];
@@ -181,7 +217,7 @@ struct CatWeights {  // B[k][n] = k < F ? W_self[k][n] : W_neigh[k-F][n]  (conti
 template <bool V>
 struct CatWeightsT {  // B[k][n] = n < F ? W_self[n][k] : W_neigh[n-F][k]  (contiguous along k); k = output feature
     static constexpr bool kContigK = true;
-    typedef Raw4 Raw;
+    typedef RawV<float, V> Raw;
     struct Lane {
         const float *row;
         bool ok;
@@ -190,7 +226,7 @@ struct CatWeightsT {  // B[k][n] = n < F ? W_self[n][k] : W_neigh[n-F][k]  (cont
     const float *Wn;
     int F;
     int Fo;
-    static __device__ __forceinline__ float4 resolve(const Raw &r) { return keep_if(r); }
+    static __device__ __forceinline__ float4 resolve(const Raw &r) { return r.get(); }
     __device__ __forceinline__ Lane prepare(int64_t n64) const
     {
         const int n = int(n64);
@@ -202,7 +238,7 @@ struct CatWeightsT {  // B[k][n] = n < F ? W_self[n][k] : W_neigh[n-F][k]  (cont
         const int k = int(k64);
         Raw r;
         r.ok = l.ok && k < Fo;
-        if (V) {
+        if constexpr (V) {
             r.v = *reinterpret_cast<const float4 *>(l.row + (k < Fo ? k : 0));
         } else if (r.ok) {
             r.v.x = l.row[k];
@@ -220,27 +256,44 @@ struct CatWeightsT {  // B[k][n] = n < F ? W_self[n][k] : W_neigh[n-F][k]  (cont
 // kAsA: used as A[m=node][k=o] (contiguous along k).  Otherwise as B[k=node][n=o] (contiguous along n).
 // The vector path may read up to three padding elements past Fo inside a row (ld is a multiple of 4);
 // resolve() discards them.
-template <bool kAsA, bool V>
+template <bool kAsA, typename T, bool V, bool kRelu>
 struct MaskedGrad {
     static constexpr bool kContigK = kAsA;
-    struct Raw {
-        float4 g, h;
+    typedef typename std::conditional<V, typename Pack4<T>::Packed, float4>::type Quad;
+    struct RawRelu {
+        Quad g, h;
         int nv;  // leading elements that are inside the operand (<= 0: none)
     };
+    struct RawPlain {
+        Quad g;
+        int nv;
+    };
+    typedef typename std::conditional<kRelu, RawRelu, RawPlain>::type Raw;
     struct Lane {
         int64_t off;  // kAsA: node * ld ; else: o
         bool ok;
     };
-    const float *dHn;
-    const float *Hn;  // forward output; read only when relu
+    const T *dHn;
+    const T *Hn;  // forward output; read only with ReLU
     int Fo;
     int64_t ld;
     int64_t rows;
-    bool relu;
+    static __device__ __forceinline__ float4 quad(const Quad &q)
+    {
+        if constexpr (V) return Pack4<T>::widen(q);
+        else return q;
+    }
     static __device__ __forceinline__ float4 resolve(const Raw &r)
     {
-        return make_float4((r.nv > 0 && r.h.x > 0.0f) ? r.g.x : 0.0f, (r.nv > 1 && r.h.y > 0.0f) ? r.g.y : 0.0f,
-                           (r.nv > 2 && r.h.z > 0.0f) ? r.g.z : 0.0f, (r.nv > 3 && r.h.w > 0.0f) ? r.g.w : 0.0f);
+        const float4 g = quad(r.g);
+        if constexpr (kRelu) {
+            const float4 h = quad(r.h);
+            return make_float4((r.nv > 0 && h.x > 0.0f) ? g.x : 0.0f, (r.nv > 1 && h.y > 0.0f) ? g.y : 0.0f,
+                               (r.nv > 2 && h.z > 0.0f) ? g.z : 0.0f, (r.nv > 3 && h.w > 0.0f) ? g.w : 0.0f);
+        } else {
+            return make_float4(r.nv > 0 ? g.x : 0.0f, r.nv > 1 ? g.y : 0.0f, r.nv > 2 ? g.z : 0.0f,
+                               r.nv > 3 ? g.w : 0.0f);
+        }
     }
     __device__ __forceinline__ Lane prepare(int64_t mn) const
     {
@@ -250,28 +303,29 @@ struct MaskedGrad {
     __device__ __forceinline__ Raw load(const Lane &l, int64_t k) const
     {
         Raw r;
-        r.h = make_float4(1.0f, 1.0f, 1.0f, 1.0f);  // identity activation: mask always open
         const int o = int(kAsA ? k : l.off);
         const bool inside = kAsA ? (l.ok && o < Fo) : (l.ok && k < rows);
         r.nv = inside ? Fo - o : 0;
-        if (V) {
+        if constexpr (V) {
             const int64_t e = kAsA ? l.off + (o < Fo ? o : 0) : (k < rows ? k : 0) * ld + o;
-            r.g = *reinterpret_cast<const float4 *>(dHn + e);
-            if (relu) r.h = *reinterpret_cast<const float4 *>(Hn + e);
-            return r;
-        }
-        r.g = zero4();
-        if (!inside) return r;
-        const int64_t e = kAsA ? l.off + o : k * ld + o;
-        r.g.x = dHn[e];
-        if (o + 1 < Fo) r.g.y = dHn[e + 1];
-        if (o + 2 < Fo) r.g.z = dHn[e + 2];
-        if (o + 3 < Fo) r.g.w = dHn[e + 3];
-        if (relu) {
-            r.h.x = Hn[e];
-            if (o + 1 < Fo) r.h.y = Hn[e + 1];
-            if (o + 2 < Fo) r.h.z = Hn[e + 2];
-            if (o + 3 < Fo) r.h.w = Hn[e + 3];
+            r.g = Pack4<T>::load(dHn + e);
+            if constexpr (kRelu) r.h = Pack4<T>::load(Hn + e);
+        } else {
+            r.g = zero4();
+            if constexpr (kRelu) r.h = zero4();
+            if (inside) {
+                const int64_t e = kAsA ? l.off + o : k * ld + o;
+                r.g.x = widen1(dHn + e);
+                if (o + 1 < Fo) r.g.y = widen1(dHn + e + 1);
+                if (o + 2 < Fo) r.g.z = widen1(dHn + e + 2);
+                if (o + 3 < Fo) r.g.w = widen1(dHn + e + 3);
+                if constexpr (kRelu) {
+                    r.h.x = widen1(Hn + e);
+                    if (o + 1 < Fo) r.h.y = widen1(Hn + e + 1);
+                    if (o + 2 < Fo) r.h.z = widen1(Hn + e + 2);
+                    if (o + 3 < Fo) r.h.w = widen1(Hn + e + 3);
+                }
+            }
         }
         return r;
     }
@@ -281,9 +335,10 @@ struct MaskedGrad {
 // Epilogues.  col_aux / row_aux are fetched once per tile column / row with a
 // clamped (always valid) index; value() is pure arithmetic on registers.
 // ---------------------------------------------------------------------------
+template <typename T>
 struct FwdEpilogue {  // H' = act(acc + b)
     static constexpr bool kColAux = true, kRowAux = false;
-    float *out;
+    T *out;
     int64_t ld;
     const float *bias;
     bool relu;
@@ -295,14 +350,15 @@ struct FwdEpilogue {  // H' = act(acc + b)
         if (relu) v = v > 0.0f ? v : 0.0f;
         return v;
     }
-    __device__ __forceinline__ void store(int64_t row, int col, float v, int) const { out[row * ld + col] = v; }
+    __device__ __forceinline__ void store(int64_t row, int col, float v, int) const { narrow1(out + row * ld + col, v); }
 };
 
+template <typename T>
 struct BwdDataEpilogue {  // columns [0,F): dH_self (leading dimension ldh) ; [F,2F): inv_deg[row] * dM (dense)
     static constexpr bool kColAux = false, kRowAux = true;
-    float *dH;
+    T *dH;
     int64_t ldh;
-    float *dMs;
+    T *dMs;
     const float *inv_deg;
     int F;
     __device__ __forceinline__ float col_aux(int) const { return 0.0f; }
@@ -310,8 +366,8 @@ struct BwdDataEpilogue {  // columns [0,F): dH_self (leading dimension ldh) ; [F
     __device__ __forceinline__ float value(float v, float, float raux, int col) const { return col < F ? v : v * raux; }
     __device__ __forceinline__ void store(int64_t row, int col, float v, int) const
     {
-        if (col < F) dH[row * ldh + col] = v;
-        else dMs[row * F + (col - F)] = v;
+        if (col < F) narrow1(dH + row * ldh + col, v);
+        else narrow1(dMs + row * F + (col - F), v);
     }
 };
 
@@ -586,7 +642,8 @@ __global__ __launch_bounds__(256) void reduce_splits_kernel(const float *__restr
     }
 }
 
-static bool vec4_ok(const void *p, int64_t ld) { return aligned(p, 16) && ld % 4 == 0; }
+template <typename T>
+static bool vec4_ok(const T *p, int64_t ld) { return aligned(p, 4 * sizeof(T)) && ld % 4 == 0; }
 
 template <int BM, int BN, int BK, int WM, int WN, bool kColSum, class AL, class BL, class Epi>
 static void launch_gemm(const char *name, const AL &a, const BL &b, const Epi &e, int64_t M, int N, int64_t K,
@@ -603,55 +660,99 @@ static void launch_gemm(const char *name, const AL &a, const BL &b, const Epi &e
                        dim3(WM * WN * 64), 0, s, a, b, e, M, N, K, k_per_split, n_tiles, tiles, total, colsum_partial);
 }
 
-// ---- forward ----------------------------------------------------------------
-template <bool VA, bool VB>
-static void fwd_dispatch(int64_t n, const float *H, int64_t ldh, const float *M, int F_in, const float *W_self,
-                         const float *W_neigh, const FwdEpilogue &e, int F_out, hipStream_t s)
+// Kernel names for the timing hook: <what>_<tile>[_bf16][_generic]; "generic" = a streaming operand is
+// on the element-wise path (the weights are small: their path does not decide the kernel's speed).
+template <typename T>
+static const char *kname(const char *f32_vec, const char *f32_gen, const char *bf16_vec, const char *bf16_gen, bool vec)
 {
-    constexpr bool V = VA;  // the weights are small: their path does not decide the kernel's speed
-    CatRows<VA> a{H, ldh, M, F_in, n};
+    if (sizeof(T) == 4) return vec ? f32_vec : f32_gen;
+    return vec ? bf16_vec : bf16_gen;
+}
+
+// ---- forward ----------------------------------------------------------------
+template <typename T, bool VA, bool VB>
+static void fwd_dispatch(int64_t n, const T *H, int64_t ldh, const T *M, int F_in, const float *W_self,
+                         const float *W_neigh, const FwdEpilogue<T> &e, int F_out, hipStream_t s)
+{
+    CatRows<T, VA> a{H, ldh, M, F_in, n};
     CatWeights<VB> b{W_self, W_neigh, F_in, F_out};
     const int64_t K = 2 * int64_t(F_in);
     const int64_t kps = int64_t(round_up(size_t(K), 32));
-    if (F_out <= 64) launch_gemm<128, 64, 32, 4, 1, false>(V ? "gemm_fwd_128x64" : "gemm_fwd_128x64_generic", a, b, e, n, F_out, K, kps, 1, nullptr, s);
-    else launch_gemm<128, 128, 32, 2, 2, false>(V ? "gemm_fwd_128x128" : "gemm_fwd_128x128_generic", a, b, e, n, F_out, K, kps, 1, nullptr, s);
+    if (F_out <= 64)
+        launch_gemm<128, 64, 32, 4, 1, false>(kname<T>("gemm_fwd_128x64", "gemm_fwd_128x64_generic", "gemm_fwd_128x64_bf16", "gemm_fwd_128x64_bf16_generic", VA),
+                                              a, b, e, n, F_out, K, kps, 1, nullptr, s);
+    else
+        launch_gemm<128, 128, 32, 2, 2, false>(kname<T>("gemm_fwd_128x128", "gemm_fwd_128x128_generic", "gemm_fwd_128x128_bf16", "gemm_fwd_128x128_bf16_generic", VA),
+                                               a, b, e, n, F_out, K, kps, 1, nullptr, s);
+}
+
+template <typename T>
+static int fwd_typed(int64_t n, const T *H, int64_t ldh, const T *M, int32_t F_in, const float *W_self,
+                     const float *W_neigh, const float *bias, int32_t F_out, int32_t act, T *Hnext, int64_t ld_next,
+                     hipStream_t stream)
+{
+    FwdEpilogue<T> e{Hnext, ld_next, bias, act == TMA_ACT_RELU};
+    const bool va = vec4_ok(H, ldh) && vec4_ok(M, F_in);
+    const bool vb = vec4_ok(W_self, F_out) && vec4_ok(W_neigh, F_out);
+    if (va && vb) fwd_dispatch<T, true, true>(n, H, ldh, M, F_in, W_self, W_neigh, e, F_out, stream);
+    else if (va) fwd_dispatch<T, true, false>(n, H, ldh, M, F_in, W_self, W_neigh, e, F_out, stream);
+    else if (vb) fwd_dispatch<T, false, true>(n, H, ldh, M, F_in, W_self, W_neigh, e, F_out, stream);
+    else fwd_dispatch<T, false, false>(n, H, ldh, M, F_in, W_self, W_neigh, e, F_out, stream);
+    return check_launch("sage gemm fwd");
 }
 
 int launch_sage_gemm_fwd(int64_t n, const void *H, int64_t ldh, const void *M, int32_t F_in, const float *W_self,
                          const float *W_neigh, const float *bias, int32_t F_out, int32_t act, int32_t dtype,
                          void *Hnext, int64_t ld_next, hipStream_t stream)
 {
-    if (dtype != TMA_F32) return fail(TMA_ERR_UNSUPPORTED_DTYPE, "sage gemm fwd: dtype %d not built yet", dtype);
     if (n == 0 || F_out == 0) return TMA_OK;
-    const float *Hf = static_cast<const float *>(H), *Mf = static_cast<const float *>(M);
-    FwdEpilogue e{static_cast<float *>(Hnext), ld_next, bias, act == TMA_ACT_RELU};
-    const bool va = vec4_ok(Hf, ldh) && vec4_ok(Mf, F_in);
-    const bool vb = vec4_ok(W_self, F_out) && vec4_ok(W_neigh, F_out);
-    if (va && vb) fwd_dispatch<true, true>(n, Hf, ldh, Mf, F_in, W_self, W_neigh, e, F_out, stream);
-    else if (va) fwd_dispatch<true, false>(n, Hf, ldh, Mf, F_in, W_self, W_neigh, e, F_out, stream);
-    else if (vb) fwd_dispatch<false, true>(n, Hf, ldh, Mf, F_in, W_self, W_neigh, e, F_out, stream);
-    else fwd_dispatch<false, false>(n, Hf, ldh, Mf, F_in, W_self, W_neigh, e, F_out, stream);
-    return check_launch("sage gemm fwd");
+    if (dtype == TMA_F32)
+        return fwd_typed<float>(n, static_cast<const float *>(H), ldh, static_cast<const float *>(M), F_in, W_self,
+                                W_neigh, bias, F_out, act, static_cast<float *>(Hnext), ld_next, stream);
+    if (dtype == TMA_BF16)
+        return fwd_typed<uint16_t>(n, static_cast<const uint16_t *>(H), ldh, static_cast<const uint16_t *>(M), F_in,
+                                   W_self, W_neigh, bias, F_out, act, static_cast<uint16_t *>(Hnext), ld_next, stream);
+    return fail(TMA_ERR_UNSUPPORTED_DTYPE, "sage gemm fwd: dtype %d", dtype);
 }
 
 // ---- backward: data ---------------------------------------------------------
-template <bool VA, bool VB>
-static void bwd_data_dispatch(int64_t n, const float *g, const float *h, int64_t ld_next, bool relu,
-                              const float *W_self, const float *W_neigh, int F_in, int F_out,
-                              const BwdDataEpilogue &e, hipStream_t s)
+template <typename T, bool VA, bool VB, bool kRelu>
+static void bwd_data_dispatch(int64_t n, const T *g, const T *h, int64_t ld_next, const float *W_self,
+                              const float *W_neigh, int F_in, int F_out, const BwdDataEpilogue<T> &e, hipStream_t s)
 {
-    constexpr bool V = VA;
-    MaskedGrad<true, VA> a{g, h, F_out, ld_next, n, relu};
+    MaskedGrad<true, T, VA, kRelu> a{g, h, F_out, ld_next, n};
     CatWeightsT<VB> b{W_self, W_neigh, F_in, F_out};
     const int N = 2 * F_in;
     const int64_t K = F_out;
+    const char *name = kname<T>("gemm_bwd_data_128x128", "gemm_bwd_data_128x128_generic", "gemm_bwd_data_128x128_bf16",
+                                "gemm_bwd_data_128x128_bf16_generic", VA);
     if (K <= 48) {  // short reduction: 16-wide slabs waste less of the last one
         const int64_t kps = int64_t(round_up(size_t(K), 16));
-        launch_gemm<128, 128, 16, 2, 2, false>(V ? "gemm_bwd_data_128x128" : "gemm_bwd_data_128x128_generic", a, b, e, n, N, K, kps, 1, nullptr, s);
+        launch_gemm<128, 128, 16, 2, 2, false>(name, a, b, e, n, N, K, kps, 1, nullptr, s);
     } else {
         const int64_t kps = int64_t(round_up(size_t(K), 32));
-        launch_gemm<128, 128, 32, 2, 2, false>(V ? "gemm_bwd_data_128x128" : "gemm_bwd_data_128x128_generic", a, b, e, n, N, K, kps, 1, nullptr, s);
+        launch_gemm<128, 128, 32, 2, 2, false>(name, a, b, e, n, N, K, kps, 1, nullptr, s);
     }
+}
+
+template <typename T>
+static int bwd_data_typed(int64_t n, const T *g, const T *h, int64_t ld_next, const float *inv_deg,
+                          const float *W_self, const float *W_neigh, int32_t F_in, int32_t F_out, int32_t act,
+                          T *dH_self_out, int64_t ldh, T *dM_scaled_out, hipStream_t stream)
+{
+    const bool relu = act == TMA_ACT_RELU;
+    BwdDataEpilogue<T> e{dH_self_out, ldh, dM_scaled_out, inv_deg, F_in};
+    const bool va = vec4_ok(g, ld_next) && (!relu || vec4_ok(h, ld_next));
+    const bool vb = vec4_ok(W_self, F_out) && vec4_ok(W_neigh, F_out);
+#define TMA_BWD_DATA(VA_, VB_)                                                                                    \
+    (relu ? bwd_data_dispatch<T, VA_, VB_, true>(n, g, h, ld_next, W_self, W_neigh, F_in, F_out, e, stream)       \
+          : bwd_data_dispatch<T, VA_, VB_, false>(n, g, h, ld_next, W_self, W_neigh, F_in, F_out, e, stream))
+    if (va && vb) TMA_BWD_DATA(true, true);
+    else if (va) TMA_BWD_DATA(true, false);
+    else if (vb) TMA_BWD_DATA(false, true);
+    else TMA_BWD_DATA(false, false);
+#undef TMA_BWD_DATA
+    return check_launch("sage gemm bwd data");
 }
 
 int launch_sage_gemm_bwd_data(int64_t n, const void *dHnext, const void *Hnext, int64_t ld_next,
@@ -659,18 +760,17 @@ int launch_sage_gemm_bwd_data(int64_t n, const void *dHnext, const void *Hnext, 
                               int32_t F_out, int32_t act, int32_t dtype, void *dH_self_out, int64_t ldh,
                               void *dM_scaled_out, hipStream_t stream)
 {
-    if (dtype != TMA_F32) return fail(TMA_ERR_UNSUPPORTED_DTYPE, "sage gemm bwd: dtype %d not built yet", dtype);
     if (n == 0 || F_in == 0) return TMA_OK;
-    const float *g = static_cast<const float *>(dHnext), *h = static_cast<const float *>(Hnext);
-    const bool relu = act == TMA_ACT_RELU;
-    BwdDataEpilogue e{static_cast<float *>(dH_self_out), ldh, static_cast<float *>(dM_scaled_out), inv_deg, F_in};
-    const bool va = vec4_ok(g, ld_next) && (!relu || vec4_ok(h, ld_next));
-    const bool vb = vec4_ok(W_self, F_out) && vec4_ok(W_neigh, F_out);
-    if (va && vb) bwd_data_dispatch<true, true>(n, g, h, ld_next, relu, W_self, W_neigh, F_in, F_out, e, stream);
-    else if (va) bwd_data_dispatch<true, false>(n, g, h, ld_next, relu, W_self, W_neigh, F_in, F_out, e, stream);
-    else if (vb) bwd_data_dispatch<false, true>(n, g, h, ld_next, relu, W_self, W_neigh, F_in, F_out, e, stream);
-    else bwd_data_dispatch<false, false>(n, g, h, ld_next, relu, W_self, W_neigh, F_in, F_out, e, stream);
-    return check_launch("sage gemm bwd data");
+    if (dtype == TMA_F32)
+        return bwd_data_typed<float>(n, static_cast<const float *>(dHnext), static_cast<const float *>(Hnext), ld_next,
+                                     inv_deg, W_self, W_neigh, F_in, F_out, act, static_cast<float *>(dH_self_out),
+                                     ldh, static_cast<float *>(dM_scaled_out), stream);
+    if (dtype == TMA_BF16)
+        return bwd_data_typed<uint16_t>(n, static_cast<const uint16_t *>(dHnext), static_cast<const uint16_t *>(Hnext),
+                                        ld_next, inv_deg, W_self, W_neigh, F_in, F_out, act,
+                                        static_cast<uint16_t *>(dH_self_out), ldh,
+                                        static_cast<uint16_t *>(dM_scaled_out), stream);
+    return fail(TMA_ERR_UNSUPPORTED_DTYPE, "sage gemm bwd: dtype %d", dtype);
 }
 
 // ---- backward: weights ------------------------------------------------------
@@ -702,28 +802,48 @@ size_t sage_gemm_bwd_weight_workspace_bytes(int64_t n, int32_t F_in, int32_t F_o
     return w.partial_bytes + w.colsum_bytes;
 }
 
-template <bool VA, bool VB>
-static void bwd_weight_dispatch(int64_t n, const float *H, int64_t ldh, const float *M, const float *g,
-                                const float *h, int64_t ld_next, bool relu, int F_in, int F_out,
-                                const WeightSplit &w, const SplitEpilogue &e, float *colsum, hipStream_t s)
+template <typename T, bool VA, bool VB, bool kRelu>
+static void bwd_weight_dispatch(int64_t n, const T *H, int64_t ldh, const T *M, const T *g, const T *h,
+                                int64_t ld_next, int F_in, int F_out, const WeightSplit &w, const SplitEpilogue &e,
+                                float *colsum, hipStream_t s)
 {
     constexpr bool V = VA && VB;
-    CatRowsT<VA> a{H, ldh, M, F_in, n};
-    MaskedGrad<false, VB> b{g, h, F_out, ld_next, n, relu};
+    CatRowsT<T, VA> a{H, ldh, M, F_in, n};
+    MaskedGrad<false, T, VB, kRelu> b{g, h, F_out, ld_next, n};
     const int64_t Mtot = 2 * int64_t(F_in);
     if (F_out <= 64)
-        launch_gemm<128, 64, 32, 4, 1, true>(V ? "gemm_bwd_weight_128x64" : "gemm_bwd_weight_128x64_generic", a, b, e, Mtot, F_out, n, w.k_per_split, w.n_splits, colsum, s);
+        launch_gemm<128, 64, 32, 4, 1, true>(kname<T>("gemm_bwd_weight_128x64", "gemm_bwd_weight_128x64_generic", "gemm_bwd_weight_128x64_bf16", "gemm_bwd_weight_128x64_bf16_generic", V),
+                                             a, b, e, Mtot, F_out, n, w.k_per_split, w.n_splits, colsum, s);
     else
-        launch_gemm<128, 128, 32, 2, 2, true>(V ? "gemm_bwd_weight_128x128" : "gemm_bwd_weight_128x128_generic", a, b, e, Mtot, F_out, n, w.k_per_split, w.n_splits, colsum, s);
+        launch_gemm<128, 128, 32, 2, 2, true>(kname<T>("gemm_bwd_weight_128x128", "gemm_bwd_weight_128x128_generic", "gemm_bwd_weight_128x128_bf16", "gemm_bwd_weight_128x128_bf16_generic", V),
+                                              a, b, e, Mtot, F_out, n, w.k_per_split, w.n_splits, colsum, s);
+}
+
+template <typename T>
+static int bwd_weight_typed(int64_t n, const T *H, int64_t ldh, const T *M, const T *g, const T *h, int64_t ld_next,
+                            int32_t F_in, int32_t F_out, int32_t act, const WeightSplit &w, const SplitEpilogue &e,
+                            float *colsum, hipStream_t stream)
+{
+    const bool relu = act == TMA_ACT_RELU;
+    const bool va = vec4_ok(H, ldh) && vec4_ok(M, F_in);
+    const bool vb = vec4_ok(g, ld_next) && (!relu || vec4_ok(h, ld_next));
+#define TMA_BWD_WEIGHT(VA_, VB_)                                                                                           \
+    (relu ? bwd_weight_dispatch<T, VA_, VB_, true>(n, H, ldh, M, g, h, ld_next, F_in, F_out, w, e, colsum, stream)         \
+          : bwd_weight_dispatch<T, VA_, VB_, false>(n, H, ldh, M, g, h, ld_next, F_in, F_out, w, e, colsum, stream))
+    if (va && vb) TMA_BWD_WEIGHT(true, true);
+    else if (va) TMA_BWD_WEIGHT(true, false);
+    else if (vb) TMA_BWD_WEIGHT(false, true);
+    else TMA_BWD_WEIGHT(false, false);
+#undef TMA_BWD_WEIGHT
+    return check_launch("sage gemm bwd weight");
 }
 
 int launch_sage_gemm_bwd_weight(int64_t n, const void *H, int64_t ldh, const void *M, const void *dHnext,
                                 const void *Hnext, int64_t ld_next, int32_t F_in, int32_t F_out, int32_t act,
-                                int32_t dtype,
-                                float *dW_self, float *dW_neigh, float *dbias, void *ws, size_t ws_bytes,
+                                int32_t dtype, float *dW_self, float *dW_neigh, float *dbias, void *ws, size_t ws_bytes,
                                 hipStream_t stream)
 {
-    if (dtype != TMA_F32) return fail(TMA_ERR_UNSUPPORTED_DTYPE, "sage gemm bwd: dtype %d not built yet", dtype);
+    if (dtype != TMA_F32 && dtype != TMA_BF16) return fail(TMA_ERR_UNSUPPORTED_DTYPE, "sage gemm bwd: dtype %d", dtype);
     if (F_out == 0) return TMA_OK;
     const WeightSplit w = plan_weight_split(n, F_in, F_out);
     if (ws_bytes < w.partial_bytes + w.colsum_bytes)
@@ -731,24 +851,25 @@ int launch_sage_gemm_bwd_weight(int64_t n, const void *H, int64_t ldh, const voi
                     w.partial_bytes + w.colsum_bytes);
     float *partial = static_cast<float *>(ws);
     float *colsum = reinterpret_cast<float *>(static_cast<char *>(ws) + w.partial_bytes);
-    const float *Hf = static_cast<const float *>(H), *Mf = static_cast<const float *>(M);
-    const float *g = static_cast<const float *>(dHnext), *h = static_cast<const float *>(Hnext);
-    const bool relu = act == TMA_ACT_RELU;
     const int64_t Mtot = 2 * int64_t(F_in);
     SplitEpilogue e{partial, Mtot, F_out};
     if (F_in > 0) {
-        const bool va = vec4_ok(Hf, ldh) && vec4_ok(Mf, F_in);
-        const bool vb = vec4_ok(g, ld_next) && (!relu || vec4_ok(h, ld_next));
-        if (va && vb) bwd_weight_dispatch<true, true>(n, Hf, ldh, Mf, g, h, ld_next, relu, F_in, F_out, w, e, colsum, stream);
-        else if (va) bwd_weight_dispatch<true, false>(n, Hf, ldh, Mf, g, h, ld_next, relu, F_in, F_out, w, e, colsum, stream);
-        else if (vb) bwd_weight_dispatch<false, true>(n, Hf, ldh, Mf, g, h, ld_next, relu, F_in, F_out, w, e, colsum, stream);
-        else bwd_weight_dispatch<false, false>(n, Hf, ldh, Mf, g, h, ld_next, relu, F_in, F_out, w, e, colsum, stream);
-        if (int rc = check_launch("sage gemm bwd weight")) return rc;
+        int rc;
+        if (dtype == TMA_F32)
+            rc = bwd_weight_typed<float>(n, static_cast<const float *>(H), ldh, static_cast<const float *>(M),
+                                         static_cast<const float *>(dHnext), static_cast<const float *>(Hnext), ld_next,
+                                         F_in, F_out, act, w, e, colsum, stream);
+        else
+            rc = bwd_weight_typed<uint16_t>(n, static_cast<const uint16_t *>(H), ldh, static_cast<const uint16_t *>(M),
+                                            static_cast<const uint16_t *>(dHnext),
+                                            static_cast<const uint16_t *>(Hnext), ld_next, F_in, F_out, act, w, e,
+                                            colsum, stream);
+        if (rc) return rc;
     }
     const int64_t total_all = Mtot * F_out + F_out;
     TMA_TIMED("reduce_splits", stream);
-    hipLaunchKernelGGL(reduce_splits_kernel, dim3(unsigned(ceil_div(total_all, 4 * kRedCols))), dim3(256), 0, stream, partial,
-                       colsum, F_in > 0 ? w.n_splits : 0, F_in, F_out, dW_self, dW_neigh, dbias);
+    hipLaunchKernelGGL(reduce_splits_kernel, dim3(unsigned(ceil_div(total_all, 4 * kRedCols))), dim3(256), 0, stream,
+                       partial, colsum, F_in > 0 ? w.n_splits : 0, F_in, F_out, dW_self, dW_neigh, dbias);
     return check_launch("sage gemm bwd weight reduce");
 }
 
