@@ -127,15 +127,22 @@ int tma_mean_aggregate(int64_t n, const int32_t *rowptr, const int32_t *colidx,
  * neighbour mean excludes the node itself).
  *   H       [n, F_in]  dtype, ld = ldh
  *   W_self, W_neigh [F_in, F_out] fp32 row-major, dense;  bias [F_out] fp32
- *   M_out   [n, F_in]  dtype, dense (ld = F_in), saved for backward
+ *   M_out   [n, F_in]  dtype, dense (ld = F_in), 16-byte aligned: the layer's saved state.  It holds
+ *           M = Abar H when the layer aggregates first (tma_sage_layer_aggregates_first() = 1).  When
+ *           F_out is at most about half of F_in the layer transforms first -- Y = H [W_self | W_neigh],
+ *           H' = act(Y_self + Abar Y_neigh + b), the same function by linearity with a much narrower
+ *           gather -- and uses M_out as scratch; backward then ignores M.
  *   Hnext_out [n, F_out] dtype, leading dimension ld_next >= F_out; padding
- *           columns are not written.  With TMA_ACT_RELU the sign pattern of
+ *           columns are either left alone or set to zero.  With TMA_ACT_RELU the sign pattern of
  *           H' equals that of Z, so H' is all that backward needs.
  * The 16-byte vector paths need 16-byte aligned pointers and leading
  * dimensions that are multiples of 4 elements (pad rows for widths such as
  * 47); anything else takes a slower element-wise path with the same result.
  * No workspace.
  * ---------------------------------------------------------------------- */
+/* 1 if a layer of these widths aggregates first (M_out = Abar H), 0 if it transforms first. */
+int tma_sage_layer_aggregates_first(int32_t F_in, int32_t F_out, int32_t dtype);
+
 int tma_sage_layer_fwd(int64_t n, const int32_t *rowptr, const int32_t *colidx,
                        const float *inv_deg,
                        const void *H, int64_t ldh, int32_t F_in,

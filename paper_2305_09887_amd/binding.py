@@ -21,7 +21,8 @@ TMA_ACT_NONE, TMA_ACT_RELU = 0, 1
 EXPORTS = (
     "tma_version", "tma_last_error", "tma_partition",
     "tma_induced_subgraph_workspace_bytes", "tma_induced_subgraph_count", "tma_induced_subgraph_fill",
-    "tma_mean_aggregate", "tma_sage_layer_fwd", "tma_sage_layer_bwd_workspace_bytes", "tma_sage_layer_bwd",
+    "tma_mean_aggregate", "tma_sage_layer_aggregates_first", "tma_sage_layer_fwd",
+    "tma_sage_layer_bwd_workspace_bytes", "tma_sage_layer_bwd",
     "tma_loss_workspace_bytes", "tma_softmax_ce", "tma_sigmoid_l2", "tma_sgd_step", "tma_average",
     "tma_gather_rows", "tma_profile_begin", "tma_profile_end", "tma_profile_count", "tma_profile_entry",
 )
@@ -168,6 +169,11 @@ def tma_mean_aggregate(rowptr, colidx, inv_deg, H, out=None, stream=None):
                                     C.c_int32(F), C.c_int32(_feat_dtype(H)), C.c_void_p(out.data_ptr()),
                                     C.c_int64(ldm), _stream(stream)))
     return out
+
+
+def tma_sage_layer_aggregates_first(F_in: int, F_out: int, dtype: int) -> bool:
+    """True if the layer computes M = Abar H first (M_out holds it); False if it transforms first."""
+    return bool(lib().tma_sage_layer_aggregates_first(C.c_int32(F_in), C.c_int32(F_out), C.c_int32(dtype)))
 
 
 def tma_sage_layer_fwd(rowptr, colidx, inv_deg, H, W_self, W_neigh, bias, act: int, M_out=None, Hnext_out=None,

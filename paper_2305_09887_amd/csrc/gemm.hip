@@ -332,6 +332,197 @@ struct MaskedGrad {
 };
 
 // ---------------------------------------------------------------------------
+// Views for the transform-before-aggregate form of the layer (F_out much smaller
+// than F_in):  Y = H [W_self | W_neigh],  H' = act(Y_self + Abar Y_neigh + b).
+// The two halves of the concatenation are padded to Fp = F_out rounded up to the
+// 16-byte element count, so that a group of four never straddles the halves;
+// positions c >= F_out inside a half read as zero.
+// ---------------------------------------------------------------------------
+template <bool V>
+struct SideWeights {  // B[k][n] = n < Fp ? W_self[k][n] : W_neigh[k][n-Fp]   (contiguous along n)
+    static constexpr bool kContigK = false;
+    typedef RawV<float, V> Raw;
+    struct Lane {
+        const float *col;  // element of row k is col[k * Fo]
+        int nv;            // valid elements from this column on (<= 0: padding)
+    };
+    const float *Ws;
+    const float *Wn;
+    int F;   // rows (= F_in)
+    int Fo;  // valid columns per half
+    int Fp;  // padded columns per half
+    static __device__ __forceinline__ float4 resolve(const Raw &r) { return r.get(); }
+    __device__ __forceinline__ Lane prepare(int64_t n64) const
+    {
+        const int n = int(n64);
+        const bool second = n >= Fp;
+        const int c = n - (second ? Fp : 0);
+        const bool ok = n < 2 * Fp && c < Fo;
+        return Lane{(second ? Wn : Ws) + (ok ? c : 0), ok ? Fo - c : 0};
+    }
+    __device__ __forceinline__ Raw load(const Lane &l, int64_t k64) const
+    {
+        const int k = int(k64);
+        Raw r;
+        r.ok = l.nv > 0 && k < F;
+        const float *p = l.col + int64_t(k < F ? k : 0) * Fo;
+        if constexpr (V) {
+            r.v = *reinterpret_cast<const float4 *>(p);
+        } else if (r.ok) {
+            r.v.x = p[0];
+            r.v.y = l.nv > 1 ? p[1] : 0.0f;
+            r.v.z = l.nv > 2 ? p[2] : 0.0f;
+            r.v.w = l.nv > 3 ? p[3] : 0.0f;
+        } else {
+            r.v = zero4();
+        }
+        return r;
+    }
+};
+
+template <bool V>
+struct SideWeightsT {  // B[k][n] = k < Fp ? W_self[n][k] : W_neigh[n][k-Fp]   (contiguous along k); n = input feature
+    static constexpr bool kContigK = true;
+    typedef RawV<float, V> Raw;
+    struct Lane {
+        const float *rs, *rn;  // rows such that element k is rs[k] (first half) or rn[k] (second half)
+        bool ok;
+    };
+    const float *Ws;
+    const float *Wn;
+    int F;  // rows of W (= F_in) = extent of n
+    int Fo;
+    int Fp;
+    static __device__ __forceinline__ float4 resolve(const Raw &r) { return r.get(); }
+    __device__ __forceinline__ Lane prepare(int64_t n64) const
+    {
+        const int n = int(n64 < F ? n64 : 0);
+        return Lane{Ws + int64_t(n) * Fo, Wn + int64_t(n) * Fo - Fp, n64 < F};
+    }
+    __device__ __forceinline__ Raw load(const Lane &l, int64_t k64) const
+    {
+        const int k = int(k64);
+        const bool second = k >= Fp;
+        const int c = k - (second ? Fp : 0);
+        Raw r;
+        r.ok = l.ok && k < 2 * Fp && c < Fo;
+        const float *p = (second ? l.rn : l.rs) + (r.ok ? k : (second ? Fp : 0));
+        if constexpr (V) {
+            r.v = *reinterpret_cast<const float4 *>(p);
+        } else if (r.ok) {
+            r.v.x = p[0];
+            r.v.y = c + 1 < Fo ? p[1] : 0.0f;
+            r.v.z = c + 2 < Fo ? p[2] : 0.0f;
+            r.v.w = c + 3 < Fo ? p[3] : 0.0f;
+        } else {
+            r.v = zero4();
+        }
+        return r;
+    }
+};
+
+// [dZ | dYn]: first half = dHnext (.) act'(Hnext) (leading dimension ld, Fo valid columns),
+// second half = dYn (leading dimension ldy, Fp columns, padding already zero).
+// kAsA: A[m=node][k] (contiguous along k); otherwise B[k=node][n] (contiguous along n).
+template <bool kAsA, typename T, bool V, bool kRelu>
+struct SideGrad {
+    static constexpr bool kContigK = kAsA;
+    typedef typename std::conditional<V, typename Pack4<T>::Packed, float4>::type Quad;
+    struct Raw {
+        Quad g, h;
+        int nv;
+        bool second;
+    };
+    struct Lane {
+        int64_t a, b;  // kAsA: node*ld, node*ldy ; else: column inside its half, unused
+        bool ok, second;
+    };
+    const T *dHn;
+    const T *Hn;
+    const T *dYn;
+    int Fo, Fp;
+    int64_t ld, ldy;
+    int64_t rows;
+    static __device__ __forceinline__ float4 quad(const Quad &q)
+    {
+        if constexpr (V) return Pack4<T>::widen(q);
+        else return q;
+    }
+    static __device__ __forceinline__ float4 resolve(const Raw &r)
+    {
+        const float4 g = quad(r.g);
+        bool o0 = r.nv > 0, o1 = r.nv > 1, o2 = r.nv > 2, o3 = r.nv > 3;
+        if constexpr (kRelu) {
+            const float4 h = quad(r.h);
+            o0 = o0 && (r.second || h.x > 0.0f);
+            o1 = o1 && (r.second || h.y > 0.0f);
+            o2 = o2 && (r.second || h.z > 0.0f);
+            o3 = o3 && (r.second || h.w > 0.0f);
+        }
+        return make_float4(o0 ? g.x : 0.0f, o1 ? g.y : 0.0f, o2 ? g.z : 0.0f, o3 ? g.w : 0.0f);
+    }
+    __device__ __forceinline__ Lane prepare(int64_t mn) const
+    {
+        if (kAsA) {
+            const int64_t node = mn < rows ? mn : 0;
+            return Lane{node * ld, node * ldy, mn < rows, false};
+        }
+        const bool second = mn >= Fp;
+        const int64_t c = mn - (second ? Fp : 0);
+        const bool ok = mn < 2 * Fp && (second || c < Fo);
+        return Lane{ok ? c : 0, 0, ok, second};
+    }
+    __device__ __forceinline__ Raw load(const Lane &l, int64_t k) const
+    {
+        Raw r;
+        bool second, inside;
+        int c;
+        int64_t eg, ey;
+        if (kAsA) {
+            second = k >= Fp;
+            c = int(k - (second ? Fp : 0));
+            inside = l.ok && k < 2 * Fp && (second || c < Fo);
+            if (!inside) c = 0;
+            eg = l.a + c;
+            ey = l.b + c;
+        } else {
+            second = l.second;
+            c = int(l.a);
+            inside = l.ok && k < rows;
+            const int64_t node = k < rows ? k : 0;
+            eg = node * ld + c;
+            ey = node * ldy + c;
+        }
+        r.second = second;
+        r.nv = inside ? (second ? Fp : Fo) - c : 0;
+        if constexpr (V) {
+            r.g = Pack4<T>::load(second ? dYn + ey : dHn + eg);
+            if constexpr (kRelu) r.h = Pack4<T>::load(Hn + eg);
+            else r.h = r.g;
+        } else {
+            r.g = zero4();
+            r.h = zero4();
+            if (inside) {
+                const T *pg = second ? dYn + ey : dHn + eg;
+                const int lim = r.nv;
+                r.g.x = widen1(pg);
+                if (lim > 1) r.g.y = widen1(pg + 1);
+                if (lim > 2) r.g.z = widen1(pg + 2);
+                if (lim > 3) r.g.w = widen1(pg + 3);
+                if (kRelu && !second) {
+                    const T *ph = Hn + eg;
+                    r.h.x = widen1(ph);
+                    if (lim > 1) r.h.y = widen1(ph + 1);
+                    if (lim > 2) r.h.z = widen1(ph + 2);
+                    if (lim > 3) r.h.w = widen1(ph + 3);
+                }
+            }
+        }
+        return r;
+    }
+};
+
+// ---------------------------------------------------------------------------
 // Epilogues.  col_aux / row_aux are fetched once per tile column / row with a
 // clamped (always valid) index; value() is pure arithmetic on registers.
 // ---------------------------------------------------------------------------
@@ -369,6 +560,34 @@ struct BwdDataEpilogue {  // columns [0,F): dH_self (leading dimension ldh) ; [F
         if (col < F) narrow1(dH + row * ldh + col, v);
         else narrow1(dMs + row * F + (col - F), v);
     }
+};
+
+template <typename T>
+struct HalvesEpilogue {  // columns [0,Fp): Y_self ; [Fp,2Fp): Y_neigh ; both [rows, ldy]
+    static constexpr bool kColAux = false, kRowAux = false;
+    T *Ys;
+    T *Yn;
+    int64_t ldy;
+    int Fp;
+    __device__ __forceinline__ float col_aux(int) const { return 0.0f; }
+    __device__ __forceinline__ float row_aux(int64_t) const { return 0.0f; }
+    __device__ __forceinline__ float value(float v, float, float, int) const { return v; }
+    __device__ __forceinline__ void store(int64_t row, int col, float v, int) const
+    {
+        if (col < Fp) narrow1(Ys + row * ldy + col, v);
+        else narrow1(Yn + row * ldy + (col - Fp), v);
+    }
+};
+
+template <typename T>
+struct RowsEpilogue {  // plain [rows, ld] output
+    static constexpr bool kColAux = false, kRowAux = false;
+    T *out;
+    int64_t ld;
+    __device__ __forceinline__ float col_aux(int) const { return 0.0f; }
+    __device__ __forceinline__ float row_aux(int64_t) const { return 0.0f; }
+    __device__ __forceinline__ float value(float v, float, float, int) const { return v; }
+    __device__ __forceinline__ void store(int64_t row, int col, float v, int) const { narrow1(out + row * ld + col, v); }
 };
 
 struct SplitEpilogue {  // partial products, one slab per split
@@ -642,6 +861,49 @@ __global__ __launch_bounds__(256) void reduce_splits_kernel(const float *__restr
     }
 }
 
+// Split reduction for the transform-first form: partial is [splits][F][2*Fp]; column c of the left half
+// goes to dW_self[:, c], of the right half to dW_neigh[:, c]; the column sums of the left half are dbias.
+__global__ __launch_bounds__(256) void reduce_splits_halves_kernel(const float *__restrict__ partial,
+                                                                   const float *__restrict__ colsum_partial,
+                                                                   int n_splits, int F, int Fo, int Fp,
+                                                                   float *__restrict__ dW_self,
+                                                                   float *__restrict__ dW_neigh,
+                                                                   float *__restrict__ dbias)
+{
+    __shared__ float part[kRedSlices][kRedCols];
+    const int N = 2 * Fp;
+    const int64_t total = int64_t(F) * N;
+    const int64_t total_all = total + N;
+    const int col = threadIdx.x % kRedCols, q = threadIdx.x / kRedCols;
+    const int64_t e = int64_t(blockIdx.x) * kRedCols + col;
+    const int per = (n_splits + kRedSlices - 1) / kRedSlices;
+    const int s_begin = q * per, s_end = (s_begin + per < n_splits) ? s_begin + per : n_splits;
+    float s = 0.0f;
+    if (e < total) {
+#pragma unroll 8
+        for (int sp = s_begin; sp < s_end; ++sp) s += partial[int64_t(sp) * total + e];
+    } else if (e < total_all) {
+        for (int sp = s_begin; sp < s_end; ++sp) s += colsum_partial[int64_t(sp) * N + (e - total)];
+    }
+    part[q][col] = s;
+    __syncthreads();
+    if (q == 0 && e < total_all) {
+        float r = 0.0f;
+#pragma unroll
+        for (int w = 0; w < kRedSlices; ++w) r += part[w][col];
+        if (e < total) {
+            const int64_t m = e / N;
+            const int c = int(e - m * N);
+            const bool second = c >= Fp;
+            const int cc = c - (second ? Fp : 0);
+            if (cc < Fo) (second ? dW_neigh : dW_self)[m * Fo + cc] = r;
+        } else {
+            const int c = int(e - total);
+            if (c < Fo) dbias[c] = r;
+        }
+    }
+}
+
 template <typename T>
 static bool vec4_ok(const T *p, int64_t ld) { return aligned(p, 4 * sizeof(T)) && ld % 4 == 0; }
 
@@ -871,6 +1133,192 @@ int launch_sage_gemm_bwd_weight(int64_t n, const void *H, int64_t ldh, const voi
     hipLaunchKernelGGL(reduce_splits_kernel, dim3(unsigned(ceil_div(total_all, 4 * kRedCols))), dim3(256), 0, stream,
                        partial, colsum, F_in > 0 ? w.n_splits : 0, F_in, F_out, dW_self, dW_neigh, dbias);
     return check_launch("sage gemm bwd weight reduce");
+}
+
+// ---- transform-before-aggregate form -----------------------------------------
+static int pad_cols(int32_t F_out, int32_t dtype) { return int(round_up(size_t(F_out), dtype == TMA_BF16 ? 8 : 4)); }
+
+template <int BK, bool kColSum, class AL, class BL, class Epi>
+static void launch_by_width(const char *name, const AL &a, const BL &b, const Epi &e, int64_t M, int N, int64_t K,
+                            int64_t kps, int n_splits, float *colsum, hipStream_t s)
+{
+    if (N <= 64) launch_gemm<128, 64, BK, 4, 1, kColSum>(name, a, b, e, M, N, K, kps, n_splits, colsum, s);
+    else if (N <= 96) launch_gemm<128, 96, BK, 4, 1, kColSum>(name, a, b, e, M, N, K, kps, n_splits, colsum, s);
+    else launch_gemm<128, 128, BK, 2, 2, kColSum>(name, a, b, e, M, N, K, kps, n_splits, colsum, s);
+}
+
+template <typename T>
+static int tf_fwd_typed(int64_t n, const T *H, int64_t ldh, int32_t F_in, const float *W_self, const float *W_neigh,
+                        int32_t F_out, int Fp, T *Ys, T *Yn, int64_t ldy, hipStream_t s)
+{
+    HalvesEpilogue<T> e{Ys, Yn, ldy, Fp};
+    const int64_t K = F_in, kps = int64_t(round_up(size_t(K), 32));
+    const bool va = vec4_ok(H, ldh);
+    const bool vb = F_out % 4 == 0 && aligned(W_self, 16) && aligned(W_neigh, 16);
+    const char *name = kname<T>("gemm_tf_fwd", "gemm_tf_fwd_generic", "gemm_tf_fwd_bf16", "gemm_tf_fwd_bf16_generic", va);
+#define TMA_TF_FWD(VA_, VB_)                                                                      \
+    do {                                                                                          \
+        CatRows<T, VA_> a{H, ldh, H, F_in, n};                                                    \
+        SideWeights<VB_> b{W_self, W_neigh, F_in, F_out, Fp};                                     \
+        launch_by_width<32, false>(name, a, b, e, n, 2 * Fp, K, kps, 1, nullptr, s);              \
+    } while (0)
+    if (va && vb) TMA_TF_FWD(true, true);
+    else if (va) TMA_TF_FWD(true, false);
+    else if (vb) TMA_TF_FWD(false, true);
+    else TMA_TF_FWD(false, false);
+#undef TMA_TF_FWD
+    return check_launch("sage gemm tf fwd");
+}
+
+int launch_sage_tf_gemm_fwd(int64_t n, const void *H, int64_t ldh, int32_t F_in, const float *W_self,
+                            const float *W_neigh, int32_t F_out, int32_t dtype, void *Ys, void *Yn, int64_t ldy,
+                            hipStream_t stream)
+{
+    if (n == 0) return TMA_OK;
+    const int Fp = pad_cols(F_out, dtype);
+    if (dtype == TMA_F32)
+        return tf_fwd_typed<float>(n, static_cast<const float *>(H), ldh, F_in, W_self, W_neigh, F_out, Fp,
+                                   static_cast<float *>(Ys), static_cast<float *>(Yn), ldy, stream);
+    if (dtype == TMA_BF16)
+        return tf_fwd_typed<uint16_t>(n, static_cast<const uint16_t *>(H), ldh, F_in, W_self, W_neigh, F_out, Fp,
+                                      static_cast<uint16_t *>(Ys), static_cast<uint16_t *>(Yn), ldy, stream);
+    return fail(TMA_ERR_UNSUPPORTED_DTYPE, "sage gemm tf fwd: dtype %d", dtype);
+}
+
+static WeightSplit plan_tf_weight_split(int64_t n, int32_t F_in, int Fp)
+{
+    const int N = 2 * Fp;
+    const int bn = N <= 64 ? 64 : (N <= 96 ? 96 : 128);
+    const int64_t tiles = ceil_div(int64_t(F_in), 128) * ceil_div(N, bn);
+    int64_t want = ceil_div(512, tiles > 0 ? tiles : 1);
+    const int64_t max_useful = ceil_div(n > 0 ? n : 1, 128);
+    if (want > max_useful) want = max_useful;
+    if (want < 1) want = 1;
+    WeightSplit w;
+    w.k_per_split = int64_t(round_up(size_t(ceil_div(n > 0 ? n : 1, want)), 32));
+    w.n_splits = int(ceil_div(n > 0 ? n : 1, w.k_per_split));
+    w.partial_bytes = round_up(size_t(w.n_splits) * size_t(F_in) * size_t(N) * 4, 256);
+    w.colsum_bytes = round_up(size_t(w.n_splits) * size_t(N) * 4, 256);
+    return w;
+}
+
+size_t sage_tf_gemm_bwd_weight_workspace_bytes(int64_t n, int32_t F_in, int32_t F_out, int32_t dtype)
+{
+    const WeightSplit w = plan_tf_weight_split(n, F_in, pad_cols(F_out, dtype));
+    return w.partial_bytes + w.colsum_bytes;
+}
+
+template <typename T>
+static int tf_bwd_weight_typed(int64_t n, const T *H, int64_t ldh, const T *g, const T *h, int64_t ld_next,
+                               const T *dYn, int64_t ldy, int32_t F_in, int32_t F_out, int Fp, bool relu,
+                               const WeightSplit &w, float *partial, float *colsum, hipStream_t s)
+{
+    SplitEpilogue e{partial, int64_t(F_in), 2 * Fp};
+    const bool va = vec4_ok(H, ldh);
+    const bool vb = vec4_ok(g, ld_next) && (!relu || vec4_ok(h, ld_next)) && vec4_ok(dYn, ldy);
+    const char *name = kname<T>("gemm_tf_bwd_weight", "gemm_tf_bwd_weight_generic", "gemm_tf_bwd_weight_bf16",
+                                "gemm_tf_bwd_weight_bf16_generic", va && vb);
+#define TMA_TF_BW(VA_, VB_, R_)                                                                                       \
+    do {                                                                                                              \
+        CatRowsT<T, VA_> a{H, ldh, H, F_in, n};                                                                       \
+        SideGrad<false, T, VB_, R_> b{g, h, dYn, F_out, Fp, ld_next, ldy, n};                                         \
+        launch_by_width<32, true>(name, a, b, e, int64_t(F_in), 2 * Fp, n, w.k_per_split, w.n_splits, colsum, s);     \
+    } while (0)
+#define TMA_TF_BW2(VA_, VB_)         \
+    do {                             \
+        if (relu) TMA_TF_BW(VA_, VB_, true); \
+        else TMA_TF_BW(VA_, VB_, false);     \
+    } while (0)
+    if (va && vb) TMA_TF_BW2(true, true);
+    else if (va) TMA_TF_BW2(true, false);
+    else if (vb) TMA_TF_BW2(false, true);
+    else TMA_TF_BW2(false, false);
+#undef TMA_TF_BW2
+#undef TMA_TF_BW
+    return check_launch("sage gemm tf bwd weight");
+}
+
+int launch_sage_tf_gemm_bwd_weight(int64_t n, const void *H, int64_t ldh, const void *dHnext, const void *Hnext,
+                                   int64_t ld_next, const void *dYn, int64_t ldy, int32_t F_in, int32_t F_out,
+                                   int32_t act, int32_t dtype, float *dW_self, float *dW_neigh, float *dbias, void *ws,
+                                   size_t ws_bytes, hipStream_t stream)
+{
+    if (dtype != TMA_F32 && dtype != TMA_BF16) return fail(TMA_ERR_UNSUPPORTED_DTYPE, "sage gemm tf bwd: dtype %d", dtype);
+    const int Fp = pad_cols(F_out, dtype);
+    const WeightSplit w = plan_tf_weight_split(n, F_in, Fp);
+    if (ws_bytes < w.partial_bytes + w.colsum_bytes)
+        return fail(TMA_ERR_WORKSPACE_TOO_SMALL, "sage gemm tf bwd weight: workspace %zu < %zu", ws_bytes,
+                    w.partial_bytes + w.colsum_bytes);
+    float *partial = static_cast<float *>(ws);
+    float *colsum = reinterpret_cast<float *>(static_cast<char *>(ws) + w.partial_bytes);
+    const bool relu = act == TMA_ACT_RELU;
+    int rc;
+    if (dtype == TMA_F32)
+        rc = tf_bwd_weight_typed<float>(n, static_cast<const float *>(H), ldh, static_cast<const float *>(dHnext),
+                                        static_cast<const float *>(Hnext), ld_next, static_cast<const float *>(dYn),
+                                        ldy, F_in, F_out, Fp, relu, w, partial, colsum, stream);
+    else
+        rc = tf_bwd_weight_typed<uint16_t>(n, static_cast<const uint16_t *>(H), ldh,
+                                           static_cast<const uint16_t *>(dHnext),
+                                           static_cast<const uint16_t *>(Hnext), ld_next,
+                                           static_cast<const uint16_t *>(dYn), ldy, F_in, F_out, Fp, relu, w, partial,
+                                           colsum, stream);
+    if (rc) return rc;
+    const int64_t total_all = int64_t(F_in) * 2 * Fp + 2 * Fp;
+    TMA_TIMED("reduce_splits_halves", stream);
+    hipLaunchKernelGGL(reduce_splits_halves_kernel, dim3(unsigned(ceil_div(total_all, kRedCols))), dim3(256), 0, stream,
+                       partial, colsum, w.n_splits, F_in, F_out, Fp, dW_self, dW_neigh, dbias);
+    return check_launch("sage gemm tf bwd weight reduce");
+}
+
+template <typename T>
+static int tf_bwd_data_typed(int64_t n, const T *g, const T *h, int64_t ld_next, const T *dYn, int64_t ldy,
+                             const float *W_self, const float *W_neigh, int32_t F_in, int32_t F_out, int Fp, bool relu,
+                             T *dH, int64_t ldh, hipStream_t s)
+{
+    RowsEpilogue<T> e{dH, ldh};
+    const int64_t K = 2 * int64_t(Fp), kps = int64_t(round_up(size_t(K), 32));
+    const bool va = vec4_ok(g, ld_next) && (!relu || vec4_ok(h, ld_next)) && vec4_ok(dYn, ldy);
+    const bool vb = F_out % 4 == 0 && aligned(W_self, 16) && aligned(W_neigh, 16);
+    const char *name = kname<T>("gemm_tf_bwd_data", "gemm_tf_bwd_data_generic", "gemm_tf_bwd_data_bf16",
+                                "gemm_tf_bwd_data_bf16_generic", va);
+#define TMA_TF_BD(VA_, VB_, R_)                                                                        \
+    do {                                                                                               \
+        SideGrad<true, T, VA_, R_> a{g, h, dYn, F_out, Fp, ld_next, ldy, n};                           \
+        SideWeightsT<VB_> b{W_self, W_neigh, F_in, F_out, Fp};                                         \
+        launch_gemm<128, 128, 32, 2, 2, false>(name, a, b, e, n, F_in, K, kps, 1, nullptr, s);         \
+    } while (0)
+#define TMA_TF_BD2(VA_, VB_)                 \
+    do {                                     \
+        if (relu) TMA_TF_BD(VA_, VB_, true); \
+        else TMA_TF_BD(VA_, VB_, false);     \
+    } while (0)
+    if (va && vb) TMA_TF_BD2(true, true);
+    else if (va) TMA_TF_BD2(true, false);
+    else if (vb) TMA_TF_BD2(false, true);
+    else TMA_TF_BD2(false, false);
+#undef TMA_TF_BD2
+#undef TMA_TF_BD
+    return check_launch("sage gemm tf bwd data");
+}
+
+int launch_sage_tf_gemm_bwd_data(int64_t n, const void *dHnext, const void *Hnext, int64_t ld_next, const void *dYn,
+                                 int64_t ldy, const float *W_self, const float *W_neigh, int32_t F_in, int32_t F_out,
+                                 int32_t act, int32_t dtype, void *dH, int64_t ldh, hipStream_t stream)
+{
+    if (n == 0) return TMA_OK;
+    const int Fp = pad_cols(F_out, dtype);
+    const bool relu = act == TMA_ACT_RELU;
+    if (dtype == TMA_F32)
+        return tf_bwd_data_typed<float>(n, static_cast<const float *>(dHnext), static_cast<const float *>(Hnext),
+                                        ld_next, static_cast<const float *>(dYn), ldy, W_self, W_neigh, F_in, F_out, Fp,
+                                        relu, static_cast<float *>(dH), ldh, stream);
+    if (dtype == TMA_BF16)
+        return tf_bwd_data_typed<uint16_t>(n, static_cast<const uint16_t *>(dHnext),
+                                           static_cast<const uint16_t *>(Hnext), ld_next,
+                                           static_cast<const uint16_t *>(dYn), ldy, W_self, W_neigh, F_in, F_out, Fp,
+                                           relu, static_cast<uint16_t *>(dH), ldh, stream);
+    return fail(TMA_ERR_UNSUPPORTED_DTYPE, "sage gemm tf bwd data: dtype %d", dtype);
 }
 
 }  // namespace tma

@@ -11,6 +11,17 @@ int launch_spmm(int64_t n, const int32_t *rowptr, const int32_t *colidx, const f
                 int64_t ld_in, int32_t F, int32_t dtype, void *out, int64_t ld_out, bool accumulate,
                 hipStream_t stream);
 
+// Same gather with the layer epilogue fused: out_v = act(scale_v * sum + [out_v] + self_v + bias).
+int launch_spmm_combine(int64_t n, const int32_t *rowptr, const int32_t *colidx, const float *inv_deg, const void *in,
+                        int64_t ld_in, int32_t F, int32_t dtype, void *out, int64_t ld_out, bool accumulate,
+                        const void *self, int64_t ld_self, const float *bias, int32_t F_valid, bool relu,
+                        hipStream_t stream);
+
+// dst_v = inv_deg[v] * g_v (.) [h_v > 0]  (mask only with relu); columns F..F_pad-1 of dst are zeroed.
+int launch_scale_mask_rows(int64_t n, int32_t F, int32_t F_pad, const void *g, const void *h, int64_t ld,
+                           const float *inv_deg, bool relu, int32_t dtype, void *dst, int64_t ld_dst,
+                           hipStream_t stream);
+
 // Z = [H | M] [W_self ; W_neigh] + b ;  Hnext = act(Z)
 int launch_sage_gemm_fwd(int64_t n, const void *H, int64_t ldh, const void *M, int32_t F_in, const float *W_self,
                          const float *W_neigh, const float *bias, int32_t F_out, int32_t act, int32_t dtype,
@@ -29,5 +40,22 @@ int launch_sage_gemm_bwd_weight(int64_t n, const void *H, int64_t ldh, const voi
                                 int32_t dtype,
                                 float *dW_self, float *dW_neigh, float *dbias, void *ws, size_t ws_bytes,
                                 hipStream_t stream);
+
+// Transform-before-aggregate form of the layer (chosen when two padded output widths fit into F_in):
+//   forward   [Y_self | Y_neigh] = H [W_self | W_neigh];  Hnext = act(Y_self + Abar Y_neigh + b)  (launch_spmm_combine)
+//   backward  dYn = Abar^T dZ (gather of inv_deg-scaled dZ);  [dW_self | dW_neigh] = H^T [dZ | dYn];  db = 1^T dZ;
+//             dH = [dZ | dYn] [W_self | W_neigh]^T
+// Ys, Yn, dYn: [n, Fp] blocks with leading dimension ldy, Fp = F_out padded to 16 bytes.
+int launch_sage_tf_gemm_fwd(int64_t n, const void *H, int64_t ldh, int32_t F_in, const float *W_self,
+                            const float *W_neigh, int32_t F_out, int32_t dtype, void *Ys, void *Yn, int64_t ldy,
+                            hipStream_t stream);
+size_t sage_tf_gemm_bwd_weight_workspace_bytes(int64_t n, int32_t F_in, int32_t F_out, int32_t dtype);
+int launch_sage_tf_gemm_bwd_weight(int64_t n, const void *H, int64_t ldh, const void *dHnext, const void *Hnext,
+                                   int64_t ld_next, const void *dYn, int64_t ldy, int32_t F_in, int32_t F_out,
+                                   int32_t act, int32_t dtype, float *dW_self, float *dW_neigh, float *dbias, void *ws,
+                                   size_t ws_bytes, hipStream_t stream);
+int launch_sage_tf_gemm_bwd_data(int64_t n, const void *dHnext, const void *Hnext, int64_t ld_next, const void *dYn,
+                                 int64_t ldy, const float *W_self, const float *W_neigh, int32_t F_in, int32_t F_out,
+                                 int32_t act, int32_t dtype, void *dH, int64_t ldh, hipStream_t stream);
 
 }  // namespace tma

@@ -13,11 +13,24 @@ struct BwdWorkspace {
     size_t total() const { return dm_bytes + weight_bytes; }
 };
 
+// Order of the two halves of a layer.  Aggregating first costs a gather of F_in-wide rows, transforming
+// first a gather of F_out-wide rows; the products cost the same either way.  The transform-first form is
+// taken when its two padded output blocks fit into the [n, F_in] buffer the caller provides for saved
+// state (M_out), i.e. when F_out is at most about half of F_in (the last layer of the models here).
+static int pad_cols(int32_t F_out, int32_t dtype) { return int(round_up(size_t(F_out), dtype == TMA_BF16 ? 8 : 4)); }
+static bool aggregates_first(int32_t F_in, int32_t F_out, int32_t dtype) { return 2 * pad_cols(F_out, dtype) > F_in; }
+
 static BwdWorkspace plan_bwd(int64_t n, int32_t F_in, int32_t F_out, int32_t dtype, bool need_dH)
 {
     BwdWorkspace w;
-    w.dm_bytes = need_dH ? round_up(size_t(n > 0 ? n : 1) * size_t(F_in > 0 ? F_in : 1) * elem_size(dtype), 256) : 0;
-    w.weight_bytes = sage_gemm_bwd_weight_workspace_bytes(n, F_in, F_out);
+    const size_t rows = size_t(n > 0 ? n : 1);
+    if (aggregates_first(F_in, F_out, dtype)) {
+        w.dm_bytes = need_dH ? round_up(rows * size_t(F_in) * elem_size(dtype), 256) : 0;
+        w.weight_bytes = sage_gemm_bwd_weight_workspace_bytes(n, F_in, F_out);
+    } else {  // scaled dZ and dYn, [n, Fp] each
+        w.dm_bytes = 2 * round_up(rows * size_t(pad_cols(F_out, dtype)) * elem_size(dtype), 256);
+        w.weight_bytes = sage_tf_gemm_bwd_weight_workspace_bytes(n, F_in, F_out, dtype);
+    }
     return w;
 }
 
@@ -40,9 +53,29 @@ extern "C" int tma_sage_layer_fwd(int64_t n, const int32_t *rowptr, const int32_
                 "%s: NULL argument", fn);
     TMA_REQUIRE(ldh >= F_in && ld_next >= F_out, TMA_ERR_BAD_SHAPE, "%s: ldh < F_in or ld_next < F_out", fn);
     hipStream_t s = as_stream(stream);
-    if (int rc = launch_spmm(n, rowptr, colidx, inv_deg, H, ldh, F_in, dtype, M_out, F_in, false, s)) return rc;
-    return launch_sage_gemm_fwd(n, H, ldh, M_out, F_in, W_self, W_neigh, bias, F_out, act, dtype, Hnext_out, ld_next,
-                                s);
+    if (aggregates_first(F_in, F_out, dtype)) {
+        if (int rc = launch_spmm(n, rowptr, colidx, inv_deg, H, ldh, F_in, dtype, M_out, F_in, false, s)) return rc;
+        return launch_sage_gemm_fwd(n, H, ldh, M_out, F_in, W_self, W_neigh, bias, F_out, act, dtype, Hnext_out,
+                                    ld_next, s);
+    }
+    // transform first: [Y_self | Y_neigh] = H [W_self | W_neigh] into the M_out buffer, then
+    // Hnext = act(Y_self + Abar Y_neigh + b) by the gather kernel.  Needs ld_next >= the padded width.
+    const int Fp = pad_cols(F_out, dtype);
+    char *scratch = static_cast<char *>(M_out);
+    void *Ys = scratch;
+    void *Yn = scratch + size_t(n) * size_t(Fp) * elem_size(dtype);
+    TMA_REQUIRE(aligned(M_out, 16), TMA_ERR_INVALID_ARG, "%s: M_out must be 16-byte aligned", fn);
+    if (int rc = launch_sage_tf_gemm_fwd(n, H, ldh, F_in, W_self, W_neigh, F_out, dtype, Ys, Yn, Fp, s)) return rc;
+    if (ld_next >= Fp)   // whole padded rows (vector path); the padding columns of Hnext receive zeros
+        return launch_spmm_combine(n, rowptr, colidx, inv_deg, Yn, Fp, Fp, dtype, Hnext_out, ld_next, false, Ys, Fp,
+                                   bias, F_out, act == TMA_ACT_RELU, s);
+    return launch_spmm_combine(n, rowptr, colidx, inv_deg, Yn, Fp, F_out, dtype, Hnext_out, ld_next, false, Ys, Fp,
+                               bias, F_out, act == TMA_ACT_RELU, s);
+}
+
+extern "C" int tma_sage_layer_aggregates_first(int32_t F_in, int32_t F_out, int32_t dtype)
+{
+    return tma::aggregates_first(F_in, F_out, dtype) ? 1 : 0;
 }
 
 extern "C" size_t tma_sage_layer_bwd_workspace_bytes(int64_t n, int32_t F_in, int32_t F_out, int32_t dtype,
@@ -71,8 +104,9 @@ extern "C" int tma_sage_layer_bwd(int64_t n, const int32_t *rowptr_T, const int3
     const BwdWorkspace w = plan_bwd(n, F_in, F_out, dtype, need_dH);
     TMA_REQUIRE(ws_bytes >= w.total(), TMA_ERR_WORKSPACE_TOO_SMALL, "%s: workspace %zu < %zu bytes", fn, ws_bytes,
                 w.total());
+    const bool agg_first = aggregates_first(F_in, F_out, dtype);
     if (n > 0) {
-        TMA_REQUIRE(H && M && dHnext && W_self && W_neigh, TMA_ERR_INVALID_ARG, "%s: NULL argument", fn);
+        TMA_REQUIRE(H && (M || !agg_first) && dHnext && W_self && W_neigh, TMA_ERR_INVALID_ARG, "%s: NULL argument", fn);
         TMA_REQUIRE(act == TMA_ACT_NONE || Hnext, TMA_ERR_INVALID_ARG, "%s: Hnext is required with ReLU", fn);
         TMA_REQUIRE(!need_dH || (rowptr_T && inv_deg), TMA_ERR_INVALID_ARG, "%s: graph is NULL", fn);
         TMA_REQUIRE(ldh >= F_in && ld_next >= F_out, TMA_ERR_BAD_SHAPE, "%s: ldh < F_in or ld_next < F_out", fn);
@@ -82,6 +116,24 @@ extern "C" int tma_sage_layer_bwd(int64_t n, const int32_t *rowptr_T, const int3
     void *dMs = base;
     void *wws = base + w.dm_bytes;
 
+    if (!agg_first) {
+        // transform-first form: dYn = Abar^T dZ as a gather of the inv_deg-scaled, masked dZ over the transposed
+        // graph; then the two products with [dZ | dYn]
+        TMA_REQUIRE(n == 0 || (rowptr_T && inv_deg), TMA_ERR_INVALID_ARG, "%s: graph is NULL", fn);
+        const int Fp = pad_cols(F_out, dtype);
+        void *dZs = base;
+        void *dYn = base + w.dm_bytes / 2;
+        if (int rc = launch_scale_mask_rows(n, F_out, Fp, dHnext, Hnext, ld_next, inv_deg, act == TMA_ACT_RELU, dtype,
+                                            dZs, Fp, s))
+            return rc;
+        if (int rc = launch_spmm(n, rowptr_T, colidx_T, nullptr, dZs, Fp, Fp, dtype, dYn, Fp, false, s)) return rc;
+        if (int rc = launch_sage_tf_gemm_bwd_weight(n, H, ldh, dHnext, Hnext, ld_next, dYn, Fp, F_in, F_out, act, dtype,
+                                                    dW_self, dW_neigh, dbias, wws, w.weight_bytes, s))
+            return rc;
+        if (!need_dH || n == 0) return TMA_OK;
+        return launch_sage_tf_gemm_bwd_data(n, dHnext, Hnext, ld_next, dYn, Fp, W_self, W_neigh, F_in, F_out, act,
+                                            dtype, dH_out, ldh, s);
+    }
     if (int rc = launch_sage_gemm_bwd_weight(n, H, ldh, M, dHnext, Hnext, ld_next, F_in, F_out, act, dtype, dW_self,
                                              dW_neigh, dbias, wws, w.weight_bytes, s))
         return rc;

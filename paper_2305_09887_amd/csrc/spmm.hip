@@ -19,7 +19,7 @@ namespace tma {
 
 constexpr int kSpmmThreads = 256;
 constexpr int kRowsPerGroup = 4;   // rows a lane group walks through per block
-constexpr int kHubDegree = 64;     // rows longer than this are summed by the whole workgroup
+constexpr int kHubDegree = 48;     // rows longer than this are summed by the whole workgroup
 
 template <typename T>
 struct Chunk;
@@ -65,68 +65,100 @@ __device__ __forceinline__ float load_elem(const uint16_t *p) { return bf16_to_f
 __device__ __forceinline__ void store_elem(float *p, float v) { *p = v; }
 __device__ __forceinline__ void store_elem(uint16_t *p, float v) { *p = f32_to_bf16(v); }
 
+// U neighbour rows (entries j .. j+U-1 of the run whose ids sit in `mine`) fetched together, then added in order.
+template <typename T, int G, int CPL, int U>
+__device__ __forceinline__ void gather_batch(const T *__restrict__ in, int64_t ld, int32_t mine, int j, int sub,
+                                             int n_chunks, float (&acc)[CPL][Chunk<T>::kElems])
+{
+    constexpr int E = Chunk<T>::kElems;
+    float v[U][CPL][E];
+#pragma unroll
+    for (int q = 0; q < U; ++q) {
+        const T *row = in + int64_t(__shfl(mine, j + q, G)) * ld;
+#pragma unroll
+        for (int c = 0; c < CPL; ++c)
+            if (sub + c * G < n_chunks) Chunk<T>::load(row + (sub + c * G) * E, v[q][c]);
+    }
+#pragma unroll
+    for (int q = 0; q < U; ++q)
+#pragma unroll
+        for (int c = 0; c < CPL; ++c)
+            if (sub + c * G < n_chunks)
+#pragma unroll
+                for (int i = 0; i < E; ++i) acc[c][i] += v[q][c][i];
+}
+
 // Adds the rows colidx[e] for e = beg, beg+1, ... in runs of G entries that start
 // `run_stride` entries apart.  Every lane of the group gets the same trip counts.
-template <typename T, int G, int CPL>
+// kDeep: up to 16 rows in flight per lane (long rows are latency bound: a 500-entry
+// row walked four loads at a time sets the kernel's tail).
+template <typename T, int G, int CPL, bool kDeep>
 __device__ __forceinline__ void gather_sum(const T *__restrict__ in, int64_t ld, const int32_t *__restrict__ colidx,
                                            int32_t beg, int32_t end, int32_t run_stride, int sub, int n_chunks,
                                            float (&acc)[CPL][Chunk<T>::kElems])
 {
-    constexpr int E = Chunk<T>::kElems;
     for (int32_t e0 = beg; e0 < end; e0 += run_stride) {
         const int cnt = (end - e0) < G ? (end - e0) : G;
         const int32_t mine = sub < cnt ? colidx[e0 + sub] : 0;
         int j = 0;
-        for (; j + 4 <= cnt; j += 4) {  // four neighbour rows in flight
-            float v[4][CPL][E];
-#pragma unroll
-            for (int q = 0; q < 4; ++q) {
-                const T *row = in + int64_t(__shfl(mine, j + q, G)) * ld;
-#pragma unroll
-                for (int c = 0; c < CPL; ++c)
-                    if (sub + c * G < n_chunks) Chunk<T>::load(row + (sub + c * G) * E, v[q][c]);
-            }
-#pragma unroll
-            for (int q = 0; q < 4; ++q)
-#pragma unroll
-                for (int c = 0; c < CPL; ++c)
-                    if (sub + c * G < n_chunks)
-#pragma unroll
-                        for (int i = 0; i < E; ++i) acc[c][i] += v[q][c][i];
-        }
-        for (; j < cnt; ++j) {
-            const T *row = in + int64_t(__shfl(mine, j, G)) * ld;
-#pragma unroll
-            for (int c = 0; c < CPL; ++c)
-                if (sub + c * G < n_chunks) {
-                    float v[E];
-                    Chunk<T>::load(row + (sub + c * G) * E, v);
-#pragma unroll
-                    for (int i = 0; i < E; ++i) acc[c][i] += v[i];
-                }
-        }
+        if constexpr (kDeep && CPL == 1 && G >= 16)
+            for (; j + 16 <= cnt; j += 16) gather_batch<T, G, CPL, 16>(in, ld, mine, j, sub, n_chunks, acc);
+        for (; j + 4 <= cnt; j += 4) gather_batch<T, G, CPL, 4>(in, ld, mine, j, sub, n_chunks, acc);
+        for (; j < cnt; ++j) gather_batch<T, G, CPL, 1>(in, ld, mine, j, sub, n_chunks, acc);
     }
 }
 
+// What happens to a finished row sum s_v:
+//   out_v = act( scale_v * s_v  [+ out_v]  [+ self_v]  [+ bias] )
+// scale_v = inv_deg[v] (mean) or 1; "+ out_v" accumulates onto what is there (backward: on top of
+// dZ W_self^T); "+ self_v + bias" and the activation turn the gather into the layer output when the
+// transform ran before the aggregation.
+template <typename T>
+struct SpmmOut {
+    T *out;
+    int64_t ld_out;
+    const float *inv_deg;
+    int accumulate;
+    const T *self;
+    int64_t ld_self;
+    const float *bias;
+    int F;  // valid elements of a row (bias is not applied to padding)
+    int relu;
+};
+
 template <typename T, int G, int CPL>
-__device__ __forceinline__ void finish_row(int64_t v, const float *__restrict__ inv_deg, T *__restrict__ out,
-                                           int64_t ld_out, bool accumulate, int sub, int n_chunks,
+__device__ __forceinline__ void finish_row(int64_t v, const SpmmOut<T> &o, int sub, int n_chunks,
                                            float (&acc)[CPL][Chunk<T>::kElems])
 {
     constexpr int E = Chunk<T>::kElems;
-    const float scale = inv_deg ? inv_deg[v] : 1.0f;
+    const float scale = o.inv_deg ? o.inv_deg[v] : 1.0f;
 #pragma unroll
     for (int c = 0; c < CPL; ++c)
         if (sub + c * G < n_chunks) {
-            T *dst = out + v * ld_out + (sub + c * G) * E;
+            const int f0 = (sub + c * G) * E;
+            T *dst = o.out + v * o.ld_out + f0;
             float r[E];
 #pragma unroll
             for (int i = 0; i < E; ++i) r[i] = acc[c][i] * scale;
-            if (accumulate) {
+            if (o.accumulate) {
                 float old[E];
                 Chunk<T>::load(dst, old);
 #pragma unroll
                 for (int i = 0; i < E; ++i) r[i] += old[i];
+            }
+            if (o.self) {
+                float sv[E];
+                Chunk<T>::load(o.self + v * o.ld_self + f0, sv);
+#pragma unroll
+                for (int i = 0; i < E; ++i) r[i] += sv[i];
+            }
+            if (o.bias) {
+#pragma unroll
+                for (int i = 0; i < E; ++i) r[i] += (f0 + i < o.F) ? o.bias[f0 + i] : 0.0f;
+            }
+            if (o.relu) {
+#pragma unroll
+                for (int i = 0; i < E; ++i) r[i] = r[i] > 0.0f ? r[i] : 0.0f;
             }
             Chunk<T>::store(dst, r);
         }
@@ -138,61 +170,54 @@ __device__ __forceinline__ void finish_row(int64_t v, const float *__restrict__ 
 // four independent 16-byte loads in flight, and steers each loaded chunk to its row by
 // predication (adding 0 elsewhere).  At a mean local degree of 2-5 this is what keeps
 // enough bytes in flight; walking the rows one after the other leaves the lanes waiting.
+template <typename T, int G, int R, int U>
+__device__ __forceinline__ void gather_rows_batch(const T *__restrict__ in, int64_t ld, int32_t mine, int j, int32_t e_first,
+                                                  const int32_t (&bound)[R + 1], int sub, bool own,
+                                                  float (&acc)[R][Chunk<T>::kElems])
+{
+    constexpr int E = Chunk<T>::kElems;
+    float v[U][E];
+#pragma unroll
+    for (int q = 0; q < U; ++q) {
+        const T *row = in + int64_t(__shfl(mine, j + q, G)) * ld;
+        if (own) Chunk<T>::load(row + sub * E, v[q]);
+    }
+#pragma unroll
+    for (int q = 0; q < U; ++q) {
+        const int32_t e = e_first + q;
+#pragma unroll
+        for (int r = 0; r < R; ++r) {
+            const bool hit = e >= bound[r] && e < bound[r + 1];
+            if (own)
+#pragma unroll
+                for (int i = 0; i < E; ++i) acc[r][i] += hit ? v[q][i] : 0.0f;
+        }
+    }
+}
+
 template <typename T, int G, int R>
 __device__ __forceinline__ void gather_sum_rows(const T *__restrict__ in, int64_t ld,
                                                 const int32_t *__restrict__ colidx, const int32_t (&bound)[R + 1],
                                                 int sub, int n_chunks, float (&acc)[R][Chunk<T>::kElems])
 {
-    constexpr int E = Chunk<T>::kElems;
     const bool own = sub < n_chunks;
     const int32_t end = bound[R];
     for (int32_t e0 = bound[0]; e0 < end; e0 += G) {
         const int cnt = (end - e0) < G ? (end - e0) : G;
         const int32_t mine = sub < cnt ? colidx[e0 + sub] : 0;
         int j = 0;
-        for (; j + 4 <= cnt; j += 4) {
-            float v[4][E];
-#pragma unroll
-            for (int q = 0; q < 4; ++q) {
-                const T *row = in + int64_t(__shfl(mine, j + q, G)) * ld;
-                if (own) Chunk<T>::load(row + sub * E, v[q]);
-            }
-#pragma unroll
-            for (int q = 0; q < 4; ++q) {
-                const int32_t e = e0 + j + q;
-#pragma unroll
-                for (int r = 0; r < R; ++r) {
-                    const bool hit = e >= bound[r] && e < bound[r + 1];
-                    if (own)
-#pragma unroll
-                        for (int i = 0; i < E; ++i) acc[r][i] += hit ? v[q][i] : 0.0f;
-                }
-            }
-        }
-        for (; j < cnt; ++j) {
-            const T *row = in + int64_t(__shfl(mine, j, G)) * ld;
-            const int32_t e = e0 + j;
-            if (own) {
-                float v[E];
-                Chunk<T>::load(row + sub * E, v);
-#pragma unroll
-                for (int r = 0; r < R; ++r) {
-                    const bool hit = e >= bound[r] && e < bound[r + 1];
-#pragma unroll
-                    for (int i = 0; i < E; ++i) acc[r][i] += hit ? v[i] : 0.0f;
-                }
-            }
-        }
+        if constexpr (G >= 8)
+            for (; j + 8 <= cnt; j += 8) gather_rows_batch<T, G, R, 8>(in, ld, mine, j, e0 + j, bound, sub, own, acc);
+        for (; j + 4 <= cnt; j += 4) gather_rows_batch<T, G, R, 4>(in, ld, mine, j, e0 + j, bound, sub, own, acc);
+        for (; j < cnt; ++j) gather_rows_batch<T, G, R, 1>(in, ld, mine, j, e0 + j, bound, sub, own, acc);
     }
 }
 
 template <typename T, int G, int CPL>
 __global__ __launch_bounds__(kSpmmThreads) void spmm_rows_kernel(int64_t n, const int32_t *__restrict__ rowptr,
                                                                  const int32_t *__restrict__ colidx,
-                                                                 const float *__restrict__ inv_deg,
                                                                  const T *__restrict__ in, int64_t ld_in,
-                                                                 T *__restrict__ out, int64_t ld_out, int n_chunks,
-                                                                 int accumulate)
+                                                                 SpmmOut<T> o, int n_chunks)
 {
     constexpr int E = Chunk<T>::kElems;
     constexpr int NG = kSpmmThreads / G;
@@ -230,7 +255,7 @@ __global__ __launch_bounds__(kSpmmThreads) void spmm_rows_kernel(int64_t n, cons
                 float one[1][E];
 #pragma unroll
                 for (int k = 0; k < E; ++k) one[0][k] = acc[r][k];
-                finish_row<T, G, 1>(v0 + r, inv_deg, out, ld_out, accumulate != 0, sub, n_chunks, one);
+                finish_row<T, G, 1>(v0 + r, o, sub, n_chunks, one);
             }
     } else {
         for (int r = 0; r < R; ++r) {
@@ -246,8 +271,8 @@ __global__ __launch_bounds__(kSpmmThreads) void spmm_rows_kernel(int64_t n, cons
             for (int c = 0; c < CPL; ++c)
 #pragma unroll
                 for (int k = 0; k < E; ++k) acc[c][k] = 0.0f;
-            gather_sum<T, G, CPL>(in, ld_in, colidx, beg, end, G, sub, n_chunks, acc);
-            finish_row<T, G, CPL>(v, inv_deg, out, ld_out, accumulate != 0, sub, n_chunks, acc);
+            gather_sum<T, G, CPL, false>(in, ld_in, colidx, beg, end, G, sub, n_chunks, acc);
+            finish_row<T, G, CPL>(v, o, sub, n_chunks, acc);
         }
     }
     __syncthreads();
@@ -261,7 +286,7 @@ __global__ __launch_bounds__(kSpmmThreads) void spmm_rows_kernel(int64_t n, cons
         for (int c = 0; c < CPL; ++c)
 #pragma unroll
             for (int k = 0; k < E; ++k) acc[c][k] = 0.0f;
-        if (beg + grp * G < end) gather_sum<T, G, CPL>(in, ld_in, colidx, beg + grp * G, end, NG * G, sub, n_chunks, acc);
+        if (beg + grp * G < end) gather_sum<T, G, CPL, true>(in, ld_in, colidx, beg + grp * G, end, NG * G, sub, n_chunks, acc);
 #pragma unroll
         for (int c = 0; c < CPL; ++c)
 #pragma unroll
@@ -276,7 +301,7 @@ __global__ __launch_bounds__(kSpmmThreads) void spmm_rows_kernel(int64_t n, cons
                     for (int g = 0; g < NG; ++g) s += partial[g][(c * G + sub) * E + k];  // fixed order
                     acc[c][k] = s;
                 }
-            finish_row<T, G, CPL>(v, inv_deg, out, ld_out, accumulate != 0, sub, n_chunks, acc);
+            finish_row<T, G, CPL>(v, o, sub, n_chunks, acc);
         }
         __syncthreads();
     }
@@ -286,17 +311,15 @@ __global__ __launch_bounds__(kSpmmThreads) void spmm_rows_kernel(int64_t n, cons
 template <typename T>
 __global__ __launch_bounds__(kSpmmThreads) void spmm_rows_generic_kernel(int64_t n, const int32_t *__restrict__ rowptr,
                                                                          const int32_t *__restrict__ colidx,
-                                                                         const float *__restrict__ inv_deg,
                                                                          const T *__restrict__ in, int64_t ld_in,
-                                                                         T *__restrict__ out, int64_t ld_out, int F,
-                                                                         int accumulate)
+                                                                         SpmmOut<T> o, int F)
 {
     constexpr int kPer = 8;  // elements per lane per sweep: 512 features per sweep
     const int lane = threadIdx.x % kWave;
     const int64_t v = int64_t(blockIdx.x) * (kSpmmThreads / kWave) + threadIdx.x / kWave;
     if (v >= n) return;
     const int32_t beg = rowptr[v], end = rowptr[v + 1];
-    const float scale = inv_deg ? inv_deg[v] : 1.0f;
+    const float scale = o.inv_deg ? o.inv_deg[v] : 1.0f;
     for (int f0 = 0; f0 < F; f0 += kWave * kPer) {
         float acc[kPer];
 #pragma unroll
@@ -313,9 +336,12 @@ __global__ __launch_bounds__(kSpmmThreads) void spmm_rows_generic_kernel(int64_t
         for (int k = 0; k < kPer; ++k) {
             const int f = f0 + k * kWave + lane;
             if (f < F) {
-                T *dst = out + v * ld_out + f;
+                T *dst = o.out + v * o.ld_out + f;
                 float r = acc[k] * scale;
-                if (accumulate) r += load_elem(dst);
+                if (o.accumulate) r += load_elem(dst);
+                if (o.self) r += load_elem(o.self + v * o.ld_self + f);
+                if (o.bias && f < o.F) r += o.bias[f];
+                if (o.relu) r = r > 0.0f ? r : 0.0f;
                 store_elem(dst, r);
             }
         }
@@ -323,35 +349,35 @@ __global__ __launch_bounds__(kSpmmThreads) void spmm_rows_generic_kernel(int64_t
 }
 
 template <typename T, int G, int CPL>
-static void launch_rows(int64_t n, const int32_t *rowptr, const int32_t *colidx, const float *inv_deg, const T *in,
-                        int64_t ld_in, T *out, int64_t ld_out, int n_chunks, bool accumulate, hipStream_t s)
+static void launch_rows(int64_t n, const int32_t *rowptr, const int32_t *colidx, const T *in, int64_t ld_in,
+                        const SpmmOut<T> &o, int n_chunks, hipStream_t s)
 {
     constexpr int RPB = (kSpmmThreads / G) * kRowsPerGroup;
     char name[48];
-    snprintf(name, sizeof(name), "%s_%s_g%dx%d", inv_deg ? "spmm_mean" : "spmm_sum", sizeof(T) == 4 ? "f32" : "bf16", G,
-             CPL);
+    snprintf(name, sizeof(name), "%s_%s_g%dx%d", o.self ? "spmm_combine" : (o.inv_deg ? "spmm_mean" : "spmm_sum"),
+             sizeof(T) == 4 ? "f32" : "bf16", G, CPL);
     TMA_TIMED(name, s);
     hipLaunchKernelGGL((spmm_rows_kernel<T, G, CPL>), dim3(unsigned(ceil_div(n, RPB))), dim3(kSpmmThreads), 0, s, n,
-                       rowptr, colidx, inv_deg, in, ld_in, out, ld_out, n_chunks, accumulate ? 1 : 0);
+                       rowptr, colidx, in, ld_in, o, n_chunks);
 }
 
 template <typename T>
-static int launch_typed(int64_t n, const int32_t *rowptr, const int32_t *colidx, const float *inv_deg, const T *in,
-                        int64_t ld_in, int32_t F, T *out, int64_t ld_out, bool accumulate, hipStream_t s)
+static int launch_typed(int64_t n, const int32_t *rowptr, const int32_t *colidx, const T *in, int64_t ld_in, int32_t F,
+                        const SpmmOut<T> &o, hipStream_t s)
 {
     const size_t row_bytes = size_t(F) * sizeof(T);
     const bool vec_ok = row_bytes % 16 == 0 && (size_t(ld_in) * sizeof(T)) % 16 == 0 &&
-                        (size_t(ld_out) * sizeof(T)) % 16 == 0 && aligned(in, 16) && aligned(out, 16) &&
+                        (size_t(o.ld_out) * sizeof(T)) % 16 == 0 && aligned(in, 16) && aligned(o.out, 16) &&
+                        (!o.self || ((size_t(o.ld_self) * sizeof(T)) % 16 == 0 && aligned(o.self, 16))) &&
                         row_bytes / 16 <= 256;
     if (!vec_ok) {
-        TMA_TIMED(inv_deg ? "spmm_mean_generic" : "spmm_sum_generic", s);
+        TMA_TIMED(o.self ? "spmm_combine_generic" : (o.inv_deg ? "spmm_mean_generic" : "spmm_sum_generic"), s);
         hipLaunchKernelGGL((spmm_rows_generic_kernel<T>), dim3(unsigned(ceil_div(n, kSpmmThreads / kWave))),
-                           dim3(kSpmmThreads), 0, s, n, rowptr, colidx, inv_deg, in, ld_in, out, ld_out, F,
-                           accumulate ? 1 : 0);
+                           dim3(kSpmmThreads), 0, s, n, rowptr, colidx, in, ld_in, o, F);
         return check_launch("spmm (generic)");
     }
     const int nc = int(row_bytes / 16);
-#define TMA_SPMM_CASE(G, CPL) launch_rows<T, G, CPL>(n, rowptr, colidx, inv_deg, in, ld_in, out, ld_out, nc, accumulate, s)
+#define TMA_SPMM_CASE(G, CPL) launch_rows<T, G, CPL>(n, rowptr, colidx, in, ld_in, o, nc, s)
     if (nc <= 4) TMA_SPMM_CASE(4, 1);
     else if (nc <= 8) TMA_SPMM_CASE(8, 1);
     else if (nc <= 16) TMA_SPMM_CASE(16, 1);
@@ -363,18 +389,77 @@ static int launch_typed(int64_t n, const int32_t *rowptr, const int32_t *colidx,
     return check_launch("spmm");
 }
 
+template <typename T>
+static int spmm_any(int64_t n, const int32_t *rowptr, const int32_t *colidx, const float *inv_deg, const void *in,
+                    int64_t ld_in, int32_t F, void *out, int64_t ld_out, bool accumulate, const void *self,
+                    int64_t ld_self, const float *bias, int32_t F_valid, bool relu, hipStream_t stream)
+{
+    SpmmOut<T> o{static_cast<T *>(out), ld_out, inv_deg, accumulate ? 1 : 0, static_cast<const T *>(self), ld_self,
+                 bias, F_valid, relu ? 1 : 0};
+    return launch_typed<T>(n, rowptr, colidx, static_cast<const T *>(in), ld_in, F, o, stream);
+}
+
 int launch_spmm(int64_t n, const int32_t *rowptr, const int32_t *colidx, const float *inv_deg, const void *in,
                 int64_t ld_in, int32_t F, int32_t dtype, void *out, int64_t ld_out, bool accumulate,
                 hipStream_t stream)
 {
+    return launch_spmm_combine(n, rowptr, colidx, inv_deg, in, ld_in, F, dtype, out, ld_out, accumulate, nullptr, 0,
+                               nullptr, F, false, stream);
+}
+
+int launch_spmm_combine(int64_t n, const int32_t *rowptr, const int32_t *colidx, const float *inv_deg, const void *in,
+                        int64_t ld_in, int32_t F, int32_t dtype, void *out, int64_t ld_out, bool accumulate,
+                        const void *self, int64_t ld_self, const float *bias, int32_t F_valid, bool relu,
+                        hipStream_t stream)
+{
     if (n == 0 || F == 0) return TMA_OK;
     if (dtype == TMA_F32)
-        return launch_typed<float>(n, rowptr, colidx, inv_deg, static_cast<const float *>(in), ld_in, F,
-                                   static_cast<float *>(out), ld_out, accumulate, stream);
+        return spmm_any<float>(n, rowptr, colidx, inv_deg, in, ld_in, F, out, ld_out, accumulate, self, ld_self, bias,
+                               F_valid, relu, stream);
     if (dtype == TMA_BF16)
-        return launch_typed<uint16_t>(n, rowptr, colidx, inv_deg, static_cast<const uint16_t *>(in), ld_in, F,
-                                      static_cast<uint16_t *>(out), ld_out, accumulate, stream);
+        return spmm_any<uint16_t>(n, rowptr, colidx, inv_deg, in, ld_in, F, out, ld_out, accumulate, self, ld_self,
+                                  bias, F_valid, relu, stream);
     return fail(TMA_ERR_UNSUPPORTED_DTYPE, "spmm: dtype %d", dtype);
+}
+
+// dst_v = inv_deg[v] * g_v (.) [h_v > 0]   (rows of F elements; padding up to F_pad is zeroed)
+template <typename T>
+__global__ __launch_bounds__(256) void scale_mask_rows_kernel(int64_t n, int F, int F_pad, const T *__restrict__ g,
+                                                              const T *__restrict__ h, int64_t ld,
+                                                              const float *__restrict__ inv_deg, int relu,
+                                                              T *__restrict__ dst, int64_t ld_dst)
+{
+    const int64_t total = n * F_pad;
+    const int64_t stride = int64_t(gridDim.x) * 256;
+    for (int64_t i = int64_t(blockIdx.x) * 256 + threadIdx.x; i < total; i += stride) {
+        const int64_t v = i / F_pad;
+        const int f = int(i - v * F_pad);
+        float r = 0.0f;
+        if (f < F) {
+            r = load_elem(g + v * ld + f) * inv_deg[v];
+            if (relu && !(load_elem(h + v * ld + f) > 0.0f)) r = 0.0f;
+        }
+        store_elem(dst + v * ld_dst + f, r);
+    }
+}
+
+int launch_scale_mask_rows(int64_t n, int32_t F, int32_t F_pad, const void *g, const void *h, int64_t ld,
+                           const float *inv_deg, bool relu, int32_t dtype, void *dst, int64_t ld_dst,
+                           hipStream_t stream)
+{
+    if (n == 0 || F_pad == 0) return TMA_OK;
+    int64_t blocks = ceil_div(n * F_pad, 256);
+    if (blocks > 256 * 32) blocks = 256 * 32;
+    TMA_TIMED("scale_mask_rows", stream);
+    if (dtype == TMA_F32)
+        hipLaunchKernelGGL(scale_mask_rows_kernel<float>, dim3(unsigned(blocks)), dim3(256), 0, stream, n, F, F_pad,
+                           static_cast<const float *>(g), static_cast<const float *>(h), ld, inv_deg, relu ? 1 : 0,
+                           static_cast<float *>(dst), ld_dst);
+    else
+        hipLaunchKernelGGL(scale_mask_rows_kernel<uint16_t>, dim3(unsigned(blocks)), dim3(256), 0, stream, n, F, F_pad,
+                           static_cast<const uint16_t *>(g), static_cast<const uint16_t *>(h), ld, inv_deg,
+                           relu ? 1 : 0, static_cast<uint16_t *>(dst), ld_dst);
+    return check_launch("scale_mask_rows");
 }
 
 }  // namespace tma
