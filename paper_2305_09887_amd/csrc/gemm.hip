@@ -615,7 +615,7 @@ struct SplitEpilogue {  // partial products, one slab per split
 // of its next one.
 // ---------------------------------------------------------------------------
 template <int BM, int BN, int BK, int WM, int WN, bool kColSum, class AL, class BL, class Epi>
-__global__ __launch_bounds__(WM *WN * 64, 2) void gemm_f32_kernel(AL a, BL b, Epi epi, int64_t M, int N, int64_t K,
+__global__ __launch_bounds__(WM *WN * 64, (BK <= 16 ? 3 : 2)) void gemm_f32_kernel(AL a, BL b, Epi epi, int64_t M, int N, int64_t K,
                                                                  int64_t k_per_split, int n_tiles,
                                                                  int64_t tiles_per_split, int64_t total_work,
                                                                  float *__restrict__ colsum_partial)
@@ -914,9 +914,12 @@ static void launch_gemm(const char *name, const AL &a, const BL &b, const Epi &e
     const int n_tiles = int(ceil_div(N, BN));
     const int64_t tiles = ceil_div(M, BM) * n_tiles;
     const int64_t total = tiles * n_splits;
-    // two resident blocks per compute unit (LDS and register budget of the kernel), 256 units in 8 dies
+    // resident blocks per compute unit follow from the kernel's LDS footprint (160 KB per unit) and its
+    // register budget (launch bounds); 256 units in 8 dies
+    constexpr int kLdsBytes = 2 * 4 * ((AL::kContigK ? BM * (BK + kPad) : BK * (BM + kPad)) + (BL::kContigK ? BN * (BK + kPad) : BK * (BN + kPad)));
+    constexpr int kPerCu = (BK <= 16 && kLdsBytes <= 53 * 1024) ? 3 : 2;
     int64_t blocks_per_die = ceil_div(total, kXcds);
-    if (blocks_per_die > 64) blocks_per_die = 64;
+    if (blocks_per_die > 32 * kPerCu) blocks_per_die = 32 * kPerCu;
     TMA_TIMED(name, s);
     hipLaunchKernelGGL((gemm_f32_kernel<BM, BN, BK, WM, WN, kColSum, AL, BL, Epi>), dim3(unsigned(blocks_per_die * kXcds)),
                        dim3(WM * WN * 64), 0, s, a, b, e, M, N, K, k_per_split, n_tiles, tiles, total, colsum_partial);
@@ -944,7 +947,7 @@ static void fwd_dispatch(int64_t n, const T *H, int64_t ldh, const T *M, int F_i
         launch_gemm<128, 64, 32, 4, 1, false>(kname<T>("gemm_fwd_128x64", "gemm_fwd_128x64_generic", "gemm_fwd_128x64_bf16", "gemm_fwd_128x64_bf16_generic", VA),
                                               a, b, e, n, F_out, K, kps, 1, nullptr, s);
     else
-        launch_gemm<128, 128, 32, 2, 2, false>(kname<T>("gemm_fwd_128x128", "gemm_fwd_128x128_generic", "gemm_fwd_128x128_bf16", "gemm_fwd_128x128_bf16_generic", VA),
+        launch_gemm<128, 128, 16, 2, 2, false>(kname<T>("gemm_fwd_128x128", "gemm_fwd_128x128_generic", "gemm_fwd_128x128_bf16", "gemm_fwd_128x128_bf16_generic", VA),
                                                a, b, e, n, F_out, K, kps, 1, nullptr, s);
 }
 
@@ -1077,7 +1080,7 @@ static void bwd_weight_dispatch(int64_t n, const T *H, int64_t ldh, const T *M, 
         launch_gemm<128, 64, 32, 4, 1, true>(kname<T>("gemm_bwd_weight_128x64", "gemm_bwd_weight_128x64_generic", "gemm_bwd_weight_128x64_bf16", "gemm_bwd_weight_128x64_bf16_generic", V),
                                              a, b, e, Mtot, F_out, n, w.k_per_split, w.n_splits, colsum, s);
     else
-        launch_gemm<128, 128, 32, 2, 2, true>(kname<T>("gemm_bwd_weight_128x128", "gemm_bwd_weight_128x128_generic", "gemm_bwd_weight_128x128_bf16", "gemm_bwd_weight_128x128_bf16_generic", V),
+        launch_gemm<128, 128, 16, 2, 2, true>(kname<T>("gemm_bwd_weight_128x128", "gemm_bwd_weight_128x128_generic", "gemm_bwd_weight_128x128_bf16", "gemm_bwd_weight_128x128_bf16_generic", V),
                                               a, b, e, Mtot, F_out, n, w.k_per_split, w.n_splits, colsum, s);
 }
 
