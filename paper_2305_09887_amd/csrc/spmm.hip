@@ -2,17 +2,26 @@
 // the plain row gather-sum used by the backward pass.  HBM/gather bound: the
 // flops (2 per gathered element) are negligible.
 //
-// Mapping.  A feature row is cut into 16-byte chunks; G lanes (a power of two,
-// the smallest that covers the row, at most the 64-lane wavefront) own one row
-// and each lane keeps its chunk(s) of the running sum in registers, so every
-// neighbour row is fetched with one coalesced 16-byte load per lane.  The G
-// lanes read up to G neighbour ids with one coalesced load and pass them round
-// by cross-lane shuffle.  Local graphs under random assignment are very sparse
-// (mean local degree 2-5) with a power-law tail, so rows are binned by degree
-// inside the block: a row of more than kHubDegree entries is deferred and then
-// summed by all groups of the workgroup together, each taking every NG-th run
-// of G neighbours, with a fixed-order combine through LDS.  The result of a
-// row depends only on its own neighbour list, never on scheduling.
+// Mapping.  A feature row is cut into 16-byte chunks; G lanes (one per chunk; any
+// G up to the 64-lane wavefront, 64 / G rows share a wavefront) own one row and
+// each lane keeps its chunk of the running sum in registers, so every neighbour
+// row is fetched with one coalesced 16-byte load per lane.
+//
+// Local graphs under random assignment are very sparse (mean local degree 2-5)
+// with a power-law tail.  Two things follow.  (1) A row is too short to hide a
+// memory latency by itself, so a lane group walks through its rows as one
+// stream of steps of up to four neighbours and runs that stream as a three-stage
+// pipeline: the neighbour ids of step s+2, the feature loads of step s+1 and the
+// additions of step s are in flight together, across row boundaries.  (2) A
+// group can only pull a few loads per latency, so a long row would become the
+// tail of the launch: rows longer than a threshold (a multiple of the mean
+// degree) are deferred and then summed by all groups of the workgroup together,
+// each taking one contiguous share, with a fixed-order combine through LDS.  The
+// result of a row depends only on its own neighbour list, never on scheduling.
+//
+// Every load in the pipeline is issued unconditionally (an unused slot repeats an
+// address that was just fetched): the wait counters are then exact and a wait for
+// step s never also waits for the loads of step s+1.
 #include "kernels.hpp"
 
 namespace tma {
@@ -32,6 +41,10 @@ struct Chunk<float> {
         const float4 x = *reinterpret_cast<const float4 *>(p);
         v[0] = x.x; v[1] = x.y; v[2] = x.z; v[3] = x.w;
     }
+    static __device__ __forceinline__ void widen(const uint4 &x, float (&v)[4])
+    {
+        v[0] = __uint_as_float(x.x); v[1] = __uint_as_float(x.y); v[2] = __uint_as_float(x.z); v[3] = __uint_as_float(x.w);
+    }
     static __device__ __forceinline__ void store(float *p, const float (&v)[4])
     {
         *reinterpret_cast<float4 *>(p) = make_float4(v[0], v[1], v[2], v[3]);
@@ -43,7 +56,10 @@ struct Chunk<uint16_t> {  // bf16 storage
     static constexpr int kElems = 8;
     static __device__ __forceinline__ void load(const uint16_t *p, float (&v)[8])
     {
-        const uint4 x = *reinterpret_cast<const uint4 *>(p);
+        widen(*reinterpret_cast<const uint4 *>(p), v);
+    }
+    static __device__ __forceinline__ void widen(const uint4 &x, float (&v)[8])
+    {
         const uint32_t w[4] = {x.x, x.y, x.z, x.w};
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
@@ -164,55 +180,267 @@ __device__ __forceinline__ void finish_row(int64_t v, const SpmmOut<T> &o, int s
         }
 }
 
-// Adds the rows colidx[e], e in [beg, end), into the accumulators of up to four consecutive
-// CSR rows at once: entry e belongs to row r when bound[r] <= e < bound[r+1].  The entries
-// of consecutive rows are contiguous in colidx, so the group walks them as one list with
-// four independent 16-byte loads in flight, and steers each loaded chunk to its row by
-// predication (adding 0 elsewhere).  At a mean local degree of 2-5 this is what keeps
-// enough bytes in flight; walking the rows one after the other leaves the lanes waiting.
-template <typename T, int G, int R, int U>
-__device__ __forceinline__ void gather_rows_batch(const T *__restrict__ in, int64_t ld, int32_t mine, int j, int32_t e_first,
-                                                  const int32_t (&bound)[R + 1], int sub, bool own,
-                                                  float (&acc)[R][Chunk<T>::kElems])
+// ---------------------------------------------------------------------------------------------------
+// Rows of at most 64 chunks: the streaming kernel.
+
+constexpr int kStreamU = 4;              // neighbours per step
+constexpr int kMinDefer = 24;            // rows up to this length are never deferred
+constexpr int kDeferFactor = 4;          // ... nor rows up to this multiple of the mean degree
+constexpr int kMaxRowsPerBlock = 1024;   // rows of one workgroup (row bounds and deferred-row list sit in LDS)
+constexpr int kPartialBytes = 16384;     // LDS for the partial sums of deferred rows
+
+// One step of a group's stream: add the rows ids[lo .. hi) (hi - lo <= kStreamU) to the running sum of
+// segment `seg`; `last` closes the segment.  seg < 0: nothing left (the loads of such a step are dummies).
+struct Step {
+    int32_t lo, hi, seg;
+    bool last;
+};
+
+template <int U>
+__device__ __forceinline__ void issue_ids(const int32_t *__restrict__ ids, int32_t last_entry, const Step &s,
+                                          int32_t (&I)[U])
+{
+    // an unused slot repeats the step's last entry; a step without entries reads any valid entry
+    const int32_t filler = s.hi > s.lo ? s.hi - 1 : (s.lo < last_entry ? s.lo : last_entry);
+#pragma unroll
+    for (int q = 0; q < U; ++q) I[q] = ids[s.lo + q < s.hi ? s.lo + q : filler];
+}
+
+template <typename T, int U>
+__device__ __forceinline__ void issue_gathers(const T *__restrict__ in, int64_t ld, const Step &s,
+                                              const int32_t (&I)[U], int32_t &recent, int sub, uint4 (&V)[U])
 {
     constexpr int E = Chunk<T>::kElems;
-    float v[U][E];
 #pragma unroll
     for (int q = 0; q < U; ++q) {
-        const T *row = in + int64_t(__shfl(mine, j + q, G)) * ld;
-        if (own) Chunk<T>::load(row + sub * E, v[q]);
-    }
-#pragma unroll
-    for (int q = 0; q < U; ++q) {
-        const int32_t e = e_first + q;
-#pragma unroll
-        for (int r = 0; r < R; ++r) {
-            const bool hit = e >= bound[r] && e < bound[r + 1];
-            if (own)
-#pragma unroll
-                for (int i = 0; i < E; ++i) acc[r][i] += hit ? v[q][i] : 0.0f;
-        }
+        recent = s.lo + q < s.hi ? I[q] : recent;   // unused slot: a row this group fetched a moment ago
+        V[q] = *reinterpret_cast<const uint4 *>(in + int64_t(recent) * ld + sub * E);
     }
 }
 
-template <typename T, int G, int R>
-__device__ __forceinline__ void gather_sum_rows(const T *__restrict__ in, int64_t ld,
-                                                const int32_t *__restrict__ colidx, const int32_t (&bound)[R + 1],
-                                                int sub, int n_chunks, float (&acc)[R][Chunk<T>::kElems])
+template <typename T, int U>
+__device__ __forceinline__ void consume(const Step &s, const uint4 (&V)[U], float (&acc)[Chunk<T>::kElems])
 {
-    const bool own = sub < n_chunks;
-    const int32_t end = bound[R];
-    for (int32_t e0 = bound[0]; e0 < end; e0 += G) {
-        const int cnt = (end - e0) < G ? (end - e0) : G;
-        const int32_t mine = sub < cnt ? colidx[e0 + sub] : 0;
-        int j = 0;
-        if constexpr (G >= 8)
-            for (; j + 8 <= cnt; j += 8) gather_rows_batch<T, G, R, 8>(in, ld, mine, j, e0 + j, bound, sub, own, acc);
-        for (; j + 4 <= cnt; j += 4) gather_rows_batch<T, G, R, 4>(in, ld, mine, j, e0 + j, bound, sub, own, acc);
-        for (; j < cnt; ++j) gather_rows_batch<T, G, R, 1>(in, ld, mine, j, e0 + j, bound, sub, own, acc);
+    constexpr int E = Chunk<T>::kElems;
+#pragma unroll
+    for (int q = 0; q < U; ++q) {
+        float v[E];
+        Chunk<T>::widen(V[q], v);
+        const bool used = s.lo + q < s.hi;
+#pragma unroll
+        for (int i = 0; i < E; ++i) acc[i] += used ? v[i] : 0.0f;
     }
 }
 
+// What a row's output needs besides the sum, fetched together with the row's last gathers.
+struct RowExtra {
+    float scale;
+    uint4 raw;
+};
+
+// Runs the steps that `gen` hands out through the ids -> gathers -> additions pipeline.  `extra(seg, X)`
+// issues the loads a closing step needs (or nothing); `emit(seg, acc, X)` takes a finished segment.
+template <typename T, typename Gen, typename Extra, typename Emit>
+__device__ __forceinline__ void stream_segments(const T *__restrict__ in, int64_t ld, const int32_t *__restrict__ ids,
+                                                int32_t last_entry, int sub, int32_t recent, Gen &&gen, Extra &&extra,
+                                                Emit &&emit)
+{
+    constexpr int E = Chunk<T>::kElems;
+    constexpr int U = kStreamU;
+    int32_t I0[U], I1[U];
+    uint4 V0[U], V1[U];
+    RowExtra X0, X1;
+    float acc[E];
+#pragma unroll
+    for (int i = 0; i < E; ++i) acc[i] = 0.0f;
+
+    Step a = gen();
+    issue_ids<U>(ids, last_entry, a, I0);
+    Step b = gen();
+    issue_ids<U>(ids, last_entry, b, I1);
+    issue_gathers<T, U>(in, ld, a, I0, recent, sub, V0);
+    extra(a.seg, X0);
+    // entering a half: step a has its gathers in flight (V0/X0 in the first half), step b its ids (I1)
+    auto half = [&](int32_t (&Ia)[U], int32_t (&Ib)[U], uint4 (&Va)[U], uint4 (&Vb)[U], RowExtra &Xa,
+                    RowExtra &Xb) __attribute__((always_inline)) {
+        const Step c = gen();
+        issue_ids<U>(ids, last_entry, c, Ia);
+        issue_gathers<T, U>(in, ld, b, Ib, recent, sub, Vb);
+        extra(b.seg, Xb);
+        consume<T, U>(a, Va, acc);
+        if (a.last) {
+            emit(a.seg, acc, Xa);
+#pragma unroll
+            for (int i = 0; i < E; ++i) acc[i] = 0.0f;
+        }
+        a = b;
+        b = c;
+    };
+    while (a.seg >= 0) {
+        half(I0, I1, V0, V1, X0, X1);
+        if (a.seg < 0) break;
+        half(I1, I0, V1, V0, X1, X0);
+    }
+}
+
+// kExtra: 0 = nothing, 1 = "+ self_v", 2 = "+ out_v" (accumulate).  kScale: multiply by inv_deg[v].
+template <typename T, int kExtra, bool kScale>
+__global__ __launch_bounds__(kSpmmThreads) void spmm_stream_kernel(int64_t n, const int32_t *__restrict__ rowptr,
+                                                                   const int32_t *__restrict__ colidx,
+                                                                   const T *__restrict__ in, int64_t ld_in,
+                                                                   SpmmOut<T> o, int G, int rows_per_group,
+                                                                   int min_defer)
+{
+    constexpr int E = Chunk<T>::kElems;
+    constexpr int U = kStreamU;
+    constexpr int kHubsPerPass = kPartialBytes / (kSpmmThreads * E * int(sizeof(float)));
+    __shared__ int32_t bounds[kMaxRowsPerBlock + 1];   // rowptr of the workgroup's rows
+    __shared__ int32_t deferred[kMaxRowsPerBlock];
+    __shared__ int32_t n_deferred;
+    __shared__ int32_t total_entries;
+    __shared__ float partial[kPartialBytes / sizeof(float)];
+
+    const int lane = threadIdx.x % kWave;
+    const int gpw = kWave / G;                       // groups per wavefront
+    const int gl = lane / G;
+    const bool live = gl < gpw;                      // lanes past the last whole group idle
+    const int sub = lane - gl * G;
+    const int NG = (kSpmmThreads / kWave) * gpw;
+    const int grp = (threadIdx.x / kWave) * gpw + gl;
+
+    const int rows_per_block = NG * rows_per_group;  // <= kMaxRowsPerBlock
+    const int64_t base = int64_t(blockIdx.x) * rows_per_block;
+    const int block_rows = int((n - base) < rows_per_block ? (n - base) : rows_per_block);   // >= 1
+    for (int i = threadIdx.x; i <= block_rows; i += kSpmmThreads) bounds[i] = rowptr[base + i];
+    if (threadIdx.x == 0) {
+        n_deferred = 0;
+        total_entries = rowptr[n];
+    }
+    __syncthreads();
+    const int32_t nnz = total_entries;
+    const int32_t *ids = nnz > 0 ? colidx : rowptr;   // readable at index 0 even without entries
+    const int32_t last_entry = nnz > 0 ? nnz - 1 : 0;
+    const int64_t by_mean = int64_t(kDeferFactor) * (int64_t(nnz) / n);
+    const int32_t defer_above = by_mean > min_defer ? int32_t(by_mean < INT32_MAX ? by_mean : INT32_MAX) : min_defer;
+
+    // ---- the group's own rows, block-local indices [r, r_end)
+    int r = live ? grp * rows_per_group : block_rows;
+    const int r_end = (r + rows_per_group) < block_rows ? (r + rows_per_group) : block_rows;
+    const int r_first = r < block_rows ? r : 0;
+    int32_t e = r < r_end ? bounds[r] : 0;
+    bool fresh = true;
+    auto next_row_step = [&]() {
+        Step s{0, 0, -1, false};
+        while (r < r_end) {
+            const int32_t end = bounds[r + 1];
+            if (fresh && end - e > defer_above) {
+                if (sub == 0) deferred[atomicAdd(&n_deferred, 1)] = r;
+                ++r;
+                e = end;
+                continue;
+            }
+            s.seg = r;
+            s.lo = e;
+            s.hi = (end - e > U) ? e + U : end;
+            s.last = s.hi == end;
+            e = s.hi;
+            fresh = s.last;
+            if (s.last) ++r;
+            break;
+        }
+        return s;
+    };
+    auto row_extra = [&](int32_t seg, RowExtra &X) {
+        const int64_t v = base + (seg >= 0 ? seg : r_first);
+        if constexpr (kScale) X.scale = o.inv_deg[v];
+        if constexpr (kExtra == 1) X.raw = *reinterpret_cast<const uint4 *>(o.self + v * o.ld_self + sub * E);
+        if constexpr (kExtra == 2) X.raw = *reinterpret_cast<const uint4 *>(o.out + v * o.ld_out + sub * E);
+    };
+    auto finish = [&](int32_t seg, const float (&acc)[E], const RowExtra &X) {
+        const int64_t v = base + seg;
+        const int f0 = sub * E;
+        float res[E];
+#pragma unroll
+        for (int i = 0; i < E; ++i) res[i] = kScale ? acc[i] * X.scale : acc[i];
+        if constexpr (kExtra != 0) {
+            float x[E];
+            Chunk<T>::widen(X.raw, x);
+#pragma unroll
+            for (int i = 0; i < E; ++i) res[i] += x[i];
+        }
+        if (o.bias) {
+#pragma unroll
+            for (int i = 0; i < E; ++i) res[i] += (f0 + i < o.F) ? o.bias[f0 + i] : 0.0f;
+        }
+        if (o.relu) {
+#pragma unroll
+            for (int i = 0; i < E; ++i) res[i] = res[i] > 0.0f ? res[i] : 0.0f;
+        }
+        Chunk<T>::store(o.out + v * o.ld_out + f0, res);
+    };
+    stream_segments<T>(in, ld_in, ids, last_entry, sub, int32_t(base + r_first), next_row_step, row_extra, finish);
+    __syncthreads();
+
+    // ---- deferred rows, kHubsPerPass at a time: group g sums the g-th share of each, then a fixed-order combine
+    const int n_hubs = n_deferred;
+    const int width = G * E;                         // floats of one partial row
+    for (int h0 = 0; h0 < n_hubs; h0 += kHubsPerPass) {
+        const int h_end = (h0 + kHubsPerPass) < n_hubs ? (h0 + kHubsPerPass) : n_hubs;
+        if (live) {
+            int h = h0;
+            int32_t pos = 0, stop = 0;
+            bool open = false;
+            auto next_share_step = [&]() {
+                Step s{0, 0, -1, false};
+                if (h >= h_end) return s;
+                if (!open) {
+                    const int row = deferred[h];
+                    const int32_t beg = bounds[row], end = bounds[row + 1];
+                    const int32_t share = int32_t((int64_t(end - beg) + int64_t(NG) * U - 1) / (int64_t(NG) * U)) * U;
+                    const int64_t lo = int64_t(beg) + int64_t(grp) * share;
+                    pos = lo < end ? int32_t(lo) : end;
+                    stop = (lo + share) < end ? int32_t(lo + share) : end;
+                    open = true;
+                }
+                s.seg = h - h0;
+                s.lo = pos;
+                s.hi = (stop - pos > U) ? pos + U : stop;
+                s.last = s.hi == stop;
+                pos = s.hi;
+                if (s.last) {
+                    ++h;
+                    open = false;
+                }
+                return s;
+            };
+            auto no_extra = [](int32_t, RowExtra &) {};
+            auto to_lds = [&](int32_t seg, const float (&acc)[E], const RowExtra &) {
+#pragma unroll
+                for (int i = 0; i < E; ++i) partial[(seg * NG + grp) * width + sub * E + i] = acc[i];
+            };
+            stream_segments<T>(in, ld_in, ids, last_entry, sub, int32_t(base + r_first), next_share_step, no_extra,
+                               to_lds);
+        }
+        __syncthreads();
+        if (live && grp < h_end - h0) {
+            const int64_t v = base + deferred[h0 + grp];
+            float acc[E];
+#pragma unroll
+            for (int i = 0; i < E; ++i) acc[i] = 0.0f;
+            for (int g = 0; g < NG; ++g)   // fixed order
+#pragma unroll
+                for (int i = 0; i < E; ++i) acc[i] += partial[(grp * NG + g) * width + sub * E + i];
+            float one[1][E];
+#pragma unroll
+            for (int i = 0; i < E; ++i) one[0][i] = acc[i];
+            finish_row<T, 1, 1>(v, o, sub, G, one);
+        }
+        __syncthreads();
+    }
+}
+
+// Rows wider than 64 chunks (1 KB): the whole wavefront owns one row, CPL chunks per lane; rows one after
+// the other, rows of more than kHubDegree entries by the whole workgroup.
 template <typename T, int G, int CPL>
 __global__ __launch_bounds__(kSpmmThreads) void spmm_rows_kernel(int64_t n, const int32_t *__restrict__ rowptr,
                                                                  const int32_t *__restrict__ colidx,
@@ -235,45 +463,21 @@ __global__ __launch_bounds__(kSpmmThreads) void spmm_rows_kernel(int64_t n, cons
     // the group owns R consecutive rows v0 .. v0+R-1
     const int64_t base = int64_t(blockIdx.x) * RPB;
     const int64_t v0 = base + int64_t(grp) * R;
-    int32_t bound[R + 1];
-#pragma unroll
-    for (int r = 0; r <= R; ++r) bound[r] = rowptr[(v0 + r) < n ? (v0 + r) : n];
-    bool any_hub = false;
-#pragma unroll
-    for (int r = 0; r < R; ++r) any_hub = any_hub || (bound[r + 1] - bound[r] > kHubDegree);
-
-    if (CPL == 1 && !any_hub) {
-        float acc[R][E];
-#pragma unroll
-        for (int r = 0; r < R; ++r)
-#pragma unroll
-            for (int k = 0; k < E; ++k) acc[r][k] = 0.0f;
-        gather_sum_rows<T, G, R>(in, ld_in, colidx, bound, sub, n_chunks, acc);
-#pragma unroll
-        for (int r = 0; r < R; ++r)
-            if (v0 + r < n) {
-                float one[1][E];
-#pragma unroll
-                for (int k = 0; k < E; ++k) one[0][k] = acc[r][k];
-                finish_row<T, G, 1>(v0 + r, o, sub, n_chunks, one);
-            }
-    } else {
-        for (int r = 0; r < R; ++r) {
-            const int64_t v = v0 + r;
-            if (v >= n) break;
-            const int32_t beg = bound[r], end = bound[r + 1];
-            if (end - beg > kHubDegree) {
-                if (sub == 0) hub_rows[atomicAdd(&hub_count, 1)] = int32_t(v - base);
-                continue;
-            }
-            float acc[CPL][E];
-#pragma unroll
-            for (int c = 0; c < CPL; ++c)
-#pragma unroll
-                for (int k = 0; k < E; ++k) acc[c][k] = 0.0f;
-            gather_sum<T, G, CPL, false>(in, ld_in, colidx, beg, end, G, sub, n_chunks, acc);
-            finish_row<T, G, CPL>(v, o, sub, n_chunks, acc);
+    for (int r = 0; r < R; ++r) {
+        const int64_t v = v0 + r;
+        if (v >= n) break;
+        const int32_t beg = rowptr[v], end = rowptr[v + 1];
+        if (end - beg > kHubDegree) {
+            if (sub == 0) hub_rows[atomicAdd(&hub_count, 1)] = int32_t(v - base);
+            continue;
         }
+        float acc[CPL][E];
+#pragma unroll
+        for (int c = 0; c < CPL; ++c)
+#pragma unroll
+            for (int k = 0; k < E; ++k) acc[c][k] = 0.0f;
+        gather_sum<T, G, CPL, false>(in, ld_in, colidx, beg, end, G, sub, n_chunks, acc);
+        finish_row<T, G, CPL>(v, o, sub, n_chunks, acc);
     }
     __syncthreads();
 
@@ -349,8 +553,8 @@ __global__ __launch_bounds__(kSpmmThreads) void spmm_rows_generic_kernel(int64_t
 }
 
 template <typename T, int G, int CPL>
-static void launch_rows(int64_t n, const int32_t *rowptr, const int32_t *colidx, const T *in, int64_t ld_in,
-                        const SpmmOut<T> &o, int n_chunks, hipStream_t s)
+static void launch_wide_rows(int64_t n, const int32_t *rowptr, const int32_t *colidx, const T *in, int64_t ld_in,
+                             const SpmmOut<T> &o, int n_chunks, hipStream_t s)
 {
     constexpr int RPB = (kSpmmThreads / G) * kRowsPerGroup;
     char name[48];
@@ -361,6 +565,24 @@ static void launch_rows(int64_t n, const int32_t *rowptr, const int32_t *colidx,
                        rowptr, colidx, in, ld_in, o, n_chunks);
 }
 
+template <typename T, int kExtra, bool kScale>
+static void launch_stream(int64_t n, const int32_t *rowptr, const int32_t *colidx, const T *in, int64_t ld_in,
+                          const SpmmOut<T> &o, int G, hipStream_t s)
+{
+    // rows per group: long enough a stream for the pipeline to pay, short enough to leave the chip
+    // several workgroups per compute unit
+    const int NG = (kSpmmThreads / kWave) * (kWave / G);
+    int64_t rpg = ceil_div(n, int64_t(NG) * 256 * 6);
+    rpg = rpg < 4 ? 4 : (rpg > 8 ? 8 : rpg);
+    if (rpg * NG > kMaxRowsPerBlock) rpg = kMaxRowsPerBlock / NG;
+    char name[48];
+    snprintf(name, sizeof(name), "%s_%s_g%dx1", kExtra == 1 ? "spmm_combine" : (kScale ? "spmm_mean" : "spmm_sum"),
+             sizeof(T) == 4 ? "f32" : "bf16", G);
+    TMA_TIMED(name, s);
+    hipLaunchKernelGGL((spmm_stream_kernel<T, kExtra, kScale>), dim3(unsigned(ceil_div(n, rpg * NG))),
+                       dim3(kSpmmThreads), 0, s, n, rowptr, colidx, in, ld_in, o, G, int(rpg), kMinDefer);
+}
+
 template <typename T>
 static int launch_typed(int64_t n, const int32_t *rowptr, const int32_t *colidx, const T *in, int64_t ld_in, int32_t F,
                         const SpmmOut<T> &o, hipStream_t s)
@@ -369,7 +591,7 @@ static int launch_typed(int64_t n, const int32_t *rowptr, const int32_t *colidx,
     const bool vec_ok = row_bytes % 16 == 0 && (size_t(ld_in) * sizeof(T)) % 16 == 0 &&
                         (size_t(o.ld_out) * sizeof(T)) % 16 == 0 && aligned(in, 16) && aligned(o.out, 16) &&
                         (!o.self || ((size_t(o.ld_self) * sizeof(T)) % 16 == 0 && aligned(o.self, 16))) &&
-                        row_bytes / 16 <= 256;
+                        row_bytes / 16 <= 256 && !(o.self && o.accumulate);
     if (!vec_ok) {
         TMA_TIMED(o.self ? "spmm_combine_generic" : (o.inv_deg ? "spmm_mean_generic" : "spmm_sum_generic"), s);
         hipLaunchKernelGGL((spmm_rows_generic_kernel<T>), dim3(unsigned(ceil_div(n, kSpmmThreads / kWave))),
@@ -377,15 +599,24 @@ static int launch_typed(int64_t n, const int32_t *rowptr, const int32_t *colidx,
         return check_launch("spmm (generic)");
     }
     const int nc = int(row_bytes / 16);
-#define TMA_SPMM_CASE(G, CPL) launch_rows<T, G, CPL>(n, rowptr, colidx, in, ld_in, o, nc, s)
-    if (nc <= 4) TMA_SPMM_CASE(4, 1);
-    else if (nc <= 8) TMA_SPMM_CASE(8, 1);
-    else if (nc <= 16) TMA_SPMM_CASE(16, 1);
-    else if (nc <= 32) TMA_SPMM_CASE(32, 1);
-    else if (nc <= 64) TMA_SPMM_CASE(64, 1);
-    else if (nc <= 128) TMA_SPMM_CASE(64, 2);
-    else TMA_SPMM_CASE(64, 4);
-#undef TMA_SPMM_CASE
+    if (nc <= 64) {
+        const int extra = o.self ? 1 : (o.accumulate ? 2 : 0);
+#define TMA_SPMM_STREAM(X, S) launch_stream<T, X, S>(n, rowptr, colidx, in, ld_in, o, nc, s)
+        if (o.inv_deg) {
+            if (extra == 0) TMA_SPMM_STREAM(0, true);
+            else if (extra == 1) TMA_SPMM_STREAM(1, true);
+            else TMA_SPMM_STREAM(2, true);
+        } else {
+            if (extra == 0) TMA_SPMM_STREAM(0, false);
+            else if (extra == 1) TMA_SPMM_STREAM(1, false);
+            else TMA_SPMM_STREAM(2, false);
+        }
+#undef TMA_SPMM_STREAM
+    } else if (nc <= 128) {
+        launch_wide_rows<T, 64, 2>(n, rowptr, colidx, in, ld_in, o, nc, s);
+    } else {
+        launch_wide_rows<T, 64, 4>(n, rowptr, colidx, in, ld_in, o, nc, s);
+    }
     return check_launch("spmm");
 }
 

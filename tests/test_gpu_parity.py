@@ -161,7 +161,7 @@ def _local_graph(n, m, seed, K=2, kind="uniform"):
     return oracle.induced_subgraph(rowptr, colidx, part, 0)
 
 
-@pytest.mark.parametrize("F", [1, 3, 16, 47, 64, 100, 128, 256, 260, 512, 1024])
+@pytest.mark.parametrize("F", [1, 3, 4, 12, 16, 20, 47, 48, 64, 84, 100, 128, 252, 256, 260, 512, 1024])
 def test_mean_aggregate_feature_widths(B, F):
     sub = _local_graph(6000, 24_000, seed=F)
     n = len(sub["l2g"])
@@ -191,6 +191,55 @@ def test_mean_aggregate_hub_rows_padded_rows_and_isolated(B):
     B.tma_mean_aggregate(dev(sub["rowptr"]), dev(sub["colidx"]), dev(sub["inv_deg"], torch.float32), buf[:, :F],
                          out=out2[:, :F])
     assert torch.equal(out[:, :F], out2[:, :F])
+
+
+def _csr_from_degrees(deg, n_cols, seed):
+    rng = np.random.default_rng(seed)
+    rowptr = np.zeros(len(deg) + 1, dtype=np.int32)
+    rowptr[1:] = np.cumsum(deg)
+    return rowptr, rng.integers(0, n_cols, int(rowptr[-1])).astype(np.int32)
+
+
+@pytest.mark.parametrize("F,bf16", [(48, False), (128, False), (256, False), (16, False), (104, True), (256, True)])
+@pytest.mark.parametrize("shape", ["hub_cluster", "dense_uniform", "threshold_lengths", "no_entries", "one_long_row"])
+def test_mean_aggregate_degree_structures(B, F, bf16, shape):
+    """Degree patterns that steer rows through every path of the aggregation kernel: rows streamed by their
+    own lane group (steps of four neighbours, rows of 0, 1..4, 5.. entries), rows deferred to the whole
+    workgroup (more of them in one workgroup than one pass holds, shares that are empty or ragged), long rows
+    that stay with their group because the whole graph is dense, and a graph without any entry."""
+    n = 3000
+    rng = np.random.default_rng(F)
+    if shape == "hub_cluster":        # 40 neighbouring long rows in a sea of short ones
+        deg = rng.integers(0, 4, n)
+        deg[100:140] = rng.integers(150, 900, 40)
+        deg[2999] = 333
+    elif shape == "dense_uniform":    # mean degree 50: the deferral threshold follows the mean
+        deg = rng.integers(40, 61, n)
+        deg[7] = 0
+    elif shape == "threshold_lengths":
+        deg = rng.integers(0, 3, n)
+        deg[::7] = np.resize([3, 4, 5, 8, 9, 23, 24, 25, 26, 31, 32, 33, 63, 64, 65, 127, 129], len(deg[::7]))
+    elif shape == "no_entries":
+        deg = np.zeros(n, dtype=np.int64)
+    else:
+        deg = np.zeros(n, dtype=np.int64)
+        deg[1234] = 20_001
+    rowptr, colidx = _csr_from_degrees(deg, n, seed=F + len(shape))
+    inv = np.where(deg > 0, 1.0 / np.maximum(deg, 1), 0.0).astype(np.float32)
+    H = synth.features(n, F, seed=5)
+    col = dev(colidx) if len(colidx) else torch.zeros(0, dtype=torch.int32, device="cuda")
+    if bf16:
+        H = synth.round_bf16(H)
+        bits = synth.to_bf16_bits(H).reshape(H.shape)
+        Hd = torch.from_numpy(bits.view(np.int16)).cuda().view(torch.bfloat16)
+        tol = 2e-2
+    else:
+        Hd, tol = dev(H), TOL_F32
+    got = B.tma_mean_aggregate(dev(rowptr), col, dev(inv), Hd)
+    want = oracle.mean_aggregate(rowptr, colidx, H)
+    assert_close(got.float().cpu().numpy(), want, tol=tol, what=f"M {shape} F={F} bf16={bf16}")
+    again = B.tma_mean_aggregate(dev(rowptr), col, dev(inv), Hd)
+    assert torch.equal(got, again)
 
 
 def test_mean_aggregate_empty(B):
