@@ -89,9 +89,13 @@ int tma_partition(int64_t n_nodes, const int32_t *cluster, int64_t n_clusters,
  *         than 2^31-1 kept entries also give TMA_ERR_BAD_SHAPE.
  * _fill   writes colidx_loc_out [nnz_loc] and inv_deg_out [n_loc]
  *         (1/local degree in fp32, 0 for a node without local neighbours);
- *         asynchronous.
- * Workspace: tma_induced_subgraph_workspace_bytes(n_nodes, cap_n_loc) bytes,
- * 256-byte aligned, for _count only.
+ *         asynchronous.  It takes the g2l and rowptr_loc that _count wrote and
+ *         the SAME workspace and cap_n_loc, untouched since that call: _count
+ *         leaves there a membership bitmap and every local row's bounds in the
+ *         global CSR, which is why _fill needs neither rowptr, part nor l2g.
+ * Workspace: tma_induced_subgraph_workspace_bytes(n_nodes, cap_n_loc) bytes
+ * (about n_nodes/8 + 32 * cap_n_loc), 256-byte aligned, shared by the two
+ * calls of one extraction.
  * ---------------------------------------------------------------------- */
 size_t tma_induced_subgraph_workspace_bytes(int64_t n_nodes, int64_t cap_n_loc);
 
@@ -101,11 +105,23 @@ int tma_induced_subgraph_count(int64_t n_nodes, const int64_t *rowptr, const int
                                int64_t cap_n_loc, int64_t *h_n_loc, int64_t *h_nnz_loc,
                                void *ws, size_t ws_bytes, tma_stream_t stream);
 
-int tma_induced_subgraph_fill(int64_t n_nodes, const int64_t *rowptr, const int32_t *colidx,
-                              const int32_t *part, int32_t p,
-                              const int32_t *g2l, const int32_t *l2g, int64_t n_loc,
-                              const int32_t *rowptr_loc,
-                              int32_t *colidx_loc_out, float *inv_deg_out, tma_stream_t stream);
+/* Both calls in one, for a caller that brings buffers of a capacity it chose
+ * (colidx_loc_out [cap_nnz_loc], inv_deg_out [cap_n_loc], the others as for
+ * _count): no return to the caller between the host wait and the second
+ * pass.  TMA_ERR_BAD_SHAPE, with the sizes reported, if either capacity is
+ * too small (nothing is then written to colidx_loc_out / inv_deg_out). */
+int tma_induced_subgraph(int64_t n_nodes, const int64_t *rowptr, const int32_t *colidx,
+                         const int32_t *part, int32_t p,
+                         int32_t *g2l_out, int32_t *l2g_out, int32_t *rowptr_loc_out,
+                         int32_t *colidx_loc_out, float *inv_deg_out,
+                         int64_t cap_n_loc, int64_t cap_nnz_loc,
+                         int64_t *h_n_loc, int64_t *h_nnz_loc,
+                         void *ws, size_t ws_bytes, tma_stream_t stream);
+
+int tma_induced_subgraph_fill(int64_t n_nodes, const int32_t *colidx,
+                              const int32_t *g2l, int64_t n_loc, const int32_t *rowptr_loc,
+                              int32_t *colidx_loc_out, float *inv_deg_out,
+                              int64_t cap_n_loc, const void *ws, size_t ws_bytes, tma_stream_t stream);
 
 /* ------------------------------------------------------------------------
  * Mean aggregation with the row-normalised adjacency (paper Thm. 1 and the

@@ -21,6 +21,7 @@ TMA_ACT_NONE, TMA_ACT_RELU = 0, 1
 EXPORTS = (
     "tma_version", "tma_last_error", "tma_partition",
     "tma_induced_subgraph_workspace_bytes", "tma_induced_subgraph_count", "tma_induced_subgraph_fill",
+    "tma_induced_subgraph",
     "tma_mean_aggregate", "tma_sage_layer_aggregates_first", "tma_sage_layer_fwd",
     "tma_sage_layer_bwd_workspace_bytes", "tma_sage_layer_bwd",
     "tma_loss_workspace_bytes", "tma_softmax_ce", "tma_sigmoid_l2", "tma_sgd_step", "tma_average",
@@ -125,8 +126,11 @@ def tma_partition(n_nodes: int, K: int, seed: int, cluster=None, n_clusters: int
     return out
 
 
-def tma_induced_subgraph(rowptr, colidx, part, p: int, cap_n_loc: int | None = None, stream=None):
-    """Both calls of the extraction.  Returns dict(g2l, l2g, rowptr, colidx, inv_deg, n_loc, nnz_loc)."""
+def tma_induced_subgraph(rowptr, colidx, part, p: int, cap_n_loc: int | None = None, cap_nnz_loc: int | None = None,
+                         stream=None):
+    """The extraction.  Returns dict(g2l, l2g, rowptr, colidx, inv_deg, n_loc, nnz_loc).  With both capacities
+    given every buffer is allocated up front and the library makes both passes in one call; otherwise the
+    entry list is allocated between the passes, at its exact size."""
     n = rowptr.numel() - 1
     if part.numel() != n:
         raise TmaError("tma_induced_subgraph: part must have one entry per node")
@@ -141,16 +145,26 @@ def tma_induced_subgraph(rowptr, colidx, part, p: int, cap_n_loc: int | None = N
     l2g = torch.empty(max(cap, 1), dtype=torch.int32, device=dev)
     rp = torch.empty(cap + 1, dtype=torch.int32, device=dev)
     n_loc, nnz_loc = C.c_int64(0), C.c_int64(0)
-    _check(L.tma_induced_subgraph_count(
-        C.c_int64(n), _ptr(rowptr, torch.int64, "rowptr"), _ptr(colidx, torch.int32, "colidx"),
-        _ptr(part, torch.int32, "part"), C.c_int32(p), _ptr(g2l), _ptr(l2g), _ptr(rp), C.c_int64(cap),
-        C.byref(n_loc), C.byref(nnz_loc), _ptr(ws), C.c_size_t(ws.numel()), _stream(stream)))
-    n_loc, nnz_loc = n_loc.value, nnz_loc.value
-    ci = torch.empty(max(nnz_loc, 1), dtype=torch.int32, device=dev)
-    inv = torch.empty(max(n_loc, 1), dtype=torch.float32, device=dev)
-    _check(L.tma_induced_subgraph_fill(
-        C.c_int64(n), _ptr(rowptr), _ptr(colidx), _ptr(part), C.c_int32(p), _ptr(g2l), _ptr(l2g),
-        C.c_int64(n_loc), _ptr(rp), _ptr(ci), _ptr(inv), _stream(stream)))
+    if cap_nnz_loc is not None:
+        ci = torch.empty(max(int(cap_nnz_loc), 1), dtype=torch.int32, device=dev)
+        inv = torch.empty(max(cap, 1), dtype=torch.float32, device=dev)
+        _check(L.tma_induced_subgraph(
+            C.c_int64(n), _ptr(rowptr, torch.int64, "rowptr"), _ptr(colidx, torch.int32, "colidx"),
+            _ptr(part, torch.int32, "part"), C.c_int32(p), _ptr(g2l), _ptr(l2g), _ptr(rp), _ptr(ci), _ptr(inv),
+            C.c_int64(cap), C.c_int64(int(cap_nnz_loc)), C.byref(n_loc), C.byref(nnz_loc), _ptr(ws),
+            C.c_size_t(ws.numel()), _stream(stream)))
+        n_loc, nnz_loc = n_loc.value, nnz_loc.value
+    else:
+        _check(L.tma_induced_subgraph_count(
+            C.c_int64(n), _ptr(rowptr, torch.int64, "rowptr"), _ptr(colidx, torch.int32, "colidx"),
+            _ptr(part, torch.int32, "part"), C.c_int32(p), _ptr(g2l), _ptr(l2g), _ptr(rp), C.c_int64(cap),
+            C.byref(n_loc), C.byref(nnz_loc), _ptr(ws), C.c_size_t(ws.numel()), _stream(stream)))
+        n_loc, nnz_loc = n_loc.value, nnz_loc.value
+        ci = torch.empty(max(nnz_loc, 1), dtype=torch.int32, device=dev)
+        inv = torch.empty(max(n_loc, 1), dtype=torch.float32, device=dev)
+        _check(L.tma_induced_subgraph_fill(
+            C.c_int64(n), _ptr(colidx), _ptr(g2l), C.c_int64(n_loc), _ptr(rp), _ptr(ci), _ptr(inv), C.c_int64(cap),
+            _ptr(ws), C.c_size_t(ws.numel()), _stream(stream)))
     return dict(g2l=g2l[:n], l2g=l2g[:n_loc], rowptr=rp[:n_loc + 1], colidx=ci[:nnz_loc], inv_deg=inv[:n_loc],
                 n_loc=n_loc, nnz_loc=nnz_loc)
 

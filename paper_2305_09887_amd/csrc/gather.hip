@@ -37,7 +37,7 @@ static int launch_gather(int64_t n_loc, const int32_t *l2g, const void *src, int
     // about 2048 words (8 per thread) per block
     int64_t rows_per_block = 2048 / words;
     if (rows_per_block < 1) rows_per_block = 1;
-    TMA_TIMED("gather_rows", s);
+    TMA_TIMED(sizeof(W) == 16 ? "gather_rows_w16" : (sizeof(W) == 4 ? "gather_rows_w4" : "gather_rows_w1"), s);
     hipLaunchKernelGGL(gather_rows_kernel<W>, dim3(unsigned(ceil_div(n_loc, rows_per_block))), dim3(256), 0, s, n_loc,
                        l2g, static_cast<const char *>(src), src_ld, int32_t(words), int32_t(rows_per_block),
                        static_cast<char *>(dst), dst_ld);

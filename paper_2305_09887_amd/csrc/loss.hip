@@ -25,38 +25,75 @@ __device__ __forceinline__ float block_sum_256(float v)
 }
 
 // Sixteen lanes per node (coalesced row reads): log-sum-exp, loss term,
-// gradient (softmax - onehot)/n.  The row is read three times; it stays in L1.
+// gradient (softmax - onehot)/n.  kRegs > 0: the row (C <= 16 * kRegs) is read once and kept in
+// registers, one exp per element; kRegs = 0: any C, the row is read three times (it stays in L1).
+// A block walks over several groups of 16 rows so that the number of partial loss sums stays small.
 constexpr int kCeLanes = 16;
 constexpr int kCeRows = 256 / kCeLanes;
+constexpr int kCeMaxBlocks = 2048;
 
-template <typename T>
+template <typename T, int kRegs>
 __global__ __launch_bounds__(256) void softmax_ce_kernel(int64_t n, int C, const T *__restrict__ logits, int64_t ld_in,
                                                          const int32_t *__restrict__ labels,
                                                          T *__restrict__ dlogits, float *__restrict__ block_loss)
 {
     const int sub = threadIdx.x % kCeLanes;
-    const int64_t v = int64_t(blockIdx.x) * kCeRows + threadIdx.x / kCeLanes;
+    const float inv_n = 1.0f / float(n);
     float term = 0.0f;
-    const bool live = v < n;
-    const T *z = logits + (live ? v : 0) * ld_in;
-    float mx = -INFINITY;
-    if (live)
-        for (int c = sub; c < C; c += kCeLanes) mx = fmaxf(mx, ld(z + c));
+    for (int64_t v0 = int64_t(blockIdx.x) * kCeRows; v0 < n; v0 += int64_t(gridDim.x) * kCeRows) {
+        const int64_t v = v0 + threadIdx.x / kCeLanes;
+        const bool live = v < n;
+        const T *z = logits + (live ? v : 0) * ld_in;
+        if constexpr (kRegs > 0) {
+            float zr[kRegs];
+            float mx = -INFINITY;
 #pragma unroll
-    for (int d = kCeLanes / 2; d >= 1; d >>= 1) mx = fmaxf(mx, __shfl_xor(mx, d, kWave));
-    float se = 0.0f;
-    if (live)
-        for (int c = sub; c < C; c += kCeLanes) se += expf(ld(z + c) - mx);
+            for (int k = 0; k < kRegs; ++k) {
+                const int c = sub + k * kCeLanes;
+                zr[k] = (live && c < C) ? ld(z + c) : -INFINITY;
+                mx = fmaxf(mx, zr[k]);
+            }
 #pragma unroll
-    for (int d = kCeLanes / 2; d >= 1; d >>= 1) se += __shfl_xor(se, d, kWave);
-    if (live) {
-        const float lse = mx + logf(se);
-        const int y = labels[v];
-        if (sub == 0) term = lse - ld(z + y);
-        if (dlogits) {
-            const float inv_n = 1.0f / float(n);
-            for (int c = sub; c < C; c += kCeLanes)
-                st(dlogits + v * ld_in + c, (expf(ld(z + c) - lse) - (c == y ? 1.0f : 0.0f)) * inv_n);
+            for (int d = kCeLanes / 2; d >= 1; d >>= 1) mx = fmaxf(mx, __shfl_xor(mx, d, kWave));
+            float ex[kRegs];
+            float se = 0.0f;
+#pragma unroll
+            for (int k = 0; k < kRegs; ++k) {
+                ex[k] = (live && sub + k * kCeLanes < C) ? expf(zr[k] - mx) : 0.0f;
+                se += ex[k];
+            }
+#pragma unroll
+            for (int d = kCeLanes / 2; d >= 1; d >>= 1) se += __shfl_xor(se, d, kWave);
+            if (live) {
+                const int y = labels[v];
+                const float lse = mx + logf(se);
+                const float inv_se = 1.0f / se;
+#pragma unroll
+                for (int k = 0; k < kRegs; ++k) {
+                    const int c = sub + k * kCeLanes;
+                    if (c == y) term += lse - zr[k];
+                    if (dlogits && c < C) st(dlogits + v * ld_in + c, (ex[k] * inv_se - (c == y ? 1.0f : 0.0f)) * inv_n);
+                }
+            }
+        } else {
+            float mx = -INFINITY;
+            if (live)
+                for (int c = sub; c < C; c += kCeLanes) mx = fmaxf(mx, ld(z + c));
+#pragma unroll
+            for (int d = kCeLanes / 2; d >= 1; d >>= 1) mx = fmaxf(mx, __shfl_xor(mx, d, kWave));
+            float se = 0.0f;
+            if (live)
+                for (int c = sub; c < C; c += kCeLanes) se += expf(ld(z + c) - mx);
+#pragma unroll
+            for (int d = kCeLanes / 2; d >= 1; d >>= 1) se += __shfl_xor(se, d, kWave);
+            if (live) {
+                const float lse = mx + logf(se);
+                const int y = labels[v];
+                if (sub == 0) term += lse - ld(z + y);
+                if (dlogits)
+                    for (int c = sub; c < C; c += kCeLanes)
+                        st(dlogits + v * ld_in + c, (expf(ld(z + c) - lse) - (c == y ? 1.0f : 0.0f)) * inv_n);
+            }
         }
     }
     const float s = block_sum_256(term);
@@ -153,17 +190,23 @@ extern "C" int tma_softmax_ce(int64_t n, int32_t C, const void *logits, int64_t 
     TMA_REQUIRE(n == 0 || labels, TMA_ERR_INVALID_ARG, "%s: labels is NULL", fn);
     hipStream_t s = as_stream(stream);
     float *block_loss = static_cast<float *>(ws);
-    const int64_t nb = n > 0 ? ceil_div(n, kCeRows) : 0;
+    int64_t nb = n > 0 ? ceil_div(n, kCeRows) : 0;
+    if (nb > kCeMaxBlocks) nb = kCeMaxBlocks;
     if (nb > 0) {
         TMA_TIMED("softmax_ce", s);
-        if (dtype == TMA_F32)
-            hipLaunchKernelGGL(softmax_ce_kernel<float>, dim3(unsigned(nb)), dim3(256), 0, s, n, C,
-                               static_cast<const float *>(logits), ldz, labels, static_cast<float *>(dlogits_out),
-                               block_loss);
-        else
-            hipLaunchKernelGGL(softmax_ce_kernel<uint16_t>, dim3(unsigned(nb)), dim3(256), 0, s, n, C,
-                               static_cast<const uint16_t *>(logits), ldz, labels,
-                               static_cast<uint16_t *>(dlogits_out), block_loss);
+#define TMA_CE(T, R)                                                                                              \
+    hipLaunchKernelGGL((softmax_ce_kernel<T, R>), dim3(unsigned(nb)), dim3(256), 0, s, n, C,                      \
+                       static_cast<const T *>(logits), ldz, labels, static_cast<T *>(dlogits_out), block_loss)
+        if (dtype == TMA_F32) {
+            if (C <= 2 * kCeLanes) TMA_CE(float, 2);
+            else if (C <= 4 * kCeLanes) TMA_CE(float, 4);
+            else TMA_CE(float, 0);
+        } else {
+            if (C <= 2 * kCeLanes) TMA_CE(uint16_t, 2);
+            else if (C <= 4 * kCeLanes) TMA_CE(uint16_t, 4);
+            else TMA_CE(uint16_t, 0);
+        }
+#undef TMA_CE
     }
     TMA_TIMED("finish_loss", s);
     hipLaunchKernelGGL(finish_loss_kernel, dim3(1), dim3(256), 0, s, nb, block_loss, n > 0 ? 1.0f / float(n) : 0.0f,

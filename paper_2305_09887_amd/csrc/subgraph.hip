@@ -6,6 +6,12 @@
 // inter-block waiting, and a per-row order-preserving compaction that uses
 // wavefront ballots.  Sixteen lanes share one global row (global average
 // degree of the workloads is about 20), four rows per wavefront.
+//
+// The flag scan also leaves, for the two passes over the local rows, a
+// membership bitmap (one bit per global node: 1/32 of the bytes of the id map,
+// so the random look-ups per entry stay in cache) and each local row's bounds in
+// the global CSR in local order (read coalesced instead of through l2g ->
+// rowptr).  Only entries that are kept go on to the id map.
 #include "common.hpp"
 
 namespace tma {
@@ -22,14 +28,28 @@ struct FlagIn {  // 1 where the node belongs to partition p
     int32_t p;
     __device__ int32_t load(int64_t i) const { return part[i] == p ? 1 : 0; }
 };
-struct FlagOut {  // local id = exclusive rank; inverse map for the first `cap` local nodes
+struct FlagOut {  // local id = exclusive rank; inverse map, row bounds for the first `cap` local nodes; bitmap
     int32_t *g2l;
     int32_t *l2g;
     int64_t cap;
+    const int64_t *rowptr;
+    int64_t *row_beg;
+    int32_t *row_len;
+    uint8_t *member;
     __device__ void store(int64_t i, int64_t prefix, int32_t v, int64_t /*n*/) const
     {
         g2l[i] = v ? int32_t(prefix) : -1;
-        if (v && prefix < cap) l2g[prefix] = int32_t(i);
+        if (v && prefix < cap) {
+            l2g[prefix] = int32_t(i);
+            const int64_t b = rowptr[i];
+            row_beg[prefix] = b;
+            row_len[prefix] = int32_t(rowptr[i + 1] - b);
+        }
+    }
+    // the eight flags of one thread's consecutive items (first item = bit 0) are one byte of the bitmap
+    __device__ void store_flags(int64_t first, uint32_t bits, int64_t n) const
+    {
+        if (first < n) member[first >> 3] = uint8_t(bits);
     }
 };
 struct DegIn {
@@ -43,6 +63,7 @@ struct DegOut {  // rowptr_loc[i] = exclusive prefix, rowptr_loc[n] = total
         rowptr_loc[i] = int32_t(prefix);
         if (i == n - 1) rowptr_loc[n] = int32_t(prefix + v);
     }
+    __device__ void store_flags(int64_t, uint32_t, int64_t) const {}
 };
 
 __device__ __forceinline__ int64_t effective_n(const int64_t *d_n, int64_t cap)
@@ -96,8 +117,10 @@ __global__ __launch_bounds__(kScanThreads) void scan_reduce_kernel(const int64_t
 // One block turns the per-block sums into exclusive offsets and stores the
 // grand total.  nb is at most a few 10^4 (10^8 nodes / 2048).
 __global__ __launch_bounds__(1024) void scan_sums_kernel(int64_t nb, int64_t *__restrict__ block_sums,
-                                                         int64_t *__restrict__ total_out)
+                                                         int64_t *__restrict__ total_out, int32_t *first_out)
 {
+    // first_out: rowptr_loc[0] = 0 also when the partition is empty (the apply kernel then stores nothing)
+    if (threadIdx.x == 0 && first_out) *first_out = 0;
     __shared__ int64_t wave_sums[1024 / kWave];
     __shared__ int64_t carry_s;
     const int lane = threadIdx.x & (kWave - 1);
@@ -135,13 +158,17 @@ __global__ __launch_bounds__(kScanThreads) void scan_apply_kernel(const int64_t 
 {
     const int64_t n = effective_n(d_n, cap);
     const int64_t base = int64_t(blockIdx.x) * kScanTile + int64_t(threadIdx.x) * kScanItems;
+    static_assert(kScanItems == 8, "one thread's flags are one byte of the bitmap");
     int32_t v[kScanItems];
     int32_t c = 0;
+    uint32_t bits = 0;
 #pragma unroll
     for (int j = 0; j < kScanItems; ++j) {
         v[j] = (base + j < n) ? in.load(base + j) : 0;
         c += v[j];
+        bits |= (v[j] != 0 ? 1u : 0u) << j;
     }
+    out.store_flags(base, bits, n);
     int32_t total;
     int64_t prefix = block_offsets[blockIdx.x] + block_exclusive_scan(c, total);
 #pragma unroll
@@ -151,8 +178,10 @@ __global__ __launch_bounds__(kScanThreads) void scan_apply_kernel(const int64_t 
     }
 }
 
-// rowptr_loc[0] = 0 also when the partition is empty (the apply kernel then stores nothing).
-__global__ void write_zero_kernel(int32_t *p) { *p = 0; }
+__device__ __forceinline__ int member_bit(const uint32_t *__restrict__ member, int32_t u)
+{
+    return int((member[uint32_t(u) >> 5] >> (uint32_t(u) & 31u)) & 1u);
+}
 
 // Global rows longer than this are scanned by the whole workgroup instead of 16 lanes
 // (power-law graphs: a few rows hold thousands of entries and would otherwise set the kernel's tail).
@@ -160,10 +189,10 @@ constexpr int kHubRow = 128;
 
 // Kept degree of every local row: entries whose column is local too.
 __global__ __launch_bounds__(256) void row_count_kernel(const int64_t *d_n_loc, int64_t cap,
-                                                        const int32_t *__restrict__ l2g,
-                                                        const int64_t *__restrict__ rowptr,
+                                                        const int64_t *__restrict__ row_beg,
+                                                        const int32_t *__restrict__ row_len,
                                                         const int32_t *__restrict__ colidx,
-                                                        const int32_t *__restrict__ g2l,
+                                                        const uint32_t *__restrict__ member,
                                                         int32_t *__restrict__ deg)
 {
     __shared__ int32_t hub_rows[kRowsPerBlock];
@@ -179,13 +208,18 @@ __global__ __launch_bounds__(256) void row_count_kernel(const int64_t *d_n_loc, 
     int32_t c = 0;
     bool light = false;
     if (i < n_loc) {
-        const int64_t v = l2g[i];
-        const int64_t beg = rowptr[v], end = rowptr[v + 1];
-        if (end - beg > kHubRow) {
+        const int64_t beg = row_beg[i];
+        const int32_t len = row_len[i];
+        if (len > kHubRow) {
             if (sub == 0) hub_rows[atomicAdd(&hub_count, 1)] = int32_t(i - row0);
         } else {
             light = true;
-            for (int64_t e = beg + sub; e < end; e += kRowLanes) c += g2l[colidx[e]] >= 0 ? 1 : 0;
+            int32_t off = sub;
+            for (; off + kRowLanes < len; off += 2 * kRowLanes) {   // two index -> bit chains in flight
+                const int32_t u0 = colidx[beg + off], u1 = colidx[beg + off + kRowLanes];
+                c += member_bit(member, u0) + member_bit(member, u1);
+            }
+            if (off < len) c += member_bit(member, colidx[beg + off]);
         }
     }
 #pragma unroll
@@ -196,16 +230,14 @@ __global__ __launch_bounds__(256) void row_count_kernel(const int64_t *d_n_loc, 
     const int n_hubs = hub_count;
     for (int h = 0; h < n_hubs; ++h) {
         const int64_t ih = row0 + hub_rows[h];
-        const int64_t v = l2g[ih];
-        const int64_t end = rowptr[v + 1];
+        const int64_t end = row_beg[ih] + row_len[ih];
         int32_t ch = 0;
-        int64_t e = rowptr[v] + threadIdx.x;
-        for (; e + 3 * 256 < end; e += 4 * 256) {  // four independent index -> flag chains in flight
+        int64_t e = row_beg[ih] + threadIdx.x;
+        for (; e + 3 * 256 < end; e += 4 * 256) {  // four independent index -> bit chains in flight
             const int32_t u0 = colidx[e], u1 = colidx[e + 256], u2 = colidx[e + 512], u3 = colidx[e + 768];
-            const int32_t f0 = g2l[u0], f1 = g2l[u1], f2 = g2l[u2], f3 = g2l[u3];
-            ch += (f0 >= 0) + (f1 >= 0) + (f2 >= 0) + (f3 >= 0);
+            ch += member_bit(member, u0) + member_bit(member, u1) + member_bit(member, u2) + member_bit(member, u3);
         }
-        for (; e < end; e += 256) ch += g2l[colidx[e]] >= 0 ? 1 : 0;
+        for (; e < end; e += 256) ch += member_bit(member, colidx[e]);
 #pragma unroll
         for (int d = kWave / 2; d >= 1; d >>= 1) ch += __shfl_xor(ch, d, kWave);
         if ((threadIdx.x & (kWave - 1)) == 0) wave_part[threadIdx.x / kWave] = ch;
@@ -216,9 +248,10 @@ __global__ __launch_bounds__(256) void row_count_kernel(const int64_t *d_n_loc, 
 }
 
 // Order-preserving compaction of each local row into colidx_loc, relabelled.
-__global__ __launch_bounds__(256) void row_fill_kernel(int64_t n_loc, const int32_t *__restrict__ l2g,
-                                                       const int64_t *__restrict__ rowptr,
+__global__ __launch_bounds__(256) void row_fill_kernel(int64_t n_loc, const int64_t *__restrict__ row_beg,
+                                                       const int32_t *__restrict__ row_len,
                                                        const int32_t *__restrict__ colidx,
+                                                       const uint32_t *__restrict__ member,
                                                        const int32_t *__restrict__ g2l,
                                                        const int32_t *__restrict__ rowptr_loc,
                                                        int32_t *__restrict__ colidx_loc,
@@ -234,38 +267,48 @@ __global__ __launch_bounds__(256) void row_fill_kernel(int64_t n_loc, const int3
     const int group_shift = ((threadIdx.x % kWave) / kRowLanes) * kRowLanes;
     const int64_t row0 = int64_t(blockIdx.x) * kRowsPerBlock;
     const int64_t i = row0 + threadIdx.x / kRowLanes;
-    int64_t beg = 0, end = 0;
+    int64_t beg = 0;
+    int32_t len = 0;
     int32_t out = 0;
     if (i < n_loc) {
-        const int64_t v = l2g[i];
-        beg = rowptr[v];
-        end = rowptr[v + 1];
+        beg = row_beg[i];
+        len = row_len[i];
         out = rowptr_loc[i];
         if (sub == 0) {
             const int32_t d = rowptr_loc[i + 1] - out;
             inv_deg[i] = d > 0 ? 1.0f / float(d) : 0.0f;
         }
-        if (end - beg > kHubRow) {  // left to the whole workgroup below
+        if (len > kHubRow) {  // left to the whole workgroup below
             if (sub == 0) hub_rows[atomicAdd(&hub_count, 1)] = int32_t(i - row0);
-            end = beg;
+            len = 0;
         }
     }
     // Every lane of the wavefront runs the same number of rounds so that the
     // ballot below is executed by all of them.
-    int64_t len = end - beg;
+    int32_t rounds = len;
 #pragma unroll
     for (int d = kRowLanes; d < kWave; d <<= 1) {
-        int64_t o = __shfl_xor(len, d, kWave);
-        len = o > len ? o : len;
+        int32_t o = __shfl_xor(rounds, d, kWave);
+        rounds = o > rounds ? o : rounds;
     }
-    for (int64_t off = 0; off < len; off += kRowLanes) {
-        const int64_t e = beg + off + sub;
-        int32_t lid = -1;
-        if (e < end) lid = g2l[colidx[e]];
-        const uint64_t ballot = __ballot(lid >= 0);
-        const uint32_t mine = uint32_t(ballot >> group_shift) & ((1u << kRowLanes) - 1u);
-        if (lid >= 0) colidx_loc[out + __popc(mine & ((1u << sub) - 1u))] = lid;
-        out += __popc(mine);
+    // two runs of kRowLanes entries per round: both index -> bit -> id chains are in flight together
+    for (int32_t off = 0; off < rounds; off += 2 * kRowLanes) {
+        int32_t u0 = -1, u1 = -1;
+        if (off + sub < len) u0 = colidx[beg + off + sub];
+        if (off + kRowLanes + sub < len) u1 = colidx[beg + off + kRowLanes + sub];
+        const bool keep0 = u0 >= 0 && member_bit(member, u0) != 0;
+        const bool keep1 = u1 >= 0 && member_bit(member, u1) != 0;
+        int32_t lid0 = 0, lid1 = 0;
+        if (keep0) lid0 = g2l[u0];
+        if (keep1) lid1 = g2l[u1];
+        const uint64_t ballot0 = __ballot(keep0);
+        const uint64_t ballot1 = __ballot(keep1);
+        const uint32_t mine0 = uint32_t(ballot0 >> group_shift) & ((1u << kRowLanes) - 1u);
+        const uint32_t mine1 = uint32_t(ballot1 >> group_shift) & ((1u << kRowLanes) - 1u);
+        if (keep0) colidx_loc[out + __popc(mine0 & ((1u << sub) - 1u))] = lid0;
+        out += __popc(mine0);
+        if (keep1) colidx_loc[out + __popc(mine1 & ((1u << sub) - 1u))] = lid1;
+        out += __popc(mine1);
     }
     __syncthreads();
 
@@ -273,17 +316,17 @@ __global__ __launch_bounds__(256) void row_fill_kernel(int64_t n_loc, const int3
     const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
     for (int h = 0; h < n_hubs; ++h) {
         const int64_t ih = row0 + hub_rows[h];
-        const int64_t v = l2g[ih];
-        const int64_t hbeg = rowptr[v], hend = rowptr[v + 1];
+        const int64_t hbeg = row_beg[ih], hend = hbeg + row_len[ih];
         int32_t hout = rowptr_loc[ih];
-        int32_t lid_next = -1;
-        if (hbeg + threadIdx.x < hend) lid_next = g2l[colidx[hbeg + threadIdx.x]];
+        int32_t u_next = -1;
+        if (hbeg + threadIdx.x < hend) u_next = colidx[hbeg + threadIdx.x];
         for (int64_t off = 0; off < hend - hbeg; off += 256) {   // 256 entries per round, order kept
-            const int32_t lid = lid_next;
+            const int32_t u = u_next;
             const int64_t en = hbeg + off + 256 + threadIdx.x;   // next round's entry is fetched during this one
-            lid_next = -1;
-            if (en < hend) lid_next = g2l[colidx[en]];
-            const uint64_t ballot = __ballot(lid >= 0);
+            u_next = -1;
+            if (en < hend) u_next = colidx[en];
+            const bool keep = u >= 0 && member_bit(member, u) != 0;
+            const uint64_t ballot = __ballot(keep);
             if (lane == 0) wave_part[wave] = __popcll(ballot);
             __syncthreads();
             int32_t before = 0, total = 0;
@@ -293,7 +336,7 @@ __global__ __launch_bounds__(256) void row_fill_kernel(int64_t n_loc, const int3
                 if (w < wave) before += t;
                 total += t;
             }
-            if (lid >= 0) colidx_loc[hout + before + __popcll(ballot & ((1ull << lane) - 1ull))] = lid;
+            if (keep) colidx_loc[hout + before + __popcll(ballot & ((1ull << lane) - 1ull))] = g2l[u];
             hout += total;
             __syncthreads();
         }
@@ -305,6 +348,9 @@ struct CountWorkspace {
     int64_t *row_block_sums;   // [nb_rows]
     int64_t *sizes;            // [2] n_loc, nnz_loc
     int32_t *deg;              // [cap_n_loc]
+    int64_t *row_beg;          // [cap_n_loc] first entry of the local row in the global CSR
+    int32_t *row_len;          // [cap_n_loc] its global degree
+    uint32_t *member;          // bit v = node v belongs to the partition
     size_t bytes;
 };
 
@@ -323,6 +369,12 @@ static CountWorkspace carve(void *ws, int64_t n_nodes, int64_t cap)
     off += 256;
     w.deg = reinterpret_cast<int32_t *>(p + off);
     off += round_up(size_t(cap > 0 ? cap : 1) * 4, 256);
+    w.row_beg = reinterpret_cast<int64_t *>(p + off);
+    off += round_up(size_t(cap > 0 ? cap : 1) * 8, 256);
+    w.row_len = reinterpret_cast<int32_t *>(p + off);
+    off += round_up(size_t(cap > 0 ? cap : 1) * 4, 256);
+    w.member = reinterpret_cast<uint32_t *>(p + off);
+    off += round_up(size_t(n_nodes > 0 ? n_nodes : 1) / 8 + 8, 256);
     w.bytes = off;
     return w;
 }
@@ -359,7 +411,7 @@ extern "C" int tma_induced_subgraph_count(int64_t n_nodes, const int64_t *rowptr
     const unsigned nb_nodes = unsigned(ceil_div(n_nodes > 0 ? n_nodes : 1, kScanTile));
     const unsigned nb_rows = unsigned(ceil_div(cap_n_loc > 0 ? cap_n_loc : 1, kScanTile));
     FlagIn fin{part, p};
-    FlagOut fout{g2l_out, l2g_out, cap_n_loc};
+    FlagOut fout{g2l_out, l2g_out, cap_n_loc, rowptr, w.row_beg, w.row_len, reinterpret_cast<uint8_t *>(w.member)};
     // 1. rank local nodes
     {
         TMA_TIMED("scan_reduce_flags", s);
@@ -369,7 +421,7 @@ extern "C" int tma_induced_subgraph_count(int64_t n_nodes, const int64_t *rowptr
     {
         TMA_TIMED("scan_sums", s);
         hipLaunchKernelGGL(scan_sums_kernel, dim3(1), dim3(1024), 0, s, int64_t(nb_nodes), w.node_block_sums,
-                           w.sizes + 0);
+                           w.sizes + 0, rowptr_loc_out);
     }
     {
         TMA_TIMED("scan_apply_flags", s);
@@ -377,12 +429,11 @@ extern "C" int tma_induced_subgraph_count(int64_t n_nodes, const int64_t *rowptr
                            n_nodes, fin, fout, w.node_block_sums);
     }
     // 2. kept degree per local row, then rowptr_loc by a second scan
-    hipLaunchKernelGGL(write_zero_kernel, dim3(1), dim3(1), 0, s, rowptr_loc_out);
     if (cap_n_loc > 0) {
         const unsigned row_blocks = unsigned(ceil_div(cap_n_loc, kRowsPerBlock));
         TMA_TIMED("row_count", s);
-        hipLaunchKernelGGL(row_count_kernel, dim3(row_blocks), dim3(256), 0, s, w.sizes + 0, cap_n_loc, l2g_out,
-                           rowptr, colidx, g2l_out, w.deg);
+        hipLaunchKernelGGL(row_count_kernel, dim3(row_blocks), dim3(256), 0, s, w.sizes + 0, cap_n_loc, w.row_beg,
+                           w.row_len, colidx, w.member, w.deg);
     }
     DegIn din{w.deg};
     DegOut dout{rowptr_loc_out};
@@ -394,7 +445,7 @@ extern "C" int tma_induced_subgraph_count(int64_t n_nodes, const int64_t *rowptr
     {
         TMA_TIMED("scan_sums", s);
         hipLaunchKernelGGL(scan_sums_kernel, dim3(1), dim3(1024), 0, s, int64_t(nb_rows), w.row_block_sums,
-                           w.sizes + 1);
+                           w.sizes + 1, static_cast<int32_t *>(nullptr));
     }
     {
         TMA_TIMED("scan_apply_deg", s);
@@ -404,8 +455,9 @@ extern "C" int tma_induced_subgraph_count(int64_t n_nodes, const int64_t *rowptr
     if (int rc = check_launch(fn)) return rc;
 
     int64_t h_sizes[2] = {0, 0};
-    TMA_HIP_TRY(hipMemcpyAsync(h_sizes, w.sizes, sizeof(h_sizes), hipMemcpyDeviceToHost, s), fn);
-    TMA_HIP_TRY(hipStreamSynchronize(s), fn);
+    // copy in stream order and wait for it (one call: measurably shorter than an asynchronous copy
+    // followed by a stream synchronisation)
+    TMA_HIP_TRY(hipMemcpyWithStream(h_sizes, w.sizes, sizeof(h_sizes), hipMemcpyDeviceToHost, s), fn);
     *h_n_loc = h_sizes[0];
     *h_nnz_loc = h_sizes[1];
     TMA_REQUIRE(h_sizes[0] <= cap_n_loc, TMA_ERR_BAD_SHAPE,
@@ -416,24 +468,45 @@ extern "C" int tma_induced_subgraph_count(int64_t n_nodes, const int64_t *rowptr
     return TMA_OK;
 }
 
-extern "C" int tma_induced_subgraph_fill(int64_t n_nodes, const int64_t *rowptr, const int32_t *colidx,
-                                         const int32_t *part, int32_t p, const int32_t *g2l, const int32_t *l2g,
-                                         int64_t n_loc, const int32_t *rowptr_loc, int32_t *colidx_loc_out,
-                                         float *inv_deg_out, tma_stream_t stream)
+extern "C" int tma_induced_subgraph_fill(int64_t n_nodes, const int32_t *colidx, const int32_t *g2l, int64_t n_loc,
+                                         const int32_t *rowptr_loc, int32_t *colidx_loc_out, float *inv_deg_out,
+                                         int64_t cap_n_loc, const void *ws, size_t ws_bytes, tma_stream_t stream)
 {
     using namespace tma;
     const char *fn = "tma_induced_subgraph_fill";
-    (void)part;
-    (void)p;
-    TMA_REQUIRE(n_nodes >= 0 && n_loc >= 0 && n_loc <= n_nodes, TMA_ERR_INVALID_ARG, "%s: bad n_nodes / n_loc", fn);
+    TMA_REQUIRE(n_nodes >= 0 && n_nodes <= INT32_MAX && n_loc >= 0 && n_loc <= cap_n_loc && cap_n_loc <= n_nodes,
+                TMA_ERR_INVALID_ARG, "%s: need 0 <= n_loc <= cap_n_loc <= n_nodes < 2^31", fn);
     if (n_loc == 0) return TMA_OK;
-    TMA_REQUIRE(rowptr && g2l && l2g && rowptr_loc && inv_deg_out, TMA_ERR_INVALID_ARG, "%s: NULL argument", fn);
+    TMA_REQUIRE(ws && aligned(ws, 256), TMA_ERR_INVALID_ARG, "%s: workspace NULL or not 256-byte aligned", fn);
+    const CountWorkspace w = carve(const_cast<void *>(ws), n_nodes, cap_n_loc);
+    TMA_REQUIRE(ws_bytes >= w.bytes, TMA_ERR_WORKSPACE_TOO_SMALL, "%s: workspace %zu < %zu bytes", fn, ws_bytes,
+                w.bytes);
+    TMA_REQUIRE(g2l && rowptr_loc && inv_deg_out, TMA_ERR_INVALID_ARG, "%s: NULL argument", fn);
     // colidx / colidx_loc_out may be NULL only for a graph without entries; not knowable here without a
     // device read, so they are required whenever there are local rows.
     TMA_REQUIRE(colidx && colidx_loc_out, TMA_ERR_INVALID_ARG, "%s: colidx / colidx_loc_out is NULL", fn);
     const unsigned blocks = unsigned(ceil_div(n_loc, kRowsPerBlock));
     TMA_TIMED("row_fill", as_stream(stream));
-    hipLaunchKernelGGL(row_fill_kernel, dim3(blocks), dim3(256), 0, as_stream(stream), n_loc, l2g, rowptr, colidx,
-                       g2l, rowptr_loc, colidx_loc_out, inv_deg_out);
+    hipLaunchKernelGGL(row_fill_kernel, dim3(blocks), dim3(256), 0, as_stream(stream), n_loc, w.row_beg, w.row_len,
+                       colidx, w.member, g2l, rowptr_loc, colidx_loc_out, inv_deg_out);
     return check_launch(fn);
+}
+
+extern "C" int tma_induced_subgraph(int64_t n_nodes, const int64_t *rowptr, const int32_t *colidx, const int32_t *part,
+                                    int32_t p, int32_t *g2l_out, int32_t *l2g_out, int32_t *rowptr_loc_out,
+                                    int32_t *colidx_loc_out, float *inv_deg_out, int64_t cap_n_loc,
+                                    int64_t cap_nnz_loc, int64_t *h_n_loc, int64_t *h_nnz_loc, void *ws,
+                                    size_t ws_bytes, tma_stream_t stream)
+{
+    using namespace tma;
+    const char *fn = "tma_induced_subgraph";
+    TMA_REQUIRE(cap_nnz_loc >= 0, TMA_ERR_INVALID_ARG, "%s: cap_nnz_loc < 0", fn);
+    if (int rc = tma_induced_subgraph_count(n_nodes, rowptr, colidx, part, p, g2l_out, l2g_out, rowptr_loc_out,
+                                            cap_n_loc, h_n_loc, h_nnz_loc, ws, ws_bytes, stream))
+        return rc;
+    TMA_REQUIRE(*h_nnz_loc <= cap_nnz_loc, TMA_ERR_BAD_SHAPE,
+                "%s: the subgraph keeps %lld entries but cap_nnz_loc is %lld", fn, (long long)*h_nnz_loc,
+                (long long)cap_nnz_loc);
+    return tma_induced_subgraph_fill(n_nodes, colidx, g2l_out, *h_n_loc, rowptr_loc_out, colidx_loc_out, inv_deg_out,
+                                     cap_n_loc, ws, ws_bytes, stream);
 }

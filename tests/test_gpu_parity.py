@@ -151,6 +151,24 @@ def test_subgraph_capacity_too_small_is_an_error(B):
     torch.cuda.synchronize()
 
 
+def test_subgraph_single_call_with_capacities(B):
+    """Both passes in one library call into buffers of a chosen capacity: same result, bit for bit; an entry
+    capacity that is too small is an error that reports the sizes."""
+    rowptr, colidx = synth.chung_lu_graph(60_000, 12, 2.1, seed=2)
+    part = oracle.partition(60_000, 4, seed=9)
+    want = oracle.induced_subgraph(rowptr, colidx, part, 2)
+    n_loc, nnz_loc = len(want["l2g"]), len(want["colidx"])
+    for cap_n, cap_e in ((n_loc, nnz_loc), (n_loc + 777, nnz_loc + 12345)):
+        got = B.tma_induced_subgraph(dev(rowptr), dev(colidx), dev(part), 2, cap_n_loc=cap_n, cap_nnz_loc=cap_e)
+        assert (got["n_loc"], got["nnz_loc"]) == (n_loc, nnz_loc)
+        for key in ("g2l", "l2g", "rowptr", "colidx"):
+            assert np.array_equal(got[key].cpu().numpy(), want[key]), key
+        assert np.array_equal(got["inv_deg"].cpu().numpy(), want["inv_deg"].astype(np.float32))
+    with pytest.raises(B.TmaError, match="cap_nnz_loc"):
+        B.tma_induced_subgraph(dev(rowptr), dev(colidx), dev(part), 2, cap_n_loc=n_loc, cap_nnz_loc=nnz_loc - 1)
+    torch.cuda.synchronize()
+
+
 # ------------------------------------------------------------------ aggregation
 def _local_graph(n, m, seed, K=2, kind="uniform"):
     if kind == "uniform":
@@ -331,7 +349,7 @@ def test_sage_layer_rejects_bad_shapes(B):
 
 
 # ----------------------------------------------------------- losses, sgd, average
-@pytest.mark.parametrize("n,C", [(1, 2), (255, 16), (257, 47), (10_000, 47)])
+@pytest.mark.parametrize("n,C", [(1, 2), (255, 16), (257, 47), (10_000, 47), (300, 33), (300, 64), (300, 65), (700, 200), (40_000, 5)])
 def test_softmax_ce(B, n, C):
     rng = np.random.default_rng(n)
     z = (3 * rng.standard_normal((n, C))).astype(np.float32)
