@@ -32,14 +32,17 @@ WORKLOAD = dict(n_nodes=1_000_000, avg_degree=20, gamma=2.1, K=8, part=0, F=128,
 # (profiles/bench_configs1_hbm_traffic.txt): (FETCH_SIZE * 2.0 + WRITE_SIZE * 1.0) KiB, the factors being what the
 # same counters read for a plain 1 GiB device copy (FETCH_SIZE reports half the bytes read, WRITE_SIZE all written).
 MEASURED_TRAFFIC_BYTES = {
-    "gemm_bwd_weight_128x128": (208632 * 2.0 + 32639) * 1024,
-    "gemm_fwd_128x128": (68300 * 2.0 + 125237) * 1024,
-    "gemm_bwd_data_128x128": (12988 * 2.0 + 250474) * 1024,
-    "gemm_fwd_128x64": (126468 * 2.0 + 23527) * 1024,
-    "gemm_bwd_weight_128x64": (137408 * 2.0 + 11964) * 1024,
-    "spmm_mean_f32_g64x1": (150540 * 2.0 + 125237) * 1024,
-    "spmm_sum_f32_g64x1": (150540 * 2.0 + 125237) * 1024,
-    "spmm_mean_f32_g32x1": (54110 * 2.0 + 62618) * 1024,
+    "gemm_bwd_weight_128x128": (211514 * 2.0 + 32639) * 1024,
+    "gemm_fwd_128x128": (67763 * 2.0 + 125237) * 1024,
+    "gemm_tf_fwd": (63469 * 2.0 + 47077) * 1024,
+    "gemm_tf_bwd_weight": (86228 * 2.0 + 23612) * 1024,
+    "gemm_tf_bwd_data": (24306 * 2.0 + 125237) * 1024,
+    "spmm_mean_f32_g32x1": (55743 * 2.0 + 62618) * 1024,
+    "spmm_combine_f32_g12x1": (42987 * 2.0 + 24981) * 1024,
+    "spmm_sum_f32_g12x1": (25502 * 2.0 + 24421) * 1024,
+    "gather_rows_w16": (31577 * 2.0 + 62618) * 1024,
+    "row_fill": (20809 * 2.0 + 1926) * 1024,
+    "row_count": (12037 * 2.0 + 490) * 1024,
 }
 
 
@@ -207,12 +210,13 @@ def main():
         if b is None or ms <= 0:
             continue
         per_launch_s = ms * 1e-3 / launches
+        traffic = MEASURED_TRAFFIC_BYTES.get(k.replace("_generic", ""))
         if b == "mfma":
             kernel_rooflines[k] = {"bound": b, "achieved": round(wk / per_launch_s / 1e12, 2), "peak": PEAK_MFMA_F32_TFLOPS,
-                                   "unit": "TFLOP/s", "frac": round(wk / per_launch_s / 1e12 / PEAK_MFMA_F32_TFLOPS, 4)}
+                                   "unit": "TFLOP/s", "frac": round(wk / per_launch_s / 1e12 / PEAK_MFMA_F32_TFLOPS, 4), "traffic": traffic}
         else:
             kernel_rooflines[k] = {"bound": b, "achieved": round(wk / per_launch_s / 1e9, 1), "peak": PEAK_HBM_GBS,
-                                   "unit": "GB/s", "frac": round(wk / per_launch_s / 1e9 / PEAK_HBM_GBS, 4)}
+                                   "unit": "GB/s", "frac": round(wk / per_launch_s / 1e9 / PEAK_HBM_GBS, 4), "traffic": traffic}
 
     value = L * nnz_loc / (ms_per_step * 1e-3)
     train_ms = sum(v for k, v in per_step.items() if k.startswith(("spmm", "gemm", "reduce", "softmax", "finish", "sgd")))
