@@ -213,10 +213,12 @@ def main():
         traffic = MEASURED_TRAFFIC_BYTES.get(k.replace("_generic", ""))
         if b == "mfma":
             kernel_rooflines[k] = {"bound": b, "achieved": round(wk / per_launch_s / 1e12, 2), "peak": PEAK_MFMA_F32_TFLOPS,
-                                   "unit": "TFLOP/s", "frac": round(wk / per_launch_s / 1e12 / PEAK_MFMA_F32_TFLOPS, 4), "traffic": traffic}
+                                   "unit": "TFLOP/s", "frac": round(wk / per_launch_s / 1e12 / PEAK_MFMA_F32_TFLOPS, 4), "traffic": traffic,
+                                   "traffic_GBs": round(traffic / per_launch_s / 1e9, 1) if traffic else None}
         else:
             kernel_rooflines[k] = {"bound": b, "achieved": round(wk / per_launch_s / 1e9, 1), "peak": PEAK_HBM_GBS,
-                                   "unit": "GB/s", "frac": round(wk / per_launch_s / 1e9 / PEAK_HBM_GBS, 4), "traffic": traffic}
+                                   "unit": "GB/s", "frac": round(wk / per_launch_s / 1e9 / PEAK_HBM_GBS, 4), "traffic": traffic,
+                                   "traffic_GBs": round(traffic / per_launch_s / 1e9, 1) if traffic else None}
 
     value = L * nnz_loc / (ms_per_step * 1e-3)
     train_ms = sum(v for k, v in per_step.items() if k.startswith(("spmm", "gemm", "reduce", "softmax", "finish", "sgd")))

@@ -137,6 +137,19 @@ struct CatRows {  // A[m][k] = k < F ? H[m][k] : M[m][k-F]          (contiguous 
         }
         return r;
     }
+    __device__ __forceinline__ bool k_plain() const { return V; }
+    __device__ __forceinline__ Raw load_plain(const Lane &l, int64_t k64) const
+    {
+        if constexpr (V) {
+            const int k = int(k64);
+            Raw r;
+            r.ok = l.ok;
+            r.v = Pack4<T>::load((k < F ? l.p0 : l.p1) + k);
+            return r;
+        } else {
+            return load(l, k64);
+        }
+    }
 };
 
 template <typename T, bool V>
@@ -178,6 +191,18 @@ struct CatRowsT {  // A[m][k] = (m < F ? H[k][m] : M[k][m-F])          (contiguo
         }
         return r;
     }
+    __device__ __forceinline__ bool k_plain() const { return V; }
+    __device__ __forceinline__ Raw load_plain(const Lane &l, int64_t node) const
+    {
+        if constexpr (V) {
+            Raw r;
+            r.ok = l.ok;
+            r.v = Pack4<T>::load(l.p + node * l.ld);
+            return r;
+        } else {
+            return load(l, node);
+        }
+    }
 };
 
 template <bool V>
@@ -211,6 +236,20 @@ struct CatWeights {  // B[k][n] = k < F ? W_self[k][n] : W_neigh[k-F][n]  (conti
             r.v = zero4();
         }
         return r;
+    }
+    __device__ __forceinline__ bool k_plain() const { return V; }
+    __device__ __forceinline__ Raw load_plain(const Lane &l, int64_t k64) const
+    {
+        if constexpr (V) {
+            const int k = int(k64);
+            Raw r;
+            r.ok = l.n < N;
+            const float *row = k < F ? Ws + int64_t(k) * N : Wn + int64_t(k - F) * N;
+            r.v = *reinterpret_cast<const float4 *>(row + (l.n < N ? l.n : 0));
+            return r;
+        } else {
+            return load(l, k64);
+        }
     }
 };
 
@@ -249,6 +288,18 @@ struct CatWeightsT {  // B[k][n] = n < F ? W_self[n][k] : W_neigh[n-F][k]  (cont
             r.v = zero4();
         }
         return r;
+    }
+    __device__ __forceinline__ bool k_plain() const { return V; }
+    __device__ __forceinline__ Raw load_plain(const Lane &l, int64_t k64) const
+    {
+        if constexpr (V) {
+            Raw r;
+            r.ok = l.ok;
+            r.v = *reinterpret_cast<const float4 *>(l.row + k64);
+            return r;
+        } else {
+            return load(l, k64);
+        }
     }
 };
 
@@ -329,6 +380,26 @@ struct MaskedGrad {
         }
         return r;
     }
+    __device__ __forceinline__ bool k_plain() const { return V; }
+    __device__ __forceinline__ Raw load_plain(const Lane &l, int64_t k) const
+    {
+        if constexpr (V) {
+            Raw r;
+            int64_t e;
+            if (kAsA) {   // k = output feature, whole groups of four inside [0, Fo)
+                r.nv = l.ok ? 4 : 0;
+                e = l.off + k;
+            } else {      // k = node
+                r.nv = l.ok ? Fo - int(l.off) : 0;
+                e = k * ld + l.off;
+            }
+            r.g = Pack4<T>::load(dHn + e);
+            if constexpr (kRelu) r.h = Pack4<T>::load(Hn + e);
+            return r;
+        } else {
+            return load(l, k);
+        }
+    }
 };
 
 // ---------------------------------------------------------------------------
@@ -378,6 +449,18 @@ struct SideWeights {  // B[k][n] = n < Fp ? W_self[k][n] : W_neigh[k][n-Fp]   (c
         }
         return r;
     }
+    __device__ __forceinline__ bool k_plain() const { return V; }
+    __device__ __forceinline__ Raw load_plain(const Lane &l, int64_t k64) const
+    {
+        if constexpr (V) {
+            Raw r;
+            r.ok = l.nv > 0;
+            r.v = *reinterpret_cast<const float4 *>(l.col + k64 * Fo);
+            return r;
+        } else {
+            return load(l, k64);
+        }
+    }
 };
 
 template <bool V>
@@ -418,6 +501,20 @@ struct SideWeightsT {  // B[k][n] = k < Fp ? W_self[n][k] : W_neigh[n][k-Fp]   (
             r.v = zero4();
         }
         return r;
+    }
+    // without padding columns inside the halves every group of four along k is whole
+    __device__ __forceinline__ bool k_plain() const { return V && Fo == Fp; }
+    __device__ __forceinline__ Raw load_plain(const Lane &l, int64_t k64) const
+    {
+        if constexpr (V) {
+            const int k = int(k64);
+            Raw r;
+            r.ok = l.ok;
+            r.v = *reinterpret_cast<const float4 *>((k >= Fp ? l.rn : l.rs) + k);
+            return r;
+        } else {
+            return load(l, k64);
+        }
     }
 };
 
@@ -520,6 +617,33 @@ struct SideGrad {
         }
         return r;
     }
+    __device__ __forceinline__ bool k_plain() const { return V && (!kAsA || Fo == Fp); }
+    __device__ __forceinline__ Raw load_plain(const Lane &l, int64_t k) const
+    {
+        if constexpr (V) {
+            Raw r;
+            int64_t eg, ey;
+            if (kAsA) {   // k = position in [dZ | dYn], no padding inside the halves
+                r.second = k >= Fp;
+                const int c = int(k - (r.second ? Fp : 0));
+                r.nv = l.ok ? 4 : 0;
+                eg = l.a + c;
+                ey = l.b + c;
+            } else {      // k = node
+                r.second = l.second;
+                const int c = int(l.a);
+                r.nv = l.ok ? (r.second ? Fp : Fo) - c : 0;
+                eg = k * ld + c;
+                ey = k * ldy + c;
+            }
+            r.g = Pack4<T>::load(r.second ? dYn + ey : dHn + eg);
+            if constexpr (kRelu) r.h = Pack4<T>::load(Hn + eg);
+            else r.h = r.g;
+            return r;
+        } else {
+            return load(l, k);
+        }
+    }
 };
 
 // ---------------------------------------------------------------------------
@@ -611,11 +735,16 @@ struct SplitEpilogue {  // partial products, one slab per split
 // on die b % 8 and walks the work items  die*per_die + b/8, + blocks_per_die, ...
 // so that at any time the blocks of a die work on neighbouring items (the n-tiles
 // of one row block, the output tiles of one node range) and share them in its L2.
-// A block that has issued the stores of one tile goes straight on to the loads
-// of its next one.
+// The first slab of a block's next tile is fetched before the results of the
+// current one are written out, so that its latency passes behind the stores.
+// A tile whose k range consists of whole slabs inside both operands runs a main
+// loop with unguarded loads (addresses affine in k: one addition per load and
+// slab instead of clamps and 64-bit multiplications); a tile that lies wholly
+// inside the result is written out without per-element bounds tests, which also
+// gives the compiler a fixed number of stores to count its waits against.
 // ---------------------------------------------------------------------------
 template <int BM, int BN, int BK, int WM, int WN, bool kColSum, class AL, class BL, class Epi>
-__global__ __launch_bounds__(WM *WN * 64, (BK <= 16 ? 3 : 2)) void gemm_f32_kernel(AL a, BL b, Epi epi, int64_t M, int N, int64_t K,
+__global__ __launch_bounds__(WM *WN * 64, (BK <= 16 && !Epi::kRowAux ? 3 : 2)) void gemm_f32_kernel(AL a, BL b, Epi epi, int64_t M, int N, int64_t K,
                                                                  int64_t k_per_split, int n_tiles,
                                                                  int64_t tiles_per_split, int64_t total_work,
                                                                  float *__restrict__ colsum_partial)
@@ -669,22 +798,77 @@ __global__ __launch_bounds__(WM *WN * 64, (BK <= 16 ? 3 : 2)) void gemm_f32_kern
     int64_t die_end = (die + 1) * per_die;
     if (die_end > total_work) die_end = total_work;
 
-    for (int64_t work = die * per_die + blockIdx.x / kXcds; work < die_end; work += blocks_per_die) {
-        const int split = int(work / tiles_per_split);
+    struct Tile {
+        int64_t m0;
+        int n0, split;
+        int64_t k_begin, k_end;
+    };
+    auto tile_of = [&](int64_t work) {
+        Tile t;
+        t.split = int(work / tiles_per_split);
         const int64_t tile = work % tiles_per_split;
-        const int64_t m0 = (tile / n_tiles) * BM;
-        const int n0 = int(tile % n_tiles) * BN;
-        const int64_t k_begin = int64_t(split) * k_per_split;
-        int64_t k_end = k_begin + k_per_split;
-        if (k_end > K) k_end = K;
+        t.m0 = (tile / n_tiles) * BM;
+        t.n0 = int(tile % n_tiles) * BN;
+        t.k_begin = int64_t(t.split) * k_per_split;
+        t.k_end = t.k_begin + k_per_split;
+        if (t.k_end > K) t.k_end = K;
+        return t;
+    };
 
-        typename AL::Lane alane[A_V];
-        typename BL::Lane blane[B_V];
+    typename AL::Lane alane[A_V];
+    typename BL::Lane blane[B_V];
+    // first slab of the tile that comes next; the slabs inside a tile's main loop have registers of their own
+    typename AL::Raw afirst[A_V];
+    typename BL::Raw bfirst[B_V];
+    auto prepare = [&](const Tile &t) {
 #pragma unroll
-        for (int i = 0; i < A_V; ++i) alane[i] = a.prepare(m0 + a_mn[i]);
+        for (int i = 0; i < A_V; ++i) alane[i] = a.prepare(t.m0 + a_mn[i]);
 #pragma unroll
-        for (int i = 0; i < B_V; ++i) blane[i] = b.prepare(n0 + b_mn[i]);
+        for (int i = 0; i < B_V; ++i) blane[i] = b.prepare(t.n0 + b_mn[i]);
+    };
+    // guarded: any position, clamped and flagged; plain: the caller knows the whole slab lies inside the
+    // operands' k range, so the addresses are affine in k and cost one addition per slab
+    auto fetch = [&](int64_t kt, typename AL::Raw(&ar)[A_V], typename BL::Raw(&br)[B_V]) {
+#pragma unroll
+        for (int i = 0; i < A_V; ++i) ar[i] = a.load(alane[i], kt + a_k[i]);
+#pragma unroll
+        for (int i = 0; i < B_V; ++i) br[i] = b.load(blane[i], kt + b_k[i]);
+    };
+    auto fetch_plain = [&](int64_t kt, typename AL::Raw(&ar)[A_V], typename BL::Raw(&br)[B_V]) {
+#pragma unroll
+        for (int i = 0; i < A_V; ++i) ar[i] = a.load_plain(alane[i], kt + a_k[i]);
+#pragma unroll
+        for (int i = 0; i < B_V; ++i) br[i] = b.load_plain(blane[i], kt + b_k[i]);
+    };
+    auto stage = [&](int buf, const typename AL::Raw(&ar)[A_V], const typename BL::Raw(&br)[B_V]) {
+#pragma unroll
+        for (int i = 0; i < A_V; ++i) *reinterpret_cast<float4 *>(&As[buf][a_lds[i]]) = AL::resolve(ar[i]);
+#pragma unroll
+        for (int i = 0; i < B_V; ++i) *reinterpret_cast<float4 *>(&Bs[buf][b_lds[i]]) = BL::resolve(br[i]);
+    };
+    // The four k-values (4*hi + 0..3 of group g) of this lane's row/column, for the 4 MFMAs of the group.
+    auto frag_a = [&](int buf, int g, int i) -> float4 {
+        const int mn = wm0 + i * 32 + l31;
+        const int k = g * 8 + 4 * hi;
+        if (AL::kContigK) return *reinterpret_cast<const float4 *>(&As[buf][mn * A_LD + k]);
+        return make_float4(As[buf][(k + 0) * A_LD + mn], As[buf][(k + 1) * A_LD + mn], As[buf][(k + 2) * A_LD + mn],
+                           As[buf][(k + 3) * A_LD + mn]);
+    };
+    auto frag_b = [&](int buf, int g, int j) -> float4 {
+        const int mn = wn0 + j * 32 + l31;
+        const int k = g * 8 + 4 * hi;
+        if (BL::kContigK) return *reinterpret_cast<const float4 *>(&Bs[buf][mn * B_LD + k]);
+        return make_float4(Bs[buf][(k + 0) * B_LD + mn], Bs[buf][(k + 1) * B_LD + mn], Bs[buf][(k + 2) * B_LD + mn],
+                           Bs[buf][(k + 3) * B_LD + mn]);
+    };
 
+    int64_t work = die * per_die + blockIdx.x / kXcds;
+    if (work >= die_end) return;
+    const bool views_plain = a.k_plain() && b.k_plain();
+    Tile t = tile_of(work);
+    prepare(t);
+    fetch(t.k_begin, afirst, bfirst);
+    while (true) {
         floatx16 acc[TM][TN];
 #pragma unroll
         for (int i = 0; i < TM; ++i)
@@ -692,112 +876,111 @@ __global__ __launch_bounds__(WM *WN * 64, (BK <= 16 ? 3 : 2)) void gemm_f32_kern
             for (int j = 0; j < TN; ++j)
 #pragma unroll
                 for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.0f;
-
-        typename AL::Raw areg[A_V];
-        typename BL::Raw breg[B_V];
         float colsum = 0.0f;
 
-        auto fetch = [&](int64_t kt) {
-#pragma unroll
-            for (int i = 0; i < A_V; ++i) areg[i] = a.load(alane[i], kt + a_k[i]);
-#pragma unroll
-            for (int i = 0; i < B_V; ++i) breg[i] = b.load(blane[i], kt + b_k[i]);
-        };
-        auto stage = [&](int buf) {
-#pragma unroll
-            for (int i = 0; i < A_V; ++i) *reinterpret_cast<float4 *>(&As[buf][a_lds[i]]) = AL::resolve(areg[i]);
-#pragma unroll
-            for (int i = 0; i < B_V; ++i) *reinterpret_cast<float4 *>(&Bs[buf][b_lds[i]]) = BL::resolve(breg[i]);
-        };
-        // The four k-values (4*hi + 0..3 of group g) of this lane's row/column, for the 4 MFMAs of the group.
-        auto frag_a = [&](int buf, int g, int i) -> float4 {
-            const int mn = wm0 + i * 32 + l31;
-            const int k = g * 8 + 4 * hi;
-            if (AL::kContigK) return *reinterpret_cast<const float4 *>(&As[buf][mn * A_LD + k]);
-            return make_float4(As[buf][(k + 0) * A_LD + mn], As[buf][(k + 1) * A_LD + mn],
-                               As[buf][(k + 2) * A_LD + mn], As[buf][(k + 3) * A_LD + mn]);
-        };
-        auto frag_b = [&](int buf, int g, int j) -> float4 {
-            const int mn = wn0 + j * 32 + l31;
-            const int k = g * 8 + 4 * hi;
-            if (BL::kContigK) return *reinterpret_cast<const float4 *>(&Bs[buf][mn * B_LD + k]);
-            return make_float4(Bs[buf][(k + 0) * B_LD + mn], Bs[buf][(k + 1) * B_LD + mn],
-                               Bs[buf][(k + 2) * B_LD + mn], Bs[buf][(k + 3) * B_LD + mn]);
-        };
-
         __syncthreads();  // the previous tile's epilogue has finished reading LDS
-        fetch(k_begin);
-        stage(0);
+        stage(0, afirst, bfirst);
         __syncthreads();
-        int buf = 0;
-        for (int64_t kt = k_begin; kt < k_end; kt += BK) {
-            const bool more = kt + BK < k_end;
-            if (more) fetch(kt + BK);  // in flight while this slab is multiplied
 
-            float4 fa[2][TM], fb[2][TN];
-#pragma unroll
-            for (int i = 0; i < TM; ++i) fa[0][i] = frag_a(buf, 0, i);
-#pragma unroll
-            for (int j = 0; j < TN; ++j) fb[0][j] = frag_b(buf, 0, j);
-#pragma unroll
-            for (int g = 0; g < KG; ++g) {
-                const int cur = g & 1, nxt = cur ^ 1;
-                if (g + 1 < KG) {  // next group's fragments are in flight while this group's MFMAs run
-#pragma unroll
-                    for (int i = 0; i < TM; ++i) fa[nxt][i] = frag_a(buf, g + 1, i);
-#pragma unroll
-                    for (int j = 0; j < TN; ++j) fb[nxt][j] = frag_b(buf, g + 1, j);
+        auto main_loop = [&](auto plain_tag) {
+            constexpr bool kPlain = decltype(plain_tag)::value;
+            typename AL::Raw areg[A_V];
+            typename BL::Raw breg[B_V];
+            int buf = 0;
+            for (int64_t kt = t.k_begin; kt < t.k_end; kt += BK) {
+                const bool more = kt + BK < t.k_end;
+                if (more) {  // in flight while this slab is multiplied
+                    if constexpr (kPlain) fetch_plain(kt + BK, areg, breg);
+                    else fetch(kt + BK, areg, breg);
                 }
+
+                float4 fa[2][TM], fb[2][TN];
 #pragma unroll
-                for (int q = 0; q < 4; ++q)
+                for (int i = 0; i < TM; ++i) fa[0][i] = frag_a(buf, 0, i);
 #pragma unroll
-                    for (int i = 0; i < TM; ++i)
+                for (int j = 0; j < TN; ++j) fb[0][j] = frag_b(buf, 0, j);
 #pragma unroll
-                        for (int j = 0; j < TN; ++j) {
-                            const float av = q == 0 ? fa[cur][i].x : q == 1 ? fa[cur][i].y : q == 2 ? fa[cur][i].z : fa[cur][i].w;
-                            const float bv = q == 0 ? fb[cur][j].x : q == 1 ? fb[cur][j].y : q == 2 ? fb[cur][j].z : fb[cur][j].w;
-                            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(av, bv, acc[i][j], 0, 0, 0);
-                        }
+                for (int g = 0; g < KG; ++g) {
+                    const int cur = g & 1, nxt = cur ^ 1;
+                    if (g + 1 < KG) {  // next group's fragments are in flight while this group's MFMAs run
+#pragma unroll
+                        for (int i = 0; i < TM; ++i) fa[nxt][i] = frag_a(buf, g + 1, i);
+#pragma unroll
+                        for (int j = 0; j < TN; ++j) fb[nxt][j] = frag_b(buf, g + 1, j);
+                    }
+#pragma unroll
+                    for (int q = 0; q < 4; ++q)
+#pragma unroll
+                        for (int i = 0; i < TM; ++i)
+#pragma unroll
+                            for (int j = 0; j < TN; ++j) {
+                                const float av = q == 0 ? fa[cur][i].x : q == 1 ? fa[cur][i].y : q == 2 ? fa[cur][i].z : fa[cur][i].w;
+                                const float bv = q == 0 ? fb[cur][j].x : q == 1 ? fb[cur][j].y : q == 2 ? fb[cur][j].z : fb[cur][j].w;
+                                acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(av, bv, acc[i][j], 0, 0, 0);
+                            }
+                }
+                if (kColSum && t.m0 == 0 && tid < BN) {
+#pragma unroll
+                    for (int k = 0; k < BK; ++k) colsum += Bs[buf][k * B_LD + tid];
+                }
+                if (more) stage(buf ^ 1, areg, breg);  // the other buffer was last read before the previous barrier
+                __syncthreads();
+                buf ^= 1;
             }
-            if (kColSum && m0 == 0 && tid < BN) {
-#pragma unroll
-                for (int k = 0; k < BK; ++k) colsum += Bs[buf][k * B_LD + tid];
-            }
-            if (more) stage(buf ^ 1);  // the other buffer was last read before the previous barrier
-            __syncthreads();
-            buf ^= 1;
-        }
+        };
+        if (views_plain && (t.k_end - t.k_begin) % BK == 0) main_loop(std::true_type{});
+        else main_loop(std::false_type{});
 
         // Per-column / per-row epilogue inputs (bias, 1/deg) go through LDS: they are loaded from
         // global memory once, here, before any store is in flight.  Fetched into registers directly they
         // would make the compiler guard every store below with a wait on the memory counter, which
         // also waits for the earlier stores and serialises the whole write-out.
-        if (Epi::kColAux && tid < BN) As[0][tid] = epi.col_aux(n0 + tid < N ? n0 + tid : N - 1);
-        if (Epi::kRowAux && tid < BM) Bs[0][tid] = epi.row_aux(m0 + tid < M ? m0 + tid : M - 1);
+        if (Epi::kColAux && tid < BN) As[0][tid] = epi.col_aux(t.n0 + tid < N ? t.n0 + tid : N - 1);
+        if (Epi::kRowAux && tid < BM) Bs[0][tid] = epi.row_aux(t.m0 + tid < M ? t.m0 + tid : M - 1);
         if (Epi::kColAux || Epi::kRowAux) __syncthreads();
+
+        // The first slab of this block's next tile is fetched now, so that its latency passes while the
+        // results below are written out.
+        const Tile done = t;
+        const float done_colsum = colsum;
+        const int64_t next = work + blocks_per_die;
+        const bool has_next = next < die_end;
+        if (has_next) {
+            t = tile_of(next);
+            prepare(t);
+            fetch(t.k_begin, afirst, bfirst);
+        }
 
         // MFMA 32x32 result layout: register r of lane l holds row 8*(r/4) + 4*(l/32) + r%4, column l%32.
         float caux[TN];
 #pragma unroll
         for (int j = 0; j < TN; ++j) caux[j] = Epi::kColAux ? As[0][wn0 + j * 32 + l31] : 0.0f;
+        auto write_out = [&](auto inside_tag) {
+            constexpr bool kInside = decltype(inside_tag)::value;   // the whole tile lies inside the result
 #pragma unroll
-        for (int i = 0; i < TM; ++i) {
-            float raux[16];
+            for (int i = 0; i < TM; ++i) {
+                float raux[16];
 #pragma unroll
-            for (int r = 0; r < 16; ++r)
-                raux[r] = Epi::kRowAux ? Bs[0][wm0 + i * 32 + 8 * (r / 4) + 4 * hi + (r % 4)] : 0.0f;
+                for (int r = 0; r < 16; ++r)
+                    raux[r] = Epi::kRowAux ? Bs[0][wm0 + i * 32 + 8 * (r / 4) + 4 * hi + (r % 4)] : 0.0f;
 #pragma unroll
-            for (int j = 0; j < TN; ++j) {
-                const int col = n0 + wn0 + j * 32 + l31;
+                for (int j = 0; j < TN; ++j) {
+                    const int col = done.n0 + wn0 + j * 32 + l31;
 #pragma unroll
-                for (int r = 0; r < 16; ++r) {
-                    const int64_t row = m0 + wm0 + i * 32 + 8 * (r / 4) + 4 * hi + (r % 4);
-                    const float val = epi.value(acc[i][j][r], caux[j], raux[r], col);
-                    if (row < M && col < N) epi.store(row, col, val, split);
+                    for (int r = 0; r < 16; ++r) {
+                        const int64_t row = done.m0 + wm0 + i * 32 + 8 * (r / 4) + 4 * hi + (r % 4);
+                        const float val = epi.value(acc[i][j][r], caux[j], raux[r], col);
+                        if (kInside || (row < M && col < N)) epi.store(row, col, val, done.split);
+                    }
                 }
             }
-        }
-        if (kColSum && m0 == 0 && tid < BN && n0 + tid < N) colsum_partial[int64_t(split) * N + n0 + tid] = colsum;
+        };
+        if (done.m0 + BM <= M && done.n0 + BN <= N) write_out(std::true_type{});
+        else write_out(std::false_type{});
+        if (kColSum && done.m0 == 0 && tid < BN && done.n0 + tid < N)
+            colsum_partial[int64_t(done.split) * N + done.n0 + tid] = done_colsum;
+        if (!has_next) break;
+        work = next;
     }
 }
 
@@ -917,7 +1100,7 @@ static void launch_gemm(const char *name, const AL &a, const BL &b, const Epi &e
     // resident blocks per compute unit follow from the kernel's LDS footprint (160 KB per unit) and its
     // register budget (launch bounds); 256 units in 8 dies
     constexpr int kLdsBytes = 2 * 4 * ((AL::kContigK ? BM * (BK + kPad) : BK * (BM + kPad)) + (BL::kContigK ? BN * (BK + kPad) : BK * (BN + kPad)));
-    constexpr int kPerCu = (BK <= 16 && kLdsBytes <= 53 * 1024) ? 3 : 2;
+    constexpr int kPerCu = (BK <= 16 && !Epi::kRowAux && kLdsBytes <= 53 * 1024) ? 3 : 2;
     int64_t blocks_per_die = ceil_div(total, kXcds);
     if (blocks_per_die > 32 * kPerCu) blocks_per_die = 32 * kPerCu;
     TMA_TIMED(name, s);
