@@ -150,6 +150,37 @@ def sage_layer_bwd(rowptr, colidx, H, M, Z, dHnext, W_self, W_neigh, act: int, n
     return dWs, dWn, db, dH
 
 
+# ------------------------------------------------------ normalisation + activation
+LN_EPS = 1e-5
+
+
+def layernorm_prelu_fwd(Z, gamma, beta, slope: float, eps: float = LN_EPS) -> np.ndarray:
+    """H' = PReLU_slope(LayerNorm_{gamma,beta}(Z)) over the feature axis of every row."""
+    Z, gamma, beta = _f64(Z), _f64(gamma), _f64(beta)
+    n, F = Z.shape
+    assert gamma.shape == (F,) and beta.shape == (F,)
+    Hn = np.empty((n, F))
+    lib().orc_layernorm_prelu_fwd(C.c_int64(n), C.c_int64(F), _p(Z), _p(gamma), _p(beta), C.c_double(slope),
+                                  C.c_double(eps), _p(Hn))
+    return Hn
+
+
+def layernorm_prelu_bwd(Z, dHn, gamma, beta, slope: float, eps: float = LN_EPS, open_mask=None):
+    """Returns (dZ, dgamma, dbeta, dslope).  open_mask (bool [n,F]) overrides the decision Y > 0."""
+    Z, dHn, gamma, beta = _f64(Z), _f64(dHn), _f64(gamma), _f64(beta)
+    n, F = Z.shape
+    dZ = np.empty((n, F))
+    dg = np.empty(F)
+    db = np.empty(F)
+    ds = C.c_double(0.0)
+    om = None if open_mask is None else np.ascontiguousarray(np.asarray(open_mask).astype(np.uint8))
+    zh = np.empty(F)
+    dzh = np.empty(F)
+    lib().orc_layernorm_prelu_bwd(C.c_int64(n), C.c_int64(F), _p(Z), _p(dHn), _p(gamma), _p(beta), C.c_double(slope),
+                                  C.c_double(eps), _p(om), _p(dZ), _p(dg), _p(db), C.byref(ds), _p(zh), _p(dzh))
+    return dZ, dg, db, float(ds.value)
+
+
 # ------------------------------------------------------------------- losses
 def softmax_ce(logits, labels, need_grad=True):
     logits, labels = _f64(logits), _i32(labels)

@@ -9,19 +9,28 @@ from __future__ import annotations
 
 import numpy as np
 
-from . import (ACT_NONE, ACT_RELU, average, sage_layer_bwd, sage_layer_fwd,
-               sgd_step, softmax_ce)
+from . import (ACT_NONE, ACT_RELU, average, layernorm_prelu_bwd, layernorm_prelu_fwd,
+               sage_layer_bwd, sage_layer_fwd, sgd_step, softmax_ce)
+
+ACT_LN_PRELU = "ln_prelu"   # a layer whose parameter tuple is (W_self, W_neigh, b, gamma, beta, slope)
 
 
 def forward(rowptr, colidx, X, params):
-    """ReLU between layers, identity on the last.  Returns (logits, saved)."""
+    """Identity on the last layer; between layers ReLU, or, for a layer that carries (gamma, beta, slope),
+    layer normalisation followed by PReLU (the paper's encoder variant, Sec. 4.1).  Returns (logits, saved)."""
     H = np.asarray(X, dtype=np.float64)
     saved = []
     L = len(params)
-    for l, (Ws, Wn, b) in enumerate(params):
-        act = ACT_RELU if l < L - 1 else ACT_NONE
-        M, Z, Hn = sage_layer_fwd(rowptr, colidx, H, Ws, Wn, b, act)
-        saved.append((H, M, Z, act))
+    for l, layer in enumerate(params):
+        Ws, Wn, b = layer[:3]
+        if len(layer) == 6:
+            M, Z, _ = sage_layer_fwd(rowptr, colidx, H, Ws, Wn, b, ACT_NONE)
+            Hn = layernorm_prelu_fwd(Z, layer[3], layer[4], float(np.asarray(layer[5]).ravel()[0]))
+            saved.append((H, M, Z, ACT_LN_PRELU))
+        else:
+            act = ACT_RELU if l < L - 1 else ACT_NONE
+            M, Z, Hn = sage_layer_fwd(rowptr, colidx, H, Ws, Wn, b, act)
+            saved.append((H, M, Z, act))
         H = Hn
     return H, saved
 
@@ -29,8 +38,8 @@ def forward(rowptr, colidx, X, params):
 def loss_and_grads(rowptr, colidx, X, y, params, relu_open=None):
     """Mean softmax-CE over all local nodes and d(loss)/d(params).
 
-    ``relu_open[l]`` (optional, boolean [n, F_{l+1}]) fixes where layer l's ReLU is open instead of
-    deciding it from this fp64 forward pass.  ReLU' is a yes/no decision taken from a floating-point
+    ``relu_open[l]`` (optional, boolean [n, F_{l+1}]) fixes where layer l's ReLU (or PReLU) is open instead
+    of deciding it from this fp64 forward pass.  ReLU' is a yes/no decision taken from a floating-point
     value; a pre-activation within rounding distance of zero can fall on different sides in fp32 and
     fp64, which changes one whole term of a weight-gradient sum.  A parity test therefore hands the
     decision taken in the kernel's precision to both sides; the arithmetic is unchanged.
@@ -40,11 +49,18 @@ def loss_and_grads(rowptr, colidx, X, y, params, relu_open=None):
     grads = [None] * len(params)
     for l in range(len(params) - 1, -1, -1):
         H, M, Z, act = saved[l]
-        if relu_open is not None and act == ACT_RELU and relu_open[l] is not None:
-            Z = np.where(np.asarray(relu_open[l]), 1.0, -1.0)   # only the sign of Z is used by the backward pass
-        Ws, Wn, _ = params[l]
-        dWs, dWn, db, dH = sage_layer_bwd(rowptr, colidx, H, M, Z, d, Ws, Wn, act, need_dH=l > 0)
-        grads[l] = (dWs, dWn, db)
+        Ws, Wn = params[l][0], params[l][1]
+        forced = relu_open[l] if relu_open is not None else None
+        if act == ACT_LN_PRELU:
+            gamma, beta, slope = params[l][3], params[l][4], float(np.asarray(params[l][5]).ravel()[0])
+            dZ, dg, dbeta, ds = layernorm_prelu_bwd(Z, d, gamma, beta, slope, open_mask=forced)
+            dWs, dWn, db, dH = sage_layer_bwd(rowptr, colidx, H, M, Z, dZ, Ws, Wn, ACT_NONE, need_dH=l > 0)
+            grads[l] = (dWs, dWn, db, dg, dbeta, np.array([ds]))
+        else:
+            if forced is not None and act == ACT_RELU:
+                Z = np.where(np.asarray(forced), 1.0, -1.0)   # only the sign of Z is used by the backward pass
+            dWs, dWn, db, dH = sage_layer_bwd(rowptr, colidx, H, M, Z, d, Ws, Wn, act, need_dH=l > 0)
+            grads[l] = (dWs, dWn, db)
         d = dH
     return loss, grads, logits, saved
 
@@ -58,7 +74,7 @@ def train_step(rowptr, colidx, X, y, params, lr, relu_open=None):
 
 
 def flatten(params) -> np.ndarray:
-    """Flat parameter vector, layer by layer: W_self, W_neigh, b."""
+    """Flat parameter vector, layer by layer: W_self, W_neigh, b (then gamma, beta, slope where present)."""
     return np.concatenate([np.asarray(t, dtype=np.float64).ravel() for layer in params for t in layer])
 
 

@@ -274,6 +274,85 @@ double orc_sigmoid_l2(int64_t n, int64_t C, const double *G, const double *Y, do
 }
 
 /* ------------------------------------------------------------------------
+ * Normalisation and activation of the paper's encoders (Sec. 4.1, paragraph
+ * on GNN encoders: PReLU as non-linearity, Layer Normalization before the
+ * activation), applied to a layer's pre-activation Z [n, F]:
+ *     mu_v  = mean_f Z_vf,  var_v = mean_f (Z_vf - mu_v)^2      (per node)
+ *     Zh    = (Z - mu) / sqrt(var + eps)
+ *     Y     = gamma (.) Zh + beta
+ *     H'    = Y            where Y > 0
+ *             slope * Y    elsewhere                              (PReLU)
+ * The paper gives no more than the two names; readings taken here: the
+ * normalisation runs over the feature axis of each node with a learnable
+ * scale and shift per feature and the biased variance (Ba et al. 2016), the
+ * activation has ONE learnable slope per layer (He et al. 2015, shared
+ * variant).  `open` (optional, n*F bytes) overrides the decision Y > 0 in the
+ * backward pass, as for ReLU.
+ * ---------------------------------------------------------------------- */
+void orc_layernorm_prelu_fwd(int64_t n, int64_t F, const double *Z, const double *gamma,
+                             const double *beta, double slope, double eps, double *Hn)
+{
+    for (int64_t v = 0; v < n; ++v) {
+        const double *z = Z + v * F;
+        double mu = 0.0;
+        for (int64_t f = 0; f < F; ++f) mu += z[f];
+        mu /= (double)F;
+        double var = 0.0;
+        for (int64_t f = 0; f < F; ++f) var += (z[f] - mu) * (z[f] - mu);
+        var /= (double)F;
+        const double rstd = 1.0 / sqrt(var + eps);
+        for (int64_t f = 0; f < F; ++f) {
+            const double y = gamma[f] * ((z[f] - mu) * rstd) + beta[f];
+            Hn[v * F + f] = y > 0.0 ? y : slope * y;
+        }
+    }
+}
+
+/* Chain rule through the three maps above.  With Zh, Y as in the forward pass and g = dL/dH':
+ *     dY      = g            where Y > 0,   slope * g elsewhere
+ *     dslope  = sum over all v,f with Y <= 0 of g * Y
+ *     dgamma_f = sum_v dY_vf Zh_vf,   dbeta_f = sum_v dY_vf
+ *     dZh     = dY (.) gamma
+ *     dZ_v    = ( dZh_v - mean_f(dZh_v) - Zh_v * mean_f(dZh_v (.) Zh_v) ) / sqrt(var_v + eps)
+ */
+void orc_layernorm_prelu_bwd(int64_t n, int64_t F, const double *Z, const double *dHn,
+                             const double *gamma, const double *beta, double slope, double eps,
+                             const uint8_t *open, double *dZ, double *dgamma, double *dbeta,
+                             double *dslope, double *zh, double *dzh)
+{
+    for (int64_t f = 0; f < F; ++f) { dgamma[f] = 0.0; dbeta[f] = 0.0; }
+    double ds = 0.0;
+    for (int64_t v = 0; v < n; ++v) {
+        const double *z = Z + v * F;
+        double mu = 0.0;
+        for (int64_t f = 0; f < F; ++f) mu += z[f];
+        mu /= (double)F;
+        double var = 0.0;
+        for (int64_t f = 0; f < F; ++f) var += (z[f] - mu) * (z[f] - mu);
+        var /= (double)F;
+        const double rstd = 1.0 / sqrt(var + eps);
+        double m1 = 0.0, m2 = 0.0;
+        for (int64_t f = 0; f < F; ++f) {
+            zh[f] = (z[f] - mu) * rstd;
+            const double y = gamma[f] * zh[f] + beta[f];
+            const double g = dHn[v * F + f];
+            const int is_open = open ? (open[v * F + f] != 0) : (y > 0.0);
+            const double dy = is_open ? g : slope * g;
+            if (!is_open) ds += g * y;
+            dgamma[f] += dy * zh[f];
+            dbeta[f] += dy;
+            dzh[f] = dy * gamma[f];
+            m1 += dzh[f];
+            m2 += dzh[f] * zh[f];
+        }
+        m1 /= (double)F;
+        m2 /= (double)F;
+        for (int64_t f = 0; f < F; ++f) dZ[v * F + f] = (dzh[f] - m1 - zh[f] * m2) * rstd;
+    }
+    *dslope = ds;
+}
+
+/* ------------------------------------------------------------------------
  * Optimizer step (Alg. 2, the `optimizer` call; read as plain SGD) and the
  * aggregation operator phi = arithmetic mean of the trainers' parameters
  * (Sec. 3.1; Alg. 1 aggregation line), followed by the overwrite of every
