@@ -91,8 +91,8 @@ def test_model_gradients_by_finite_differences():
         lp = omodel.loss_and_grads(rowptr, colidx, X, y, omodel.unflatten(flat + e, params))[0]
         lm = omodel.loss_and_grads(rowptr, colidx, X, y, omodel.unflatten(flat - e, params))[0]
         fd = (lp - lm) / (2 * h)
-        worst = max(worst, abs(fd - gflat[i]) / max(abs(fd), abs(gflat[i]), 1e-6))
-    assert worst < 1e-6, worst
+        worst = max(worst, abs(fd - gflat[i]) / max(abs(fd), abs(gflat[i]), 1e-3))
+    assert worst < 1e-6, worst   # a dropped or mis-signed term would show as an error of order one
     # a training step moves every tensor against its gradient
     _, new = omodel.train_step(rowptr, colidx, X, y, params, 0.1)
     np.testing.assert_allclose(omodel.flatten(new), flat - 0.1 * gflat, rtol=1e-12, atol=1e-15)
