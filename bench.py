@@ -74,6 +74,8 @@ def kernel_work(name, n, nnz, dims, N=0, nnz_glob=0, K=1, n_params=0):
         "spmm_sum_f32_g12x1": n * Cp * s + nnz * 4 + n * 4 + n * Cp * s,
         "scale_mask_rows": n * C * s + n * 4 + n * Cp * s,
         "softmax_ce": 2 * n * C * s + n * 4,
+        "ln_prelu_fwd_f32": 2 * n * F1 * s,                   # Z read, H' written
+        "ln_prelu_bwd_f32": 3 * n * F1 * s,                   # Z and dH' read, dZ written
         "gather_rows_w16": n * 4 + 2 * n * F0 * s,            # feature rows: ids + rows read + rows written
         "gather_rows_w4": 3 * n * 4,                          # labels
         "partition": N * 4,
@@ -98,6 +100,9 @@ def main():
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--norm-act", action="store_true",
+                    help="hidden layers with layer normalisation + PReLU (the paper's encoder variant) instead of "
+                         "ReLU; a second measurement, not the headline workload")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="only run a plain 1 GiB device copy (reference for scaling rocprofv3 FETCH_SIZE/WRITE_SIZE)")
     args = ap.parse_args()
@@ -146,7 +151,11 @@ def main():
     n_loc, nnz_loc = sub["n_loc"], sub["nnz_loc"]
     Xl = torch.empty((n_loc, dims[0]), dtype=torch.float32, device=dev)
     yl = torch.empty(n_loc, dtype=torch.int32, device=dev)
-    tr = LocalTrainer(sub["rowptr"], sub["colidx"], sub["inv_deg"], Xl, yl, dims, params=params)
+    if args.norm_act:   # gamma = 1, beta = 0, slope = 0.25 on the hidden layers
+        params = [tuple(l) + ((np.ones(dims[i + 1], np.float32), np.zeros(dims[i + 1], np.float32),
+                               np.full(1, 0.25, np.float32)) if i < L - 1 else ()) for i, l in enumerate(params)]
+    tr = LocalTrainer(sub["rowptr"], sub["colidx"], sub["inv_deg"], Xl, yl, dims, params=params,
+                      norm_act=args.norm_act)
     peers = [tr.W.clone() for _ in range(K - 1)]      # the other K-1 trainers' parameter vectors
     W_all = [tr.W] + peers
     ptrs = torch.tensor([t.data_ptr() for t in W_all], dtype=torch.int64, device=dev)
@@ -221,7 +230,8 @@ def main():
                                    "traffic_GBs": round(traffic / per_launch_s / 1e9, 1) if traffic else None}
 
     value = L * nnz_loc / (ms_per_step * 1e-3)
-    train_ms = sum(v for k, v in per_step.items() if k.startswith(("spmm", "gemm", "reduce", "softmax", "finish", "sgd")))
+    train_ms = sum(v for k, v in per_step.items()
+                   if k.startswith(("spmm", "gemm", "reduce", "softmax", "finish", "sgd", "ln_prelu", "scale_mask")))
     out = {
         "metric": "trainer edges/sec per SAGE layer fwd+bwd; achieved HBM GB/s vs peak",
         "value": round(value, 1), "unit": "edges/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
@@ -232,7 +242,7 @@ def main():
                                "induced-subgraph extraction of part 0 + row gather + 2-layer mean-SAGE (hidden 256) "
                                "full-batch fwd+bwd+SGD + 8-way parameter averaging",
                    "n_nodes": N, "nnz_global": int(rowptr[-1]), "K": K, "n_loc": n_loc, "nnz_loc": nnz_loc,
-                   "layers": L, "dims": dims, "edge_definition": "directed local CSR entry; value = layers*nnz_loc/step time"},
+                   "layers": L, "dims": dims, "hidden_activation": "layernorm+prelu" if args.norm_act else "relu", "edge_definition": "directed local CSR entry; value = layers*nnz_loc/step time"},
         "roofline": roofline,
         "kernel_rooflines": kernel_rooflines,
         "kernel_ms_per_step": {k: round(v, 5) for k, v in sorted(per_step.items(), key=lambda kv: -kv[1])},

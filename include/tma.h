@@ -198,6 +198,35 @@ int tma_sage_layer_bwd(int64_t n, const int32_t *rowptr_T, const int32_t *colidx
                        void *ws, size_t ws_bytes, tma_stream_t stream);
 
 /* ------------------------------------------------------------------------
+ * Normalisation and activation of the paper's encoders (Sec. 4.1, paragraph on
+ * GNN encoders: PReLU as the non-linearity, Layer Normalization before it),
+ * applied to a layer's pre-activation Z (run the layer with TMA_ACT_NONE):
+ *     Zh = (Z - mean_f Z) / sqrt(var_f Z + eps)     per node, biased variance
+ *     Y  = gamma (.) Zh + beta                      gamma, beta [F] fp32
+ *     H' = Y where Y > 0, slope * Y elsewhere       slope: ONE fp32 value (device)
+ * _fwd writes H' [n, F] (leading dimension ld_out); Z is kept by the caller for
+ * backward.  _bwd takes dL/dH' and writes dZ_out [n, F] = dL/dZ (pass it to
+ * tma_sage_layer_bwd as dHnext with TMA_ACT_NONE; dZ_out may alias dHnext),
+ * dgamma [F], dbeta [F], dslope [1] (overwritten, fixed summation order).
+ * Z, dHnext, H', dZ of `dtype`; rows of at most 1024 elements; 16-byte
+ * aligned pointers and leading dimensions take the vector path.
+ * Workspace (_bwd): tma_layernorm_prelu_bwd_workspace_bytes(n, F), 256-byte
+ * aligned.
+ * ---------------------------------------------------------------------- */
+int tma_layernorm_prelu_fwd(int64_t n, int32_t F, const void *Z, int64_t ldz,
+                            const float *gamma, const float *beta, const float *slope, float eps,
+                            int32_t dtype, void *Hnext_out, int64_t ld_out, tma_stream_t stream);
+
+size_t tma_layernorm_prelu_bwd_workspace_bytes(int64_t n, int32_t F);
+
+int tma_layernorm_prelu_bwd(int64_t n, int32_t F, const void *Z, int64_t ldz,
+                            const void *dHnext, int64_t ld_d,
+                            const float *gamma, const float *beta, const float *slope, float eps,
+                            int32_t dtype, void *dZ_out, int64_t ld_dz,
+                            float *dgamma, float *dbeta, float *dslope,
+                            void *ws, size_t ws_bytes, tma_stream_t stream);
+
+/* ------------------------------------------------------------------------
  * Losses on the last layer's output.
  * tma_softmax_ce: mean softmax cross-entropy over the n local nodes (reading
  *   taken for workloads with class labels); loss_out[0] fp32 (device),

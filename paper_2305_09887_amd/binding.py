@@ -24,6 +24,7 @@ EXPORTS = (
     "tma_induced_subgraph",
     "tma_mean_aggregate", "tma_sage_layer_aggregates_first", "tma_sage_layer_fwd",
     "tma_sage_layer_bwd_workspace_bytes", "tma_sage_layer_bwd",
+    "tma_layernorm_prelu_fwd", "tma_layernorm_prelu_bwd_workspace_bytes", "tma_layernorm_prelu_bwd",
     "tma_loss_workspace_bytes", "tma_softmax_ce", "tma_sigmoid_l2", "tma_sgd_step", "tma_average",
     "tma_gather_rows", "tma_profile_begin", "tma_profile_end", "tma_profile_count", "tma_profile_entry",
 )
@@ -266,6 +267,61 @@ def tma_sage_layer_bwd(rowptr_T, colidx_T, inv_deg, H, M, Hnext, dHnext, W_self,
 
 def tma_loss_workspace_bytes(n: int, Cc: int) -> int:
     return int(lib().tma_loss_workspace_bytes(C.c_int64(n), C.c_int32(Cc)))
+
+
+LN_EPS = 1e-5
+
+
+def tma_layernorm_prelu_fwd(Z, gamma, beta, slope, eps: float = LN_EPS, out=None, stream=None):
+    """H' = PReLU_slope(LayerNorm_{gamma,beta}(Z)); slope is a 1-element fp32 device tensor."""
+    n, F, ldz = _rows_ld(Z, "Z")
+    if gamma.numel() != F or beta.numel() != F or slope.numel() != 1:
+        raise TmaError("tma_layernorm_prelu_fwd: gamma / beta need F entries, slope one")
+    if out is None:
+        out = _padded(n, F, Z.dtype, Z.device)
+    if tuple(out.shape) != (n, F) or out.dtype != Z.dtype:
+        raise TmaError("tma_layernorm_prelu_fwd: out shape/dtype mismatch")
+    _, _, ldo = _rows_ld(out, "out")
+    _check(lib().tma_layernorm_prelu_fwd(
+        C.c_int64(n), C.c_int32(F), C.c_void_p(Z.data_ptr()), C.c_int64(ldz), _ptr(gamma, torch.float32, "gamma"),
+        _ptr(beta, torch.float32, "beta"), _ptr(slope, torch.float32, "slope"), C.c_float(eps),
+        C.c_int32(_feat_dtype(Z)), C.c_void_p(out.data_ptr()), C.c_int64(ldo), _stream(stream)))
+    return out
+
+
+def tma_layernorm_prelu_bwd_workspace_bytes(n: int, F: int) -> int:
+    return lib().tma_layernorm_prelu_bwd_workspace_bytes(C.c_int64(n), C.c_int32(F))
+
+
+def tma_layernorm_prelu_bwd(Z, dHnext, gamma, beta, slope, eps: float = LN_EPS, dZ_out=None, dgamma=None, dbeta=None,
+                            dslope=None, ws=None, stream=None):
+    """Returns (dZ, dgamma, dbeta, dslope).  dZ_out may be dHnext itself (overwritten in place)."""
+    n, F, ldz = _rows_ld(Z, "Z")
+    dev = Z.device
+    if tuple(dHnext.shape) != (n, F) or dHnext.dtype != Z.dtype:
+        raise TmaError("tma_layernorm_prelu_bwd: dHnext shape/dtype mismatch")
+    if gamma.numel() != F or beta.numel() != F or slope.numel() != 1:
+        raise TmaError("tma_layernorm_prelu_bwd: gamma / beta need F entries, slope one")
+    if dZ_out is None:
+        dZ_out = _padded(n, F, Z.dtype, dev)
+    if tuple(dZ_out.shape) != (n, F) or dZ_out.dtype != Z.dtype:
+        raise TmaError("tma_layernorm_prelu_bwd: dZ_out shape/dtype mismatch")
+    dgamma = torch.empty(F, dtype=torch.float32, device=dev) if dgamma is None else dgamma
+    dbeta = torch.empty(F, dtype=torch.float32, device=dev) if dbeta is None else dbeta
+    dslope = torch.empty(1, dtype=torch.float32, device=dev) if dslope is None else dslope
+    if dgamma.numel() != F or dbeta.numel() != F or dslope.numel() != 1:
+        raise TmaError("tma_layernorm_prelu_bwd: gradient output sizes")
+    if ws is None:
+        ws = _workspace(tma_layernorm_prelu_bwd_workspace_bytes(n, F), dev)
+    _, _, ldd = _rows_ld(dHnext, "dHnext")
+    _, _, ldo = _rows_ld(dZ_out, "dZ_out")
+    _check(lib().tma_layernorm_prelu_bwd(
+        C.c_int64(n), C.c_int32(F), C.c_void_p(Z.data_ptr()), C.c_int64(ldz), C.c_void_p(dHnext.data_ptr()),
+        C.c_int64(ldd), _ptr(gamma, torch.float32, "gamma"), _ptr(beta, torch.float32, "beta"),
+        _ptr(slope, torch.float32, "slope"), C.c_float(eps), C.c_int32(_feat_dtype(Z)),
+        C.c_void_p(dZ_out.data_ptr()), C.c_int64(ldo), _ptr(dgamma, torch.float32), _ptr(dbeta, torch.float32),
+        _ptr(dslope, torch.float32), _ptr(ws), C.c_size_t(ws.numel()), _stream(stream)))
+    return dZ_out, dgamma, dbeta, dslope
 
 
 def tma_softmax_ce(logits, labels, loss_out=None, dlogits_out=None, need_grad=True, ws=None, stream=None):

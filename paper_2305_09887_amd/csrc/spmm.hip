@@ -30,52 +30,6 @@ constexpr int kSpmmThreads = 256;
 constexpr int kRowsPerGroup = 4;   // rows a lane group walks through per block
 constexpr int kHubDegree = 48;     // rows longer than this are summed by the whole workgroup
 
-template <typename T>
-struct Chunk;
-
-template <>
-struct Chunk<float> {
-    static constexpr int kElems = 4;
-    static __device__ __forceinline__ void load(const float *p, float (&v)[4])
-    {
-        const float4 x = *reinterpret_cast<const float4 *>(p);
-        v[0] = x.x; v[1] = x.y; v[2] = x.z; v[3] = x.w;
-    }
-    static __device__ __forceinline__ void widen(const uint4 &x, float (&v)[4])
-    {
-        v[0] = __uint_as_float(x.x); v[1] = __uint_as_float(x.y); v[2] = __uint_as_float(x.z); v[3] = __uint_as_float(x.w);
-    }
-    static __device__ __forceinline__ void store(float *p, const float (&v)[4])
-    {
-        *reinterpret_cast<float4 *>(p) = make_float4(v[0], v[1], v[2], v[3]);
-    }
-};
-
-template <>
-struct Chunk<uint16_t> {  // bf16 storage
-    static constexpr int kElems = 8;
-    static __device__ __forceinline__ void load(const uint16_t *p, float (&v)[8])
-    {
-        widen(*reinterpret_cast<const uint4 *>(p), v);
-    }
-    static __device__ __forceinline__ void widen(const uint4 &x, float (&v)[8])
-    {
-        const uint32_t w[4] = {x.x, x.y, x.z, x.w};
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            v[2 * i] = __uint_as_float(w[i] << 16);
-            v[2 * i + 1] = __uint_as_float(w[i] & 0xFFFF0000u);
-        }
-    }
-    static __device__ __forceinline__ void store(uint16_t *p, const float (&v)[8])
-    {
-        uint32_t w[4];
-#pragma unroll
-        for (int i = 0; i < 4; ++i) w[i] = uint32_t(f32_to_bf16(v[2 * i])) | (uint32_t(f32_to_bf16(v[2 * i + 1])) << 16);
-        *reinterpret_cast<uint4 *>(p) = make_uint4(w[0], w[1], w[2], w[3]);
-    }
-};
-
 __device__ __forceinline__ float load_elem(const float *p) { return *p; }
 __device__ __forceinline__ float load_elem(const uint16_t *p) { return bf16_to_f32(*p); }
 __device__ __forceinline__ void store_elem(float *p, float v) { *p = v; }

@@ -1,0 +1,157 @@
+"""Layer normalisation + PReLU (the paper's encoder variant, Sec. 4.1) on the GPU against the fp64 oracle:
+the two entry points alone (fp32 1e-4, bf16 2e-2), and whole training steps of a model whose hidden layers use
+them.  The yes/no decision Y > 0 is taken in the kernel's precision on both sides (the sign of the kernel's own
+H', valid for a positive slope), as for ReLU."""
+import numpy as np
+import pytest
+
+import oracle
+from oracle import model as omodel
+from paper_2305_09887_amd import synth
+
+torch = pytest.importorskip("torch")
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def B():
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    from paper_2305_09887_amd import binding
+    binding.lib()
+    return binding
+
+
+def dev(a, dtype=None):
+    t = torch.as_tensor(np.ascontiguousarray(a))
+    return (t if dtype is None else t.to(dtype)).cuda()
+
+
+def dev_bf16(a):
+    bits = synth.to_bf16_bits(np.asarray(a, dtype=np.float32)).reshape(np.shape(a))
+    return torch.from_numpy(bits.view(np.int16)).cuda().view(torch.bfloat16)
+
+
+def close(got, want, tol, what):
+    got, want = np.asarray(got, np.float64), np.asarray(want, np.float64)
+    assert got.shape == want.shape, what
+    rel = np.linalg.norm((got - want).ravel()) / max(np.linalg.norm(want.ravel()), 1e-300)
+    mx = np.abs(got - want).max() / max(np.abs(want).max(), 1e-300)
+    assert rel <= tol and mx <= tol, f"{what}: rel fro {rel:.2e}, max abs / max {mx:.2e}"
+
+
+def _inputs(n, F, seed):
+    rng = np.random.default_rng(seed)
+    Z = rng.normal(0.2, 1.5, (n, F)).astype(np.float32)
+    g = (rng.normal(0.0, 1.0, (n, F)) / n).astype(np.float32)
+    gamma = rng.normal(1.0, 0.3, F).astype(np.float32)
+    beta = rng.normal(0.0, 0.4, F).astype(np.float32)
+    return Z, g, gamma, beta
+
+
+# widths: one chunk per lane with 4..64 lanes, several chunks per lane, rows that are not a multiple of 16 bytes
+@pytest.mark.parametrize("n,F", [(1, 8), (5000, 256), (3001, 64), (777, 16), (1500, 4), (900, 512), (300, 1024),
+                                 (2000, 100), (1000, 47), (640, 1), (1200, 300), (20_001, 128)])
+def test_layernorm_prelu_fp32(B, n, F):
+    Z, g, gamma, beta = _inputs(n, F, seed=F)
+    slope = torch.tensor([0.25], device="cuda")
+    Zd = B._padded(n, F, torch.float32, "cuda")
+    Zd.copy_(dev(Z))
+    H = B.tma_layernorm_prelu_fwd(Zd, dev(gamma), dev(beta), slope)
+    want = oracle.layernorm_prelu_fwd(Z, gamma, beta, 0.25)
+    close(H.cpu().numpy(), want, 1e-4, f"H' F={F}")
+    gd = B._padded(n, F, torch.float32, "cuda")
+    gd.copy_(dev(g))
+    dZ, dga, dbe, dsl = B.tma_layernorm_prelu_bwd(Zd, gd, dev(gamma), dev(beta), slope)
+    wZ, wga, wbe, wsl = oracle.layernorm_prelu_bwd(Z, g, gamma, beta, 0.25, open_mask=H.cpu().numpy() > 0)
+    close(dZ.cpu().numpy(), wZ, 1e-4, f"dZ F={F}")
+    close(dga.cpu().numpy(), wga, 1e-4, f"dgamma F={F}")
+    close(dbe.cpu().numpy(), wbe, 1e-4, f"dbeta F={F}")
+    assert abs(dsl.item() - wsl) <= 1e-4 * max(abs(wsl), np.abs(g * want).sum() * 1e-3), (dsl.item(), wsl)
+    # in place (dZ over dH') and run-to-run: the same bits
+    again = B.tma_layernorm_prelu_bwd(Zd, gd, dev(gamma), dev(beta), slope, dZ_out=gd)
+    assert torch.equal(again[0], dZ) and torch.equal(again[1], dga) and torch.equal(again[3], dsl)
+
+
+def test_layernorm_prelu_unpadded_rows_take_the_element_path(B):
+    n, F = 1234, 100
+    Z, g, gamma, beta = _inputs(n, F, seed=3)
+    slope = torch.tensor([0.1], device="cuda")
+    big = torch.zeros((n, F + 3), device="cuda")          # leading dimension 103: no 16-byte alignment
+    Zd = big[:, 1:F + 1]
+    Zd.copy_(dev(Z))
+    out = torch.full((n, F + 3), 9.0, device="cuda")
+    H = B.tma_layernorm_prelu_fwd(Zd, dev(gamma), dev(beta), slope, out=out[:, 1:F + 1])
+    close(H.cpu().numpy(), oracle.layernorm_prelu_fwd(Z, gamma, beta, 0.1), 1e-4, "H'")
+    assert torch.all(out[:, 0] == 9.0) and torch.all(out[:, F + 1:] == 9.0)
+
+
+@pytest.mark.parametrize("n,F", [(4000, 256), (1500, 104), (900, 64), (700, 100)])
+def test_layernorm_prelu_bf16(B, n, F):
+    Z, g, gamma, beta = _inputs(n, F, seed=F + 1)
+    Z, g = synth.round_bf16(Z), synth.round_bf16(g)
+    slope = torch.tensor([0.25], device="cuda")
+    Zd = B._padded(n, F, torch.bfloat16, "cuda")
+    Zd.copy_(dev_bf16(Z))
+    H = B.tma_layernorm_prelu_fwd(Zd, dev(gamma), dev(beta), slope)
+    assert H.dtype == torch.bfloat16
+    close(H.float().cpu().numpy(), oracle.layernorm_prelu_fwd(Z, gamma, beta, 0.25), 2e-2, "H'")
+    gd = B._padded(n, F, torch.bfloat16, "cuda")
+    gd.copy_(dev_bf16(g))
+    dZ, dga, dbe, dsl = B.tma_layernorm_prelu_bwd(Zd, gd, dev(gamma), dev(beta), slope)
+    wZ, wga, wbe, wsl = oracle.layernorm_prelu_bwd(Z, g, gamma, beta, 0.25, open_mask=H.float().cpu().numpy() > 0)
+    close(dZ.float().cpu().numpy(), wZ, 2e-2, "dZ")
+    close(dga.cpu().numpy(), wga, 2e-2, "dgamma")
+    close(dbe.cpu().numpy(), wbe, 2e-2, "dbeta")
+    assert abs(dsl.item() - wsl) <= 2e-2 * max(abs(wsl), 1e-6)
+
+
+def test_layernorm_prelu_rejects_bad_arguments(B):
+    Z = torch.zeros((10, 8), device="cuda")
+    ga, be, sl = torch.ones(8, device="cuda"), torch.zeros(8, device="cuda"), torch.ones(1, device="cuda")
+    with pytest.raises(B.TmaError):
+        B.tma_layernorm_prelu_fwd(Z, ga[:7], be, sl)
+    with pytest.raises(B.TmaError, match="eps"):
+        B.tma_layernorm_prelu_fwd(Z, ga, be, sl, eps=-1.0)
+    with pytest.raises(B.TmaError, match="beyond"):
+        B.tma_layernorm_prelu_fwd(torch.zeros((2, 1028), device="cuda"), torch.ones(1028, device="cuda"),
+                                  torch.ones(1028, device="cuda"), sl)
+    assert B.tma_layernorm_prelu_fwd(Z[:0], ga, be, sl).shape == (0, 8)
+    torch.cuda.synchronize()
+
+
+def test_training_steps_with_normalised_hidden_layers(B):
+    """Three steps of a 3-layer model (64-96-64-16) on the tiny configuration's part 0."""
+    from paper_2305_09887_amd.trainer import LocalTrainer
+    N, K, dims = 20_000, 4, [64, 96, 64, 16]
+    rowptr, colidx = synth.uniform_graph(N, 100_000, seed=1)
+    X, y = synth.features(N, dims[0], seed=2), synth.labels(N, dims[-1], seed=3)
+    rng = np.random.default_rng(7)
+    params = []
+    for l, (Ws, Wn, b) in enumerate(synth.sage_params(dims, seed=5)):
+        layer = [Ws, Wn, b]
+        if l < len(dims) - 2:
+            layer += [rng.normal(1.0, 0.1, dims[l + 1]).astype(np.float32),
+                      rng.normal(0.0, 0.1, dims[l + 1]).astype(np.float32), np.array([0.25], dtype=np.float32)]
+        params.append(tuple(layer))
+    part_o = oracle.partition(N, K, seed=4)
+    sub_o = oracle.induced_subgraph(rowptr, colidx, part_o, 0)
+    Xo, yo = X[sub_o["l2g"]], y[sub_o["l2g"]]
+    tr = LocalTrainer(dev(sub_o["rowptr"]), dev(sub_o["colidx"]), dev(sub_o["inv_deg"], torch.float32), dev(Xo), dev(yo),
+                      dims, params=params, norm_act=True)
+    p_o = [tuple(np.asarray(t, dtype=np.float64) for t in l) for l in params]
+    assert tr.n_params == omodel.flatten(p_o).size
+    lr, losses = 0.05, []
+    names = ("dW_self", "dW_neigh", "dbias", "dgamma", "dbeta", "dslope")
+    for step in range(3):
+        loss_g = tr.step(lr).item()
+        open_ = [tr.H[1].cpu().numpy() > 0, tr.H[2].cpu().numpy() > 0, None]
+        loss_o, grads_o, _, _ = omodel.loss_and_grads(sub_o["rowptr"], sub_o["colidx"], Xo, yo, p_o, open_)
+        assert abs(loss_g - loss_o) <= 1e-4 * abs(loss_o), f"loss at step {step}"
+        for l in range(3):
+            for g, w, name in zip(tr.grads[l], grads_o[l], names):
+                close(g.cpu().numpy().ravel(), np.asarray(w).ravel(), 1e-4, f"step {step} layer {l} {name}")
+        _, p_o = omodel.train_step(sub_o["rowptr"], sub_o["colidx"], Xo, yo, p_o, lr, open_)
+        close(tr.W.cpu().numpy(), omodel.flatten(p_o), 1e-4, f"weights after step {step}")
+        losses.append(loss_g)
+    assert losses[2] < losses[0]
