@@ -206,6 +206,15 @@ def sgd_step(W, dW, lr: float) -> np.ndarray:
     return W
 
 
+def adam_step(W, dW, m, v, lr: float, t: int, b1: float = 0.9, b2: float = 0.999, eps: float = 1e-8):
+    """One Adam update; returns new (W, m, v).  t = 1 for the first step."""
+    W, m, v = _f64(W).copy(), _f64(m).copy(), _f64(v).copy()
+    dW = _f64(dW)
+    lib().orc_adam_step(C.c_int64(W.size), _p(W), _p(dW), _p(m), _p(v), C.c_double(lr), C.c_double(b1),
+                        C.c_double(b2), C.c_double(eps), C.c_int64(t))
+    return W, m, v
+
+
 def average(W_stack, active_mask: int | None = None):
     """phi = mean over active trainers.  W_stack [M, P] -> (W_after [M,P], W_global [P])."""
     W = _f64(W_stack).copy()

@@ -365,6 +365,22 @@ void orc_sgd_step(int64_t P, double *W, const double *dW, double lr)
     for (int64_t i = 0; i < P; ++i) W[i] -= lr * dW[i];
 }
 
+/* Adam (Kingma & Ba 2015) as a second choice for Alg. 2's `optimizer` call, which the paper leaves
+ * unnamed.  t = 1, 2, ... is the number of the step being taken.  The moment estimates m, v are the
+ * trainer's own state: the aggregation operator averages model parameters only (Sec. 3.1).
+ *     m <- b1 m + (1-b1) g,   v <- b2 v + (1-b2) g^2,
+ *     W <- W - lr * (m / (1-b1^t)) / (sqrt(v / (1-b2^t)) + eps)                                    */
+void orc_adam_step(int64_t P, double *W, const double *dW, double *m, double *v, double lr,
+                   double b1, double b2, double eps, int64_t t)
+{
+    const double c1 = 1.0 - pow(b1, (double)t), c2 = 1.0 - pow(b2, (double)t);
+    for (int64_t i = 0; i < P; ++i) {
+        m[i] = b1 * m[i] + (1.0 - b1) * dW[i];
+        v[i] = b2 * v[i] + (1.0 - b2) * dW[i] * dW[i];
+        W[i] -= lr * (m[i] / c1) / (sqrt(v[i] / c2) + eps);
+    }
+}
+
 void orc_average(int32_t M, int64_t P, uint64_t active, double *W, double *W_global)
 {
     int cnt = 0;
