@@ -253,6 +253,15 @@ int tma_sigmoid_l2(int64_t n, int32_t C, const void *G, int64_t ld, int32_t dtyp
  * ---------------------------------------------------------------------- */
 int tma_sgd_step(int64_t n_params, float *W, const float *dW, float lr, tma_stream_t stream);
 
+/* Adam (Kingma & Ba) as a second choice for the same call, with bias correction:
+ *     m <- beta1 m + (1-beta1) dW,  v <- beta2 v + (1-beta2) dW^2,
+ *     W <- W - lr (m / (1-beta1^step)) / (sqrt(v / (1-beta2^step)) + eps),   step = 1, 2, ...
+ * The scalars are doubles so that 1-beta and the bias corrections are formed exactly before they are
+ * narrowed.  m, v [n_params] fp32 are the trainer's own state (zero before the first step); the
+ * aggregation operator averages parameters only (Sec. 3.1), never this state. */
+int tma_adam_step(int64_t n_params, float *W, const float *dW, float *m, float *v,
+                  double lr, double beta1, double beta2, double eps, int64_t step, tma_stream_t stream);
+
 /* ------------------------------------------------------------------------
  * Aggregation operator phi of Alg. 1 = arithmetic mean of the trainers'
  * parameters (Sec. 3.1), followed by the overwrite of Alg. 2: every ACTIVE

@@ -9,7 +9,7 @@ from __future__ import annotations
 
 import numpy as np
 
-from . import (ACT_NONE, ACT_RELU, average, layernorm_prelu_bwd, layernorm_prelu_fwd,
+from . import (ACT_NONE, ACT_RELU, adam_step, average, layernorm_prelu_bwd, layernorm_prelu_fwd,
                sage_layer_bwd, sage_layer_fwd, sgd_step, softmax_ce)
 
 ACT_LN_PRELU = "ln_prelu"   # a layer whose parameter tuple is (W_self, W_neigh, b, gamma, beta, slope)
@@ -71,6 +71,16 @@ def train_step(rowptr, colidx, X, y, params, lr, relu_open=None):
     new = [tuple(sgd_step(w, g, lr).reshape(np.shape(w)) for w, g in zip(pl, gl))
            for pl, gl in zip(params, grads)]
     return loss, new
+
+
+def train_step_adam(rowptr, colidx, X, y, params, lr, state, t, relu_open=None):
+    """One Alg. 2 iteration with Adam.  state = (m, v) flat vectors (None before the first step), t = 1, 2, ...
+    Returns (loss, new params, new state); the state belongs to the trainer and is never averaged."""
+    loss, grads, _, _ = loss_and_grads(rowptr, colidx, X, y, params, relu_open)
+    w, g = flatten(params), flatten(grads)
+    m, v = (np.zeros_like(w), np.zeros_like(w)) if state is None else state
+    w, m, v = adam_step(w, g, m, v, lr, t)
+    return loss, unflatten(w, params), (m, v)
 
 
 def flatten(params) -> np.ndarray:

@@ -25,7 +25,7 @@ EXPORTS = (
     "tma_mean_aggregate", "tma_sage_layer_aggregates_first", "tma_sage_layer_fwd",
     "tma_sage_layer_bwd_workspace_bytes", "tma_sage_layer_bwd",
     "tma_layernorm_prelu_fwd", "tma_layernorm_prelu_bwd_workspace_bytes", "tma_layernorm_prelu_bwd",
-    "tma_loss_workspace_bytes", "tma_softmax_ce", "tma_sigmoid_l2", "tma_sgd_step", "tma_average",
+    "tma_loss_workspace_bytes", "tma_softmax_ce", "tma_sigmoid_l2", "tma_sgd_step", "tma_adam_step", "tma_average",
     "tma_gather_rows", "tma_profile_begin", "tma_profile_end", "tma_profile_count", "tma_profile_entry",
 )
 
@@ -371,6 +371,16 @@ def tma_sgd_step(W, dW, lr: float, stream=None):
         raise TmaError("tma_sgd_step: W and dW differ in size")
     _check(lib().tma_sgd_step(C.c_int64(W.numel()), _ptr(W, torch.float32, "W"), _ptr(dW, torch.float32, "dW"),
                               C.c_float(lr), _stream(stream)))
+    return W
+
+
+def tma_adam_step(W, dW, m, v, lr: float, step: int, beta1: float = 0.9, beta2: float = 0.999, eps: float = 1e-8,
+                  stream=None):
+    if not (W.numel() == dW.numel() == m.numel() == v.numel()):
+        raise TmaError("tma_adam_step: W, dW, m, v must have the same length")
+    _check(lib().tma_adam_step(C.c_int64(W.numel()), _ptr(W, torch.float32, "W"), _ptr(dW, torch.float32, "dW"),
+                               _ptr(m, torch.float32, "m"), _ptr(v, torch.float32, "v"), C.c_double(lr),
+                               C.c_double(beta1), C.c_double(beta2), C.c_double(eps), C.c_int64(step), _stream(stream)))
     return W
 
 

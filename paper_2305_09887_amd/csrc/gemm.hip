@@ -1094,6 +1094,7 @@ template <int BM, int BN, int BK, int WM, int WN, bool kColSum, class AL, class 
 static void launch_gemm(const char *name, const AL &a, const BL &b, const Epi &e, int64_t M, int N, int64_t K,
                         int64_t k_per_split, int n_splits, float *colsum_partial, hipStream_t s)
 {
+    if (M <= 0 || N <= 0 || K <= 0) return;   // an empty product: callers zero-fill what they need
     const int n_tiles = int(ceil_div(N, BN));
     const int64_t tiles = ceil_div(M, BM) * n_tiles;
     const int64_t total = tiles * n_splits;
@@ -1301,7 +1302,10 @@ int launch_sage_gemm_bwd_weight(int64_t n, const void *H, int64_t ldh, const voi
     float *colsum = reinterpret_cast<float *>(static_cast<char *>(ws) + w.partial_bytes);
     const int64_t Mtot = 2 * int64_t(F_in);
     SplitEpilogue e{partial, Mtot, F_out};
-    if (F_in > 0) {
+    // An empty node set leaves nothing to multiply: the operands may then be NULL, and the kernel's clamped
+    // loads would have no valid row to fall back to.  The second stage alone writes the zero gradients.
+    const bool have_rows = F_in > 0 && n > 0;
+    if (have_rows) {
         int rc;
         if (dtype == TMA_F32)
             rc = bwd_weight_typed<float>(n, static_cast<const float *>(H), ldh, static_cast<const float *>(M),
@@ -1317,7 +1321,7 @@ int launch_sage_gemm_bwd_weight(int64_t n, const void *H, int64_t ldh, const voi
     const int64_t total_all = Mtot * F_out + F_out;
     TMA_TIMED("reduce_splits", stream);
     hipLaunchKernelGGL(reduce_splits_kernel, dim3(unsigned(ceil_div(total_all, 4 * kRedCols))), dim3(256), 0, stream,
-                       partial, colsum, F_in > 0 ? w.n_splits : 0, F_in, F_out, dW_self, dW_neigh, dbias);
+                       partial, colsum, have_rows ? w.n_splits : 0, F_in, F_out, dW_self, dW_neigh, dbias);
     return check_launch("sage gemm bwd weight reduce");
 }
 
@@ -1438,8 +1442,10 @@ int launch_sage_tf_gemm_bwd_weight(int64_t n, const void *H, int64_t ldh, const 
     float *partial = static_cast<float *>(ws);
     float *colsum = reinterpret_cast<float *>(static_cast<char *>(ws) + w.partial_bytes);
     const bool relu = act == TMA_ACT_RELU;
-    int rc;
-    if (dtype == TMA_F32)
+    int rc = TMA_OK;
+    if (n == 0) {
+        // no rows: nothing to multiply (operands may be NULL); the second stage writes the zero gradients
+    } else if (dtype == TMA_F32)
         rc = tf_bwd_weight_typed<float>(n, static_cast<const float *>(H), ldh, static_cast<const float *>(dHnext),
                                         static_cast<const float *>(Hnext), ld_next, static_cast<const float *>(dYn),
                                         ldy, F_in, F_out, Fp, relu, w, partial, colsum, stream);
@@ -1453,7 +1459,7 @@ int launch_sage_tf_gemm_bwd_weight(int64_t n, const void *H, int64_t ldh, const 
     const int64_t total_all = int64_t(F_in) * 2 * Fp + 2 * Fp;
     TMA_TIMED("reduce_splits_halves", stream);
     hipLaunchKernelGGL(reduce_splits_halves_kernel, dim3(unsigned(ceil_div(total_all, kRedCols))), dim3(256), 0, stream,
-                       partial, colsum, w.n_splits, F_in, F_out, Fp, dW_self, dW_neigh, dbias);
+                       partial, colsum, n > 0 ? w.n_splits : 0, F_in, F_out, Fp, dW_self, dW_neigh, dbias);
     return check_launch("sage gemm tf bwd weight reduce");
 }
 

@@ -2,6 +2,8 @@
 // averaging operator.  All small, streaming or latency-bound kernels.
 #include "common.hpp"
 
+#include <cmath>
+
 namespace tma {
 
 __device__ __forceinline__ float ld(const float *p) { return *p; }
@@ -137,6 +139,24 @@ __global__ __launch_bounds__(256) void sgd_kernel(int64_t n, float *__restrict__
     for (int64_t i = int64_t(blockIdx.x) * 256 + threadIdx.x; i < n; i += stride) W[i] -= lr * dW[i];
 }
 
+// Adam with bias correction; 1 - b, c1 = 1 - b1^t and c2 = 1 - b2^t are formed on the host in double precision
+// (1 - 0.999 taken in fp32 is already off by 1e-5).
+__global__ __launch_bounds__(256) void adam_kernel(int64_t n, float *__restrict__ W, const float *__restrict__ dW,
+                                                   float *__restrict__ m, float *__restrict__ v, float lr, float b1,
+                                                   float omb1, float b2, float omb2, float eps, float inv_c1,
+                                                   float inv_c2)
+{
+    const int64_t stride = int64_t(gridDim.x) * 256;
+    for (int64_t i = int64_t(blockIdx.x) * 256 + threadIdx.x; i < n; i += stride) {
+        const float g = dW[i];
+        const float mi = b1 * m[i] + omb1 * g;
+        const float vi = b2 * v[i] + omb2 * g * g;
+        m[i] = mi;
+        v[i] = vi;
+        W[i] -= lr * (mi * inv_c1) / (sqrtf(vi * inv_c2) + eps);
+    }
+}
+
 // Mean over the active trainers in index order, written back to each of them.
 __global__ __launch_bounds__(256) void average_kernel(float *const *__restrict__ W_ptrs, int n_trainers,
                                                       uint64_t active, float inv_count, int64_t n,
@@ -249,6 +269,27 @@ extern "C" int tma_sgd_step(int64_t n_params, float *W, const float *dW, float l
     if (blocks > 4096) blocks = 4096;
     TMA_TIMED("sgd", as_stream(stream));
     hipLaunchKernelGGL(sgd_kernel, dim3(unsigned(blocks)), dim3(256), 0, as_stream(stream), n_params, W, dW, lr);
+    return check_launch(fn);
+}
+
+extern "C" int tma_adam_step(int64_t n_params, float *W, const float *dW, float *m, float *v, double lr, double beta1,
+                             double beta2, double eps, int64_t step, tma_stream_t stream)
+{
+    using namespace tma;
+    const char *fn = "tma_adam_step";
+    TMA_REQUIRE(n_params >= 0, TMA_ERR_INVALID_ARG, "%s: n_params < 0", fn);
+    TMA_REQUIRE(step >= 1, TMA_ERR_INVALID_ARG, "%s: step counts from 1", fn);
+    TMA_REQUIRE(beta1 >= 0.0 && beta1 < 1.0 && beta2 >= 0.0 && beta2 < 1.0 && eps >= 0.0, TMA_ERR_INVALID_ARG,
+                "%s: need 0 <= beta < 1 and eps >= 0", fn);
+    if (n_params == 0) return TMA_OK;
+    TMA_REQUIRE(W && dW && m && v, TMA_ERR_INVALID_ARG, "%s: NULL argument", fn);
+    const double c1 = 1.0 - pow(beta1, double(step)), c2 = 1.0 - pow(beta2, double(step));
+    int64_t blocks = ceil_div(n_params, 256);
+    if (blocks > 4096) blocks = 4096;
+    TMA_TIMED("adam", as_stream(stream));
+    hipLaunchKernelGGL(adam_kernel, dim3(unsigned(blocks)), dim3(256), 0, as_stream(stream), n_params, W, dW, m, v,
+                       float(lr), float(beta1), float(1.0 - beta1), float(beta2), float(1.0 - beta2), float(eps),
+                       float(1.0 / c1), float(1.0 / c2));
     return check_launch(fn);
 }
 

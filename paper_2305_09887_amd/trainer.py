@@ -17,7 +17,7 @@ class LocalTrainer:
 
     ``dims`` = [F_0, F_1, ..., F_L]; between layers ReLU, or with ``norm_act`` layer
     normalisation followed by PReLU (the paper's encoder variant, Sec. 4.1); identity on
-    the last; mean softmax cross-entropy over all local nodes; plain SGD.
+    the last; mean softmax cross-entropy over all local nodes; plain SGD, or Adam with trainer-local moments.
     Parameters live in one flat fp32 vector ``W`` (layer by layer: W_self,
     W_neigh, bias, and with ``norm_act`` gamma, beta, slope of the hidden layers),
     gradients in ``dW`` with the same layout, so that the optimizer step and the
@@ -25,8 +25,11 @@ class LocalTrainer:
     """
 
     def __init__(self, rowptr, colidx, inv_deg, X, labels, dims, params=None, stream=None,
-                 rowptr_T=None, colidx_T=None, norm_act=False):
+                 rowptr_T=None, colidx_T=None, norm_act=False, optimizer="sgd"):
         self.norm_act = bool(norm_act)
+        if optimizer not in ("sgd", "adam"):
+            raise B.TmaError("LocalTrainer: optimizer must be 'sgd' or 'adam'")
+        self.optimizer = optimizer
         self.rowptr, self.colidx, self.inv_deg = rowptr, colidx, inv_deg
         # transposed graph for the backward gather; the same CSR for a symmetric graph
         self.rowptr_T = rowptr if rowptr_T is None else rowptr_T
@@ -47,6 +50,9 @@ class LocalTrainer:
         self.W = torch.zeros(self.n_params, dtype=torch.float32, device=dev)
         self.dW = torch.zeros(self.n_params, dtype=torch.float32, device=dev)
         self.layers, self.grads = self._views(self.W), self._views(self.dW)
+        if optimizer == "adam":   # moment estimates: this trainer's own state, never averaged
+            self.adam_m = torch.zeros_like(self.W)
+            self.adam_v = torch.zeros_like(self.W)
         if params is not None:
             self.load_params(params)
 
@@ -137,6 +143,9 @@ class LocalTrainer:
         """One iteration of Alg. 2's loop body on the full local subgraph."""
         self.forward()
         self.backward()
-        B.tma_sgd_step(self.W, self.dW, lr, stream=self.stream)
+        if self.optimizer == "adam":
+            B.tma_adam_step(self.W, self.dW, self.adam_m, self.adam_v, lr, self.steps_done + 1, stream=self.stream)
+        else:
+            B.tma_sgd_step(self.W, self.dW, lr, stream=self.stream)
         self.steps_done += 1
         return self.loss

@@ -335,6 +335,22 @@ def test_sage_layer_backward_on_asymmetric_graph_uses_transposed_csr(B):
         assert_close(g.cpu().numpy(), w, what=name)
 
 
+@pytest.mark.parametrize("F_in,F_out", [(32, 48), (64, 8)])
+def test_sage_layer_with_an_empty_node_set(B, F_in, F_out):
+    """A trainer whose partition received no node: forward does nothing, backward writes zero gradients, and
+    no kernel touches the (empty, possibly NULL) operands.  Both forms of the layer."""
+    e32 = torch.zeros(1, dtype=torch.int32, device="cuda")
+    H = torch.empty((0, F_in), device="cuda")
+    Ws, Wn, b = torch.randn(F_in, F_out, device="cuda"), torch.randn(F_in, F_out, device="cuda"), torch.randn(F_out, device="cuda")
+    M, Hn = B.tma_sage_layer_fwd(e32, e32[:0], torch.zeros(0, device="cuda"), H, Ws, Wn, b, B.TMA_ACT_RELU)
+    assert M.shape == (0, F_in) and Hn.shape == (0, F_out)
+    dWs, dWn, db = torch.full_like(Ws, 7.0), torch.full_like(Wn, 7.0), torch.full_like(b, 7.0)
+    B.tma_sage_layer_bwd(e32, e32[:0], torch.zeros(0, device="cuda"), H, M, Hn, torch.empty((0, F_out), device="cuda"),
+                         Ws, Wn, B.TMA_ACT_RELU, dW_self=dWs, dW_neigh=dWn, dbias=db, need_dH=True)
+    torch.cuda.synchronize()
+    assert torch.all(dWs == 0) and torch.all(dWn == 0) and torch.all(db == 0)
+
+
 def test_sage_layer_rejects_bad_shapes(B):
     z32 = torch.zeros(4, dtype=torch.int32, device="cuda")
     H = torch.zeros((3, 8), device="cuda")
