@@ -277,6 +277,6 @@ def test_tma_schedule_timeline():
     assert final == [36] * 3
     # a slow trainer (1.4x) finishes fewer steps; the fast ones wait for it at each round
     rounds, _ = model.tma_schedule(lambda i, k: 1.4 if i == 2 else 1.0, 3, dt_int=10.5, dt_train=25.0)
-    # round 1: flag at 10.5; fast cross it after 11 steps (t=11.0), slow after 8 (t=11.2)
-    # round 2 starts at 11.2: flag at 21.7; fast need 11 more (22.2), slow 8 more (22.4)
+    # first aggregation: flag at 10.5; fast cross it after 11 steps (t=11.0), slow after 8 (t=11.2)
+    # the second interval starts at 11.2: flag at 21.7; fast need 11 more (22.2), slow 8 more (22.4)
     assert rounds == [[11, 11, 8], [22, 22, 16]]
