@@ -729,6 +729,77 @@ struct SplitEpilogue {  // partial products, one slab per split
 };
 
 // ---------------------------------------------------------------------------
+// Arithmetic of the tile product.  CT = float: operands sit in LDS as fp32 and a
+// group of 8 k-values is four v_mfma_f32_32x32x2_f32.  CT = uint16_t: operands sit
+// in LDS as bf16 (activations stored in bf16 pass through unchanged, fp32 weights
+// are rounded to nearest even on their way in) and the same group is ONE
+// v_mfma_f32_32x32x8_bf16_1k, whose operand layout -- lane l holds row l%32 and the
+// four k-values 4*(l/32) .. +3 -- is exactly the fragment the fp32 path reads, so
+// tile layouts, loaders and epilogues are shared.  Accumulation is fp32 in both.
+// ---------------------------------------------------------------------------
+typedef short shortx4 __attribute__((ext_vector_type(4)));
+typedef float floatx2 __attribute__((ext_vector_type(2)));
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+
+// two fp32 values to a pair of bf16, round to nearest even (one v_cvt_pk_bf16_f32)
+__device__ __forceinline__ uint32_t pack_bf16(float lo, float hi)
+{
+    floatx2 v;
+    v[0] = lo;
+    v[1] = hi;
+    return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2));
+}
+
+template <typename CT>
+struct TileMath;
+
+template <>
+struct TileMath<float> {
+    typedef float4 Frag;
+    static __device__ __forceinline__ void put(float *dst, const float4 &v) { *reinterpret_cast<float4 *>(dst) = v; }
+    static __device__ __forceinline__ Frag along(const float *p) { return *reinterpret_cast<const float4 *>(p); }
+    static __device__ __forceinline__ Frag strided(const float *p, int ld)
+    {
+        return make_float4(p[0], p[ld], p[2 * ld], p[3 * ld]);
+    }
+    static __device__ __forceinline__ float value(const float *p) { return *p; }
+    static __device__ __forceinline__ void mma(const Frag &a, const Frag &b, floatx16 &acc)
+    {
+        acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a.x, b.x, acc, 0, 0, 0);
+        acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a.y, b.y, acc, 0, 0, 0);
+        acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a.z, b.z, acc, 0, 0, 0);
+        acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a.w, b.w, acc, 0, 0, 0);
+    }
+};
+
+template <>
+struct TileMath<uint16_t> {
+    typedef shortx4 Frag;
+    static __device__ __forceinline__ void put(uint16_t *dst, const float4 &v)
+    {
+        *reinterpret_cast<uint2 *>(dst) = make_uint2(pack_bf16(v.x, v.y), pack_bf16(v.z, v.w));
+    }
+    static __device__ __forceinline__ Frag along(const uint16_t *p)
+    {
+        const uint2 w = *reinterpret_cast<const uint2 *>(p);
+        Frag f;
+        f[0] = short(w.x & 0xFFFFu); f[1] = short(w.x >> 16); f[2] = short(w.y & 0xFFFFu); f[3] = short(w.y >> 16);
+        return f;
+    }
+    static __device__ __forceinline__ Frag strided(const uint16_t *p, int ld)
+    {
+        Frag f;
+        f[0] = short(p[0]); f[1] = short(p[ld]); f[2] = short(p[2 * ld]); f[3] = short(p[3 * ld]);
+        return f;
+    }
+    static __device__ __forceinline__ float value(const uint16_t *p) { return bf16_to_f32(*p); }
+    static __device__ __forceinline__ void mma(const Frag &a, const Frag &b, floatx16 &acc)
+    {
+        acc = __builtin_amdgcn_mfma_f32_32x32x8bf16_1k(a, b, acc, 0, 0, 0);
+    }
+};
+
+// ---------------------------------------------------------------------------
 // C[M,N] = A[M,K] B[K,N], k split into ranges of k_per_split, fp32 MFMA.
 // Work item = (split, m-tile, n-tile), numbered split-major then m then n.
 // Persistent blocks: the grid is 8 x (blocks per die); the block with id b sits
@@ -743,8 +814,8 @@ struct SplitEpilogue {  // partial products, one slab per split
 // inside the result is written out without per-element bounds tests, which also
 // gives the compiler a fixed number of stores to count its waits against.
 // ---------------------------------------------------------------------------
-template <int BM, int BN, int BK, int WM, int WN, bool kColSum, class AL, class BL, class Epi>
-__global__ __launch_bounds__(WM *WN * 64, (BK <= 16 && !Epi::kRowAux ? 3 : 2)) void gemm_f32_kernel(AL a, BL b, Epi epi, int64_t M, int N, int64_t K,
+template <typename CT, int BM, int BN, int BK, int WM, int WN, bool kColSum, class AL, class BL, class Epi>
+__global__ __launch_bounds__(WM *WN * 64, (BK * sizeof(CT) <= 64 && !Epi::kRowAux ? 3 : 2)) void gemm_f32_kernel(AL a, BL b, Epi epi, int64_t M, int N, int64_t K,
                                                                  int64_t k_per_split, int n_tiles,
                                                                  int64_t tiles_per_split, int64_t total_work,
                                                                  float *__restrict__ colsum_partial)
@@ -754,7 +825,9 @@ __global__ __launch_bounds__(WM *WN * 64, (BK <= 16 && !Epi::kRowAux ? 3 : 2)) v
     constexpr int TN = BN / WN / 32;
     constexpr int A_V = BM * BK / 4 / NT;
     constexpr int B_V = BN * BK / 4 / NT;
-    constexpr int KG = BK / 8;  // groups of 8 k-values = 4 MFMAs
+    using Math = TileMath<CT>;
+    typedef typename Math::Frag Frag;
+    constexpr int KG = BK / 8;  // groups of 8 k-values = 4 fp32 MFMAs or one bf16 MFMA
     constexpr int A_LD = AL::kContigK ? BK + kPad : BM + kPad;
     constexpr int B_LD = BL::kContigK ? BK + kPad : BN + kPad;
     constexpr int A_WORDS = AL::kContigK ? BM * A_LD : BK * A_LD;
@@ -762,10 +835,13 @@ __global__ __launch_bounds__(WM *WN * 64, (BK <= 16 && !Epi::kRowAux ? 3 : 2)) v
     static_assert(BM % (WM * 32) == 0 && BN % (WN * 32) == 0 && BK % 8 == 0, "tile shape");
     static_assert((BM * BK / 4) % NT == 0 && (BN * BK / 4) % NT == 0, "loader shape");
     static_assert(!kColSum || !BL::kContigK, "column sums are taken from a [k][n] tile");
-    static_assert(A_WORDS >= BN && B_WORDS >= BM, "epilogue staging fits");
+    static_assert(A_WORDS * sizeof(CT) >= BN * sizeof(float) && B_WORDS * sizeof(CT) >= BM * sizeof(float),
+                  "epilogue staging fits");
 
-    __shared__ __attribute__((aligned(16))) float As[2][A_WORDS];
-    __shared__ __attribute__((aligned(16))) float Bs[2][B_WORDS];
+    __shared__ __attribute__((aligned(16))) CT As[2][A_WORDS];
+    __shared__ __attribute__((aligned(16))) CT Bs[2][B_WORDS];
+    float *const a_aux = reinterpret_cast<float *>(&As[0][0]);   // per-column / per-row epilogue inputs
+    float *const b_aux = reinterpret_cast<float *>(&Bs[0][0]);
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
@@ -842,24 +918,22 @@ __global__ __launch_bounds__(WM *WN * 64, (BK <= 16 && !Epi::kRowAux ? 3 : 2)) v
     };
     auto stage = [&](int buf, const typename AL::Raw(&ar)[A_V], const typename BL::Raw(&br)[B_V]) {
 #pragma unroll
-        for (int i = 0; i < A_V; ++i) *reinterpret_cast<float4 *>(&As[buf][a_lds[i]]) = AL::resolve(ar[i]);
+        for (int i = 0; i < A_V; ++i) Math::put(&As[buf][a_lds[i]], AL::resolve(ar[i]));
 #pragma unroll
-        for (int i = 0; i < B_V; ++i) *reinterpret_cast<float4 *>(&Bs[buf][b_lds[i]]) = BL::resolve(br[i]);
+        for (int i = 0; i < B_V; ++i) Math::put(&Bs[buf][b_lds[i]], BL::resolve(br[i]));
     };
     // The four k-values (4*hi + 0..3 of group g) of this lane's row/column, for the 4 MFMAs of the group.
-    auto frag_a = [&](int buf, int g, int i) -> float4 {
+    auto frag_a = [&](int buf, int g, int i) -> Frag {
         const int mn = wm0 + i * 32 + l31;
         const int k = g * 8 + 4 * hi;
-        if (AL::kContigK) return *reinterpret_cast<const float4 *>(&As[buf][mn * A_LD + k]);
-        return make_float4(As[buf][(k + 0) * A_LD + mn], As[buf][(k + 1) * A_LD + mn], As[buf][(k + 2) * A_LD + mn],
-                           As[buf][(k + 3) * A_LD + mn]);
+        if (AL::kContigK) return Math::along(&As[buf][mn * A_LD + k]);
+        return Math::strided(&As[buf][k * A_LD + mn], A_LD);
     };
-    auto frag_b = [&](int buf, int g, int j) -> float4 {
+    auto frag_b = [&](int buf, int g, int j) -> Frag {
         const int mn = wn0 + j * 32 + l31;
         const int k = g * 8 + 4 * hi;
-        if (BL::kContigK) return *reinterpret_cast<const float4 *>(&Bs[buf][mn * B_LD + k]);
-        return make_float4(Bs[buf][(k + 0) * B_LD + mn], Bs[buf][(k + 1) * B_LD + mn], Bs[buf][(k + 2) * B_LD + mn],
-                           Bs[buf][(k + 3) * B_LD + mn]);
+        if (BL::kContigK) return Math::along(&Bs[buf][mn * B_LD + k]);
+        return Math::strided(&Bs[buf][k * B_LD + mn], B_LD);
     };
 
     int64_t work = die * per_die + blockIdx.x / kXcds;
@@ -894,7 +968,7 @@ __global__ __launch_bounds__(WM *WN * 64, (BK <= 16 && !Epi::kRowAux ? 3 : 2)) v
                     else fetch(kt + BK, areg, breg);
                 }
 
-                float4 fa[2][TM], fb[2][TN];
+                Frag fa[2][TM], fb[2][TN];
 #pragma unroll
                 for (int i = 0; i < TM; ++i) fa[0][i] = frag_a(buf, 0, i);
 #pragma unroll
@@ -908,20 +982,27 @@ __global__ __launch_bounds__(WM *WN * 64, (BK <= 16 && !Epi::kRowAux ? 3 : 2)) v
 #pragma unroll
                         for (int j = 0; j < TN; ++j) fb[nxt][j] = frag_b(buf, g + 1, j);
                     }
+                    if constexpr (sizeof(CT) == 4) {   // fp32: the four k-pairs in turn, round-robin over the output tiles
 #pragma unroll
-                    for (int q = 0; q < 4; ++q)
+                        for (int q = 0; q < 4; ++q)
+#pragma unroll
+                            for (int i = 0; i < TM; ++i)
+#pragma unroll
+                                for (int j = 0; j < TN; ++j) {
+                                    const float av = q == 0 ? fa[cur][i].x : q == 1 ? fa[cur][i].y : q == 2 ? fa[cur][i].z : fa[cur][i].w;
+                                    const float bv = q == 0 ? fb[cur][j].x : q == 1 ? fb[cur][j].y : q == 2 ? fb[cur][j].z : fb[cur][j].w;
+                                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(av, bv, acc[i][j], 0, 0, 0);
+                                }
+                    } else {
 #pragma unroll
                         for (int i = 0; i < TM; ++i)
 #pragma unroll
-                            for (int j = 0; j < TN; ++j) {
-                                const float av = q == 0 ? fa[cur][i].x : q == 1 ? fa[cur][i].y : q == 2 ? fa[cur][i].z : fa[cur][i].w;
-                                const float bv = q == 0 ? fb[cur][j].x : q == 1 ? fb[cur][j].y : q == 2 ? fb[cur][j].z : fb[cur][j].w;
-                                acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(av, bv, acc[i][j], 0, 0, 0);
-                            }
+                            for (int j = 0; j < TN; ++j) Math::mma(fa[cur][i], fb[cur][j], acc[i][j]);
+                    }
                 }
                 if (kColSum && t.m0 == 0 && tid < BN) {
 #pragma unroll
-                    for (int k = 0; k < BK; ++k) colsum += Bs[buf][k * B_LD + tid];
+                    for (int k = 0; k < BK; ++k) colsum += Math::value(&Bs[buf][k * B_LD + tid]);
                 }
                 if (more) stage(buf ^ 1, areg, breg);  // the other buffer was last read before the previous barrier
                 __syncthreads();
@@ -935,8 +1016,8 @@ __global__ __launch_bounds__(WM *WN * 64, (BK <= 16 && !Epi::kRowAux ? 3 : 2)) v
         // global memory once, here, before any store is in flight.  Fetched into registers directly they
         // would make the compiler guard every store below with a wait on the memory counter, which
         // also waits for the earlier stores and serialises the whole write-out.
-        if (Epi::kColAux && tid < BN) As[0][tid] = epi.col_aux(t.n0 + tid < N ? t.n0 + tid : N - 1);
-        if (Epi::kRowAux && tid < BM) Bs[0][tid] = epi.row_aux(t.m0 + tid < M ? t.m0 + tid : M - 1);
+        if (Epi::kColAux && tid < BN) a_aux[tid] = epi.col_aux(t.n0 + tid < N ? t.n0 + tid : N - 1);
+        if (Epi::kRowAux && tid < BM) b_aux[tid] = epi.row_aux(t.m0 + tid < M ? t.m0 + tid : M - 1);
         if (Epi::kColAux || Epi::kRowAux) __syncthreads();
 
         // The first slab of this block's next tile is fetched now, so that its latency passes while the
@@ -954,7 +1035,7 @@ __global__ __launch_bounds__(WM *WN * 64, (BK <= 16 && !Epi::kRowAux ? 3 : 2)) v
         // MFMA 32x32 result layout: register r of lane l holds row 8*(r/4) + 4*(l/32) + r%4, column l%32.
         float caux[TN];
 #pragma unroll
-        for (int j = 0; j < TN; ++j) caux[j] = Epi::kColAux ? As[0][wn0 + j * 32 + l31] : 0.0f;
+        for (int j = 0; j < TN; ++j) caux[j] = Epi::kColAux ? a_aux[wn0 + j * 32 + l31] : 0.0f;
         auto write_out = [&](auto inside_tag) {
             constexpr bool kInside = decltype(inside_tag)::value;   // the whole tile lies inside the result
 #pragma unroll
@@ -962,7 +1043,7 @@ __global__ __launch_bounds__(WM *WN * 64, (BK <= 16 && !Epi::kRowAux ? 3 : 2)) v
                 float raux[16];
 #pragma unroll
                 for (int r = 0; r < 16; ++r)
-                    raux[r] = Epi::kRowAux ? Bs[0][wm0 + i * 32 + 8 * (r / 4) + 4 * hi + (r % 4)] : 0.0f;
+                    raux[r] = Epi::kRowAux ? b_aux[wm0 + i * 32 + 8 * (r / 4) + 4 * hi + (r % 4)] : 0.0f;
 #pragma unroll
                 for (int j = 0; j < TN; ++j) {
                     const int col = done.n0 + wn0 + j * 32 + l31;
@@ -1090,7 +1171,7 @@ __global__ __launch_bounds__(256) void reduce_splits_halves_kernel(const float *
 template <typename T>
 static bool vec4_ok(const T *p, int64_t ld) { return aligned(p, 4 * sizeof(T)) && ld % 4 == 0; }
 
-template <int BM, int BN, int BK, int WM, int WN, bool kColSum, class AL, class BL, class Epi>
+template <int BM, int BN, int BK, int WM, int WN, bool kColSum, typename CT = float, class AL, class BL, class Epi>
 static void launch_gemm(const char *name, const AL &a, const BL &b, const Epi &e, int64_t M, int N, int64_t K,
                         int64_t k_per_split, int n_splits, float *colsum_partial, hipStream_t s)
 {
@@ -1100,12 +1181,12 @@ static void launch_gemm(const char *name, const AL &a, const BL &b, const Epi &e
     const int64_t total = tiles * n_splits;
     // resident blocks per compute unit follow from the kernel's LDS footprint (160 KB per unit) and its
     // register budget (launch bounds); 256 units in 8 dies
-    constexpr int kLdsBytes = 2 * 4 * ((AL::kContigK ? BM * (BK + kPad) : BK * (BM + kPad)) + (BL::kContigK ? BN * (BK + kPad) : BK * (BN + kPad)));
-    constexpr int kPerCu = (BK <= 16 && !Epi::kRowAux && kLdsBytes <= 53 * 1024) ? 3 : 2;
+    constexpr int kLdsBytes = 2 * int(sizeof(CT)) * ((AL::kContigK ? BM * (BK + kPad) : BK * (BM + kPad)) + (BL::kContigK ? BN * (BK + kPad) : BK * (BN + kPad)));
+    constexpr int kPerCu = (BK * sizeof(CT) <= 64 && !Epi::kRowAux && kLdsBytes <= 53 * 1024) ? 3 : 2;
     int64_t blocks_per_die = ceil_div(total, kXcds);
     if (blocks_per_die > 32 * kPerCu) blocks_per_die = 32 * kPerCu;
     TMA_TIMED(name, s);
-    hipLaunchKernelGGL((gemm_f32_kernel<BM, BN, BK, WM, WN, kColSum, AL, BL, Epi>), dim3(unsigned(blocks_per_die * kXcds)),
+    hipLaunchKernelGGL((gemm_f32_kernel<CT, BM, BN, BK, WM, WN, kColSum, AL, BL, Epi>), dim3(unsigned(blocks_per_die * kXcds)),
                        dim3(WM * WN * 64), 0, s, a, b, e, M, N, K, k_per_split, n_tiles, tiles, total, colsum_partial);
 }
 
@@ -1128,10 +1209,10 @@ static void fwd_dispatch(int64_t n, const T *H, int64_t ldh, const T *M, int F_i
     const int64_t K = 2 * int64_t(F_in);
     const int64_t kps = int64_t(round_up(size_t(K), 32));
     if (F_out <= 64)
-        launch_gemm<128, 64, 32, 4, 1, false>(kname<T>("gemm_fwd_128x64", "gemm_fwd_128x64_generic", "gemm_fwd_128x64_bf16", "gemm_fwd_128x64_bf16_generic", VA),
+        launch_gemm<128, 64, 32, 4, 1, false, T>(kname<T>("gemm_fwd_128x64", "gemm_fwd_128x64_generic", "gemm_fwd_128x64_bf16", "gemm_fwd_128x64_bf16_generic", VA),
                                               a, b, e, n, F_out, K, kps, 1, nullptr, s);
     else
-        launch_gemm<128, 128, 16, 2, 2, false>(kname<T>("gemm_fwd_128x128", "gemm_fwd_128x128_generic", "gemm_fwd_128x128_bf16", "gemm_fwd_128x128_bf16_generic", VA),
+        launch_gemm<128, 128, (sizeof(T) == 2 ? 32 : 16), 2, 2, false, T>(kname<T>("gemm_fwd_128x128", "gemm_fwd_128x128_generic", "gemm_fwd_128x128_bf16", "gemm_fwd_128x128_bf16_generic", VA),
                                                a, b, e, n, F_out, K, kps, 1, nullptr, s);
 }
 
@@ -1177,10 +1258,10 @@ static void bwd_data_dispatch(int64_t n, const T *g, const T *h, int64_t ld_next
                                 "gemm_bwd_data_128x128_bf16_generic", VA);
     if (K <= 48) {  // short reduction: 16-wide slabs waste less of the last one
         const int64_t kps = int64_t(round_up(size_t(K), 16));
-        launch_gemm<128, 128, 16, 2, 2, false>(name, a, b, e, n, N, K, kps, 1, nullptr, s);
+        launch_gemm<128, 128, 16, 2, 2, false, T>(name, a, b, e, n, N, K, kps, 1, nullptr, s);
     } else {
         const int64_t kps = int64_t(round_up(size_t(K), 32));
-        launch_gemm<128, 128, 32, 2, 2, false>(name, a, b, e, n, N, K, kps, 1, nullptr, s);
+        launch_gemm<128, 128, 32, 2, 2, false, T>(name, a, b, e, n, N, K, kps, 1, nullptr, s);
     }
 }
 
@@ -1261,10 +1342,10 @@ static void bwd_weight_dispatch(int64_t n, const T *H, int64_t ldh, const T *M, 
     MaskedGrad<false, T, VB, kRelu> b{g, h, F_out, ld_next, n};
     const int64_t Mtot = 2 * int64_t(F_in);
     if (F_out <= 64)
-        launch_gemm<128, 64, 32, 4, 1, true>(kname<T>("gemm_bwd_weight_128x64", "gemm_bwd_weight_128x64_generic", "gemm_bwd_weight_128x64_bf16", "gemm_bwd_weight_128x64_bf16_generic", V),
+        launch_gemm<128, 64, 32, 4, 1, true, T>(kname<T>("gemm_bwd_weight_128x64", "gemm_bwd_weight_128x64_generic", "gemm_bwd_weight_128x64_bf16", "gemm_bwd_weight_128x64_bf16_generic", V),
                                              a, b, e, Mtot, F_out, n, w.k_per_split, w.n_splits, colsum, s);
     else
-        launch_gemm<128, 128, 16, 2, 2, true>(kname<T>("gemm_bwd_weight_128x128", "gemm_bwd_weight_128x128_generic", "gemm_bwd_weight_128x128_bf16", "gemm_bwd_weight_128x128_bf16_generic", V),
+        launch_gemm<128, 128, (sizeof(T) == 2 ? 32 : 16), 2, 2, true, T>(kname<T>("gemm_bwd_weight_128x128", "gemm_bwd_weight_128x128_generic", "gemm_bwd_weight_128x128_bf16", "gemm_bwd_weight_128x128_bf16_generic", V),
                                               a, b, e, Mtot, F_out, n, w.k_per_split, w.n_splits, colsum, s);
 }
 
@@ -1328,13 +1409,13 @@ int launch_sage_gemm_bwd_weight(int64_t n, const void *H, int64_t ldh, const voi
 // ---- transform-before-aggregate form -----------------------------------------
 static int pad_cols(int32_t F_out, int32_t dtype) { return int(round_up(size_t(F_out), dtype == TMA_BF16 ? 8 : 4)); }
 
-template <int BK, bool kColSum, class AL, class BL, class Epi>
+template <typename CT, int BK, bool kColSum, class AL, class BL, class Epi>
 static void launch_by_width(const char *name, const AL &a, const BL &b, const Epi &e, int64_t M, int N, int64_t K,
                             int64_t kps, int n_splits, float *colsum, hipStream_t s)
 {
-    if (N <= 64) launch_gemm<128, 64, BK, 4, 1, kColSum>(name, a, b, e, M, N, K, kps, n_splits, colsum, s);
-    else if (N <= 96) launch_gemm<128, 96, BK, 4, 1, kColSum>(name, a, b, e, M, N, K, kps, n_splits, colsum, s);
-    else launch_gemm<128, 128, BK, 2, 2, kColSum>(name, a, b, e, M, N, K, kps, n_splits, colsum, s);
+    if (N <= 64) launch_gemm<128, 64, BK, 4, 1, kColSum, CT>(name, a, b, e, M, N, K, kps, n_splits, colsum, s);
+    else if (N <= 96) launch_gemm<128, 96, BK, 4, 1, kColSum, CT>(name, a, b, e, M, N, K, kps, n_splits, colsum, s);
+    else launch_gemm<128, 128, BK, 2, 2, kColSum, CT>(name, a, b, e, M, N, K, kps, n_splits, colsum, s);
 }
 
 template <typename T>
@@ -1350,7 +1431,7 @@ static int tf_fwd_typed(int64_t n, const T *H, int64_t ldh, int32_t F_in, const 
     do {                                                                                          \
         CatRows<T, VA_> a{H, ldh, H, F_in, n};                                                    \
         SideWeights<VB_> b{W_self, W_neigh, F_in, F_out, Fp};                                     \
-        launch_by_width<32, false>(name, a, b, e, n, 2 * Fp, K, kps, 1, nullptr, s);              \
+        launch_by_width<T, 32, false>(name, a, b, e, n, 2 * Fp, K, kps, 1, nullptr, s);              \
     } while (0)
     if (va && vb) TMA_TF_FWD(true, true);
     else if (va) TMA_TF_FWD(true, false);
@@ -1412,7 +1493,7 @@ static int tf_bwd_weight_typed(int64_t n, const T *H, int64_t ldh, const T *g, c
     do {                                                                                                              \
         CatRowsT<T, VA_> a{H, ldh, H, F_in, n};                                                                       \
         SideGrad<false, T, VB_, R_> b{g, h, dYn, F_out, Fp, ld_next, ldy, n};                                         \
-        launch_by_width<32, true>(name, a, b, e, int64_t(F_in), 2 * Fp, n, w.k_per_split, w.n_splits, colsum, s);     \
+        launch_by_width<T, 32, true>(name, a, b, e, int64_t(F_in), 2 * Fp, n, w.k_per_split, w.n_splits, colsum, s);     \
     } while (0)
 #define TMA_TF_BW2(VA_, VB_)         \
     do {                             \
@@ -1478,7 +1559,7 @@ static int tf_bwd_data_typed(int64_t n, const T *g, const T *h, int64_t ld_next,
     do {                                                                                               \
         SideGrad<true, T, VA_, R_> a{g, h, dYn, F_out, Fp, ld_next, ldy, n};                           \
         SideWeightsT<VB_> b{W_self, W_neigh, F_in, F_out, Fp};                                         \
-        launch_gemm<128, 128, 32, 2, 2, false>(name, a, b, e, n, F_in, K, kps, 1, nullptr, s);         \
+        launch_gemm<128, 128, 32, 2, 2, false, T>(name, a, b, e, n, F_in, K, kps, 1, nullptr, s);         \
     } while (0)
 #define TMA_TF_BD2(VA_, VB_)                 \
     do {                                     \
