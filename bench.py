@@ -32,11 +32,11 @@ WORKLOAD = dict(n_nodes=1_000_000, avg_degree=20, gamma=2.1, K=8, part=0, F=128,
 # (profiles/bench_configs1_hbm_traffic.txt): (FETCH_SIZE * 2.0 + WRITE_SIZE * 1.0) KiB, the factors being what the
 # same counters read for a plain 1 GiB device copy (FETCH_SIZE reports half the bytes read, WRITE_SIZE all written).
 MEASURED_TRAFFIC_BYTES = {
-    "gemm_bwd_weight_128x128": (211514 * 2.0 + 32639) * 1024,
-    "gemm_fwd_128x128": (67763 * 2.0 + 125237) * 1024,
-    "gemm_tf_fwd": (63469 * 2.0 + 47077) * 1024,
-    "gemm_tf_bwd_weight": (86228 * 2.0 + 23612) * 1024,
-    "gemm_tf_bwd_data": (24306 * 2.0 + 125237) * 1024,
+    "gemm_bwd_weight_128x128": (230097 * 2.0 + 34671) * 1024,
+    "gemm_fwd_128x128": (68527 * 2.0 + 125237) * 1024,
+    "gemm_tf_fwd": (63682 * 2.0 + 46984) * 1024,
+    "gemm_tf_bwd_weight": (87522 * 2.0 + 23612) * 1024,
+    "gemm_tf_bwd_data": (24594 * 2.0 + 125237) * 1024,
     "spmm_mean_f32_g32x1": (55743 * 2.0 + 62618) * 1024,
     "spmm_combine_f32_g12x1": (42987 * 2.0 + 24981) * 1024,
     "spmm_sum_f32_g12x1": (25502 * 2.0 + 24421) * 1024,
