@@ -27,6 +27,16 @@ struct FlagIn {  // 1 where the node belongs to partition p
     const int32_t *part;
     int32_t p;
     __device__ int32_t load(int64_t i) const { return part[i] == p ? 1 : 0; }
+    // eight consecutive items from a 32-byte aligned position: two 16-byte loads
+    __device__ bool load8(int64_t first, int32_t (&v)[8]) const
+    {
+        if ((reinterpret_cast<uintptr_t>(part) & 15) != 0) return false;
+        const int4 a = *reinterpret_cast<const int4 *>(part + first);
+        const int4 b = *reinterpret_cast<const int4 *>(part + first + 4);
+        v[0] = a.x == p; v[1] = a.y == p; v[2] = a.z == p; v[3] = a.w == p;
+        v[4] = b.x == p; v[5] = b.y == p; v[6] = b.z == p; v[7] = b.w == p;
+        return true;
+    }
 };
 struct FlagOut {  // local id = exclusive rank; inverse map, row bounds for the first `cap` local nodes; bitmap
     int32_t *g2l;
@@ -46,6 +56,26 @@ struct FlagOut {  // local id = exclusive rank; inverse map, row bounds for the 
             row_len[prefix] = int32_t(rowptr[i + 1] - b);
         }
     }
+    // all eight items of a thread at once: the id map goes out as two 16-byte stores
+    __device__ bool store8(int64_t first, int64_t prefix, const int32_t (&v)[8]) const
+    {
+        if ((reinterpret_cast<uintptr_t>(g2l) & 15) != 0) return false;
+        int32_t id[8];
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            id[j] = v[j] ? int32_t(prefix) : -1;
+            if (v[j] && prefix < cap) {
+                l2g[prefix] = int32_t(first + j);
+                const int64_t b = rowptr[first + j];
+                row_beg[prefix] = b;
+                row_len[prefix] = int32_t(rowptr[first + j + 1] - b);
+            }
+            prefix += v[j];
+        }
+        *reinterpret_cast<int4 *>(g2l + first) = make_int4(id[0], id[1], id[2], id[3]);
+        *reinterpret_cast<int4 *>(g2l + first + 4) = make_int4(id[4], id[5], id[6], id[7]);
+        return true;
+    }
     // the eight flags of one thread's consecutive items (first item = bit 0) are one byte of the bitmap
     __device__ void store_flags(int64_t first, uint32_t bits, int64_t n) const
     {
@@ -55,6 +85,15 @@ struct FlagOut {  // local id = exclusive rank; inverse map, row bounds for the 
 struct DegIn {
     const int32_t *deg;
     __device__ int32_t load(int64_t i) const { return deg[i]; }
+    __device__ bool load8(int64_t first, int32_t (&v)[8]) const
+    {
+        if ((reinterpret_cast<uintptr_t>(deg) & 15) != 0) return false;
+        const int4 a = *reinterpret_cast<const int4 *>(deg + first);
+        const int4 b = *reinterpret_cast<const int4 *>(deg + first + 4);
+        v[0] = a.x; v[1] = a.y; v[2] = a.z; v[3] = a.w;
+        v[4] = b.x; v[5] = b.y; v[6] = b.z; v[7] = b.w;
+        return true;
+    }
 };
 struct DegOut {  // rowptr_loc[i] = exclusive prefix, rowptr_loc[n] = total
     int32_t *rowptr_loc;
@@ -64,6 +103,19 @@ struct DegOut {  // rowptr_loc[i] = exclusive prefix, rowptr_loc[n] = total
         if (i == n - 1) rowptr_loc[n] = int32_t(prefix + v);
     }
     __device__ void store_flags(int64_t, uint32_t, int64_t) const {}
+    __device__ bool store8(int64_t first, int64_t prefix, const int32_t (&v)[8]) const
+    {
+        if ((reinterpret_cast<uintptr_t>(rowptr_loc) & 15) != 0) return false;
+        int32_t x[8];
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            x[j] = int32_t(prefix);
+            prefix += v[j];
+        }
+        *reinterpret_cast<int4 *>(rowptr_loc + first) = make_int4(x[0], x[1], x[2], x[3]);
+        *reinterpret_cast<int4 *>(rowptr_loc + first + 4) = make_int4(x[4], x[5], x[6], x[7]);
+        return true;
+    }
 };
 
 __device__ __forceinline__ int64_t effective_n(const int64_t *d_n, int64_t cap)
@@ -106,9 +158,15 @@ __global__ __launch_bounds__(kScanThreads) void scan_reduce_kernel(const int64_t
     const int64_t n = effective_n(d_n, cap);
     const int64_t base = int64_t(blockIdx.x) * kScanTile + int64_t(threadIdx.x) * kScanItems;
     int32_t c = 0;
+    int32_t v[kScanItems];
+    if (base + kScanItems <= n && in.load8(base, v)) {
 #pragma unroll
-    for (int j = 0; j < kScanItems; ++j)
-        if (base + j < n) c += in.load(base + j);
+        for (int j = 0; j < kScanItems; ++j) c += v[j];
+    } else {
+#pragma unroll
+        for (int j = 0; j < kScanItems; ++j)
+            if (base + j < n) c += in.load(base + j);
+    }
     int32_t total;
     block_exclusive_scan(c, total);
     if (threadIdx.x == 0) block_sums[blockIdx.x] = total;
@@ -162,15 +220,21 @@ __global__ __launch_bounds__(kScanThreads) void scan_apply_kernel(const int64_t 
     int32_t v[kScanItems];
     int32_t c = 0;
     uint32_t bits = 0;
+    const bool whole = base + kScanItems <= n;   // all eight items exist: 16-byte loads and stores where aligned
+    if (!(whole && in.load8(base, v))) {
+#pragma unroll
+        for (int j = 0; j < kScanItems; ++j) v[j] = (base + j < n) ? in.load(base + j) : 0;
+    }
 #pragma unroll
     for (int j = 0; j < kScanItems; ++j) {
-        v[j] = (base + j < n) ? in.load(base + j) : 0;
         c += v[j];
         bits |= (v[j] != 0 ? 1u : 0u) << j;
     }
     out.store_flags(base, bits, n);
     int32_t total;
     int64_t prefix = block_offsets[blockIdx.x] + block_exclusive_scan(c, total);
+    // the last item also closes the output (DegOut writes the total after it): left to the item-wise path
+    if (whole && base + kScanItems < n && out.store8(base, prefix, v)) return;
 #pragma unroll
     for (int j = 0; j < kScanItems; ++j) {
         if (base + j < n) out.store(base + j, prefix, v[j], n);
