@@ -150,6 +150,85 @@ def sage_layer_bwd(rowptr, colidx, H, M, Z, dHnext, W_self, W_neigh, act: int, n
     return dWs, dWn, db, dH
 
 
+# --------------------------------------------- GCN and MLP encoders (Sec. 4.1)
+def gcn_norm(rowptr) -> np.ndarray:
+    """s_v = (d_v + 1)^-1/2 over the local degrees."""
+    rowptr = _i32(rowptr)
+    n = rowptr.shape[0] - 1
+    s = np.empty(n)
+    lib().orc_gcn_norm(C.c_int64(n), _p(rowptr), _p(s))
+    return s
+
+
+def gcn_aggregate(rowptr, colidx, H, transpose: bool = False) -> np.ndarray:
+    """Ahat H (or Ahat^T H), Ahat = Dt^-1/2 (A + I) Dt^-1/2."""
+    rowptr, colidx, H = _i32(rowptr), _i32(colidx), _f64(H)
+    n, F = H.shape
+    M = np.empty_like(H)
+    fn = lib().orc_gcn_aggregate_T if transpose else lib().orc_gcn_aggregate
+    fn(C.c_int64(n), _p(rowptr), _p(colidx), _p(H), C.c_int64(F), _p(M))
+    return M
+
+
+def dense_fwd(X, W, bias, act: int):
+    """Returns (Z, Y): Z = X W + b (bias may be None), Y = act(Z)."""
+    X, W = _f64(X), _f64(W)
+    b = None if bias is None else _f64(bias)
+    n, F_in = X.shape
+    F_out = W.shape[1]
+    assert W.shape == (F_in, F_out) and (b is None or b.shape == (F_out,))
+    Z = np.empty((n, F_out))
+    Y = np.empty((n, F_out))
+    lib().orc_dense_fwd(C.c_int64(n), _p(X), C.c_int64(F_in), _p(W), _p(b), C.c_int64(F_out), C.c_int(act),
+                        _p(Z), _p(Y))
+    return Z, Y
+
+
+def dense_bwd(X, Z, dY, W, act: int, need_dbias=True, need_dX=True):
+    """Returns (dW, dbias or None, dX or None)."""
+    X, Z, dY, W = _f64(X), _f64(Z), _f64(dY), _f64(W)
+    n, F_in = X.shape
+    F_out = W.shape[1]
+    dW = np.empty((F_in, F_out))
+    db = np.empty(F_out) if need_dbias else None
+    dX = np.empty((n, F_in)) if need_dX else None
+    sZ = np.empty((n, F_out))
+    lib().orc_dense_bwd(C.c_int64(n), _p(X), _p(Z), _p(dY), _p(W), C.c_int64(F_in), C.c_int64(F_out), C.c_int(act),
+                        _p(dW), _p(db), _p(dX), _p(sZ))
+    return dW, db, dX
+
+
+def gcn_layer_fwd(rowptr, colidx, H, W, bias, act: int):
+    """Returns (M, Z, Hnext) of one GCN layer: M = Ahat H, Z = M W + b."""
+    rowptr, colidx = _i32(rowptr), _i32(colidx)
+    H, W, bias = _f64(H), _f64(W), _f64(bias)
+    n, F_in = H.shape
+    F_out = W.shape[1]
+    assert W.shape == (F_in, F_out) and bias.shape == (F_out,)
+    M = np.empty((n, F_in))
+    Z = np.empty((n, F_out))
+    Hn = np.empty((n, F_out))
+    lib().orc_gcn_layer_fwd(C.c_int64(n), _p(rowptr), _p(colidx), _p(H), C.c_int64(F_in), _p(W), _p(bias),
+                            C.c_int64(F_out), C.c_int(act), _p(M), _p(Z), _p(Hn))
+    return M, Z, Hn
+
+
+def gcn_layer_bwd(rowptr, colidx, M, Z, dHnext, W, act: int, need_dH=True):
+    """Returns (dW, dbias, dH or None)."""
+    rowptr, colidx = _i32(rowptr), _i32(colidx)
+    M, Z, dHnext, W = _f64(M), _f64(Z), _f64(dHnext), _f64(W)
+    n, F_in = M.shape
+    F_out = W.shape[1]
+    dW = np.empty((F_in, F_out))
+    db = np.empty(F_out)
+    dH = np.empty((n, F_in)) if need_dH else None
+    sM = np.empty((n, F_in))
+    sZ = np.empty((n, F_out))
+    lib().orc_gcn_layer_bwd(C.c_int64(n), _p(rowptr), _p(colidx), _p(M), _p(Z), _p(dHnext), _p(W),
+                            C.c_int64(F_in), C.c_int64(F_out), C.c_int(act), _p(dW), _p(db), _p(dH), _p(sM), _p(sZ))
+    return dW, db, dH
+
+
 # ------------------------------------------------------ normalisation + activation
 LN_EPS = 1e-5
 

@@ -9,33 +9,89 @@ from __future__ import annotations
 
 import numpy as np
 
-from . import (ACT_NONE, ACT_RELU, adam_step, average, layernorm_prelu_bwd, layernorm_prelu_fwd,
-               sage_layer_bwd, sage_layer_fwd, sgd_step, softmax_ce)
+from . import (ACT_NONE, ACT_RELU, adam_step, average, dense_bwd, dense_fwd, gcn_layer_bwd, gcn_layer_fwd,
+               layernorm_prelu_bwd, layernorm_prelu_fwd, sage_layer_bwd, sage_layer_fwd, sgd_step, softmax_ce)
 
-ACT_LN_PRELU = "ln_prelu"   # a layer whose parameter tuple is (W_self, W_neigh, b, gamma, beta, slope)
+ACT_LN_PRELU = "ln_prelu"   # a layer whose parameter tuple ends with (gamma, beta, slope)
 
 
-def forward(rowptr, colidx, X, params):
-    """Identity on the last layer; between layers ReLU, or, for a layer that carries (gamma, beta, slope),
-    layer normalisation followed by PReLU (the paper's encoder variant, Sec. 4.1).  Returns (logits, saved)."""
+def _layer_fwd(encoder, rowptr, colidx, H, lin, act):
+    """(M, Z, Hnext) of one layer of the chosen encoder (Sec. 4.1): "sage" (W_self, W_neigh, b),
+    "gcn" (W, b) or the graph-agnostic "mlp" (W, b), whose M is its input."""
+    if encoder == "sage":
+        return sage_layer_fwd(rowptr, colidx, H, lin[0], lin[1], lin[2], act)
+    if encoder == "gcn":
+        return gcn_layer_fwd(rowptr, colidx, H, lin[0], lin[1], act)
+    if encoder == "mlp":
+        Z, Hn = dense_fwd(H, lin[0], lin[1], act)
+        return H, Z, Hn
+    raise ValueError(encoder)
+
+
+def _layer_bwd(encoder, rowptr, colidx, H, M, Z, d, lin, act, need_dH):
+    """(gradients of the linear parameters, dH)."""
+    if encoder == "sage":
+        dWs, dWn, db, dH = sage_layer_bwd(rowptr, colidx, H, M, Z, d, lin[0], lin[1], act, need_dH=need_dH)
+        return (dWs, dWn, db), dH
+    if encoder == "gcn":
+        dW, db, dH = gcn_layer_bwd(rowptr, colidx, M, Z, d, lin[0], act, need_dH=need_dH)
+        return (dW, db), dH
+    dW, db, dH = dense_bwd(H, Z, d, lin[0], act, need_dX=need_dH)
+    return (dW, db), dH
+
+
+def n_linear(encoder):
+    return 3 if encoder == "sage" else 2
+
+
+def forward(rowptr, colidx, X, params, encoder="sage"):
+    """Identity on the last layer; between layers ReLU, or, for a layer that carries (gamma, beta, slope)
+    after its linear parameters, layer normalisation followed by PReLU (the paper's encoder variant,
+    Sec. 4.1).  Returns (logits, saved)."""
     H = np.asarray(X, dtype=np.float64)
     saved = []
     L = len(params)
+    nl = n_linear(encoder)
     for l, layer in enumerate(params):
-        Ws, Wn, b = layer[:3]
-        if len(layer) == 6:
-            M, Z, _ = sage_layer_fwd(rowptr, colidx, H, Ws, Wn, b, ACT_NONE)
-            Hn = layernorm_prelu_fwd(Z, layer[3], layer[4], float(np.asarray(layer[5]).ravel()[0]))
+        lin = layer[:nl]
+        if len(layer) == nl + 3:
+            M, Z, _ = _layer_fwd(encoder, rowptr, colidx, H, lin, ACT_NONE)
+            Hn = layernorm_prelu_fwd(Z, layer[nl], layer[nl + 1], float(np.asarray(layer[nl + 2]).ravel()[0]))
             saved.append((H, M, Z, ACT_LN_PRELU))
         else:
             act = ACT_RELU if l < L - 1 else ACT_NONE
-            M, Z, Hn = sage_layer_fwd(rowptr, colidx, H, Ws, Wn, b, act)
+            M, Z, Hn = _layer_fwd(encoder, rowptr, colidx, H, lin, act)
             saved.append((H, M, Z, act))
         H = Hn
     return H, saved
 
 
-def loss_and_grads(rowptr, colidx, X, y, params, relu_open=None):
+def backward(rowptr, colidx, params, saved, d, relu_open=None, encoder="sage", need_dX=False):
+    """Chain rule from d = d(loss)/d(output of the last layer) down to the parameters (and, with need_dX,
+    to the input features).  Returns (grads, dX or None)."""
+    nl = n_linear(encoder)
+    grads = [None] * len(params)
+    for l in range(len(params) - 1, -1, -1):
+        H, M, Z, act = saved[l]
+        lin = params[l][:nl]
+        forced = relu_open[l] if relu_open is not None else None
+        need_dH = l > 0 or need_dX
+        if act == ACT_LN_PRELU:
+            gamma, beta = params[l][nl], params[l][nl + 1]
+            slope = float(np.asarray(params[l][nl + 2]).ravel()[0])
+            dZ, dg, dbeta, ds = layernorm_prelu_bwd(Z, d, gamma, beta, slope, open_mask=forced)
+            glin, dH = _layer_bwd(encoder, rowptr, colidx, H, M, Z, dZ, lin, ACT_NONE, need_dH)
+            grads[l] = glin + (dg, dbeta, np.array([ds]))
+        else:
+            if forced is not None and act == ACT_RELU:
+                Z = np.where(np.asarray(forced), 1.0, -1.0)   # only the sign of Z is used by the backward pass
+            glin, dH = _layer_bwd(encoder, rowptr, colidx, H, M, Z, d, lin, act, need_dH)
+            grads[l] = glin
+        d = dH
+    return grads, d
+
+
+def loss_and_grads(rowptr, colidx, X, y, params, relu_open=None, encoder="sage"):
     """Mean softmax-CE over all local nodes and d(loss)/d(params).
 
     ``relu_open[l]`` (optional, boolean [n, F_{l+1}]) fixes where layer l's ReLU (or PReLU) is open instead
@@ -44,39 +100,24 @@ def loss_and_grads(rowptr, colidx, X, y, params, relu_open=None):
     fp64, which changes one whole term of a weight-gradient sum.  A parity test therefore hands the
     decision taken in the kernel's precision to both sides; the arithmetic is unchanged.
     """
-    logits, saved = forward(rowptr, colidx, X, params)
+    logits, saved = forward(rowptr, colidx, X, params, encoder)
     loss, d = softmax_ce(logits, y)
-    grads = [None] * len(params)
-    for l in range(len(params) - 1, -1, -1):
-        H, M, Z, act = saved[l]
-        Ws, Wn = params[l][0], params[l][1]
-        forced = relu_open[l] if relu_open is not None else None
-        if act == ACT_LN_PRELU:
-            gamma, beta, slope = params[l][3], params[l][4], float(np.asarray(params[l][5]).ravel()[0])
-            dZ, dg, dbeta, ds = layernorm_prelu_bwd(Z, d, gamma, beta, slope, open_mask=forced)
-            dWs, dWn, db, dH = sage_layer_bwd(rowptr, colidx, H, M, Z, dZ, Ws, Wn, ACT_NONE, need_dH=l > 0)
-            grads[l] = (dWs, dWn, db, dg, dbeta, np.array([ds]))
-        else:
-            if forced is not None and act == ACT_RELU:
-                Z = np.where(np.asarray(forced), 1.0, -1.0)   # only the sign of Z is used by the backward pass
-            dWs, dWn, db, dH = sage_layer_bwd(rowptr, colidx, H, M, Z, d, Ws, Wn, act, need_dH=l > 0)
-            grads[l] = (dWs, dWn, db)
-        d = dH
+    grads, _ = backward(rowptr, colidx, params, saved, d, relu_open, encoder)
     return loss, grads, logits, saved
 
 
-def train_step(rowptr, colidx, X, y, params, lr, relu_open=None):
+def train_step(rowptr, colidx, X, y, params, lr, relu_open=None, encoder="sage"):
     """One Alg. 2 iteration on the full local subgraph; returns (loss, new params)."""
-    loss, grads, _, _ = loss_and_grads(rowptr, colidx, X, y, params, relu_open)
+    loss, grads, _, _ = loss_and_grads(rowptr, colidx, X, y, params, relu_open, encoder)
     new = [tuple(sgd_step(w, g, lr).reshape(np.shape(w)) for w, g in zip(pl, gl))
            for pl, gl in zip(params, grads)]
     return loss, new
 
 
-def train_step_adam(rowptr, colidx, X, y, params, lr, state, t, relu_open=None):
+def train_step_adam(rowptr, colidx, X, y, params, lr, state, t, relu_open=None, encoder="sage"):
     """One Alg. 2 iteration with Adam.  state = (m, v) flat vectors (None before the first step), t = 1, 2, ...
     Returns (loss, new params, new state); the state belongs to the trainer and is never averaged."""
-    loss, grads, _, _ = loss_and_grads(rowptr, colidx, X, y, params, relu_open)
+    loss, grads, _, _ = loss_and_grads(rowptr, colidx, X, y, params, relu_open, encoder)
     w, g = flatten(params), flatten(grads)
     m, v = (np.zeros_like(w), np.zeros_like(w)) if state is None else state
     w, m, v = adam_step(w, g, m, v, lr, t)

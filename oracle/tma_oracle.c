@@ -23,6 +23,10 @@
  * [(1-h), h], central finite differences and the adjoint identity.
  * The composed multi-layer training step has no value printed in the paper:
  * it is pinned only through its parts plus finite differences.
+ * GCN and dense layers (tests/test_oracle_gcn.py): the sqrt-degree eigenvector
+ * of the normalised adjacency, its forms on regular, complete and empty graphs,
+ * a sparse library's matrix algebra, a library's reverse-mode derivative, the
+ * adjoint identity and finite differences.
  */
 #include <math.h>
 #include <stddef.h>
@@ -395,4 +399,115 @@ void orc_average(int32_t M, int64_t P, uint64_t active, double *W, double *W_glo
         for (int32_t i = 0; i < M; ++i)
             if ((active >> i) & 1u) W[(int64_t)i * P + j] = s;
     }
+}
+
+/* ------------------------------------------------------------------------
+ * Other encoders of Sec. 4.1 (paragraph on GNN encoders): the graph
+ * convolution of Kipf & Welling (2017), which the paper cites for its GCN
+ * encoder, and the graph-agnostic MLP encoder.
+ *
+ * GCN layer on the local (node-induced) subgraph:
+ *     Ahat = Dt^-1/2 (A + I) Dt^-1/2,   Dt = diag(d_v + 1)   (d_v = local degree)
+ *     M = Ahat H,   Z = M W + 1 b^T,   H' = act(Z)
+ * Entry (v,u) of Ahat is s_v s_u for every CSR entry (v,u) plus s_v^2 on the
+ * diagonal, with s_v = (d_v + 1)^-1/2.  The degree on both sides is the row's
+ * own entry count; the local graphs here store both directions of every edge,
+ * so this is the symmetric normalisation of the cited paper.
+ * ---------------------------------------------------------------------- */
+void orc_gcn_norm(int64_t n, const int32_t *rowptr, double *s)
+{
+    for (int64_t v = 0; v < n; ++v) s[v] = 1.0 / sqrt((double)(rowptr[v + 1] - rowptr[v]) + 1.0);
+}
+
+void orc_gcn_aggregate(int64_t n, const int32_t *rowptr, const int32_t *colidx,
+                       const double *H, int64_t F, double *M)
+{
+    for (int64_t v = 0; v < n; ++v) {
+        const double sv = 1.0 / sqrt((double)(rowptr[v + 1] - rowptr[v]) + 1.0);
+        double *m = M + v * F;
+        for (int64_t f = 0; f < F; ++f) m[f] = sv * sv * H[v * F + f];
+        for (int32_t e = rowptr[v]; e < rowptr[v + 1]; ++e) {
+            const int64_t u = colidx[e];
+            const double su = 1.0 / sqrt((double)(rowptr[u + 1] - rowptr[u]) + 1.0);
+            for (int64_t f = 0; f < F; ++f) m[f] += sv * su * H[u * F + f];
+        }
+    }
+}
+
+/* out = Ahat^T G as a scatter over the same CSR (no symmetry assumed). */
+void orc_gcn_aggregate_T(int64_t n, const int32_t *rowptr, const int32_t *colidx,
+                         const double *G, int64_t F, double *out)
+{
+    memset(out, 0, (size_t)(n * F) * sizeof(double));
+    for (int64_t v = 0; v < n; ++v) {
+        const double sv = 1.0 / sqrt((double)(rowptr[v + 1] - rowptr[v]) + 1.0);
+        for (int64_t f = 0; f < F; ++f) out[v * F + f] += sv * sv * G[v * F + f];
+        for (int32_t e = rowptr[v]; e < rowptr[v + 1]; ++e) {
+            const int64_t u = colidx[e];
+            const double su = 1.0 / sqrt((double)(rowptr[u + 1] - rowptr[u]) + 1.0);
+            for (int64_t f = 0; f < F; ++f) out[u * F + f] += sv * su * G[v * F + f];
+        }
+    }
+}
+
+/* Z = X W + 1 b^T (b may be NULL), Y = act(Z): the MLP encoder's layer, the
+ * transform of the GCN layer (X = Ahat H) and, without bias, a layer of the
+ * link decoder (App., formulation of the MLP decoder). */
+void orc_dense_fwd(int64_t n, const double *X, int64_t F_in, const double *W, const double *bias,
+                   int64_t F_out, int act, double *Z, double *Y)
+{
+    for (int64_t v = 0; v < n; ++v) {
+        double *z = Z + v * F_out;
+        for (int64_t o = 0; o < F_out; ++o) z[o] = bias ? bias[o] : 0.0;
+        for (int64_t k = 0; k < F_in; ++k) {
+            const double x = X[v * F_in + k];
+            for (int64_t o = 0; o < F_out; ++o) z[o] += x * W[k * F_out + o];
+        }
+        for (int64_t o = 0; o < F_out; ++o)
+            Y[v * F_out + o] = (act == 1) ? (z[o] > 0.0 ? z[o] : 0.0) : z[o];
+    }
+}
+
+/* dZ = dY (.) act'(Z);  dW = X^T dZ;  db = column sums of dZ (skipped when NULL);
+ * dX = dZ W^T (skipped when NULL).  scratch_dZ: n*F_out doubles. */
+void orc_dense_bwd(int64_t n, const double *X, const double *Z, const double *dY, const double *W,
+                   int64_t F_in, int64_t F_out, int act, double *dW, double *dbias, double *dX,
+                   double *scratch_dZ)
+{
+    double *dZ = scratch_dZ;
+    for (int64_t i = 0; i < n * F_out; ++i)
+        dZ[i] = (act == 1) ? (Z[i] > 0.0 ? dY[i] : 0.0) : dY[i];
+    for (int64_t i = 0; i < F_in * F_out; ++i) dW[i] = 0.0;
+    if (dbias) for (int64_t o = 0; o < F_out; ++o) dbias[o] = 0.0;
+    for (int64_t v = 0; v < n; ++v) {
+        for (int64_t k = 0; k < F_in; ++k)
+            for (int64_t o = 0; o < F_out; ++o) dW[k * F_out + o] += X[v * F_in + k] * dZ[v * F_out + o];
+        if (dbias) for (int64_t o = 0; o < F_out; ++o) dbias[o] += dZ[v * F_out + o];
+    }
+    if (!dX) return;
+    for (int64_t v = 0; v < n; ++v)
+        for (int64_t k = 0; k < F_in; ++k) {
+            double s = 0.0;
+            for (int64_t o = 0; o < F_out; ++o) s += dZ[v * F_out + o] * W[k * F_out + o];
+            dX[v * F_in + k] = s;
+        }
+}
+
+void orc_gcn_layer_fwd(int64_t n, const int32_t *rowptr, const int32_t *colidx,
+                       const double *H, int64_t F_in, const double *W, const double *bias,
+                       int64_t F_out, int act, double *M, double *Z, double *Hnext)
+{
+    orc_gcn_aggregate(n, rowptr, colidx, H, F_in, M);
+    orc_dense_fwd(n, M, F_in, W, bias, F_out, act, Z, Hnext);
+}
+
+/* dW = M^T dZ, db = 1^T dZ, dH = Ahat^T (dZ W^T)   (dH skipped when NULL).
+ * scratch_dM: n*F_in doubles, scratch_dZ: n*F_out doubles. */
+void orc_gcn_layer_bwd(int64_t n, const int32_t *rowptr, const int32_t *colidx,
+                       const double *M, const double *Z, const double *dHnext, const double *W,
+                       int64_t F_in, int64_t F_out, int act, double *dW, double *dbias, double *dH,
+                       double *scratch_dM, double *scratch_dZ)
+{
+    orc_dense_bwd(n, M, Z, dHnext, W, F_in, F_out, act, dW, dbias, dH ? scratch_dM : NULL, scratch_dZ);
+    if (dH) orc_gcn_aggregate_T(n, rowptr, colidx, scratch_dM, F_in, dH);
 }
