@@ -227,6 +227,69 @@ int tma_layernorm_prelu_bwd(int64_t n, int32_t F, const void *Z, int64_t ldz,
                             void *ws, size_t ws_bytes, tma_stream_t stream);
 
 /* ------------------------------------------------------------------------
+ * The paper's other encoders (Sec. 4.1, paragraph on GNN encoders).
+ *
+ * Dense layer -- a layer of the graph-agnostic MLP encoder and, without bias,
+ * of the link decoder (App., formulation of the MLP decoder):
+ *     Y = act(X W + 1 b^T)
+ *     dZ = dY (.) act'(Y);  dW = X^T dZ;  dbias = 1^T dZ;  dX = dZ W^T
+ *   X [n, F_in] dtype, ldx;  W [F_in, F_out] fp32 row-major;  bias [F_out] fp32
+ *   or NULL;  Y, dY [n, F_out] dtype, ldy;  act as for the SAGE layer (Y is
+ *   read by the backward only with TMA_ACT_RELU).
+ *   dW [F_in, F_out] fp32 OVERWRITTEN; dbias [F_out] fp32 or NULL; dX_out
+ *   [n, F_in] dtype with leading dimension ld_dx, or NULL to skip it.
+ * All pointers device memory; n = 0 is a no-op forward and writes zero
+ * gradients backward.  Workspace of the backward:
+ * tma_dense_bwd_workspace_bytes(n, F_in, F_out), 256-byte aligned.
+ * Deterministic (fixed reduction order).
+ * ---------------------------------------------------------------------- */
+int tma_dense_fwd(int64_t n, const void *X, int64_t ldx, int32_t F_in,
+                  const float *W, const float *bias, int32_t F_out, int32_t act, int32_t dtype,
+                  void *Y_out, int64_t ldy, tma_stream_t stream);
+
+size_t tma_dense_bwd_workspace_bytes(int64_t n, int32_t F_in, int32_t F_out);
+
+int tma_dense_bwd(int64_t n, const void *X, int64_t ldx, const void *Y, const void *dY, int64_t ldy,
+                  const float *W, int32_t F_in, int32_t F_out, int32_t act, int32_t dtype,
+                  float *dW, float *dbias, void *dX_out, int64_t ld_dx,
+                  void *ws, size_t ws_bytes, tma_stream_t stream);
+
+/* ------------------------------------------------------------------------
+ * GCN layer (the graph convolution of Kipf & Welling, which the paper cites
+ * for its GCN encoder) on the local subgraph:
+ *     Ahat = S (A + I) S,  S = diag(s),  s_v = (d_v + 1)^-1/2, d_v = local degree
+ *     Hnext = act(Ahat H W + 1 b^T)
+ *     dZ = dHnext (.) act'(Hnext);  dW = (Ahat H)^T dZ;  dbias = 1^T dZ;
+ *     dH = Ahat^T dZ W^T
+ * tma_gcn_norm writes s [n] fp32 from the local rowptr (once per extraction).
+ *   rowptr/colidx, H, ldh, act, dtype, Hnext, dHnext, ld_next: as for the SAGE
+ *   layer;  W [F_in, F_out], bias [F_out] fp32.  The backward takes the CSR
+ *   of the TRANSPOSED local graph (the same arrays for a symmetric graph).
+ *   dW [F_in, F_out], dbias [F_out] fp32 OVERWRITTEN;  dH_out [n, F_in] dtype
+ *   with leading dimension ldh, or NULL.
+ * The layer multiplies first and aggregates F_out-wide rows (any widths).
+ * Workspaces (256-byte aligned): tma_gcn_layer_fwd_workspace_bytes(n, F_out,
+ * dtype) and tma_gcn_layer_bwd_workspace_bytes(n, F_in, F_out, dtype); the
+ * backward needs nothing the forward left there.  Deterministic.
+ * ---------------------------------------------------------------------- */
+int tma_gcn_norm(int64_t n, const int32_t *rowptr, float *s_out, tma_stream_t stream);
+
+size_t tma_gcn_layer_fwd_workspace_bytes(int64_t n, int32_t F_out, int32_t dtype);
+
+int tma_gcn_layer_fwd(int64_t n, const int32_t *rowptr, const int32_t *colidx, const float *s_norm,
+                      const void *H, int64_t ldh, int32_t F_in,
+                      const float *W, const float *bias, int32_t F_out, int32_t act, int32_t dtype,
+                      void *Hnext_out, int64_t ld_next, void *ws, size_t ws_bytes, tma_stream_t stream);
+
+size_t tma_gcn_layer_bwd_workspace_bytes(int64_t n, int32_t F_in, int32_t F_out, int32_t dtype);
+
+int tma_gcn_layer_bwd(int64_t n, const int32_t *rowptr_T, const int32_t *colidx_T, const float *s_norm,
+                      const void *H, int64_t ldh, const void *Hnext, const void *dHnext, int64_t ld_next,
+                      const float *W, int32_t F_in, int32_t F_out, int32_t act, int32_t dtype,
+                      float *dW, float *dbias, void *dH_out,
+                      void *ws, size_t ws_bytes, tma_stream_t stream);
+
+/* ------------------------------------------------------------------------
  * Losses on the last layer's output.
  * tma_softmax_ce: mean softmax cross-entropy over the n local nodes (reading
  *   taken for workloads with class labels); loss_out[0] fp32 (device),

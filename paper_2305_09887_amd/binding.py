@@ -25,6 +25,9 @@ EXPORTS = (
     "tma_mean_aggregate", "tma_sage_layer_aggregates_first", "tma_sage_layer_fwd",
     "tma_sage_layer_bwd_workspace_bytes", "tma_sage_layer_bwd",
     "tma_layernorm_prelu_fwd", "tma_layernorm_prelu_bwd_workspace_bytes", "tma_layernorm_prelu_bwd",
+    "tma_dense_fwd", "tma_dense_bwd_workspace_bytes", "tma_dense_bwd",
+    "tma_gcn_norm", "tma_gcn_layer_fwd_workspace_bytes", "tma_gcn_layer_fwd",
+    "tma_gcn_layer_bwd_workspace_bytes", "tma_gcn_layer_bwd",
     "tma_loss_workspace_bytes", "tma_softmax_ce", "tma_sigmoid_l2", "tma_sgd_step", "tma_adam_step", "tma_average",
     "tma_gather_rows", "tma_profile_begin", "tma_profile_end", "tma_profile_count", "tma_profile_entry",
 )
@@ -47,7 +50,9 @@ def lib() -> C.CDLL:
         L = C.CDLL(_LIB_PATH)
         L.tma_last_error.restype = C.c_char_p
         for name in ("tma_induced_subgraph_workspace_bytes", "tma_sage_layer_bwd_workspace_bytes",
-                     "tma_loss_workspace_bytes"):
+                     "tma_loss_workspace_bytes", "tma_layernorm_prelu_bwd_workspace_bytes",
+                     "tma_dense_bwd_workspace_bytes", "tma_gcn_layer_fwd_workspace_bytes",
+                     "tma_gcn_layer_bwd_workspace_bytes"):
             getattr(L, name).restype = C.c_size_t
         _lib = L
     return _lib
@@ -263,6 +268,150 @@ def tma_sage_layer_bwd(rowptr_T, colidx_T, inv_deg, H, M, Hnext, dHnext, W_self,
         _ptr(dbias, torch.float32, "dbias"), C.c_void_p(dH_out.data_ptr() if dH_out is not None else 0), _ptr(ws),
         C.c_size_t(ws.numel()), _stream(stream)))
     return dW_self, dW_neigh, dbias, dH_out
+
+
+# --------------------------------------------------------------------------- other encoders (Sec. 4.1)
+def tma_dense_fwd(X, W, bias, act: int, Y_out=None, stream=None):
+    """Y = act(X W + b); bias may be None."""
+    n, F_in, ldx = _rows_ld(X, "X")
+    F_out = W.shape[1]
+    if tuple(W.shape) != (F_in, F_out) or (bias is not None and bias.numel() != F_out):
+        raise TmaError("tma_dense_fwd: weight shapes do not match X")
+    if Y_out is None:
+        Y_out = _padded(n, F_out, X.dtype, X.device)
+    if tuple(Y_out.shape) != (n, F_out) or Y_out.dtype != X.dtype:
+        raise TmaError("tma_dense_fwd: output shape/dtype")
+    _, _, ldy = _rows_ld(Y_out, "Y_out")
+    _check(lib().tma_dense_fwd(
+        C.c_int64(n), C.c_void_p(X.data_ptr()), C.c_int64(ldx), C.c_int32(F_in), _ptr(W, torch.float32, "W"),
+        _ptr(bias, torch.float32, "bias"), C.c_int32(F_out), C.c_int32(act), C.c_int32(_feat_dtype(X)),
+        C.c_void_p(Y_out.data_ptr()), C.c_int64(ldy), _stream(stream)))
+    return Y_out
+
+
+def tma_dense_bwd_workspace_bytes(n: int, F_in: int, F_out: int) -> int:
+    return int(lib().tma_dense_bwd_workspace_bytes(C.c_int64(n), C.c_int32(F_in), C.c_int32(F_out)))
+
+
+def tma_dense_bwd(X, Y, dY, W, act: int, dW=None, dbias=None, dX_out=None, need_dbias=True, need_dX=True, ws=None,
+                  stream=None):
+    """Returns (dW, dbias or None, dX or None)."""
+    n, F_in, ldx = _rows_ld(X, "X")
+    F_out = W.shape[1]
+    dev = X.device
+    if tuple(dY.shape) != (n, F_out) or dY.dtype != X.dtype:
+        raise TmaError("tma_dense_bwd: dY shape/dtype")
+    if act == TMA_ACT_RELU and (Y is None or tuple(Y.shape) != (n, F_out)):
+        raise TmaError("tma_dense_bwd: Y is required with ReLU")
+    if dW is None:
+        dW = torch.empty((F_in, F_out), dtype=torch.float32, device=dev)
+    if need_dbias and dbias is None:
+        dbias = torch.empty(F_out, dtype=torch.float32, device=dev)
+    if not need_dbias:
+        dbias = None
+    if need_dX and dX_out is None:
+        dX_out = _padded(n, F_in, X.dtype, dev)
+    if not need_dX:
+        dX_out = None
+    ld_dx = _rows_ld(dX_out, "dX_out")[2] if dX_out is not None else F_in
+    if dX_out is not None and tuple(dX_out.shape) != (n, F_in):
+        raise TmaError("tma_dense_bwd: dX_out shape")
+    _, _, ldy = _rows_ld(dY, "dY")
+    if act == TMA_ACT_RELU:
+        _same_ld(Y, dY, "tma_dense_bwd: Y / dY")
+    if ws is None:
+        ws = _workspace(tma_dense_bwd_workspace_bytes(n, F_in, F_out), dev)
+    _check(lib().tma_dense_bwd(
+        C.c_int64(n), C.c_void_p(X.data_ptr()), C.c_int64(ldx), C.c_void_p(Y.data_ptr() if Y is not None else 0),
+        C.c_void_p(dY.data_ptr()), C.c_int64(ldy), _ptr(W, torch.float32, "W"), C.c_int32(F_in), C.c_int32(F_out),
+        C.c_int32(act), C.c_int32(_feat_dtype(X)), _ptr(dW, torch.float32, "dW"), _ptr(dbias, torch.float32, "dbias"),
+        C.c_void_p(dX_out.data_ptr() if dX_out is not None else 0), C.c_int64(ld_dx), _ptr(ws),
+        C.c_size_t(ws.numel()), _stream(stream)))
+    return dW, dbias, dX_out
+
+
+def tma_gcn_norm(rowptr, out=None, stream=None):
+    """s_v = (d_v + 1)^-1/2 from the local rowptr (int32 [n+1])."""
+    n = rowptr.numel() - 1
+    if out is None:
+        out = torch.empty(max(n, 0), dtype=torch.float32, device=rowptr.device)
+    if out.numel() != n:
+        raise TmaError("tma_gcn_norm: out must have n entries")
+    _check(lib().tma_gcn_norm(C.c_int64(n), _ptr(rowptr, torch.int32, "rowptr"), _ptr(out, torch.float32, "out"),
+                              _stream(stream)))
+    return out
+
+
+def tma_gcn_layer_fwd_workspace_bytes(n: int, F_out: int, dtype: int) -> int:
+    return int(lib().tma_gcn_layer_fwd_workspace_bytes(C.c_int64(n), C.c_int32(F_out), C.c_int32(dtype)))
+
+
+def tma_gcn_layer_fwd(rowptr, colidx, s_norm, H, W, bias, act: int, Hnext_out=None, ws=None, stream=None):
+    """Hnext = act(Ahat H W + b)."""
+    n, F_in, ldh = _rows_ld(H, "H")
+    F_out = W.shape[1]
+    if tuple(W.shape) != (F_in, F_out) or bias.numel() != F_out:
+        raise TmaError("tma_gcn_layer_fwd: weight shapes do not match H")
+    if rowptr.numel() != n + 1 or s_norm.numel() != n:
+        raise TmaError("tma_gcn_layer_fwd: graph and feature row counts differ")
+    if Hnext_out is None:
+        Hnext_out = _padded(n, F_out, H.dtype, H.device)
+    if tuple(Hnext_out.shape) != (n, F_out) or Hnext_out.dtype != H.dtype:
+        raise TmaError("tma_gcn_layer_fwd: output shape/dtype")
+    _, _, ld_next = _rows_ld(Hnext_out, "Hnext_out")
+    dt = _feat_dtype(H)
+    if ws is None:
+        ws = _workspace(tma_gcn_layer_fwd_workspace_bytes(n, F_out, dt), H.device)
+    _check(lib().tma_gcn_layer_fwd(
+        C.c_int64(n), _ptr(rowptr, torch.int32), _ptr(colidx, torch.int32), _ptr(s_norm, torch.float32, "s_norm"),
+        C.c_void_p(H.data_ptr()), C.c_int64(ldh), C.c_int32(F_in), _ptr(W, torch.float32, "W"),
+        _ptr(bias, torch.float32, "bias"), C.c_int32(F_out), C.c_int32(act), C.c_int32(dt),
+        C.c_void_p(Hnext_out.data_ptr()), C.c_int64(ld_next), _ptr(ws), C.c_size_t(ws.numel()), _stream(stream)))
+    return Hnext_out
+
+
+def tma_gcn_layer_bwd_workspace_bytes(n: int, F_in: int, F_out: int, dtype: int) -> int:
+    return int(lib().tma_gcn_layer_bwd_workspace_bytes(C.c_int64(n), C.c_int32(F_in), C.c_int32(F_out),
+                                                       C.c_int32(dtype)))
+
+
+def tma_gcn_layer_bwd(rowptr_T, colidx_T, s_norm, H, Hnext, dHnext, W, act: int, dW=None, dbias=None, dH_out=None,
+                      need_dH=True, ws=None, stream=None):
+    """Returns (dW, dbias, dH or None)."""
+    n, F_in, ldh = _rows_ld(H, "H")
+    F_out = W.shape[1]
+    dev = H.device
+    if tuple(dHnext.shape) != (n, F_out) or dHnext.dtype != H.dtype:
+        raise TmaError("tma_gcn_layer_bwd: dHnext shape/dtype")
+    if act == TMA_ACT_RELU and (Hnext is None or tuple(Hnext.shape) != (n, F_out)):
+        raise TmaError("tma_gcn_layer_bwd: Hnext is required with ReLU")
+    if rowptr_T.numel() != n + 1 or s_norm.numel() != n:
+        raise TmaError("tma_gcn_layer_bwd: graph and feature row counts differ")
+    if dW is None:
+        dW = torch.empty((F_in, F_out), dtype=torch.float32, device=dev)
+    if dbias is None:
+        dbias = torch.empty(F_out, dtype=torch.float32, device=dev)
+    if need_dH and dH_out is None:
+        dH_out = torch.empty((max(n, 1), ldh), dtype=H.dtype, device=dev)[:n, :F_in]
+    if not need_dH:
+        dH_out = None
+    if dH_out is not None:
+        if tuple(dH_out.shape) != (n, F_in) or _rows_ld(dH_out, "dH_out")[2] != ldh:
+            raise TmaError("tma_gcn_layer_bwd: dH_out must have the shape and leading dimension of H")
+    _, _, ld_next = _rows_ld(dHnext, "dHnext")
+    if act == TMA_ACT_RELU:
+        _same_ld(Hnext, dHnext, "tma_gcn_layer_bwd: Hnext / dHnext")
+    dt = _feat_dtype(H)
+    if ws is None:
+        ws = _workspace(tma_gcn_layer_bwd_workspace_bytes(n, F_in, F_out, dt), dev)
+    _check(lib().tma_gcn_layer_bwd(
+        C.c_int64(n), _ptr(rowptr_T, torch.int32), _ptr(colidx_T, torch.int32), _ptr(s_norm, torch.float32, "s_norm"),
+        C.c_void_p(H.data_ptr()), C.c_int64(ldh), C.c_void_p(Hnext.data_ptr() if Hnext is not None else 0),
+        C.c_void_p(dHnext.data_ptr()), C.c_int64(ld_next), _ptr(W, torch.float32, "W"), C.c_int32(F_in),
+        C.c_int32(F_out), C.c_int32(act), C.c_int32(dt), _ptr(dW, torch.float32, "dW"),
+        _ptr(dbias, torch.float32, "dbias"), C.c_void_p(dH_out.data_ptr() if dH_out is not None else 0), _ptr(ws),
+        C.c_size_t(ws.numel()), _stream(stream)))
+    return dW, dbias, dH_out
 
 
 def tma_loss_workspace_bytes(n: int, Cc: int) -> int:

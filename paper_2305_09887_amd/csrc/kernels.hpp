@@ -11,11 +11,12 @@ int launch_spmm(int64_t n, const int32_t *rowptr, const int32_t *colidx, const f
                 int64_t ld_in, int32_t F, int32_t dtype, void *out, int64_t ld_out, bool accumulate,
                 hipStream_t stream);
 
-// Same gather with the layer epilogue fused: out_v = act(scale_v * sum + [out_v] + self_v + bias).
+// Same gather with the layer epilogue fused: out_v = act(scale_v * sum + [out_v] + self_v + bias), or, with
+// scale_all, out_v = act(scale_v * (sum + [out_v] + self_v) + bias) (the GCN form, self inside the normalisation).
 int launch_spmm_combine(int64_t n, const int32_t *rowptr, const int32_t *colidx, const float *inv_deg, const void *in,
                         int64_t ld_in, int32_t F, int32_t dtype, void *out, int64_t ld_out, bool accumulate,
                         const void *self, int64_t ld_self, const float *bias, int32_t F_valid, bool relu,
-                        hipStream_t stream);
+                        bool scale_all, hipStream_t stream);
 
 // dst_v = inv_deg[v] * g_v (.) [h_v > 0]  (mask only with relu); columns F..F_pad-1 of dst are zeroed.
 int launch_scale_mask_rows(int64_t n, int32_t F, int32_t F_pad, const void *g, const void *h, int64_t ld,
@@ -57,5 +58,28 @@ int launch_sage_tf_gemm_bwd_weight(int64_t n, const void *H, int64_t ldh, const 
 int launch_sage_tf_gemm_bwd_data(int64_t n, const void *dHnext, const void *Hnext, int64_t ld_next, const void *dYn,
                                  int64_t ldy, const float *W_self, const float *W_neigh, int32_t F_in, int32_t F_out,
                                  int32_t act, int32_t dtype, void *dH, int64_t ldh, hipStream_t stream);
+
+// Second stage of a split weight-gradient product, fixed order: partial is [n_splits][halves * F][N] and
+// colsum_partial [n_splits][N]; rows [0, F) go to dW_first, rows [F, 2F) (halves = 2) to dW_second, the
+// column sums to dbias (skipped when NULL).  n_splits = 0 writes zeros.
+int launch_reduce_splits(const float *partial, const float *colsum_partial, int n_splits, int32_t F, int32_t N,
+                         int halves, float *dW_first, float *dW_second, float *dbias, hipStream_t stream);
+
+// Single-operand transforms (dense layer; GCN products).  row_scale (may be NULL) multiplies output row v by
+// row_scale[v]; bias may be NULL.
+//   fwd:        Y = act(X W + b)  or  diag(row_scale) (X W); N_out >= F_out columns are written (at most F_out
+//               rounded up to 8, only without bias), zeros past F_out
+//   bwd data:   dX = [diag(row_scale)] dZ W^T,   dZ = dY (.) act'(Y)
+//   bwd weight: dW = X^T dZ,  dbias = 1^T dZ (skipped when NULL)
+int launch_dense_gemm_fwd(int64_t n, const void *X, int64_t ldx, int32_t F_in, const float *W, const float *bias,
+                          const float *row_scale, int32_t F_out, int32_t N_out, int32_t act, int32_t dtype, void *Y,
+                          int64_t ldy, hipStream_t s);
+int launch_dense_gemm_bwd_data(int64_t n, const void *dY, const void *Y, int64_t ld, const float *W, int32_t F_in,
+                               int32_t F_out, int32_t act, int32_t dtype, const float *row_scale, void *dX,
+                               int64_t ldx, hipStream_t s);
+size_t dense_gemm_bwd_weight_workspace_bytes(int64_t n, int32_t F_in, int32_t F_out);
+int launch_dense_gemm_bwd_weight(int64_t n, const void *X, int64_t ldx, const void *dY, const void *Y, int64_t ld,
+                                 int32_t F_in, int32_t F_out, int32_t act, int32_t dtype, float *dW, float *dbias,
+                                 void *ws, size_t ws_bytes, hipStream_t s);
 
 }  // namespace tma

@@ -80,6 +80,7 @@ __device__ __forceinline__ void gather_sum(const T *__restrict__ in, int64_t ld,
 
 // What happens to a finished row sum s_v:
 //   out_v = act( scale_v * s_v  [+ out_v]  [+ self_v]  [+ bias] )
+//   out_v = act( scale_v * (s_v  [+ out_v]  [+ self_v])  [+ bias] )      with scale_all
 // scale_v = inv_deg[v] (mean) or 1; "+ out_v" accumulates onto what is there (backward: on top of
 // dZ W_self^T); "+ self_v + bias" and the activation turn the gather into the layer output when the
 // transform ran before the aggregation.
@@ -94,6 +95,7 @@ struct SpmmOut {
     const float *bias;
     int F;  // valid elements of a row (bias is not applied to padding)
     int relu;
+    int scale_all;  // the scale multiplies the sum with "+ out_v" / "+ self_v" already added (GCN: s_v (sum + self_v))
 };
 
 template <typename T, int G, int CPL>
@@ -109,7 +111,7 @@ __device__ __forceinline__ void finish_row(int64_t v, const SpmmOut<T> &o, int s
             T *dst = o.out + v * o.ld_out + f0;
             float r[E];
 #pragma unroll
-            for (int i = 0; i < E; ++i) r[i] = acc[c][i] * scale;
+            for (int i = 0; i < E; ++i) r[i] = o.scale_all ? acc[c][i] : acc[c][i] * scale;
             if (o.accumulate) {
                 float old[E];
                 Chunk<T>::load(dst, old);
@@ -121,6 +123,10 @@ __device__ __forceinline__ void finish_row(int64_t v, const SpmmOut<T> &o, int s
                 Chunk<T>::load(o.self + v * o.ld_self + f0, sv);
 #pragma unroll
                 for (int i = 0; i < E; ++i) r[i] += sv[i];
+            }
+            if (o.scale_all) {
+#pragma unroll
+                for (int i = 0; i < E; ++i) r[i] *= scale;
             }
             if (o.bias) {
 #pragma unroll
@@ -315,12 +321,16 @@ __global__ __launch_bounds__(kSpmmThreads) void spmm_stream_kernel(int64_t n, co
         const int f0 = sub * E;
         float res[E];
 #pragma unroll
-        for (int i = 0; i < E; ++i) res[i] = kScale ? acc[i] * X.scale : acc[i];
+        for (int i = 0; i < E; ++i) res[i] = (kScale && !o.scale_all) ? acc[i] * X.scale : acc[i];
         if constexpr (kExtra != 0) {
             float x[E];
             Chunk<T>::widen(X.raw, x);
 #pragma unroll
             for (int i = 0; i < E; ++i) res[i] += x[i];
+        }
+        if (kScale && o.scale_all) {
+#pragma unroll
+            for (int i = 0; i < E; ++i) res[i] *= X.scale;
         }
         if (o.bias) {
 #pragma unroll
@@ -495,9 +505,10 @@ __global__ __launch_bounds__(kSpmmThreads) void spmm_rows_generic_kernel(int64_t
             const int f = f0 + k * kWave + lane;
             if (f < F) {
                 T *dst = o.out + v * o.ld_out + f;
-                float r = acc[k] * scale;
+                float r = o.scale_all ? acc[k] : acc[k] * scale;
                 if (o.accumulate) r += load_elem(dst);
                 if (o.self) r += load_elem(o.self + v * o.ld_self + f);
+                if (o.scale_all) r *= scale;
                 if (o.bias && f < o.F) r += o.bias[f];
                 if (o.relu) r = r > 0.0f ? r : 0.0f;
                 store_elem(dst, r);
@@ -577,10 +588,10 @@ static int launch_typed(int64_t n, const int32_t *rowptr, const int32_t *colidx,
 template <typename T>
 static int spmm_any(int64_t n, const int32_t *rowptr, const int32_t *colidx, const float *inv_deg, const void *in,
                     int64_t ld_in, int32_t F, void *out, int64_t ld_out, bool accumulate, const void *self,
-                    int64_t ld_self, const float *bias, int32_t F_valid, bool relu, hipStream_t stream)
+                    int64_t ld_self, const float *bias, int32_t F_valid, bool relu, bool scale_all, hipStream_t stream)
 {
     SpmmOut<T> o{static_cast<T *>(out), ld_out, inv_deg, accumulate ? 1 : 0, static_cast<const T *>(self), ld_self,
-                 bias, F_valid, relu ? 1 : 0};
+                 bias, F_valid, relu ? 1 : 0, (scale_all && inv_deg) ? 1 : 0};
     return launch_typed<T>(n, rowptr, colidx, static_cast<const T *>(in), ld_in, F, o, stream);
 }
 
@@ -589,21 +600,21 @@ int launch_spmm(int64_t n, const int32_t *rowptr, const int32_t *colidx, const f
                 hipStream_t stream)
 {
     return launch_spmm_combine(n, rowptr, colidx, inv_deg, in, ld_in, F, dtype, out, ld_out, accumulate, nullptr, 0,
-                               nullptr, F, false, stream);
+                               nullptr, F, false, false, stream);
 }
 
 int launch_spmm_combine(int64_t n, const int32_t *rowptr, const int32_t *colidx, const float *inv_deg, const void *in,
                         int64_t ld_in, int32_t F, int32_t dtype, void *out, int64_t ld_out, bool accumulate,
                         const void *self, int64_t ld_self, const float *bias, int32_t F_valid, bool relu,
-                        hipStream_t stream)
+                        bool scale_all, hipStream_t stream)
 {
     if (n == 0 || F == 0) return TMA_OK;
     if (dtype == TMA_F32)
         return spmm_any<float>(n, rowptr, colidx, inv_deg, in, ld_in, F, out, ld_out, accumulate, self, ld_self, bias,
-                               F_valid, relu, stream);
+                               F_valid, relu, scale_all, stream);
     if (dtype == TMA_BF16)
         return spmm_any<uint16_t>(n, rowptr, colidx, inv_deg, in, ld_in, F, out, ld_out, accumulate, self, ld_self,
-                                  bias, F_valid, relu, stream);
+                                  bias, F_valid, relu, scale_all, stream);
     return fail(TMA_ERR_UNSUPPORTED_DTYPE, "spmm: dtype %d", dtype);
 }
 
