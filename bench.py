@@ -46,14 +46,30 @@ MEASURED_TRAFFIC_BYTES = {
 }
 
 
-def kernel_work(name, n, nnz, dims, N=0, nnz_glob=0, K=1, n_params=0):
+def kernel_work(name, n, nnz, dims, N=0, nnz_glob=0, K=1, n_params=0, encoder="sage"):
     """Algorithmic work of one launch of kernel `name` in this workload: ("mfma", flops) or ("hbm", bytes).
 
     Bytes count every array the kernel must touch once (distinct input rows once, however often they are
-    gathered; outputs once); flops count the products of the layer's definition, not the padding."""
+    gathered; outputs once); flops count the products of the layer's definition, not the padding.  A kernel
+    name that both layers launch (the GCN / MLP encoders) gets the mean over its launches of a step."""
     F0, F1, C = dims
     Cp = (C + 3) // 4 * 4        # padded width of the transform-first blocks
     s = 4
+    if encoder != "sage":
+        both = (2.0 * n * F0 * F1 + 2.0 * n * F1 * C) / 2
+        other = {
+            "gemm_dense_fwd": ("mfma", both),                      # Y = X W, both layers
+            "gemm_dense_bwd_weight": ("mfma", both),               # dW = X^T G, both layers
+            "gemm_dense_bwd_data": ("mfma", 2.0 * n * F1 * C),     # dH1 = G W^T, layer 1 only
+            # layer 0 aggregates first: M = S (A + I) S H0, rows of H0 once + ids + rowptr, s + output
+            "spmm_weighted_f32_g32x1": ("hbm", 2.0 * n * F0 * s + nnz * 4 + n * 8),
+            # layer 1 transforms first: H2 = S (A + I) Y + b forward and G = S (A + I)^T Q backward
+            "spmm_combine_f32_g12x1": ("hbm", 2.0 * n * Cp * s + nnz * 4 + n * 8),
+            # Q = S dZ of layer 1: dH2 read, Q written, s read
+            "scale_mask_colsum": ("hbm", n * (C + Cp) * s + n * 4.0),
+        }
+        if name.replace("_generic", "") in other:
+            return other[name.replace("_generic", "")]
     gemm = {
         "gemm_fwd_128x128": 2.0 * n * (2 * F0) * F1,          # Z1 = [H0 | M0] [Ws; Wn]
         "gemm_bwd_weight_128x128": 2.0 * n * (2 * F0) * F1,   # [dWs; dWn] = [H0 | M0]^T dZ1
@@ -103,6 +119,9 @@ def main():
     ap.add_argument("--norm-act", action="store_true",
                     help="hidden layers with layer normalisation + PReLU (the paper's encoder variant) instead of "
                          "ReLU; a second measurement, not the headline workload")
+    ap.add_argument("--encoder", choices=("sage", "gcn", "mlp"), default="sage",
+                    help="the paper's other encoders (GCN, graph-agnostic MLP); a second measurement, not the "
+                         "headline workload")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="only run a plain 1 GiB device copy (reference for scaling rocprofv3 FETCH_SIZE/WRITE_SIZE)")
     args = ap.parse_args()
@@ -151,11 +170,13 @@ def main():
     n_loc, nnz_loc = sub["n_loc"], sub["nnz_loc"]
     Xl = torch.empty((n_loc, dims[0]), dtype=torch.float32, device=dev)
     yl = torch.empty(n_loc, dtype=torch.int32, device=dev)
+    if args.encoder != "sage":   # one weight matrix per layer
+        params = [(Ws, b) for Ws, _, b in params]
     if args.norm_act:   # gamma = 1, beta = 0, slope = 0.25 on the hidden layers
         params = [tuple(l) + ((np.ones(dims[i + 1], np.float32), np.zeros(dims[i + 1], np.float32),
                                np.full(1, 0.25, np.float32)) if i < L - 1 else ()) for i, l in enumerate(params)]
     tr = LocalTrainer(sub["rowptr"], sub["colidx"], sub["inv_deg"], Xl, yl, dims, params=params,
-                      norm_act=args.norm_act)
+                      norm_act=args.norm_act, encoder=args.encoder)
     peers = [tr.W.clone() for _ in range(K - 1)]      # the other K-1 trainers' parameter vectors
     W_all = [tr.W] + peers
     ptrs = torch.tensor([t.data_ptr() for t in W_all], dtype=torch.int64, device=dev)
@@ -197,7 +218,7 @@ def main():
     ms_per_step = elapsed * 1e3 / args.steps
     loss = float(tr.loss.item())
 
-    kw = dict(N=N, nnz_glob=int(rowptr[-1]), K=K, n_params=int(tr.W.numel()))
+    kw = dict(N=N, nnz_glob=int(rowptr[-1]), K=K, n_params=int(tr.W.numel()), encoder=args.encoder)
     bound, work = kernel_work(dominant, n_loc, nnz_loc, dims, **kw)
     avg_ms = dom[1] / max(dom[0], 1)
     if bound == "mfma":
@@ -231,7 +252,7 @@ def main():
 
     value = L * nnz_loc / (ms_per_step * 1e-3)
     train_ms = sum(v for k, v in per_step.items()
-                   if k.startswith(("spmm", "gemm", "reduce", "softmax", "finish", "sgd", "ln_prelu", "scale_mask")))
+                   if k.startswith(("spmm", "gemm", "reduce", "softmax", "finish", "sgd", "ln_prelu", "scale_mask", "sum_partials")))
     out = {
         "metric": "trainer edges/sec per SAGE layer fwd+bwd; achieved HBM GB/s vs peak",
         "value": round(value, 1), "unit": "edges/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
@@ -242,7 +263,7 @@ def main():
                                "induced-subgraph extraction of part 0 + row gather + 2-layer mean-SAGE (hidden 256) "
                                "full-batch fwd+bwd+SGD + 8-way parameter averaging",
                    "n_nodes": N, "nnz_global": int(rowptr[-1]), "K": K, "n_loc": n_loc, "nnz_loc": nnz_loc,
-                   "layers": L, "dims": dims, "hidden_activation": "layernorm+prelu" if args.norm_act else "relu", "edge_definition": "directed local CSR entry; value = layers*nnz_loc/step time"},
+                   "layers": L, "dims": dims, "encoder": args.encoder, "hidden_activation": "layernorm+prelu" if args.norm_act else "relu", "edge_definition": "directed local CSR entry; value = layers*nnz_loc/step time"},
         "roofline": roofline,
         "kernel_rooflines": kernel_rooflines,
         "kernel_ms_per_step": {k: round(v, 5) for k, v in sorted(per_step.items(), key=lambda kv: -kv[1])},
@@ -258,7 +279,7 @@ def main():
         sub_o = oracle.induced_subgraph(rowptr, colidx, part_o, p)
         Xo, yo = X[sub_o["l2g"]], y[sub_o["l2g"]]
         p_o = [tuple(np.asarray(t, dtype=np.float64) for t in l) for l in params]
-        _, p_new = omodel.train_step(sub_o["rowptr"], sub_o["colidx"], Xo, yo, p_o, w["lr"])
+        _, p_new = omodel.train_step(sub_o["rowptr"], sub_o["colidx"], Xo, yo, p_o, w["lr"], encoder=args.encoder)
         omodel.aggregate([p_new] + [p_o] * (K - 1))
         t_cpu = time.perf_counter() - t_cpu
         out["cpu_baseline"] = {"value": round(L * len(sub_o["colidx"]) / t_cpu, 1), "unit": "edges/s", "cores": 1,

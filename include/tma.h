@@ -267,24 +267,30 @@ int tma_dense_bwd(int64_t n, const void *X, int64_t ldx, const void *Y, const vo
  *   of the TRANSPOSED local graph (the same arrays for a symmetric graph).
  *   dW [F_in, F_out], dbias [F_out] fp32 OVERWRITTEN;  dH_out [n, F_in] dtype
  *   with leading dimension ldh, or NULL.
- * The layer multiplies first and aggregates F_out-wide rows (any widths).
- * Workspaces (256-byte aligned): tma_gcn_layer_fwd_workspace_bytes(n, F_out,
- * dtype) and tma_gcn_layer_bwd_workspace_bytes(n, F_in, F_out, dtype); the
- * backward needs nothing the forward left there.  Deterministic.
+ * The gather runs on the narrower side: the layer aggregates first (M_out =
+ * Ahat H, kept for the backward) unless F_out padded to 16 bytes is smaller
+ * than F_in; then it multiplies first and M_out is scratch; tma_gcn_layer_aggregates_first
+ * tells which.  M_out / M: [n, F_in] dtype, dense, 16-byte aligned, never
+ * aliasing H; the backward reads M only in the aggregate-first form and H only
+ * in the other (the unused one may be NULL).
+ * Backward workspace (256-byte aligned): tma_gcn_layer_bwd_workspace_bytes(n,
+ * F_in, F_out, dtype, dH_out != NULL).  Deterministic.
  * ---------------------------------------------------------------------- */
 int tma_gcn_norm(int64_t n, const int32_t *rowptr, float *s_out, tma_stream_t stream);
 
-size_t tma_gcn_layer_fwd_workspace_bytes(int64_t n, int32_t F_out, int32_t dtype);
+int tma_gcn_layer_aggregates_first(int32_t F_in, int32_t F_out, int32_t dtype);
 
 int tma_gcn_layer_fwd(int64_t n, const int32_t *rowptr, const int32_t *colidx, const float *s_norm,
                       const void *H, int64_t ldh, int32_t F_in,
                       const float *W, const float *bias, int32_t F_out, int32_t act, int32_t dtype,
-                      void *Hnext_out, int64_t ld_next, void *ws, size_t ws_bytes, tma_stream_t stream);
+                      void *M_out, void *Hnext_out, int64_t ld_next, tma_stream_t stream);
 
-size_t tma_gcn_layer_bwd_workspace_bytes(int64_t n, int32_t F_in, int32_t F_out, int32_t dtype);
+size_t tma_gcn_layer_bwd_workspace_bytes(int64_t n, int32_t F_in, int32_t F_out, int32_t dtype,
+                                         int32_t need_dH);
 
 int tma_gcn_layer_bwd(int64_t n, const int32_t *rowptr_T, const int32_t *colidx_T, const float *s_norm,
-                      const void *H, int64_t ldh, const void *Hnext, const void *dHnext, int64_t ld_next,
+                      const void *H, int64_t ldh, const void *M, const void *Hnext, const void *dHnext,
+                      int64_t ld_next,
                       const float *W, int32_t F_in, int32_t F_out, int32_t act, int32_t dtype,
                       float *dW, float *dbias, void *dH_out,
                       void *ws, size_t ws_bytes, tma_stream_t stream);

@@ -26,7 +26,7 @@ EXPORTS = (
     "tma_sage_layer_bwd_workspace_bytes", "tma_sage_layer_bwd",
     "tma_layernorm_prelu_fwd", "tma_layernorm_prelu_bwd_workspace_bytes", "tma_layernorm_prelu_bwd",
     "tma_dense_fwd", "tma_dense_bwd_workspace_bytes", "tma_dense_bwd",
-    "tma_gcn_norm", "tma_gcn_layer_fwd_workspace_bytes", "tma_gcn_layer_fwd",
+    "tma_gcn_norm", "tma_gcn_layer_aggregates_first", "tma_gcn_layer_fwd",
     "tma_gcn_layer_bwd_workspace_bytes", "tma_gcn_layer_bwd",
     "tma_loss_workspace_bytes", "tma_softmax_ce", "tma_sigmoid_l2", "tma_sgd_step", "tma_adam_step", "tma_average",
     "tma_gather_rows", "tma_profile_begin", "tma_profile_end", "tma_profile_count", "tma_profile_entry",
@@ -51,8 +51,7 @@ def lib() -> C.CDLL:
         L.tma_last_error.restype = C.c_char_p
         for name in ("tma_induced_subgraph_workspace_bytes", "tma_sage_layer_bwd_workspace_bytes",
                      "tma_loss_workspace_bytes", "tma_layernorm_prelu_bwd_workspace_bytes",
-                     "tma_dense_bwd_workspace_bytes", "tma_gcn_layer_fwd_workspace_bytes",
-                     "tma_gcn_layer_bwd_workspace_bytes"):
+                     "tma_dense_bwd_workspace_bytes", "tma_gcn_layer_bwd_workspace_bytes"):
             getattr(L, name).restype = C.c_size_t
         _lib = L
     return _lib
@@ -342,47 +341,46 @@ def tma_gcn_norm(rowptr, out=None, stream=None):
     return out
 
 
-def tma_gcn_layer_fwd_workspace_bytes(n: int, F_out: int, dtype: int) -> int:
-    return int(lib().tma_gcn_layer_fwd_workspace_bytes(C.c_int64(n), C.c_int32(F_out), C.c_int32(dtype)))
+def tma_gcn_layer_aggregates_first(F_in: int, F_out: int, dtype: int) -> bool:
+    return bool(lib().tma_gcn_layer_aggregates_first(C.c_int32(F_in), C.c_int32(F_out), C.c_int32(dtype)))
 
 
-def tma_gcn_layer_fwd(rowptr, colidx, s_norm, H, W, bias, act: int, Hnext_out=None, ws=None, stream=None):
-    """Hnext = act(Ahat H W + b)."""
+def tma_gcn_layer_fwd(rowptr, colidx, s_norm, H, W, bias, act: int, M_out=None, Hnext_out=None, stream=None):
+    """Hnext = act(Ahat H W + b).  Returns (M, Hnext); M is Ahat H when the layer aggregates first."""
     n, F_in, ldh = _rows_ld(H, "H")
     F_out = W.shape[1]
     if tuple(W.shape) != (F_in, F_out) or bias.numel() != F_out:
         raise TmaError("tma_gcn_layer_fwd: weight shapes do not match H")
     if rowptr.numel() != n + 1 or s_norm.numel() != n:
         raise TmaError("tma_gcn_layer_fwd: graph and feature row counts differ")
+    if M_out is None:
+        M_out = torch.empty((n, F_in), dtype=H.dtype, device=H.device)
     if Hnext_out is None:
         Hnext_out = _padded(n, F_out, H.dtype, H.device)
-    if tuple(Hnext_out.shape) != (n, F_out) or Hnext_out.dtype != H.dtype:
+    if tuple(M_out.shape) != (n, F_in) or tuple(Hnext_out.shape) != (n, F_out) or Hnext_out.dtype != H.dtype:
         raise TmaError("tma_gcn_layer_fwd: output shape/dtype")
     _, _, ld_next = _rows_ld(Hnext_out, "Hnext_out")
-    dt = _feat_dtype(H)
-    if ws is None:
-        ws = _workspace(tma_gcn_layer_fwd_workspace_bytes(n, F_out, dt), H.device)
     _check(lib().tma_gcn_layer_fwd(
         C.c_int64(n), _ptr(rowptr, torch.int32), _ptr(colidx, torch.int32), _ptr(s_norm, torch.float32, "s_norm"),
         C.c_void_p(H.data_ptr()), C.c_int64(ldh), C.c_int32(F_in), _ptr(W, torch.float32, "W"),
-        _ptr(bias, torch.float32, "bias"), C.c_int32(F_out), C.c_int32(act), C.c_int32(dt),
-        C.c_void_p(Hnext_out.data_ptr()), C.c_int64(ld_next), _ptr(ws), C.c_size_t(ws.numel()), _stream(stream)))
-    return Hnext_out
+        _ptr(bias, torch.float32, "bias"), C.c_int32(F_out), C.c_int32(act), C.c_int32(_feat_dtype(H)),
+        _ptr(M_out, H.dtype, "M_out"), C.c_void_p(Hnext_out.data_ptr()), C.c_int64(ld_next), _stream(stream)))
+    return M_out, Hnext_out
 
 
-def tma_gcn_layer_bwd_workspace_bytes(n: int, F_in: int, F_out: int, dtype: int) -> int:
+def tma_gcn_layer_bwd_workspace_bytes(n: int, F_in: int, F_out: int, dtype: int, need_dH: bool) -> int:
     return int(lib().tma_gcn_layer_bwd_workspace_bytes(C.c_int64(n), C.c_int32(F_in), C.c_int32(F_out),
-                                                       C.c_int32(dtype)))
+                                                       C.c_int32(dtype), C.c_int32(1 if need_dH else 0)))
 
 
-def tma_gcn_layer_bwd(rowptr_T, colidx_T, s_norm, H, Hnext, dHnext, W, act: int, dW=None, dbias=None, dH_out=None,
+def tma_gcn_layer_bwd(rowptr_T, colidx_T, s_norm, H, M, Hnext, dHnext, W, act: int, dW=None, dbias=None, dH_out=None,
                       need_dH=True, ws=None, stream=None):
-    """Returns (dW, dbias, dH or None)."""
+    """Returns (dW, dbias, dH or None).  M: what the forward left in M_out."""
     n, F_in, ldh = _rows_ld(H, "H")
     F_out = W.shape[1]
     dev = H.device
-    if tuple(dHnext.shape) != (n, F_out) or dHnext.dtype != H.dtype:
-        raise TmaError("tma_gcn_layer_bwd: dHnext shape/dtype")
+    if tuple(dHnext.shape) != (n, F_out) or dHnext.dtype != H.dtype or tuple(M.shape) != (n, F_in):
+        raise TmaError("tma_gcn_layer_bwd: M / dHnext shape or dtype")
     if act == TMA_ACT_RELU and (Hnext is None or tuple(Hnext.shape) != (n, F_out)):
         raise TmaError("tma_gcn_layer_bwd: Hnext is required with ReLU")
     if rowptr_T.numel() != n + 1 or s_norm.numel() != n:
@@ -403,10 +401,11 @@ def tma_gcn_layer_bwd(rowptr_T, colidx_T, s_norm, H, Hnext, dHnext, W, act: int,
         _same_ld(Hnext, dHnext, "tma_gcn_layer_bwd: Hnext / dHnext")
     dt = _feat_dtype(H)
     if ws is None:
-        ws = _workspace(tma_gcn_layer_bwd_workspace_bytes(n, F_in, F_out, dt), dev)
+        ws = _workspace(tma_gcn_layer_bwd_workspace_bytes(n, F_in, F_out, dt, need_dH), dev)
     _check(lib().tma_gcn_layer_bwd(
         C.c_int64(n), _ptr(rowptr_T, torch.int32), _ptr(colidx_T, torch.int32), _ptr(s_norm, torch.float32, "s_norm"),
-        C.c_void_p(H.data_ptr()), C.c_int64(ldh), C.c_void_p(Hnext.data_ptr() if Hnext is not None else 0),
+        C.c_void_p(H.data_ptr()), C.c_int64(ldh), _ptr(M, H.dtype, "M"),
+        C.c_void_p(Hnext.data_ptr() if Hnext is not None else 0),
         C.c_void_p(dHnext.data_ptr()), C.c_int64(ld_next), _ptr(W, torch.float32, "W"), C.c_int32(F_in),
         C.c_int32(F_out), C.c_int32(act), C.c_int32(dt), _ptr(dW, torch.float32, "dW"),
         _ptr(dbias, torch.float32, "dbias"), C.c_void_p(dH_out.data_ptr() if dH_out is not None else 0), _ptr(ws),

@@ -42,19 +42,21 @@ static int dense_fwd_typed(int64_t n, const T *X, int64_t ldx, int32_t F_in, con
 {
     DenseEpilogue<T, kRowScale> e{Y, ldy, bias, row_scale, relu};
     const int64_t K = F_in, kps = int64_t(round_up(size_t(K), 32));
-    // the views' second parts start F_in (resp. the padded F_out) elements in: only whole groups of four stay aligned
-    const bool v = vec4_ok(X, ldx) && F_in % 4 == 0 && F_out % 4 == 0 && aligned(W, 16);
+    // a group of four along k must not reach into row padding, nor a group of four columns past F_out
+    const bool va = vec4_ok(X, ldx) && F_in % 4 == 0;
+    const bool vb = F_out % 4 == 0 && aligned(W, 16);
     const char *name = kname<T>("gemm_dense_fwd", "gemm_dense_fwd_generic", "gemm_dense_fwd_bf16",
-                                "gemm_dense_fwd_bf16_generic", v);
-    if (v) {
-        CatRows<T, true> a{X, ldx, X, F_in, n, F_in};
-        SideWeights<true> b{W, W, F_in, F_out, pad8(F_out)};
-        launch_by_width<T, 32, false>(name, a, b, e, n, N_out, K, kps, 1, nullptr, s);
-    } else {
-        CatRows<T, false> a{X, ldx, X, F_in, n, F_in};
-        SideWeights<false> b{W, W, F_in, F_out, pad8(F_out)};
-        launch_by_width<T, 32, false>(name, a, b, e, n, N_out, K, kps, 1, nullptr, s);
-    }
+                                "gemm_dense_fwd_bf16_generic", va);
+#define TMA_DENSE_FWD(VA_, VB_)                                                               \
+    do {                                                                                      \
+        CatRows<T, VA_> a{X, ldx, X, F_in, n, F_in};                                          \
+        SideWeights<VB_> b{W, W, F_in, F_out, pad8(F_out)};                                   \
+        launch_by_width<T, 32, false>(name, a, b, e, n, N_out, K, kps, 1, nullptr, s);        \
+    } while (0)
+    if (va && vb) TMA_DENSE_FWD(true, true);
+    else if (va) TMA_DENSE_FWD(true, false);
+    else TMA_DENSE_FWD(false, false);
+#undef TMA_DENSE_FWD
     return check_launch("dense gemm fwd");
 }
 
@@ -88,18 +90,20 @@ static int dense_bwd_data_typed(int64_t n, const T *g, const T *h, int64_t ld, c
 {
     DenseEpilogue<T, kRowScale> e{dX, ldx, nullptr, row_scale, false};
     const int64_t K = F_out, kps = int64_t(round_up(size_t(K), 32));
-    const bool v = vec4_ok(g, ld) && (!kRelu || vec4_ok(h, ld)) && vec4_ok(W, F_out);
+    const bool va = vec4_ok(g, ld) && (!kRelu || vec4_ok(h, ld));
+    const bool vb = vec4_ok(W, F_out);
     const char *name = kname<T>("gemm_dense_bwd_data", "gemm_dense_bwd_data_generic", "gemm_dense_bwd_data_bf16",
-                                "gemm_dense_bwd_data_bf16_generic", v);
-    if (v) {
-        MaskedGrad<true, T, true, kRelu> a{g, h, F_out, ld, n};
-        CatWeightsT<true> b{W, W, F_in, F_out};
-        launch_by_width<T, 32, false>(name, a, b, e, n, F_in, K, kps, 1, nullptr, s);
-    } else {
-        MaskedGrad<true, T, false, kRelu> a{g, h, F_out, ld, n};
-        CatWeightsT<false> b{W, W, F_in, F_out};
-        launch_by_width<T, 32, false>(name, a, b, e, n, F_in, K, kps, 1, nullptr, s);
-    }
+                                "gemm_dense_bwd_data_bf16_generic", va);
+#define TMA_DENSE_BD(VA_, VB_)                                                                \
+    do {                                                                                      \
+        MaskedGrad<true, T, VA_, kRelu> a{g, h, F_out, ld, n};                                \
+        CatWeightsT<VB_> b{W, W, F_in, F_out};                                                \
+        launch_by_width<T, 32, false>(name, a, b, e, n, F_in, K, kps, 1, nullptr, s);         \
+    } while (0)
+    if (va && vb) TMA_DENSE_BD(true, true);
+    else if (va) TMA_DENSE_BD(true, false);
+    else TMA_DENSE_BD(false, false);
+#undef TMA_DENSE_BD
     return check_launch("dense gemm bwd data");
 }
 

@@ -4,13 +4,17 @@
 // decoder).  Sequencing plus two small row-wise kernels; the products run in the
 // matrix-core template, the aggregation in the streaming gather.
 //
-// GCN layer, transform first:   Ahat = S (A + I) S,  S = diag((d_v + 1)^-1/2)
+// GCN layer:   Ahat = S (A + I) S,  S = diag((d_v + 1)^-1/2).  The gather runs on the narrower side.
+// Transform first (F_out < F_in):
 //   forward   Y = S (H W)                               (product, rows scaled in its epilogue)
 //             H' = act(S (A + I) Y + b)                 (gather: sum of neighbour rows + own row, scaled)
 //   backward  dZ = dH' (.) act'(H'),  db = 1^T dZ,  Q = S dZ        (one row-wise pass)
 //             G = S (A + I)^T Q  = Ahat^T dZ            (gather over the transposed graph)
 //             dW = H^T G,   dH = G W^T                  (products)
-// The aggregation thus always runs on F_out-wide rows; nothing needs a scale per neighbour.
+// Aggregate first (F_out >= F_in):
+//   forward   M = S (A + I) S H                         (gather with a weight per neighbour), H' = act(M W + b)
+//   backward  dW = M^T dZ, db = 1^T dZ                  (mask applied while loading; no gather for a first layer)
+//             dH = S (A + I)^T (S dZ W^T)               (product with scaled rows, then the gather)
 #include "kernels.hpp"
 
 namespace tma {
@@ -153,20 +157,31 @@ static ColsumPlan plan_colsum(int64_t n, int F, int F_pad, size_t elem, bool vec
     return p;
 }
 
+// Order of the two halves of the layer.  Aggregating first gathers F_in-wide rows and needs no gather at all
+// in the backward of a first layer, nor a pass over dZ of its own; transforming first gathers F_out-wide rows.
+// The layer transforms first only when the padded F_out is smaller than F_in, which also makes the caller's
+// [n, F_in] state buffer large enough for either form.
+static bool gcn_aggregates_first(int32_t F_in, int32_t F_out, int32_t dtype) { return pad_cols(F_out, dtype) >= F_in; }
+
 struct GcnBwdWorkspace {
-    size_t grad_bytes;     // Q and G, [n, Fp] each
-    size_t colsum_bytes;   // per-block column sums
+    size_t grad_bytes;     // transform first: Q and G, [n, Fp] each; aggregate first: S (dZ W^T), [n, F_in]
+    size_t colsum_bytes;   // per-block column sums (transform first)
     size_t weight_bytes;   // split partials of dW
     size_t total() const { return grad_bytes + colsum_bytes + weight_bytes; }
 };
 
-static GcnBwdWorkspace plan_gcn_bwd(int64_t n, int32_t F_in, int32_t F_out, int32_t dtype)
+static GcnBwdWorkspace plan_gcn_bwd(int64_t n, int32_t F_in, int32_t F_out, int32_t dtype, bool need_dH)
 {
     GcnBwdWorkspace w;
     const size_t rows = size_t(n > 0 ? n : 1);
-    const int Fp = pad_cols(F_out, dtype);
-    w.grad_bytes = 2 * round_up(rows * size_t(Fp) * elem_size(dtype), 256);
-    w.colsum_bytes = round_up(size_t(kColsumMaxBlocks) * size_t(Fp) * 4, 256);
+    if (gcn_aggregates_first(F_in, F_out, dtype)) {
+        w.grad_bytes = need_dH ? round_up(rows * size_t(F_in) * elem_size(dtype), 256) : 0;
+        w.colsum_bytes = 0;
+    } else {
+        const int Fp = pad_cols(F_out, dtype);
+        w.grad_bytes = 2 * round_up(rows * size_t(Fp) * elem_size(dtype), 256);
+        w.colsum_bytes = round_up(size_t(kColsumMaxBlocks) * size_t(Fp) * 4, 256);
+    }
     w.weight_bytes = dense_gemm_bwd_weight_workspace_bytes(n, F_in, F_out);
     return w;
 }
@@ -208,16 +223,15 @@ extern "C" int tma_gcn_norm(int64_t n, const int32_t *rowptr, float *s_out, tma_
     return check_launch(fn);
 }
 
-extern "C" size_t tma_gcn_layer_fwd_workspace_bytes(int64_t n, int32_t F_out, int32_t dtype)
+extern "C" int tma_gcn_layer_aggregates_first(int32_t F_in, int32_t F_out, int32_t dtype)
 {
-    if (n < 0 || F_out < 1) return 0;
-    return tma::round_up(size_t(n > 0 ? n : 1) * size_t(tma::pad_cols(F_out, dtype)) * tma::elem_size(dtype), 256);
+    return tma::gcn_aggregates_first(F_in, F_out, dtype) ? 1 : 0;
 }
 
 extern "C" int tma_gcn_layer_fwd(int64_t n, const int32_t *rowptr, const int32_t *colidx, const float *s_norm,
                                  const void *H, int64_t ldh, int32_t F_in, const float *W, const float *bias,
-                                 int32_t F_out, int32_t act, int32_t dtype, void *Hnext_out, int64_t ld_next, void *ws,
-                                 size_t ws_bytes, tma_stream_t stream)
+                                 int32_t F_out, int32_t act, int32_t dtype, void *M_out, void *Hnext_out,
+                                 int64_t ld_next, tma_stream_t stream)
 {
     using namespace tma;
     const char *fn = "tma_gcn_layer_fwd";
@@ -227,31 +241,40 @@ extern "C" int tma_gcn_layer_fwd(int64_t n, const int32_t *rowptr, const int32_t
     TMA_REQUIRE(act == TMA_ACT_NONE || act == TMA_ACT_RELU, TMA_ERR_INVALID_ARG, "%s: act %d", fn, act);
     TMA_REQUIRE(dtype == TMA_F32 || dtype == TMA_BF16, TMA_ERR_UNSUPPORTED_DTYPE, "%s: dtype %d", fn, dtype);
     if (n == 0) return TMA_OK;
-    TMA_REQUIRE(rowptr && s_norm && H && W && bias && Hnext_out, TMA_ERR_INVALID_ARG, "%s: NULL argument", fn);
+    TMA_REQUIRE(rowptr && s_norm && H && W && bias && M_out && Hnext_out, TMA_ERR_INVALID_ARG, "%s: NULL argument", fn);
     TMA_REQUIRE(ldh >= F_in && ld_next >= F_out, TMA_ERR_BAD_SHAPE, "%s: ldh < F_in or ld_next < F_out", fn);
-    TMA_REQUIRE(ws && aligned(ws, 256), TMA_ERR_INVALID_ARG, "%s: workspace NULL or not 256-byte aligned", fn);
-    const size_t need = tma_gcn_layer_fwd_workspace_bytes(n, F_out, dtype);
-    TMA_REQUIRE(ws_bytes >= need, TMA_ERR_WORKSPACE_TOO_SMALL, "%s: workspace %zu < %zu bytes", fn, ws_bytes, need);
+    TMA_REQUIRE(aligned(M_out, 16), TMA_ERR_INVALID_ARG, "%s: M_out must be 16-byte aligned", fn);
+    TMA_REQUIRE(H != M_out, TMA_ERR_INVALID_ARG, "%s: M_out must not alias H", fn);
     hipStream_t s = as_stream(stream);
-    const int Fp = pad_cols(F_out, dtype);
-    if (int rc = launch_dense_gemm_fwd(n, H, ldh, F_in, W, nullptr, s_norm, F_out, Fp, TMA_ACT_NONE, dtype, ws, Fp, s))
+    if (gcn_aggregates_first(F_in, F_out, dtype)) {
+        // M = S (A + I) S H in one pass over H: neighbours and the own row weighted by s, the sum scaled by s_v
+        if (int rc = launch_spmm_combine(n, rowptr, colidx, s_norm, H, ldh, F_in, dtype, M_out, F_in, false, H, ldh,
+                                         nullptr, F_in, false, true, s_norm, s))
+            return rc;
+        return launch_dense_gemm_fwd(n, M_out, F_in, F_in, W, bias, nullptr, F_out, F_out, act, dtype, Hnext_out, ld_next,
+                                     s);
+    }
+    const int Fp = pad_cols(F_out, dtype);   // Fp < F_in: Y = S (H W) fits into the state buffer as [n, Fp]
+    if (int rc = launch_dense_gemm_fwd(n, H, ldh, F_in, W, nullptr, s_norm, F_out, Fp, TMA_ACT_NONE, dtype, M_out, Fp, s))
         return rc;
     // whole padded rows when the output has room for them (vector path); its padding columns receive zeros
     const int F_rows = ld_next >= Fp ? Fp : F_out;
-    return launch_spmm_combine(n, rowptr, colidx, s_norm, ws, Fp, F_rows, dtype, Hnext_out, ld_next, false, ws, Fp, bias,
-                               F_out, act == TMA_ACT_RELU, true, s);
+    return launch_spmm_combine(n, rowptr, colidx, s_norm, M_out, Fp, F_rows, dtype, Hnext_out, ld_next, false, M_out, Fp,
+                               bias, F_out, act == TMA_ACT_RELU, true, nullptr, s);
 }
 
-extern "C" size_t tma_gcn_layer_bwd_workspace_bytes(int64_t n, int32_t F_in, int32_t F_out, int32_t dtype)
+extern "C" size_t tma_gcn_layer_bwd_workspace_bytes(int64_t n, int32_t F_in, int32_t F_out, int32_t dtype,
+                                                    int32_t need_dH)
 {
     if (n < 0 || F_in < 1 || F_out < 1) return 0;
-    return tma::plan_gcn_bwd(n, F_in, F_out, dtype).total();
+    return tma::plan_gcn_bwd(n, F_in, F_out, dtype, need_dH != 0).total();
 }
 
 extern "C" int tma_gcn_layer_bwd(int64_t n, const int32_t *rowptr_T, const int32_t *colidx_T, const float *s_norm,
-                                 const void *H, int64_t ldh, const void *Hnext, const void *dHnext, int64_t ld_next,
-                                 const float *W, int32_t F_in, int32_t F_out, int32_t act, int32_t dtype, float *dW,
-                                 float *dbias, void *dH_out, void *ws, size_t ws_bytes, tma_stream_t stream)
+                                 const void *H, int64_t ldh, const void *M, const void *Hnext, const void *dHnext,
+                                 int64_t ld_next, const float *W, int32_t F_in, int32_t F_out, int32_t act,
+                                 int32_t dtype, float *dW, float *dbias, void *dH_out, void *ws, size_t ws_bytes,
+                                 tma_stream_t stream)
 {
     using namespace tma;
     const char *fn = "tma_gcn_layer_bwd";
@@ -262,23 +285,39 @@ extern "C" int tma_gcn_layer_bwd(int64_t n, const int32_t *rowptr_T, const int32
     TMA_REQUIRE(dtype == TMA_F32 || dtype == TMA_BF16, TMA_ERR_UNSUPPORTED_DTYPE, "%s: dtype %d", fn, dtype);
     TMA_REQUIRE(dW && dbias, TMA_ERR_INVALID_ARG, "%s: gradient output is NULL", fn);
     TMA_REQUIRE(ws && aligned(ws, 256), TMA_ERR_INVALID_ARG, "%s: workspace NULL or not 256-byte aligned", fn);
-    const GcnBwdWorkspace w = plan_gcn_bwd(n, F_in, F_out, dtype);
+    const bool need_dH = dH_out != nullptr;
+    const bool agg_first = gcn_aggregates_first(F_in, F_out, dtype);
+    const GcnBwdWorkspace w = plan_gcn_bwd(n, F_in, F_out, dtype, need_dH);
     TMA_REQUIRE(ws_bytes >= w.total(), TMA_ERR_WORKSPACE_TOO_SMALL, "%s: workspace %zu < %zu bytes", fn, ws_bytes,
                 w.total());
     if (n > 0) {
-        TMA_REQUIRE(rowptr_T && s_norm && H && dHnext && W, TMA_ERR_INVALID_ARG, "%s: NULL argument", fn);
+        TMA_REQUIRE(s_norm && dHnext && W && (agg_first ? M != nullptr : H != nullptr), TMA_ERR_INVALID_ARG,
+                    "%s: NULL argument", fn);
         TMA_REQUIRE(act == TMA_ACT_NONE || Hnext, TMA_ERR_INVALID_ARG, "%s: Hnext is required with ReLU", fn);
+        TMA_REQUIRE((agg_first && !need_dH) || rowptr_T, TMA_ERR_INVALID_ARG, "%s: graph is NULL", fn);
         TMA_REQUIRE(ldh >= F_in && ld_next >= F_out, TMA_ERR_BAD_SHAPE, "%s: ldh < F_in or ld_next < F_out", fn);
     }
     hipStream_t s = as_stream(stream);
-    const int Fp = pad_cols(F_out, dtype);
     char *base = static_cast<char *>(ws);
+    void *wws = base + w.grad_bytes + w.colsum_bytes;
+    int rc;
+    if (agg_first) {
+        // dW = M^T dZ, db = 1^T dZ;  dH = S (A + I)^T (S dZ W^T): product with its rows scaled, then the gather
+        if ((rc = launch_dense_gemm_bwd_weight(n, M, F_in, dHnext, Hnext, ld_next, F_in, F_out, act, dtype, dW, dbias, wws,
+                                               w.weight_bytes, s)))
+            return rc;
+        if (!need_dH || n == 0) return TMA_OK;
+        void *P = base;
+        if ((rc = launch_dense_gemm_bwd_data(n, dHnext, Hnext, ld_next, W, F_in, F_out, act, dtype, s_norm, P, F_in, s)))
+            return rc;
+        return launch_spmm_combine(n, rowptr_T, colidx_T, s_norm, P, F_in, F_in, dtype, dH_out, ldh, false, P, F_in,
+                                   nullptr, F_in, false, true, nullptr, s);
+    }
+    const int Fp = pad_cols(F_out, dtype);
     void *Q = base;
     void *G = base + w.grad_bytes / 2;
     float *colsum = reinterpret_cast<float *>(base + w.grad_bytes);
-    void *wws = base + w.grad_bytes + w.colsum_bytes;
     const bool relu = act == TMA_ACT_RELU;
-    int rc;
     if (dtype == TMA_F32)
         rc = scale_mask_colsum<float>(n, F_out, Fp, static_cast<const float *>(dHnext), static_cast<const float *>(Hnext),
                                       ld_next, s_norm, relu, static_cast<float *>(Q), colsum, dbias, s);
@@ -288,12 +327,12 @@ extern "C" int tma_gcn_layer_bwd(int64_t n, const int32_t *rowptr_T, const int32
                                          static_cast<uint16_t *>(Q), colsum, dbias, s);
     if (rc) return rc;
     if ((rc = launch_spmm_combine(n, rowptr_T, colidx_T, s_norm, Q, Fp, Fp, dtype, G, Fp, false, Q, Fp, nullptr, Fp, false,
-                                  true, s)))
+                                  true, nullptr, s)))
         return rc;
     if ((rc = launch_dense_gemm_bwd_weight(n, H, ldh, G, nullptr, Fp, F_in, F_out, TMA_ACT_NONE, dtype, dW, nullptr, wws,
                                            w.weight_bytes, s)))
         return rc;
-    if (!dH_out || n == 0) return TMA_OK;
+    if (!need_dH || n == 0) return TMA_OK;
     return launch_dense_gemm_bwd_data(n, G, nullptr, Fp, W, F_in, F_out, TMA_ACT_NONE, dtype, nullptr, dH_out, ldh, s);
 }
 

@@ -13,10 +13,11 @@ int launch_spmm(int64_t n, const int32_t *rowptr, const int32_t *colidx, const f
 
 // Same gather with the layer epilogue fused: out_v = act(scale_v * sum + [out_v] + self_v + bias), or, with
 // scale_all, out_v = act(scale_v * (sum + [out_v] + self_v) + bias) (the GCN form, self inside the normalisation).
+// edge_scale (may be NULL): neighbour u enters the sum as edge_scale[u] * in_u and self_v as edge_scale[v] * self_v.
 int launch_spmm_combine(int64_t n, const int32_t *rowptr, const int32_t *colidx, const float *inv_deg, const void *in,
                         int64_t ld_in, int32_t F, int32_t dtype, void *out, int64_t ld_out, bool accumulate,
                         const void *self, int64_t ld_self, const float *bias, int32_t F_valid, bool relu,
-                        bool scale_all, hipStream_t stream);
+                        bool scale_all, const float *edge_scale, hipStream_t stream);
 
 // dst_v = inv_deg[v] * g_v (.) [h_v > 0]  (mask only with relu); columns F..F_pad-1 of dst are zeroed.
 int launch_scale_mask_rows(int64_t n, int32_t F, int32_t F_pad, const void *g, const void *h, int64_t ld,

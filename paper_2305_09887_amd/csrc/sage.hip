@@ -68,9 +68,9 @@ extern "C" int tma_sage_layer_fwd(int64_t n, const int32_t *rowptr, const int32_
     if (int rc = launch_sage_tf_gemm_fwd(n, H, ldh, F_in, W_self, W_neigh, F_out, dtype, Ys, Yn, Fp, s)) return rc;
     if (ld_next >= Fp)   // whole padded rows (vector path); the padding columns of Hnext receive zeros
         return launch_spmm_combine(n, rowptr, colidx, inv_deg, Yn, Fp, Fp, dtype, Hnext_out, ld_next, false, Ys, Fp,
-                                   bias, F_out, act == TMA_ACT_RELU, false, s);
+                                   bias, F_out, act == TMA_ACT_RELU, false, nullptr, s);
     return launch_spmm_combine(n, rowptr, colidx, inv_deg, Yn, Fp, F_out, dtype, Hnext_out, ld_next, false, Ys, Fp,
-                               bias, F_out, act == TMA_ACT_RELU, false, s);
+                               bias, F_out, act == TMA_ACT_RELU, false, nullptr, s);
 }
 
 extern "C" int tma_sage_layer_aggregates_first(int32_t F_in, int32_t F_out, int32_t dtype)

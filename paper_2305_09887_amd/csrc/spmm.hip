@@ -38,13 +38,17 @@ __device__ __forceinline__ void store_elem(uint16_t *p, float v) { *p = f32_to_b
 // U neighbour rows (entries j .. j+U-1 of the run whose ids sit in `mine`) fetched together, then added in order.
 template <typename T, int G, int CPL, int U>
 __device__ __forceinline__ void gather_batch(const T *__restrict__ in, int64_t ld, int32_t mine, int j, int sub,
-                                             int n_chunks, float (&acc)[CPL][Chunk<T>::kElems])
+                                             int n_chunks, const float *__restrict__ edge_scale,
+                                             float (&acc)[CPL][Chunk<T>::kElems])
 {
     constexpr int E = Chunk<T>::kElems;
     float v[U][CPL][E];
+    float w[U];
 #pragma unroll
     for (int q = 0; q < U; ++q) {
-        const T *row = in + int64_t(__shfl(mine, j + q, G)) * ld;
+        const int32_t id = __shfl(mine, j + q, G);
+        w[q] = edge_scale ? edge_scale[id] : 1.0f;
+        const T *row = in + int64_t(id) * ld;
 #pragma unroll
         for (int c = 0; c < CPL; ++c)
             if (sub + c * G < n_chunks) Chunk<T>::load(row + (sub + c * G) * E, v[q][c]);
@@ -55,7 +59,7 @@ __device__ __forceinline__ void gather_batch(const T *__restrict__ in, int64_t l
         for (int c = 0; c < CPL; ++c)
             if (sub + c * G < n_chunks)
 #pragma unroll
-                for (int i = 0; i < E; ++i) acc[c][i] += v[q][c][i];
+                for (int i = 0; i < E; ++i) acc[c][i] += edge_scale ? w[q] * v[q][c][i] : v[q][c][i];
 }
 
 // Adds the rows colidx[e] for e = beg, beg+1, ... in runs of G entries that start
@@ -65,6 +69,7 @@ __device__ __forceinline__ void gather_batch(const T *__restrict__ in, int64_t l
 template <typename T, int G, int CPL, bool kDeep>
 __device__ __forceinline__ void gather_sum(const T *__restrict__ in, int64_t ld, const int32_t *__restrict__ colidx,
                                            int32_t beg, int32_t end, int32_t run_stride, int sub, int n_chunks,
+                                           const float *__restrict__ edge_scale,
                                            float (&acc)[CPL][Chunk<T>::kElems])
 {
     for (int32_t e0 = beg; e0 < end; e0 += run_stride) {
@@ -72,15 +77,17 @@ __device__ __forceinline__ void gather_sum(const T *__restrict__ in, int64_t ld,
         const int32_t mine = sub < cnt ? colidx[e0 + sub] : 0;
         int j = 0;
         if constexpr (kDeep && CPL == 1 && G >= 16)
-            for (; j + 16 <= cnt; j += 16) gather_batch<T, G, CPL, 16>(in, ld, mine, j, sub, n_chunks, acc);
-        for (; j + 4 <= cnt; j += 4) gather_batch<T, G, CPL, 4>(in, ld, mine, j, sub, n_chunks, acc);
-        for (; j < cnt; ++j) gather_batch<T, G, CPL, 1>(in, ld, mine, j, sub, n_chunks, acc);
+            for (; j + 16 <= cnt; j += 16) gather_batch<T, G, CPL, 16>(in, ld, mine, j, sub, n_chunks, edge_scale, acc);
+        for (; j + 4 <= cnt; j += 4) gather_batch<T, G, CPL, 4>(in, ld, mine, j, sub, n_chunks, edge_scale, acc);
+        for (; j < cnt; ++j) gather_batch<T, G, CPL, 1>(in, ld, mine, j, sub, n_chunks, edge_scale, acc);
     }
 }
 
 // What happens to a finished row sum s_v:
 //   out_v = act( scale_v * s_v  [+ out_v]  [+ self_v]  [+ bias] )
 //   out_v = act( scale_v * (s_v  [+ out_v]  [+ self_v])  [+ bias] )      with scale_all
+// With edge_scale the sum is s_v = sum_u edge_scale[u] in_u and self_v stands for edge_scale[v] self_v
+// (GCN aggregation S (A + I) S H in one pass over the unscaled H).
 // scale_v = inv_deg[v] (mean) or 1; "+ out_v" accumulates onto what is there (backward: on top of
 // dZ W_self^T); "+ self_v + bias" and the activation turn the gather into the layer output when the
 // transform ran before the aggregation.
@@ -96,6 +103,7 @@ struct SpmmOut {
     int F;  // valid elements of a row (bias is not applied to padding)
     int relu;
     int scale_all;  // the scale multiplies the sum with "+ out_v" / "+ self_v" already added (GCN: s_v (sum + self_v))
+    const float *edge_scale;  // neighbour u enters the sum as edge_scale[u] * in_u, and self_v as edge_scale[v] * self_v
 };
 
 template <typename T, int G, int CPL>
@@ -121,8 +129,9 @@ __device__ __forceinline__ void finish_row(int64_t v, const SpmmOut<T> &o, int s
             if (o.self) {
                 float sv[E];
                 Chunk<T>::load(o.self + v * o.ld_self + f0, sv);
+                const float ws = o.edge_scale ? o.edge_scale[v] : 1.0f;
 #pragma unroll
-                for (int i = 0; i < E; ++i) r[i] += sv[i];
+                for (int i = 0; i < E; ++i) r[i] += ws * sv[i];
             }
             if (o.scale_all) {
 #pragma unroll
@@ -166,20 +175,24 @@ __device__ __forceinline__ void issue_ids(const int32_t *__restrict__ ids, int32
     for (int q = 0; q < U; ++q) I[q] = ids[s.lo + q < s.hi ? s.lo + q : filler];
 }
 
-template <typename T, int U>
-__device__ __forceinline__ void issue_gathers(const T *__restrict__ in, int64_t ld, const Step &s,
-                                              const int32_t (&I)[U], int32_t &recent, int sub, uint4 (&V)[U])
+// kEdge: every neighbour row comes with a weight edge_scale[id], fetched next to the row
+template <typename T, int U, bool kEdge>
+__device__ __forceinline__ void issue_gathers(const T *__restrict__ in, int64_t ld, const float *__restrict__ edge_scale,
+                                              const Step &s, const int32_t (&I)[U], int32_t &recent, int sub,
+                                              uint4 (&V)[U], float (&Wt)[U])
 {
     constexpr int E = Chunk<T>::kElems;
 #pragma unroll
     for (int q = 0; q < U; ++q) {
         recent = s.lo + q < s.hi ? I[q] : recent;   // unused slot: a row this group fetched a moment ago
         V[q] = *reinterpret_cast<const uint4 *>(in + int64_t(recent) * ld + sub * E);
+        if constexpr (kEdge) Wt[q] = edge_scale[recent];
     }
 }
 
-template <typename T, int U>
-__device__ __forceinline__ void consume(const Step &s, const uint4 (&V)[U], float (&acc)[Chunk<T>::kElems])
+template <typename T, int U, bool kEdge>
+__device__ __forceinline__ void consume(const Step &s, const uint4 (&V)[U], const float (&Wt)[U],
+                                        float (&acc)[Chunk<T>::kElems])
 {
     constexpr int E = Chunk<T>::kElems;
 #pragma unroll
@@ -188,7 +201,7 @@ __device__ __forceinline__ void consume(const Step &s, const uint4 (&V)[U], floa
         Chunk<T>::widen(V[q], v);
         const bool used = s.lo + q < s.hi;
 #pragma unroll
-        for (int i = 0; i < E; ++i) acc[i] += used ? v[i] : 0.0f;
+        for (int i = 0; i < E; ++i) acc[i] += used ? (kEdge ? Wt[q] * v[i] : v[i]) : 0.0f;
     }
 }
 
@@ -200,15 +213,16 @@ struct RowExtra {
 
 // Runs the steps that `gen` hands out through the ids -> gathers -> additions pipeline.  `extra(seg, X)`
 // issues the loads a closing step needs (or nothing); `emit(seg, acc, X)` takes a finished segment.
-template <typename T, typename Gen, typename Extra, typename Emit>
+template <typename T, bool kEdge, typename Gen, typename Extra, typename Emit>
 __device__ __forceinline__ void stream_segments(const T *__restrict__ in, int64_t ld, const int32_t *__restrict__ ids,
-                                                int32_t last_entry, int sub, int32_t recent, Gen &&gen, Extra &&extra,
-                                                Emit &&emit)
+                                                const float *__restrict__ edge_scale, int32_t last_entry, int sub,
+                                                int32_t recent, Gen &&gen, Extra &&extra, Emit &&emit)
 {
     constexpr int E = Chunk<T>::kElems;
     constexpr int U = kStreamU;
     int32_t I0[U], I1[U];
     uint4 V0[U], V1[U];
+    float W0[U], W1[U];
     RowExtra X0, X1;
     float acc[E];
 #pragma unroll
@@ -218,16 +232,16 @@ __device__ __forceinline__ void stream_segments(const T *__restrict__ in, int64_
     issue_ids<U>(ids, last_entry, a, I0);
     Step b = gen();
     issue_ids<U>(ids, last_entry, b, I1);
-    issue_gathers<T, U>(in, ld, a, I0, recent, sub, V0);
+    issue_gathers<T, U, kEdge>(in, ld, edge_scale, a, I0, recent, sub, V0, W0);
     extra(a.seg, X0);
     // entering a half: step a has its gathers in flight (V0/X0 in the first half), step b its ids (I1)
-    auto half = [&](int32_t (&Ia)[U], int32_t (&Ib)[U], uint4 (&Va)[U], uint4 (&Vb)[U], RowExtra &Xa,
-                    RowExtra &Xb) __attribute__((always_inline)) {
+    auto half = [&](int32_t (&Ia)[U], int32_t (&Ib)[U], uint4 (&Va)[U], uint4 (&Vb)[U], float (&Wa)[U],
+                    float (&Wb)[U], RowExtra &Xa, RowExtra &Xb) __attribute__((always_inline)) {
         const Step c = gen();
         issue_ids<U>(ids, last_entry, c, Ia);
-        issue_gathers<T, U>(in, ld, b, Ib, recent, sub, Vb);
+        issue_gathers<T, U, kEdge>(in, ld, edge_scale, b, Ib, recent, sub, Vb, Wb);
         extra(b.seg, Xb);
-        consume<T, U>(a, Va, acc);
+        consume<T, U, kEdge>(a, Va, Wa, acc);
         if (a.last) {
             emit(a.seg, acc, Xa);
 #pragma unroll
@@ -237,14 +251,15 @@ __device__ __forceinline__ void stream_segments(const T *__restrict__ in, int64_
         b = c;
     };
     while (a.seg >= 0) {
-        half(I0, I1, V0, V1, X0, X1);
+        half(I0, I1, V0, V1, W0, W1, X0, X1);
         if (a.seg < 0) break;
-        half(I1, I0, V1, V0, X1, X0);
+        half(I1, I0, V1, V0, W1, W0, X1, X0);
     }
 }
 
 // kExtra: 0 = nothing, 1 = "+ self_v", 2 = "+ out_v" (accumulate).  kScale: multiply by inv_deg[v].
-template <typename T, int kExtra, bool kScale>
+// kEdge: weighted neighbours (and self row), see SpmmOut::edge_scale.
+template <typename T, int kExtra, bool kScale, bool kEdge = false>
 __global__ __launch_bounds__(kSpmmThreads) void spmm_stream_kernel(int64_t n, const int32_t *__restrict__ rowptr,
                                                                    const int32_t *__restrict__ colidx,
                                                                    const T *__restrict__ in, int64_t ld_in,
@@ -326,7 +341,7 @@ __global__ __launch_bounds__(kSpmmThreads) void spmm_stream_kernel(int64_t n, co
             float x[E];
             Chunk<T>::widen(X.raw, x);
 #pragma unroll
-            for (int i = 0; i < E; ++i) res[i] += x[i];
+            for (int i = 0; i < E; ++i) res[i] += (kEdge && kExtra == 1) ? X.scale * x[i] : x[i];
         }
         if (kScale && o.scale_all) {
 #pragma unroll
@@ -342,7 +357,8 @@ __global__ __launch_bounds__(kSpmmThreads) void spmm_stream_kernel(int64_t n, co
         }
         Chunk<T>::store(o.out + v * o.ld_out + f0, res);
     };
-    stream_segments<T>(in, ld_in, ids, last_entry, sub, int32_t(base + r_first), next_row_step, row_extra, finish);
+    stream_segments<T, kEdge>(in, ld_in, ids, o.edge_scale, last_entry, sub, int32_t(base + r_first), next_row_step,
+                              row_extra, finish);
     __syncthreads();
 
     // ---- deferred rows, kHubsPerPass at a time: group g sums the g-th share of each, then a fixed-order combine
@@ -382,8 +398,8 @@ __global__ __launch_bounds__(kSpmmThreads) void spmm_stream_kernel(int64_t n, co
 #pragma unroll
                 for (int i = 0; i < E; ++i) partial[(seg * NG + grp) * width + sub * E + i] = acc[i];
             };
-            stream_segments<T>(in, ld_in, ids, last_entry, sub, int32_t(base + r_first), next_share_step, no_extra,
-                               to_lds);
+            stream_segments<T, kEdge>(in, ld_in, ids, o.edge_scale, last_entry, sub, int32_t(base + r_first),
+                                      next_share_step, no_extra, to_lds);
         }
         __syncthreads();
         if (live && grp < h_end - h0) {
@@ -440,7 +456,7 @@ __global__ __launch_bounds__(kSpmmThreads) void spmm_rows_kernel(int64_t n, cons
         for (int c = 0; c < CPL; ++c)
 #pragma unroll
             for (int k = 0; k < E; ++k) acc[c][k] = 0.0f;
-        gather_sum<T, G, CPL, false>(in, ld_in, colidx, beg, end, G, sub, n_chunks, acc);
+        gather_sum<T, G, CPL, false>(in, ld_in, colidx, beg, end, G, sub, n_chunks, o.edge_scale, acc);
         finish_row<T, G, CPL>(v, o, sub, n_chunks, acc);
     }
     __syncthreads();
@@ -454,7 +470,7 @@ __global__ __launch_bounds__(kSpmmThreads) void spmm_rows_kernel(int64_t n, cons
         for (int c = 0; c < CPL; ++c)
 #pragma unroll
             for (int k = 0; k < E; ++k) acc[c][k] = 0.0f;
-        if (beg + grp * G < end) gather_sum<T, G, CPL, true>(in, ld_in, colidx, beg + grp * G, end, NG * G, sub, n_chunks, acc);
+        if (beg + grp * G < end) gather_sum<T, G, CPL, true>(in, ld_in, colidx, beg + grp * G, end, NG * G, sub, n_chunks, o.edge_scale, acc);
 #pragma unroll
         for (int c = 0; c < CPL; ++c)
 #pragma unroll
@@ -493,11 +509,13 @@ __global__ __launch_bounds__(kSpmmThreads) void spmm_rows_generic_kernel(int64_t
 #pragma unroll
         for (int k = 0; k < kPer; ++k) acc[k] = 0.0f;
         for (int32_t e = beg; e < end; ++e) {
-            const T *row = in + int64_t(colidx[e]) * ld_in;
+            const int32_t u = colidx[e];
+            const T *row = in + int64_t(u) * ld_in;
+            const float w = o.edge_scale ? o.edge_scale[u] : 1.0f;
 #pragma unroll
             for (int k = 0; k < kPer; ++k) {
                 const int f = f0 + k * kWave + lane;
-                if (f < F) acc[k] += load_elem(row + f);
+                if (f < F) acc[k] += w * load_elem(row + f);
             }
         }
 #pragma unroll
@@ -507,7 +525,7 @@ __global__ __launch_bounds__(kSpmmThreads) void spmm_rows_generic_kernel(int64_t
                 T *dst = o.out + v * o.ld_out + f;
                 float r = o.scale_all ? acc[k] : acc[k] * scale;
                 if (o.accumulate) r += load_elem(dst);
-                if (o.self) r += load_elem(o.self + v * o.ld_self + f);
+                if (o.self) r += (o.edge_scale ? o.edge_scale[v] : 1.0f) * load_elem(o.self + v * o.ld_self + f);
                 if (o.scale_all) r *= scale;
                 if (o.bias && f < o.F) r += o.bias[f];
                 if (o.relu) r = r > 0.0f ? r : 0.0f;
@@ -530,7 +548,7 @@ static void launch_wide_rows(int64_t n, const int32_t *rowptr, const int32_t *co
                        rowptr, colidx, in, ld_in, o, n_chunks);
 }
 
-template <typename T, int kExtra, bool kScale>
+template <typename T, int kExtra, bool kScale, bool kEdge = false>
 static void launch_stream(int64_t n, const int32_t *rowptr, const int32_t *colidx, const T *in, int64_t ld_in,
                           const SpmmOut<T> &o, int G, hipStream_t s)
 {
@@ -541,10 +559,11 @@ static void launch_stream(int64_t n, const int32_t *rowptr, const int32_t *colid
     rpg = rpg < 4 ? 4 : (rpg > 8 ? 8 : rpg);
     if (rpg * NG > kMaxRowsPerBlock) rpg = kMaxRowsPerBlock / NG;
     char name[48];
-    snprintf(name, sizeof(name), "%s_%s_g%dx1", kExtra == 1 ? "spmm_combine" : (kScale ? "spmm_mean" : "spmm_sum"),
+    snprintf(name, sizeof(name), "%s_%s_g%dx1",
+             kEdge ? "spmm_weighted" : (kExtra == 1 ? "spmm_combine" : (kScale ? "spmm_mean" : "spmm_sum")),
              sizeof(T) == 4 ? "f32" : "bf16", G);
     TMA_TIMED(name, s);
-    hipLaunchKernelGGL((spmm_stream_kernel<T, kExtra, kScale>), dim3(unsigned(ceil_div(n, rpg * NG))),
+    hipLaunchKernelGGL((spmm_stream_kernel<T, kExtra, kScale, kEdge>), dim3(unsigned(ceil_div(n, rpg * NG))),
                        dim3(kSpmmThreads), 0, s, n, rowptr, colidx, in, ld_in, o, G, int(rpg), kMinDefer);
 }
 
@@ -557,7 +576,9 @@ static int launch_typed(int64_t n, const int32_t *rowptr, const int32_t *colidx,
                         (size_t(o.ld_out) * sizeof(T)) % 16 == 0 && aligned(in, 16) && aligned(o.out, 16) &&
                         (!o.self || ((size_t(o.ld_self) * sizeof(T)) % 16 == 0 && aligned(o.self, 16))) &&
                         row_bytes / 16 <= 256 && !(o.self && o.accumulate);
-    if (!vec_ok) {
+    // the streaming kernel's weighted form takes the self weight from the row scale it already holds
+    const bool edge_stream = o.edge_scale && o.self && o.inv_deg == o.edge_scale;
+    if (!vec_ok || (o.edge_scale && !edge_stream && row_bytes / 16 <= 64)) {
         TMA_TIMED(o.self ? "spmm_combine_generic" : (o.inv_deg ? "spmm_mean_generic" : "spmm_sum_generic"), s);
         hipLaunchKernelGGL((spmm_rows_generic_kernel<T>), dim3(unsigned(ceil_div(n, kSpmmThreads / kWave))),
                            dim3(kSpmmThreads), 0, s, n, rowptr, colidx, in, ld_in, o, F);
@@ -567,7 +588,9 @@ static int launch_typed(int64_t n, const int32_t *rowptr, const int32_t *colidx,
     if (nc <= 64) {
         const int extra = o.self ? 1 : (o.accumulate ? 2 : 0);
 #define TMA_SPMM_STREAM(X, S) launch_stream<T, X, S>(n, rowptr, colidx, in, ld_in, o, nc, s)
-        if (o.inv_deg) {
+        if (o.edge_scale) {
+            launch_stream<T, 1, true, true>(n, rowptr, colidx, in, ld_in, o, nc, s);
+        } else if (o.inv_deg) {
             if (extra == 0) TMA_SPMM_STREAM(0, true);
             else if (extra == 1) TMA_SPMM_STREAM(1, true);
             else TMA_SPMM_STREAM(2, true);
@@ -588,10 +611,11 @@ static int launch_typed(int64_t n, const int32_t *rowptr, const int32_t *colidx,
 template <typename T>
 static int spmm_any(int64_t n, const int32_t *rowptr, const int32_t *colidx, const float *inv_deg, const void *in,
                     int64_t ld_in, int32_t F, void *out, int64_t ld_out, bool accumulate, const void *self,
-                    int64_t ld_self, const float *bias, int32_t F_valid, bool relu, bool scale_all, hipStream_t stream)
+                    int64_t ld_self, const float *bias, int32_t F_valid, bool relu, bool scale_all,
+                    const float *edge_scale, hipStream_t stream)
 {
     SpmmOut<T> o{static_cast<T *>(out), ld_out, inv_deg, accumulate ? 1 : 0, static_cast<const T *>(self), ld_self,
-                 bias, F_valid, relu ? 1 : 0, (scale_all && inv_deg) ? 1 : 0};
+                 bias, F_valid, relu ? 1 : 0, (scale_all && inv_deg) ? 1 : 0, edge_scale};
     return launch_typed<T>(n, rowptr, colidx, static_cast<const T *>(in), ld_in, F, o, stream);
 }
 
@@ -600,21 +624,21 @@ int launch_spmm(int64_t n, const int32_t *rowptr, const int32_t *colidx, const f
                 hipStream_t stream)
 {
     return launch_spmm_combine(n, rowptr, colidx, inv_deg, in, ld_in, F, dtype, out, ld_out, accumulate, nullptr, 0,
-                               nullptr, F, false, false, stream);
+                               nullptr, F, false, false, nullptr, stream);
 }
 
 int launch_spmm_combine(int64_t n, const int32_t *rowptr, const int32_t *colidx, const float *inv_deg, const void *in,
                         int64_t ld_in, int32_t F, int32_t dtype, void *out, int64_t ld_out, bool accumulate,
                         const void *self, int64_t ld_self, const float *bias, int32_t F_valid, bool relu,
-                        bool scale_all, hipStream_t stream)
+                        bool scale_all, const float *edge_scale, hipStream_t stream)
 {
     if (n == 0 || F == 0) return TMA_OK;
     if (dtype == TMA_F32)
         return spmm_any<float>(n, rowptr, colidx, inv_deg, in, ld_in, F, out, ld_out, accumulate, self, ld_self, bias,
-                               F_valid, relu, scale_all, stream);
+                               F_valid, relu, scale_all, edge_scale, stream);
     if (dtype == TMA_BF16)
         return spmm_any<uint16_t>(n, rowptr, colidx, inv_deg, in, ld_in, F, out, ld_out, accumulate, self, ld_self,
-                                  bias, F_valid, relu, scale_all, stream);
+                                  bias, F_valid, relu, scale_all, edge_scale, stream);
     return fail(TMA_ERR_UNSUPPORTED_DTYPE, "spmm: dtype %d", dtype);
 }
 

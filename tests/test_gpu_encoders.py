@@ -150,16 +150,18 @@ def test_gcn_layer_fp32(B, Fi, Fo, act):
     rpd, cid = dev(rp), dev(ci)
     s = B.tma_gcn_norm(rpd)
     Hd, gd = padded(B, H), padded(B, g)
-    Hn = B.tma_gcn_layer_fwd(rpd, cid, s, Hd, dev(W), dev(b), act)
+    Mg, Hn = B.tma_gcn_layer_fwd(rpd, cid, s, Hd, dev(W), dev(b), act)
     M, Z, want = oracle.gcn_layer_fwd(rp, ci, H, W, b, act)
     close(host(Hn), want, 1e-4, "Hnext")
-    dW, db, dH = B.tma_gcn_layer_bwd(rpd, cid, s, Hd, Hn, gd, dev(W), act)
+    if B.tma_gcn_layer_aggregates_first(Fi, Fo, B.TMA_F32):
+        close(host(Mg), M, 1e-4, "M = Ahat H")
+    dW, db, dH = B.tma_gcn_layer_bwd(rpd, cid, s, Hd, Mg, Hn, gd, dev(W), act)
     Zs = np.where(host(Hn) > 0, 1.0, -1.0) if act == 1 else Z
     wW, wb, wH = oracle.gcn_layer_bwd(rp, ci, M, Zs, g, W, act)
     close(host(dW), wW, 1e-4, "dW")
     close(host(db), wb, 1e-4, "db")
     close(host(dH), wH, 1e-4, "dH")
-    dW2, db2, dH2 = B.tma_gcn_layer_bwd(rpd, cid, s, Hd, Hn, gd, dev(W), act, need_dH=False)
+    dW2, db2, dH2 = B.tma_gcn_layer_bwd(rpd, cid, s, Hd, Mg, Hn, gd, dev(W), act, need_dH=False)
     assert dH2 is None and torch.equal(dW2, dW) and torch.equal(db2, db)     # run to run: the same bits
 
 
@@ -172,10 +174,10 @@ def test_gcn_layer_bf16(B, Fi, Fo):
     rpd, cid = dev(rp), dev(ci)
     s = B.tma_gcn_norm(rpd)
     Hd, gd = padded(B, H, True), padded(B, g, True)
-    Hn = B.tma_gcn_layer_fwd(rpd, cid, s, Hd, dev(W), dev(b), 1)
+    Mg, Hn = B.tma_gcn_layer_fwd(rpd, cid, s, Hd, dev(W), dev(b), 1)
     M, Z, want = oracle.gcn_layer_fwd(rp, ci, H, W, b, 1)
     close(host(Hn), want, 2e-2, "Hnext")
-    dW, db, dH = B.tma_gcn_layer_bwd(rpd, cid, s, Hd, Hn, gd, dev(W), 1)
+    dW, db, dH = B.tma_gcn_layer_bwd(rpd, cid, s, Hd, Mg, Hn, gd, dev(W), 1)
     wW, wb, wH = oracle.gcn_layer_bwd(rp, ci, M, np.where(host(Hn) > 0, 1.0, -1.0), g, W, 1)
     close(host(dW), wW, 2e-2, "dW")
     close(host(db), wb, 2e-2, "db")
@@ -184,8 +186,24 @@ def test_gcn_layer_bf16(B, Fi, Fo):
 
 def test_gcn_layer_directed_entries_and_empty(B):
     # a non-symmetric entry list: the backward takes the transposed CSR
+    _directed_case(B, 32, 24)      # transforms first
+    _directed_case(B, 24, 40)      # aggregates first
+    W, b = dev(np.ones((32, 24), np.float32)), dev(np.zeros(24, np.float32))
+    Fi, Fo = 32, 24
+    # no nodes at all
+    rp0 = dev(np.zeros(1, np.int32))
+    ci0 = torch.empty(0, dtype=torch.int32, device="cuda")
+    s0 = torch.empty(0, device="cuda")
+    H0 = torch.empty((0, Fi), device="cuda")
+    assert B.tma_gcn_layer_fwd(rp0, ci0, s0, H0, W, b, 1)[1].shape == (0, Fo)
+    dW, db, dH = B.tma_gcn_layer_bwd(rp0, ci0, s0, H0, H0, torch.empty((0, Fo), device="cuda"),
+                                     torch.empty((0, Fo), device="cuda"), W, 1)
+    assert not dW.any() and not db.any() and dH.shape == (0, Fi)
+
+
+def _directed_case(B, Fi, Fo):
     rng = np.random.default_rng(4)
-    n, nnz, Fi, Fo = 3000, 9000, 32, 24
+    n, nnz = 3000, 9000
     u, v = rng.integers(0, n, nnz), rng.integers(0, n, nnz)
     order = np.lexsort((v, u))
     rp = np.zeros(n + 1, np.int32)
@@ -200,23 +218,14 @@ def test_gcn_layer_directed_entries_and_empty(B):
     H, W, b, g = _layer_inputs(n, Fi, Fo, seed=2)
     s = B.tma_gcn_norm(dev(rp))
     Hd, gd = padded(B, H), padded(B, g)
-    Hn = B.tma_gcn_layer_fwd(dev(rp), dev(ci), s, Hd, dev(W), dev(b), 0)
+    Mg, Hn = B.tma_gcn_layer_fwd(dev(rp), dev(ci), s, Hd, dev(W), dev(b), 0)
     M, Z, want = oracle.gcn_layer_fwd(rp, ci, H, W, b, 0)
     close(host(Hn), want, 1e-4, "Hnext (directed)")
-    dW, db, dH = B.tma_gcn_layer_bwd(dev(rpt), dev(cit), s, Hd, None, gd, dev(W), 0)
+    dW, db, dH = B.tma_gcn_layer_bwd(dev(rpt), dev(cit), s, Hd, Mg, None, gd, dev(W), 0)
     wW, wb, wH = oracle.gcn_layer_bwd(rp, ci, M, Z, g, W, 0)
     close(host(dW), wW, 1e-4, "dW (directed)")
     close(host(dH), wH, 1e-4, "dH (directed)")
     close(host(db), wb, 1e-4, "db (directed)")
-    # no nodes at all
-    rp0 = dev(np.zeros(1, np.int32))
-    ci0 = torch.empty(0, dtype=torch.int32, device="cuda")
-    s0 = torch.empty(0, device="cuda")
-    H0 = torch.empty((0, Fi), device="cuda")
-    assert B.tma_gcn_layer_fwd(rp0, ci0, s0, H0, dev(W), dev(b), 1).shape == (0, Fo)
-    dW, db, dH = B.tma_gcn_layer_bwd(rp0, ci0, s0, H0, torch.empty((0, Fo), device="cuda"),
-                                     torch.empty((0, Fo), device="cuda"), dev(W), 1)
-    assert not dW.any() and not db.any() and dH.shape == (0, Fi)
 
 
 def test_row_padding_is_never_multiplied(B):
@@ -241,5 +250,50 @@ def test_row_padding_is_never_multiplied(B):
     want = oracle.sage_layer_fwd(rp, ci, H, W, Wn, b, 0)[2]
     close(host(Hn), want, 2e-2, "SAGE Hnext")
     s = B.tma_gcn_norm(dev(rp))
-    Hg = B.tma_gcn_layer_fwd(dev(rp), dev(ci), s, Hd, dev(W), dev(b), 0)
+    Hg = B.tma_gcn_layer_fwd(dev(rp), dev(ci), s, Hd, dev(W), dev(b), 0)[1]
     close(host(Hg), oracle.gcn_layer_fwd(rp, ci, H, W, b, 0)[2], 2e-2, "GCN Hnext")
+
+
+@pytest.mark.parametrize("encoder", ["gcn", "mlp"])
+@pytest.mark.parametrize("norm_act", [False, True])
+@pytest.mark.parametrize("optimizer", ["sgd", "adam"])
+def test_training_steps_with_other_encoders(B, encoder, norm_act, optimizer):
+    """Three steps of a 3-layer model (64-96-64-16) on the tiny configuration's part 0: losses, every gradient
+    and the weights after each step against the oracle's trainer."""
+    from oracle import model as omodel
+    from paper_2305_09887_amd.trainer import LocalTrainer
+    N, K, dims = 20_000, 4, [64, 96, 64, 16]
+    rowptr, colidx = synth.uniform_graph(N, 100_000, seed=1)
+    X, y = synth.features(N, dims[0], seed=2), synth.labels(N, dims[-1], seed=3)
+    rng = np.random.default_rng(7)
+    params = []
+    for l, (Ws, _, b) in enumerate(synth.sage_params(dims, seed=5)):
+        layer = [Ws, b]
+        if norm_act and l < len(dims) - 2:
+            layer += [rng.normal(1.0, 0.1, dims[l + 1]).astype(np.float32),
+                      rng.normal(0.0, 0.1, dims[l + 1]).astype(np.float32), np.array([0.25], dtype=np.float32)]
+        params.append(tuple(layer))
+    sub = oracle.induced_subgraph(rowptr, colidx, oracle.partition(N, K, seed=4), 0)
+    Xo, yo = X[sub["l2g"]], y[sub["l2g"]]
+    tr = LocalTrainer(dev(sub["rowptr"]), dev(sub["colidx"]), dev(sub["inv_deg"], torch.float32), dev(Xo), dev(yo),
+                      dims, params=params, norm_act=norm_act, optimizer=optimizer, encoder=encoder)
+    p_o = [tuple(np.asarray(t, dtype=np.float64) for t in l) for l in params]
+    assert tr.n_params == omodel.flatten(p_o).size
+    lr = 0.05 if optimizer == "sgd" else 0.01
+    state, losses = None, []
+    for step in range(3):
+        loss_g = tr.step(lr).item()
+        open_ = [host(tr.H[1]) > 0, host(tr.H[2]) > 0, None]
+        loss_o, grads_o, _, _ = omodel.loss_and_grads(sub["rowptr"], sub["colidx"], Xo, yo, p_o, open_, encoder)
+        assert abs(loss_g - loss_o) <= 1e-4 * abs(loss_o), f"loss at step {step}"
+        for l in range(3):
+            for i, (g, w) in enumerate(zip(tr.grads[l], grads_o[l])):
+                close(host(g).ravel(), np.asarray(w).ravel(), 1e-4, f"step {step} layer {l} gradient {i}")
+        if optimizer == "sgd":
+            _, p_o = omodel.train_step(sub["rowptr"], sub["colidx"], Xo, yo, p_o, lr, open_, encoder)
+        else:
+            _, p_o, state = omodel.train_step_adam(sub["rowptr"], sub["colidx"], Xo, yo, p_o, lr, state, step + 1, open_,
+                                                   encoder)
+        close(host(tr.W), omodel.flatten(p_o), 1e-4, f"weights after step {step}")
+        losses.append(loss_g)
+    assert losses[2] < losses[0]
