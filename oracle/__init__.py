@@ -39,6 +39,7 @@ def lib():
         _lib.orc_mix64.argtypes = [C.c_uint64, C.c_uint64]
         _lib.orc_softmax_ce.restype = C.c_double
         _lib.orc_sigmoid_l2.restype = C.c_double
+        _lib.orc_bce_logits.restype = C.c_double
     return _lib
 
 
@@ -303,3 +304,58 @@ def average(W_stack, active_mask: int | None = None):
     Wg = np.zeros(P)
     lib().orc_average(C.c_int32(M), C.c_int64(P), C.c_uint64(active_mask), _p(W), _p(Wg))
     return W, Wg
+
+
+# ------------------------------------------------ link-prediction head (Sec. 4.1, App.)
+def edge_batch(rowptr, colidx, seed: int, first_counter: int, B: int):
+    """B positive edges (u, v) and one negative tail v' each, from the counter-based spec; int32 arrays."""
+    rowptr, colidx = _i32(rowptr), _i32(colidx)
+    n = rowptr.shape[0] - 1
+    assert B == 0 or (rowptr[-1] > 0 and n > 1)
+    u, v, vn = (np.empty(B, dtype=np.int32) for _ in range(3))
+    lib().orc_edge_batch(C.c_int64(n), _p(rowptr), _p(colidx), C.c_uint64(seed), C.c_uint64(first_counter),
+                         C.c_int64(B), _p(u), _p(v), _p(vn))
+    return u, v, vn
+
+
+def pair_product_fwd(R, u, v, vneg) -> np.ndarray:
+    """E0 [2B, F]: r_u (.) r_v for the positives, then r_u (.) r_v' for the negatives."""
+    R, u, v, vneg = _f64(R), _i32(u), _i32(v), _i32(vneg)
+    B, F = u.shape[0], R.shape[1]
+    E0 = np.empty((2 * B, F))
+    lib().orc_pair_product_fwd(C.c_int64(B), C.c_int64(F), _p(R), _p(u), _p(v), _p(vneg), _p(E0))
+    return E0
+
+
+def pair_product_bwd(R, u, v, vneg, dE0) -> np.ndarray:
+    R, u, v, vneg, dE0 = _f64(R), _i32(u), _i32(v), _i32(vneg), _f64(dE0)
+    n, F = R.shape
+    dR = np.empty((n, F))
+    lib().orc_pair_product_bwd(C.c_int64(n), C.c_int64(u.shape[0]), C.c_int64(F), _p(R), _p(u), _p(v), _p(vneg),
+                               _p(dE0), _p(dR))
+    return dR
+
+
+def prelu_fwd(Z, slope: float) -> np.ndarray:
+    Z = _f64(Z)
+    Y = np.empty_like(Z)
+    lib().orc_prelu_fwd(C.c_int64(Z.size), _p(Z), C.c_double(slope), _p(Y))
+    return Y
+
+
+def prelu_bwd(Z, dY, slope: float, open_mask=None):
+    """Returns (dZ, dslope)."""
+    Z, dY = _f64(Z), _f64(dY)
+    dZ = np.empty_like(Z)
+    ds = C.c_double(0.0)
+    om = None if open_mask is None else np.ascontiguousarray(np.asarray(open_mask).astype(np.uint8))
+    lib().orc_prelu_bwd(C.c_int64(Z.size), _p(Z), _p(dY), C.c_double(slope), _p(om), _p(dZ), C.byref(ds))
+    return dZ, float(ds.value)
+
+
+def bce_logits(z, n_pos: int, need_grad=True):
+    """Mean binary cross-entropy of logits z; the first n_pos are positives.  Returns (loss, dz)."""
+    z = _f64(z).ravel()
+    dz = np.empty_like(z) if need_grad else None
+    loss = lib().orc_bce_logits(C.c_int64(z.size), C.c_int64(n_pos), _p(z), _p(dz))
+    return float(loss), dz

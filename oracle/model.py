@@ -9,8 +9,9 @@ from __future__ import annotations
 
 import numpy as np
 
-from . import (ACT_NONE, ACT_RELU, adam_step, average, dense_bwd, dense_fwd, gcn_layer_bwd, gcn_layer_fwd,
-               layernorm_prelu_bwd, layernorm_prelu_fwd, sage_layer_bwd, sage_layer_fwd, sgd_step, softmax_ce)
+from . import (ACT_NONE, ACT_RELU, adam_step, average, bce_logits, dense_bwd, dense_fwd, gcn_layer_bwd, gcn_layer_fwd,
+               layernorm_prelu_bwd, layernorm_prelu_fwd, pair_product_bwd, pair_product_fwd, prelu_bwd, prelu_fwd,
+               sage_layer_bwd, sage_layer_fwd, sgd_step, softmax_ce)
 
 ACT_LN_PRELU = "ln_prelu"   # a layer whose parameter tuple ends with (gamma, beta, slope)
 
@@ -104,6 +105,47 @@ def loss_and_grads(rowptr, colidx, X, y, params, relu_open=None, encoder="sage")
     loss, d = softmax_ce(logits, y)
     grads, _ = backward(rowptr, colidx, params, saved, d, relu_open, encoder)
     return loss, grads, logits, saved
+
+
+def decoder_forward(R, batch, dec_params):
+    """MLP link decoder (App., formulation of the MLP decoder): e0 = r_u (.) r_v, e_{k+1} = PReLU(e_k Theta_k)
+    on the hidden layers, the last layer's single column is the logit.  dec_params: (Theta_k, slope_k) per
+    hidden layer, (Theta_K,) for the last.  Returns (logits [2B], saved)."""
+    u, v, vneg = batch
+    E = pair_product_fwd(R, u, v, vneg)
+    saved = []
+    for k, layer in enumerate(dec_params):
+        Z, _ = dense_fwd(E, layer[0], None, ACT_NONE)
+        saved.append((E, Z))
+        E = prelu_fwd(Z, float(np.asarray(layer[1]).ravel()[0])) if k < len(dec_params) - 1 else Z
+    return E.ravel(), saved
+
+
+def link_loss_and_grads(rowptr, colidx, X, batch, enc_params, dec_params, encoder="sage", relu_open=None,
+                        dec_open=None):
+    """Link-prediction step (Sec. 4.1): encoder on the whole local subgraph, pair products of the batch's
+    positive and negative edges, MLP decoder, mean binary cross-entropy on the logits; gradients of both
+    parameter sets.  ``relu_open`` as in loss_and_grads; ``dec_open[k]`` the same for the decoder's PReLU k.
+    Returns (loss, enc_grads, dec_grads, logits)."""
+    R, saved = forward(rowptr, colidx, X, enc_params, encoder)
+    z, dsaved = decoder_forward(R, batch, dec_params)
+    loss, dz = bce_logits(z, len(batch[0]))
+    d = dz.reshape(-1, 1)
+    K = len(dec_params)
+    dec_grads = [None] * K
+    for k in range(K - 1, -1, -1):
+        E, Z = dsaved[k]
+        extra = ()
+        if k < K - 1:
+            forced = dec_open[k] if dec_open is not None else None
+            d, ds = prelu_bwd(Z, d, float(np.asarray(dec_params[k][1]).ravel()[0]), open_mask=forced)
+            extra = (np.array([ds]),)
+        dTheta, _, dE = dense_bwd(E, Z, d, dec_params[k][0], ACT_NONE, need_dbias=False)
+        dec_grads[k] = (dTheta,) + extra
+        d = dE
+    dR = pair_product_bwd(R, batch[0], batch[1], batch[2], d)
+    enc_grads, _ = backward(rowptr, colidx, enc_params, saved, dR, relu_open, encoder)
+    return loss, enc_grads, dec_grads, z
 
 
 def train_step(rowptr, colidx, X, y, params, lr, relu_open=None, encoder="sage"):

@@ -27,6 +27,10 @@
  * of the normalised adjacency, its forms on regular, complete and empty graphs,
  * a sparse library's matrix algebra, a library's reverse-mode derivative, the
  * adjoint identity and finite differences.
+ * Link-prediction head (tests/test_oracle_link.py): membership of every drawn
+ * positive in the edge list, tail != positive tail, chi-square uniformity of
+ * both draws, a library's index / multiply / PReLU / BCE routines with their
+ * reverse-mode derivatives, finite differences through encoder + decoder.
  */
 #include <math.h>
 #include <stddef.h>
@@ -510,4 +514,104 @@ void orc_gcn_layer_bwd(int64_t n, const int32_t *rowptr, const int32_t *colidx,
 {
     orc_dense_bwd(n, M, Z, dHnext, W, F_in, F_out, act, dW, dbias, dH ? scratch_dM : NULL, scratch_dZ);
     if (dH) orc_gcn_aggregate_T(n, rowptr, colidx, scratch_dM, F_in, dH);
+}
+
+/* ------------------------------------------------------------------------
+ * Link-prediction head (Sec. 4.1, paragraphs on the link prediction decoder
+ * and on mini-batch and negative sampling; App., formulation of the MLP
+ * decoder).
+ *
+ * Mini-batch: B positive edges drawn uniformly, with replacement, from the
+ * local edge list (the directed CSR entries), and for each positive (u, v) one
+ * negative (u, v') whose tail v' is uniform over the local nodes other than v.
+ * The paper fixes no generator; this build's written spec, with the SplitMix64
+ * stream of the partitioner and c = first_counter + i for sample i:
+ *     e  = floor(mix64(seed, 2c)   * nnz   / 2^64),  u = row of entry e, v = colidx[e]
+ *     r  = floor(mix64(seed, 2c+1) * (n-1) / 2^64),  v' = r + (r >= v)
+ * ---------------------------------------------------------------------- */
+static int64_t scaled_draw(uint64_t seed, uint64_t counter, uint64_t range)
+{
+    unsigned __int128 wide = (unsigned __int128)orc_mix64(seed, counter) * range;
+    return (int64_t)(wide >> 64);
+}
+
+void orc_edge_batch(int64_t n, const int32_t *rowptr, const int32_t *colidx, uint64_t seed,
+                    uint64_t first_counter, int64_t B, int32_t *u, int32_t *v, int32_t *vneg)
+{
+    const int64_t nnz = rowptr[n];
+    for (int64_t i = 0; i < B; ++i) {
+        const uint64_t c = first_counter + (uint64_t)i;
+        const int64_t e = scaled_draw(seed, 2 * c, (uint64_t)nnz);
+        int64_t row = 0;
+        while (rowptr[row + 1] <= e) ++row;          /* the row whose range holds e */
+        const int64_t r = scaled_draw(seed, 2 * c + 1, (uint64_t)(n - 1));
+        u[i] = (int32_t)row;
+        v[i] = colidx[e];
+        vneg[i] = (int32_t)(r + (r >= v[i] ? 1 : 0));
+    }
+}
+
+/* Decoder input: e0(u, v) = r_u (.) r_v.  Rows 0..B-1 of E0 are the positive
+ * pairs (u_i, v_i), rows B..2B-1 the negative pairs (u_i, v'_i). */
+void orc_pair_product_fwd(int64_t B, int64_t F, const double *R, const int32_t *u, const int32_t *v,
+                          const int32_t *vneg, double *E0)
+{
+    for (int64_t i = 0; i < B; ++i)
+        for (int64_t f = 0; f < F; ++f) {
+            E0[i * F + f] = R[(int64_t)u[i] * F + f] * R[(int64_t)v[i] * F + f];
+            E0[(B + i) * F + f] = R[(int64_t)u[i] * F + f] * R[(int64_t)vneg[i] * F + f];
+        }
+}
+
+/* dR = gradient of the pair products w.r.t. the embeddings: every sample adds
+ * dE0 (.) (the other factor) to both of its rows; nodes outside the batch get 0. */
+void orc_pair_product_bwd(int64_t n, int64_t B, int64_t F, const double *R, const int32_t *u,
+                          const int32_t *v, const int32_t *vneg, const double *dE0, double *dR)
+{
+    memset(dR, 0, (size_t)(n * F) * sizeof(double));
+    for (int64_t i = 0; i < B; ++i)
+        for (int64_t f = 0; f < F; ++f) {
+            const double gp = dE0[i * F + f], gn = dE0[(B + i) * F + f];
+            const double ru = R[(int64_t)u[i] * F + f];
+            dR[(int64_t)u[i] * F + f] += gp * R[(int64_t)v[i] * F + f] + gn * R[(int64_t)vneg[i] * F + f];
+            dR[(int64_t)v[i] * F + f] += gp * ru;
+            dR[(int64_t)vneg[i] * F + f] += gn * ru;
+        }
+}
+
+/* PReLU with one learnable slope (the decoder's activation): y = z > 0 ? z : a z.
+ * Backward: dz = dy * (z > 0 ? 1 : a),  da = sum of dy * z over the entries with z <= 0.
+ * open_mask (optional, one byte per entry) replaces the decision z > 0. */
+void orc_prelu_fwd(int64_t count, const double *Z, double slope, double *Y)
+{
+    for (int64_t i = 0; i < count; ++i) Y[i] = Z[i] > 0.0 ? Z[i] : slope * Z[i];
+}
+
+void orc_prelu_bwd(int64_t count, const double *Z, const double *dY, double slope,
+                   const uint8_t *open_mask, double *dZ, double *dslope)
+{
+    double da = 0.0;
+    for (int64_t i = 0; i < count; ++i) {
+        const int open = open_mask ? (open_mask[i] != 0) : (Z[i] > 0.0);
+        dZ[i] = open ? dY[i] : slope * dY[i];
+        if (!open) da += dY[i] * Z[i];
+    }
+    *dslope = da;
+}
+
+/* Binary cross-entropy on logits, mean over all samples; the first n_pos
+ * samples are positives (label 1), the rest negatives (label 0).  The paper
+ * names the decoder's output the predicted link probability and no loss; this
+ * build reads the last layer's scalar as a logit.
+ *     loss = mean( y = 1 ? log(1 + exp(-z)) : log(1 + exp(z)) ),  dz = (sigmoid(z) - y) / count */
+double orc_bce_logits(int64_t count, int64_t n_pos, const double *z, double *dz)
+{
+    double loss = 0.0;
+    for (int64_t i = 0; i < count; ++i) {
+        const double y = i < n_pos ? 1.0 : 0.0;
+        const double t = y > 0.5 ? -z[i] : z[i];                  /* loss_i = log(1 + exp(t)) */
+        loss += t > 0.0 ? t + log1p(exp(-t)) : log1p(exp(t));
+        if (dz) dz[i] = (1.0 / (1.0 + exp(-z[i])) - y) / (double)count;
+    }
+    return count > 0 ? loss / (double)count : 0.0;
 }
