@@ -296,6 +296,74 @@ int tma_gcn_layer_bwd(int64_t n, const int32_t *rowptr_T, const int32_t *colidx_
                       void *ws, size_t ws_bytes, tma_stream_t stream);
 
 /* ------------------------------------------------------------------------
+ * Link-prediction head (Sec. 4.1, paragraphs on the link prediction decoder
+ * and on mini-batch and negative sampling; App., formulation of the MLP
+ * decoder).  All pointers device memory unless stated; every call is ordered
+ * on `stream`, allocates nothing, and is deterministic.
+ *
+ * tma_edge_batch: B positive edges drawn uniformly with replacement from the
+ * local CSR entries and one negative tail per positive, uniform over the local
+ * nodes other than the positive tail.  Counter-based: sample i uses counter
+ * c = first_counter + i of the SplitMix64 stream of tma_partition,
+ *     e = floor(z(2c) * nnz / 2^64),  u = row of entry e,  v = colidx[e],
+ *     r = floor(z(2c+1) * (n-1) / 2^64),  v' = r + (r >= v).
+ *   n, nnz : local node and entry counts (host values; B > 0 needs n >= 2 and
+ *            nnz >= 1);  rowptr [n+1], colidx [nnz] int32
+ *   u_out, v_out, vneg_out [B] int32.
+ *
+ * tma_pair_product_fwd: decoder input E0 [2B, F] (leading dimension lde):
+ * row i = r_u(i) (.) r_v(i), row B+i = r_u(i) (.) r_v'(i), from the embeddings
+ * R [n, F] dtype (leading dimension ldr).
+ *
+ * tma_pair_product_bwd: dR [n, F] (leading dimension ld_dr) = gradient of E0
+ * w.r.t. R given dE0 [2B, F]; rows of nodes outside the batch are zero.  A
+ * node's terms are summed in a fixed order (no floating-point atomics).
+ * Workspace: tma_pair_product_bwd_workspace_bytes(n, B, F, dtype), 256-byte
+ * aligned.
+ *
+ * tma_prelu_fwd / _bwd: Y = Z > 0 ? Z : a Z with one learnable slope a
+ * (slope: 1 fp32 value in device memory); dZ = dY (Z > 0 ? 1 : a), dslope_out
+ * [1] fp32 = sum of dY Z over Z <= 0 (OVERWRITTEN).  dZ_out may alias dY.
+ * Workspace of the backward: tma_prelu_bwd_workspace_bytes(), 16-byte aligned.
+ *
+ * tma_bce_logits: mean binary cross-entropy of `count` logits z[i * ldz]
+ * (dtype), the first n_pos being positives; loss_out [1] fp32 OVERWRITTEN;
+ * dz_out[i * ld_dz] = (sigmoid(z_i) - y_i) / count, or NULL.  The paper calls
+ * the decoder's output the link probability and names no loss: this build
+ * treats the last layer's scalar as a logit.  Workspace:
+ * tma_bce_logits_workspace_bytes(), 16-byte aligned.
+ * ---------------------------------------------------------------------- */
+int tma_edge_batch(int64_t n, int64_t nnz, const int32_t *rowptr, const int32_t *colidx,
+                   uint64_t seed, uint64_t first_counter, int64_t B,
+                   int32_t *u_out, int32_t *v_out, int32_t *vneg_out, tma_stream_t stream);
+
+int tma_pair_product_fwd(int64_t B, int32_t F, const void *R, int64_t ldr, int32_t dtype,
+                         const int32_t *u, const int32_t *v, const int32_t *vneg,
+                         void *E0_out, int64_t lde, tma_stream_t stream);
+
+size_t tma_pair_product_bwd_workspace_bytes(int64_t n, int64_t B, int32_t F, int32_t dtype);
+
+int tma_pair_product_bwd(int64_t n, int64_t B, int32_t F, const void *R, int64_t ldr, int32_t dtype,
+                         const int32_t *u, const int32_t *v, const int32_t *vneg,
+                         const void *dE0, int64_t lde, void *dR_out, int64_t ld_dr,
+                         void *ws, size_t ws_bytes, tma_stream_t stream);
+
+int tma_prelu_fwd(int64_t n, int32_t F, const void *Z, int64_t ldz, const float *slope, int32_t dtype,
+                  void *Y_out, int64_t ldy, tma_stream_t stream);
+
+size_t tma_prelu_bwd_workspace_bytes(void);
+
+int tma_prelu_bwd(int64_t n, int32_t F, const void *Z, int64_t ldz, const void *dY, int64_t ldd,
+                  const float *slope, int32_t dtype, void *dZ_out, int64_t ld_dz, float *dslope_out,
+                  void *ws, size_t ws_bytes, tma_stream_t stream);
+
+size_t tma_bce_logits_workspace_bytes(void);
+
+int tma_bce_logits(int64_t count, int64_t n_pos, const void *z, int64_t ldz, int32_t dtype,
+                   float *loss_out, void *dz_out, int64_t ld_dz,
+                   void *ws, size_t ws_bytes, tma_stream_t stream);
+
+/* ------------------------------------------------------------------------
  * Losses on the last layer's output.
  * tma_softmax_ce: mean softmax cross-entropy over the n local nodes (reading
  *   taken for workloads with class labels); loss_out[0] fp32 (device),

@@ -28,6 +28,9 @@ EXPORTS = (
     "tma_dense_fwd", "tma_dense_bwd_workspace_bytes", "tma_dense_bwd",
     "tma_gcn_norm", "tma_gcn_layer_aggregates_first", "tma_gcn_layer_fwd",
     "tma_gcn_layer_bwd_workspace_bytes", "tma_gcn_layer_bwd",
+    "tma_edge_batch", "tma_pair_product_fwd", "tma_pair_product_bwd_workspace_bytes", "tma_pair_product_bwd",
+    "tma_prelu_fwd", "tma_prelu_bwd_workspace_bytes", "tma_prelu_bwd", "tma_bce_logits_workspace_bytes",
+    "tma_bce_logits",
     "tma_loss_workspace_bytes", "tma_softmax_ce", "tma_sigmoid_l2", "tma_sgd_step", "tma_adam_step", "tma_average",
     "tma_gather_rows", "tma_profile_begin", "tma_profile_end", "tma_profile_count", "tma_profile_entry",
 )
@@ -51,7 +54,9 @@ def lib() -> C.CDLL:
         L.tma_last_error.restype = C.c_char_p
         for name in ("tma_induced_subgraph_workspace_bytes", "tma_sage_layer_bwd_workspace_bytes",
                      "tma_loss_workspace_bytes", "tma_layernorm_prelu_bwd_workspace_bytes",
-                     "tma_dense_bwd_workspace_bytes", "tma_gcn_layer_bwd_workspace_bytes"):
+                     "tma_dense_bwd_workspace_bytes", "tma_gcn_layer_bwd_workspace_bytes",
+                     "tma_pair_product_bwd_workspace_bytes", "tma_prelu_bwd_workspace_bytes",
+                     "tma_bce_logits_workspace_bytes"):
             getattr(L, name).restype = C.c_size_t
         _lib = L
     return _lib
@@ -411,6 +416,138 @@ def tma_gcn_layer_bwd(rowptr_T, colidx_T, s_norm, H, M, Hnext, dHnext, W, act: i
         _ptr(dbias, torch.float32, "dbias"), C.c_void_p(dH_out.data_ptr() if dH_out is not None else 0), _ptr(ws),
         C.c_size_t(ws.numel()), _stream(stream)))
     return dW, dbias, dH_out
+
+
+# --------------------------------------------------------------------------- link-prediction head (Sec. 4.1, App.)
+def tma_edge_batch(rowptr, colidx, nnz: int, seed: int, first_counter: int, B: int, u_out=None, v_out=None,
+                   vneg_out=None, stream=None):
+    """B positive edges (u, v) of the local CSR and one negative tail v' each; int32 device tensors."""
+    n = rowptr.numel() - 1
+    dev = rowptr.device
+    outs = []
+    for t in (u_out, v_out, vneg_out):
+        if t is None:
+            t = torch.empty(B, dtype=torch.int32, device=dev)
+        if t.numel() != B:
+            raise TmaError("tma_edge_batch: outputs need B entries")
+        outs.append(t)
+    _check(lib().tma_edge_batch(
+        C.c_int64(n), C.c_int64(nnz), _ptr(rowptr, torch.int32, "rowptr"), _ptr(colidx, torch.int32, "colidx"),
+        C.c_uint64(seed), C.c_uint64(first_counter), C.c_int64(B), _ptr(outs[0], torch.int32), _ptr(outs[1], torch.int32),
+        _ptr(outs[2], torch.int32), _stream(stream)))
+    return tuple(outs)
+
+
+def tma_pair_product_fwd(R, u, v, vneg, E0_out=None, stream=None):
+    """E0 [2B, F]: r_u (.) r_v for the positives, then r_u (.) r_v' for the negatives."""
+    n, F, ldr = _rows_ld(R, "R")
+    Bn = u.numel()
+    if v.numel() != Bn or vneg.numel() != Bn:
+        raise TmaError("tma_pair_product_fwd: u, v, vneg need the same length")
+    if E0_out is None:
+        E0_out = _padded(2 * Bn, F, R.dtype, R.device)
+    if tuple(E0_out.shape) != (2 * Bn, F) or E0_out.dtype != R.dtype:
+        raise TmaError("tma_pair_product_fwd: E0_out shape/dtype")
+    _, _, lde = _rows_ld(E0_out, "E0_out")
+    _check(lib().tma_pair_product_fwd(
+        C.c_int64(Bn), C.c_int32(F), C.c_void_p(R.data_ptr()), C.c_int64(ldr), C.c_int32(_feat_dtype(R)),
+        _ptr(u, torch.int32, "u"), _ptr(v, torch.int32, "v"), _ptr(vneg, torch.int32, "vneg"),
+        C.c_void_p(E0_out.data_ptr()), C.c_int64(lde), _stream(stream)))
+    return E0_out
+
+
+def tma_pair_product_bwd_workspace_bytes(n: int, Bn: int, F: int, dtype: int) -> int:
+    return int(lib().tma_pair_product_bwd_workspace_bytes(C.c_int64(n), C.c_int64(Bn), C.c_int32(F), C.c_int32(dtype)))
+
+
+def tma_pair_product_bwd(R, u, v, vneg, dE0, dR_out=None, ws=None, stream=None):
+    """dR [n, F]: gradient of the pair products w.r.t. the embeddings (zero rows outside the batch)."""
+    n, F, ldr = _rows_ld(R, "R")
+    Bn = u.numel()
+    if tuple(dE0.shape) != (2 * Bn, F) or dE0.dtype != R.dtype:
+        raise TmaError("tma_pair_product_bwd: dE0 shape/dtype")
+    if dR_out is None:
+        dR_out = _padded(n, F, R.dtype, R.device)
+    if tuple(dR_out.shape) != (n, F) or dR_out.dtype != R.dtype:
+        raise TmaError("tma_pair_product_bwd: dR_out shape/dtype")
+    _, _, lde = _rows_ld(dE0, "dE0")
+    _, _, ld_dr = _rows_ld(dR_out, "dR_out")
+    dt = _feat_dtype(R)
+    if ws is None:
+        ws = _workspace(tma_pair_product_bwd_workspace_bytes(n, Bn, F, dt), R.device)
+    _check(lib().tma_pair_product_bwd(
+        C.c_int64(n), C.c_int64(Bn), C.c_int32(F), C.c_void_p(R.data_ptr()), C.c_int64(ldr), C.c_int32(dt),
+        _ptr(u, torch.int32, "u"), _ptr(v, torch.int32, "v"), _ptr(vneg, torch.int32, "vneg"),
+        C.c_void_p(dE0.data_ptr()), C.c_int64(lde), C.c_void_p(dR_out.data_ptr()), C.c_int64(ld_dr), _ptr(ws),
+        C.c_size_t(ws.numel()), _stream(stream)))
+    return dR_out
+
+
+def tma_prelu_fwd(Z, slope, out=None, stream=None):
+    """Y = PReLU_slope(Z); slope is a 1-element fp32 device tensor."""
+    n, F, ldz = _rows_ld(Z, "Z")
+    if out is None:
+        out = _padded(n, F, Z.dtype, Z.device)
+    if tuple(out.shape) != (n, F) or out.dtype != Z.dtype or slope.numel() != 1:
+        raise TmaError("tma_prelu_fwd: out shape/dtype or slope")
+    _, _, ldy = _rows_ld(out, "out")
+    _check(lib().tma_prelu_fwd(C.c_int64(n), C.c_int32(F), C.c_void_p(Z.data_ptr()), C.c_int64(ldz),
+                               _ptr(slope, torch.float32, "slope"), C.c_int32(_feat_dtype(Z)),
+                               C.c_void_p(out.data_ptr()), C.c_int64(ldy), _stream(stream)))
+    return out
+
+
+def tma_prelu_bwd_workspace_bytes() -> int:
+    return int(lib().tma_prelu_bwd_workspace_bytes())
+
+
+def tma_prelu_bwd(Z, dY, slope, dZ_out=None, dslope=None, ws=None, stream=None):
+    """Returns (dZ, dslope).  dZ_out may be dY itself."""
+    n, F, ldz = _rows_ld(Z, "Z")
+    if tuple(dY.shape) != (n, F) or dY.dtype != Z.dtype or slope.numel() != 1:
+        raise TmaError("tma_prelu_bwd: dY shape/dtype or slope")
+    if dZ_out is None:
+        dZ_out = _padded(n, F, Z.dtype, Z.device)
+    if dslope is None:
+        dslope = torch.empty(1, dtype=torch.float32, device=Z.device)
+    if tuple(dZ_out.shape) != (n, F) or dZ_out.dtype != Z.dtype or dslope.numel() != 1:
+        raise TmaError("tma_prelu_bwd: output shape/dtype")
+    _, _, ldd = _rows_ld(dY, "dY")
+    _, _, ld_dz = _rows_ld(dZ_out, "dZ_out")
+    if ws is None:
+        ws = _workspace(tma_prelu_bwd_workspace_bytes(), Z.device)
+    _check(lib().tma_prelu_bwd(
+        C.c_int64(n), C.c_int32(F), C.c_void_p(Z.data_ptr()), C.c_int64(ldz), C.c_void_p(dY.data_ptr()), C.c_int64(ldd),
+        _ptr(slope, torch.float32, "slope"), C.c_int32(_feat_dtype(Z)), C.c_void_p(dZ_out.data_ptr()), C.c_int64(ld_dz),
+        _ptr(dslope, torch.float32, "dslope"), _ptr(ws), C.c_size_t(ws.numel()), _stream(stream)))
+    return dZ_out, dslope
+
+
+def tma_bce_logits_workspace_bytes() -> int:
+    return int(lib().tma_bce_logits_workspace_bytes())
+
+
+def tma_bce_logits(z, n_pos: int, loss_out=None, dz_out=None, need_grad=True, ws=None, stream=None):
+    """Mean binary cross-entropy of the logits z [count, 1] (first n_pos positives).  Returns (loss, dz or None)."""
+    count, one, ldz = _rows_ld(z, "z")
+    if one != 1:
+        raise TmaError("tma_bce_logits: z must have one column")
+    if loss_out is None:
+        loss_out = torch.empty(1, dtype=torch.float32, device=z.device)
+    if need_grad and dz_out is None:
+        dz_out = _padded(count, 1, z.dtype, z.device)
+    if not need_grad:
+        dz_out = None
+    ld_dz = _rows_ld(dz_out, "dz_out")[2] if dz_out is not None else 1
+    if dz_out is not None and (tuple(dz_out.shape) != (count, 1) or dz_out.dtype != z.dtype):
+        raise TmaError("tma_bce_logits: dz_out shape/dtype")
+    if ws is None:
+        ws = _workspace(tma_bce_logits_workspace_bytes(), z.device)
+    _check(lib().tma_bce_logits(
+        C.c_int64(count), C.c_int64(n_pos), C.c_void_p(z.data_ptr()), C.c_int64(ldz), C.c_int32(_feat_dtype(z)),
+        _ptr(loss_out, torch.float32, "loss_out"), C.c_void_p(dz_out.data_ptr() if dz_out is not None else 0),
+        C.c_int64(ld_dz), _ptr(ws), C.c_size_t(ws.numel()), _stream(stream)))
+    return loss_out, dz_out
 
 
 def tma_loss_workspace_bytes(n: int, Cc: int) -> int:

@@ -73,6 +73,16 @@ __device__ __forceinline__ uint16_t f32_to_bf16(float f)
     return uint16_t(u >> 16);
 }
 
+// Output number (unit+1) of the SplitMix64 stream (Steele, Lea, Flood 2014) seeded with `seed`: the library's
+// counter-based generator (partition assignment, mini-batch draws).
+__device__ __forceinline__ uint64_t splitmix64_at(uint64_t seed, uint64_t unit)
+{
+    uint64_t z = seed + (unit + 1ull) * 0x9E3779B97F4A7C15ull;
+    z = (z ^ (z >> 30)) * 0xBF58476D1CE4E5B9ull;
+    z = (z ^ (z >> 27)) * 0x94D049BB133111EBull;
+    return z ^ (z >> 31);
+}
+
 // A 16-byte piece of a feature row: 4 fp32 or 8 bf16 elements, handled as fp32 in registers.
 template <typename T>
 struct Chunk;

@@ -134,6 +134,15 @@ __global__ __launch_bounds__(256) void sum_partials_kernel(int nb, int width, in
     }
 }
 
+int launch_sum_partials(int nb, int width, int F, const float *partial, float *out, hipStream_t stream)
+{
+    if (F <= 0) return TMA_OK;
+    TMA_TIMED("sum_partials", stream);
+    hipLaunchKernelGGL(sum_partials_kernel, dim3(unsigned(ceil_div(F, 16))), dim3(256), 0, stream, nb, width, F, partial,
+                       out);
+    return check_launch("sum_partials");
+}
+
 constexpr int kColsumMaxBlocks = 1024;
 
 struct ColsumPlan {
@@ -202,10 +211,7 @@ static int scale_mask_colsum(int64_t n, int F, int Fp, const T *g, const T *h, i
                                Fp, g, h, ld, s, relu ? 1 : 0, dst, int64_t(Fp), partial, p.rows_per_block, p.tpr);
         if (int rc = check_launch("scale_mask_colsum")) return rc;
     }
-    TMA_TIMED("sum_partials", stream);
-    hipLaunchKernelGGL(sum_partials_kernel, dim3(unsigned(ceil_div(F, 16))), dim3(256), 0, stream,
-                       n > 0 ? int(p.blocks) : 0, Fp, F, partial, dbias);
-    return check_launch("sum_partials");
+    return launch_sum_partials(n > 0 ? int(p.blocks) : 0, Fp, F, partial, dbias, stream);
 }
 
 }  // namespace tma

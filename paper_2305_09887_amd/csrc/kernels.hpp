@@ -7,9 +7,10 @@ namespace tma {
 
 // Row gather-reduce over a CSR:  out_v = scale_v * sum_{u in row v} in_u  (+ out_v when accumulate).
 // scale_v = inv_deg[v] when inv_deg != nullptr, else 1.  fp32 accumulation in neighbour order.
+// in_rows: rows of `in` when it is not an n-row matrix (the ids of colidx index it); 0 = n rows.
 int launch_spmm(int64_t n, const int32_t *rowptr, const int32_t *colidx, const float *inv_deg, const void *in,
                 int64_t ld_in, int32_t F, int32_t dtype, void *out, int64_t ld_out, bool accumulate,
-                hipStream_t stream);
+                hipStream_t stream, int64_t in_rows = 0);
 
 // Same gather with the layer epilogue fused: out_v = act(scale_v * sum + [out_v] + self_v + bias), or, with
 // scale_all, out_v = act(scale_v * (sum + [out_v] + self_v) + bias) (the GCN form, self inside the normalisation).
@@ -17,7 +18,7 @@ int launch_spmm(int64_t n, const int32_t *rowptr, const int32_t *colidx, const f
 int launch_spmm_combine(int64_t n, const int32_t *rowptr, const int32_t *colidx, const float *inv_deg, const void *in,
                         int64_t ld_in, int32_t F, int32_t dtype, void *out, int64_t ld_out, bool accumulate,
                         const void *self, int64_t ld_self, const float *bias, int32_t F_valid, bool relu,
-                        bool scale_all, const float *edge_scale, hipStream_t stream);
+                        bool scale_all, const float *edge_scale, hipStream_t stream, int64_t in_rows = 0);
 
 // dst_v = inv_deg[v] * g_v (.) [h_v > 0]  (mask only with relu); columns F..F_pad-1 of dst are zeroed.
 int launch_scale_mask_rows(int64_t n, int32_t F, int32_t F_pad, const void *g, const void *h, int64_t ld,
@@ -82,5 +83,12 @@ size_t dense_gemm_bwd_weight_workspace_bytes(int64_t n, int32_t F_in, int32_t F_
 int launch_dense_gemm_bwd_weight(int64_t n, const void *X, int64_t ldx, const void *dY, const void *Y, int64_t ld,
                                  int32_t F_in, int32_t F_out, int32_t act, int32_t dtype, float *dW, float *dbias,
                                  void *ws, size_t ws_bytes, hipStream_t s);
+
+// prefix_out[i] = values[0] + ... + values[i-1] for i <= n (n + 1 outputs).  ws: exclusive_scan_i32_workspace_bytes(n).
+size_t exclusive_scan_i32_workspace_bytes(int64_t n);
+int launch_exclusive_scan_i32(int64_t n, const int32_t *values, int32_t *prefix_out, void *ws, hipStream_t s);
+
+// out[j] = sum over b < nb of partial[b * width + j], j < F, in a fixed order (nb = 0 writes zeros).
+int launch_sum_partials(int nb, int width, int F, const float *partial, float *out, hipStream_t stream);
 
 }  // namespace tma

@@ -5,15 +5,6 @@
 
 namespace tma {
 
-// Output number (unit+1) of the SplitMix64 stream seeded with `seed`.
-__device__ __forceinline__ uint64_t splitmix64_at(uint64_t seed, uint64_t unit)
-{
-    uint64_t z = seed + (unit + 1ull) * 0x9E3779B97F4A7C15ull;
-    z = (z ^ (z >> 30)) * 0xBF58476D1CE4E5B9ull;
-    z = (z ^ (z >> 27)) * 0x94D049BB133111EBull;
-    return z ^ (z >> 31);
-}
-
 // Four consecutive nodes per thread so that the store is one 16-byte write.
 __global__ __launch_bounds__(256) void partition_kernel(int64_t n_nodes,
                                                         const int32_t *__restrict__ cluster,

@@ -104,6 +104,7 @@ struct SpmmOut {
     int relu;
     int scale_all;  // the scale multiplies the sum with "+ out_v" / "+ self_v" already added (GCN: s_v (sum + self_v))
     const float *edge_scale;  // neighbour u enters the sum as edge_scale[u] * in_u, and self_v as edge_scale[v] * self_v
+    int64_t in_rows;          // rows of the gathered matrix (>= 1): filler loads stay below it
 };
 
 template <typename T, int G, int CPL>
@@ -357,8 +358,10 @@ __global__ __launch_bounds__(kSpmmThreads) void spmm_stream_kernel(int64_t n, co
         }
         Chunk<T>::store(o.out + v * o.ld_out + f0, res);
     };
-    stream_segments<T, kEdge>(in, ld_in, ids, o.edge_scale, last_entry, sub, int32_t(base + r_first), next_row_step,
-                              row_extra, finish);
+    // a row that exists in the gathered matrix, for the loads of slots that carry nothing yet
+    const int32_t filler_row = int32_t((base + r_first) < o.in_rows ? (base + r_first) : o.in_rows - 1);
+    stream_segments<T, kEdge>(in, ld_in, ids, o.edge_scale, last_entry, sub, filler_row, next_row_step, row_extra,
+                              finish);
     __syncthreads();
 
     // ---- deferred rows, kHubsPerPass at a time: group g sums the g-th share of each, then a fixed-order combine
@@ -398,8 +401,8 @@ __global__ __launch_bounds__(kSpmmThreads) void spmm_stream_kernel(int64_t n, co
 #pragma unroll
                 for (int i = 0; i < E; ++i) partial[(seg * NG + grp) * width + sub * E + i] = acc[i];
             };
-            stream_segments<T, kEdge>(in, ld_in, ids, o.edge_scale, last_entry, sub, int32_t(base + r_first),
-                                      next_share_step, no_extra, to_lds);
+            stream_segments<T, kEdge>(in, ld_in, ids, o.edge_scale, last_entry, sub, filler_row, next_share_step,
+                                      no_extra, to_lds);
         }
         __syncthreads();
         if (live && grp < h_end - h0) {
@@ -612,33 +615,33 @@ template <typename T>
 static int spmm_any(int64_t n, const int32_t *rowptr, const int32_t *colidx, const float *inv_deg, const void *in,
                     int64_t ld_in, int32_t F, void *out, int64_t ld_out, bool accumulate, const void *self,
                     int64_t ld_self, const float *bias, int32_t F_valid, bool relu, bool scale_all,
-                    const float *edge_scale, hipStream_t stream)
+                    const float *edge_scale, int64_t in_rows, hipStream_t stream)
 {
     SpmmOut<T> o{static_cast<T *>(out), ld_out, inv_deg, accumulate ? 1 : 0, static_cast<const T *>(self), ld_self,
-                 bias, F_valid, relu ? 1 : 0, (scale_all && inv_deg) ? 1 : 0, edge_scale};
+                 bias, F_valid, relu ? 1 : 0, (scale_all && inv_deg) ? 1 : 0, edge_scale, in_rows > 0 ? in_rows : n};
     return launch_typed<T>(n, rowptr, colidx, static_cast<const T *>(in), ld_in, F, o, stream);
 }
 
 int launch_spmm(int64_t n, const int32_t *rowptr, const int32_t *colidx, const float *inv_deg, const void *in,
                 int64_t ld_in, int32_t F, int32_t dtype, void *out, int64_t ld_out, bool accumulate,
-                hipStream_t stream)
+                hipStream_t stream, int64_t in_rows)
 {
     return launch_spmm_combine(n, rowptr, colidx, inv_deg, in, ld_in, F, dtype, out, ld_out, accumulate, nullptr, 0,
-                               nullptr, F, false, false, nullptr, stream);
+                               nullptr, F, false, false, nullptr, stream, in_rows);
 }
 
 int launch_spmm_combine(int64_t n, const int32_t *rowptr, const int32_t *colidx, const float *inv_deg, const void *in,
                         int64_t ld_in, int32_t F, int32_t dtype, void *out, int64_t ld_out, bool accumulate,
                         const void *self, int64_t ld_self, const float *bias, int32_t F_valid, bool relu,
-                        bool scale_all, const float *edge_scale, hipStream_t stream)
+                        bool scale_all, const float *edge_scale, hipStream_t stream, int64_t in_rows)
 {
     if (n == 0 || F == 0) return TMA_OK;
     if (dtype == TMA_F32)
         return spmm_any<float>(n, rowptr, colidx, inv_deg, in, ld_in, F, out, ld_out, accumulate, self, ld_self, bias,
-                               F_valid, relu, scale_all, edge_scale, stream);
+                               F_valid, relu, scale_all, edge_scale, in_rows, stream);
     if (dtype == TMA_BF16)
         return spmm_any<uint16_t>(n, rowptr, colidx, inv_deg, in, ld_in, F, out, ld_out, accumulate, self, ld_self,
-                                  bias, F_valid, relu, scale_all, edge_scale, stream);
+                                  bias, F_valid, relu, scale_all, edge_scale, in_rows, stream);
     return fail(TMA_ERR_UNSUPPORTED_DTYPE, "spmm: dtype %d", dtype);
 }
 

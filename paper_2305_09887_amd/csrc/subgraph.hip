@@ -443,6 +443,29 @@ static CountWorkspace carve(void *ws, int64_t n_nodes, int64_t cap)
     return w;
 }
 
+size_t exclusive_scan_i32_workspace_bytes(int64_t n)
+{
+    return round_up(size_t(ceil_div(n > 0 ? n : 1, kScanTile) + 1) * sizeof(int64_t), 256);
+}
+
+int launch_exclusive_scan_i32(int64_t n, const int32_t *values, int32_t *prefix_out, void *ws, hipStream_t s)
+{
+    int64_t *block_sums = static_cast<int64_t *>(ws);
+    const int64_t nb = n > 0 ? ceil_div(n, kScanTile) : 0;
+    int64_t *total = block_sums + (nb > 0 ? nb : 1);
+    DegIn in{values};
+    DegOut out{prefix_out};
+    TMA_TIMED("exclusive_scan", s);
+    if (nb > 0)
+        hipLaunchKernelGGL(scan_reduce_kernel<DegIn>, dim3(unsigned(nb)), dim3(kScanThreads), 0, s,
+                           static_cast<const int64_t *>(nullptr), n, in, block_sums);
+    hipLaunchKernelGGL(scan_sums_kernel, dim3(1), dim3(1024), 0, s, nb, block_sums, total, prefix_out);
+    if (nb > 0)
+        hipLaunchKernelGGL((scan_apply_kernel<DegIn, DegOut>), dim3(unsigned(nb)), dim3(kScanThreads), 0, s,
+                           static_cast<const int64_t *>(nullptr), n, in, out, block_sums);
+    return check_launch("exclusive scan");
+}
+
 }  // namespace tma
 
 extern "C" size_t tma_induced_subgraph_workspace_bytes(int64_t n_nodes, int64_t cap_n_loc)

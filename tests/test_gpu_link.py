@@ -1,0 +1,179 @@
+"""Link-prediction head (Sec. 4.1; App.: MLP decoder) on the GPU against the oracle, through the C ABI: the
+edge mini-batch bit for bit, pair products / PReLU / BCE and their gradients to 1e-4 (fp32) and 2e-2 (bf16
+storage), the deterministic scatter of the pair-product gradient, and whole link-prediction training steps of
+the three encoders."""
+import numpy as np
+import pytest
+
+import oracle
+from oracle import model as omodel
+from paper_2305_09887_amd import synth
+
+torch = pytest.importorskip("torch")
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def B():
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    from paper_2305_09887_amd import binding
+    binding.lib()
+    return binding
+
+
+def dev(a, dtype=None):
+    t = torch.as_tensor(np.ascontiguousarray(a))
+    return (t if dtype is None else t.to(dtype)).cuda()
+
+
+def dev_bf16(a):
+    bits = synth.to_bf16_bits(np.asarray(a, dtype=np.float32)).reshape(np.shape(a))
+    return torch.from_numpy(bits.view(np.int16)).cuda().view(torch.bfloat16)
+
+
+def host(t):
+    return t.float().cpu().numpy().astype(np.float64)
+
+
+def close(got, want, tol, what):
+    got, want = np.asarray(got, np.float64), np.asarray(want, np.float64)
+    assert got.shape == want.shape, what
+    rel = np.linalg.norm((got - want).ravel()) / max(np.linalg.norm(want.ravel()), 1e-300)
+    mx = np.abs(got - want).max() / max(np.abs(want).max(), 1e-300)
+    assert rel <= tol and mx <= tol, f"{what}: rel fro {rel:.2e}, max abs / max {mx:.2e}"
+
+
+def padded(B, a, bf16=False):
+    a = np.asarray(a, dtype=np.float32)
+    t = B._padded(a.shape[0], a.shape[1], torch.bfloat16 if bf16 else torch.float32, "cuda")
+    t.copy_(dev_bf16(a) if bf16 else dev(a))
+    return t
+
+
+def local_graph(n_glob, m, seed, K=2, kind="uniform"):
+    if kind == "uniform":
+        rowptr, colidx = synth.uniform_graph(n_glob, m, seed)
+    else:
+        rowptr, colidx = synth.chung_lu_graph(n_glob, 2.0 * m / n_glob, 2.1, seed)
+    sub = oracle.induced_subgraph(rowptr, colidx, oracle.partition(n_glob, K, seed=seed), 0)
+    return sub["rowptr"], sub["colidx"]
+
+
+@pytest.mark.parametrize("kind,Bn,first", [("uniform", 10_000, 0), ("chung_lu", 70_001, 123_456_789),
+                                           ("chung_lu", 1, 2 ** 63 + 5), ("uniform", 0, 0)])
+def test_edge_batch_bit_exact(B, kind, Bn, first):
+    rp, ci = local_graph(30_000, 150_000, 5, kind=kind)
+    u, v, vn = B.tma_edge_batch(dev(rp), dev(ci), int(rp[-1]), seed=77, first_counter=first, B=Bn)
+    wu, wv, wn = oracle.edge_batch(rp, ci, 77, first, Bn)
+    assert np.array_equal(u.cpu().numpy(), wu) and np.array_equal(v.cpu().numpy(), wv)
+    assert np.array_equal(vn.cpu().numpy(), wn)
+
+
+def test_edge_batch_rejects_graphs_without_a_choice(B):
+    rp = dev(np.zeros(3, np.int32))
+    ci = torch.empty(0, dtype=torch.int32, device="cuda")
+    with pytest.raises(B.TmaError):
+        B.tma_edge_batch(rp, ci, 0, 1, 0, 4)
+    with pytest.raises(B.TmaError):
+        B.tma_edge_batch(dev(np.array([0, 1], np.int32)), dev(np.array([0], np.int32)), 1, 1, 0, 4)   # one node
+
+
+def _batch(n, Bn, seed, hub=False):
+    rng = np.random.default_rng(seed)
+    u = rng.integers(0, n, Bn).astype(np.int32)
+    v = rng.integers(0, n, Bn).astype(np.int32)
+    if hub:        # a few nodes take part in very many samples: long per-node term lists
+        u[: Bn // 2] = rng.integers(0, 3, Bn // 2)
+        v[: Bn // 4] = 1
+    vn = ((v + 1 + rng.integers(0, n - 1, Bn)) % n).astype(np.int32)
+    return u, v, vn
+
+
+@pytest.mark.parametrize("n,F,Bn,hub", [(5000, 64, 3000, False), (700, 256, 4096, True), (3000, 47, 1000, False),
+                                        (20_000, 128, 100, False), (64, 16, 9000, True), (2000, 100, 0, False),
+                                        (1500, 8, 1, False)])
+def test_pair_products_fp32(B, n, F, Bn, hub):
+    rng = np.random.default_rng(F + Bn)
+    R = rng.standard_normal((n, F)).astype(np.float32)
+    g = rng.standard_normal((2 * Bn, F)).astype(np.float32)
+    u, v, vn = _batch(n, Bn, seed=n, hub=hub)
+    Rd, gd = padded(B, R), padded(B, g)
+    ud, vd, nd = dev(u), dev(v), dev(vn)
+    E0 = B.tma_pair_product_fwd(Rd, ud, vd, nd)
+    close(host(E0), oracle.pair_product_fwd(R, u, v, vn), 1e-6, "E0") if Bn else None
+    dR = B.tma_pair_product_bwd(Rd, ud, vd, nd, gd)
+    want = oracle.pair_product_bwd(R, u, v, vn, g)
+    if Bn:
+        close(host(dR), want, 1e-4, "dR")
+    touched = np.zeros(n, bool)
+    touched[u] = touched[v] = touched[vn] = True
+    assert not host(dR)[~touched].any()                       # nodes outside the batch: exact zeros
+    again = B.tma_pair_product_bwd(Rd, ud, vd, nd, gd)         # fixed summation order: the same bits
+    assert torch.equal(again, dR)
+
+
+def test_pair_products_bf16_and_unaligned(B):
+    n, F, Bn = 4000, 128, 5000
+    rng = np.random.default_rng(3)
+    R = synth.round_bf16(rng.standard_normal((n, F)).astype(np.float32))
+    g = synth.round_bf16(rng.standard_normal((2 * Bn, F)).astype(np.float32))
+    u, v, vn = _batch(n, Bn, seed=1, hub=True)
+    Rd, gd = padded(B, R, True), padded(B, g, True)
+    E0 = B.tma_pair_product_fwd(Rd, dev(u), dev(v), dev(vn))
+    close(host(E0), oracle.pair_product_fwd(R, u, v, vn), 2e-2, "E0 bf16")
+    dR = B.tma_pair_product_bwd(Rd, dev(u), dev(v), dev(vn), gd)
+    close(host(dR), oracle.pair_product_bwd(R, u, v, vn, g), 2e-2, "dR bf16")
+    # fp32 rows with a pitch that is no multiple of 16 bytes
+    F = 30
+    R = rng.standard_normal((n, F)).astype(np.float32)
+    g = rng.standard_normal((2 * Bn, F)).astype(np.float32)
+    big = torch.zeros((n, F + 1), device="cuda")
+    big[:, :F] = dev(R)
+    gbig = torch.zeros((2 * Bn, F + 3), device="cuda")
+    gbig[:, :F] = dev(g)
+    E0 = B.tma_pair_product_fwd(big[:, :F], dev(u), dev(v), dev(vn))
+    close(host(E0), oracle.pair_product_fwd(R, u, v, vn), 1e-6, "E0 unaligned")
+    dout = torch.zeros((n, F + 1), device="cuda")
+    dR = B.tma_pair_product_bwd(big[:, :F], dev(u), dev(v), dev(vn), gbig[:, :F], dR_out=dout[:, :F])
+    close(host(dR), oracle.pair_product_bwd(R, u, v, vn, g), 1e-4, "dR unaligned")
+
+
+@pytest.mark.parametrize("n,F", [(3000, 256), (1001, 47), (1, 4), (50_000, 128), (0, 16)])
+def test_prelu(B, n, F):
+    rng = np.random.default_rng(F)
+    Z = rng.standard_normal((n, F)).astype(np.float32)
+    g = rng.standard_normal((n, F)).astype(np.float32)
+    slope = torch.tensor([0.25], device="cuda")
+    Zd, gd = padded(B, Z), padded(B, g)
+    Y = B.tma_prelu_fwd(Zd, slope)
+    dZ, ds = B.tma_prelu_bwd(Zd, gd, slope)
+    wZ, ws_ = oracle.prelu_bwd(Z, g, 0.25)
+    if n:
+        close(host(Y), oracle.prelu_fwd(Z, 0.25), 1e-7, "Y")
+        close(host(dZ), wZ, 1e-7, "dZ")
+    assert abs(ds.item() - ws_) <= 1e-4 * max(np.abs(g * Z).sum(), 1e-30) + 1e-30
+    inplace, ds2 = B.tma_prelu_bwd(Zd, gd, slope, dZ_out=gd)
+    assert torch.equal(inplace, dZ) and torch.equal(ds2, ds)
+    if n:
+        Zb, gb = synth.round_bf16(Z), synth.round_bf16(g)
+        Yb = B.tma_prelu_fwd(padded(B, Zb, True), slope)
+        close(host(Yb), oracle.prelu_fwd(Zb, 0.25), 2e-2, "Y bf16")
+        dZb, dsb = B.tma_prelu_bwd(padded(B, Zb, True), padded(B, gb, True), slope)
+        close(host(dZb), oracle.prelu_bwd(Zb, gb, 0.25)[0], 2e-2, "dZ bf16")
+
+
+@pytest.mark.parametrize("count,n_pos", [(2000, 1000), (131_072, 65_536), (1, 1), (7, 0), (0, 0)])
+def test_bce_logits(B, count, n_pos):
+    rng = np.random.default_rng(count)
+    z = rng.normal(0, 3, (count, 1)).astype(np.float32)
+    if count > 4:
+        z[:4, 0] = [60.0, -60.0, 0.0, 90.0]
+    zd = padded(B, z)
+    loss, dz = B.tma_bce_logits(zd, n_pos)
+    wl, wd = oracle.bce_logits(z, n_pos)
+    assert abs(loss.item() - wl) <= 1e-5 * max(abs(wl), 1e-30) + 1e-30
+    if count:
+        close(host(dz), wd.reshape(-1, 1), 1e-5, "dz")
+    loss2, none = B.tma_bce_logits(zd, n_pos, need_grad=False)
+    assert none is None and torch.equal(loss2, loss)
