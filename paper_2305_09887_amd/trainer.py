@@ -23,11 +23,26 @@ class LocalTrainer:
     W_neigh, bias -- W, bias for GCN and MLP -- and with ``norm_act`` gamma, beta, slope of the hidden layers),
     gradients in ``dW`` with the same layout, so that the optimizer step and the
     averaging operator are single launches.
+
+    With ``decoder_dims`` = [F_L, D_1, ..., 1] the task is link prediction (Sec. 4.1; App., formulation of the MLP
+    decoder) instead of node classification: each step draws ``batch_size`` positive local edges and one
+    random-tail negative each (counter-based, ``batch_seed``), multiplies the encoder's embeddings of the two
+    ends, runs the MLP decoder (PReLU between its layers, no bias) and takes the mean binary cross-entropy of its
+    logits; ``labels`` is then unused.  The decoder's weights (Theta_k, and a slope per hidden layer) follow the
+    encoder's in ``W``, so they are averaged with them.
     """
 
     def __init__(self, rowptr, colidx, inv_deg, X, labels, dims, params=None, stream=None,
-                 rowptr_T=None, colidx_T=None, norm_act=False, optimizer="sgd", encoder="sage"):
+                 rowptr_T=None, colidx_T=None, norm_act=False, optimizer="sgd", encoder="sage",
+                 decoder_dims=None, batch_size=0, batch_seed=0, nnz=None):
         self.norm_act = bool(norm_act)
+        self.dec_dims = list(decoder_dims) if decoder_dims is not None else None
+        if self.dec_dims is not None:
+            if self.dec_dims[0] != dims[-1] or self.dec_dims[-1] != 1 or len(self.dec_dims) < 2 or batch_size < 1:
+                raise B.TmaError("LocalTrainer: decoder_dims must run from dims[-1] to 1, with a batch size")
+            if nnz is None:
+                raise B.TmaError("LocalTrainer: the link task needs the local entry count nnz")
+        self.batch_size, self.batch_seed, self.nnz = int(batch_size), int(batch_seed), nnz
         if encoder not in ("sage", "gcn", "mlp"):
             raise B.TmaError("LocalTrainer: encoder must be 'sage', 'gcn' or 'mlp'")
         self.encoder = encoder
@@ -53,9 +68,11 @@ class LocalTrainer:
         self.n_params = sum(n_w * fi * fo + fo for fi, fo in zip(dims[:-1], dims[1:]))
         if self.norm_act:
             self.n_params += sum(2 * fo + 1 for fo in dims[1:-1])
+        if self.dec_dims is not None:
+            self.n_params += sum(a * b for a, b in zip(self.dec_dims[:-1], self.dec_dims[1:])) + len(self.dec_dims) - 2
         self.W = torch.zeros(self.n_params, dtype=torch.float32, device=dev)
         self.dW = torch.zeros(self.n_params, dtype=torch.float32, device=dev)
-        self.layers, self.grads = self._views(self.W), self._views(self.dW)
+        (self.layers, self.dec_layers), (self.grads, self.dec_grads) = self._views(self.W), self._views(self.dW)
         if optimizer == "adam":   # moment estimates: this trainer's own state, never averaged
             self.adam_m = torch.zeros_like(self.W)
             self.adam_v = torch.zeros_like(self.W)
@@ -89,12 +106,25 @@ class LocalTrainer:
         ws_bytes = max(ws_bytes, B.tma_loss_workspace_bytes(self.n, dims[-1]))
         if self.norm_act and self.L > 1:
             ws_bytes = max(ws_bytes, max(B.tma_layernorm_prelu_bwd_workspace_bytes(self.n, f) for f in dims[1:-1]))
+        if self.dec_dims is not None:
+            Bn, dd = self.batch_size, self.dec_dims
+            self.batch = tuple(torch.empty(Bn, dtype=torch.int32, device=dev) for _ in range(3))   # u, v, v'
+            # E[k]: input of decoder layer k (E[0] the pair products); Zd[k]: output of layer k-1 before its PReLU;
+            # dE[k]: gradient w.r.t. E[k], and, for k >= 1, w.r.t. Zd[k] once the PReLU's backward has run in place
+            self.E = [B._padded(2 * Bn, f, self.dtype, dev) for f in dd[:-1]]
+            self.Zd = [None] + [B._padded(2 * Bn, f, self.dtype, dev) for f in dd[1:]]
+            self.dE = [B._padded(2 * Bn, f, self.dtype, dev) for f in dd]
+            ws_bytes = max(ws_bytes, B.tma_pair_product_bwd_workspace_bytes(self.n, Bn, dd[0], dt),
+                           B.tma_prelu_bwd_workspace_bytes(), B.tma_bce_logits_workspace_bytes(),
+                           max(B.tma_dense_bwd_workspace_bytes(2 * Bn, a, b) for a, b in zip(dd[:-1], dd[1:])))
         self.ws = torch.empty(max(ws_bytes, 256), dtype=torch.uint8, device=dev)
         self.loss = torch.zeros(1, dtype=torch.float32, device=dev)
         self.steps_done = 0
 
-    def set_graph(self, rowptr, colidx, inv_deg, rowptr_T=None, colidx_T=None):
+    def set_graph(self, rowptr, colidx, inv_deg, rowptr_T=None, colidx_T=None, nnz=None):
         """Point the trainer at a freshly extracted subgraph with the same node count."""
+        if nnz is not None:
+            self.nnz = nnz
         if rowptr.numel() != self.n + 1 or inv_deg.numel() != self.n:
             raise B.TmaError("LocalTrainer.set_graph: node count differs from the allocated buffers")
         self.rowptr, self.colidx, self.inv_deg = rowptr, colidx, inv_deg
@@ -114,13 +144,24 @@ class LocalTrainer:
                 layer += [flat[o:o + fo], flat[o + fo:o + 2 * fo], flat[o + 2 * fo:o + 2 * fo + 1]]
                 o += 2 * fo + 1
             out.append(tuple(layer))
-        return out
+        dec = []
+        if self.dec_dims is not None:
+            K = len(self.dec_dims) - 1
+            for k, (a, b) in enumerate(zip(self.dec_dims[:-1], self.dec_dims[1:])):
+                layer = [flat[o:o + a * b].view(a, b)]; o += a * b
+                if k < K - 1:
+                    layer.append(flat[o:o + 1]); o += 1
+                dec.append(tuple(layer))
+        return out, dec
 
-    def load_params(self, params):
+    def load_params(self, params, decoder_params=None):
         """params: per layer (W_self, W_neigh, bias) -- (W, bias) for GCN and MLP -- or, for a normalised layer,
-        (..., gamma, beta, slope)."""
+        (..., gamma, beta, slope).  decoder_params: per decoder layer (Theta, slope), the last one (Theta,)."""
+        pairs = list(zip(self.layers, params))
+        if decoder_params is not None:
+            pairs += list(zip(self.dec_layers, decoder_params))
         with torch.cuda.stream(self.stream):
-            for mine, given in zip(self.layers, params):
+            for mine, given in pairs:
                 if len(mine) != len(given):
                     raise B.TmaError("LocalTrainer.load_params: layer has a different number of tensors")
                 for dst, src in zip(mine, given):
@@ -161,9 +202,42 @@ class LocalTrainer:
             self._layer_fwd(l, B.TMA_ACT_RELU if l < self.L - 1 else B.TMA_ACT_NONE, self.H[l + 1])
         return self.H[self.L]
 
+    def _decoder_forward(self):
+        """Mini-batch of this step, pair products, decoder layers; the logits end up in Zd[K]."""
+        u, v, vneg = self.batch
+        B.tma_edge_batch(self.rowptr, self.colidx, self.nnz, self.batch_seed, self.steps_done * self.batch_size,
+                         self.batch_size, u_out=u, v_out=v, vneg_out=vneg, stream=self.stream)
+        B.tma_pair_product_fwd(self.H[self.L], u, v, vneg, E0_out=self.E[0], stream=self.stream)
+        K = len(self.dec_dims) - 1
+        for k in range(K):
+            B.tma_dense_fwd(self.E[k], self.dec_layers[k][0], None, B.TMA_ACT_NONE, Y_out=self.Zd[k + 1],
+                            stream=self.stream)
+            if k < K - 1:
+                B.tma_prelu_fwd(self.Zd[k + 1], self.dec_layers[k][1], out=self.E[k + 1], stream=self.stream)
+        return self.Zd[K]
+
+    def _decoder_backward(self):
+        """Loss of the logits and the chain rule down to d(loss)/d(embeddings), left in dH[L]."""
+        K = len(self.dec_dims) - 1
+        u, v, vneg = self.batch
+        B.tma_bce_logits(self.Zd[K], self.batch_size, loss_out=self.loss, dz_out=self.dE[K], ws=self.ws,
+                         stream=self.stream)
+        for k in range(K - 1, -1, -1):
+            if k < K - 1:   # through the PReLU that follows layer k, in place
+                B.tma_prelu_bwd(self.Zd[k + 1], self.dE[k + 1], self.dec_layers[k][1], dZ_out=self.dE[k + 1],
+                                dslope=self.dec_grads[k][1], ws=self.ws, stream=self.stream)
+            B.tma_dense_bwd(self.E[k], None, self.dE[k + 1], self.dec_layers[k][0], B.TMA_ACT_NONE,
+                            dW=self.dec_grads[k][0], need_dbias=False, dX_out=self.dE[k], ws=self.ws,
+                            stream=self.stream)
+        B.tma_pair_product_bwd(self.H[self.L], u, v, vneg, self.dE[0], dR_out=self.dH[self.L], ws=self.ws,
+                               stream=self.stream)
+
     def backward(self):
-        B.tma_softmax_ce(self.H[self.L], self.labels, loss_out=self.loss, dlogits_out=self.dH[self.L],
-                         ws=self.ws, stream=self.stream)
+        if self.dec_dims is not None:
+            self._decoder_backward()
+        else:
+            B.tma_softmax_ce(self.H[self.L], self.labels, loss_out=self.loss, dlogits_out=self.dH[self.L],
+                             ws=self.ws, stream=self.stream)
         for l in range(self.L - 1, -1, -1):
             act = B.TMA_ACT_RELU if l < self.L - 1 else B.TMA_ACT_NONE
             out_act = self.H[l + 1]
@@ -179,6 +253,8 @@ class LocalTrainer:
     def step(self, lr: float):
         """One iteration of Alg. 2's loop body on the full local subgraph."""
         self.forward()
+        if self.dec_dims is not None:
+            self._decoder_forward()
         self.backward()
         if self.optimizer == "adam":
             B.tma_adam_step(self.W, self.dW, self.adam_m, self.adam_v, lr, self.steps_done + 1, stream=self.stream)

@@ -177,3 +177,55 @@ def test_bce_logits(B, count, n_pos):
         close(host(dz), wd.reshape(-1, 1), 1e-5, "dz")
     loss2, none = B.tma_bce_logits(zd, n_pos, need_grad=False)
     assert none is None and torch.equal(loss2, loss)
+
+
+@pytest.mark.parametrize("encoder,norm_act", [("sage", False), ("gcn", True), ("mlp", False), ("sage", True)])
+def test_link_prediction_training_steps(B, encoder, norm_act):
+    """Three link-prediction steps (2-layer encoder 64-96-32, decoder 32-48-1, 2048 positives per step) on the tiny
+    configuration's part 0: the drawn batch bit for bit, loss, every gradient of encoder and decoder, and the
+    weights after each SGD step against the oracle."""
+    from paper_2305_09887_amd.trainer import LocalTrainer
+    N, K, dims, dec_dims, Bn = 20_000, 4, [64, 96, 32], [32, 48, 1], 2048
+    rowptr, colidx = synth.uniform_graph(N, 100_000, seed=1)
+    X = synth.features(N, dims[0], seed=2)
+    rng = np.random.default_rng(7)
+    enc = []
+    for l, (Ws, Wn, b) in enumerate(synth.sage_params(dims, seed=5)):
+        layer = [Ws, Wn, b] if encoder == "sage" else [Ws, b]
+        if norm_act and l < len(dims) - 2:
+            layer += [rng.normal(1.0, 0.1, dims[l + 1]).astype(np.float32),
+                      rng.normal(0.0, 0.1, dims[l + 1]).astype(np.float32), np.array([0.25], dtype=np.float32)]
+        enc.append(tuple(layer))
+    dec = [(synth.glorot(32, 48, rng).astype(np.float32), np.array([0.25], np.float32)),
+           (synth.glorot(48, 1, rng).astype(np.float32),)]
+    sub = oracle.induced_subgraph(rowptr, colidx, oracle.partition(N, K, seed=4), 0)
+    rp, ci = sub["rowptr"], sub["colidx"]
+    Xo = X[sub["l2g"]]
+    tr = LocalTrainer(dev(rp), dev(ci), dev(sub["inv_deg"], torch.float32), dev(Xo), None, dims, params=enc,
+                      norm_act=norm_act, encoder=encoder, decoder_dims=dec_dims, batch_size=Bn, batch_seed=99,
+                      nnz=int(rp[-1]))
+    tr.load_params(enc, dec)
+    e_o = [tuple(np.asarray(t, dtype=np.float64) for t in l) for l in enc]
+    d_o = [tuple(np.asarray(t, dtype=np.float64) for t in l) for l in dec]
+    assert tr.n_params == omodel.flatten(e_o + d_o).size
+    lr, losses = 0.5, []
+    for step in range(3):
+        loss_g = tr.step(lr).item()
+        batch = oracle.edge_batch(rp, ci, 99, step * Bn, Bn)
+        for got, want in zip(tr.batch, batch):
+            assert np.array_equal(got.cpu().numpy(), want)
+        open_ = [host(tr.H[1]) > 0, None]
+        dec_open = [host(tr.E[1]) > 0]
+        loss_o, ge, gd, z = omodel.link_loss_and_grads(rp, ci, Xo, batch, e_o, d_o, encoder, open_, dec_open)
+        assert abs(loss_g - loss_o) <= 1e-4 * abs(loss_o), f"loss at step {step}"
+        close(host(tr.Zd[2]).ravel(), z, 1e-4, f"logits at step {step}")
+        for l in range(2):
+            for i, (g, w) in enumerate(zip(tr.grads[l], ge[l])):
+                close(host(g).ravel(), np.asarray(w).ravel(), 1e-4, f"step {step} encoder layer {l} gradient {i}")
+            for i, (g, w) in enumerate(zip(tr.dec_grads[l], gd[l])):
+                close(host(g).ravel(), np.asarray(w).ravel(), 1e-4, f"step {step} decoder layer {l} gradient {i}")
+        e_o = [tuple(oracle.sgd_step(w, g, lr).reshape(np.shape(w)) for w, g in zip(pl, gl)) for pl, gl in zip(e_o, ge)]
+        d_o = [tuple(oracle.sgd_step(w, g, lr).reshape(np.shape(w)) for w, g in zip(pl, gl)) for pl, gl in zip(d_o, gd)]
+        close(host(tr.W), omodel.flatten(e_o + d_o), 1e-4, f"weights after step {step}")
+        losses.append(loss_g)
+    assert losses[2] < losses[0]
