@@ -46,6 +46,32 @@ MEASURED_TRAFFIC_BYTES = {
 }
 
 
+def link_kernel_work(name, n, nnz, dims, dec_dims, Bn):
+    """Same for the link-prediction task with the SAGE encoder (both layers aggregate first), mean over the
+    launches of a step where a kernel name is launched with different shapes."""
+    F0, F1, F2 = dims
+    D0, D1, _ = dec_dims
+    s, rows = 4, 2 * Bn
+    gather = lambda F: 2.0 * n * F * s + nnz * 4 + n * 8          # rows once + ids + rowptr, 1/deg + output
+    table = {
+        "gemm_fwd_128x128": ("mfma", (2.0 * n * 2 * F0 * F1 + 2.0 * n * 2 * F1 * F2) / 2),
+        "gemm_bwd_weight_128x128": ("mfma", (2.0 * n * 2 * F0 * F1 + 2.0 * n * 2 * F1 * F2) / 2),
+        "gemm_bwd_data_128x128": ("mfma", 2.0 * n * F2 * 2 * F1),
+        "gemm_dense_fwd": ("mfma", (2.0 * rows * D0 * D1 + 2.0 * rows * D1) / 2),
+        "gemm_dense_bwd_weight": ("mfma", (2.0 * rows * D0 * D1 + 2.0 * rows * D1) / 2),
+        "gemm_dense_bwd_data": ("mfma", (2.0 * rows * D0 * D1 + 2.0 * rows * D1) / 2),
+        "spmm_mean_f32_g32x1": ("hbm", gather(F0)),
+        "spmm_mean_f32_g64x1": ("hbm", gather(F1)),
+        # dH1 += A^T dM (dM rows once, dH read and written) and dR = sum of each node's terms (4B rows of F2)
+        "spmm_sum_f32_g64x1": ("hbm", ((3.0 * n * F1 * s + nnz * 4 + n * 4) + (4.0 * Bn * F2 * s + 4 * Bn * 4 + n * 4 + n * F2 * s)) / 2),
+        "pair_product_fwd": ("hbm", 5.0 * Bn * F2 * s + 12.0 * Bn),        # three gathered rows read, two written
+        "pair_product_terms": ("hbm", 9.0 * Bn * F2 * s + 12.0 * Bn),      # + two gradient rows read, four written
+        "prelu_fwd": ("hbm", 2.0 * rows * D1 * s),
+        "prelu_bwd": ("hbm", 3.0 * rows * D1 * s),
+    }
+    return table.get(name.replace("_generic", ""), (None, 0.0))
+
+
 def kernel_work(name, n, nnz, dims, N=0, nnz_glob=0, K=1, n_params=0, encoder="sage"):
     """Algorithmic work of one launch of kernel `name` in this workload: ("mfma", flops) or ("hbm", bytes).
 
@@ -122,6 +148,10 @@ def main():
     ap.add_argument("--encoder", choices=("sage", "gcn", "mlp"), default="sage",
                     help="the paper's other encoders (GCN, graph-agnostic MLP); a second measurement, not the "
                          "headline workload")
+    ap.add_argument("--task", choices=("node", "link"), default="node",
+                    help="link: link prediction (edge mini-batch + random-tail negatives, MLP decoder on the pair "
+                         "products of 256-d embeddings, BCE) instead of node classification; a second measurement")
+    ap.add_argument("--batch", type=int, default=65536, help="positive edges per step of the link task")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="only run a plain 1 GiB device copy (reference for scaling rocprofv3 FETCH_SIZE/WRITE_SIZE)")
     args = ap.parse_args()
@@ -149,6 +179,10 @@ def main():
     w = WORKLOAD
     N, K, p = w["n_nodes"], w["K"], w["part"]
     dims = [w["F"], w["hidden"], w["classes"]]
+    dec_dims = None
+    if args.task == "link":      # hidden size 256 for encoder and decoder (the paper's setting for its mid-size graphs)
+        dims = [w["F"], w["hidden"], w["hidden"]]
+        dec_dims = [w["hidden"], w["hidden"], 1]
     L = len(dims) - 1
     sd = w["seeds"]
 
@@ -175,8 +209,16 @@ def main():
     if args.norm_act:   # gamma = 1, beta = 0, slope = 0.25 on the hidden layers
         params = [tuple(l) + ((np.ones(dims[i + 1], np.float32), np.zeros(dims[i + 1], np.float32),
                                np.full(1, 0.25, np.float32)) if i < L - 1 else ()) for i, l in enumerate(params)]
+    link = {}
+    if dec_dims is not None:
+        link = dict(decoder_dims=dec_dims, batch_size=args.batch, batch_seed=sd["part"] + 1, nnz=nnz_loc)
     tr = LocalTrainer(sub["rowptr"], sub["colidx"], sub["inv_deg"], Xl, yl, dims, params=params,
-                      norm_act=args.norm_act, encoder=args.encoder)
+                      norm_act=args.norm_act, encoder=args.encoder, **link)
+    if dec_dims is not None:
+        rng = np.random.default_rng(sd["weights"] + 1)
+        K_dec = len(dec_dims) - 1
+        tr.load_params(params, [(synth.glorot(a, b, rng),) + ((np.full(1, 0.25, np.float32),) if k < K_dec - 1 else ())
+                                for k, (a, b) in enumerate(zip(dec_dims[:-1], dec_dims[1:]))])
     peers = [tr.W.clone() for _ in range(K - 1)]      # the other K-1 trainers' parameter vectors
     W_all = [tr.W] + peers
     ptrs = torch.tensor([t.data_ptr() for t in W_all], dtype=torch.int64, device=dev)
@@ -189,7 +231,7 @@ def main():
         s = B.tma_induced_subgraph(d_rowptr, d_colidx, part, p, cap_n_loc=cap, cap_nnz_loc=cap_nnz)
         B.tma_gather_rows(s["l2g"], d_X, out=Xl)
         B.tma_gather_rows(s["l2g"], d_y, out=yl)
-        tr.set_graph(s["rowptr"], s["colidx"], s["inv_deg"])
+        tr.set_graph(s["rowptr"], s["colidx"], s["inv_deg"], nnz=s["nnz_loc"])
         tr.step(w["lr"])
         B.tma_average(W_all, W_global_out=W_global, ptr_table=ptrs)
 
@@ -219,7 +261,16 @@ def main():
     loss = float(tr.loss.item())
 
     kw = dict(N=N, nnz_glob=int(rowptr[-1]), K=K, n_params=int(tr.W.numel()), encoder=args.encoder)
-    bound, work = kernel_work(dominant, n_loc, nnz_loc, dims, **kw)
+    def work_of(k):
+        if args.task == "link" and args.encoder == "sage":
+            hit = link_kernel_work(k, n_loc, nnz_loc, dims, dec_dims, args.batch)
+            if hit[0]:
+                return hit
+        if args.task == "link" and k.startswith(("gemm", "spmm", "scale_mask", "softmax", "ln_prelu")):
+            return None, 0.0     # shapes of the link task that the tables do not cover
+        return kernel_work(k, n_loc, nnz_loc, dims, **kw)
+
+    bound, work = work_of(dominant)
     avg_ms = dom[1] / max(dom[0], 1)
     if bound == "mfma":
         achieved, peak, unit = work / (avg_ms * 1e-3) / 1e12, PEAK_MFMA_F32_TFLOPS, "TFLOP/s"
@@ -235,7 +286,7 @@ def main():
     # microseconds to a launch, so the short kernels read low; profiles/ holds the rocprofv3 durations)
     kernel_rooflines = {}
     for k, ms in per_step.items():
-        b, wk = kernel_work(k, n_loc, nnz_loc, dims, **kw)
+        b, wk = work_of(k)
         launches = prof[k][0] / 3.0
         if b is None or ms <= 0:
             continue
@@ -252,7 +303,8 @@ def main():
 
     value = L * nnz_loc / (ms_per_step * 1e-3)
     train_ms = sum(v for k, v in per_step.items()
-                   if k.startswith(("spmm", "gemm", "reduce", "softmax", "finish", "sgd", "ln_prelu", "scale_mask", "sum_partials")))
+                   if k.startswith(("spmm", "gemm", "reduce", "softmax", "finish", "sgd", "ln_prelu", "scale_mask", "sum_partials", "edge_batch",
+                                    "pair_product", "incidence", "exclusive_scan", "prelu", "bce")))
     out = {
         "metric": "trainer edges/sec per SAGE layer fwd+bwd; achieved HBM GB/s vs peak",
         "value": round(value, 1), "unit": "edges/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
@@ -263,7 +315,8 @@ def main():
                                "induced-subgraph extraction of part 0 + row gather + 2-layer mean-SAGE (hidden 256) "
                                "full-batch fwd+bwd+SGD + 8-way parameter averaging",
                    "n_nodes": N, "nnz_global": int(rowptr[-1]), "K": K, "n_loc": n_loc, "nnz_loc": nnz_loc,
-                   "layers": L, "dims": dims, "encoder": args.encoder, "hidden_activation": "layernorm+prelu" if args.norm_act else "relu", "edge_definition": "directed local CSR entry; value = layers*nnz_loc/step time"},
+                   "layers": L, "dims": dims, "task": args.task, "decoder_dims": dec_dims, "batch_positive_edges": args.batch if dec_dims else None,
+                   "encoder": args.encoder, "hidden_activation": "layernorm+prelu" if args.norm_act else "relu", "edge_definition": "directed local CSR entry; value = layers*nnz_loc/step time"},
         "roofline": roofline,
         "kernel_rooflines": kernel_rooflines,
         "kernel_ms_per_step": {k: round(v, 5) for k, v in sorted(per_step.items(), key=lambda kv: -kv[1])},
@@ -271,7 +324,7 @@ def main():
         "final_loss": loss,
     }
 
-    if not args.no_cpu_baseline:
+    if not args.no_cpu_baseline and args.task == "node":
         import oracle
         from oracle import model as omodel
         t_cpu = time.perf_counter()

@@ -171,54 +171,93 @@ __global__ __launch_bounds__(256) void incidence_fill_kernel(int64_t B, const in
     unsorted[rowptr[t] + atomicAdd(&cursor[t], 1)] = int32_t(j);
 }
 
-// sorted[range of node] = the node's term numbers in ascending order.  A thread sorts a range of up to 8 by
-// insertion; longer ranges are ranked by a whole wavefront (the numbers are distinct: the rank of a number is
-// the count of smaller ones).
+// sorted[range of node] = the node's term numbers in ascending order.  First kernel: a thread sorts a range of
+// up to 8 by insertion and queues longer ranges.  Second kernel: a wavefront per queued range ranks its numbers
+// (they are distinct: the rank of a number is the count of smaller ones) from a copy in LDS.  The queue's order
+// does not matter: every range is sorted independently.
 constexpr int kShortList = 8;
+constexpr int kRankLds = 2048;     // entries of a range that fit a wavefront's LDS segment
 
-__global__ __launch_bounds__(256) void incidence_sort_kernel(int64_t n, const int32_t *__restrict__ rowptr,
-                                                             const int32_t *__restrict__ unsorted,
-                                                             int32_t *__restrict__ sorted)
+__global__ __launch_bounds__(256) void incidence_sort_short_kernel(int64_t n, const int32_t *__restrict__ rowptr,
+                                                                   const int32_t *__restrict__ unsorted,
+                                                                   int32_t *__restrict__ sorted,
+                                                                   int32_t *__restrict__ long_rows,
+                                                                   int32_t *__restrict__ n_long)
 {
-    __shared__ int32_t long_rows[256];
-    __shared__ int32_t n_long;
-    if (threadIdx.x == 0) n_long = 0;
-    __syncthreads();
     const int64_t r = int64_t(blockIdx.x) * 256 + threadIdx.x;
+    const int lane = threadIdx.x % kWave;
+    int32_t beg = 0, len = 0;
     if (r < n) {
-        const int32_t beg = rowptr[r], len = rowptr[r + 1] - beg;
-        if (len > kShortList) {
-            long_rows[atomicAdd(&n_long, 1)] = int32_t(threadIdx.x);
-        } else if (len > 0) {
-            int32_t a[kShortList];
-#pragma unroll
-            for (int k = 0; k < kShortList; ++k) a[k] = k < len ? unsorted[beg + k] : INT32_MAX;
-#pragma unroll
-            for (int k = 1; k < kShortList; ++k)
-#pragma unroll
-                for (int m = k; m > 0; --m)
-                    if (a[m] < a[m - 1]) {
-                        const int32_t t = a[m];
-                        a[m] = a[m - 1];
-                        a[m - 1] = t;
-                    }
-#pragma unroll
-            for (int k = 0; k < kShortList; ++k)
-                if (k < len) sorted[beg + k] = a[k];
-        }
+        beg = rowptr[r];
+        len = rowptr[r + 1] - beg;
     }
-    __syncthreads();
+    // one queue reservation per wavefront, not per range (the ranges of hub nodes sit next to each other)
+    const bool is_long = len > kShortList;
+    const uint64_t longs = __ballot(is_long);
+    if (longs != 0) {
+        const int leader = __ffsll(static_cast<long long>(longs)) - 1;
+        int32_t first = 0;
+        if (lane == leader) first = atomicAdd(n_long, int32_t(__popcll(longs)));
+        first = __shfl(first, leader, kWave);
+        if (is_long) long_rows[first + __popcll(longs & ((uint64_t(1) << lane) - 1))] = int32_t(r);
+    }
+    if (!is_long && len > 0) {
+        int32_t a[kShortList];
+#pragma unroll
+        for (int k = 0; k < kShortList; ++k) a[k] = k < len ? unsorted[beg + k] : INT32_MAX;
+#pragma unroll
+        for (int k = 1; k < kShortList; ++k)
+#pragma unroll
+            for (int m = k; m > 0; --m)
+                if (a[m] < a[m - 1]) {
+                    const int32_t t = a[m];
+                    a[m] = a[m - 1];
+                    a[m - 1] = t;
+                }
+#pragma unroll
+        for (int k = 0; k < kShortList; ++k)
+            if (k < len) sorted[beg + k] = a[k];
+    }
+}
+
+__global__ __launch_bounds__(256) void incidence_sort_long_kernel(const int32_t *__restrict__ rowptr,
+                                                                  const int32_t *__restrict__ unsorted,
+                                                                  int32_t *__restrict__ sorted,
+                                                                  const int32_t *__restrict__ long_rows,
+                                                                  const int32_t *__restrict__ n_long)
+{
+    __shared__ __attribute__((aligned(16))) int32_t stage[256 / kWave][kRankLds];
     const int lane = threadIdx.x % kWave, wave = threadIdx.x / kWave;
-    const int count = n_long;
-    for (int q = wave; q < count; q += 256 / kWave) {
-        const int64_t row = int64_t(blockIdx.x) * 256 + long_rows[q];
+    const int count = *n_long;
+    const int waves = gridDim.x * (256 / kWave);
+    for (int q = blockIdx.x * (256 / kWave) + wave; q < count; q += waves) {
+        const int32_t row = long_rows[q];
         const int32_t beg = rowptr[row], len = rowptr[row + 1] - beg;
+        const bool in_lds = len <= kRankLds;
+        const int32_t len4 = (len + 3) & ~3;   // padded with the largest number, which is smaller than nothing
+        if (in_lds)
+            for (int32_t k = lane; k < len4; k += kWave) stage[wave][k] = k < len ? unsorted[beg + k] : INT32_MAX;
+        // a wavefront's LDS accesses complete in program order: its own writes above are visible to the reads below
+        __builtin_amdgcn_wave_barrier();
         for (int32_t k = lane; k < len; k += kWave) {
-            const int32_t mine = unsorted[beg + k];
             int32_t rank = 0;
-            for (int32_t m = 0; m < len; ++m) rank += unsorted[beg + m] < mine ? 1 : 0;
-            sorted[beg + rank] = mine;
+            if (in_lds) {
+                const int32_t mine = stage[wave][k];
+                const int4 *quads = reinterpret_cast<const int4 *>(&stage[wave][0]);
+#pragma unroll 4
+                for (int32_t m = 0; m < len4 / 4; ++m) {   // four numbers per LDS read, several reads in flight
+                    const int4 t = quads[m];
+                    rank += (t.x < mine ? 1 : 0) + (t.y < mine ? 1 : 0) + (t.z < mine ? 1 : 0) + (t.w < mine ? 1 : 0);
+                }
+                sorted[beg + rank] = mine;
+            } else {
+                const int32_t mine = unsorted[beg + k];
+#pragma unroll 8
+                for (int32_t m = 0; m < len; ++m) rank += unsorted[beg + m] < mine ? 1 : 0;
+                sorted[beg + rank] = mine;
+            }
         }
+        __builtin_amdgcn_wave_barrier();   // before the segment is overwritten by the next range
     }
 }
 
@@ -325,7 +364,7 @@ static PairBwdWorkspace plan_pair_bwd(int64_t n, int64_t B, int32_t F, int32_t d
     PairBwdWorkspace w;
     const size_t b = size_t(B > 0 ? B : 1), rows = size_t(n > 0 ? n : 1);
     w.terms_bytes = round_up(4 * b * size_t(pad_cols(F, dtype)) * elem_size(dtype), 256);
-    w.deg_bytes = round_up(2 * rows * 4, 256);          // per-node counts, then the fill cursors
+    w.deg_bytes = round_up((2 * rows + 1) * 4, 256);    // per-node counts (later the queue of long lists), fill cursors, queue length
     w.rowptr_bytes = round_up((rows + 1) * 4, 256);
     w.list_bytes = round_up(4 * b * 4, 256);            // unsorted and sorted term lists
     w.scan_bytes = exclusive_scan_i32_workspace_bytes(n);
@@ -429,8 +468,9 @@ extern "C" int tma_pair_product_bwd(int64_t n, int64_t B, int32_t F, const void 
     const int Fc = pad_cols(F, dtype);
 
     {
-        TMA_TIMED("incidence_build", s);
-        hipLaunchKernelGGL(fill_zero_i32_kernel, dim3(capped_blocks(ceil_div(2 * n, 256))), dim3(256), 0, s, 2 * n, deg);
+        TMA_TIMED("incidence_count", s);
+        hipLaunchKernelGGL(fill_zero_i32_kernel, dim3(capped_blocks(ceil_div(2 * n + 1, 256))), dim3(256), 0, s, 2 * n + 1,
+                           deg);
         if (B > 0)
             hipLaunchKernelGGL(incidence_count_kernel, dim3(unsigned(ceil_div(B, 256))), dim3(256), 0, s, B, u, v, vneg,
                                deg);
@@ -439,11 +479,20 @@ extern "C" int tma_pair_product_bwd(int64_t n, int64_t B, int32_t F, const void 
     if (int rc = launch_exclusive_scan_i32(n, deg, rowptr, scan_ws, s)) return rc;
     if (B > 0) {
         {
-            TMA_TIMED("incidence_build", s);
+            TMA_TIMED("incidence_fill", s);
             hipLaunchKernelGGL(incidence_fill_kernel, dim3(unsigned(ceil_div(4 * B, 256))), dim3(256), 0, s, B, u, v, vneg,
                                rowptr, cursor, unsorted);
-            hipLaunchKernelGGL(incidence_sort_kernel, dim3(unsigned(ceil_div(n, 256))), dim3(256), 0, s, n, rowptr,
-                               unsorted, sorted);
+        }
+        {
+            TMA_TIMED("incidence_sort_short", s);
+            // the per-node counts are spent once the scan has run: their array takes the queue of long lists
+            hipLaunchKernelGGL(incidence_sort_short_kernel, dim3(unsigned(ceil_div(n, 256))), dim3(256), 0, s, n, rowptr,
+                               unsorted, sorted, deg, deg + 2 * n);
+        }
+        {
+            TMA_TIMED("incidence_sort_long", s);
+            hipLaunchKernelGGL(incidence_sort_long_kernel, dim3(1024), dim3(256), 0, s, rowptr, unsorted, sorted, deg,
+                               deg + 2 * n);
         }
         TMA_TIMED("pair_product_terms", s);
         if (dtype == TMA_F32) {
