@@ -69,3 +69,81 @@ def test_configs1_whole_path_against_oracle():
             _close(g.cpu().numpy(), w, f"layer {l} {name}")
     new_o = [tuple(oracle.sgd_step(w, g, lr).reshape(np.shape(w)) for w, g in zip(pl, gl)) for pl, gl in zip(p_o, grads_o)]
     _close(tr.W.cpu().numpy(), omodel.flatten(new_o), "weights after the step", tol=1e-6)
+
+
+@pytest.fixture(scope="module")
+def configs1_part0():
+    """The quoted workload's graph, features and part 0 (oracle side), shared by the tests below."""
+    N, K = 1_000_000, 8
+    rowptr, colidx = synth.chung_lu_graph(N, 20, 2.1, seed=11)
+    X = synth.features(N, 128, seed=12)
+    sub_o = oracle.induced_subgraph(rowptr, colidx, oracle.partition(N, K, seed=14), 0)
+    return sub_o, X[sub_o["l2g"]], synth.labels(N, 47, seed=13)[sub_o["l2g"]]
+
+
+def test_configs1_gcn_step_against_oracle(configs1_part0):
+    """The GCN encoder (Sec. 4.1) at the same size and launch configuration as `bench.py --encoder gcn`:
+    layer 0 (128 -> 256) aggregates first, layer 1 (256 -> 47) transforms first."""
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    from paper_2305_09887_amd import binding as B
+    from paper_2305_09887_amd.trainer import LocalTrainer
+    sub_o, Xo, yo = configs1_part0
+    dims, lr = [128, 256, 47], 1e-3
+    params = [(Ws, b) for Ws, _, b in synth.sage_params(dims, seed=15)]
+    d = lambda a, dt=None: (torch.as_tensor(a) if dt is None else torch.as_tensor(a).to(dt)).cuda()
+    assert B.tma_gcn_layer_aggregates_first(128, 256, B.TMA_F32) and not B.tma_gcn_layer_aggregates_first(256, 47, B.TMA_F32)
+    tr = LocalTrainer(d(sub_o["rowptr"]), d(sub_o["colidx"]), d(sub_o["inv_deg"], torch.float32), d(Xo), d(yo), dims,
+                      params=params, encoder="gcn")
+    loss_g = tr.step(lr).item()
+    p_o = [tuple(np.asarray(t, dtype=np.float64) for t in l) for l in params]
+    relu_open = [tr.H[1].cpu().numpy() > 0, None]
+    loss_o, grads_o, logits_o, saved = omodel.loss_and_grads(sub_o["rowptr"], sub_o["colidx"], Xo, yo, p_o, relu_open,
+                                                             "gcn")
+    flips = int((relu_open[0] != (saved[0][2] > 0)).sum())
+    assert flips <= 1e-5 * relu_open[0].size
+    assert abs(loss_g - loss_o) <= TOL * abs(loss_o)
+    _close(tr.M[0].cpu().numpy(), saved[0][1], "Ahat H of layer 0")
+    _close(tr.H[2].cpu().numpy(), logits_o, "logits")
+    for l in range(2):
+        for g, w, name in zip(tr.grads[l], grads_o[l], ("dW", "dbias")):
+            _close(g.cpu().numpy(), w, f"layer {l} {name}")
+    new_o = [tuple(oracle.sgd_step(w, g, lr).reshape(np.shape(w)) for w, g in zip(pl, gl)) for pl, gl in zip(p_o, grads_o)]
+    _close(tr.W.cpu().numpy(), omodel.flatten(new_o), "weights after the step", tol=1e-6)
+
+
+def test_configs1_link_prediction_step_against_oracle(configs1_part0):
+    """The link-prediction task at the size and launch configuration of `bench.py --task link`: SAGE 128-256-256,
+    decoder 256-256-1, 65,536 positives and as many negatives; the batch bit for bit, logits, loss, every gradient."""
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    from paper_2305_09887_amd.trainer import LocalTrainer
+    sub_o, Xo, _ = configs1_part0
+    rp, ci = sub_o["rowptr"], sub_o["colidx"]
+    dims, dec_dims, Bn, lr = [128, 256, 256], [256, 256, 1], 65_536, 1e-3
+    enc = synth.sage_params(dims, seed=15)
+    rng = np.random.default_rng(16)
+    dec = [(synth.glorot(256, 256, rng).astype(np.float32), np.array([0.25], np.float32)),
+           (synth.glorot(256, 1, rng).astype(np.float32),)]
+    d = lambda a, dt=None: (torch.as_tensor(a) if dt is None else torch.as_tensor(a).to(dt)).cuda()
+    tr = LocalTrainer(d(rp), d(ci), d(sub_o["inv_deg"], torch.float32), d(Xo), None, dims, params=enc,
+                      decoder_dims=dec_dims, batch_size=Bn, batch_seed=15, nnz=int(rp[-1]))
+    tr.load_params(enc, dec)
+    loss_g = tr.step(lr).item()
+    batch = oracle.edge_batch(rp, ci, 15, 0, Bn)
+    for got, want in zip(tr.batch, batch):
+        assert np.array_equal(got.cpu().numpy(), want)
+    counts = np.bincount(np.concatenate([batch[0], batch[0], batch[1], batch[2]]), minlength=len(rp) - 1)
+    assert counts.max() > 256 and (counts == 0).mean() > 0.2      # long and empty per-node term lists are in the case
+    e_o = [tuple(np.asarray(t, dtype=np.float64) for t in l) for l in enc]
+    d_o = [tuple(np.asarray(t, dtype=np.float64) for t in l) for l in dec]
+    open_ = [tr.H[1].cpu().numpy() > 0, None]
+    dec_open = [tr.E[1].cpu().numpy() > 0]
+    loss_o, ge, gd, z = omodel.link_loss_and_grads(rp, ci, Xo, batch, e_o, d_o, "sage", open_, dec_open)
+    assert abs(loss_g - loss_o) <= TOL * abs(loss_o)
+    _close(tr.Zd[2].cpu().numpy().ravel(), z, "logits")
+    for l in range(2):
+        for g, w, name in zip(tr.grads[l], ge[l], ("dW_self", "dW_neigh", "dbias")):
+            _close(g.cpu().numpy(), w, f"encoder layer {l} {name}")
+        for g, w, name in zip(tr.dec_grads[l], gd[l], ("dTheta", "dslope")):
+            _close(g.cpu().numpy().ravel(), np.asarray(w).ravel(), f"decoder layer {l} {name}")
