@@ -32,17 +32,17 @@ WORKLOAD = dict(n_nodes=1_000_000, avg_degree=20, gamma=2.1, K=8, part=0, F=128,
 # (profiles/bench_configs1_hbm_traffic.txt): (FETCH_SIZE * 2.0 + WRITE_SIZE * 1.0) KiB, the factors being what the
 # same counters read for a plain 1 GiB device copy (FETCH_SIZE reports half the bytes read, WRITE_SIZE all written).
 MEASURED_TRAFFIC_BYTES = {
-    "gemm_bwd_weight_128x128": (230097 * 2.0 + 34671) * 1024,
-    "gemm_fwd_128x128": (68527 * 2.0 + 125237) * 1024,
-    "gemm_tf_fwd": (63682 * 2.0 + 46984) * 1024,
-    "gemm_tf_bwd_weight": (87522 * 2.0 + 23612) * 1024,
-    "gemm_tf_bwd_data": (24594 * 2.0 + 125237) * 1024,
-    "spmm_mean_f32_g32x1": (55743 * 2.0 + 62618) * 1024,
-    "spmm_combine_f32_g12x1": (42987 * 2.0 + 24981) * 1024,
-    "spmm_sum_f32_g12x1": (25502 * 2.0 + 24421) * 1024,
+    "gemm_bwd_weight_128x128": (230384 * 2.0 + 34671) * 1024,
+    "gemm_fwd_128x128": (68518 * 2.0 + 125237) * 1024,
+    "gemm_tf_fwd": (63665 * 2.0 + 46984) * 1024,
+    "gemm_tf_bwd_weight": (87546 * 2.0 + 23612) * 1024,
+    "gemm_tf_bwd_data": (24533 * 2.0 + 125237) * 1024,
+    "spmm_mean_f32_g32x1": (55748 * 2.0 + 62618) * 1024,
+    "spmm_combine_f32_g12x1": (42899 * 2.0 + 24979) * 1024,
+    "spmm_sum_f32_g12x1": (25532 * 2.0 + 24447) * 1024,
     "gather_rows_w16": (31577 * 2.0 + 62618) * 1024,
-    "row_fill": (20809 * 2.0 + 1926) * 1024,
-    "row_count": (12037 * 2.0 + 490) * 1024,
+    "row_fill": (20812 * 2.0 + 1926) * 1024,
+    "row_count": (12038 * 2.0 + 490) * 1024,
 }
 
 
