@@ -120,9 +120,10 @@ def sage_layer_fwd(rowptr, colidx, H, W_self, W_neigh, bias, act: int):
     """Returns (M, Z, Hnext) of one mean-SAGE layer."""
     rowptr, colidx = _i32(rowptr), _i32(colidx)
     H, W_self, W_neigh, bias = _f64(H), _f64(W_self), _f64(W_neigh), _f64(bias)
-    n, F_in = H.shape
+    n, F_in = rowptr.shape[0] - 1, H.shape[1]      # a bipartite block has fewer rows than H: its first n rows are the dst nodes
     F_out = W_self.shape[1]
     assert W_self.shape == (F_in, F_out) and W_neigh.shape == (F_in, F_out) and bias.shape == (F_out,)
+    assert n <= H.shape[0]
     M = np.empty((n, F_in))
     Z = np.empty((n, F_out))
     Hn = np.empty((n, F_out))
@@ -133,16 +134,17 @@ def sage_layer_fwd(rowptr, colidx, H, W_self, W_neigh, bias, act: int):
 
 
 def sage_layer_bwd(rowptr, colidx, H, M, Z, dHnext, W_self, W_neigh, act: int, need_dH=True):
-    """Returns (dW_self, dW_neigh, dbias, dH or None)."""
+    """Returns (dW_self, dW_neigh, dbias, dH or None).  On a bipartite block (H has more rows than the graph:
+    the first n are the destination nodes) dH covers all rows of H."""
     rowptr, colidx = _i32(rowptr), _i32(colidx)
     H, M, Z, dHnext = _f64(H), _f64(M), _f64(Z), _f64(dHnext)
     W_self, W_neigh = _f64(W_self), _f64(W_neigh)
-    n, F_in = H.shape
+    n, F_in = M.shape
     F_out = W_self.shape[1]
     dWs = np.empty((F_in, F_out))
     dWn = np.empty((F_in, F_out))
     db = np.empty(F_out)
-    dH = np.empty((n, F_in)) if need_dH else None
+    dH = np.zeros((H.shape[0], F_in)) if need_dH else None     # rows past n only receive scattered terms
     sM = np.empty((n, F_in))
     sZ = np.empty((n, F_out))
     lib().orc_sage_layer_bwd(C.c_int64(n), _p(rowptr), _p(colidx), _p(H), _p(M), _p(Z), _p(dHnext),
@@ -359,3 +361,25 @@ def bce_logits(z, n_pos: int, need_grad=True):
     dz = np.empty_like(z) if need_grad else None
     loss = lib().orc_bce_logits(C.c_int64(z.size), C.c_int64(n_pos), _p(z), _p(dz))
     return float(loss), dz
+
+
+# ------------------------------------------------ sampled message-flow graphs (Sec. 4.1)
+def neighbor_sample(dst, rowptr, colidx, fanout: int, seed: int):
+    """Block CSR over the local ids: per dst node all its neighbours, or a uniform `fanout`-subset of them."""
+    dst, rowptr, colidx = _i32(dst), _i32(rowptr), _i32(colidx)
+    n_dst = dst.shape[0]
+    brp = np.empty(n_dst + 1, dtype=np.int32)
+    bci = np.empty(max(n_dst * fanout, 1), dtype=np.int32)
+    lib().orc_neighbor_sample(C.c_int64(n_dst), _p(dst), _p(rowptr), _p(colidx), C.c_int32(fanout), C.c_uint64(seed),
+                              _p(brp), _p(bci))
+    return brp, bci[:brp[-1]].copy()
+
+
+def mfg_relabel(dst, blk_col):
+    """Source node list of a block: the dst nodes first, in their order, then the other sampled nodes in
+    ascending id order; and the block's columns as positions in that list.  Returns (src, blk_col_positions)."""
+    dst, blk_col = _i32(dst), _i32(blk_col)
+    new = np.setdiff1d(blk_col, dst)                   # sorted, unique
+    src = np.concatenate([dst, new]).astype(np.int32)
+    pos = {int(g): i for i, g in enumerate(src.tolist())}
+    return src, np.fromiter((pos[int(c)] for c in blk_col.tolist()), dtype=np.int32, count=blk_col.shape[0])

@@ -10,8 +10,8 @@ from __future__ import annotations
 import numpy as np
 
 from . import (ACT_NONE, ACT_RELU, adam_step, average, bce_logits, dense_bwd, dense_fwd, gcn_layer_bwd, gcn_layer_fwd,
-               layernorm_prelu_bwd, layernorm_prelu_fwd, pair_product_bwd, pair_product_fwd, prelu_bwd, prelu_fwd,
-               sage_layer_bwd, sage_layer_fwd, sgd_step, softmax_ce)
+               layernorm_prelu_bwd, layernorm_prelu_fwd, mfg_relabel, mix64, neighbor_sample, pair_product_bwd,
+               pair_product_fwd, prelu_bwd, prelu_fwd, sage_layer_bwd, sage_layer_fwd, sgd_step, softmax_ce)
 
 ACT_LN_PRELU = "ln_prelu"   # a layer whose parameter tuple ends with (gamma, beta, slope)
 
@@ -53,7 +53,10 @@ def forward(rowptr, colidx, X, params, encoder="sage"):
     saved = []
     L = len(params)
     nl = n_linear(encoder)
+    per_layer = isinstance(rowptr, (list, tuple))     # one bipartite block per layer (a sampled message-flow graph)
+    graphs = (rowptr, colidx)
     for l, layer in enumerate(params):
+        rowptr, colidx = (graphs[0][l], graphs[1][l]) if per_layer else graphs
         lin = layer[:nl]
         if len(layer) == nl + 3:
             M, Z, _ = _layer_fwd(encoder, rowptr, colidx, H, lin, ACT_NONE)
@@ -72,7 +75,10 @@ def backward(rowptr, colidx, params, saved, d, relu_open=None, encoder="sage", n
     to the input features).  Returns (grads, dX or None)."""
     nl = n_linear(encoder)
     grads = [None] * len(params)
+    per_layer = isinstance(rowptr, (list, tuple))
+    graphs = (rowptr, colidx)
     for l in range(len(params) - 1, -1, -1):
+        rowptr, colidx = (graphs[0][l], graphs[1][l]) if per_layer else graphs
         H, M, Z, act = saved[l]
         lin = params[l][:nl]
         forced = relu_open[l] if relu_open is not None else None
@@ -146,6 +152,57 @@ def link_loss_and_grads(rowptr, colidx, X, batch, enc_params, dec_params, encode
     dR = pair_product_bwd(R, batch[0], batch[1], batch[2], d)
     enc_grads, _ = backward(rowptr, colidx, enc_params, saved, dR, relu_open, encoder)
     return loss, enc_grads, dec_grads, z
+
+
+def layer_seed(seed: int, step: int, layer: int) -> int:
+    """Seed of the neighbour sampler for one step and one layer (this build's convention: at most 64 layers)."""
+    return mix64(seed, step * 64 + layer)
+
+
+def sample_mfg(rowptr, colidx, seeds, fanouts, seed: int, step: int):
+    """Message-flow graph of a mini-batch (Sec. 4.1: GraphSAGE sampler): starting from the batch's nodes `seeds`
+    (the dst nodes of the last layer), every layer l = L-1 .. 0 samples up to fanouts[l] neighbours per dst node;
+    its source nodes (dst first, then the new ones in ascending id) are the dst nodes of the layer below.
+    Returns (block rowptrs, block colidx in source positions, input node ids), lists indexed by layer."""
+    L = len(fanouts)
+    rps, cis = [None] * L, [None] * L
+    dst = np.asarray(seeds, dtype=np.int32)
+    for l in range(L - 1, -1, -1):
+        brp, bcol = neighbor_sample(dst, rowptr, colidx, fanouts[l], layer_seed(seed, step, l))
+        src, cols = mfg_relabel(dst, bcol)
+        rps[l], cis[l] = brp, cols
+        dst = src
+    return rps, cis, dst
+
+
+def sampled_link_loss_and_grads(rowptr, colidx, X, batch, enc_params, dec_params, fanouts, seed, step,
+                                relu_open=None, dec_open=None):
+    """The link-prediction step on the sampled message-flow graph of its batch (SAGE encoder): the encoder runs on
+    the bipartite blocks only, from the features of the sampled input nodes up to the embeddings of the batch's
+    nodes.  Returns (loss, enc_grads, dec_grads, logits, (rps, cis, input_nodes, seeds))."""
+    u, v, vneg = batch
+    seeds = np.unique(np.concatenate([u, v, vneg])).astype(np.int32)
+    rps, cis, inputs = sample_mfg(rowptr, colidx, seeds, fanouts, seed, step)
+    R, saved = forward(rps, cis, np.asarray(X)[inputs], enc_params, "sage")
+    pos = tuple(np.searchsorted(seeds, a).astype(np.int32) for a in (u, v, vneg))
+    z, dsaved = decoder_forward(R, pos, dec_params)
+    loss, dz = bce_logits(z, len(u))
+    d = dz.reshape(-1, 1)
+    K = len(dec_params)
+    dec_grads = [None] * K
+    for k in range(K - 1, -1, -1):
+        E, Z = dsaved[k]
+        extra = ()
+        if k < K - 1:
+            forced = dec_open[k] if dec_open is not None else None
+            d, ds = prelu_bwd(Z, d, float(np.asarray(dec_params[k][1]).ravel()[0]), open_mask=forced)
+            extra = (np.array([ds]),)
+        dTheta, _, dE = dense_bwd(E, Z, d, dec_params[k][0], ACT_NONE, need_dbias=False)
+        dec_grads[k] = (dTheta,) + extra
+        d = dE
+    dR = pair_product_bwd(R, pos[0], pos[1], pos[2], d)
+    enc_grads, _ = backward(rps, cis, enc_params, saved, dR, relu_open, "sage")
+    return loss, enc_grads, dec_grads, z, (rps, cis, inputs, seeds)
 
 
 def train_step(rowptr, colidx, X, y, params, lr, relu_open=None, encoder="sage"):

@@ -615,3 +615,41 @@ double orc_bce_logits(int64_t count, int64_t n_pos, const double *z, double *dz)
     }
     return count > 0 ? loss / (double)count : 0.0;
 }
+
+/* ------------------------------------------------------------------------
+ * Fan-out neighbour sampling for the message-flow graph of a mini-batch
+ * (Sec. 4.1, paragraph on mini-batch and negative sampling: the GraphSAGE
+ * sampler of Hamilton et al. 2017 caps the neighbours a node aggregates).
+ * A node with at most `fanout` local neighbours keeps them all; otherwise a
+ * uniformly random subset of exactly `fanout` distinct neighbours is kept.
+ * The paper fixes neither sizes nor generator; this build's written spec:
+ * entry e of the local CSR gets the key z(e) = mix64(seed, e); a row keeps the
+ * `fanout` entries with the smallest (key, e), listed in CSR order.  (Keys are
+ * i.i.d., so the kept set is a uniform subset; `seed` is the caller's per step
+ * and per layer.)
+ *   dst [n_dst]: the local nodes to sample for; blk_rowptr [n_dst+1];
+ *   blk_col: kept neighbours (local ids), at most n_dst * fanout.
+ * ---------------------------------------------------------------------- */
+void orc_neighbor_sample(int64_t n_dst, const int32_t *dst, const int32_t *rowptr, const int32_t *colidx,
+                         int32_t fanout, uint64_t seed, int32_t *blk_rowptr, int32_t *blk_col)
+{
+    int32_t out = 0;
+    blk_rowptr[0] = 0;
+    for (int64_t i = 0; i < n_dst; ++i) {
+        const int32_t beg = rowptr[dst[i]], end = rowptr[dst[i] + 1];
+        for (int32_t e = beg; e < end; ++e) {
+            int keep = 1;
+            if (end - beg > fanout) {          /* rank of (key, e) among the row's entries */
+                const uint64_t ke = orc_mix64(seed, (uint64_t)e);
+                int32_t smaller = 0;
+                for (int32_t o = beg; o < end; ++o) {
+                    const uint64_t ko = orc_mix64(seed, (uint64_t)o);
+                    if (ko < ke || (ko == ke && o < e)) ++smaller;
+                }
+                keep = smaller < fanout;
+            }
+            if (keep) blk_col[out++] = colidx[e];
+        }
+        blk_rowptr[i + 1] = out;
+    }
+}
