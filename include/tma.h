@@ -364,6 +364,82 @@ int tma_bce_logits(int64_t count, int64_t n_pos, const void *z, int64_t ldz, int
                    void *ws, size_t ws_bytes, tma_stream_t stream);
 
 /* ------------------------------------------------------------------------
+ * Sampled message-flow graphs (Sec. 4.1, paragraph on mini-batch and negative
+ * sampling: a GraphSAGE-style sampler caps the neighbours a node aggregates, so
+ * a step runs the encoder on the sampled neighbourhood of its batch only).
+ * All pointers device memory unless stated; ordered on `stream`; no allocation;
+ * deterministic.
+ *
+ * tma_neighbor_sample: for each of the n_dst DISTINCT local nodes dst[i], all its local
+ * neighbours if it has at most `fanout`, else a uniform subset of exactly
+ * `fanout` of them: entry e of the local CSR gets the key SplitMix64(seed, e)
+ * (the stream of tma_partition) and the row keeps the `fanout` smallest
+ * (key, e), in row order.  `seed` is the caller's per step and layer.
+ *   nnz            local entry count (host value); rowptr [n+1], colidx [nnz]
+ *   blk_rowptr_out [n_dst+1]; blk_col_out, blk_row_out [cap_entries]: kept
+ *                  neighbours (local ids) and the row i each belongs to;
+ *                  cap_entries >= min(n_dst * fanout, nnz), which distinct
+ *                  nodes cannot exceed (nothing is written past it).  The
+ *                  number of kept entries is blk_rowptr_out[n_dst] (stays on
+ *                  the device).
+ * Workspace: tma_neighbor_sample_workspace_bytes(n_dst), 256-byte aligned.
+ *
+ * tma_mfg_relabel: node list of a block.  src_out = the n_dst nodes of dst, in
+ * their order, followed by the other nodes that occur in cols, in ascending
+ * id; cols (max_items entries, of which the first *d_items count when d_items
+ * is not NULL) is overwritten with positions in src_out.  *h_n_src (HOST)
+ * receives the length of src_out: the call waits for the stream.  n = number
+ * of local nodes (ids < n); cap_src >= min(n, n_dst + max_items).  With
+ * n_dst = 0 this is "sorted unique ids + positions" (the nodes of a batch).
+ * Workspace: tma_mfg_relabel_workspace_bytes(n), 256-byte aligned.
+ *
+ * tma_block_inv_deg: inv_deg_out[i] = 1 / (entries of block row i), 0 for an
+ * empty row.
+ *
+ * tma_sage_block_fwd / _bwd: the mean-aggregation GraphSAGE layer of
+ * tma_sage_layer_fwd / _bwd on a bipartite block: n_dst output rows; H has
+ * n_src >= n_dst rows whose first n_dst are the dst nodes themselves; blk_col
+ * holds positions in [0, n_src).  M_out [n_dst, F_in] always receives Abar H
+ * (the block form always aggregates first).  The backward writes dH_out for
+ * all n_src rows (leading dimension ldh; NULL to skip) and builds the block's
+ * transpose itself (it needs blk_row and max_entries >= the entry count).
+ * Workspace: tma_sage_block_bwd_workspace_bytes(n_dst, n_src, max_entries,
+ * F_in, F_out, dtype, dH_out != NULL), 256-byte aligned.
+ * ---------------------------------------------------------------------- */
+size_t tma_neighbor_sample_workspace_bytes(int64_t n_dst);
+
+int tma_neighbor_sample(int64_t n_dst, const int32_t *dst, int64_t nnz, const int32_t *rowptr,
+                        const int32_t *colidx, int32_t fanout, uint64_t seed,
+                        int32_t *blk_rowptr_out, int32_t *blk_col_out, int32_t *blk_row_out,
+                        int64_t cap_entries, void *ws, size_t ws_bytes, tma_stream_t stream);
+
+size_t tma_mfg_relabel_workspace_bytes(int64_t n);
+
+int tma_mfg_relabel(int64_t n, int64_t n_dst, const int32_t *dst, int64_t max_items,
+                    const int32_t *d_items, int32_t *cols_inout, int32_t *src_out, int64_t cap_src,
+                    int64_t *h_n_src, void *ws, size_t ws_bytes, tma_stream_t stream);
+
+int tma_block_inv_deg(int64_t n_dst, const int32_t *blk_rowptr, float *inv_deg_out, tma_stream_t stream);
+
+int tma_sage_block_fwd(int64_t n_dst, int64_t n_src, const int32_t *blk_rowptr, const int32_t *blk_col,
+                       const float *inv_deg, const void *H, int64_t ldh, int32_t F_in,
+                       const float *W_self, const float *W_neigh, const float *bias,
+                       int32_t F_out, int32_t act, int32_t dtype,
+                       void *M_out, void *Hnext_out, int64_t ld_next, tma_stream_t stream);
+
+size_t tma_sage_block_bwd_workspace_bytes(int64_t n_dst, int64_t n_src, int64_t max_entries,
+                                          int32_t F_in, int32_t F_out, int32_t dtype, int32_t need_dH);
+
+int tma_sage_block_bwd(int64_t n_dst, int64_t n_src, int64_t max_entries,
+                       const int32_t *blk_rowptr, const int32_t *blk_col, const int32_t *blk_row,
+                       const float *inv_deg, const void *H, int64_t ldh, const void *M,
+                       const void *Hnext, const void *dHnext, int64_t ld_next,
+                       const float *W_self, const float *W_neigh, int32_t F_in, int32_t F_out,
+                       int32_t act, int32_t dtype,
+                       float *dW_self, float *dW_neigh, float *dbias, void *dH_out,
+                       void *ws, size_t ws_bytes, tma_stream_t stream);
+
+/* ------------------------------------------------------------------------
  * Losses on the last layer's output.
  * tma_softmax_ce: mean softmax cross-entropy over the n local nodes (reading
  *   taken for workloads with class labels); loss_out[0] fp32 (device),

@@ -31,6 +31,8 @@ EXPORTS = (
     "tma_edge_batch", "tma_pair_product_fwd", "tma_pair_product_bwd_workspace_bytes", "tma_pair_product_bwd",
     "tma_prelu_fwd", "tma_prelu_bwd_workspace_bytes", "tma_prelu_bwd", "tma_bce_logits_workspace_bytes",
     "tma_bce_logits",
+    "tma_neighbor_sample_workspace_bytes", "tma_neighbor_sample", "tma_mfg_relabel_workspace_bytes", "tma_mfg_relabel",
+    "tma_block_inv_deg", "tma_sage_block_fwd", "tma_sage_block_bwd_workspace_bytes", "tma_sage_block_bwd",
     "tma_loss_workspace_bytes", "tma_softmax_ce", "tma_sigmoid_l2", "tma_sgd_step", "tma_adam_step", "tma_average",
     "tma_gather_rows", "tma_profile_begin", "tma_profile_end", "tma_profile_count", "tma_profile_entry",
 )
@@ -56,7 +58,8 @@ def lib() -> C.CDLL:
                      "tma_loss_workspace_bytes", "tma_layernorm_prelu_bwd_workspace_bytes",
                      "tma_dense_bwd_workspace_bytes", "tma_gcn_layer_bwd_workspace_bytes",
                      "tma_pair_product_bwd_workspace_bytes", "tma_prelu_bwd_workspace_bytes",
-                     "tma_bce_logits_workspace_bytes"):
+                     "tma_bce_logits_workspace_bytes", "tma_neighbor_sample_workspace_bytes",
+                     "tma_mfg_relabel_workspace_bytes", "tma_sage_block_bwd_workspace_bytes"):
             getattr(L, name).restype = C.c_size_t
         _lib = L
     return _lib
@@ -548,6 +551,117 @@ def tma_bce_logits(z, n_pos: int, loss_out=None, dz_out=None, need_grad=True, ws
         _ptr(loss_out, torch.float32, "loss_out"), C.c_void_p(dz_out.data_ptr() if dz_out is not None else 0),
         C.c_int64(ld_dz), _ptr(ws), C.c_size_t(ws.numel()), _stream(stream)))
     return loss_out, dz_out
+
+
+# --------------------------------------------------------------------------- sampled message-flow graphs (Sec. 4.1)
+def tma_neighbor_sample_workspace_bytes(n_dst: int) -> int:
+    return int(lib().tma_neighbor_sample_workspace_bytes(C.c_int64(n_dst)))
+
+
+def tma_neighbor_sample(dst, n_dst: int, nnz: int, rowptr, colidx, fanout: int, seed: int, blk_rowptr_out=None,
+                        blk_col_out=None, blk_row_out=None, ws=None, stream=None):
+    """Block over the first n_dst entries of dst: returns (blk_rowptr [n_dst+1], blk_col, blk_row); the number of
+    kept entries stays on the device in blk_rowptr[n_dst]."""
+    dev = rowptr.device
+    cap = max(min(n_dst * fanout, nnz), 1)
+    if blk_rowptr_out is None:
+        blk_rowptr_out = torch.empty(n_dst + 1, dtype=torch.int32, device=dev)
+    if blk_col_out is None:
+        blk_col_out = torch.empty(cap, dtype=torch.int32, device=dev)
+    if blk_row_out is None:
+        blk_row_out = torch.empty(cap, dtype=torch.int32, device=dev)
+    if blk_rowptr_out.numel() < n_dst + 1 or dst.numel() < n_dst:
+        raise TmaError("tma_neighbor_sample: dst / blk_rowptr_out too short")
+    if ws is None:
+        ws = _workspace(tma_neighbor_sample_workspace_bytes(n_dst), dev)
+    _check(lib().tma_neighbor_sample(
+        C.c_int64(n_dst), _ptr(dst, torch.int32, "dst"), C.c_int64(nnz), _ptr(rowptr, torch.int32, "rowptr"),
+        _ptr(colidx, torch.int32, "colidx"), C.c_int32(fanout), C.c_uint64(seed), _ptr(blk_rowptr_out, torch.int32),
+        _ptr(blk_col_out, torch.int32), _ptr(blk_row_out, torch.int32), C.c_int64(min(blk_col_out.numel(), blk_row_out.numel())),
+        _ptr(ws), C.c_size_t(ws.numel()), _stream(stream)))
+    return blk_rowptr_out, blk_col_out, blk_row_out
+
+
+def tma_mfg_relabel_workspace_bytes(n: int) -> int:
+    return int(lib().tma_mfg_relabel_workspace_bytes(C.c_int64(n)))
+
+
+def tma_mfg_relabel(n: int, dst, n_dst: int, cols, max_items: int, d_items=None, src_out=None, ws=None, stream=None):
+    """cols[:count] becomes positions in the node list src = dst[:n_dst] + the other nodes of cols (ascending).
+    d_items: 1-element int32 device tensor (view) with the count, or None for max_items.  Returns (src, n_src)."""
+    dev = cols.device
+    if src_out is None:
+        src_out = torch.empty(max(min(n, n_dst + max_items), 1), dtype=torch.int32, device=dev)
+    if ws is None:
+        ws = _workspace(tma_mfg_relabel_workspace_bytes(n), dev)
+    n_src = C.c_int64(0)
+    _check(lib().tma_mfg_relabel(
+        C.c_int64(n), C.c_int64(n_dst), _ptr(dst, torch.int32, "dst") if n_dst > 0 else C.c_void_p(0), C.c_int64(max_items),
+        C.c_void_p(d_items.data_ptr() if d_items is not None else 0), _ptr(cols, torch.int32, "cols"),
+        _ptr(src_out, torch.int32, "src_out"), C.c_int64(src_out.numel()), C.byref(n_src), _ptr(ws), C.c_size_t(ws.numel()),
+        _stream(stream)))
+    return src_out, int(n_src.value)
+
+
+def tma_block_inv_deg(blk_rowptr, n_dst: int, out=None, stream=None):
+    if out is None:
+        out = torch.empty(max(n_dst, 1), dtype=torch.float32, device=blk_rowptr.device)
+    _check(lib().tma_block_inv_deg(C.c_int64(n_dst), _ptr(blk_rowptr, torch.int32, "blk_rowptr"),
+                                   _ptr(out, torch.float32, "out"), _stream(stream)))
+    return out
+
+
+def tma_sage_block_fwd(n_dst: int, n_src: int, blk_rowptr, blk_col, inv_deg, H, W_self, W_neigh, bias, act: int,
+                       M_out, Hnext_out, stream=None):
+    """Layer on a bipartite block; H, M_out, Hnext_out are buffers with at least n_src / n_dst / n_dst rows."""
+    _, F_in, ldh = _rows_ld(H, "H")
+    F_out = W_self.shape[1]
+    if H.shape[0] < n_src or M_out.shape[0] < n_dst or Hnext_out.shape[0] < n_dst:
+        raise TmaError("tma_sage_block_fwd: a buffer has too few rows")
+    if tuple(W_self.shape) != (F_in, F_out) or tuple(W_neigh.shape) != (F_in, F_out) or bias.numel() != F_out:
+        raise TmaError("tma_sage_block_fwd: weight shapes do not match H")
+    if M_out.shape[1] != F_in or Hnext_out.shape[1] != F_out or not M_out.is_contiguous():
+        raise TmaError("tma_sage_block_fwd: M_out must be a dense [rows, F_in] buffer, Hnext_out [rows, F_out]")
+    _, _, ld_next = _rows_ld(Hnext_out, "Hnext_out")
+    _check(lib().tma_sage_block_fwd(
+        C.c_int64(n_dst), C.c_int64(n_src), _ptr(blk_rowptr, torch.int32), _ptr(blk_col, torch.int32),
+        _ptr(inv_deg, torch.float32), C.c_void_p(H.data_ptr()), C.c_int64(ldh), C.c_int32(F_in),
+        _ptr(W_self, torch.float32, "W_self"), _ptr(W_neigh, torch.float32, "W_neigh"), _ptr(bias, torch.float32, "bias"),
+        C.c_int32(F_out), C.c_int32(act), C.c_int32(_feat_dtype(H)), C.c_void_p(M_out.data_ptr()),
+        C.c_void_p(Hnext_out.data_ptr()), C.c_int64(ld_next), _stream(stream)))
+    return M_out, Hnext_out
+
+
+def tma_sage_block_bwd_workspace_bytes(n_dst: int, n_src: int, max_entries: int, F_in: int, F_out: int, dtype: int,
+                                       need_dH: bool) -> int:
+    return int(lib().tma_sage_block_bwd_workspace_bytes(C.c_int64(n_dst), C.c_int64(n_src), C.c_int64(max_entries),
+                                                        C.c_int32(F_in), C.c_int32(F_out), C.c_int32(dtype),
+                                                        C.c_int32(1 if need_dH else 0)))
+
+
+def tma_sage_block_bwd(n_dst: int, n_src: int, max_entries: int, blk_rowptr, blk_col, blk_row, inv_deg, H, M, Hnext,
+                       dHnext, W_self, W_neigh, act: int, dW_self, dW_neigh, dbias, dH_out=None, ws=None, stream=None):
+    """Backward on a bipartite block; dH_out (buffer with the leading dimension of H, at least n_src rows) or None."""
+    _, F_in, ldh = _rows_ld(H, "H")
+    F_out = W_self.shape[1]
+    _, _, ld_next = _rows_ld(dHnext, "dHnext")
+    if act == TMA_ACT_RELU:
+        _same_ld(Hnext, dHnext, "tma_sage_block_bwd: Hnext / dHnext")
+    if dH_out is not None and (dH_out.shape[0] < n_src or _rows_ld(dH_out, "dH_out")[2] != ldh):
+        raise TmaError("tma_sage_block_bwd: dH_out needs n_src rows and the leading dimension of H")
+    dt = _feat_dtype(H)
+    if ws is None:
+        ws = _workspace(tma_sage_block_bwd_workspace_bytes(n_dst, n_src, max_entries, F_in, F_out, dt, dH_out is not None),
+                        H.device)
+    _check(lib().tma_sage_block_bwd(
+        C.c_int64(n_dst), C.c_int64(n_src), C.c_int64(max_entries), _ptr(blk_rowptr, torch.int32),
+        _ptr(blk_col, torch.int32), _ptr(blk_row, torch.int32), _ptr(inv_deg, torch.float32), C.c_void_p(H.data_ptr()),
+        C.c_int64(ldh), C.c_void_p(M.data_ptr()), C.c_void_p(Hnext.data_ptr() if Hnext is not None else 0),
+        C.c_void_p(dHnext.data_ptr()), C.c_int64(ld_next), _ptr(W_self, torch.float32), _ptr(W_neigh, torch.float32),
+        C.c_int32(F_in), C.c_int32(F_out), C.c_int32(act), C.c_int32(dt), _ptr(dW_self, torch.float32, "dW_self"),
+        _ptr(dW_neigh, torch.float32, "dW_neigh"), _ptr(dbias, torch.float32, "dbias"),
+        C.c_void_p(dH_out.data_ptr() if dH_out is not None else 0), _ptr(ws), C.c_size_t(ws.numel()), _stream(stream)))
+    return dH_out
 
 
 def tma_loss_workspace_bytes(n: int, Cc: int) -> int:

@@ -91,4 +91,9 @@ int launch_exclusive_scan_i32(int64_t n, const int32_t *values, int32_t *prefix_
 // out[j] = sum over b < nb of partial[b * width + j], j < F, in a fixed order (nb = 0 writes zeros).
 int launch_sum_partials(int nb, int width, int F, const float *partial, float *out, hipStream_t stream);
 
+// sorted[range r] = unsorted[range r] in ascending order, for the n ranges of rowptr (distinct numbers per range).
+// queue: n int32 of scratch; counter: one int32 that is zero on entry.
+int launch_sort_lists(int64_t n, const int32_t *rowptr, const int32_t *unsorted, int32_t *sorted, int32_t *queue,
+                      int32_t *counter, hipStream_t s);
+
 }  // namespace tma

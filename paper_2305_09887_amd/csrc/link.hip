@@ -261,6 +261,22 @@ __global__ __launch_bounds__(256) void incidence_sort_long_kernel(const int32_t 
     }
 }
 
+// sorted[range r] = unsorted[range r] in ascending order for every range of rowptr (n ranges).  queue: n int32
+// of scratch; counter: one int32 that is ZERO on entry.
+int launch_sort_lists(int64_t n, const int32_t *rowptr, const int32_t *unsorted, int32_t *sorted, int32_t *queue,
+                      int32_t *counter, hipStream_t s)
+{
+    if (n <= 0) return TMA_OK;
+    {
+        TMA_TIMED("incidence_sort_short", s);
+        hipLaunchKernelGGL(incidence_sort_short_kernel, dim3(unsigned(ceil_div(n, 256))), dim3(256), 0, s, n, rowptr,
+                           unsorted, sorted, queue, counter);
+    }
+    TMA_TIMED("incidence_sort_long", s);
+    hipLaunchKernelGGL(incidence_sort_long_kernel, dim3(1024), dim3(256), 0, s, rowptr, unsorted, sorted, queue, counter);
+    return check_launch("sort lists");
+}
+
 // ---- PReLU with one learnable slope ---------------------------------------------------------------
 template <typename T, bool kVec>
 __global__ __launch_bounds__(256) void prelu_fwd_kernel(int64_t n, int units, const T *__restrict__ Z, int64_t ldz,
@@ -483,17 +499,8 @@ extern "C" int tma_pair_product_bwd(int64_t n, int64_t B, int32_t F, const void 
             hipLaunchKernelGGL(incidence_fill_kernel, dim3(unsigned(ceil_div(4 * B, 256))), dim3(256), 0, s, B, u, v, vneg,
                                rowptr, cursor, unsorted);
         }
-        {
-            TMA_TIMED("incidence_sort_short", s);
-            // the per-node counts are spent once the scan has run: their array takes the queue of long lists
-            hipLaunchKernelGGL(incidence_sort_short_kernel, dim3(unsigned(ceil_div(n, 256))), dim3(256), 0, s, n, rowptr,
-                               unsorted, sorted, deg, deg + 2 * n);
-        }
-        {
-            TMA_TIMED("incidence_sort_long", s);
-            hipLaunchKernelGGL(incidence_sort_long_kernel, dim3(1024), dim3(256), 0, s, rowptr, unsorted, sorted, deg,
-                               deg + 2 * n);
-        }
+        // the per-node counts are spent once the scan has run: their array takes the queue of long lists
+        if (int rc = launch_sort_lists(n, rowptr, unsorted, sorted, deg, deg + 2 * n, s)) return rc;
         TMA_TIMED("pair_product_terms", s);
         if (dtype == TMA_F32) {
             const float *r = static_cast<const float *>(R), *g = static_cast<const float *>(dE0);

@@ -1,0 +1,486 @@
+// Sampled message-flow graphs (paper Sec. 4.1, paragraph on mini-batch and
+// negative sampling: a GraphSAGE-style sampler caps the neighbours a node
+// aggregates, so a step touches the sampled neighbourhood of its batch only):
+//   * fan-out neighbour sampling on the local CSR (a uniform subset per row, by key ranking);
+//   * the node list of a block (dst nodes first, the new ones in ascending id) and the
+//     relabelling of its columns, with the scan of the subgraph extraction;
+//   * the mean-aggregation GraphSAGE layer on such a bipartite block, forward and backward;
+//     the backward gathers over the block's transpose, which is built here with integer
+//     counting, a scan, a fill and a sort of every list (no floating-point atomics).
+// Integer / latency bound work around the layer kernels.
+#include "kernels.hpp"
+
+namespace tma {
+
+constexpr int kThreadCopy = 32;     // rows kept whole and no longer than this are copied by their thread
+constexpr int kKeyLds = 2048;       // keys of a row that fit a wavefront's LDS segment
+
+__device__ __forceinline__ int32_t item_count(const int32_t *d_items, int64_t max_items)
+{
+    if (!d_items) return int32_t(max_items);
+    const int32_t c = *d_items;
+    return c < max_items ? c : int32_t(max_items);
+}
+
+// ---- neighbour sampling -----------------------------------------------------------------------
+__global__ __launch_bounds__(256) void sample_count_kernel(int64_t n_dst, const int32_t *__restrict__ dst,
+                                                           const int32_t *__restrict__ rowptr, int32_t fanout,
+                                                           int32_t *__restrict__ deg)
+{
+    const int64_t i = int64_t(blockIdx.x) * 256 + threadIdx.x;
+    if (i >= n_dst) return;
+    const int32_t w = dst[i];
+    const int32_t d = rowptr[w + 1] - rowptr[w];
+    deg[i] = d < fanout ? d : fanout;
+}
+
+// Rows that are kept whole and short are copied by their thread; the others are queued for a wavefront each
+// (one queue reservation per wavefront).
+__global__ __launch_bounds__(256) void sample_fill_short_kernel(int64_t n_dst, const int32_t *__restrict__ dst,
+                                                                const int32_t *__restrict__ rowptr,
+                                                                const int32_t *__restrict__ colidx, int32_t fanout,
+                                                                const int32_t *__restrict__ blk_rowptr,
+                                                                int32_t *__restrict__ blk_col, int32_t *__restrict__ blk_row,
+                                                                int64_t cap, int32_t *__restrict__ queue,
+                                                                int32_t *__restrict__ n_queued)
+{
+    const int64_t i = int64_t(blockIdx.x) * 256 + threadIdx.x;
+    const int lane = threadIdx.x % kWave;
+    int32_t beg = 0, d = 0;
+    if (i < n_dst) {
+        const int32_t w = dst[i];
+        beg = rowptr[w];
+        d = rowptr[w + 1] - beg;
+    }
+    const bool whole = d <= fanout;
+    const bool queued = d > 0 && !(whole && d <= kThreadCopy);
+    const uint64_t mask = __ballot(queued);
+    if (mask != 0) {
+        const int leader = __ffsll(static_cast<long long>(mask)) - 1;
+        int32_t first = 0;
+        if (lane == leader) first = atomicAdd(n_queued, int32_t(__popcll(mask)));
+        first = __shfl(first, leader, kWave);
+        if (queued) queue[first + __popcll(mask & ((uint64_t(1) << lane) - 1))] = int32_t(i);
+    }
+    if (d > 0 && !queued) {
+        const int32_t out = blk_rowptr[i];
+        for (int32_t k = 0; k < d && out + k < cap; ++k) {   // (cap is only reached with repeated dst nodes)
+            blk_col[out + k] = colidx[beg + k];
+            blk_row[out + k] = int32_t(i);
+        }
+    }
+}
+
+// A wavefront per queued row.  A row longer than the fan-out keeps the `fanout` entries with the smallest
+// (key, entry index), key(e) = SplitMix64(seed, e), in row order: the rank of an entry is the number of smaller
+// pairs in its row, counted against the row's keys in LDS (recomputed for rows that do not fit).
+__global__ __launch_bounds__(256) void sample_fill_long_kernel(const int32_t *__restrict__ dst,
+                                                               const int32_t *__restrict__ rowptr,
+                                                               const int32_t *__restrict__ colidx, int32_t fanout,
+                                                               uint64_t seed, const int32_t *__restrict__ blk_rowptr,
+                                                               int32_t *__restrict__ blk_col, int32_t *__restrict__ blk_row,
+                                                               int64_t cap, const int32_t *__restrict__ queue,
+                                                               const int32_t *__restrict__ n_queued)
+{
+    __shared__ uint64_t keys[256 / kWave][kKeyLds];
+    const int lane = threadIdx.x % kWave, wave = threadIdx.x / kWave;
+    const int count = *n_queued;
+    const int waves = gridDim.x * (256 / kWave);
+    for (int q = blockIdx.x * (256 / kWave) + wave; q < count; q += waves) {
+        const int32_t i = queue[q];
+        const int32_t w = dst[i];
+        const int32_t beg = rowptr[w], d = rowptr[w + 1] - beg;
+        const int32_t out = blk_rowptr[i];
+        if (d <= fanout) {
+            for (int32_t k = lane; k < d && out + k < cap; k += kWave) {
+                blk_col[out + k] = colidx[beg + k];
+                blk_row[out + k] = i;
+            }
+            continue;
+        }
+        const bool in_lds = d <= kKeyLds;
+        if (in_lds)
+            for (int32_t k = lane; k < d; k += kWave) keys[wave][k] = splitmix64_at(seed, uint64_t(beg + k));
+        // a wavefront's LDS accesses complete in program order: its own writes above are visible to the reads below
+        __builtin_amdgcn_wave_barrier();
+        int32_t kept_before = 0;
+        for (int32_t base = 0; base < d; base += kWave) {
+            const int32_t k = base + lane;
+            bool keep = false;
+            if (k < d) {
+                const uint64_t mine = in_lds ? keys[wave][k] : splitmix64_at(seed, uint64_t(beg + k));
+                int32_t smaller = 0;
+                if (in_lds) {
+#pragma unroll 4
+                    for (int32_t o = 0; o < d; ++o) {
+                        const uint64_t other = keys[wave][o];
+                        smaller += (other < mine || (other == mine && o < k)) ? 1 : 0;
+                    }
+                } else {
+                    for (int32_t o = 0; o < d; ++o) {
+                        const uint64_t other = splitmix64_at(seed, uint64_t(beg + o));
+                        smaller += (other < mine || (other == mine && o < k)) ? 1 : 0;
+                    }
+                }
+                keep = smaller < fanout;
+            }
+            const uint64_t kept = __ballot(keep);
+            if (keep) {
+                const int32_t p = out + kept_before + __popcll(kept & ((uint64_t(1) << lane) - 1));
+                if (p < cap) {
+                    blk_col[p] = colidx[beg + k];
+                    blk_row[p] = i;
+                }
+            }
+            kept_before += int32_t(__popcll(kept));
+        }
+        __builtin_amdgcn_wave_barrier();   // before the segment is overwritten by the next row
+    }
+}
+
+// ---- node list of a block and relabelling -------------------------------------------------------
+__global__ __launch_bounds__(256) void fill_i32_kernel(int64_t count, int32_t *__restrict__ p, int32_t value)
+{
+    const int64_t stride = int64_t(gridDim.x) * 256;
+    for (int64_t i = int64_t(blockIdx.x) * 256 + threadIdx.x; i < count; i += stride) p[i] = value;
+}
+
+__global__ __launch_bounds__(256) void mark_dst_kernel(int64_t n_dst, const int32_t *__restrict__ dst,
+                                                       int32_t *__restrict__ pos, int32_t *__restrict__ src)
+{
+    const int64_t i = int64_t(blockIdx.x) * 256 + threadIdx.x;
+    if (i >= n_dst) return;
+    pos[dst[i]] = int32_t(i);
+    src[i] = dst[i];
+}
+
+__global__ __launch_bounds__(256) void flag_new_kernel(int64_t max_items, const int32_t *__restrict__ d_items,
+                                                       const int32_t *__restrict__ cols, const int32_t *__restrict__ pos,
+                                                       int32_t *__restrict__ isnew)
+{
+    const int64_t e = int64_t(blockIdx.x) * 256 + threadIdx.x;
+    if (e >= item_count(d_items, max_items)) return;
+    const int32_t c = cols[e];
+    if (pos[c] < 0) isnew[c] = 1;     // several writers, one value
+}
+
+__global__ __launch_bounds__(256) void assign_new_kernel(int64_t n, int64_t n_dst, const int32_t *__restrict__ isnew,
+                                                         const int32_t *__restrict__ rank, int32_t *__restrict__ pos,
+                                                         int32_t *__restrict__ src)
+{
+    const int64_t c = int64_t(blockIdx.x) * 256 + threadIdx.x;
+    if (c >= n || !isnew[c]) return;
+    const int32_t p = int32_t(n_dst) + rank[c];
+    pos[c] = p;
+    src[p] = int32_t(c);
+}
+
+__global__ __launch_bounds__(256) void relabel_kernel(int64_t max_items, const int32_t *__restrict__ d_items,
+                                                      int32_t *__restrict__ cols, const int32_t *__restrict__ pos)
+{
+    const int64_t e = int64_t(blockIdx.x) * 256 + threadIdx.x;
+    if (e >= item_count(d_items, max_items)) return;
+    cols[e] = pos[cols[e]];
+}
+
+__global__ __launch_bounds__(256) void block_inv_deg_kernel(int64_t n_dst, const int32_t *__restrict__ blk_rowptr,
+                                                            float *__restrict__ inv_deg)
+{
+    const int64_t i = int64_t(blockIdx.x) * 256 + threadIdx.x;
+    if (i >= n_dst) return;
+    const int32_t d = blk_rowptr[i + 1] - blk_rowptr[i];
+    inv_deg[i] = d > 0 ? 1.0f / float(d) : 0.0f;
+}
+
+// ---- transpose of a block -----------------------------------------------------------------------
+__global__ __launch_bounds__(256) void transpose_count_kernel(int64_t max_items, const int32_t *__restrict__ d_items,
+                                                              const int32_t *__restrict__ cols, int32_t *__restrict__ deg)
+{
+    const int64_t e = int64_t(blockIdx.x) * 256 + threadIdx.x;
+    if (e >= item_count(d_items, max_items)) return;
+    atomicAdd(&deg[cols[e]], 1);
+}
+
+__global__ __launch_bounds__(256) void transpose_fill_kernel(int64_t max_items, const int32_t *__restrict__ d_items,
+                                                             const int32_t *__restrict__ cols,
+                                                             const int32_t *__restrict__ rowptr_T,
+                                                             int32_t *__restrict__ cursor, int32_t *__restrict__ unsorted)
+{
+    const int64_t e = int64_t(blockIdx.x) * 256 + threadIdx.x;
+    if (e >= item_count(d_items, max_items)) return;
+    const int32_t c = cols[e];
+    unsorted[rowptr_T[c] + atomicAdd(&cursor[c], 1)] = int32_t(e);
+}
+
+// entry numbers -> the dst rows they belong to (ascending entry numbers are ascending rows)
+__global__ __launch_bounds__(256) void entries_to_rows_kernel(int64_t max_items, const int32_t *__restrict__ d_items,
+                                                              int32_t *__restrict__ list, const int32_t *__restrict__ blk_row)
+{
+    const int64_t e = int64_t(blockIdx.x) * 256 + threadIdx.x;
+    if (e >= item_count(d_items, max_items)) return;
+    list[e] = blk_row[list[e]];
+}
+
+static size_t elem_size(int32_t dtype) { return dtype == TMA_BF16 ? 2 : 4; }
+static unsigned blocks_for(int64_t work) { return unsigned(ceil_div(work > 0 ? work : 1, 256)); }
+static unsigned capped_blocks(int64_t work)
+{
+    const int64_t b = ceil_div(work > 0 ? work : 1, 256);
+    return unsigned(b > 256 * 64 ? 256 * 64 : b);
+}
+
+struct BlockBwdWorkspace {
+    size_t dm_bytes;       // inv_deg-scaled dM, [n_dst, F_in]
+    size_t deg_bytes;      // per-source counts (then the sort's queue), fill cursors, queue length
+    size_t rowptr_bytes;   // transposed rowptr
+    size_t list_bytes;     // unsorted and sorted lists, one of each
+    size_t scan_bytes;
+    size_t weight_bytes;
+    size_t total() const { return dm_bytes + deg_bytes + rowptr_bytes + 2 * list_bytes + scan_bytes + weight_bytes; }
+};
+
+static BlockBwdWorkspace plan_block_bwd(int64_t n_dst, int64_t n_src, int64_t max_entries, int32_t F_in, int32_t F_out,
+                                        int32_t dtype, bool need_dH)
+{
+    BlockBwdWorkspace w{};
+    const size_t rows = size_t(n_dst > 0 ? n_dst : 1), srcs = size_t(n_src > 0 ? n_src : 1);
+    const size_t items = size_t(max_entries > 0 ? max_entries : 1);
+    if (need_dH) {
+        w.dm_bytes = round_up(rows * size_t(F_in) * elem_size(dtype), 256);
+        w.deg_bytes = round_up((2 * srcs + 1) * 4, 256);
+        w.rowptr_bytes = round_up((srcs + 1) * 4, 256);
+        w.list_bytes = round_up(items * 4, 256);
+        w.scan_bytes = exclusive_scan_i32_workspace_bytes(n_src);
+    }
+    w.weight_bytes = sage_gemm_bwd_weight_workspace_bytes(n_dst, F_in, F_out);
+    return w;
+}
+
+}  // namespace tma
+
+extern "C" size_t tma_neighbor_sample_workspace_bytes(int64_t n_dst)
+{
+    if (n_dst < 0) return 0;
+    const size_t rows = size_t(n_dst > 0 ? n_dst : 1);
+    return tma::round_up((2 * rows + 1) * 4, 256) + tma::exclusive_scan_i32_workspace_bytes(n_dst);
+}
+
+extern "C" int tma_neighbor_sample(int64_t n_dst, const int32_t *dst, int64_t nnz, const int32_t *rowptr,
+                                   const int32_t *colidx, int32_t fanout, uint64_t seed, int32_t *blk_rowptr_out,
+                                   int32_t *blk_col_out, int32_t *blk_row_out, int64_t cap_entries, void *ws,
+                                   size_t ws_bytes, tma_stream_t stream)
+{
+    using namespace tma;
+    const char *fn = "tma_neighbor_sample";
+    TMA_REQUIRE(n_dst >= 0 && n_dst <= INT32_MAX && nnz >= 0 && nnz <= INT32_MAX && fanout >= 1, TMA_ERR_INVALID_ARG,
+                "%s: n_dst, nnz or fanout", fn);
+    TMA_REQUIRE(blk_rowptr_out && ws && aligned(ws, 256) && ws_bytes >= tma_neighbor_sample_workspace_bytes(n_dst),
+                TMA_ERR_INVALID_ARG, "%s: blk_rowptr_out / workspace", fn);
+    const int64_t bound = n_dst * int64_t(fanout) < nnz ? n_dst * int64_t(fanout) : nnz;
+    TMA_REQUIRE(cap_entries >= bound && cap_entries <= INT32_MAX, TMA_ERR_WORKSPACE_TOO_SMALL,
+                "%s: room for %lld entries, up to %lld may be kept", fn, (long long)cap_entries, (long long)bound);
+    hipStream_t s = as_stream(stream);
+    int32_t *deg = static_cast<int32_t *>(ws);                 // per-row counts, then the queue of rows for a wavefront
+    const size_t rows = size_t(n_dst > 0 ? n_dst : 1);
+    int32_t *n_queued = deg + 2 * rows;
+    void *scan_ws = static_cast<char *>(ws) + round_up((2 * rows + 1) * 4, 256);
+    if (n_dst > 0) {
+        TMA_REQUIRE(dst && rowptr && (nnz == 0 || (colidx && blk_col_out && blk_row_out)), TMA_ERR_INVALID_ARG,
+                    "%s: NULL argument", fn);
+        TMA_TIMED("sample_count", s);
+        hipLaunchKernelGGL(sample_count_kernel, dim3(blocks_for(n_dst)), dim3(256), 0, s, n_dst, dst, rowptr, fanout, deg);
+        hipLaunchKernelGGL(fill_i32_kernel, dim3(1), dim3(256), 0, s, int64_t(1), n_queued, 0);
+    }
+    if (int rc = check_launch(fn)) return rc;
+    if (int rc = launch_exclusive_scan_i32(n_dst, deg, blk_rowptr_out, scan_ws, s)) return rc;
+    if (n_dst == 0 || nnz == 0) return TMA_OK;
+    int32_t *queue = deg + rows;
+    {
+        TMA_TIMED("sample_fill_short", s);
+        hipLaunchKernelGGL(sample_fill_short_kernel, dim3(blocks_for(n_dst)), dim3(256), 0, s, n_dst, dst, rowptr, colidx,
+                           fanout, blk_rowptr_out, blk_col_out, blk_row_out, cap_entries, queue, n_queued);
+    }
+    TMA_TIMED("sample_fill_long", s);
+    hipLaunchKernelGGL(sample_fill_long_kernel, dim3(1024), dim3(256), 0, s, dst, rowptr, colidx, fanout, seed,
+                       blk_rowptr_out, blk_col_out, blk_row_out, cap_entries, queue, n_queued);
+    return check_launch(fn);
+}
+
+extern "C" size_t tma_mfg_relabel_workspace_bytes(int64_t n)
+{
+    if (n < 0) return 0;
+    const size_t rows = size_t(n > 0 ? n : 1);
+    return 2 * tma::round_up(rows * 4, 256) + tma::round_up((rows + 1) * 4, 256) + tma::exclusive_scan_i32_workspace_bytes(n);
+}
+
+extern "C" int tma_mfg_relabel(int64_t n, int64_t n_dst, const int32_t *dst, int64_t max_items, const int32_t *d_items,
+                               int32_t *cols_inout, int32_t *src_out, int64_t cap_src, int64_t *h_n_src, void *ws,
+                               size_t ws_bytes, tma_stream_t stream)
+{
+    using namespace tma;
+    const char *fn = "tma_mfg_relabel";
+    TMA_REQUIRE(n >= 0 && n <= INT32_MAX && n_dst >= 0 && n_dst <= n && max_items >= 0 && max_items <= INT32_MAX,
+                TMA_ERR_INVALID_ARG, "%s: n, n_dst or max_items", fn);
+    TMA_REQUIRE(h_n_src && ws && aligned(ws, 256) && ws_bytes >= tma_mfg_relabel_workspace_bytes(n), TMA_ERR_INVALID_ARG,
+                "%s: h_n_src / workspace", fn);
+    const int64_t bound = n_dst + max_items < n ? n_dst + max_items : n;
+    TMA_REQUIRE(cap_src >= bound, TMA_ERR_WORKSPACE_TOO_SMALL, "%s: room for %lld source nodes, up to %lld possible", fn,
+                (long long)cap_src, (long long)bound);
+    *h_n_src = n_dst;
+    if (n == 0) return TMA_OK;
+    TMA_REQUIRE((n_dst == 0 || dst) && (max_items == 0 || cols_inout) && (bound == 0 || src_out), TMA_ERR_INVALID_ARG,
+                "%s: NULL argument", fn);
+    hipStream_t s = as_stream(stream);
+    const size_t rows = size_t(n);
+    char *base = static_cast<char *>(ws);
+    int32_t *pos = reinterpret_cast<int32_t *>(base);
+    int32_t *isnew = reinterpret_cast<int32_t *>(base + round_up(rows * 4, 256));
+    int32_t *rank = reinterpret_cast<int32_t *>(base + 2 * round_up(rows * 4, 256));
+    void *scan_ws = base + 2 * round_up(rows * 4, 256) + round_up((rows + 1) * 4, 256);
+    {
+        TMA_TIMED("mfg_mark", s);
+        hipLaunchKernelGGL(fill_i32_kernel, dim3(capped_blocks(n)), dim3(256), 0, s, n, pos, -1);
+        hipLaunchKernelGGL(fill_i32_kernel, dim3(capped_blocks(n)), dim3(256), 0, s, n, isnew, 0);
+        if (n_dst > 0)
+            hipLaunchKernelGGL(mark_dst_kernel, dim3(blocks_for(n_dst)), dim3(256), 0, s, n_dst, dst, pos, src_out);
+        if (max_items > 0)
+            hipLaunchKernelGGL(flag_new_kernel, dim3(blocks_for(max_items)), dim3(256), 0, s, max_items, d_items,
+                               cols_inout, pos, isnew);
+    }
+    if (int rc = check_launch(fn)) return rc;
+    if (int rc = launch_exclusive_scan_i32(n, isnew, rank, scan_ws, s)) return rc;
+    {
+        TMA_TIMED("mfg_relabel", s);
+        hipLaunchKernelGGL(assign_new_kernel, dim3(blocks_for(n)), dim3(256), 0, s, n, n_dst, isnew, rank, pos, src_out);
+        if (max_items > 0)
+            hipLaunchKernelGGL(relabel_kernel, dim3(blocks_for(max_items)), dim3(256), 0, s, max_items, d_items, cols_inout,
+                               pos);
+    }
+    if (int rc = check_launch(fn)) return rc;
+    int32_t n_new = 0;
+    // copy in stream order and wait for it: the caller sizes the next launches with the count
+    TMA_HIP_TRY(hipMemcpyWithStream(&n_new, rank + n, sizeof(n_new), hipMemcpyDeviceToHost, s), fn);
+    *h_n_src = n_dst + n_new;
+    return TMA_OK;
+}
+
+extern "C" int tma_block_inv_deg(int64_t n_dst, const int32_t *blk_rowptr, float *inv_deg_out, tma_stream_t stream)
+{
+    using namespace tma;
+    const char *fn = "tma_block_inv_deg";
+    TMA_REQUIRE(n_dst >= 0 && n_dst <= INT32_MAX, TMA_ERR_INVALID_ARG, "%s: n_dst", fn);
+    if (n_dst == 0) return TMA_OK;
+    TMA_REQUIRE(blk_rowptr && inv_deg_out, TMA_ERR_INVALID_ARG, "%s: NULL argument", fn);
+    hipStream_t s = as_stream(stream);
+    TMA_TIMED("block_inv_deg", s);
+    hipLaunchKernelGGL(block_inv_deg_kernel, dim3(blocks_for(n_dst)), dim3(256), 0, s, n_dst, blk_rowptr, inv_deg_out);
+    return check_launch(fn);
+}
+
+extern "C" int tma_sage_block_fwd(int64_t n_dst, int64_t n_src, const int32_t *blk_rowptr, const int32_t *blk_col,
+                                  const float *inv_deg, const void *H, int64_t ldh, int32_t F_in, const float *W_self,
+                                  const float *W_neigh, const float *bias, int32_t F_out, int32_t act, int32_t dtype,
+                                  void *M_out, void *Hnext_out, int64_t ld_next, tma_stream_t stream)
+{
+    using namespace tma;
+    const char *fn = "tma_sage_block_fwd";
+    TMA_REQUIRE(n_dst >= 0 && n_dst <= n_src && n_src <= INT32_MAX, TMA_ERR_INVALID_ARG, "%s: need 0 <= n_dst <= n_src", fn);
+    TMA_REQUIRE(F_in >= 1 && F_out >= 1 && F_in <= (1 << 20) && F_out <= (1 << 20), TMA_ERR_BAD_SHAPE,
+                "%s: F_in=%d F_out=%d", fn, F_in, F_out);
+    TMA_REQUIRE(act == TMA_ACT_NONE || act == TMA_ACT_RELU, TMA_ERR_INVALID_ARG, "%s: act %d", fn, act);
+    TMA_REQUIRE(dtype == TMA_F32 || dtype == TMA_BF16, TMA_ERR_UNSUPPORTED_DTYPE, "%s: dtype %d", fn, dtype);
+    if (n_dst == 0) return TMA_OK;
+    TMA_REQUIRE(blk_rowptr && inv_deg && H && W_self && W_neigh && bias && M_out && Hnext_out, TMA_ERR_INVALID_ARG,
+                "%s: NULL argument", fn);
+    TMA_REQUIRE(ldh >= F_in && ld_next >= F_out && H != M_out, TMA_ERR_BAD_SHAPE, "%s: leading dimensions / aliasing", fn);
+    hipStream_t s = as_stream(stream);
+    if (int rc = launch_spmm(n_dst, blk_rowptr, blk_col, inv_deg, H, ldh, F_in, dtype, M_out, F_in, false, s, n_src))
+        return rc;
+    return launch_sage_gemm_fwd(n_dst, H, ldh, M_out, F_in, W_self, W_neigh, bias, F_out, act, dtype, Hnext_out, ld_next, s);
+}
+
+extern "C" size_t tma_sage_block_bwd_workspace_bytes(int64_t n_dst, int64_t n_src, int64_t max_entries, int32_t F_in,
+                                                     int32_t F_out, int32_t dtype, int32_t need_dH)
+{
+    if (n_dst < 0 || n_src < n_dst || max_entries < 0 || F_in < 1 || F_out < 1) return 0;
+    return tma::plan_block_bwd(n_dst, n_src, max_entries, F_in, F_out, dtype, need_dH != 0).total();
+}
+
+extern "C" int tma_sage_block_bwd(int64_t n_dst, int64_t n_src, int64_t max_entries, const int32_t *blk_rowptr,
+                                  const int32_t *blk_col, const int32_t *blk_row, const float *inv_deg, const void *H,
+                                  int64_t ldh, const void *M, const void *Hnext, const void *dHnext, int64_t ld_next,
+                                  const float *W_self, const float *W_neigh, int32_t F_in, int32_t F_out, int32_t act,
+                                  int32_t dtype, float *dW_self, float *dW_neigh, float *dbias, void *dH_out, void *ws,
+                                  size_t ws_bytes, tma_stream_t stream)
+{
+    using namespace tma;
+    const char *fn = "tma_sage_block_bwd";
+    TMA_REQUIRE(n_dst >= 0 && n_dst <= n_src && n_src <= INT32_MAX && max_entries >= 0 && max_entries <= INT32_MAX,
+                TMA_ERR_INVALID_ARG, "%s: need 0 <= n_dst <= n_src", fn);
+    TMA_REQUIRE(F_in >= 1 && F_out >= 1 && F_in <= (1 << 20) && F_out <= (1 << 20), TMA_ERR_BAD_SHAPE,
+                "%s: F_in=%d F_out=%d", fn, F_in, F_out);
+    TMA_REQUIRE(act == TMA_ACT_NONE || act == TMA_ACT_RELU, TMA_ERR_INVALID_ARG, "%s: act %d", fn, act);
+    TMA_REQUIRE(dtype == TMA_F32 || dtype == TMA_BF16, TMA_ERR_UNSUPPORTED_DTYPE, "%s: dtype %d", fn, dtype);
+    TMA_REQUIRE(dW_self && dW_neigh && dbias, TMA_ERR_INVALID_ARG, "%s: gradient output is NULL", fn);
+    TMA_REQUIRE(ws && aligned(ws, 256), TMA_ERR_INVALID_ARG, "%s: workspace NULL or not 256-byte aligned", fn);
+    const bool need_dH = dH_out != nullptr;
+    const BlockBwdWorkspace w = plan_block_bwd(n_dst, n_src, max_entries, F_in, F_out, dtype, need_dH);
+    TMA_REQUIRE(ws_bytes >= w.total(), TMA_ERR_WORKSPACE_TOO_SMALL, "%s: workspace %zu < %zu bytes", fn, ws_bytes,
+                w.total());
+    if (n_dst > 0) {
+        TMA_REQUIRE(H && M && dHnext && W_self && W_neigh, TMA_ERR_INVALID_ARG, "%s: NULL argument", fn);
+        TMA_REQUIRE(act == TMA_ACT_NONE || Hnext, TMA_ERR_INVALID_ARG, "%s: Hnext is required with ReLU", fn);
+        TMA_REQUIRE(!need_dH || (blk_rowptr && inv_deg && (max_entries == 0 || (blk_col && blk_row))), TMA_ERR_INVALID_ARG,
+                    "%s: block is NULL", fn);
+        TMA_REQUIRE(ldh >= F_in && ld_next >= F_out, TMA_ERR_BAD_SHAPE, "%s: ldh < F_in or ld_next < F_out", fn);
+    }
+    hipStream_t s = as_stream(stream);
+    char *base = static_cast<char *>(ws);
+    void *dMs = base;
+    int32_t *deg = reinterpret_cast<int32_t *>(base + w.dm_bytes);
+    int32_t *rowptr_T = reinterpret_cast<int32_t *>(base + w.dm_bytes + w.deg_bytes);
+    int32_t *unsorted = reinterpret_cast<int32_t *>(base + w.dm_bytes + w.deg_bytes + w.rowptr_bytes);
+    int32_t *sorted = reinterpret_cast<int32_t *>(base + w.dm_bytes + w.deg_bytes + w.rowptr_bytes + w.list_bytes);
+    void *scan_ws = base + w.dm_bytes + w.deg_bytes + w.rowptr_bytes + 2 * w.list_bytes;
+    void *wws = base + w.dm_bytes + w.deg_bytes + w.rowptr_bytes + 2 * w.list_bytes + w.scan_bytes;
+
+    if (int rc = launch_sage_gemm_bwd_weight(n_dst, H, ldh, M, dHnext, Hnext, ld_next, F_in, F_out, act, dtype, dW_self,
+                                             dW_neigh, dbias, wws, w.weight_bytes, s))
+        return rc;
+    if (!need_dH || n_src == 0) return TMA_OK;
+    // dH rows of the dst nodes: dZ W_self^T; D^-1 dZ W_neigh^T goes to the workspace
+    if (int rc = launch_sage_gemm_bwd_data(n_dst, dHnext, Hnext, ld_next, inv_deg, W_self, W_neigh, F_in, F_out, act, dtype,
+                                           dH_out, ldh, dMs, s))
+        return rc;
+    // transpose of the block: source node -> the dst rows that sampled it, in ascending order
+    const int32_t *d_items = blk_rowptr ? blk_rowptr + n_dst : nullptr;
+    int32_t *cursor = deg + n_src;
+    {
+        TMA_TIMED("transpose_count", s);
+        hipLaunchKernelGGL(fill_i32_kernel, dim3(capped_blocks(2 * n_src + 1)), dim3(256), 0, s, 2 * n_src + 1, deg, 0);
+        if (max_entries > 0 && n_dst > 0)
+            hipLaunchKernelGGL(transpose_count_kernel, dim3(blocks_for(max_entries)), dim3(256), 0, s, max_entries, d_items,
+                               blk_col, deg);
+    }
+    if (int rc = check_launch(fn)) return rc;
+    if (int rc = launch_exclusive_scan_i32(n_src, deg, rowptr_T, scan_ws, s)) return rc;
+    if (max_entries > 0 && n_dst > 0) {
+        {
+            TMA_TIMED("transpose_fill", s);
+            hipLaunchKernelGGL(transpose_fill_kernel, dim3(blocks_for(max_entries)), dim3(256), 0, s, max_entries, d_items,
+                               blk_col, rowptr_T, cursor, unsorted);
+        }
+        if (int rc = launch_sort_lists(n_src, rowptr_T, unsorted, sorted, deg, deg + 2 * n_src, s)) return rc;
+        TMA_TIMED("transpose_rows", s);
+        hipLaunchKernelGGL(entries_to_rows_kernel, dim3(blocks_for(max_entries)), dim3(256), 0, s, max_entries, d_items,
+                           sorted, blk_row);
+        if (int rc = check_launch(fn)) return rc;
+    }
+    // dH += A^T (D^-1 dM): on top of the product for the dst rows, plain for the rows that are sources only
+    const int64_t n_rows_dm = n_dst > 0 ? n_dst : 1;
+    if (int rc = launch_spmm(n_dst, rowptr_T, sorted, nullptr, dMs, F_in, F_in, dtype, dH_out, ldh, true, s, n_rows_dm))
+        return rc;
+    char *tail = static_cast<char *>(dH_out) + size_t(n_dst) * size_t(ldh) * elem_size(dtype);
+    return launch_spmm(n_src - n_dst, rowptr_T + n_dst, sorted, nullptr, dMs, F_in, F_in, dtype, tail, ldh, false, s,
+                       n_rows_dm);
+}
