@@ -202,12 +202,15 @@ class LocalTrainer:
             self._layer_fwd(l, B.TMA_ACT_RELU if l < self.L - 1 else B.TMA_ACT_NONE, self.H[l + 1])
         return self.H[self.L]
 
-    def _decoder_forward(self):
-        """Mini-batch of this step, pair products, decoder layers; the logits end up in Zd[K]."""
+    def _draw_batch(self):
         u, v, vneg = self.batch
         B.tma_edge_batch(self.rowptr, self.colidx, self.nnz, self.batch_seed, self.steps_done * self.batch_size,
                          self.batch_size, u_out=u, v_out=v, vneg_out=vneg, stream=self.stream)
-        B.tma_pair_product_fwd(self.H[self.L], u, v, vneg, E0_out=self.E[0], stream=self.stream)
+
+    def _decoder_forward(self, R):
+        """Pair products of the batch (indices into the rows of R), decoder layers; the logits end up in Zd[K]."""
+        u, v, vneg = self.batch
+        B.tma_pair_product_fwd(R, u, v, vneg, E0_out=self.E[0], stream=self.stream)
         K = len(self.dec_dims) - 1
         for k in range(K):
             B.tma_dense_fwd(self.E[k], self.dec_layers[k][0], None, B.TMA_ACT_NONE, Y_out=self.Zd[k + 1],
@@ -216,8 +219,8 @@ class LocalTrainer:
                 B.tma_prelu_fwd(self.Zd[k + 1], self.dec_layers[k][1], out=self.E[k + 1], stream=self.stream)
         return self.Zd[K]
 
-    def _decoder_backward(self):
-        """Loss of the logits and the chain rule down to d(loss)/d(embeddings), left in dH[L]."""
+    def _decoder_backward(self, R, dR_out):
+        """Loss of the logits and the chain rule down to d(loss)/d(R), written to dR_out."""
         K = len(self.dec_dims) - 1
         u, v, vneg = self.batch
         B.tma_bce_logits(self.Zd[K], self.batch_size, loss_out=self.loss, dz_out=self.dE[K], ws=self.ws,
@@ -229,12 +232,11 @@ class LocalTrainer:
             B.tma_dense_bwd(self.E[k], None, self.dE[k + 1], self.dec_layers[k][0], B.TMA_ACT_NONE,
                             dW=self.dec_grads[k][0], need_dbias=False, dX_out=self.dE[k], ws=self.ws,
                             stream=self.stream)
-        B.tma_pair_product_bwd(self.H[self.L], u, v, vneg, self.dE[0], dR_out=self.dH[self.L], ws=self.ws,
-                               stream=self.stream)
+        B.tma_pair_product_bwd(R, u, v, vneg, self.dE[0], dR_out=dR_out, ws=self.ws, stream=self.stream)
 
     def backward(self):
         if self.dec_dims is not None:
-            self._decoder_backward()
+            self._decoder_backward(self.H[self.L], self.dH[self.L])
         else:
             B.tma_softmax_ce(self.H[self.L], self.labels, loss_out=self.loss, dlogits_out=self.dH[self.L],
                              ws=self.ws, stream=self.stream)
@@ -250,15 +252,161 @@ class LocalTrainer:
                 act, out_act = B.TMA_ACT_NONE, self.Z[l + 1]
             self._layer_bwd(l, act, out_act)
 
-    def step(self, lr: float):
-        """One iteration of Alg. 2's loop body on the full local subgraph."""
-        self.forward()
-        if self.dec_dims is not None:
-            self._decoder_forward()
-        self.backward()
+    def _optimizer_step(self, lr: float):
         if self.optimizer == "adam":
             B.tma_adam_step(self.W, self.dW, self.adam_m, self.adam_v, lr, self.steps_done + 1, stream=self.stream)
         else:
             B.tma_sgd_step(self.W, self.dW, lr, stream=self.stream)
         self.steps_done += 1
+
+    def step(self, lr: float):
+        """One iteration of Alg. 2's loop body on the full local subgraph."""
+        self.forward()
+        if self.dec_dims is not None:
+            self._draw_batch()
+            self._decoder_forward(self.H[self.L])
+        self.backward()
+        self._optimizer_step(lr)
+        return self.loss
+
+
+def _splitmix64(seed: int, unit: int) -> int:
+    """Output number unit+1 of the SplitMix64 stream seeded with `seed` (host copy of the library's generator,
+    for deriving per-step seeds)."""
+    m = (1 << 64) - 1
+    z = (seed + (unit + 1) * 0x9E3779B97F4A7C15) & m
+    z = ((z ^ (z >> 30)) * 0xBF58476D1CE4E5B9) & m
+    z = ((z ^ (z >> 27)) * 0x94D049BB133111EB) & m
+    return z ^ (z >> 31)
+
+
+class SampledLinkTrainer(LocalTrainer):
+    """Link prediction on the sampled message-flow graph of each mini-batch (Sec. 4.1: random positive edges, one
+    random-tail negative each, a GraphSAGE-style sampler that caps the neighbours per node and layer, MLP decoder).
+
+    Per step: draw the batch, list its distinct nodes, and for layer l = L-1 .. 0 sample up to ``fanouts[l]``
+    neighbours of every node of the level above and list the nodes reached; gather the features of the lowest
+    level; run the mean-aggregation SAGE layers on the bipartite blocks, the decoder and the loss; go back the same
+    way.  Only the sampled neighbourhood is touched.  All buffers are sized once for the largest possible level
+    (3 * batch_size nodes at the top, times 1 + fanout per layer, capped by the local node count); the level sizes
+    of a step come back from the device, one wait per level.  The neighbour sampler's seed for step t and layer l is
+    SplitMix64(batch_seed, 64 t + l).
+    """
+
+    def __init__(self, rowptr, colidx, nnz, X, dims, decoder_dims, fanouts, batch_size, batch_seed=0, params=None,
+                 decoder_params=None, stream=None, optimizer="sgd"):
+        if len(fanouts) != len(dims) - 1:
+            raise B.TmaError("SampledLinkTrainer: one fan-out per layer")
+        self.norm_act, self.encoder, self.n_lin = False, "sage", 3
+        if optimizer not in ("sgd", "adam"):
+            raise B.TmaError("SampledLinkTrainer: optimizer must be 'sgd' or 'adam'")
+        self.optimizer = optimizer
+        self.dec_dims = list(decoder_dims)
+        if self.dec_dims[0] != dims[-1] or self.dec_dims[-1] != 1 or batch_size < 1:
+            raise B.TmaError("SampledLinkTrainer: decoder_dims must run from dims[-1] to 1, with a batch size")
+        self.rowptr, self.colidx, self.nnz, self.X = rowptr, colidx, int(nnz), X
+        self.dims, self.L, self.n, self.dtype = list(dims), len(dims) - 1, X.shape[0], X.dtype
+        self.fanouts = [int(f) for f in fanouts]
+        self.batch_size, self.batch_seed = int(batch_size), int(batch_seed)
+        dev, L, Bn = X.device, self.L, self.batch_size
+        self.stream = stream if stream is not None else torch.cuda.current_stream()
+        if X.shape[1] != dims[0] or not X.is_contiguous():
+            raise B.TmaError("SampledLinkTrainer: X must be a dense [n, dims[0]] table")
+
+        self.n_params = sum(2 * fi * fo + fo for fi, fo in zip(dims[:-1], dims[1:]))
+        self.n_params += sum(a * b for a, b in zip(self.dec_dims[:-1], self.dec_dims[1:])) + len(self.dec_dims) - 2
+        self.W = torch.zeros(self.n_params, dtype=torch.float32, device=dev)
+        self.dW = torch.zeros(self.n_params, dtype=torch.float32, device=dev)
+        (self.layers, self.dec_layers), (self.grads, self.dec_grads) = self._views(self.W), self._views(self.dW)
+        if optimizer == "adam":
+            self.adam_m, self.adam_v = torch.zeros_like(self.W), torch.zeros_like(self.W)
+        if params is not None:
+            self.load_params(params, decoder_params)
+
+        # capacities: nodes of level l (the input rows of layer l; level L = the batch's nodes), entries of block l
+        cap = [0] * (L + 1)
+        cap[L] = max(min(self.n, 3 * Bn), 1)
+        for l in range(L - 1, -1, -1):
+            cap[l] = max(min(self.n, cap[l + 1] * (1 + self.fanouts[l])), 1)
+        self.cap = cap
+        self.ecap = [max(min(cap[l + 1] * self.fanouts[l], self.nnz), 1) for l in range(L)]
+        i32 = lambda k: torch.empty(k, dtype=torch.int32, device=dev)
+        self.nodes = [i32(c) for c in cap]
+        self.count = [0] * (L + 1)
+        self.blk_rowptr = [i32(cap[l + 1] + 1) for l in range(L)]
+        self.blk_col = [i32(self.ecap[l]) for l in range(L)]
+        self.blk_row = [i32(self.ecap[l]) for l in range(L)]
+        self.blk_inv_deg = [torch.empty(cap[l + 1], dtype=torch.float32, device=dev) for l in range(L)]
+        self.H = [torch.empty((cap[0], dims[0]), dtype=self.dtype, device=dev)]
+        self.H += [B._padded(cap[l], dims[l], self.dtype, dev) for l in range(1, L + 1)]
+        self.M = [torch.empty((cap[l + 1], dims[l]), dtype=self.dtype, device=dev) for l in range(L)]
+        self.dH = [None] + [B._padded(cap[l], dims[l], self.dtype, dev) for l in range(1, L + 1)]
+        self.bcat = i32(3 * Bn)                       # u | v | v': node ids when drawn, then positions in level L
+        self.batch = (self.bcat[:Bn], self.bcat[Bn:2 * Bn], self.bcat[2 * Bn:])
+        dd, dt = self.dec_dims, B._feat_dtype(X)
+        self.E = [B._padded(2 * Bn, f, self.dtype, dev) for f in dd[:-1]]
+        self.Zd = [None] + [B._padded(2 * Bn, f, self.dtype, dev) for f in dd[1:]]
+        self.dE = [B._padded(2 * Bn, f, self.dtype, dev) for f in dd]
+        ws_bytes = max(
+            max(B.tma_neighbor_sample_workspace_bytes(cap[l + 1]) for l in range(L)),
+            B.tma_mfg_relabel_workspace_bytes(self.n),
+            max(B.tma_sage_block_bwd_workspace_bytes(cap[l + 1], cap[l], self.ecap[l], dims[l], dims[l + 1], dt, l > 0)
+                for l in range(L)),
+            B.tma_pair_product_bwd_workspace_bytes(cap[L], Bn, dd[0], dt), B.tma_prelu_bwd_workspace_bytes(),
+            B.tma_bce_logits_workspace_bytes(),
+            max(B.tma_dense_bwd_workspace_bytes(2 * Bn, a, b) for a, b in zip(dd[:-1], dd[1:])))
+        self.ws = torch.empty(max(ws_bytes, 256), dtype=torch.uint8, device=dev)
+        self.loss = torch.zeros(1, dtype=torch.float32, device=dev)
+        self.steps_done = 0
+
+    def set_graph(self, rowptr, colidx, nnz):
+        """Point the trainer at another local graph over the same nodes (capacities were sized with the old nnz)."""
+        if rowptr.numel() != self.n + 1 or nnz > max(self.ecap):
+            raise B.TmaError("SampledLinkTrainer.set_graph: node count or entry count beyond the allocated buffers")
+        self.rowptr, self.colidx, self.nnz = rowptr, colidx, int(nnz)
+
+    def sample(self):
+        """The batch of this step and its message-flow graph: node lists, blocks, input features."""
+        L, Bn, st = self.L, self.batch_size, self.stream
+        self._draw_batch()
+        _, self.count[L] = B.tma_mfg_relabel(self.n, None, 0, self.bcat, 3 * Bn, src_out=self.nodes[L], ws=self.ws,
+                                             stream=st)
+        for l in range(L - 1, -1, -1):
+            n_dst = self.count[l + 1]
+            B.tma_neighbor_sample(self.nodes[l + 1], n_dst, self.nnz, self.rowptr, self.colidx, self.fanouts[l],
+                                  _splitmix64(self.batch_seed, 64 * self.steps_done + l), blk_rowptr_out=self.blk_rowptr[l],
+                                  blk_col_out=self.blk_col[l], blk_row_out=self.blk_row[l], ws=self.ws, stream=st)
+            _, self.count[l] = B.tma_mfg_relabel(self.n, self.nodes[l + 1], n_dst, self.blk_col[l], self.ecap[l],
+                                                 d_items=self.blk_rowptr[l][n_dst:n_dst + 1], src_out=self.nodes[l],
+                                                 ws=self.ws, stream=st)
+            B.tma_block_inv_deg(self.blk_rowptr[l], n_dst, out=self.blk_inv_deg[l], stream=st)
+        B.tma_gather_rows(self.nodes[0][:self.count[0]], self.X, out=self.H[0][:self.count[0]], stream=st)
+
+    def forward(self):
+        for l in range(self.L):
+            ws_, wn, b = self.layers[l]
+            act = B.TMA_ACT_RELU if l < self.L - 1 else B.TMA_ACT_NONE
+            B.tma_sage_block_fwd(self.count[l + 1], self.count[l], self.blk_rowptr[l], self.blk_col[l], self.blk_inv_deg[l],
+                                 self.H[l], ws_, wn, b, act, self.M[l], self.H[l + 1], stream=self.stream)
+        return self.H[self.L][:self.count[self.L]]
+
+    def backward(self):
+        n_top = self.count[self.L]
+        self._decoder_backward(self.H[self.L][:n_top], self.dH[self.L][:n_top])
+        for l in range(self.L - 1, -1, -1):
+            ws_, wn, _ = self.layers[l]
+            dws, dwn, db = self.grads[l]
+            act = B.TMA_ACT_RELU if l < self.L - 1 else B.TMA_ACT_NONE
+            B.tma_sage_block_bwd(self.count[l + 1], self.count[l], self.ecap[l], self.blk_rowptr[l], self.blk_col[l],
+                                 self.blk_row[l], self.blk_inv_deg[l], self.H[l], self.M[l], self.H[l + 1], self.dH[l + 1],
+                                 ws_, wn, act, dws, dwn, db, dH_out=self.dH[l] if l > 0 else None, ws=self.ws,
+                                 stream=self.stream)
+
+    def step(self, lr: float):
+        """One iteration of Alg. 2's loop body on the sampled neighbourhood of one mini-batch."""
+        self.sample()
+        R = self.forward()
+        self._decoder_forward(R)
+        self.backward()
+        self._optimizer_step(lr)
         return self.loss

@@ -161,3 +161,59 @@ def test_sage_layer_on_a_sampled_block(B, F_in, F_out, fanout, bf16, act):
     B.tma_sage_block_bwd(n_dst, n_src, len(cols), rpd, cid, rows, inv, Hd, Md, Hn, gd, dev(Ws), dev(Wn), act, dWs, dWn, db,
                          dH_out=None)                       # a first layer: no input gradient
     close(host(dWs), wWs, tol, "dW_self without dH")
+
+
+@pytest.mark.parametrize("fanouts,Bn", [([5, 5], 512), ([10, 25], 300), ([10**6, 10**6], 200), ([1, 2], 1000)])
+def test_sampled_link_prediction_training_steps(B, fanouts, Bn):
+    """Three steps of link prediction on sampled message-flow graphs (2-layer SAGE 64-96-32, decoder 32-48-1) on the
+    tiny configuration's part 0: batch, node lists and blocks bit for bit; loss, logits, every gradient and the
+    weights after each SGD step against the oracle."""
+    from oracle import model as omodel
+    from paper_2305_09887_amd.trainer import SampledLinkTrainer
+    N, K, dims, dec_dims = 20_000, 4, [64, 96, 32], [32, 48, 1]
+    rowptr, colidx = synth.chung_lu_graph(N, 12, 2.1, seed=1)
+    X = synth.features(N, dims[0], seed=2)
+    rng = np.random.default_rng(7)
+    enc = [tuple(l) for l in synth.sage_params(dims, seed=5)]
+    dec = [(synth.glorot(32, 48, rng).astype(np.float32), np.array([0.25], np.float32)),
+           (synth.glorot(48, 1, rng).astype(np.float32),)]
+    sub = oracle.induced_subgraph(rowptr, colidx, oracle.partition(N, K, seed=4), 0)
+    rp, ci = sub["rowptr"], sub["colidx"]
+    Xo = X[sub["l2g"]]
+    tr = SampledLinkTrainer(dev(rp), dev(ci), int(rp[-1]), dev(Xo), dims, dec_dims, fanouts, Bn, batch_seed=99,
+                            params=enc, decoder_params=dec)
+    e_o = [tuple(np.asarray(t, dtype=np.float64) for t in l) for l in enc]
+    d_o = [tuple(np.asarray(t, dtype=np.float64) for t in l) for l in dec]
+    assert tr.n_params == omodel.flatten(e_o + d_o).size
+    lr, losses = 0.5, []
+    for step in range(3):
+        loss_g = tr.step(lr).item()
+        batch = oracle.edge_batch(rp, ci, 99, step * Bn, Bn)
+        # first pass for the structure, then with the kernel's activation decisions
+        probe = omodel.sampled_link_loss_and_grads(rp, ci, Xo, batch, e_o, d_o, fanouts, 99, step)
+        rps, cis, inputs, seeds = probe[4]
+        assert tr.count[2] == len(seeds) and np.array_equal(tr.nodes[2].cpu().numpy()[:len(seeds)], seeds)
+        for got, want in zip(tr.batch, batch):
+            assert np.array_equal(got.cpu().numpy(), np.searchsorted(seeds, want))
+        for l in range(2):
+            n_dst = len(rps[l]) - 1
+            assert tr.count[l + 1] == n_dst
+            assert np.array_equal(tr.blk_rowptr[l].cpu().numpy()[:n_dst + 1], rps[l])
+            assert np.array_equal(tr.blk_col[l].cpu().numpy()[:rps[l][-1]], cis[l])
+        assert tr.count[0] == len(inputs) and np.array_equal(tr.nodes[0].cpu().numpy()[:len(inputs)], inputs)
+        open_ = [host(tr.H[1][:tr.count[1]]) > 0, None]
+        dec_open = [host(tr.E[1]) > 0]
+        loss_o, ge, gd, z, _ = omodel.sampled_link_loss_and_grads(rp, ci, Xo, batch, e_o, d_o, fanouts, 99, step, open_,
+                                                                  dec_open)
+        assert abs(loss_g - loss_o) <= 1e-4 * abs(loss_o), f"loss at step {step}"
+        close(host(tr.Zd[2]).ravel(), z, 1e-4, f"logits at step {step}")
+        for l in range(2):
+            for i, (g, w) in enumerate(zip(tr.grads[l], ge[l])):
+                close(host(g).ravel(), np.asarray(w).ravel(), 1e-4, f"step {step} encoder layer {l} gradient {i}")
+            for i, (g, w) in enumerate(zip(tr.dec_grads[l], gd[l])):
+                close(host(g).ravel(), np.asarray(w).ravel(), 1e-4, f"step {step} decoder layer {l} gradient {i}")
+        e_o = [tuple(oracle.sgd_step(w, g, lr).reshape(np.shape(w)) for w, g in zip(pl, gl)) for pl, gl in zip(e_o, ge)]
+        d_o = [tuple(oracle.sgd_step(w, g, lr).reshape(np.shape(w)) for w, g in zip(pl, gl)) for pl, gl in zip(d_o, gd)]
+        close(host(tr.W), omodel.flatten(e_o + d_o), 1e-4, f"weights after step {step}")
+        losses.append(loss_g)
+    assert np.isfinite(losses).all()      # (every step sees another batch: the loss need not fall step by step)
