@@ -148,13 +148,20 @@ def main():
     ap.add_argument("--encoder", choices=("sage", "gcn", "mlp"), default="sage",
                     help="the paper's other encoders (GCN, graph-agnostic MLP); a second measurement, not the "
                          "headline workload")
-    ap.add_argument("--task", choices=("node", "link"), default="node",
+    ap.add_argument("--task", choices=("node", "link", "link-sampled"), default="node",
                     help="link: link prediction (edge mini-batch + random-tail negatives, MLP decoder on the pair "
-                         "products of 256-d embeddings, BCE) instead of node classification; a second measurement")
-    ap.add_argument("--batch", type=int, default=65536, help="positive edges per step of the link task")
+                         "products of 256-d embeddings, BCE) instead of node classification; link-sampled: the same on "
+                         "the sampled message-flow graph of each batch instead of the whole local subgraph; second "
+                         "measurements")
+    ap.add_argument("--batch", type=int, default=None,
+                    help="positive edges per step of the link tasks (default 65536; 1024 for link-sampled)")
+    ap.add_argument("--fanouts", default="10,25",
+                    help="link-sampled: neighbours kept per node, first layer first (the layer next to the batch last)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="only run a plain 1 GiB device copy (reference for scaling rocprofv3 FETCH_SIZE/WRITE_SIZE)")
     args = ap.parse_args()
+    if args.batch is None:
+        args.batch = 1024 if args.task == "link-sampled" else 65536
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on ONE GPU only (trainers are independent; nothing is sharded "
                  "across GPUs). Use --gpus 1.")
@@ -162,7 +169,7 @@ def main():
     import numpy as np
     import torch
     from paper_2305_09887_amd import binding as B, synth
-    from paper_2305_09887_amd.trainer import LocalTrainer
+    from paper_2305_09887_amd.trainer import LocalTrainer, SampledLinkTrainer
 
     if not torch.cuda.is_available():
         sys.exit("bench.py needs a GPU")
@@ -180,7 +187,7 @@ def main():
     N, K, p = w["n_nodes"], w["K"], w["part"]
     dims = [w["F"], w["hidden"], w["classes"]]
     dec_dims = None
-    if args.task == "link":      # hidden size 256 for encoder and decoder (the paper's setting for its mid-size graphs)
+    if args.task != "node":      # hidden size 256 for encoder and decoder (the paper's setting for its mid-size graphs)
         dims = [w["F"], w["hidden"], w["hidden"]]
         dec_dims = [w["hidden"], w["hidden"], 1]
     L = len(dims) - 1
@@ -212,8 +219,17 @@ def main():
     link = {}
     if dec_dims is not None:
         link = dict(decoder_dims=dec_dims, batch_size=args.batch, batch_seed=sd["part"] + 1, nnz=nnz_loc)
-    tr = LocalTrainer(sub["rowptr"], sub["colidx"], sub["inv_deg"], Xl, yl, dims, params=params,
-                      norm_act=args.norm_act, encoder=args.encoder, **link)
+    sampled = args.task == "link-sampled"
+    fanouts = [int(f) for f in args.fanouts.split(",")] if sampled else None
+    if sampled:
+        if args.encoder != "sage" or args.norm_act or len(fanouts) != L:
+            sys.exit("bench.py: link-sampled runs the SAGE encoder with ReLU and needs one fan-out per layer")
+        tr = SampledLinkTrainer(sub["rowptr"], sub["colidx"], nnz_loc + nnz_loc // 4 + 4096, Xl, dims, dec_dims, fanouts,
+                                args.batch, batch_seed=sd["part"] + 1, params=params)
+        tr.nnz = nnz_loc
+    else:
+        tr = LocalTrainer(sub["rowptr"], sub["colidx"], sub["inv_deg"], Xl, yl, dims, params=params,
+                          norm_act=args.norm_act, encoder=args.encoder, **link)
     if dec_dims is not None:
         rng = np.random.default_rng(sd["weights"] + 1)
         K_dec = len(dec_dims) - 1
@@ -231,7 +247,10 @@ def main():
         s = B.tma_induced_subgraph(d_rowptr, d_colidx, part, p, cap_n_loc=cap, cap_nnz_loc=cap_nnz)
         B.tma_gather_rows(s["l2g"], d_X, out=Xl)
         B.tma_gather_rows(s["l2g"], d_y, out=yl)
-        tr.set_graph(s["rowptr"], s["colidx"], s["inv_deg"], nnz=s["nnz_loc"])
+        if sampled:
+            tr.set_graph(s["rowptr"], s["colidx"], s["nnz_loc"])
+        else:
+            tr.set_graph(s["rowptr"], s["colidx"], s["inv_deg"], nnz=s["nnz_loc"])
         tr.step(w["lr"])
         B.tma_average(W_all, W_global_out=W_global, ptr_table=ptrs)
 
@@ -266,7 +285,7 @@ def main():
             hit = link_kernel_work(k, n_loc, nnz_loc, dims, dec_dims, args.batch)
             if hit[0]:
                 return hit
-        if args.task == "link" and k.startswith(("gemm", "spmm", "scale_mask", "softmax", "ln_prelu")):
+        if args.task != "node" and k.startswith(("gemm", "spmm", "scale_mask", "softmax", "ln_prelu", "pair_", "prelu")):
             return None, 0.0     # shapes of the link task that the tables do not cover
         return kernel_work(k, n_loc, nnz_loc, dims, **kw)
 
@@ -302,9 +321,17 @@ def main():
                                    "traffic_GBs": round(traffic / per_launch_s / 1e9, 1) if traffic else None}
 
     value = L * nnz_loc / (ms_per_step * 1e-3)
+    sampled_info = None
+    if sampled:      # the step aggregates over the sampled blocks only: count their entries (of the last step)
+        entries = [int(tr.blk_rowptr[l][tr.count[l + 1]].item()) for l in range(L)]
+        value = sum(entries) / (ms_per_step * 1e-3)
+        sampled_info = {"fanouts": fanouts, "level_nodes": list(tr.count), "block_entries": entries,
+                        "positives_per_s": round(args.batch / (ms_per_step * 1e-3), 1),
+                        "value_definition": "entries of the sampled blocks (all layers) / step time"}
     train_ms = sum(v for k, v in per_step.items()
                    if k.startswith(("spmm", "gemm", "reduce", "softmax", "finish", "sgd", "ln_prelu", "scale_mask", "sum_partials", "edge_batch",
-                                    "pair_product", "incidence", "exclusive_scan", "prelu", "bce")))
+                                    "pair_product", "incidence", "exclusive_scan", "prelu", "bce", "sample_", "mfg_",
+                                    "block_", "transpose_")))
     out = {
         "metric": "trainer edges/sec per SAGE layer fwd+bwd; achieved HBM GB/s vs peak",
         "value": round(value, 1), "unit": "edges/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
@@ -315,7 +342,7 @@ def main():
                                "induced-subgraph extraction of part 0 + row gather + 2-layer mean-SAGE (hidden 256) "
                                "full-batch fwd+bwd+SGD + 8-way parameter averaging",
                    "n_nodes": N, "nnz_global": int(rowptr[-1]), "K": K, "n_loc": n_loc, "nnz_loc": nnz_loc,
-                   "layers": L, "dims": dims, "task": args.task, "decoder_dims": dec_dims, "batch_positive_edges": args.batch if dec_dims else None,
+                   "layers": L, "dims": dims, "task": args.task, "sampled": sampled_info, "decoder_dims": dec_dims, "batch_positive_edges": args.batch if dec_dims else None,
                    "encoder": args.encoder, "hidden_activation": "layernorm+prelu" if args.norm_act else "relu", "edge_definition": "directed local CSR entry; value = layers*nnz_loc/step time"},
         "roofline": roofline,
         "kernel_rooflines": kernel_rooflines,

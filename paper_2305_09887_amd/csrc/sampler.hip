@@ -71,9 +71,38 @@ __global__ __launch_bounds__(256) void sample_fill_short_kernel(int64_t n_dst, c
     }
 }
 
+// The fanout-th smallest key of a row whose keys fit NC registers per lane (chunk c of the row: entry
+// c * 64 + lane), found bit by bit from the top: per bit one count over the row (ballots), no sorting.  On return
+// T is that key and `remaining` says how many of the keys equal to T are still needed after all keys below T.
+// Lanes past the row hold the all-ones key, which never counts as having a zero bit.
+template <int NC>
+__device__ __forceinline__ void threshold_in_registers(uint64_t seed, int32_t beg, int32_t d, int lane, int32_t fanout,
+                                                       uint64_t &T, int32_t &remaining)
+{
+    uint64_t kreg[NC];
+#pragma unroll
+    for (int c = 0; c < NC; ++c)
+        kreg[c] = (c * kWave + lane < d) ? splitmix64_at(seed, uint64_t(beg + c * kWave + lane)) : ~uint64_t(0);
+    T = 0;
+    remaining = fanout;
+    for (int bit = 63; bit >= 0; --bit) {
+        const uint64_t above = bit == 63 ? uint64_t(0) : (~uint64_t(0) << (bit + 1));
+        int32_t zeros = 0;
+#pragma unroll
+        for (int c = 0; c < NC; ++c) {
+            const bool hit = ((kreg[c] ^ T) & above) == 0 && ((kreg[c] >> bit) & 1) == 0;
+            zeros += int32_t(__popcll(__ballot(hit)));
+        }
+        if (zeros < remaining) {   // the threshold has a 1 here; the keys with a 0 are all below it
+            remaining -= zeros;
+            T |= uint64_t(1) << bit;
+        }
+    }
+}
+
 // A wavefront per queued row.  A row longer than the fan-out keeps the `fanout` entries with the smallest
-// (key, entry index), key(e) = SplitMix64(seed, e), in row order: the rank of an entry is the number of smaller
-// pairs in its row, counted against the row's keys in LDS (recomputed for rows that do not fit).
+// (key, entry index), key(e) = SplitMix64(seed, e), in row order: kept are the keys below the fanout-th smallest
+// key T and, of the keys equal to T, the first ones in row order that are still needed.
 __global__ __launch_bounds__(256) void sample_fill_long_kernel(const int32_t *__restrict__ dst,
                                                                const int32_t *__restrict__ rowptr,
                                                                const int32_t *__restrict__ colidx, int32_t fanout,
@@ -98,41 +127,64 @@ __global__ __launch_bounds__(256) void sample_fill_long_kernel(const int32_t *__
             }
             continue;
         }
-        const bool in_lds = d <= kKeyLds;
+        // short rows keep their keys in registers; longer ones in LDS; beyond that they are recomputed
+        const bool in_regs = d <= 16 * kWave;
+        const bool in_lds = !in_regs && d <= kKeyLds;
         if (in_lds)
             for (int32_t k = lane; k < d; k += kWave) keys[wave][k] = splitmix64_at(seed, uint64_t(beg + k));
         // a wavefront's LDS accesses complete in program order: its own writes above are visible to the reads below
         __builtin_amdgcn_wave_barrier();
-        int32_t kept_before = 0;
+        auto key_of = [&](int32_t k) { return in_lds ? keys[wave][k] : splitmix64_at(seed, uint64_t(beg + k)); };
+
+        uint64_t T = 0;                // bits of the threshold decided so far (the undecided low bits are 0)
+        int32_t remaining = fanout;    // the threshold is the remaining-th smallest of the keys that match T's decided bits
+        if (d <= kWave) threshold_in_registers<1>(seed, beg, d, lane, fanout, T, remaining);
+        else if (d <= 2 * kWave) threshold_in_registers<2>(seed, beg, d, lane, fanout, T, remaining);
+        else if (d <= 4 * kWave) threshold_in_registers<4>(seed, beg, d, lane, fanout, T, remaining);
+        else if (d <= 8 * kWave) threshold_in_registers<8>(seed, beg, d, lane, fanout, T, remaining);
+        else if (in_regs) threshold_in_registers<16>(seed, beg, d, lane, fanout, T, remaining);
+        else {
+            for (int bit = 63; bit >= 0; --bit) {
+                const uint64_t above = bit == 63 ? uint64_t(0) : (~uint64_t(0) << (bit + 1));
+                int32_t zeros = 0;         // matching keys whose bit `bit` is 0
+                for (int32_t base = 0; base < d; base += kWave) {
+                    const int32_t k = base + lane;
+                    bool hit = false;
+                    if (k < d) {
+                        const uint64_t key = key_of(k);
+                        hit = ((key ^ T) & above) == 0 && ((key >> bit) & 1) == 0;
+                    }
+                    zeros += int32_t(__popcll(__ballot(hit)));
+                }
+                if (zeros < remaining) {
+                    remaining -= zeros;
+                    T |= uint64_t(1) << bit;
+                }
+            }
+        }
+        // keys below T: fanout - remaining of them; of the keys equal to T the first `remaining` in row order
+        int32_t kept_before = 0, equal_before = 0;
         for (int32_t base = 0; base < d; base += kWave) {
             const int32_t k = base + lane;
-            bool keep = false;
+            bool below = false, equal = false;
             if (k < d) {
-                const uint64_t mine = in_lds ? keys[wave][k] : splitmix64_at(seed, uint64_t(beg + k));
-                int32_t smaller = 0;
-                if (in_lds) {
-#pragma unroll 4
-                    for (int32_t o = 0; o < d; ++o) {
-                        const uint64_t other = keys[wave][o];
-                        smaller += (other < mine || (other == mine && o < k)) ? 1 : 0;
-                    }
-                } else {
-                    for (int32_t o = 0; o < d; ++o) {
-                        const uint64_t other = splitmix64_at(seed, uint64_t(beg + o));
-                        smaller += (other < mine || (other == mine && o < k)) ? 1 : 0;
-                    }
-                }
-                keep = smaller < fanout;
+                const uint64_t key = key_of(k);
+                below = key < T;
+                equal = key == T;
             }
+            const uint64_t lower_lanes = (uint64_t(1) << lane) - 1;
+            const uint64_t equals = __ballot(equal);
+            const bool keep = below || (equal && equal_before + int32_t(__popcll(equals & lower_lanes)) < remaining);
             const uint64_t kept = __ballot(keep);
             if (keep) {
-                const int32_t p = out + kept_before + __popcll(kept & ((uint64_t(1) << lane) - 1));
+                const int32_t p = out + kept_before + int32_t(__popcll(kept & lower_lanes));
                 if (p < cap) {
                     blk_col[p] = colidx[beg + k];
                     blk_row[p] = i;
                 }
             }
             kept_before += int32_t(__popcll(kept));
+            equal_before += int32_t(__popcll(equals));
         }
         __builtin_amdgcn_wave_barrier();   // before the segment is overwritten by the next row
     }

@@ -305,6 +305,7 @@ class SampledLinkTrainer(LocalTrainer):
         if self.dec_dims[0] != dims[-1] or self.dec_dims[-1] != 1 or batch_size < 1:
             raise B.TmaError("SampledLinkTrainer: decoder_dims must run from dims[-1] to 1, with a batch size")
         self.rowptr, self.colidx, self.nnz, self.X = rowptr, colidx, int(nnz), X
+        self.nnz_cap = int(nnz)      # the block buffers are sized for graphs of up to this many entries
         self.dims, self.L, self.n, self.dtype = list(dims), len(dims) - 1, X.shape[0], X.dtype
         self.fanouts = [int(f) for f in fanouts]
         self.batch_size, self.batch_seed = int(batch_size), int(batch_seed)
@@ -360,8 +361,9 @@ class SampledLinkTrainer(LocalTrainer):
         self.steps_done = 0
 
     def set_graph(self, rowptr, colidx, nnz):
-        """Point the trainer at another local graph over the same nodes (capacities were sized with the old nnz)."""
-        if rowptr.numel() != self.n + 1 or nnz > max(self.ecap):
+        """Point the trainer at another local graph over the same nodes, with at most the entry count given at
+        construction."""
+        if rowptr.numel() != self.n + 1 or nnz > self.nnz_cap:
             raise B.TmaError("SampledLinkTrainer.set_graph: node count or entry count beyond the allocated buffers")
         self.rowptr, self.colidx, self.nnz = rowptr, colidx, int(nnz)
 
