@@ -229,3 +229,34 @@ def test_link_prediction_training_steps(B, encoder, norm_act):
         close(host(tr.W), omodel.flatten(e_o + d_o), 1e-4, f"weights after step {step}")
         losses.append(loss_g)
     assert losses[2] < losses[0]
+
+
+def test_link_prediction_step_bf16_storage(B):
+    """The full-graph link-prediction step with bf16 storage: one step against the oracle at the bf16 tolerance."""
+    from paper_2305_09887_amd.trainer import LocalTrainer
+    N, K, dims, dec_dims, Bn = 20_000, 4, [64, 96, 32], [32, 48, 1], 2048
+    rowptr, colidx = synth.uniform_graph(N, 100_000, seed=1)
+    X = synth.round_bf16(synth.features(N, dims[0], seed=2))
+    rng = np.random.default_rng(7)
+    enc = [tuple(l) for l in synth.sage_params(dims, seed=5)]
+    dec = [(synth.glorot(32, 48, rng).astype(np.float32), np.array([0.25], np.float32)),
+           (synth.glorot(48, 1, rng).astype(np.float32),)]
+    sub = oracle.induced_subgraph(rowptr, colidx, oracle.partition(N, K, seed=4), 0)
+    rp, ci = sub["rowptr"], sub["colidx"]
+    Xo = X[sub["l2g"]]
+    tr = LocalTrainer(dev(rp), dev(ci), dev(sub["inv_deg"], torch.float32), dev_bf16(Xo).contiguous(), None, dims,
+                      params=enc, decoder_dims=dec_dims, batch_size=Bn, batch_seed=5, nnz=int(rp[-1]))
+    tr.load_params(enc, dec)
+    loss_g = tr.step(0.1).item()
+    e_o = [tuple(np.asarray(t, dtype=np.float64) for t in l) for l in enc]
+    d_o = [tuple(np.asarray(t, dtype=np.float64) for t in l) for l in dec]
+    batch = oracle.edge_batch(rp, ci, 5, 0, Bn)
+    loss_o, ge, gd, z = omodel.link_loss_and_grads(rp, ci, Xo, batch, e_o, d_o, "sage", [host(tr.H[1]) > 0, None],
+                                                    [host(tr.E[1]) > 0])
+    assert abs(loss_g - loss_o) <= 2e-2 * abs(loss_o)
+    close(host(tr.Zd[2]).ravel(), z, 2e-2, "logits")
+    for l in range(2):
+        for i, (g, w) in enumerate(zip(tr.grads[l], ge[l])):
+            close(host(g).ravel(), np.asarray(w).ravel(), 2e-2, f"encoder layer {l} gradient {i}")
+        for i, (g, w) in enumerate(zip(tr.dec_grads[l], gd[l])):
+            close(host(g).ravel(), np.asarray(w).ravel(), 2e-2, f"decoder layer {l} gradient {i}")

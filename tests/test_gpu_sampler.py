@@ -217,3 +217,38 @@ def test_sampled_link_prediction_training_steps(B, fanouts, Bn):
         close(host(tr.W), omodel.flatten(e_o + d_o), 1e-4, f"weights after step {step}")
         losses.append(loss_g)
     assert np.isfinite(losses).all()      # (every step sees another batch: the loss need not fall step by step)
+
+
+def test_sampled_link_prediction_bf16_storage(B):
+    """The sampled link-prediction step with bf16 feature / activation storage (bf16 MFMA products, fp32
+    accumulation and parameters): one step against the oracle at the bf16 tolerance; structure bit for bit."""
+    from oracle import model as omodel
+    from paper_2305_09887_amd.trainer import SampledLinkTrainer
+    N, K, dims, dec_dims, fanouts, Bn = 20_000, 4, [64, 96, 32], [32, 48, 1], [5, 10], 600
+    rowptr, colidx = synth.chung_lu_graph(N, 12, 2.1, seed=1)
+    X = synth.round_bf16(synth.features(N, dims[0], seed=2))
+    rng = np.random.default_rng(7)
+    enc = [tuple(l) for l in synth.sage_params(dims, seed=5)]
+    dec = [(synth.glorot(32, 48, rng).astype(np.float32), np.array([0.25], np.float32)),
+           (synth.glorot(48, 1, rng).astype(np.float32),)]
+    sub = oracle.induced_subgraph(rowptr, colidx, oracle.partition(N, K, seed=4), 0)
+    rp, ci = sub["rowptr"], sub["colidx"]
+    Xo = X[sub["l2g"]]
+    tr = SampledLinkTrainer(dev(rp), dev(ci), int(rp[-1]), dev_bf16(Xo).contiguous(), dims, dec_dims, fanouts, Bn,
+                            batch_seed=3, params=enc, decoder_params=dec)
+    loss_g = tr.step(0.1).item()
+    e_o = [tuple(np.asarray(t, dtype=np.float64) for t in l) for l in enc]
+    d_o = [tuple(np.asarray(t, dtype=np.float64) for t in l) for l in dec]
+    batch = oracle.edge_batch(rp, ci, 3, 0, Bn)
+    open_ = [host(tr.H[1][:tr.count[1]]) > 0, None]
+    loss_o, ge, gd, z, (rps, cis, inputs, seeds) = omodel.sampled_link_loss_and_grads(
+        rp, ci, Xo, batch, e_o, d_o, fanouts, 3, 0, open_, [host(tr.E[1]) > 0])
+    assert tr.count == [len(inputs), len(rps[0]) - 1, len(seeds)]
+    assert np.array_equal(tr.nodes[0].cpu().numpy()[:len(inputs)], inputs)
+    assert abs(loss_g - loss_o) <= 2e-2 * abs(loss_o)
+    close(host(tr.Zd[2]).ravel(), z, 2e-2, "logits")
+    for l in range(2):
+        for i, (g, w) in enumerate(zip(tr.grads[l], ge[l])):
+            close(host(g).ravel(), np.asarray(w).ravel(), 2e-2, f"encoder layer {l} gradient {i}")
+        for i, (g, w) in enumerate(zip(tr.dec_grads[l], gd[l])):
+            close(host(g).ravel(), np.asarray(w).ravel(), 2e-2, f"decoder layer {l} gradient {i}")
