@@ -72,6 +72,18 @@ def link_kernel_work(name, n, nnz, dims, dec_dims, Bn):
     return table.get(name.replace("_generic", ""), (None, 0.0))
 
 
+def gathered_bytes(name, n, nnz, dims):
+    """Bytes a gather kernel of the headline workload requests when every gathered neighbour row is counted (no
+    reuse between rows), next to the algorithmic bytes of kernel_work that count each distinct input row once."""
+    F0, F1, C = dims
+    Cp, s = (C + 3) // 4 * 4, 4
+    return {
+        "spmm_mean_f32_g32x1": nnz * (F0 * s + 4) + n * (F0 * s + 8),
+        "spmm_combine_f32_g12x1": nnz * (Cp * s + 4) + n * (2 * Cp * s + 8),
+        "spmm_sum_f32_g12x1": nnz * (Cp * s + 4) + n * (Cp * s + 4),
+    }.get(name)
+
+
 def kernel_work(name, n, nnz, dims, N=0, nnz_glob=0, K=1, n_params=0, encoder="sage"):
     """Algorithmic work of one launch of kernel `name` in this workload: ("mfma", flops) or ("hbm", bytes).
 
@@ -319,6 +331,10 @@ def main():
             kernel_rooflines[k] = {"bound": b, "achieved": round(wk / per_launch_s / 1e9, 1), "peak": PEAK_HBM_GBS,
                                    "unit": "GB/s", "frac": round(wk / per_launch_s / 1e9 / PEAK_HBM_GBS, 4), "traffic": traffic,
                                    "traffic_GBs": round(traffic / per_launch_s / 1e9, 1) if traffic else None}
+            gb = gathered_bytes(k, n_loc, nnz_loc, dims) if args.task == "node" and args.encoder == "sage" else None
+            if gb:    # every gathered row counted: the rate at which the kernel pulls rows through the memory system
+                kernel_rooflines[k]["gathered_GBs"] = round(gb / per_launch_s / 1e9, 1)
+                kernel_rooflines[k]["gathered_frac"] = round(gb / per_launch_s / 1e9 / PEAK_HBM_GBS, 4)
 
     value = L * nnz_loc / (ms_per_step * 1e-3)
     sampled_info = None

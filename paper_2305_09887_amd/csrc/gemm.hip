@@ -422,7 +422,7 @@ static int tf_bwd_weight_typed(int64_t n, const T *H, int64_t ldh, const T *g, c
     do {                                                                                                              \
         CatRowsT<T, VA_> a{H, ldh, H, F_in, n};                                                                       \
         SideGrad<false, T, VB_, R_> b{g, h, dYn, F_out, Fp, ld_next, ldy, n};                                         \
-        launch_by_width<T, 32, true>(name, a, b, e, int64_t(F_in), 2 * Fp, n, w.k_per_split, w.n_splits, colsum, s);     \
+        launch_by_width<T, (sizeof(T) == 2 ? 32 : 16), true>(name, a, b, e, int64_t(F_in), 2 * Fp, n, w.k_per_split, w.n_splits, colsum, s);     \
     } while (0)
 #define TMA_TF_BW2(VA_, VB_)         \
     do {                             \

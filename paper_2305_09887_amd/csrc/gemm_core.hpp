@@ -798,8 +798,9 @@ __global__ __launch_bounds__(WM *WN * 64, (BK * sizeof(CT) <= 64 && !Epi::kRowAu
     constexpr int NT = WM * WN * 64;
     constexpr int TM = BM / WM / 32;
     constexpr int TN = BN / WN / 32;
-    constexpr int A_V = BM * BK / 4 / NT;
-    constexpr int B_V = BN * BK / 4 / NT;
+    constexpr int A_Q = BM * BK / 4, B_Q = BN * BK / 4;   // 16-byte pieces of a slab
+    constexpr int A_V = (A_Q + NT - 1) / NT;              // load slots per thread; when the pieces do not divide
+    constexpr int B_V = (B_Q + NT - 1) / NT;              // evenly the last slots repeat the last piece (same value)
     using Math = TileMath<CT>;
     typedef typename Math::Frag Frag;
     constexpr int KG = BK / 8;  // groups of 8 k-values = 4 fp32 MFMAs or one bf16 MFMA
@@ -808,7 +809,6 @@ __global__ __launch_bounds__(WM *WN * 64, (BK * sizeof(CT) <= 64 && !Epi::kRowAu
     constexpr int A_WORDS = AL::kContigK ? BM * A_LD : BK * A_LD;
     constexpr int B_WORDS = BL::kContigK ? BN * B_LD : BK * B_LD;
     static_assert(BM % (WM * 32) == 0 && BN % (WN * 32) == 0 && BK % 8 == 0, "tile shape");
-    static_assert((BM * BK / 4) % NT == 0 && (BN * BK / 4) % NT == 0, "loader shape");
     static_assert(!kColSum || !BL::kContigK, "column sums are taken from a [k][n] tile");
     static_assert(A_WORDS * sizeof(CT) >= BN * sizeof(float) && B_WORDS * sizeof(CT) >= BM * sizeof(float),
                   "epilogue staging fits");
@@ -830,14 +830,14 @@ __global__ __launch_bounds__(WM *WN * 64, (BK * sizeof(CT) <= 64 && !Epi::kRowAu
     int a_mn[A_V], a_k[A_V], a_lds[A_V], b_mn[B_V], b_k[B_V], b_lds[B_V];
 #pragma unroll
     for (int i = 0; i < A_V; ++i) {
-        const int idx = tid + i * NT;
+        const int idx = (tid + i * NT) < A_Q ? (tid + i * NT) : A_Q - 1;
         a_mn[i] = AL::kContigK ? idx / (BK / 4) : (idx % (BM / 4)) * 4;
         a_k[i] = AL::kContigK ? (idx % (BK / 4)) * 4 : idx / (BM / 4);
         a_lds[i] = AL::kContigK ? a_mn[i] * A_LD + a_k[i] : a_k[i] * A_LD + a_mn[i];
     }
 #pragma unroll
     for (int i = 0; i < B_V; ++i) {
-        const int idx = tid + i * NT;
+        const int idx = (tid + i * NT) < B_Q ? (tid + i * NT) : B_Q - 1;
         b_mn[i] = BL::kContigK ? idx / (BK / 4) : (idx % (BN / 4)) * 4;
         b_k[i] = BL::kContigK ? (idx % (BK / 4)) * 4 : idx / (BN / 4);
         b_lds[i] = BL::kContigK ? b_mn[i] * B_LD + b_k[i] : b_k[i] * B_LD + b_mn[i];
