@@ -287,17 +287,18 @@ class SampledLinkTrainer(LocalTrainer):
     Per step: draw the batch, list its distinct nodes, and for layer l = L-1 .. 0 sample up to ``fanouts[l]``
     neighbours of every node of the level above and list the nodes reached; gather the features of the lowest
     level; run the mean-aggregation SAGE layers on the bipartite blocks, the decoder and the loss; go back the same
-    way.  Only the sampled neighbourhood is touched.  All buffers are sized once for the largest possible level
+    way.  Only the sampled neighbourhood is touched.  Hidden layers use ReLU, or with ``norm_act`` layer
+    normalisation followed by PReLU.  All buffers are sized once for the largest possible level
     (3 * batch_size nodes at the top, times 1 + fanout per layer, capped by the local node count); the level sizes
     of a step come back from the device, one wait per level.  The neighbour sampler's seed for step t and layer l is
     SplitMix64(batch_seed, 64 t + l).
     """
 
     def __init__(self, rowptr, colidx, nnz, X, dims, decoder_dims, fanouts, batch_size, batch_seed=0, params=None,
-                 decoder_params=None, stream=None, optimizer="sgd"):
+                 decoder_params=None, stream=None, optimizer="sgd", norm_act=False):
         if len(fanouts) != len(dims) - 1:
             raise B.TmaError("SampledLinkTrainer: one fan-out per layer")
-        self.norm_act, self.encoder, self.n_lin = False, "sage", 3
+        self.norm_act, self.encoder, self.n_lin = bool(norm_act), "sage", 3
         if optimizer not in ("sgd", "adam"):
             raise B.TmaError("SampledLinkTrainer: optimizer must be 'sgd' or 'adam'")
         self.optimizer = optimizer
@@ -315,6 +316,8 @@ class SampledLinkTrainer(LocalTrainer):
             raise B.TmaError("SampledLinkTrainer: X must be a dense [n, dims[0]] table")
 
         self.n_params = sum(2 * fi * fo + fo for fi, fo in zip(dims[:-1], dims[1:]))
+        if self.norm_act:
+            self.n_params += sum(2 * fo + 1 for fo in dims[1:-1])
         self.n_params += sum(a * b for a, b in zip(self.dec_dims[:-1], self.dec_dims[1:])) + len(self.dec_dims) - 2
         self.W = torch.zeros(self.n_params, dtype=torch.float32, device=dev)
         self.dW = torch.zeros(self.n_params, dtype=torch.float32, device=dev)
@@ -342,6 +345,9 @@ class SampledLinkTrainer(LocalTrainer):
         self.H += [B._padded(cap[l], dims[l], self.dtype, dev) for l in range(1, L + 1)]
         self.M = [torch.empty((cap[l + 1], dims[l]), dtype=self.dtype, device=dev) for l in range(L)]
         self.dH = [None] + [B._padded(cap[l], dims[l], self.dtype, dev) for l in range(1, L + 1)]
+        # pre-activations of the normalised hidden layers (index l + 1 = output of layer l), kept for the backward
+        self.Z = [None] + [B._padded(cap[l], dims[l], self.dtype, dev) if self.norm_act and l < L else None
+                           for l in range(1, L + 1)]
         self.bcat = i32(3 * Bn)                       # u | v | v': node ids when drawn, then positions in level L
         self.batch = (self.bcat[:Bn], self.bcat[Bn:2 * Bn], self.bcat[2 * Bn:])
         dd, dt = self.dec_dims, B._feat_dtype(X)
@@ -356,6 +362,8 @@ class SampledLinkTrainer(LocalTrainer):
             B.tma_pair_product_bwd_workspace_bytes(cap[L], Bn, dd[0], dt), B.tma_prelu_bwd_workspace_bytes(),
             B.tma_bce_logits_workspace_bytes(),
             max(B.tma_dense_bwd_workspace_bytes(2 * Bn, a, b) for a, b in zip(dd[:-1], dd[1:])))
+        if self.norm_act and L > 1:
+            ws_bytes = max(ws_bytes, max(B.tma_layernorm_prelu_bwd_workspace_bytes(cap[l], dims[l]) for l in range(1, L)))
         self.ws = torch.empty(max(ws_bytes, 256), dtype=torch.uint8, device=dev)
         self.loss = torch.zeros(1, dtype=torch.float32, device=dev)
         self.steps_done = 0
@@ -386,23 +394,39 @@ class SampledLinkTrainer(LocalTrainer):
 
     def forward(self):
         for l in range(self.L):
-            ws_, wn, b = self.layers[l]
+            ws_, wn, b = self.layers[l][:3]
+            n_dst = self.count[l + 1]
+            if self.norm_act and l < self.L - 1:
+                gamma, beta, slope = self.layers[l][3:]
+                B.tma_sage_block_fwd(n_dst, self.count[l], self.blk_rowptr[l], self.blk_col[l], self.blk_inv_deg[l], self.H[l],
+                                     ws_, wn, b, B.TMA_ACT_NONE, self.M[l], self.Z[l + 1], stream=self.stream)
+                B.tma_layernorm_prelu_fwd(self.Z[l + 1][:n_dst], gamma, beta, slope, out=self.H[l + 1][:n_dst],
+                                          stream=self.stream)
+                continue
             act = B.TMA_ACT_RELU if l < self.L - 1 else B.TMA_ACT_NONE
-            B.tma_sage_block_fwd(self.count[l + 1], self.count[l], self.blk_rowptr[l], self.blk_col[l], self.blk_inv_deg[l],
-                                 self.H[l], ws_, wn, b, act, self.M[l], self.H[l + 1], stream=self.stream)
+            B.tma_sage_block_fwd(n_dst, self.count[l], self.blk_rowptr[l], self.blk_col[l], self.blk_inv_deg[l], self.H[l],
+                                 ws_, wn, b, act, self.M[l], self.H[l + 1], stream=self.stream)
         return self.H[self.L][:self.count[self.L]]
 
     def backward(self):
         n_top = self.count[self.L]
         self._decoder_backward(self.H[self.L][:n_top], self.dH[self.L][:n_top])
         for l in range(self.L - 1, -1, -1):
-            ws_, wn, _ = self.layers[l]
-            dws, dwn, db = self.grads[l]
+            ws_, wn = self.layers[l][:2]
+            dws, dwn, db = self.grads[l][:3]
             act = B.TMA_ACT_RELU if l < self.L - 1 else B.TMA_ACT_NONE
-            B.tma_sage_block_bwd(self.count[l + 1], self.count[l], self.ecap[l], self.blk_rowptr[l], self.blk_col[l],
-                                 self.blk_row[l], self.blk_inv_deg[l], self.H[l], self.M[l], self.H[l + 1], self.dH[l + 1],
-                                 ws_, wn, act, dws, dwn, db, dH_out=self.dH[l] if l > 0 else None, ws=self.ws,
-                                 stream=self.stream)
+            out_act, n_dst = self.H[l + 1], self.count[l + 1]
+            if self.norm_act and l < self.L - 1:
+                gamma, beta, slope = self.layers[l][3:]
+                dgamma, dbeta, dslope = self.grads[l][3:]
+                # dL/dZ replaces dL/dH' in place; the layer below then runs without an activation of its own
+                B.tma_layernorm_prelu_bwd(self.Z[l + 1][:n_dst], self.dH[l + 1][:n_dst], gamma, beta, slope,
+                                          dZ_out=self.dH[l + 1][:n_dst], dgamma=dgamma, dbeta=dbeta, dslope=dslope,
+                                          ws=self.ws, stream=self.stream)
+                act, out_act = B.TMA_ACT_NONE, self.Z[l + 1]
+            B.tma_sage_block_bwd(n_dst, self.count[l], self.ecap[l], self.blk_rowptr[l], self.blk_col[l], self.blk_row[l],
+                                 self.blk_inv_deg[l], self.H[l], self.M[l], out_act, self.dH[l + 1], ws_, wn, act, dws, dwn,
+                                 db, dH_out=self.dH[l] if l > 0 else None, ws=self.ws, stream=self.stream)
 
     def step(self, lr: float):
         """One iteration of Alg. 2's loop body on the sampled neighbourhood of one mini-batch."""

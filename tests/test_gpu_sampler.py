@@ -163,8 +163,9 @@ def test_sage_layer_on_a_sampled_block(B, F_in, F_out, fanout, bf16, act):
     close(host(dWs), wWs, tol, "dW_self without dH")
 
 
-@pytest.mark.parametrize("fanouts,Bn", [([5, 5], 512), ([10, 25], 300), ([10**6, 10**6], 200), ([1, 2], 1000)])
-def test_sampled_link_prediction_training_steps(B, fanouts, Bn):
+@pytest.mark.parametrize("fanouts,Bn,norm_act", [([5, 5], 512, False), ([10, 25], 300, False), ([10**6, 10**6], 200, False),
+                                                 ([1, 2], 1000, False), ([5, 10], 400, True)])
+def test_sampled_link_prediction_training_steps(B, fanouts, Bn, norm_act):
     """Three steps of link prediction on sampled message-flow graphs (2-layer SAGE 64-96-32, decoder 32-48-1) on the
     tiny configuration's part 0: batch, node lists and blocks bit for bit; loss, logits, every gradient and the
     weights after each SGD step against the oracle."""
@@ -174,14 +175,20 @@ def test_sampled_link_prediction_training_steps(B, fanouts, Bn):
     rowptr, colidx = synth.chung_lu_graph(N, 12, 2.1, seed=1)
     X = synth.features(N, dims[0], seed=2)
     rng = np.random.default_rng(7)
-    enc = [tuple(l) for l in synth.sage_params(dims, seed=5)]
+    enc = []
+    for l, layer in enumerate(synth.sage_params(dims, seed=5)):
+        layer = list(layer)
+        if norm_act and l < len(dims) - 2:      # the paper's encoder variant: layer normalisation + PReLU
+            layer += [rng.normal(1.0, 0.1, dims[l + 1]).astype(np.float32),
+                      rng.normal(0.0, 0.1, dims[l + 1]).astype(np.float32), np.array([0.25], dtype=np.float32)]
+        enc.append(tuple(layer))
     dec = [(synth.glorot(32, 48, rng).astype(np.float32), np.array([0.25], np.float32)),
            (synth.glorot(48, 1, rng).astype(np.float32),)]
     sub = oracle.induced_subgraph(rowptr, colidx, oracle.partition(N, K, seed=4), 0)
     rp, ci = sub["rowptr"], sub["colidx"]
     Xo = X[sub["l2g"]]
     tr = SampledLinkTrainer(dev(rp), dev(ci), int(rp[-1]), dev(Xo), dims, dec_dims, fanouts, Bn, batch_seed=99,
-                            params=enc, decoder_params=dec)
+                            params=enc, decoder_params=dec, norm_act=norm_act)
     e_o = [tuple(np.asarray(t, dtype=np.float64) for t in l) for l in enc]
     d_o = [tuple(np.asarray(t, dtype=np.float64) for t in l) for l in dec]
     assert tr.n_params == omodel.flatten(e_o + d_o).size
