@@ -6,27 +6,10 @@
 // with dZ = dH' (.) act'(Z) formed while loading (chain rule as in the proof of
 // the paper's Thm. 1).
 //
-// All products use v_mfma_f32_32x32x2_f32 (fp32 in, fp32 accumulate), so the
-// fp32 path's 1e-4 parity bound holds without any reduced-precision pass; bf16
-// storage is widened on the way into LDS and rounded once on the way out.  One kernel
-// template serves the three products: operands are described by small "view"
-// structs that present the concatenations [H | M] / [W_self ; W_neigh], the
-// ReLU mask and the transposes as plain A[m][k], B[k][n], and by an epilogue
-// struct.
-//
-// Tiling.  128 x BN block tile, 4 wavefronts, each owning a (BM/WM) x (BN/WN)
-// patch of 32x32 MFMA tiles; k is consumed in slabs of BK through two LDS
-// buffers (one barrier per slab) while the next slab's global loads are in
-// flight in registers.  Every operand keeps in LDS the orientation it has in
-// HBM, so all global->LDS traffic is 16-byte loads and 16-byte LDS writes:
-//   k-contiguous operand : LDS [mn][BK+4]; a lane fetches 4 k-values of its row
-//                          with one ds_read_b128 and feeds 4 MFMAs from it;
-//   mn-contiguous operand: LDS [BK][MN+4]; a lane reads one word per MFMA.
-// Within a group of 8 k-values MFMA j takes k = 4*(lane/32) + j from both
-// operands (any bijection of k is allowed as long as A and B agree).
-// Blocks are numbered so that the tiles sharing operand rows (the n-tiles of a
-// row block, the output tiles of one node split) land on the same XCD and hit
-// its L2.
+// The products run in the tile kernel template of gemm_core.hpp (fp32 storage: fp32 MFMA, so the 1e-4 parity
+// bound holds without any reduced-precision pass; bf16 storage: bf16 MFMA with fp32 accumulation); this file
+// holds the operand / epilogue combinations of the GraphSAGE layer, the split planning of the weight gradient
+// and its fixed-order second stage.
 #include "gemm_core.hpp"
 
 namespace tma {

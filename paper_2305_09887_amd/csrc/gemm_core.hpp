@@ -1,5 +1,21 @@
 // The tile-product kernel template of libtma with its operand views, epilogues and launcher; included by the
 // translation units that instantiate it (the GraphSAGE transforms, the dense / GCN transforms).
+//
+// One kernel template serves every product: operands are described by small "view" structs that present
+// concatenations ([H | M], [W_self ; W_neigh]), the ReLU mask and transposes as plain A[m][k], B[k][n], and by
+// an epilogue struct.  Arithmetic: fp32 storage multiplies with v_mfma_f32_32x32x2_f32 (fp32 in, fp32
+// accumulate), bf16 storage with v_mfma_f32_32x32x8_bf16 (see TileMath).
+//
+// Tiling.  128 x BN block tile, 4 wavefronts, each owning a (BM/WM) x (BN/WN) patch of 32x32 MFMA tiles; k is
+// consumed in slabs of BK through two LDS buffers (one barrier per slab) while the next slab's global loads are
+// in flight in registers.  Every operand keeps in LDS the orientation it has in HBM, so all global->LDS
+// traffic is 16-byte loads and 16-byte LDS writes:
+//   k-contiguous operand : LDS [mn][BK+4]; a lane fetches 4 k-values of its row with one ds_read_b128 and
+//                          feeds 4 MFMAs (or one bf16 MFMA) from it;
+//   mn-contiguous operand: LDS [BK][MN+4]; a lane reads one word per k-value.
+// Within a group of 8 k-values the lanes of the upper half take k = 4 .. 7, those of the lower half 0 .. 3,
+// from both operands (any bijection of k is allowed as long as A and B agree).  Blocks are persistent and
+// numbered so that the tiles sharing operand rows land on the same die (XCD) and hit its L2.
 #pragma once
 #include "kernels.hpp"
 
@@ -15,9 +31,10 @@ constexpr int kXcds = 8;  // MI355X: 8 accelerator dies, workgroups are dealt ro
 __device__ __forceinline__ float4 zero4() { return make_float4(0.0f, 0.0f, 0.0f, 0.0f); }
 
 // ---------------------------------------------------------------------------
-// Storage types.  T = float (fp32 storage) or uint16_t (bf16 storage).  bf16
-// operands are widened to fp32 while they are written to LDS and multiplied
-// with the fp32 MFMA; results are rounded to bf16 (nearest even) on store.
+// Storage types.  T = float (fp32 storage) or uint16_t (bf16 storage).  The
+// views hand every operand over as fp32 quads (bf16 widened exactly); TileMath
+// decides what sits in LDS and which MFMA multiplies it.  Results are rounded
+// to bf16 (nearest even) on store.
 // ---------------------------------------------------------------------------
 template <typename T>
 struct Pack4;
