@@ -427,6 +427,8 @@ def tma_edge_batch(rowptr, colidx, nnz: int, seed: int, first_counter: int, B: i
     """B positive edges (u, v) of the local CSR and one negative tail v' each; int32 device tensors."""
     n = rowptr.numel() - 1
     dev = rowptr.device
+    if colidx.numel() < nnz:
+        raise TmaError("tma_edge_batch: colidx holds fewer than nnz entries")
     outs = []
     for t in (u_out, v_out, vneg_out):
         if t is None:
@@ -570,8 +572,8 @@ def tma_neighbor_sample(dst, n_dst: int, nnz: int, rowptr, colidx, fanout: int, 
         blk_col_out = torch.empty(cap, dtype=torch.int32, device=dev)
     if blk_row_out is None:
         blk_row_out = torch.empty(cap, dtype=torch.int32, device=dev)
-    if blk_rowptr_out.numel() < n_dst + 1 or dst.numel() < n_dst:
-        raise TmaError("tma_neighbor_sample: dst / blk_rowptr_out too short")
+    if blk_rowptr_out.numel() < n_dst + 1 or dst.numel() < n_dst or colidx.numel() < nnz:
+        raise TmaError("tma_neighbor_sample: dst / blk_rowptr_out / colidx too short")
     if ws is None:
         ws = _workspace(tma_neighbor_sample_workspace_bytes(n_dst), dev)
     _check(lib().tma_neighbor_sample(

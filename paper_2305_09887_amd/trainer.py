@@ -295,9 +295,11 @@ class SampledLinkTrainer(LocalTrainer):
     """
 
     def __init__(self, rowptr, colidx, nnz, X, dims, decoder_dims, fanouts, batch_size, batch_seed=0, params=None,
-                 decoder_params=None, stream=None, optimizer="sgd", norm_act=False):
+                 decoder_params=None, stream=None, optimizer="sgd", norm_act=False, nnz_cap=None):
         if len(fanouts) != len(dims) - 1:
             raise B.TmaError("SampledLinkTrainer: one fan-out per layer")
+        if colidx.numel() < nnz or (nnz_cap is not None and nnz_cap < nnz):
+            raise B.TmaError("SampledLinkTrainer: nnz entries must be there in colidx, and nnz_cap >= nnz")
         self.norm_act, self.encoder, self.n_lin = bool(norm_act), "sage", 3
         if optimizer not in ("sgd", "adam"):
             raise B.TmaError("SampledLinkTrainer: optimizer must be 'sgd' or 'adam'")
@@ -306,7 +308,8 @@ class SampledLinkTrainer(LocalTrainer):
         if self.dec_dims[0] != dims[-1] or self.dec_dims[-1] != 1 or batch_size < 1:
             raise B.TmaError("SampledLinkTrainer: decoder_dims must run from dims[-1] to 1, with a batch size")
         self.rowptr, self.colidx, self.nnz, self.X = rowptr, colidx, int(nnz), X
-        self.nnz_cap = int(nnz)      # the block buffers are sized for graphs of up to this many entries
+        # the block buffers are sized for graphs of up to this many entries (set_graph may bring a larger graph)
+        self.nnz_cap = int(nnz if nnz_cap is None else nnz_cap)
         self.dims, self.L, self.n, self.dtype = list(dims), len(dims) - 1, X.shape[0], X.dtype
         self.fanouts = [int(f) for f in fanouts]
         self.batch_size, self.batch_seed = int(batch_size), int(batch_seed)
@@ -333,7 +336,7 @@ class SampledLinkTrainer(LocalTrainer):
         for l in range(L - 1, -1, -1):
             cap[l] = max(min(self.n, cap[l + 1] * (1 + self.fanouts[l])), 1)
         self.cap = cap
-        self.ecap = [max(min(cap[l + 1] * self.fanouts[l], self.nnz), 1) for l in range(L)]
+        self.ecap = [max(min(cap[l + 1] * self.fanouts[l], self.nnz_cap), 1) for l in range(L)]
         i32 = lambda k: torch.empty(k, dtype=torch.int32, device=dev)
         self.nodes = [i32(c) for c in cap]
         self.count = [0] * (L + 1)
