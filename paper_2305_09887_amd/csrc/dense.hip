@@ -53,9 +53,10 @@ static int dense_fwd_typed(int64_t n, const T *X, int64_t ldx, int32_t F_in, con
         SideWeights<VB_> b{W, W, F_in, F_out, pad8(F_out)};                                   \
         launch_by_width<T, 32, false>(name, a, b, e, n, N_out, K, kps, 1, nullptr, s);        \
     } while (0)
-    if (va && vb) TMA_DENSE_FWD(true, true);
-    else if (va) TMA_DENSE_FWD(true, false);
-    else TMA_DENSE_FWD(false, false);
+    // (va: F_in is a multiple of four, so W holds at least four elements and may be read in unaligned groups)
+    if (va && vb) TMA_DENSE_FWD(true, kAligned4);
+    else if (va) TMA_DENSE_FWD(true, kUnaligned4);
+    else TMA_DENSE_FWD(false, kElementwise);
 #undef TMA_DENSE_FWD
     return check_launch("dense gemm fwd");
 }

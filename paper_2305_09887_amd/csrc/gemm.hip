@@ -338,6 +338,7 @@ static int tf_fwd_typed(int64_t n, const T *H, int64_t ldh, int32_t F_in, const 
     const int64_t K = F_in, kps = int64_t(round_up(size_t(K), 32));
     const bool va = vec4_ok(H, ldh);
     const bool vb = F_out % 4 == 0 && aligned(W_self, 16) && aligned(W_neigh, 16);
+    TMA_REQUIRE(vb || int64_t(F_in) * F_out >= 4, TMA_ERR_INVALID_ARG, "sage gemm tf fwd: weight matrix below four elements");
     const char *name = kname<T>("gemm_tf_fwd", "gemm_tf_fwd_generic", "gemm_tf_fwd_bf16", "gemm_tf_fwd_bf16_generic", va);
 #define TMA_TF_FWD(VA_, VB_)                                                                      \
     do {                                                                                          \
@@ -345,10 +346,12 @@ static int tf_fwd_typed(int64_t n, const T *H, int64_t ldh, int32_t F_in, const 
         SideWeights<VB_> b{W_self, W_neigh, F_in, F_out, Fp};                                     \
         launch_by_width<T, 32, false>(name, a, b, e, n, 2 * Fp, K, kps, 1, nullptr, s);              \
     } while (0)
-    if (va && vb) TMA_TF_FWD(true, true);
-    else if (va) TMA_TF_FWD(true, false);
-    else if (vb) TMA_TF_FWD(false, true);
-    else TMA_TF_FWD(false, false);
+    // weights whose rows are not multiples of four: 16-byte loads from 4-byte-aligned addresses
+    // (the form is only chosen for F_in >= 8, so the matrices hold at least four elements)
+    if (va && vb) TMA_TF_FWD(true, kAligned4);
+    else if (va) TMA_TF_FWD(true, kUnaligned4);
+    else if (vb) TMA_TF_FWD(false, kAligned4);
+    else TMA_TF_FWD(false, kUnaligned4);
 #undef TMA_TF_FWD
     return check_launch("sage gemm tf fwd");
 }
@@ -465,6 +468,7 @@ static int tf_bwd_data_typed(int64_t n, const T *g, const T *h, int64_t ld_next,
     const int64_t K = 2 * int64_t(Fp), kps = int64_t(round_up(size_t(K), 32));
     const bool va = vec4_ok(g, ld_next) && (!relu || vec4_ok(h, ld_next)) && vec4_ok(dYn, ldy);
     const bool vb = F_out % 4 == 0 && aligned(W_self, 16) && aligned(W_neigh, 16);
+    TMA_REQUIRE(vb || int64_t(F_in) * F_out >= 4, TMA_ERR_INVALID_ARG, "sage gemm tf bwd data: weight matrix below four elements");
     const char *name = kname<T>("gemm_tf_bwd_data", "gemm_tf_bwd_data_generic", "gemm_tf_bwd_data_bf16",
                                 "gemm_tf_bwd_data_bf16_generic", va);
 #define TMA_TF_BD(VA_, VB_, R_)                                                                        \
@@ -478,10 +482,10 @@ static int tf_bwd_data_typed(int64_t n, const T *g, const T *h, int64_t ld_next,
         if (relu) TMA_TF_BD(VA_, VB_, true); \
         else TMA_TF_BD(VA_, VB_, false);     \
     } while (0)
-    if (va && vb) TMA_TF_BD2(true, true);
-    else if (va) TMA_TF_BD2(true, false);
-    else if (vb) TMA_TF_BD2(false, true);
-    else TMA_TF_BD2(false, false);
+    if (va && vb) TMA_TF_BD2(true, kAligned4);
+    else if (va) TMA_TF_BD2(true, kUnaligned4);
+    else if (vb) TMA_TF_BD2(false, kAligned4);
+    else TMA_TF_BD2(false, kUnaligned4);
 #undef TMA_TF_BD2
 #undef TMA_TF_BD
     return check_launch("sage gemm tf bwd data");

@@ -92,6 +92,34 @@ struct RawV<T, false> {  // element-wise path: already fp32, already zero outsid
     __device__ __forceinline__ float4 get() const { return v; }
 };
 
+// Weight matrices whose rows are not multiples of four (F_out = 47): four consecutive elements starting at
+// element e of a dense fp32 array of `count` >= 4 elements, fetched with one 16-byte load from a base that is
+// only 4-byte aligned (the load instruction needs no more), unconditionally.  A group that would run past the
+// end of the array is fetched `shift` elements earlier and moved back in registers; `valid` leading elements are
+// kept, the rest read as zero.
+struct RawU {
+    float4 v;
+    int meta;  // valid (0..4) | shift (0..3) << 4
+    __device__ __forceinline__ float4 get() const
+    {
+        const int valid = meta & 15;
+        float4 t = v;
+        if (meta & 16) t = make_float4(t.y, t.z, t.w, 0.0f);
+        if (meta & 32) t = make_float4(t.z, t.w, 0.0f, 0.0f);
+        return make_float4(valid > 0 ? t.x : 0.0f, valid > 1 ? t.y : 0.0f, valid > 2 ? t.z : 0.0f, valid > 3 ? t.w : 0.0f);
+    }
+};
+__device__ __forceinline__ RawU load_unaligned4(const float *base, int e, int count, int valid)
+{
+    const int over = e + 4 - count;
+    const int shift = over > 0 ? over : 0;
+    RawU r;
+    __builtin_memcpy(&r.v, base + (e - shift), 16);
+    r.meta = (valid < 4 ? valid : 4) | (shift << 4);
+    return r;
+}
+enum : int { kElementwise = 0, kAligned4 = 1, kUnaligned4 = 2 };   // how a weight view fetches its groups of four
+
 template <typename T, bool V>
 struct CatRows {  // A[m][k] = k < F ? H[m][k] : M[m][k-F]  for k < Kv, zero beyond    (contiguous along k)
     static constexpr bool kContigK = true;
@@ -401,13 +429,15 @@ struct MaskedGrad {
 // 16-byte element count, so that a group of four never straddles the halves;
 // positions c >= F_out inside a half read as zero.
 // ---------------------------------------------------------------------------
-template <bool V>
+template <int kMode>
 struct SideWeights {  // B[k][n] = n < Fp ? W_self[k][n] : W_neigh[k][n-Fp]   (contiguous along n)
     static constexpr bool kContigK = false;
-    typedef RawV<float, V> Raw;
+    static constexpr bool V = kMode == kAligned4;
+    typedef typename std::conditional<kMode == kUnaligned4, RawU, RawV<float, V>>::type Raw;
     struct Lane {
-        const float *col;  // element of row k is col[k * Fo]
+        const float *col;  // element of row k is col[k * Fo]  (kUnaligned4: the matrix, and c = first column)
         int nv;            // valid elements from this column on (<= 0: padding)
+        int c;
     };
     const float *Ws;
     const float *Wn;
@@ -421,25 +451,30 @@ struct SideWeights {  // B[k][n] = n < Fp ? W_self[k][n] : W_neigh[k][n-Fp]   (c
         const bool second = n >= Fp;
         const int c = n - (second ? Fp : 0);
         const bool ok = n < 2 * Fp && c < Fo;
-        return Lane{(second ? Wn : Ws) + (ok ? c : 0), ok ? Fo - c : 0};
+        if constexpr (kMode == kUnaligned4) return Lane{second ? Wn : Ws, ok ? Fo - c : 0, ok ? c : 0};
+        else return Lane{(second ? Wn : Ws) + (ok ? c : 0), ok ? Fo - c : 0, 0};
     }
     __device__ __forceinline__ Raw load(const Lane &l, int64_t k64) const
     {
         const int k = int(k64);
-        Raw r;
-        r.ok = l.nv > 0 && k < F;
-        const float *p = l.col + int64_t(k < F ? k : 0) * Fo;
-        if constexpr (V) {
-            r.v = *reinterpret_cast<const float4 *>(p);
-        } else if (r.ok) {
-            r.v.x = p[0];
-            r.v.y = l.nv > 1 ? p[1] : 0.0f;
-            r.v.z = l.nv > 2 ? p[2] : 0.0f;
-            r.v.w = l.nv > 3 ? p[3] : 0.0f;
+        if constexpr (kMode == kUnaligned4) {
+            return load_unaligned4(l.col, (k < F ? k : 0) * Fo + l.c, F * Fo, (l.nv > 0 && k < F) ? l.nv : 0);
         } else {
-            r.v = zero4();
+            Raw r;
+            r.ok = l.nv > 0 && k < F;
+            const float *p = l.col + int64_t(k < F ? k : 0) * Fo;
+            if constexpr (V) {
+                r.v = *reinterpret_cast<const float4 *>(p);
+            } else if (r.ok) {
+                r.v.x = p[0];
+                r.v.y = l.nv > 1 ? p[1] : 0.0f;
+                r.v.z = l.nv > 2 ? p[2] : 0.0f;
+                r.v.w = l.nv > 3 ? p[3] : 0.0f;
+            } else {
+                r.v = zero4();
+            }
+            return r;
         }
-        return r;
     }
     __device__ __forceinline__ bool k_plain() const { return V; }
     __device__ __forceinline__ Raw load_plain(const Lane &l, int64_t k64) const
@@ -455,12 +490,14 @@ struct SideWeights {  // B[k][n] = n < Fp ? W_self[k][n] : W_neigh[k][n-Fp]   (c
     }
 };
 
-template <bool V>
+template <int kMode>
 struct SideWeightsT {  // B[k][n] = k < Fp ? W_self[n][k] : W_neigh[n][k-Fp]   (contiguous along k); n = input feature
     static constexpr bool kContigK = true;
-    typedef RawV<float, V> Raw;
+    static constexpr bool V = kMode == kAligned4;
+    typedef typename std::conditional<kMode == kUnaligned4, RawU, RawV<float, V>>::type Raw;
     struct Lane {
         const float *rs, *rn;  // rows such that element k is rs[k] (first half) or rn[k] (second half)
+        int row;               // first element of the row inside its matrix
         bool ok;
     };
     const float *Ws;
@@ -472,27 +509,32 @@ struct SideWeightsT {  // B[k][n] = k < Fp ? W_self[n][k] : W_neigh[n][k-Fp]   (
     __device__ __forceinline__ Lane prepare(int64_t n64) const
     {
         const int n = int(n64 < F ? n64 : 0);
-        return Lane{Ws + int64_t(n) * Fo, Wn + int64_t(n) * Fo - Fp, n64 < F};
+        return Lane{Ws + int64_t(n) * Fo, Wn + int64_t(n) * Fo - Fp, n * Fo, n64 < F};
     }
     __device__ __forceinline__ Raw load(const Lane &l, int64_t k64) const
     {
         const int k = int(k64);
         const bool second = k >= Fp;
         const int c = k - (second ? Fp : 0);
-        Raw r;
-        r.ok = l.ok && k < 2 * Fp && c < Fo;
-        const float *p = (second ? l.rn : l.rs) + (r.ok ? k : (second ? Fp : 0));
-        if constexpr (V) {
-            r.v = *reinterpret_cast<const float4 *>(p);
-        } else if (r.ok) {
-            r.v.x = p[0];
-            r.v.y = c + 1 < Fo ? p[1] : 0.0f;
-            r.v.z = c + 2 < Fo ? p[2] : 0.0f;
-            r.v.w = c + 3 < Fo ? p[3] : 0.0f;
+        const bool ok = l.ok && k < 2 * Fp && c < Fo;
+        if constexpr (kMode == kUnaligned4) {
+            return load_unaligned4(second ? Wn : Ws, l.row + (ok ? c : 0), F * Fo, ok ? Fo - c : 0);
         } else {
-            r.v = zero4();
+            Raw r;
+            r.ok = ok;
+            const float *p = (second ? l.rn : l.rs) + (r.ok ? k : (second ? Fp : 0));
+            if constexpr (V) {
+                r.v = *reinterpret_cast<const float4 *>(p);
+            } else if (r.ok) {
+                r.v.x = p[0];
+                r.v.y = c + 1 < Fo ? p[1] : 0.0f;
+                r.v.z = c + 2 < Fo ? p[2] : 0.0f;
+                r.v.w = c + 3 < Fo ? p[3] : 0.0f;
+            } else {
+                r.v = zero4();
+            }
+            return r;
         }
-        return r;
     }
     // without padding columns inside the halves every group of four along k is whole
     __device__ __forceinline__ bool k_plain() const { return V && Fo == Fp; }

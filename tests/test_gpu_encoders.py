@@ -254,6 +254,39 @@ def test_row_padding_is_never_multiplied(B):
     close(host(Hg), oracle.gcn_layer_fwd(rp, ci, H, W, b, 0)[2], 2e-2, "GCN Hnext")
 
 
+@pytest.mark.parametrize("Fi,Fo", [(64, 13), (256, 47), (32, 6), (96, 3)])
+def test_weights_with_ragged_rows_end_where_the_matrix_ends(B, Fi, Fo):
+    """Weight rows that are no multiple of four elements are read in 16-byte groups from 4-byte-aligned addresses,
+    and the group that would run past the end of the matrix is fetched earlier and moved back in registers.
+    Whatever follows (or precedes) the matrix in memory, NaN here, must not reach a product: forward and input
+    gradient of the transform-first SAGE layer, forward of the dense layer."""
+    rp, ci = local_graph(5000, 25_000, 31)
+    n = len(rp) - 1
+    H, Ws, b, g = _layer_inputs(n, Fi, Fo, seed=9)
+    Wn = synth.glorot(Fi, Fo, np.random.default_rng(2)).astype(np.float32)
+
+    def carved(W):      # the matrix at an address that is only 4-byte aligned, NaN on both sides
+        buf = torch.full((Fi * Fo + 16,), float("nan"), dtype=torch.float32, device="cuda")
+        view = buf[5:5 + Fi * Fo].view(Fi, Fo)
+        view.copy_(dev(W))
+        return view
+
+    dWs, dWn = carved(Ws), carved(Wn)
+    Hd = padded(B, H)
+    assert not B.lib().tma_sage_layer_aggregates_first(Fi, Fo, B.TMA_F32)
+    inv = dev((1.0 / np.maximum(np.diff(rp), 1) * (np.diff(rp) > 0)).astype(np.float32))
+    _, Hn = B.tma_sage_layer_fwd(dev(rp), dev(ci), inv, Hd, dWs, dWn, dev(b), 1)
+    M_o, Z_o, Hn_o = oracle.sage_layer_fwd(rp, ci, H, Ws, Wn, b, 1)
+    close(host(Hn), Hn_o, 1e-4, "SAGE Hnext")
+    Hn32 = Hn_o.astype(np.float32)
+    want = oracle.sage_layer_bwd(rp, ci, H, M_o.astype(np.float32), Hn32, g, Ws, Wn, 1)
+    got = B.tma_sage_layer_bwd(dev(rp), dev(ci), inv, Hd, padded(B, M_o), padded(B, Hn32), padded(B, g), dWs, dWn, 1)
+    for a, w, name in zip(got, want, ("dW_self", "dW_neigh", "dbias", "dH")):
+        close(host(a), w, 1e-4, name)
+    Y = B.tma_dense_fwd(Hd, dWs, dev(b), 0)
+    close(host(Y), oracle.dense_fwd(H, Ws, b, 0)[1], 1e-4, "dense Y")
+
+
 @pytest.mark.parametrize("encoder", ["gcn", "mlp"])
 @pytest.mark.parametrize("norm_act", [False, True])
 @pytest.mark.parametrize("optimizer", ["sgd", "adam"])
