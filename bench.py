@@ -32,17 +32,17 @@ WORKLOAD = dict(n_nodes=1_000_000, avg_degree=20, gamma=2.1, K=8, part=0, F=128,
 # (profiles/bench_configs1_hbm_traffic.txt): (FETCH_SIZE * 2.0 + WRITE_SIZE * 1.0) KiB, the factors being what the
 # same counters read for a plain 1 GiB device copy (FETCH_SIZE reports half the bytes read, WRITE_SIZE all written).
 MEASURED_TRAFFIC_BYTES = {
-    "gemm_bwd_weight_128x128": (230384 * 2.0 + 34671) * 1024,
-    "gemm_fwd_128x128": (68518 * 2.0 + 125237) * 1024,
-    "gemm_tf_fwd": (63665 * 2.0 + 46984) * 1024,
-    "gemm_tf_bwd_weight": (87546 * 2.0 + 23612) * 1024,
-    "gemm_tf_bwd_data": (24533 * 2.0 + 125237) * 1024,
-    "spmm_mean_f32_g32x1": (55748 * 2.0 + 62618) * 1024,
-    "spmm_combine_f32_g12x1": (42899 * 2.0 + 24979) * 1024,
-    "spmm_sum_f32_g12x1": (25532 * 2.0 + 24447) * 1024,
+    "gemm_bwd_weight_128x128": (234593 * 2.0 + 36703) * 1024,
+    "gemm_fwd_128x128": (70334 * 2.0 + 126773) * 1024,
+    "gemm_tf_fwd": (63591 * 2.0 + 46988) * 1024,
+    "gemm_tf_bwd_weight": (86307 * 2.0 + 23612) * 1024,
+    "gemm_tf_bwd_data": (26107 * 2.0 + 125237) * 1024,
+    "spmm_mean_f32_g32x1": (55763 * 2.0 + 62618) * 1024,
+    "spmm_combine_f32_g12x1": (43104 * 2.0 + 24974) * 1024,
+    "spmm_sum_f32_g12x1": (25526 * 2.0 + 24449) * 1024,
     "gather_rows_w16": (31577 * 2.0 + 62618) * 1024,
-    "row_fill": (20812 * 2.0 + 1926) * 1024,
-    "row_count": (12038 * 2.0 + 490) * 1024,
+    "row_fill": (20817 * 2.0 + 1926) * 1024,
+    "row_count": (12038 * 2.0 + 489) * 1024,
 }
 
 
