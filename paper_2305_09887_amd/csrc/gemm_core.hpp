@@ -73,7 +73,7 @@ __device__ __forceinline__ void narrow1(uint16_t *p, float v) { *p = f32_to_bf16
 // leading dimensions and inner extents multiples of 4); its loads are
 // branch-free: an out-of-range position is clamped to a valid address and the
 // value is discarded by resolve() through the `ok` flag.  Without V the view
-// loads element by element, guarded.
+// loads element by element, guarded (the side-weight views have a third way: see RawU).
 // ---------------------------------------------------------------------------
 template <typename T, bool V>
 struct RawV {
@@ -1122,7 +1122,8 @@ static void launch_gemm(const char *name, const AL &a, const BL &b, const Epi &e
 }
 
 // Kernel names for the timing hook: <what>_<tile>[_bf16][_generic]; "generic" = a streaming operand is
-// on the element-wise path (the weights are small: their path does not decide the kernel's speed).
+// on the element-wise path (the name does not say how the weights are read: aligned groups, unaligned groups
+// or element by element, which costs a transform-first product about a tenth of its time).
 template <typename T>
 static const char *kname(const char *f32_vec, const char *f32_gen, const char *bf16_vec, const char *bf16_gen, bool vec)
 {
