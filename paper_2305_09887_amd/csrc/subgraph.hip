@@ -376,22 +376,45 @@ __global__ __launch_bounds__(256) void row_fill_kernel(int64_t n_loc, const int6
     }
     __syncthreads();
 
+    // Hub rows: the whole workgroup, 4 consecutive entries per thread and round (1024 per round, order kept: a
+    // thread's entries follow those of all lower threads).  The longest row of a power-law graph sets the tail of
+    // this kernel, so a round carries as many independent index -> bit -> id chains as the registers allow.
     const int n_hubs = hub_count;
     const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
+    constexpr int kPerThread = 4;
     for (int h = 0; h < n_hubs; ++h) {
         const int64_t ih = row0 + hub_rows[h];
         const int64_t hbeg = row_beg[ih], hend = hbeg + row_len[ih];
         int32_t hout = rowptr_loc[ih];
-        int32_t u_next = -1;
-        if (hbeg + threadIdx.x < hend) u_next = colidx[hbeg + threadIdx.x];
-        for (int64_t off = 0; off < hend - hbeg; off += 256) {   // 256 entries per round, order kept
-            const int32_t u = u_next;
-            const int64_t en = hbeg + off + 256 + threadIdx.x;   // next round's entry is fetched during this one
-            u_next = -1;
-            if (en < hend) u_next = colidx[en];
-            const bool keep = u >= 0 && member_bit(member, u) != 0;
-            const uint64_t ballot = __ballot(keep);
-            if (lane == 0) wave_part[wave] = __popcll(ballot);
+        int32_t u_next[kPerThread];
+#pragma unroll
+        for (int j = 0; j < kPerThread; ++j) {
+            const int64_t e = hbeg + int64_t(threadIdx.x) * kPerThread + j;
+            u_next[j] = e < hend ? colidx[e] : -1;
+        }
+        for (int64_t off = 0; off < hend - hbeg; off += 256 * kPerThread) {
+            int32_t u[kPerThread], lid[kPerThread];
+            bool keep[kPerThread];
+            uint64_t ballot[kPerThread];
+#pragma unroll
+            for (int j = 0; j < kPerThread; ++j) u[j] = u_next[j];
+#pragma unroll
+            for (int j = 0; j < kPerThread; ++j) {   // next round's entries are fetched during this one
+                const int64_t e = hbeg + off + 256 * kPerThread + int64_t(threadIdx.x) * kPerThread + j;
+                u_next[j] = e < hend ? colidx[e] : -1;
+            }
+#pragma unroll
+            for (int j = 0; j < kPerThread; ++j) keep[j] = u[j] >= 0 && member_bit(member, u[j]) != 0;
+#pragma unroll
+            for (int j = 0; j < kPerThread; ++j) lid[j] = keep[j] ? g2l[u[j]] : 0;
+            int32_t wave_kept = 0, below = 0;
+#pragma unroll
+            for (int j = 0; j < kPerThread; ++j) {
+                ballot[j] = __ballot(keep[j]);
+                wave_kept += __popcll(ballot[j]);
+                below += __popcll(ballot[j] & ((1ull << lane) - 1ull));
+            }
+            if (lane == 0) wave_part[wave] = wave_kept;
             __syncthreads();
             int32_t before = 0, total = 0;
 #pragma unroll
@@ -400,7 +423,11 @@ __global__ __launch_bounds__(256) void row_fill_kernel(int64_t n_loc, const int6
                 if (w < wave) before += t;
                 total += t;
             }
-            if (keep) colidx_loc[hout + before + __popcll(ballot & ((1ull << lane) - 1ull))] = g2l[u];
+            int32_t pos = hout + before + below;
+#pragma unroll
+            for (int j = 0; j < kPerThread; ++j) {
+                if (keep[j]) colidx_loc[pos++] = lid[j];
+            }
             hout += total;
             __syncthreads();
         }
