@@ -296,12 +296,14 @@ __global__ __launch_bounds__(256) void row_count_kernel(const int64_t *d_n_loc, 
         const int64_t ih = row0 + hub_rows[h];
         const int64_t end = row_beg[ih] + row_len[ih];
         int32_t ch = 0;
-        int64_t e = row_beg[ih] + threadIdx.x;
-        for (; e + 3 * 256 < end; e += 4 * 256) {  // four independent index -> bit chains in flight
-            const int32_t u0 = colidx[e], u1 = colidx[e + 256], u2 = colidx[e + 512], u3 = colidx[e + 768];
-            ch += member_bit(member, u0) + member_bit(member, u1) + member_bit(member, u2) + member_bit(member, u3);
+        for (int64_t e = row_beg[ih] + threadIdx.x; e < end; e += 4 * 256) {  // up to four index -> bit chains in flight
+            int32_t u[4];
+#pragma unroll
+            for (int j = 0; j < 4; ++j) u[j] = e + j * 256 < end ? colidx[e + j * 256] : -1;
+#pragma unroll
+            for (int j = 0; j < 4; ++j)
+                if (u[j] >= 0) ch += member_bit(member, u[j]);
         }
-        for (; e < end; e += 256) ch += member_bit(member, colidx[e]);
 #pragma unroll
         for (int d = kWave / 2; d >= 1; d >>= 1) ch += __shfl_xor(ch, d, kWave);
         if ((threadIdx.x & (kWave - 1)) == 0) wave_part[threadIdx.x / kWave] = ch;
