@@ -475,7 +475,7 @@ static int tf_bwd_data_typed(int64_t n, const T *g, const T *h, int64_t ld_next,
     do {                                                                                               \
         SideGrad<true, T, VA_, R_> a{g, h, dYn, F_out, Fp, ld_next, ldy, n};                           \
         SideWeightsT<VB_> b{W_self, W_neigh, F_in, F_out, Fp};                                         \
-        launch_gemm<128, 128, 32, 2, 2, false, T>(name, a, b, e, n, F_in, K, kps, 1, nullptr, s);         \
+        launch_gemm<128, 128, (sizeof(T) == 2 ? 32 : 16), 2, 2, false, T>(name, a, b, e, n, F_in, K, kps, 1, nullptr, s);         \
     } while (0)
 #define TMA_TF_BD2(VA_, VB_)                 \
     do {                                     \
