@@ -439,3 +439,35 @@ class SampledLinkTrainer(LocalTrainer):
         self.backward()
         self._optimizer_step(lr)
         return self.loss
+
+
+class SubgraphPrefetcher:
+    """Partition + induced-subgraph extraction of the NEXT step on a stream of its own while the current step
+    trains (Alg. 1: a trainer's part and its subgraph depend on the assignment seed only, not on the model).
+
+    ``start(seed)`` launches both on the extraction stream, waits on the host for the two sizes (the library's
+    extraction call returns them) and hands back ``(subgraph dict, event)``; the consumer's stream waits for the
+    event before its first kernel that reads the subgraph.  The host therefore never stalls the training stream for
+    the sizes: they arrive while the previous step is still running.  ``after``: an event the extraction must wait
+    for before it may write, namely the end of the last training step that read buffers which this extraction
+    could be handed again by the allocator (the step before the one now running).  Host logic only.
+    """
+
+    def __init__(self, rowptr, colidx, n_nodes: int, K: int, p: int, cap_n_loc=None, cap_nnz_loc=None, cluster=None,
+                 n_clusters: int = 0):
+        self.rowptr, self.colidx, self.n_nodes, self.K, self.p = rowptr, colidx, int(n_nodes), int(K), int(p)
+        self.cap_n_loc, self.cap_nnz_loc = cap_n_loc, cap_nnz_loc
+        self.cluster, self.n_clusters = cluster, n_clusters
+        self.stream = torch.cuda.Stream(device=rowptr.device)        # default priority
+        self.part = torch.empty(self.n_nodes, dtype=torch.int32, device=rowptr.device)
+
+    def start(self, seed: int, after=None):
+        with torch.cuda.stream(self.stream):
+            if after is not None:
+                self.stream.wait_event(after)
+            B.tma_partition(self.n_nodes, self.K, seed, cluster=self.cluster, n_clusters=self.n_clusters, out=self.part)
+            sub = B.tma_induced_subgraph(self.rowptr, self.colidx, self.part, self.p, cap_n_loc=self.cap_n_loc,
+                                         cap_nnz_loc=self.cap_nnz_loc)
+            done = torch.cuda.Event()
+            done.record(self.stream)
+        return sub, done
