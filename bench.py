@@ -258,7 +258,8 @@ def main():
     # The next step's partition + extraction run on a second stream while this step trains (they depend on the
     # assignment seed only), so the host's wait for the subgraph sizes never idles the training stream.  Every
     # step still does all of its own work: K timed steps = K extractions + K training passes.
-    prefetch = None if args.no_prefetch else SubgraphPrefetcher(d_rowptr, d_colidx, N, K, p, cap, cap_nnz)
+    prefetch = None if args.no_prefetch else SubgraphPrefetcher(d_rowptr, d_colidx, N, K, p, cap, cap_nnz,
+                                                                tables=(d_X,) if sampled else (d_X, d_y))
     state = {"next": None, "trained": None}
 
     def step():
@@ -268,10 +269,12 @@ def main():
         else:
             if state["next"] is None:
                 state["next"] = prefetch.start(sd["part"])
-            s, ready = state["next"]
+            s, rows, ready = state["next"]
             torch.cuda.current_stream().wait_event(ready)
-        B.tma_gather_rows(s["l2g"], d_X, out=Xl)
-        B.tma_gather_rows(s["l2g"], d_y, out=yl)
+            tr.set_data(*rows)
+        if prefetch is None:
+            B.tma_gather_rows(s["l2g"], d_X, out=Xl)
+            B.tma_gather_rows(s["l2g"], d_y, out=yl)
         if sampled:
             tr.set_graph(s["rowptr"], s["colidx"], s["nnz_loc"])
         else:

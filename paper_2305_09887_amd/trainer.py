@@ -133,6 +133,18 @@ class LocalTrainer:
         if self.encoder == "gcn":
             B.tma_gcn_norm(rowptr, out=self.s_norm, stream=self.stream)
 
+    def set_data(self, X, labels=None):
+        """Point the trainer at other feature rows (and labels) for the same nodes, e.g. the other half of a
+        double buffer that a second stream has filled."""
+        if X.shape != self.H[0].shape or X.dtype != self.dtype or X.stride() != self.H[0].stride():
+            raise B.TmaError("LocalTrainer.set_data: X differs in shape, dtype or row stride from the one it replaces")
+        if labels is not None and (self.labels is None or labels.shape != self.labels.shape):
+            raise B.TmaError("LocalTrainer.set_data: labels differ in shape from the ones they replace")
+        self.X = X
+        self.H[0] = X
+        if labels is not None:
+            self.labels = labels
+
     def _views(self, flat):
         out, o = [], 0
         for l, (fi, fo) in enumerate(zip(self.dims[:-1], self.dims[1:])):
@@ -378,6 +390,12 @@ class SampledLinkTrainer(LocalTrainer):
             raise B.TmaError("SampledLinkTrainer.set_graph: node count or entry count beyond the allocated buffers")
         self.rowptr, self.colidx, self.nnz = rowptr, colidx, int(nnz)
 
+    def set_data(self, X, labels=None):
+        """Point the trainer at another feature table over the same nodes."""
+        if X.shape != self.X.shape or X.dtype != self.dtype or not X.is_contiguous():
+            raise B.TmaError("SampledLinkTrainer.set_data: X differs in shape or dtype from the one it replaces")
+        self.X = X
+
     def sample(self):
         """The batch of this step and its message-flow graph: node lists, blocks, input features."""
         L, Bn, st = self.L, self.batch_size, self.stream
@@ -442,24 +460,34 @@ class SampledLinkTrainer(LocalTrainer):
 
 
 class SubgraphPrefetcher:
-    """Partition + induced-subgraph extraction of the NEXT step on a stream of its own while the current step
-    trains (Alg. 1: a trainer's part and its subgraph depend on the assignment seed only, not on the model).
+    """Partition + induced-subgraph extraction + row gathers of the NEXT step on a stream of its own while the
+    current step trains (Alg. 1: a trainer's part, its subgraph and its feature rows depend on the assignment seed
+    only, not on the model).
 
-    ``start(seed)`` launches both on the extraction stream, waits on the host for the two sizes (the library's
-    extraction call returns them) and hands back ``(subgraph dict, event)``; the consumer's stream waits for the
-    event before its first kernel that reads the subgraph.  The host therefore never stalls the training stream for
-    the sizes: they arrive while the previous step is still running.  ``after``: an event the extraction must wait
-    for before it may write, namely the end of the last training step that read buffers which this extraction
-    could be handed again by the allocator (the step before the one now running).  Host logic only.
+    ``start(seed)`` launches them on the extraction stream, waits on the host for the two sizes (the library's
+    extraction call returns them) and hands back ``(subgraph dict, gathered tables, event)``; the consumer's stream
+    waits for the event before its first kernel that reads any of it.  The host therefore never stalls the training
+    stream for the sizes: they arrive while the previous step is still running.  ``tables``: global per-node arrays
+    whose local rows are gathered into one of two buffers each (capacity cap_n_loc rows), alternating between
+    calls.  ``after``: an event the work must wait for before it may write, namely the end of the last training
+    step that read what this call overwrites or may be handed again by the allocator (the step before the one now
+    running).  Host logic only.
     """
 
     def __init__(self, rowptr, colidx, n_nodes: int, K: int, p: int, cap_n_loc=None, cap_nnz_loc=None, cluster=None,
-                 n_clusters: int = 0):
+                 n_clusters: int = 0, tables=()):
         self.rowptr, self.colidx, self.n_nodes, self.K, self.p = rowptr, colidx, int(n_nodes), int(K), int(p)
         self.cap_n_loc, self.cap_nnz_loc = cap_n_loc, cap_nnz_loc
         self.cluster, self.n_clusters = cluster, n_clusters
-        self.stream = torch.cuda.Stream(device=rowptr.device)        # default priority
-        self.part = torch.empty(self.n_nodes, dtype=torch.int32, device=rowptr.device)
+        dev = rowptr.device
+        self.stream = torch.cuda.Stream(device=dev)        # default priority
+        self.part = torch.empty(self.n_nodes, dtype=torch.int32, device=dev)
+        self.tables = list(tables)
+        if self.tables and cap_n_loc is None:
+            raise B.TmaError("SubgraphPrefetcher: gathering tables needs cap_n_loc")
+        self.slot = 0
+        self.buffers = [[torch.empty((int(cap_n_loc),) + tuple(t.shape[1:]), dtype=t.dtype, device=dev) for t in self.tables]
+                        for _ in range(2)]
 
     def start(self, seed: int, after=None):
         with torch.cuda.stream(self.stream):
@@ -468,6 +496,9 @@ class SubgraphPrefetcher:
             B.tma_partition(self.n_nodes, self.K, seed, cluster=self.cluster, n_clusters=self.n_clusters, out=self.part)
             sub = B.tma_induced_subgraph(self.rowptr, self.colidx, self.part, self.p, cap_n_loc=self.cap_n_loc,
                                          cap_nnz_loc=self.cap_nnz_loc)
+            gathered = [B.tma_gather_rows(sub["l2g"], t, out=buf[:sub["n_loc"]])
+                        for t, buf in zip(self.tables, self.buffers[self.slot])]
+            self.slot ^= 1
             done = torch.cuda.Event()
             done.record(self.stream)
-        return sub, done
+        return sub, gathered, done

@@ -19,7 +19,7 @@ def _run(prefetch: bool, steps: int):
     d_rp, d_ci = d(rowptr), d(colidx)
     d_X, d_y = d(synth.features(N, dims[0], seed=2)), d(synth.labels(N, dims[-1], seed=3))
     cap, cap_nnz = N // K + N // 16, int(rowptr[-1]) // (K * K) * 2 + 4096
-    pf = SubgraphPrefetcher(d_rp, d_ci, N, K, p, cap, cap_nnz) if prefetch else None
+    pf = SubgraphPrefetcher(d_rp, d_ci, N, K, p, cap, cap_nnz, tables=(d_X, d_y)) if prefetch else None
     part = torch.empty(N, dtype=torch.int32, device="cuda")
     W = torch.as_tensor(np.concatenate([np.asarray(t, np.float32).ravel() for l in synth.sage_params(dims, seed=5)
                                         for t in l])).cuda()
@@ -31,10 +31,11 @@ def _run(prefetch: bool, steps: int):
         else:
             if nxt is None:
                 nxt = pf.start(100 + t)
-            s, ready = nxt
+            s, (Xl, yl), ready = nxt
             torch.cuda.current_stream().wait_event(ready)
         sizes.append((s["n_loc"], s["nnz_loc"]))
-        Xl, yl = B.tma_gather_rows(s["l2g"], d_X), B.tma_gather_rows(s["l2g"], d_y)
+        if pf is None:
+            Xl, yl = B.tma_gather_rows(s["l2g"], d_X), B.tma_gather_rows(s["l2g"], d_y)
         # the trainer's buffers are sized for one node count: a new one per step, carrying the weights over
         tr = LocalTrainer(s["rowptr"], s["colidx"], s["inv_deg"], Xl, yl, dims)
         assert tr.W.numel() == W.numel()
