@@ -157,8 +157,8 @@ def main():
     ap.add_argument("--prefetch", action="store_true",
                     help="run the timed loop with the next step's partition, extraction and row gathers on a second "
                          "stream (kernels then overlap, so per-kernel durations no longer measure a kernel alone)")
-    ap.add_argument("--no-two-stream", action="store_true",
-                    help="skip the second, two-stream measurement that is reported beside the headline")
+    ap.add_argument("--headline-only", action="store_true",
+                    help="skip the measurements reported beside the headline: per-layer fwd+bwd times, the two-stream loop")
     ap.add_argument("--norm-act", action="store_true",
                     help="hidden layers with layer normalisation + PReLU (the paper's encoder variant) instead of "
                          "ReLU; a second measurement, not the headline workload")
@@ -317,9 +317,23 @@ def main():
     ms_per_step = elapsed * 1e3 / args.steps
     loss = float(tr.loss.item())
 
+    # beside the headline: every encoder layer's forward and backward bracketed by events, median over 20 more steps
+    per_layer = None
+    if not sampled and not args.headline_only:
+        tr.time_layers(True)
+        for _ in range(20):
+            step()
+        t_layers = tr.layer_times_ms()
+        tr.time_layers(False)
+        per_layer = []
+        for l in range(L):
+            f, b = float(np.median(t_layers["fwd"][l])), float(np.median(t_layers["bwd"][l]))
+            per_layer.append({"layer": l, "F_in": dims[l], "F_out": dims[l + 1], "fwd_ms": round(f, 4), "bwd_ms": round(b, 4),
+                              "edges_per_s": round(nnz_loc / ((f + b) * 1e-3), 1)})
+
     # second measurement, reported beside the headline: the same K steps with the two-stream loop
     two_stream_ms = None
-    if not args.prefetch and not args.no_two_stream:
+    if not args.prefetch and not args.headline_only:
         for _ in range(max(args.warmup, 2)):
             step(two_stream)
         torch.cuda.synchronize()
@@ -406,6 +420,8 @@ def main():
         "final_loss": loss,
         "streams": 2 if args.prefetch else 1,
     }
+    if per_layer is not None:
+        out["per_layer_fwd_bwd"] = per_layer      # edges_per_s = nnz_loc / (fwd + bwd) of that layer alone
     if two_stream_ms is not None:
         out["two_stream"] = {"ms_per_step": round(two_stream_ms, 4), "value": round(value * ms_per_step / two_stream_ms, 1),
                              "unit": "edges/s", "steps": args.steps,

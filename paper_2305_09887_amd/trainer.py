@@ -204,14 +204,36 @@ class LocalTrainer:
             B.tma_dense_bwd(self.H[l], out_act, self.dH[l + 1], lin[0], act, dW=g[0], dbias=g[1], dX_out=self.dH[l],
                             need_dX=l > 0, ws=self.ws, stream=self.stream)
 
+    def time_layers(self, on: bool = True):
+        """Bracket every encoder layer's forward and backward with a pair of events on the trainer's stream
+        (aggregation, products, normalisation of that layer); `layer_times_ms()` reads them back."""
+        self._layer_events = {"fwd": [[] for _ in range(self.L)], "bwd": [[] for _ in range(self.L)]} if on else None
+
+    def _mark(self, which, l):
+        ev = getattr(self, "_layer_events", None)
+        if ev is None:
+            return None
+        e = torch.cuda.Event(enable_timing=True)
+        e.record(self.stream)
+        ev[which][l].append(e)
+        return e
+
+    def layer_times_ms(self):
+        """{"fwd": [[ms per recorded pass] per layer], "bwd": ...}; waits for the stream."""
+        self.stream.synchronize()
+        ev = self._layer_events
+        return {w: [[a.elapsed_time(b) for a, b in zip(per[0::2], per[1::2])] for per in ev[w]] for w in ("fwd", "bwd")}
+
     def forward(self):
         for l in range(self.L):
+            self._mark("fwd", l)
             if self.norm_act and l < self.L - 1:
                 gamma, beta, slope = self.layers[l][self.n_lin:]
                 self._layer_fwd(l, B.TMA_ACT_NONE, self.Z[l + 1])
                 B.tma_layernorm_prelu_fwd(self.Z[l + 1], gamma, beta, slope, out=self.H[l + 1], stream=self.stream)
-                continue
-            self._layer_fwd(l, B.TMA_ACT_RELU if l < self.L - 1 else B.TMA_ACT_NONE, self.H[l + 1])
+            else:
+                self._layer_fwd(l, B.TMA_ACT_RELU if l < self.L - 1 else B.TMA_ACT_NONE, self.H[l + 1])
+            self._mark("fwd", l)
         return self.H[self.L]
 
     def _draw_batch(self):
@@ -253,6 +275,7 @@ class LocalTrainer:
             B.tma_softmax_ce(self.H[self.L], self.labels, loss_out=self.loss, dlogits_out=self.dH[self.L],
                              ws=self.ws, stream=self.stream)
         for l in range(self.L - 1, -1, -1):
+            self._mark("bwd", l)
             act = B.TMA_ACT_RELU if l < self.L - 1 else B.TMA_ACT_NONE
             out_act = self.H[l + 1]
             if self.norm_act and l < self.L - 1:
@@ -263,6 +286,7 @@ class LocalTrainer:
                                           dgamma=dgamma, dbeta=dbeta, dslope=dslope, ws=self.ws, stream=self.stream)
                 act, out_act = B.TMA_ACT_NONE, self.Z[l + 1]
             self._layer_bwd(l, act, out_act)
+            self._mark("bwd", l)
 
     def _optimizer_step(self, lr: float):
         if self.optimizer == "adam":
