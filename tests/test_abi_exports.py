@@ -52,3 +52,14 @@ def test_host_side_argument_validation_needs_no_gpu(lib):
     small = lib.tma_sage_layer_bwd_workspace_bytes(ctypes.c_int64(1000), 64, 64, 0, 0)
     large = lib.tma_sage_layer_bwd_workspace_bytes(ctypes.c_int64(1000), 64, 64, 0, 1)
     assert large >= small + 1000 * 64 * 4
+
+
+def test_bench_refuses_more_than_one_gpu():
+    """One GPU only: `bench.py --gpus N` with N > 1 exits with a message that says so (no GPU needed to see it)."""
+    import os
+    import subprocess
+    import sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    r = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"], capture_output=True, text=True,
+                       timeout=300)
+    assert r.returncode != 0 and "ONE GPU" in (r.stdout + r.stderr)
