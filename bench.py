@@ -14,6 +14,7 @@ from __future__ import annotations
 import argparse
 import json
 import os
+import re
 import sys
 import time
 
@@ -24,6 +25,7 @@ if ROOT not in sys.path:
 # MI355X published peaks
 PEAK_HBM_GBS = 8000.0
 PEAK_MFMA_F32_TFLOPS = 157.3
+PEAK_MFMA_BF16_TFLOPS = 2500.0
 
 WORKLOAD = dict(n_nodes=1_000_000, avg_degree=20, gamma=2.1, K=8, part=0, F=128, hidden=256, classes=47,
                 seeds=dict(graph=11, feat=12, label=13, part=14, weights=15), lr=1e-3)
@@ -46,12 +48,22 @@ MEASURED_TRAFFIC_BYTES = {
 }
 
 
-def link_kernel_work(name, n, nnz, dims, dec_dims, Bn):
+def canonical(name, s):
+    """Kernel name as the work tables spell it: without the storage / path suffixes, and with a gather's
+    16-byte pieces per row counted as for fp32 rows (a bf16 row of the same width has half as many)."""
+    name = name.replace("_generic", "")
+    m = re.match(r"(spmm_[a-z]+)_(?:f32|bf16)_g(\d+)x1$", name)
+    if m:
+        return "%s_f32_g%dx1" % (m.group(1), int(m.group(2)) * 4 // s)
+    return name.replace("_bf16", "")
+
+
+def link_kernel_work(name, n, nnz, dims, dec_dims, Bn, s=4):
     """Same for the link-prediction task with the SAGE encoder (both layers aggregate first), mean over the
     launches of a step where a kernel name is launched with different shapes."""
     F0, F1, F2 = dims
     D0, D1, _ = dec_dims
-    s, rows = 4, 2 * Bn
+    rows = 2 * Bn
     gather = lambda F: 2.0 * n * F * s + nnz * 4 + n * 8          # rows once + ids + rowptr, 1/deg + output
     table = {
         "gemm_fwd_128x128": ("mfma", (2.0 * n * 2 * F0 * F1 + 2.0 * n * 2 * F1 * F2) / 2),
@@ -69,30 +81,30 @@ def link_kernel_work(name, n, nnz, dims, dec_dims, Bn):
         "prelu_fwd": ("hbm", 2.0 * rows * D1 * s),
         "prelu_bwd": ("hbm", 3.0 * rows * D1 * s),
     }
-    return table.get(name.replace("_generic", ""), (None, 0.0))
+    return table.get(canonical(name, s), (None, 0.0))
 
 
-def gathered_bytes(name, n, nnz, dims):
+def gathered_bytes(name, n, nnz, dims, s=4):
     """Bytes a gather kernel of the headline workload requests when every gathered neighbour row is counted (no
     reuse between rows), next to the algorithmic bytes of kernel_work that count each distinct input row once."""
     F0, F1, C = dims
-    Cp, s = (C + 3) // 4 * 4, 4
+    Cp = (C * s + 15) // 16 * 16 // s
     return {
         "spmm_mean_f32_g32x1": nnz * (F0 * s + 4) + n * (F0 * s + 8),
         "spmm_combine_f32_g12x1": nnz * (Cp * s + 4) + n * (2 * Cp * s + 8),
         "spmm_sum_f32_g12x1": nnz * (Cp * s + 4) + n * (Cp * s + 4),
-    }.get(name)
+    }.get(canonical(name, s))
 
 
-def kernel_work(name, n, nnz, dims, N=0, nnz_glob=0, K=1, n_params=0, encoder="sage"):
+def kernel_work(name, n, nnz, dims, N=0, nnz_glob=0, K=1, n_params=0, encoder="sage", s=4):
     """Algorithmic work of one launch of kernel `name` in this workload: ("mfma", flops) or ("hbm", bytes).
 
     Bytes count every array the kernel must touch once (distinct input rows once, however often they are
     gathered; outputs once); flops count the products of the layer's definition, not the padding.  A kernel
     name that both layers launch (the GCN / MLP encoders) gets the mean over its launches of a step."""
     F0, F1, C = dims
-    Cp = (C + 3) // 4 * 4        # padded width of the transform-first blocks
-    s = 4
+    Cp = (C * s + 15) // 16 * 16 // s        # padded width of the transform-first blocks (rows of whole 16-byte pieces)
+    name = canonical(name, s)
     if encoder != "sage":
         both = (2.0 * n * F0 * F1 + 2.0 * n * F1 * C) / 2
         other = {
@@ -106,8 +118,8 @@ def kernel_work(name, n, nnz, dims, N=0, nnz_glob=0, K=1, n_params=0, encoder="s
             # Q = S dZ of layer 1: dH2 read, Q written, s read
             "scale_mask_colsum": ("hbm", n * (C + Cp) * s + n * 4.0),
         }
-        if name.replace("_generic", "") in other:
-            return other[name.replace("_generic", "")]
+        if name in other:
+            return other[name]
     gemm = {
         "gemm_fwd_128x128": 2.0 * n * (2 * F0) * F1,          # Z1 = [H0 | M0] [Ws; Wn]
         "gemm_bwd_weight_128x128": 2.0 * n * (2 * F0) * F1,   # [dWs; dWn] = [H0 | M0]^T dZ1
@@ -115,7 +127,6 @@ def kernel_work(name, n, nnz, dims, N=0, nnz_glob=0, K=1, n_params=0, encoder="s
         "gemm_tf_bwd_weight": 2.0 * n * F1 * (2 * C),         # [dWs | dWn] = H1^T [dZ | dYn]
         "gemm_tf_bwd_data": 2.0 * n * (2 * C) * F1,           # dH1 = [dZ | dYn] [Ws | Wn]^T
     }
-    name = name.replace("_generic", "")
     if name in gemm:
         return "mfma", gemm[name]
     rows_glob = nnz_glob / max(K, 1)     # global entries of the local rows
@@ -159,6 +170,9 @@ def main():
                          "stream (kernels then overlap, so per-kernel durations no longer measure a kernel alone)")
     ap.add_argument("--headline-only", action="store_true",
                     help="skip the measurements reported beside the headline: per-layer fwd+bwd times, the two-stream loop")
+    ap.add_argument("--dtype", choices=("f32", "bf16"), default="f32",
+                    help="storage of features and activations (bf16: bf16 MFMA products, fp32 accumulation and "
+                         "parameters); the headline workload is fp32, bf16 is a second measurement")
     ap.add_argument("--norm-act", action="store_true",
                     help="hidden layers with layer normalisation + PReLU (the paper's encoder variant) instead of "
                          "ReLU; a second measurement, not the headline workload")
@@ -219,14 +233,17 @@ def main():
 
     dev = torch.device("cuda:0")
     d_rowptr, d_colidx = torch.as_tensor(rowptr).to(dev), torch.as_tensor(colidx).to(dev)
-    d_X, d_y = torch.as_tensor(X).to(dev), torch.as_tensor(y).to(dev)
+    feat_dtype = torch.bfloat16 if args.dtype == "bf16" else torch.float32
+    sb = 2 if args.dtype == "bf16" else 4          # bytes per stored feature / activation element
+    peak_mfma = PEAK_MFMA_BF16_TFLOPS if args.dtype == "bf16" else PEAK_MFMA_F32_TFLOPS
+    d_X, d_y = torch.as_tensor(X).to(dev).to(feat_dtype), torch.as_tensor(y).to(dev)
     part = torch.empty(N, dtype=torch.int32, device=dev)
 
     # set-up pass: learn the local sizes, allocate every persistent buffer
     B.tma_partition(N, K, sd["part"], out=part)
     sub = B.tma_induced_subgraph(d_rowptr, d_colidx, part, p)
     n_loc, nnz_loc = sub["n_loc"], sub["nnz_loc"]
-    Xl = torch.empty((n_loc, dims[0]), dtype=torch.float32, device=dev)
+    Xl = torch.empty((n_loc, dims[0]), dtype=feat_dtype, device=dev)
     yl = torch.empty(n_loc, dtype=torch.int32, device=dev)
     if args.encoder != "sage":   # one weight matrix per layer
         params = [(Ws, b) for Ws, _, b in params]
@@ -347,17 +364,17 @@ def main():
     kw = dict(N=N, nnz_glob=int(rowptr[-1]), K=K, n_params=int(tr.W.numel()), encoder=args.encoder)
     def work_of(k):
         if args.task == "link" and args.encoder == "sage":
-            hit = link_kernel_work(k, n_loc, nnz_loc, dims, dec_dims, args.batch)
+            hit = link_kernel_work(k, n_loc, nnz_loc, dims, dec_dims, args.batch, s=sb)
             if hit[0]:
                 return hit
         if args.task != "node" and k.startswith(("gemm", "spmm", "scale_mask", "softmax", "ln_prelu", "pair_", "prelu")):
             return None, 0.0     # shapes of the link task that the tables do not cover
-        return kernel_work(k, n_loc, nnz_loc, dims, **kw)
+        return kernel_work(k, n_loc, nnz_loc, dims, s=sb, **kw)
 
     bound, work = work_of(dominant)
     avg_ms = dom[1] / max(dom[0], 1)
     if bound == "mfma":
-        achieved, peak, unit = work / (avg_ms * 1e-3) / 1e12, PEAK_MFMA_F32_TFLOPS, "TFLOP/s"
+        achieved, peak, unit = work / (avg_ms * 1e-3) / 1e12, peak_mfma, "TFLOP/s"
     else:
         bound = "hbm"
         achieved, peak, unit = work / (avg_ms * 1e-3) / 1e9, PEAK_HBM_GBS, "GB/s"
@@ -377,14 +394,14 @@ def main():
         per_launch_s = ms * 1e-3 / launches
         traffic = MEASURED_TRAFFIC_BYTES.get(k.replace("_generic", ""))
         if b == "mfma":
-            kernel_rooflines[k] = {"bound": b, "achieved": round(wk / per_launch_s / 1e12, 2), "peak": PEAK_MFMA_F32_TFLOPS,
-                                   "unit": "TFLOP/s", "frac": round(wk / per_launch_s / 1e12 / PEAK_MFMA_F32_TFLOPS, 4), "traffic": traffic,
+            kernel_rooflines[k] = {"bound": b, "achieved": round(wk / per_launch_s / 1e12, 2), "peak": peak_mfma,
+                                   "unit": "TFLOP/s", "frac": round(wk / per_launch_s / 1e12 / peak_mfma, 4), "traffic": traffic,
                                    "traffic_GBs": round(traffic / per_launch_s / 1e9, 1) if traffic else None}
         else:
             kernel_rooflines[k] = {"bound": b, "achieved": round(wk / per_launch_s / 1e9, 1), "peak": PEAK_HBM_GBS,
                                    "unit": "GB/s", "frac": round(wk / per_launch_s / 1e9 / PEAK_HBM_GBS, 4), "traffic": traffic,
                                    "traffic_GBs": round(traffic / per_launch_s / 1e9, 1) if traffic else None}
-            gb = gathered_bytes(k, n_loc, nnz_loc, dims) if args.task == "node" and args.encoder == "sage" else None
+            gb = gathered_bytes(k, n_loc, nnz_loc, dims, s=sb) if args.task == "node" and args.encoder == "sage" else None
             if gb:    # every gathered row counted: the rate at which the kernel pulls rows through the memory system
                 kernel_rooflines[k]["gathered_GBs"] = round(gb / per_launch_s / 1e9, 1)
                 kernel_rooflines[k]["gathered_frac"] = round(gb / per_launch_s / 1e9 / PEAK_HBM_GBS, 4)
@@ -405,8 +422,8 @@ def main():
         "metric": "trainer edges/sec per SAGE layer fwd+bwd; achieved HBM GB/s vs peak",
         "value": round(value, 1), "unit": "edges/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "f32", "data": "synthetic",
-        "config": {"workload": "configs[1]: Chung-Lu power-law graph (gamma 2.1), 1M nodes, avg degree 20, 128-d fp32 "
+        "dtype": args.dtype, "data": "synthetic",
+        "config": {"workload": "configs[1]: Chung-Lu power-law graph (gamma 2.1), 1M nodes, avg degree 20, 128-d " + ("fp32 " if args.dtype == "f32" else "bf16 (second measurement; the configuration names fp32) ") +
                                "features, 47 classes; K=8 random node partitions; whole path per step = partition + "
                                "induced-subgraph extraction of part 0 + row gather + 2-layer mean-SAGE (hidden 256) "
                                "full-batch fwd+bwd+SGD + 8-way parameter averaging",
@@ -428,7 +445,7 @@ def main():
                              "what": "the same steps with the next step's partition, extraction and row gathers on a "
                                      "second stream (bench.py --prefetch times that loop as the headline)"}
 
-    if not args.no_cpu_baseline and args.task == "node":
+    if not args.no_cpu_baseline and args.task == "node" and args.dtype == "f32":
         import oracle
         from oracle import model as omodel
         t_cpu = time.perf_counter()
