@@ -74,6 +74,12 @@ const char *tma_last_error(void);
 int tma_partition(int64_t n_nodes, const int32_t *cluster, int64_t n_clusters,
                   int32_t K, uint64_t seed, int32_t *part_out, tma_stream_t stream);
 
+/* The generator itself, on the host: SplitMix64(seed, unit) as defined above (the paper asks for random,
+ * independent assignment, Sec. 3.2.2, and names no generator).  For callers that derive one seed from another
+ * with the library's own rule, e.g. the neighbour sampler's seed of step t and layer l,
+ * tma_mix64(batch_seed, 64 t + l).  Pure function; no GPU work. */
+uint64_t tma_mix64(uint64_t seed, uint64_t unit);
+
 /* ------------------------------------------------------------------------
  * Node-induced subgraph of partition p (paper, Preliminaries):
  *   V^(p) = { v : part[v] = p },  E^(p) = { (u,v) in E : u, v in V^(p) }.

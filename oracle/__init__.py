@@ -95,11 +95,23 @@ def induced_subgraph(rowptr, colidx, part, p: int):
     return dict(g2l=g2l, l2g=l2g, rowptr=rp, colidx=ci, inv_deg=inv)
 
 
+# ------------------------------------------------------- storage formats
+def round_bf16(a) -> np.ndarray:
+    """Nearest bfloat16 value (8 significant bits, ties to even) of every entry, returned as fp64.
+
+    Written from the format's definition: x = m * 2^e with 1/2 <= |m| < 1, and m is rounded to a multiple of
+    2^-8.  Normal range only (no subnormals, no overflow): the test data stays far inside it."""
+    m, e = np.frexp(np.asarray(a, dtype=np.float64))
+    return np.ldexp(np.rint(np.ldexp(m, 8)), e - 8)
+
+
 # -------------------------------------------------------------- aggregation
 def mean_aggregate(rowptr, colidx, H) -> np.ndarray:
+    """M = Abar H.  On a bipartite block (fewer graph rows than rows of H) M has one row per graph row."""
     rowptr, colidx, H = _i32(rowptr), _i32(colidx), _f64(H)
-    n, F = H.shape
-    M = np.empty_like(H)
+    n, F = rowptr.shape[0] - 1, H.shape[1]
+    assert n <= H.shape[0]
+    M = np.empty((n, F))
     lib().orc_mean_aggregate(C.c_int64(n), _p(rowptr), _p(colidx), _p(H), C.c_int64(F), _p(M))
     return M
 

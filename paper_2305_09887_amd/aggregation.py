@@ -51,7 +51,10 @@ class AggregationTrigger:
 class ModelAggregation:
     """M local trainers on M streams with on-device parameter averaging."""
 
-    def __init__(self, trainers, active_mask: int | None = None):
+    def __init__(self, trainers, active_mask: int | None = None, record_rounds: int = 0):
+        """``record_rounds`` > 0 keeps, for the first that many aggregations, every trainer's parameters as they are
+        on the aggregation stream right before and right after phi (``rec_before`` / ``rec_after`` [round, trainer,
+        n_params]) and the mean (``rec_global``): copies enqueued on that stream, for checking the ordering."""
         if not trainers:
             raise B.TmaError("ModelAggregation: no trainers")
         n = trainers[0].n_params
@@ -67,6 +70,11 @@ class ModelAggregation:
         self.done = [torch.cuda.Event() for _ in trainers]
         self.agg_done = torch.cuda.Event()
         self.history = []   # steps finished by each trainer at every aggregation
+        self.record_rounds = int(record_rounds)
+        if self.record_rounds > 0:
+            self.rec_before = torch.zeros((self.record_rounds, self.M, n), dtype=torch.float32, device=dev)
+            self.rec_after = torch.zeros_like(self.rec_before)
+            self.rec_global = torch.zeros((self.record_rounds, n), dtype=torch.float32, device=dev)
         torch.cuda.synchronize(dev)   # uploads and initial weights are in place before the streams start
 
     def _active(self, i: int) -> bool:
@@ -78,8 +86,19 @@ class ModelAggregation:
             if self._active(i):
                 self.done[i].record(t.stream)
                 self.agg_stream.wait_event(self.done[i])
+        r = len(self.history)
+        rec = r < self.record_rounds
+        if rec:
+            with torch.cuda.stream(self.agg_stream):
+                for i, t in enumerate(self.trainers):
+                    self.rec_before[r, i].copy_(t.W)
         B.tma_average([t.W for t in self.trainers], active_mask=self.active_mask, W_global_out=self.W_global,
                       ptr_table=self.ptr_table, stream=self.agg_stream)
+        if rec:
+            with torch.cuda.stream(self.agg_stream):
+                for i, t in enumerate(self.trainers):
+                    self.rec_after[r, i].copy_(t.W)
+                self.rec_global[r].copy_(self.W_global)
         self.agg_done.record(self.agg_stream)
         for i, t in enumerate(self.trainers):
             if self._active(i):

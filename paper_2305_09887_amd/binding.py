@@ -19,7 +19,7 @@ TMA_F32, TMA_BF16 = 0, 1
 TMA_ACT_NONE, TMA_ACT_RELU = 0, 1
 
 EXPORTS = (
-    "tma_version", "tma_last_error", "tma_partition",
+    "tma_version", "tma_last_error", "tma_partition", "tma_mix64",
     "tma_induced_subgraph_workspace_bytes", "tma_induced_subgraph_count", "tma_induced_subgraph_fill",
     "tma_induced_subgraph",
     "tma_mean_aggregate", "tma_sage_layer_aggregates_first", "tma_sage_layer_fwd",
@@ -61,8 +61,16 @@ def lib() -> C.CDLL:
                      "tma_bce_logits_workspace_bytes", "tma_neighbor_sample_workspace_bytes",
                      "tma_mfg_relabel_workspace_bytes", "tma_sage_block_bwd_workspace_bytes"):
             getattr(L, name).restype = C.c_size_t
+        L.tma_mix64.restype = C.c_uint64
+        L.tma_mix64.argtypes = [C.c_uint64, C.c_uint64]
         _lib = L
     return _lib
+
+
+def tma_mix64(seed: int, unit: int) -> int:
+    """SplitMix64(seed, unit), the library's generator, on the host (no GPU work)."""
+    m = (1 << 64) - 1
+    return int(lib().tma_mix64(seed & m, unit & m))
 
 
 def _check(rc: int):
@@ -116,8 +124,16 @@ def _same_ld(a, b, what):
         raise TmaError(f"{what}: tensors must share one leading dimension")
 
 
-def _workspace(nbytes: int, device) -> torch.Tensor:
-    return torch.empty(max(int(nbytes), 256), dtype=torch.uint8, device=device)
+def _record(t: torch.Tensor, stream) -> torch.Tensor:
+    """A temporary allocated here (on torch's current stream) but used by kernels on `stream`: tell the caching
+    allocator, so that the memory is not handed out again while those kernels run."""
+    if stream is not None and t.is_cuda and stream != torch.cuda.current_stream(t.device):
+        t.record_stream(stream)
+    return t
+
+
+def _workspace(nbytes: int, device, stream=None) -> torch.Tensor:
+    return _record(torch.empty(max(int(nbytes), 256), dtype=torch.uint8, device=device), stream)
 
 
 def tma_version() -> int:
@@ -153,7 +169,7 @@ def tma_induced_subgraph(rowptr, colidx, part, p: int, cap_n_loc: int | None = N
     cap = n if cap_n_loc is None else min(int(cap_n_loc), n)
     L = lib()
     ws_bytes = L.tma_induced_subgraph_workspace_bytes(C.c_int64(n), C.c_int64(cap))
-    ws = _workspace(ws_bytes, dev)
+    ws = _workspace(ws_bytes, dev, stream)
     g2l = torch.empty(max(n, 1), dtype=torch.int32, device=dev)
     l2g = torch.empty(max(cap, 1), dtype=torch.int32, device=dev)
     rp = torch.empty(cap + 1, dtype=torch.int32, device=dev)
@@ -264,7 +280,7 @@ def tma_sage_layer_bwd(rowptr_T, colidx_T, inv_deg, H, M, Hnext, dHnext, W_self,
     dt = _feat_dtype(H)
     need = tma_sage_layer_bwd_workspace_bytes(n, F_in, F_out, dt, need_dH)
     if ws is None:
-        ws = _workspace(need, dev)
+        ws = _workspace(need, dev, stream)
     _check(lib().tma_sage_layer_bwd(
         C.c_int64(n), _ptr(rowptr_T, torch.int32), _ptr(colidx_T, torch.int32), _ptr(inv_deg, torch.float32),
         C.c_void_p(H.data_ptr()), C.c_int64(ldh), _ptr(M, H.dtype, "M"),
@@ -327,7 +343,7 @@ def tma_dense_bwd(X, Y, dY, W, act: int, dW=None, dbias=None, dX_out=None, need_
     if act == TMA_ACT_RELU:
         _same_ld(Y, dY, "tma_dense_bwd: Y / dY")
     if ws is None:
-        ws = _workspace(tma_dense_bwd_workspace_bytes(n, F_in, F_out), dev)
+        ws = _workspace(tma_dense_bwd_workspace_bytes(n, F_in, F_out), dev, stream)
     _check(lib().tma_dense_bwd(
         C.c_int64(n), C.c_void_p(X.data_ptr()), C.c_int64(ldx), C.c_void_p(Y.data_ptr() if Y is not None else 0),
         C.c_void_p(dY.data_ptr()), C.c_int64(ldy), _ptr(W, torch.float32, "W"), C.c_int32(F_in), C.c_int32(F_out),
@@ -409,7 +425,7 @@ def tma_gcn_layer_bwd(rowptr_T, colidx_T, s_norm, H, M, Hnext, dHnext, W, act: i
         _same_ld(Hnext, dHnext, "tma_gcn_layer_bwd: Hnext / dHnext")
     dt = _feat_dtype(H)
     if ws is None:
-        ws = _workspace(tma_gcn_layer_bwd_workspace_bytes(n, F_in, F_out, dt, need_dH), dev)
+        ws = _workspace(tma_gcn_layer_bwd_workspace_bytes(n, F_in, F_out, dt, need_dH), dev, stream)
     _check(lib().tma_gcn_layer_bwd(
         C.c_int64(n), _ptr(rowptr_T, torch.int32), _ptr(colidx_T, torch.int32), _ptr(s_norm, torch.float32, "s_norm"),
         C.c_void_p(H.data_ptr()), C.c_int64(ldh), _ptr(M, H.dtype, "M"),
@@ -479,7 +495,7 @@ def tma_pair_product_bwd(R, u, v, vneg, dE0, dR_out=None, ws=None, stream=None):
     _, _, ld_dr = _rows_ld(dR_out, "dR_out")
     dt = _feat_dtype(R)
     if ws is None:
-        ws = _workspace(tma_pair_product_bwd_workspace_bytes(n, Bn, F, dt), R.device)
+        ws = _workspace(tma_pair_product_bwd_workspace_bytes(n, Bn, F, dt), R.device, stream)
     _check(lib().tma_pair_product_bwd(
         C.c_int64(n), C.c_int64(Bn), C.c_int32(F), C.c_void_p(R.data_ptr()), C.c_int64(ldr), C.c_int32(dt),
         _ptr(u, torch.int32, "u"), _ptr(v, torch.int32, "v"), _ptr(vneg, torch.int32, "vneg"),
@@ -520,7 +536,7 @@ def tma_prelu_bwd(Z, dY, slope, dZ_out=None, dslope=None, ws=None, stream=None):
     _, _, ldd = _rows_ld(dY, "dY")
     _, _, ld_dz = _rows_ld(dZ_out, "dZ_out")
     if ws is None:
-        ws = _workspace(tma_prelu_bwd_workspace_bytes(), Z.device)
+        ws = _workspace(tma_prelu_bwd_workspace_bytes(), Z.device, stream)
     _check(lib().tma_prelu_bwd(
         C.c_int64(n), C.c_int32(F), C.c_void_p(Z.data_ptr()), C.c_int64(ldz), C.c_void_p(dY.data_ptr()), C.c_int64(ldd),
         _ptr(slope, torch.float32, "slope"), C.c_int32(_feat_dtype(Z)), C.c_void_p(dZ_out.data_ptr()), C.c_int64(ld_dz),
@@ -547,7 +563,7 @@ def tma_bce_logits(z, n_pos: int, loss_out=None, dz_out=None, need_grad=True, ws
     if dz_out is not None and (tuple(dz_out.shape) != (count, 1) or dz_out.dtype != z.dtype):
         raise TmaError("tma_bce_logits: dz_out shape/dtype")
     if ws is None:
-        ws = _workspace(tma_bce_logits_workspace_bytes(), z.device)
+        ws = _workspace(tma_bce_logits_workspace_bytes(), z.device, stream)
     _check(lib().tma_bce_logits(
         C.c_int64(count), C.c_int64(n_pos), C.c_void_p(z.data_ptr()), C.c_int64(ldz), C.c_int32(_feat_dtype(z)),
         _ptr(loss_out, torch.float32, "loss_out"), C.c_void_p(dz_out.data_ptr() if dz_out is not None else 0),
@@ -575,7 +591,7 @@ def tma_neighbor_sample(dst, n_dst: int, nnz: int, rowptr, colidx, fanout: int, 
     if blk_rowptr_out.numel() < n_dst + 1 or dst.numel() < n_dst or colidx.numel() < nnz:
         raise TmaError("tma_neighbor_sample: dst / blk_rowptr_out / colidx too short")
     if ws is None:
-        ws = _workspace(tma_neighbor_sample_workspace_bytes(n_dst), dev)
+        ws = _workspace(tma_neighbor_sample_workspace_bytes(n_dst), dev, stream)
     _check(lib().tma_neighbor_sample(
         C.c_int64(n_dst), _ptr(dst, torch.int32, "dst"), C.c_int64(nnz), _ptr(rowptr, torch.int32, "rowptr"),
         _ptr(colidx, torch.int32, "colidx"), C.c_int32(fanout), C.c_uint64(seed), _ptr(blk_rowptr_out, torch.int32),
@@ -595,7 +611,7 @@ def tma_mfg_relabel(n: int, dst, n_dst: int, cols, max_items: int, d_items=None,
     if src_out is None:
         src_out = torch.empty(max(min(n, n_dst + max_items), 1), dtype=torch.int32, device=dev)
     if ws is None:
-        ws = _workspace(tma_mfg_relabel_workspace_bytes(n), dev)
+        ws = _workspace(tma_mfg_relabel_workspace_bytes(n), dev, stream)
     n_src = C.c_int64(0)
     _check(lib().tma_mfg_relabel(
         C.c_int64(n), C.c_int64(n_dst), _ptr(dst, torch.int32, "dst") if n_dst > 0 else C.c_void_p(0), C.c_int64(max_items),
@@ -654,7 +670,7 @@ def tma_sage_block_bwd(n_dst: int, n_src: int, max_entries: int, blk_rowptr, blk
     dt = _feat_dtype(H)
     if ws is None:
         ws = _workspace(tma_sage_block_bwd_workspace_bytes(n_dst, n_src, max_entries, F_in, F_out, dt, dH_out is not None),
-                        H.device)
+                        H.device, stream)
     _check(lib().tma_sage_block_bwd(
         C.c_int64(n_dst), C.c_int64(n_src), C.c_int64(max_entries), _ptr(blk_rowptr, torch.int32),
         _ptr(blk_col, torch.int32), _ptr(blk_row, torch.int32), _ptr(inv_deg, torch.float32), C.c_void_p(H.data_ptr()),
@@ -713,7 +729,7 @@ def tma_layernorm_prelu_bwd(Z, dHnext, gamma, beta, slope, eps: float = LN_EPS, 
     if dgamma.numel() != F or dbeta.numel() != F or dslope.numel() != 1:
         raise TmaError("tma_layernorm_prelu_bwd: gradient output sizes")
     if ws is None:
-        ws = _workspace(tma_layernorm_prelu_bwd_workspace_bytes(n, F), dev)
+        ws = _workspace(tma_layernorm_prelu_bwd_workspace_bytes(n, F), dev, stream)
     _, _, ldd = _rows_ld(dHnext, "dHnext")
     _, _, ldo = _rows_ld(dZ_out, "dZ_out")
     _check(lib().tma_layernorm_prelu_bwd(
@@ -738,7 +754,7 @@ def tma_softmax_ce(logits, labels, loss_out=None, dlogits_out=None, need_grad=Tr
     if need_grad and (tuple(dlogits_out.shape) != (n, Cc) or _rows_ld(dlogits_out, "dlogits_out")[2] != ldz):
         raise TmaError("tma_softmax_ce: dlogits_out must have the shape and leading dimension of logits")
     if ws is None:
-        ws = _workspace(tma_loss_workspace_bytes(n, Cc), dev)
+        ws = _workspace(tma_loss_workspace_bytes(n, Cc), dev, stream)
     _check(lib().tma_softmax_ce(C.c_int64(n), C.c_int32(Cc), C.c_void_p(logits.data_ptr()), C.c_int64(ldz),
                                 C.c_int32(_feat_dtype(logits)), _ptr(labels, torch.int32, "labels"),
                                 _ptr(loss_out, torch.float32),
@@ -759,7 +775,7 @@ def tma_sigmoid_l2(G, Y, loss_out=None, dG_out=None, need_grad=True, ws=None, st
     if need_grad and (tuple(dG_out.shape) != (n, Cc) or _rows_ld(dG_out, "dG_out")[2] != ldg):
         raise TmaError("tma_sigmoid_l2: dG_out must have the shape and leading dimension of G")
     if ws is None:
-        ws = _workspace(tma_loss_workspace_bytes(n, Cc), dev)
+        ws = _workspace(tma_loss_workspace_bytes(n, Cc), dev, stream)
     _check(lib().tma_sigmoid_l2(C.c_int64(n), C.c_int32(Cc), C.c_void_p(G.data_ptr()), C.c_int64(ldg),
                                 C.c_int32(_feat_dtype(G)), _ptr(Y, torch.float32, "Y"),
                                 _ptr(loss_out, torch.float32), C.c_void_p(dG_out.data_ptr() if need_grad else 0),
@@ -799,7 +815,8 @@ def tma_average(W_list, active_mask: int | None = None, W_global_out=None, ptr_t
     if active_mask is None:
         active_mask = (1 << M) - 1
     if ptr_table is None:
-        ptr_table = torch.tensor([w.data_ptr() for w in W_list], dtype=torch.int64, device=W_list[0].device)
+        ptr_table = _record(torch.tensor([w.data_ptr() for w in W_list], dtype=torch.int64, device=W_list[0].device),
+                            stream)
     if W_global_out is not None and W_global_out.numel() != n:
         raise TmaError("tma_average: W_global_out size")
     _check(lib().tma_average(_ptr(ptr_table, torch.int64), C.c_int32(M), C.c_uint64(active_mask), C.c_int64(n),

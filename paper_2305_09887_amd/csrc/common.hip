@@ -129,4 +129,6 @@ extern "C" int tma_profile_entry(int index, const char **name_out, int64_t *laun
 
 extern "C" int tma_version(void) { return 100; }
 
+extern "C" uint64_t tma_mix64(uint64_t seed, uint64_t unit) { return tma::splitmix64_at(seed, unit); }
+
 extern "C" const char *tma_last_error(void) { return tma::error_buffer(); }

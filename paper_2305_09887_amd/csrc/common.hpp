@@ -75,7 +75,7 @@ __device__ __forceinline__ uint16_t f32_to_bf16(float f)
 
 // Output number (unit+1) of the SplitMix64 stream (Steele, Lea, Flood 2014) seeded with `seed`: the library's
 // counter-based generator (partition assignment, mini-batch draws).
-__device__ __forceinline__ uint64_t splitmix64_at(uint64_t seed, uint64_t unit)
+__host__ __device__ __forceinline__ uint64_t splitmix64_at(uint64_t seed, uint64_t unit)
 {
     uint64_t z = seed + (unit + 1ull) * 0x9E3779B97F4A7C15ull;
     z = (z ^ (z >> 30)) * 0xBF58476D1CE4E5B9ull;

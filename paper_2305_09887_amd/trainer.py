@@ -306,16 +306,6 @@ class LocalTrainer:
         return self.loss
 
 
-def _splitmix64(seed: int, unit: int) -> int:
-    """Output number unit+1 of the SplitMix64 stream seeded with `seed` (host copy of the library's generator,
-    for deriving per-step seeds)."""
-    m = (1 << 64) - 1
-    z = (seed + (unit + 1) * 0x9E3779B97F4A7C15) & m
-    z = ((z ^ (z >> 30)) * 0xBF58476D1CE4E5B9) & m
-    z = ((z ^ (z >> 27)) * 0x94D049BB133111EB) & m
-    return z ^ (z >> 31)
-
-
 class SampledLinkTrainer(LocalTrainer):
     """Link prediction on the sampled message-flow graph of each mini-batch (Sec. 4.1: random positive edges, one
     random-tail negative each, a GraphSAGE-style sampler that caps the neighbours per node and layer, MLP decoder).
@@ -429,7 +419,7 @@ class SampledLinkTrainer(LocalTrainer):
         for l in range(L - 1, -1, -1):
             n_dst = self.count[l + 1]
             B.tma_neighbor_sample(self.nodes[l + 1], n_dst, self.nnz, self.rowptr, self.colidx, self.fanouts[l],
-                                  _splitmix64(self.batch_seed, 64 * self.steps_done + l), blk_rowptr_out=self.blk_rowptr[l],
+                                  B.tma_mix64(self.batch_seed, 64 * self.steps_done + l), blk_rowptr_out=self.blk_rowptr[l],
                                   blk_col_out=self.blk_col[l], blk_row_out=self.blk_row[l], ws=self.ws, stream=st)
             _, self.count[l] = B.tma_mfg_relabel(self.n, self.nodes[l + 1], n_dst, self.blk_col[l], self.ecap[l],
                                                  d_items=self.blk_rowptr[l][n_dst:n_dst + 1], src_out=self.nodes[l],

@@ -54,6 +54,17 @@ def test_host_side_argument_validation_needs_no_gpu(lib):
     assert large >= small + 1000 * 64 * 4
 
 
+def test_host_generator_reproduces_the_published_vector(lib):
+    """tma_mix64 is host code: the library's generator against the published SplitMix64 outputs for seed 1234567
+    (the same fixture that pins the oracle's), no GPU needed."""
+    lib.tma_mix64.restype = ctypes.c_uint64
+    lib.tma_mix64.argtypes = [ctypes.c_uint64, ctypes.c_uint64]
+    want = [int(tok, 0) for line in open(os.path.join(ROOT, "tests", "golden", "splitmix64_seed1234567.txt"))
+            if not line.startswith("#") for tok in line.split()]
+    assert len(want) >= 5
+    assert [lib.tma_mix64(1234567, i) for i in range(len(want))] == want
+
+
 def test_bench_refuses_more_than_one_gpu():
     """One GPU only: `bench.py --gpus N` with N > 1 exits with a message that says so (no GPU needed to see it)."""
     import os

@@ -4,6 +4,7 @@ normalisation + PReLU, one trainer that never starts (failure mask), determinist
 import numpy as np
 import pytest
 
+import aggcheck
 import oracle
 from oracle import model as omodel
 from paper_2305_09887_amd import synth
@@ -113,21 +114,24 @@ def test_adam_trainers_of_unequal_size_with_a_failed_one_match_oracle(B):
     assert not torch.equal(ms[0], ms[1])
 
 
-def test_wall_clock_trigger_with_unequal_trainers(B):
-    """Time-based aggregation with trainers of very different size (one of them empty): every trainer joins each
-    round at a step boundary, and after an aggregation all of them hold the same weights."""
+@pytest.mark.parametrize("mask", [0b1111, 0b1011])
+def test_wall_clock_trigger_with_unequal_trainers(B, mask):
+    """Time-based aggregation with trainers of very different size (one of them empty; with mask 0b1011 one that
+    never starts, Sec. 4.4): every active trainer joins each round at a step boundary, and in EVERY round the
+    parameters recorded on the aggregation stream satisfy: mean of the active ones before phi = what each of them
+    holds after it; the failed trainer is never touched."""
     from paper_2305_09887_amd.aggregation import ModelAggregation
     trainers, _, _ = _unequal_trainers(B, norm_act=False, optimizer="sgd")
-    agg = ModelAggregation(trainers)
+    w_start = trainers[2].W.clone()
+    agg = ModelAggregation(trainers, active_mask=mask, record_rounds=64)
     hist = agg.run_timed(dt_int=0.03, dt_train=0.2, lr=1e-3)
     agg.synchronize()
     assert len(hist) >= 2
     for steps in hist:
-        assert min(steps) >= 1        # every trainer, the empty one included, joins at a step boundary
+        assert all(s >= 1 for i, s in enumerate(steps) if (mask >> i) & 1)   # the empty trainer included
     # (step counts may or may not differ between trainers: at this size the host's launch rate, not the GPU,
     # paces them; nothing in Alg. 1 depends on it)
-    last = hist[-1]
-    if [t.steps_done for t in trainers] == last:                   # nothing ran after the last aggregation
-        for t in trainers[1:]:
-            assert torch.equal(t.W, trainers[0].W)
+    aggcheck.check_recorded_rounds(agg, min(len(hist), 64), mask)
+    if not (mask >> 2) & 1:
+        assert trainers[2].steps_done == 0 and torch.equal(trainers[2].W, w_start)
     assert torch.isfinite(agg.W_global).all()

@@ -3,6 +3,7 @@ against the oracle running the same schedule (Alg. 1 aggregation + Alg. 2 overwr
 import numpy as np
 import pytest
 
+import aggcheck
 import oracle
 from oracle import model as omodel
 from paper_2305_09887_amd import synth
@@ -80,16 +81,35 @@ def test_failed_trainer_is_left_out():
 
 
 def test_timed_trigger_runs_and_preserves_the_mean_property():
+    """Wall-clock trigger (Alg. 1's interval test): trainers join at a step boundary, step counts are whatever the
+    clock gives, so what is checked is the invariant of every round: the mean of the parameters as they stood on
+    the aggregation stream before phi is what every trainer holds after it."""
     if not torch.cuda.is_available():
         pytest.skip("no GPU")
     from paper_2305_09887_amd import binding as B
     from paper_2305_09887_amd.aggregation import ModelAggregation
     K, dims, lr = 3, [16, 16, 4], 0.05
     trainers, _, _ = _setup(B, 30_000, K, dims, seed=61)
-    agg = ModelAggregation(trainers)
+    agg = ModelAggregation(trainers, record_rounds=64)
     hist = agg.run_timed(dt_int=0.02, dt_train=0.2, lr=lr)
     agg.synchronize()
     assert len(hist) >= 2                                              # several aggregation rounds happened
     assert all(b >= a for r0, r1 in zip(hist, hist[1:]) for a, b in zip(r0, r1))
     assert all(s > 0 for s in hist[-1])
     assert all(torch.isfinite(t.W).all() for t in trainers)
+    aggcheck.check_recorded_rounds(agg, min(len(hist), 64), (1 << K) - 1)
+    # before the first round every trainer had taken at least one step from the common start: they differ
+    first = agg.rec_before[0].cpu().numpy()
+    assert not np.array_equal(first[0], first[1])
+
+
+def test_step_count_trigger_preserves_the_mean_property_with_a_failed_trainer():
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    from paper_2305_09887_amd import binding as B
+    from paper_2305_09887_amd.aggregation import ModelAggregation
+    trainers, _, _ = _setup(B, 12_000, 4, [16, 16, 4], seed=71)
+    agg = ModelAggregation(trainers, active_mask=0b1101, record_rounds=3)
+    agg.run_rounds(3, 2, 0.05)
+    agg.synchronize()
+    aggcheck.check_recorded_rounds(agg, 3, 0b1101)

@@ -4,6 +4,7 @@ is taken in the kernel's precision on both sides (from the kernel's own output),
 import numpy as np
 import pytest
 
+import decisions
 import oracle
 from paper_2305_09887_amd import synth
 
@@ -80,16 +81,17 @@ def test_dense_layer_fp32(B, n, Fi, Fo, act):
     Y = B.tma_dense_fwd(Xd, dev(W), dev(b), act)
     Z, want = oracle.dense_fwd(X, W, b, act)
     close(host(Y), want, 1e-4, "Y")
-    dW, db, dX = B.tma_dense_bwd(Xd, Y, gd, dev(W), act)
-    Zs = np.where(host(Y) > 0, 1.0, -1.0) if act == 1 else Z
-    wW, wb, wX = oracle.dense_bwd(X, Zs, g, W, act)
+    # backward from the ORACLE's forward output on both sides (its sign pattern is the ReLU decision)
+    Yo = padded(B, want)
+    dW, db, dX = B.tma_dense_bwd(Xd, Yo, gd, dev(W), act)
+    wW, wb, wX = oracle.dense_bwd(X, Z, g, W, act)
     close(host(dW), wW, 1e-4, "dW")
     close(host(db), wb, 1e-4, "db")
     close(host(dX), wX, 1e-4, "dX")
     # no bias, no input gradient (a decoder layer's first use; the first layer of an encoder)
     Y0 = B.tma_dense_fwd(Xd, dev(W), None, act)
     close(host(Y0), oracle.dense_fwd(X, W, None, act)[1], 1e-4, "Y without bias")
-    dW0, db0, dX0 = B.tma_dense_bwd(Xd, Y, gd, dev(W), act, need_dbias=False, need_dX=False)
+    dW0, db0, dX0 = B.tma_dense_bwd(Xd, Yo, gd, dev(W), act, need_dbias=False, need_dX=False)
     assert db0 is None and dX0 is None and torch.equal(dW0, dW)
 
 
@@ -99,9 +101,10 @@ def test_dense_layer_bf16(B, n, Fi, Fo):
     X, g = synth.round_bf16(X), synth.round_bf16(g)
     Xd, gd = padded(B, X, True), padded(B, g, True)
     Y = B.tma_dense_fwd(Xd, dev(W), dev(b), 1)
-    close(host(Y), oracle.dense_fwd(X, W, b, 1)[1], 2e-2, "Y")
-    dW, db, dX = B.tma_dense_bwd(Xd, Y, gd, dev(W), 1)
-    wW, wb, wX = oracle.dense_bwd(X, np.where(host(Y) > 0, 1.0, -1.0), g, W, 1)
+    Z, want = oracle.dense_fwd(X, W, b, 1)
+    close(host(Y), want, 2e-2, "Y")
+    dW, db, dX = B.tma_dense_bwd(Xd, padded(B, want, True), gd, dev(W), 1)     # the oracle's output decides the ReLU
+    wW, wb, wX = oracle.dense_bwd(X, Z, g, W, 1)
     close(host(dW), wW, 2e-2, "dW")
     close(host(db), wb, 2e-2, "db")
     close(host(dX), wX, 2e-2, "dX")
@@ -155,13 +158,15 @@ def test_gcn_layer_fp32(B, Fi, Fo, act):
     close(host(Hn), want, 1e-4, "Hnext")
     if B.tma_gcn_layer_aggregates_first(Fi, Fo, B.TMA_F32):
         close(host(Mg), M, 1e-4, "M = Ahat H")
-    dW, db, dH = B.tma_gcn_layer_bwd(rpd, cid, s, Hd, Mg, Hn, gd, dev(W), act)
-    Zs = np.where(host(Hn) > 0, 1.0, -1.0) if act == 1 else Z
-    wW, wb, wH = oracle.gcn_layer_bwd(rp, ci, M, Zs, g, W, act)
+    # backward from the ORACLE's saved state on both sides: its M = Ahat H and its output (whose sign pattern is the
+    # ReLU decision), so nothing the forward kernel produced reaches the expected values
+    Mo, Ho = dev(M.astype(np.float32)), padded(B, want)
+    dW, db, dH = B.tma_gcn_layer_bwd(rpd, cid, s, Hd, Mo, Ho, gd, dev(W), act)
+    wW, wb, wH = oracle.gcn_layer_bwd(rp, ci, M, Z, g, W, act)
     close(host(dW), wW, 1e-4, "dW")
     close(host(db), wb, 1e-4, "db")
     close(host(dH), wH, 1e-4, "dH")
-    dW2, db2, dH2 = B.tma_gcn_layer_bwd(rpd, cid, s, Hd, Mg, Hn, gd, dev(W), act, need_dH=False)
+    dW2, db2, dH2 = B.tma_gcn_layer_bwd(rpd, cid, s, Hd, Mo, Ho, gd, dev(W), act, need_dH=False)
     assert dH2 is None and torch.equal(dW2, dW) and torch.equal(db2, db)     # run to run: the same bits
 
 
@@ -177,8 +182,9 @@ def test_gcn_layer_bf16(B, Fi, Fo):
     Mg, Hn = B.tma_gcn_layer_fwd(rpd, cid, s, Hd, dev(W), dev(b), 1)
     M, Z, want = oracle.gcn_layer_fwd(rp, ci, H, W, b, 1)
     close(host(Hn), want, 2e-2, "Hnext")
-    dW, db, dH = B.tma_gcn_layer_bwd(rpd, cid, s, Hd, Mg, Hn, gd, dev(W), 1)
-    wW, wb, wH = oracle.gcn_layer_bwd(rp, ci, M, np.where(host(Hn) > 0, 1.0, -1.0), g, W, 1)
+    Mo = dev_bf16(M.astype(np.float32)).contiguous()
+    dW, db, dH = B.tma_gcn_layer_bwd(rpd, cid, s, Hd, Mo, padded(B, want, True), gd, dev(W), 1)
+    wW, wb, wH = oracle.gcn_layer_bwd(rp, ci, M, Z, g, W, 1)
     close(host(dW), wW, 2e-2, "dW")
     close(host(db), wb, 2e-2, "db")
     close(host(dH), wH, 2e-2, "dH")
@@ -314,19 +320,30 @@ def test_training_steps_with_other_encoders(B, encoder, norm_act, optimizer):
     assert tr.n_params == omodel.flatten(p_o).size
     lr = 0.05 if optimizer == "sgd" else 0.01
     state, losses = None, []
+    rp, ci = sub["rowptr"], sub["colidx"]
     for step in range(3):
         loss_g = tr.step(lr).item()
-        open_ = [host(tr.H[1]) > 0, host(tr.H[2]) > 0, None]
-        loss_o, grads_o, _, _ = omodel.loss_and_grads(sub["rowptr"], sub["colidx"], Xo, yo, p_o, open_, encoder)
+        t = {}
+        if optimizer == "sgd":
+            loss_o, p_new = omodel.train_step(rp, ci, Xo, yo, p_o, lr, encoder=encoder, trace=t)
+            grads_o = t["grads"]
+        else:
+            loss_o, grads_o, _, _ = omodel.loss_and_grads(rp, ci, Xo, yo, p_o, encoder=encoder, trace=t)
+            _, p_new, state = omodel.train_step_adam(rp, ci, Xo, yo, p_o, lr, state, step + 1, encoder=encoder)
+        D = decisions.differing(t["pre"], [host(tr.H[1]), host(tr.H[2]), None], f"step {step}")
+        bounds = decisions.encoder_bounds(encoder, rp, ci, p_o, t["saved"], t["ups"], D)
         assert abs(loss_g - loss_o) <= 1e-4 * abs(loss_o), f"loss at step {step}"
         for l in range(3):
-            for i, (g, w) in enumerate(zip(tr.grads[l], grads_o[l])):
-                close(host(g).ravel(), np.asarray(w).ravel(), 1e-4, f"step {step} layer {l} gradient {i}")
-        if optimizer == "sgd":
-            _, p_o = omodel.train_step(sub["rowptr"], sub["colidx"], Xo, yo, p_o, lr, open_, encoder)
+            for i, (g, w, bd) in enumerate(zip(tr.grads[l], grads_o[l], bounds[l])):
+                decisions.close(host(g).ravel(), np.asarray(w).ravel(), 1e-4, f"step {step} layer {l} gradient {i}",
+                                extra=bd)
+        p_o = p_new
+        if decisions.any_differs(D):     # a decision next to zero fell the other way: go on from the oracle's state
+            tr.load_params(p_o)
+            if optimizer == "adam":
+                tr.adam_m.copy_(dev(state[0].astype(np.float32)))
+                tr.adam_v.copy_(dev(state[1].astype(np.float32)))
         else:
-            _, p_o, state = omodel.train_step_adam(sub["rowptr"], sub["colidx"], Xo, yo, p_o, lr, state, step + 1, open_,
-                                                   encoder)
-        close(host(tr.W), omodel.flatten(p_o), 1e-4, f"weights after step {step}")
+            close(host(tr.W), omodel.flatten(p_o), 1e-4, f"weights after step {step}")
         losses.append(loss_g)
     assert losses[2] < losses[0]

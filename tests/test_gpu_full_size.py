@@ -6,6 +6,7 @@ bit for bit, logits, loss, every gradient and the updated weights to the fp32 to
 import numpy as np
 import pytest
 
+import decisions
 import oracle
 from oracle import model as omodel
 from paper_2305_09887_amd import synth
@@ -16,12 +17,8 @@ pytestmark = pytest.mark.gpu
 TOL = 1e-4
 
 
-def _close(got, want, what, tol=TOL):
-    got, want = np.asarray(got, dtype=np.float64), np.asarray(want, dtype=np.float64)
-    assert got.shape == want.shape, what
-    rel = np.linalg.norm((got - want).ravel()) / np.linalg.norm(want.ravel())
-    mx = np.abs(got - want).max() / np.abs(want).max()
-    assert rel <= tol and mx <= tol, f"{what}: rel fro {rel:.2e}, max abs / max {mx:.2e}"
+def _close(got, want, what, tol=TOL, extra=0.0):
+    decisions.close(got, want, tol, what, extra=extra)
 
 
 def test_configs1_whole_path_against_oracle():
@@ -55,20 +52,22 @@ def test_configs1_whole_path_against_oracle():
 
     p_o = [tuple(np.asarray(t, dtype=np.float64) for t in l) for l in params]
     Xo, yo = X[sub_o["l2g"]], y[sub_o["l2g"]]
-    # the ReLU open/closed decision is taken in the kernel's precision (fp32) on both sides
-    relu_open = [tr.H[1].cpu().numpy() > 0, None]
-    loss_o, grads_o, logits_o, saved = omodel.loss_and_grads(sub_o["rowptr"], sub_o["colidx"], Xo, yo, p_o, relu_open)
-    flips = int((relu_open[0] != (saved[0][2] > 0)).sum())
-    assert flips <= 1e-5 * relu_open[0].size, f"{flips} ReLU decisions differ between fp32 and fp64"
+    # the oracle takes its own ReLU decisions; where the GPU's differ they must sit next to zero, and what those
+    # few terms can change is added to the tolerance (decisions.py)
+    t = {}
+    loss_o, grads_o, logits_o, saved = omodel.loss_and_grads(sub_o["rowptr"], sub_o["colidx"], Xo, yo, p_o, trace=t)
+    D = decisions.differing(t["pre"], [tr.H[1].cpu().numpy(), None], "configs[1] SAGE step")
+    bounds = decisions.encoder_bounds("sage", sub_o["rowptr"], sub_o["colidx"], p_o, saved, t["ups"], D)
+    print(f"differing ReLU decisions: {int(D[0].sum())} of {D[0].size}; allowed change per tensor {bounds}")
     assert abs(loss_g - loss_o) <= TOL * abs(loss_o)
     _close(tr.M[0].cpu().numpy(), saved[0][1], "M layer 0")
     _close(tr.H[1].cpu().numpy(), saved[1][0], "H layer 1")
     _close(tr.H[2].cpu().numpy(), logits_o, "logits")
     for l in range(2):
-        for g, w, name in zip(tr.grads[l], grads_o[l], ("dW_self", "dW_neigh", "dbias")):
-            _close(g.cpu().numpy(), w, f"layer {l} {name}")
+        for g, w, bd, name in zip(tr.grads[l], grads_o[l], bounds[l], ("dW_self", "dW_neigh", "dbias")):
+            _close(g.cpu().numpy(), w, f"layer {l} {name}", extra=bd)
     new_o = [tuple(oracle.sgd_step(w, g, lr).reshape(np.shape(w)) for w, g in zip(pl, gl)) for pl, gl in zip(p_o, grads_o)]
-    _close(tr.W.cpu().numpy(), omodel.flatten(new_o), "weights after the step", tol=1e-6)
+    _close(tr.W.cpu().numpy(), omodel.flatten(new_o), "weights after the step", tol=1e-6, extra=lr * decisions.total(bounds))
 
 
 @pytest.fixture(scope="module")
@@ -97,19 +96,19 @@ def test_configs1_gcn_step_against_oracle(configs1_part0):
                       params=params, encoder="gcn")
     loss_g = tr.step(lr).item()
     p_o = [tuple(np.asarray(t, dtype=np.float64) for t in l) for l in params]
-    relu_open = [tr.H[1].cpu().numpy() > 0, None]
-    loss_o, grads_o, logits_o, saved = omodel.loss_and_grads(sub_o["rowptr"], sub_o["colidx"], Xo, yo, p_o, relu_open,
-                                                             "gcn")
-    flips = int((relu_open[0] != (saved[0][2] > 0)).sum())
-    assert flips <= 1e-5 * relu_open[0].size
+    t = {}
+    loss_o, grads_o, logits_o, saved = omodel.loss_and_grads(sub_o["rowptr"], sub_o["colidx"], Xo, yo, p_o,
+                                                             encoder="gcn", trace=t)
+    D = decisions.differing(t["pre"], [tr.H[1].cpu().numpy(), None], "configs[1] GCN step")
+    bounds = decisions.encoder_bounds("gcn", sub_o["rowptr"], sub_o["colidx"], p_o, saved, t["ups"], D)
     assert abs(loss_g - loss_o) <= TOL * abs(loss_o)
     _close(tr.M[0].cpu().numpy(), saved[0][1], "Ahat H of layer 0")
     _close(tr.H[2].cpu().numpy(), logits_o, "logits")
     for l in range(2):
-        for g, w, name in zip(tr.grads[l], grads_o[l], ("dW", "dbias")):
-            _close(g.cpu().numpy(), w, f"layer {l} {name}")
+        for g, w, bd, name in zip(tr.grads[l], grads_o[l], bounds[l], ("dW", "dbias")):
+            _close(g.cpu().numpy(), w, f"layer {l} {name}", extra=bd)
     new_o = [tuple(oracle.sgd_step(w, g, lr).reshape(np.shape(w)) for w, g in zip(pl, gl)) for pl, gl in zip(p_o, grads_o)]
-    _close(tr.W.cpu().numpy(), omodel.flatten(new_o), "weights after the step", tol=1e-6)
+    _close(tr.W.cpu().numpy(), omodel.flatten(new_o), "weights after the step", tol=1e-6, extra=lr * decisions.total(bounds))
 
 
 def test_configs1_link_prediction_step_against_oracle(configs1_part0):
@@ -137,16 +136,19 @@ def test_configs1_link_prediction_step_against_oracle(configs1_part0):
     assert counts.max() > 256 and (counts == 0).mean() > 0.2      # long and empty per-node term lists are in the case
     e_o = [tuple(np.asarray(t, dtype=np.float64) for t in l) for l in enc]
     d_o = [tuple(np.asarray(t, dtype=np.float64) for t in l) for l in dec]
-    open_ = [tr.H[1].cpu().numpy() > 0, None]
-    dec_open = [tr.E[1].cpu().numpy() > 0]
-    loss_o, ge, gd, z = omodel.link_loss_and_grads(rp, ci, Xo, batch, e_o, d_o, "sage", open_, dec_open)
+    t = {}
+    loss_o, ge, gd, z = omodel.link_loss_and_grads(rp, ci, Xo, batch, e_o, d_o, "sage", trace=t)
+    D = decisions.differing(t["pre"], [tr.H[1].cpu().numpy(), None], "encoder")
+    Dd = decisions.differing(t["dec_pre"], [tr.E[1].cpu().numpy(), None], "decoder")
+    db, q_top = decisions.decoder_bounds(d_o, t["dsaved"], t["dec_ups"], Dd, t["R"], t["batch_pos"])
+    eb = decisions.encoder_bounds("sage", rp, ci, e_o, t["saved"], t["ups"], D, q_top)
     assert abs(loss_g - loss_o) <= TOL * abs(loss_o)
     _close(tr.Zd[2].cpu().numpy().ravel(), z, "logits")
     for l in range(2):
-        for g, w, name in zip(tr.grads[l], ge[l], ("dW_self", "dW_neigh", "dbias")):
-            _close(g.cpu().numpy(), w, f"encoder layer {l} {name}")
-        for g, w, name in zip(tr.dec_grads[l], gd[l], ("dTheta", "dslope")):
-            _close(g.cpu().numpy().ravel(), np.asarray(w).ravel(), f"decoder layer {l} {name}")
+        for g, w, bd, name in zip(tr.grads[l], ge[l], eb[l], ("dW_self", "dW_neigh", "dbias")):
+            _close(g.cpu().numpy(), w, f"encoder layer {l} {name}", extra=bd)
+        for g, w, bd, name in zip(tr.dec_grads[l], gd[l], db[l], ("dTheta", "dslope")):
+            _close(g.cpu().numpy().ravel(), np.asarray(w).ravel(), f"decoder layer {l} {name}", extra=bd)
 
 
 def test_configs1_sampled_link_prediction_step_against_oracle(configs1_part0):
@@ -171,10 +173,9 @@ def test_configs1_sampled_link_prediction_step_against_oracle(configs1_part0):
     batch = oracle.edge_batch(rp, ci, 15, 0, Bn)
     e_o = [tuple(np.asarray(t, dtype=np.float64) for t in l) for l in enc]
     d_o = [tuple(np.asarray(t, dtype=np.float64) for t in l) for l in dec]
-    open_ = [tr.H[1][:tr.count[1]].cpu().numpy() > 0, None]
-    dec_open = [tr.E[1].cpu().numpy() > 0]
+    t = {}
     loss_o, ge, gd, z, (rps, cis, inputs, seeds) = omodel.sampled_link_loss_and_grads(
-        rp, ci, Xo, batch, e_o, d_o, fanouts, 15, 0, open_, dec_open)
+        rp, ci, Xo, batch, e_o, d_o, fanouts, 15, 0, trace=t)
     assert tr.count == [len(inputs), len(rps[0]) - 1, len(seeds)]
     assert len(inputs) > 20_000 and np.diff(rps[0]).max() == 10 and np.diff(rps[1]).max() == 25   # the fan-outs bind
     assert np.array_equal(tr.nodes[0].cpu().numpy()[:len(inputs)], inputs)
@@ -183,10 +184,14 @@ def test_configs1_sampled_link_prediction_step_against_oracle(configs1_part0):
         n_dst = len(rps[l]) - 1
         assert np.array_equal(tr.blk_rowptr[l].cpu().numpy()[:n_dst + 1], rps[l])
         assert np.array_equal(tr.blk_col[l].cpu().numpy()[:rps[l][-1]], cis[l])
+    D = decisions.differing(t["pre"], [tr.H[1].cpu().numpy(), None], "encoder")
+    Dd = decisions.differing(t["dec_pre"], [tr.E[1].cpu().numpy(), None], "decoder")
+    db, q_top = decisions.decoder_bounds(d_o, t["dsaved"], t["dec_ups"], Dd, t["R"], t["batch_pos"])
+    eb = decisions.encoder_bounds("sage", rps, cis, e_o, t["saved"], t["ups"], D, q_top)
     assert abs(loss_g - loss_o) <= TOL * abs(loss_o)
     _close(tr.Zd[2].cpu().numpy().ravel(), z, "logits")
     for l in range(2):
-        for i, (g, w) in enumerate(zip(tr.grads[l], ge[l])):
-            _close(g.cpu().numpy().ravel(), np.asarray(w).ravel(), f"encoder layer {l} gradient {i}")
-        for i, (g, w) in enumerate(zip(tr.dec_grads[l], gd[l])):
-            _close(g.cpu().numpy().ravel(), np.asarray(w).ravel(), f"decoder layer {l} gradient {i}")
+        for i, (g, w, bd) in enumerate(zip(tr.grads[l], ge[l], eb[l])):
+            _close(g.cpu().numpy().ravel(), np.asarray(w).ravel(), f"encoder layer {l} gradient {i}", extra=bd)
+        for i, (g, w, bd) in enumerate(zip(tr.dec_grads[l], gd[l], db[l])):
+            _close(g.cpu().numpy().ravel(), np.asarray(w).ravel(), f"decoder layer {l} gradient {i}", extra=bd)

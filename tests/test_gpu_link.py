@@ -5,6 +5,7 @@ the three encoders."""
 import numpy as np
 import pytest
 
+import decisions
 import oracle
 from oracle import model as omodel
 from paper_2305_09887_amd import synth
@@ -214,19 +215,27 @@ def test_link_prediction_training_steps(B, encoder, norm_act):
         batch = oracle.edge_batch(rp, ci, 99, step * Bn, Bn)
         for got, want in zip(tr.batch, batch):
             assert np.array_equal(got.cpu().numpy(), want)
-        open_ = [host(tr.H[1]) > 0, None]
-        dec_open = [host(tr.E[1]) > 0]
-        loss_o, ge, gd, z = omodel.link_loss_and_grads(rp, ci, Xo, batch, e_o, d_o, encoder, open_, dec_open)
+        t = {}
+        loss_o, ge, gd, z = omodel.link_loss_and_grads(rp, ci, Xo, batch, e_o, d_o, encoder, trace=t)
+        D = decisions.differing(t["pre"], [host(tr.H[1]), None], f"step {step} encoder")
+        Dd = decisions.differing(t["dec_pre"], [host(tr.E[1]), None], f"step {step} decoder")
+        db, q_top = decisions.decoder_bounds(d_o, t["dsaved"], t["dec_ups"], Dd, t["R"], t["batch_pos"])
+        eb = decisions.encoder_bounds(encoder, rp, ci, e_o, t["saved"], t["ups"], D, q_top)
         assert abs(loss_g - loss_o) <= 1e-4 * abs(loss_o), f"loss at step {step}"
         close(host(tr.Zd[2]).ravel(), z, 1e-4, f"logits at step {step}")
         for l in range(2):
-            for i, (g, w) in enumerate(zip(tr.grads[l], ge[l])):
-                close(host(g).ravel(), np.asarray(w).ravel(), 1e-4, f"step {step} encoder layer {l} gradient {i}")
-            for i, (g, w) in enumerate(zip(tr.dec_grads[l], gd[l])):
-                close(host(g).ravel(), np.asarray(w).ravel(), 1e-4, f"step {step} decoder layer {l} gradient {i}")
+            for i, (g, w, bd) in enumerate(zip(tr.grads[l], ge[l], eb[l])):
+                decisions.close(host(g).ravel(), np.asarray(w).ravel(), 1e-4, f"step {step} encoder layer {l} gradient {i}",
+                                extra=bd)
+            for i, (g, w, bd) in enumerate(zip(tr.dec_grads[l], gd[l], db[l])):
+                decisions.close(host(g).ravel(), np.asarray(w).ravel(), 1e-4, f"step {step} decoder layer {l} gradient {i}",
+                                extra=bd)
         e_o = [tuple(oracle.sgd_step(w, g, lr).reshape(np.shape(w)) for w, g in zip(pl, gl)) for pl, gl in zip(e_o, ge)]
         d_o = [tuple(oracle.sgd_step(w, g, lr).reshape(np.shape(w)) for w, g in zip(pl, gl)) for pl, gl in zip(d_o, gd)]
-        close(host(tr.W), omodel.flatten(e_o + d_o), 1e-4, f"weights after step {step}")
+        decisions.close(host(tr.W), omodel.flatten(e_o + d_o), 1e-4, f"weights after step {step}",
+                        extra=lr * (decisions.total(eb) + decisions.total(db)))
+        if decisions.any_differs(D, Dd):
+            tr.load_params(e_o, d_o)
         losses.append(loss_g)
     assert losses[2] < losses[0]
 
@@ -251,12 +260,22 @@ def test_link_prediction_step_bf16_storage(B):
     e_o = [tuple(np.asarray(t, dtype=np.float64) for t in l) for l in enc]
     d_o = [tuple(np.asarray(t, dtype=np.float64) for t in l) for l in dec]
     batch = oracle.edge_batch(rp, ci, 5, 0, Bn)
-    loss_o, ge, gd, z = omodel.link_loss_and_grads(rp, ci, Xo, batch, e_o, d_o, "sage", [host(tr.H[1]) > 0, None],
-                                                    [host(tr.E[1]) > 0])
+    # activation decisions in the path's precision: those of the oracle's as-stored pass (bf16 storage, bf16 weight
+    # operands); expected values from its fp64 pass
+    t = {}
+    forms = [not B.tma_sage_layer_aggregates_first(a, b, B.TMA_BF16) for a, b in zip(dims[:-1], dims[1:])]
+    loss_o, ge, gd, z = omodel.link_loss_and_grads(rp, ci, Xo, batch, e_o, d_o, "sage", decisions="bf16", trace=t,
+                                                   transform_first=forms)
+    kw = decisions.STORED
+    D = decisions.differing(t["pre"], [host(tr.H[1]), None], "encoder", **kw)
+    Dd = decisions.differing(t["dec_pre"], [host(tr.E[1]), None], "decoder", **kw)
+    db, q_top = decisions.decoder_bounds(d_o, t["dsaved"], t["dec_ups"], Dd, t["R"], t["batch_pos"])
+    eb = decisions.encoder_bounds("sage", rp, ci, e_o, t["saved"], t["ups"], D, q_top)
+    print(f"differing decisions: encoder {int(D[0].sum())} of {D[0].size}, decoder {int(Dd[0].sum())} of {Dd[0].size}")
     assert abs(loss_g - loss_o) <= 2e-2 * abs(loss_o)
     close(host(tr.Zd[2]).ravel(), z, 2e-2, "logits")
     for l in range(2):
-        for i, (g, w) in enumerate(zip(tr.grads[l], ge[l])):
-            close(host(g).ravel(), np.asarray(w).ravel(), 2e-2, f"encoder layer {l} gradient {i}")
-        for i, (g, w) in enumerate(zip(tr.dec_grads[l], gd[l])):
-            close(host(g).ravel(), np.asarray(w).ravel(), 2e-2, f"decoder layer {l} gradient {i}")
+        for i, (g, w, bd) in enumerate(zip(tr.grads[l], ge[l], eb[l])):
+            decisions.close(host(g).ravel(), np.asarray(w).ravel(), 2e-2, f"encoder layer {l} gradient {i}", extra=bd)
+        for i, (g, w, bd) in enumerate(zip(tr.dec_grads[l], gd[l], db[l])):
+            decisions.close(host(g).ravel(), np.asarray(w).ravel(), 2e-2, f"decoder layer {l} gradient {i}", extra=bd)

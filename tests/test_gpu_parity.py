@@ -7,6 +7,7 @@ activations, gradients and losses.  Inputs are seeded and synthetic.
 import numpy as np
 import pytest
 
+import decisions
 import oracle
 from oracle import model as omodel
 from paper_2305_09887_amd import synth
@@ -450,16 +451,22 @@ def test_tiny_config_training_steps_match_oracle(B):
     p_o = [tuple(np.asarray(t, dtype=np.float64) for t in l) for l in params]
     lr = 0.05
     losses = []
+    rp, ci = sub_o["rowptr"], sub_o["colidx"]
     for step in range(3):
         loss_g = tr.step(lr).item()
-        relu_open = [tr.H[1].cpu().numpy() > 0, None]      # the ReLU decision in the kernel's precision, for both sides
-        loss_o, grads_o, _, _ = omodel.loss_and_grads(sub_o["rowptr"], sub_o["colidx"], Xo, yo, p_o, relu_open)
+        t = {}
+        loss_o, p_new = omodel.train_step(rp, ci, Xo, yo, p_o, lr, trace=t)     # the oracle decides its own ReLUs
+        D = decisions.differing(t["pre"], [tr.H[1].cpu().numpy(), None], f"step {step}")
+        bounds = decisions.encoder_bounds("sage", rp, ci, p_o, t["saved"], t["ups"], D)
         assert abs(loss_g - loss_o) <= TOL_F32 * abs(loss_o), f"loss at step {step}"
         for l in range(2):
-            for g, w, name in zip(tr.grads[l], grads_o[l], ("dW_self", "dW_neigh", "dbias")):
-                assert_close(g.cpu().numpy(), w, what=f"step {step} layer {l} {name}")
-        _, p_o = omodel.train_step(sub_o["rowptr"], sub_o["colidx"], Xo, yo, p_o, lr, relu_open)
-        assert_close(tr.W.cpu().numpy(), omodel.flatten(p_o), what=f"weights after step {step}")
+            for g, w, bd, name in zip(tr.grads[l], t["grads"][l], bounds[l], ("dW_self", "dW_neigh", "dbias")):
+                decisions.close(g.cpu().numpy(), w, TOL_F32, f"step {step} layer {l} {name}", extra=bd)
+        p_o = p_new
+        decisions.close(tr.W.cpu().numpy(), omodel.flatten(p_o), TOL_F32, f"weights after step {step}",
+                        extra=lr * decisions.total(bounds))
+        if decisions.any_differs(D):      # a decision next to zero fell the other way: go on from the oracle's weights
+            tr.load_params(p_o)
         losses.append(loss_g)
     assert losses[2] < losses[0]
 

@@ -4,6 +4,7 @@ block forward and backward to 1e-4 (fp32) / 2e-2 (bf16)."""
 import numpy as np
 import pytest
 
+import decisions
 import oracle
 from paper_2305_09887_amd import synth
 
@@ -196,9 +197,9 @@ def test_sampled_link_prediction_training_steps(B, fanouts, Bn, norm_act):
     for step in range(3):
         loss_g = tr.step(lr).item()
         batch = oracle.edge_batch(rp, ci, 99, step * Bn, Bn)
-        # first pass for the structure, then with the kernel's activation decisions
-        probe = omodel.sampled_link_loss_and_grads(rp, ci, Xo, batch, e_o, d_o, fanouts, 99, step)
-        rps, cis, inputs, seeds = probe[4]
+        t = {}
+        loss_o, ge, gd, z, (rps, cis, inputs, seeds) = omodel.sampled_link_loss_and_grads(
+            rp, ci, Xo, batch, e_o, d_o, fanouts, 99, step, trace=t)
         assert tr.count[2] == len(seeds) and np.array_equal(tr.nodes[2].cpu().numpy()[:len(seeds)], seeds)
         for got, want in zip(tr.batch, batch):
             assert np.array_equal(got.cpu().numpy(), np.searchsorted(seeds, want))
@@ -208,20 +209,25 @@ def test_sampled_link_prediction_training_steps(B, fanouts, Bn, norm_act):
             assert np.array_equal(tr.blk_rowptr[l].cpu().numpy()[:n_dst + 1], rps[l])
             assert np.array_equal(tr.blk_col[l].cpu().numpy()[:rps[l][-1]], cis[l])
         assert tr.count[0] == len(inputs) and np.array_equal(tr.nodes[0].cpu().numpy()[:len(inputs)], inputs)
-        open_ = [host(tr.H[1][:tr.count[1]]) > 0, None]
-        dec_open = [host(tr.E[1]) > 0]
-        loss_o, ge, gd, z, _ = omodel.sampled_link_loss_and_grads(rp, ci, Xo, batch, e_o, d_o, fanouts, 99, step, open_,
-                                                                  dec_open)
+        D = decisions.differing(t["pre"], [host(tr.H[1]), None], f"step {step} encoder")
+        Dd = decisions.differing(t["dec_pre"], [host(tr.E[1]), None], f"step {step} decoder")
+        db, q_top = decisions.decoder_bounds(d_o, t["dsaved"], t["dec_ups"], Dd, t["R"], t["batch_pos"])
+        eb = decisions.encoder_bounds("sage", rps, cis, e_o, t["saved"], t["ups"], D, q_top)
         assert abs(loss_g - loss_o) <= 1e-4 * abs(loss_o), f"loss at step {step}"
         close(host(tr.Zd[2]).ravel(), z, 1e-4, f"logits at step {step}")
         for l in range(2):
-            for i, (g, w) in enumerate(zip(tr.grads[l], ge[l])):
-                close(host(g).ravel(), np.asarray(w).ravel(), 1e-4, f"step {step} encoder layer {l} gradient {i}")
-            for i, (g, w) in enumerate(zip(tr.dec_grads[l], gd[l])):
-                close(host(g).ravel(), np.asarray(w).ravel(), 1e-4, f"step {step} decoder layer {l} gradient {i}")
+            for i, (g, w, bd) in enumerate(zip(tr.grads[l], ge[l], eb[l])):
+                decisions.close(host(g).ravel(), np.asarray(w).ravel(), 1e-4, f"step {step} encoder layer {l} gradient {i}",
+                                extra=bd)
+            for i, (g, w, bd) in enumerate(zip(tr.dec_grads[l], gd[l], db[l])):
+                decisions.close(host(g).ravel(), np.asarray(w).ravel(), 1e-4, f"step {step} decoder layer {l} gradient {i}",
+                                extra=bd)
         e_o = [tuple(oracle.sgd_step(w, g, lr).reshape(np.shape(w)) for w, g in zip(pl, gl)) for pl, gl in zip(e_o, ge)]
         d_o = [tuple(oracle.sgd_step(w, g, lr).reshape(np.shape(w)) for w, g in zip(pl, gl)) for pl, gl in zip(d_o, gd)]
-        close(host(tr.W), omodel.flatten(e_o + d_o), 1e-4, f"weights after step {step}")
+        decisions.close(host(tr.W), omodel.flatten(e_o + d_o), 1e-4, f"weights after step {step}",
+                        extra=lr * (decisions.total(eb) + decisions.total(db)))
+        if decisions.any_differs(D, Dd):
+            tr.load_params(e_o, d_o)
         losses.append(loss_g)
     assert np.isfinite(losses).all()      # (every step sees another batch: the loss need not fall step by step)
 
@@ -247,15 +253,21 @@ def test_sampled_link_prediction_bf16_storage(B):
     e_o = [tuple(np.asarray(t, dtype=np.float64) for t in l) for l in enc]
     d_o = [tuple(np.asarray(t, dtype=np.float64) for t in l) for l in dec]
     batch = oracle.edge_batch(rp, ci, 3, 0, Bn)
-    open_ = [host(tr.H[1][:tr.count[1]]) > 0, None]
+    t = {}
     loss_o, ge, gd, z, (rps, cis, inputs, seeds) = omodel.sampled_link_loss_and_grads(
-        rp, ci, Xo, batch, e_o, d_o, fanouts, 3, 0, open_, [host(tr.E[1]) > 0])
+        rp, ci, Xo, batch, e_o, d_o, fanouts, 3, 0, decisions="bf16", trace=t)    # decisions of the as-stored pass
     assert tr.count == [len(inputs), len(rps[0]) - 1, len(seeds)]
     assert np.array_equal(tr.nodes[0].cpu().numpy()[:len(inputs)], inputs)
+    kw = decisions.STORED
+    D = decisions.differing(t["pre"], [host(tr.H[1]), None], "encoder", **kw)
+    Dd = decisions.differing(t["dec_pre"], [host(tr.E[1]), None], "decoder", **kw)
+    db, q_top = decisions.decoder_bounds(d_o, t["dsaved"], t["dec_ups"], Dd, t["R"], t["batch_pos"])
+    eb = decisions.encoder_bounds("sage", rps, cis, e_o, t["saved"], t["ups"], D, q_top)
+    print(f"differing decisions: encoder {int(D[0].sum())} of {D[0].size}, decoder {int(Dd[0].sum())} of {Dd[0].size}")
     assert abs(loss_g - loss_o) <= 2e-2 * abs(loss_o)
     close(host(tr.Zd[2]).ravel(), z, 2e-2, "logits")
     for l in range(2):
-        for i, (g, w) in enumerate(zip(tr.grads[l], ge[l])):
-            close(host(g).ravel(), np.asarray(w).ravel(), 2e-2, f"encoder layer {l} gradient {i}")
-        for i, (g, w) in enumerate(zip(tr.dec_grads[l], gd[l])):
-            close(host(g).ravel(), np.asarray(w).ravel(), 2e-2, f"decoder layer {l} gradient {i}")
+        for i, (g, w, bd) in enumerate(zip(tr.grads[l], ge[l], eb[l])):
+            decisions.close(host(g).ravel(), np.asarray(w).ravel(), 2e-2, f"encoder layer {l} gradient {i}", extra=bd)
+        for i, (g, w, bd) in enumerate(zip(tr.dec_grads[l], gd[l], db[l])):
+            decisions.close(host(g).ravel(), np.asarray(w).ravel(), 2e-2, f"decoder layer {l} gradient {i}", extra=bd)

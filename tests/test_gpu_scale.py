@@ -11,7 +11,9 @@ v mod p = 0, for a few (o, p)): degrees 0..8, no host generation time."""
 import numpy as np
 import pytest
 
+import decisions
 import oracle
+from oracle import model as omodel
 from paper_2305_09887_amd import synth
 
 torch = pytest.importorskip("torch")
@@ -110,29 +112,25 @@ def test_layer_forward_and_backward_at_12_5_million_rows(B):
     dHn[torch.as_tensor(S, device="cuda")] = torch.from_numpy(bits.view(np.int16)).cuda().view(torch.bfloat16)
     dWs, dWn, db, dH = B.tma_sage_layer_bwd(rowptr, colidx, inv_deg, H, M, Hn, dHn, Ws, Wn, B.TMA_ACT_RELU, need_dH=True)
     torch.cuda.synchronize()
-    # the oracle's sub-problem for backward: rows of U with their saved H, M (the GPU's own, as stored), the ReLU
-    # decision of the GPU's H', dZ nonzero on S; graph rows outside S are not needed for dW (their dZ is zero)
-    Mu = _rows(M, U)
-    open_u = _rows(Hn, U) > 0
+    # the oracle's sub-problem for backward: rows of U with the oracle's own H, M and Z; dZ is nonzero on S only, so
+    # graph rows outside S are not needed.  The ReLU decision is taken in the path's precision by the oracle's
+    # as-stored pass (bf16 M and H', bf16 weight operands); the GPU's sign pattern on S is only compared with it.
+    p64 = [tuple(np.asarray(t, dtype=np.float64) for t in params)]
+    _, pre = omodel.forward_as_stored(sub_rp, sub_ci, Hu, p64, "sage", "bf16", final_relu=True)
+    D = np.zeros(pre[0].shape, dtype=bool)
+    D[s_in_u] = decisions.check(_rows(Hn, S) > 0, pre[0][s_in_u], "ReLU on the sampled rows", **decisions.STORED)
     dHn_u = np.zeros((len(U), F))
     dHn_u[s_in_u] = g
-    Zsign = np.where(open_u, 1.0, -1.0)
-    dWs_o, dWn_o, db_o, _ = oracle.sage_layer_bwd(sub_rp, sub_ci, Hu, Mu, Zsign, dHn_u, params[0], params[1],
-                                                  oracle.ACT_RELU, need_dH=False)
-    _close(dWs.cpu().numpy(), dWs_o, 2e-2, "dW_self")
-    _close(dWn.cpu().numpy(), dWn_o, 2e-2, "dW_neigh")
-    _close(db.cpu().numpy(), db_o, 2e-2, "dbias")
+    (bWs, bWn, bb), = decisions.encoder_bounds("sage", sub_rp, sub_ci, p64, [(Hu, M_o, Z_o, oracle.ACT_RELU)], [dHn_u], [D])
+    dWs_o, dWn_o, db_o, dH_o = oracle.sage_layer_bwd(sub_rp, sub_ci, Hu, M_o, pre[0], dHn_u, params[0], params[1],
+                                                     oracle.ACT_RELU, need_dH=True)
+    decisions.close(dWs.cpu().numpy(), dWs_o, 2e-2, "dW_self", extra=bWs)
+    decisions.close(dWn.cpu().numpy(), dWn_o, 2e-2, "dW_neigh", extra=bWn)
+    decisions.close(db.cpu().numpy(), db_o, 2e-2, "dbias", extra=bb)
     # dH_v = dZ_v Ws^T + sum_{u in N(v)} inv_deg[u] dZ_u Wn^T (the graph is symmetric).  dZ lives on S, so dH is
-    # nonzero on S u N(S) = U; every row of U outside that set of contributions must be exactly what this gives
-    dZ = np.where(open_u, dHn_u, 0.0)
-    inv_u = _rows(inv_deg[:, None], U)[:, 0]
-    dH_o = dZ @ np.asarray(params[0], np.float64).T
-    back = (dZ * inv_u[:, None]) @ np.asarray(params[1], np.float64).T       # rows u: inv_deg[u] dZ_u Wn^T
-    # scatter along the sampled rows' neighbour lists: u in S contributes to every neighbour v of u
-    for i in s_in_u:
-        for e in range(sub_rp[i], sub_rp[i + 1]):
-            dH_o[sub_ci[e]] += back[i]
-    _close(_rows(dH, U), dH_o, 2e-2, "dH on S and its neighbours")
+    # nonzero on S u N(S) = U, and the oracle's scatter over the sampled rows' lists gives exactly those rows
+    spec = np.linalg.norm(np.asarray(params[0], np.float64), 2) + np.linalg.norm(np.asarray(params[1], np.float64), 2)
+    decisions.close(_rows(dH, U), dH_o, 2e-2, "dH on S and its neighbours", extra=bb * spec)
     far = np.setdiff1d(np.random.default_rng(9).integers(0, N, 2000), U)
     assert not _rows(dH, far).any()                            # untouched rows are exact zeros
 
@@ -157,11 +155,15 @@ def test_row_wise_kernels_at_12_5_million_rows(B):
     dH = torch.zeros((N, F), dtype=torch.bfloat16, device="cuda")
     dH[idx] = torch.from_numpy(synth.to_bf16_bits(g).reshape(g.shape).view(np.int16)).cuda().view(torch.bfloat16)
     dZ, dga, dbe, dsl = B.tma_layernorm_prelu_bwd(Z, dH, d(gamma), d(beta), slope, dZ_out=dH)
-    wZ, wga, wbe, wsl = oracle.layernorm_prelu_bwd(Zs, g, gamma, beta, 0.25, open_mask=_rows(H, S) > 0)
-    _close(_rows(dZ, S), wZ, 2e-2, "dZ on sampled rows")
-    _close(dga.cpu().numpy(), wga, 2e-2, "dgamma")
-    _close(dbe.cpu().numpy(), wbe, 2e-2, "dbeta")
-    assert abs(dsl.item() - wsl) <= 2e-2 * abs(wsl)
+    wZ, wga, wbe, wsl = oracle.layernorm_prelu_bwd(Zs, g, gamma, beta, 0.25)
+    # both sides normalise the same bf16 Z (the kernel in fp32): its decisions may differ only next to zero
+    D = decisions.check(_rows(H, S) > 0, decisions.prelu_pre(oracle.layernorm_prelu_fwd(Zs, gamma, beta, 0.25), 0.25),
+                        "PReLU on the sampled rows")
+    bZ, bga, bbe, bsl = decisions.ln_prelu_bounds(Zs, g, gamma, beta, 0.25, D)
+    decisions.close(_rows(dZ, S), wZ, 2e-2, "dZ on sampled rows", extra=bZ)
+    decisions.close(dga.cpu().numpy(), wga, 2e-2, "dgamma", extra=bga)
+    decisions.close(dbe.cpu().numpy(), wbe, 2e-2, "dbeta", extra=bbe)
+    assert abs(dsl.item() - wsl) <= 2e-2 * abs(wsl) + bsl
     del Z, H, dH, dZ
     # loss: equal logits in every row give log(C) exactly and (1/C - onehot)/n as gradient
     C = 47
