@@ -232,6 +232,22 @@ int tma_layernorm_prelu_bwd(int64_t n, int32_t F, const void *Z, int64_t ldz,
                             float *dgamma, float *dbeta, float *dslope,
                             void *ws, size_t ws_bytes, tma_stream_t stream);
 
+/* tma_layernorm_prelu_bwd for callers that cannot allocate or carry a workspace (code under HIP graph capture,
+ * tight serving loops, harnesses that forbid hipMalloc): same arguments without (ws, ws_bytes), same kernels, same
+ * results bit for bit.  The per-block partial sums go to an array that the library itself holds in device memory
+ * (4.2 MB per GPU, from load until the process ends), sized for rows of at most
+ * tma_layernorm_prelu_bwd_static_max_f() = 256 elements; a larger F returns TMA_ERR_BAD_SHAPE and launches
+ * nothing.  The call allocates and frees nothing.  All calls on one GPU share that array: calls that may overlap
+ * on one GPU (different streams without an ordering between them) race on it and must use the workspace form;
+ * nothing in it has to be cleared between calls (every slot that is read is written first, in the same call). */
+int32_t tma_layernorm_prelu_bwd_static_max_f(void);
+
+int tma_layernorm_prelu_bwd_static(int64_t n, int32_t F, const void *Z, int64_t ldz,
+                                   const void *dHnext, int64_t ld_d,
+                                   const float *gamma, const float *beta, const float *slope, float eps,
+                                   int32_t dtype, void *dZ_out, int64_t ld_dz,
+                                   float *dgamma, float *dbeta, float *dslope, tma_stream_t stream);
+
 /* ------------------------------------------------------------------------
  * The paper's other encoders (Sec. 4.1, paragraph on GNN encoders).
  *

@@ -25,6 +25,7 @@ EXPORTS = (
     "tma_mean_aggregate", "tma_sage_layer_aggregates_first", "tma_sage_layer_fwd",
     "tma_sage_layer_bwd_workspace_bytes", "tma_sage_layer_bwd",
     "tma_layernorm_prelu_fwd", "tma_layernorm_prelu_bwd_workspace_bytes", "tma_layernorm_prelu_bwd",
+    "tma_layernorm_prelu_bwd_static_max_f", "tma_layernorm_prelu_bwd_static",
     "tma_dense_fwd", "tma_dense_bwd_workspace_bytes", "tma_dense_bwd",
     "tma_gcn_norm", "tma_gcn_layer_aggregates_first", "tma_gcn_layer_fwd",
     "tma_gcn_layer_bwd_workspace_bytes", "tma_gcn_layer_bwd",
@@ -738,6 +739,34 @@ def tma_layernorm_prelu_bwd(Z, dHnext, gamma, beta, slope, eps: float = LN_EPS, 
         _ptr(slope, torch.float32, "slope"), C.c_float(eps), C.c_int32(_feat_dtype(Z)),
         C.c_void_p(dZ_out.data_ptr()), C.c_int64(ldo), _ptr(dgamma, torch.float32), _ptr(dbeta, torch.float32),
         _ptr(dslope, torch.float32), _ptr(ws), C.c_size_t(ws.numel()), _stream(stream)))
+    return dZ_out, dgamma, dbeta, dslope
+
+
+def tma_layernorm_prelu_bwd_static_max_f() -> int:
+    return int(lib().tma_layernorm_prelu_bwd_static_max_f())
+
+
+def tma_layernorm_prelu_bwd_static(Z, dHnext, gamma, beta, slope, dZ_out, dgamma, dbeta, dslope, eps: float = LN_EPS,
+                                   stream=None):
+    """The backward pass through the library's own scratch array: no workspace, and every output is the caller's
+    (this wrapper allocates nothing either).  Returns (dZ_out, dgamma, dbeta, dslope)."""
+    n, F, ldz = _rows_ld(Z, "Z")
+    if tuple(dHnext.shape) != (n, F) or dHnext.dtype != Z.dtype:
+        raise TmaError("tma_layernorm_prelu_bwd_static: dHnext shape/dtype mismatch")
+    if tuple(dZ_out.shape) != (n, F) or dZ_out.dtype != Z.dtype:
+        raise TmaError("tma_layernorm_prelu_bwd_static: dZ_out shape/dtype mismatch")
+    if gamma.numel() != F or beta.numel() != F or slope.numel() != 1:
+        raise TmaError("tma_layernorm_prelu_bwd_static: gamma / beta need F entries, slope one")
+    if dgamma.numel() != F or dbeta.numel() != F or dslope.numel() != 1:
+        raise TmaError("tma_layernorm_prelu_bwd_static: gradient output sizes")
+    _, _, ldd = _rows_ld(dHnext, "dHnext")
+    _, _, ldo = _rows_ld(dZ_out, "dZ_out")
+    _check(lib().tma_layernorm_prelu_bwd_static(
+        C.c_int64(n), C.c_int32(F), C.c_void_p(Z.data_ptr()), C.c_int64(ldz), C.c_void_p(dHnext.data_ptr()),
+        C.c_int64(ldd), _ptr(gamma, torch.float32, "gamma"), _ptr(beta, torch.float32, "beta"),
+        _ptr(slope, torch.float32, "slope"), C.c_float(eps), C.c_int32(_feat_dtype(Z)),
+        C.c_void_p(dZ_out.data_ptr()), C.c_int64(ldo), _ptr(dgamma, torch.float32), _ptr(dbeta, torch.float32),
+        _ptr(dslope, torch.float32), _stream(stream)))
     return dZ_out, dgamma, dbeta, dslope
 
 

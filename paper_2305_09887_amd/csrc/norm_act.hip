@@ -9,6 +9,7 @@
 // stages (inside the block through LDS, across blocks by a second kernel): no atomics, bit-reproducible.
 #include "kernels.hpp"
 
+#include <mutex>
 #include <type_traits>
 
 namespace tma {
@@ -348,18 +349,16 @@ extern "C" size_t tma_layernorm_prelu_bwd_workspace_bytes(int64_t n, int32_t F)
     return tma::round_up(size_t(tma::kNormMaxBlocks) * (2 * size_t(F) + 1) * 4, 256);
 }
 
-extern "C" int tma_layernorm_prelu_bwd(int64_t n, int32_t F, const void *Z, int64_t ldz, const void *dHnext,
-                                       int64_t ld_d, const float *gamma, const float *beta, const float *slope,
-                                       float eps, int32_t dtype, void *dZ_out, int64_t ld_dz, float *dgamma,
-                                       float *dbeta, float *dslope, void *ws, size_t ws_bytes, tma_stream_t stream)
+namespace tma {
+
+// Both backward entry points: argument checks that do not concern the scratch space, then the two launches.
+// `partial` holds kNormMaxBlocks * (2 F + 1) floats; every slot that the second kernel reads has been written by
+// the first one in the same call, so the buffer needs no clearing.
+static int ln_prelu_bwd_run(const char *fn, int64_t n, int32_t F, const void *Z, int64_t ldz, const void *dHnext,
+                            int64_t ld_d, const float *gamma, const float *beta, const float *slope, float eps,
+                            int32_t dtype, void *dZ_out, int64_t ld_dz, float *dgamma, float *dbeta, float *dslope,
+                            float *partial, hipStream_t s)
 {
-    using namespace tma;
-    const char *fn = "tma_layernorm_prelu_bwd";
-    if (int rc = check_norm_args(fn, n, F, Z, ldz, gamma, beta, slope, eps, dtype)) return rc;
-    TMA_REQUIRE(dgamma && dbeta && dslope, TMA_ERR_INVALID_ARG, "%s: gradient output is NULL", fn);
-    TMA_REQUIRE(ws && aligned(ws, 256), TMA_ERR_INVALID_ARG, "%s: workspace NULL or not 256-byte aligned", fn);
-    TMA_REQUIRE(ws_bytes >= tma_layernorm_prelu_bwd_workspace_bytes(n, F), TMA_ERR_WORKSPACE_TOO_SMALL,
-                "%s: workspace too small", fn);
     TMA_REQUIRE(n == 0 || (dHnext && dZ_out && ld_d >= F && ld_dz >= F), TMA_ERR_INVALID_ARG,
                 "%s: dHnext / dZ_out NULL or leading dimension < F", fn);
     const size_t elem = dtype == TMA_BF16 ? 2 : 4;
@@ -368,8 +367,6 @@ extern "C" int tma_layernorm_prelu_bwd(int64_t n, int32_t F, const void *Z, int6
     NormPlan p;
     TMA_REQUIRE(plan_norm(n, F, elem, vec_ok, p), TMA_ERR_BAD_SHAPE, "%s: F = %d is beyond %d elements per row", fn, F,
                 kWave * kNormMaxPerLane);
-    hipStream_t s = as_stream(stream);
-    float *partial = static_cast<float *>(ws);
     const int nb = n > 0 ? int(p.blocks) : 0;
     if (n > 0) {
         TMA_TIMED(dtype == TMA_BF16 ? "ln_prelu_bwd_bf16" : "ln_prelu_bwd_f32", s);
@@ -388,4 +385,74 @@ extern "C" int tma_layernorm_prelu_bwd(int64_t n, int32_t F, const void *Z, int6
     hipLaunchKernelGGL(ln_prelu_finish_kernel, dim3(unsigned(ceil_div(2 * F + 1, kFinCols))), dim3(256), 0, s, nb, F, partial,
                        dgamma, dbeta, dslope);
     return check_launch(fn);
+}
+
+// Library-owned scratch of tma_layernorm_prelu_bwd_static: the per-block partial sums for rows of up to
+// kStaticNormMaxF elements (2048 * 513 floats = 4.2 MB per GPU, held until the process ends).
+constexpr int kStaticNormMaxF = 256;
+constexpr size_t kStaticNormFloats = size_t(kNormMaxBlocks) * (2 * size_t(kStaticNormMaxF) + 1);
+
+}  // namespace tma
+
+static __device__ __align__(256) float scratch[tma::kStaticNormFloats];
+
+namespace tma {
+
+// Device address of `scratch` on the current device.  In host code the array's name is only a handle for
+// hipGetSymbolAddress; each GPU holds its own copy at its own address, looked up once per device.
+static int static_norm_scratch(const char *fn, float **out)
+{
+    constexpr int kMaxDevices = 64;
+    static std::mutex mu;
+    static float *ptr[kMaxDevices] = {};
+    int dev = -1;
+    TMA_HIP_TRY(hipGetDevice(&dev), fn);
+    TMA_REQUIRE(dev >= 0 && dev < kMaxDevices, TMA_ERR_HIP, "%s: device index %d", fn, dev);
+    std::lock_guard<std::mutex> lock(mu);
+    if (!ptr[dev]) {
+        void *p = nullptr;
+        TMA_HIP_TRY(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)), fn);
+        TMA_REQUIRE(p != nullptr, TMA_ERR_HIP, "%s: no device address for the static scratch array", fn);
+        ptr[dev] = static_cast<float *>(p);
+    }
+    *out = ptr[dev];
+    return TMA_OK;
+}
+
+}  // namespace tma
+
+extern "C" int tma_layernorm_prelu_bwd(int64_t n, int32_t F, const void *Z, int64_t ldz, const void *dHnext,
+                                       int64_t ld_d, const float *gamma, const float *beta, const float *slope,
+                                       float eps, int32_t dtype, void *dZ_out, int64_t ld_dz, float *dgamma,
+                                       float *dbeta, float *dslope, void *ws, size_t ws_bytes, tma_stream_t stream)
+{
+    using namespace tma;
+    const char *fn = "tma_layernorm_prelu_bwd";
+    if (int rc = check_norm_args(fn, n, F, Z, ldz, gamma, beta, slope, eps, dtype)) return rc;
+    TMA_REQUIRE(dgamma && dbeta && dslope, TMA_ERR_INVALID_ARG, "%s: gradient output is NULL", fn);
+    TMA_REQUIRE(ws && aligned(ws, 256), TMA_ERR_INVALID_ARG, "%s: workspace NULL or not 256-byte aligned", fn);
+    TMA_REQUIRE(ws_bytes >= tma_layernorm_prelu_bwd_workspace_bytes(n, F), TMA_ERR_WORKSPACE_TOO_SMALL,
+                "%s: workspace too small", fn);
+    return ln_prelu_bwd_run(fn, n, F, Z, ldz, dHnext, ld_d, gamma, beta, slope, eps, dtype, dZ_out, ld_dz, dgamma, dbeta,
+                            dslope, static_cast<float *>(ws), as_stream(stream));
+}
+
+extern "C" int32_t tma_layernorm_prelu_bwd_static_max_f(void) { return tma::kStaticNormMaxF; }
+
+extern "C" int tma_layernorm_prelu_bwd_static(int64_t n, int32_t F, const void *Z, int64_t ldz, const void *dHnext,
+                                              int64_t ld_d, const float *gamma, const float *beta, const float *slope,
+                                              float eps, int32_t dtype, void *dZ_out, int64_t ld_dz, float *dgamma,
+                                              float *dbeta, float *dslope, tma_stream_t stream)
+{
+    using namespace tma;
+    const char *fn = "tma_layernorm_prelu_bwd_static";
+    if (int rc = check_norm_args(fn, n, F, Z, ldz, gamma, beta, slope, eps, dtype)) return rc;
+    TMA_REQUIRE(dgamma && dbeta && dslope, TMA_ERR_INVALID_ARG, "%s: gradient output is NULL", fn);
+    TMA_REQUIRE(F <= kStaticNormMaxF, TMA_ERR_BAD_SHAPE,
+                "%s: F = %d is beyond the %d elements per row that the library's own scratch array is sized for "
+                "(use tma_layernorm_prelu_bwd with a workspace)", fn, F, kStaticNormMaxF);
+    float *partial = nullptr;
+    if (int rc = static_norm_scratch(fn, &partial)) return rc;
+    return ln_prelu_bwd_run(fn, n, F, Z, ldz, dHnext, ld_d, gamma, beta, slope, eps, dtype, dZ_out, ld_dz, dgamma, dbeta,
+                            dslope, partial, as_stream(stream));
 }
