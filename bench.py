@@ -29,23 +29,43 @@ PEAK_MFMA_BF16_TFLOPS = 2500.0
 
 WORKLOAD = dict(n_nodes=1_000_000, avg_degree=20, gamma=2.1, K=8, part=0, F=128, hidden=256, classes=47,
                 seeds=dict(graph=11, feat=12, label=13, part=14, weights=15), lr=1e-3)
+# configs[0]: the small case the oracle finishes in a blink (uniform random graph, 100,000 undirected edges)
+TINY = dict(n_nodes=20_000, n_edges=100_000, K=4, part=0, F=64, hidden=64, classes=16,
+            seeds=dict(graph=1, feat=2, label=3, part=4, weights=5), lr=1e-3)
 
-# HBM bytes per launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this workload
-# (profiles/bench_configs1_hbm_traffic.txt): (FETCH_SIZE * 2.0 + WRITE_SIZE * 1.0) KiB, the factors being what the
-# same counters read for a plain 1 GiB device copy (FETCH_SIZE reports half the bytes read, WRITE_SIZE all written).
-MEASURED_TRAFFIC_BYTES = {
-    "gemm_bwd_weight_128x128": (234593 * 2.0 + 36703) * 1024,
-    "gemm_fwd_128x128": (70334 * 2.0 + 126773) * 1024,
-    "gemm_tf_fwd": (63591 * 2.0 + 46988) * 1024,
-    "gemm_tf_bwd_weight": (86307 * 2.0 + 23612) * 1024,
-    "gemm_tf_bwd_data": (26107 * 2.0 + 125237) * 1024,
-    "spmm_mean_f32_g32x1": (55763 * 2.0 + 62618) * 1024,
-    "spmm_combine_f32_g12x1": (43104 * 2.0 + 24974) * 1024,
-    "spmm_sum_f32_g12x1": (25526 * 2.0 + 24449) * 1024,
-    "gather_rows_w16": (31577 * 2.0 + 62618) * 1024,
-    "row_fill": (20817 * 2.0 + 1926) * 1024,
-    "row_count": (12038 * 2.0 + 489) * 1024,
-}
+def cpu_baseline_leg(sample):
+    """The oracle, as it stands, timed on this machine's host cores on a bounded sample of the workload: one thread
+    (the canonical figure), then the same loops split over rows on all cores."""
+    import numpy as np
+    import oracle
+    from oracle import model as omodel
+    p_o = [tuple(np.asarray(t, dtype=np.float64) for t in l) for l in sample["params"]]
+    encoder = sample.get("encoder", "sage")
+
+    def run(threads):
+        oracle.set_threads(threads)
+        try:
+            t = time.perf_counter()
+            if "full" in sample:
+                sample["full"](oracle, omodel, p_o)
+            else:
+                omodel.train_step(sample["rowptr"], sample["colidx"], sample["X"], sample["y"], p_o, sample["lr"],
+                                  encoder=encoder)
+            return time.perf_counter() - t
+        finally:
+            oracle.set_threads(1)
+
+    sec = run(1)
+    out = {"value": round(sample["edges"] / sec, 1), "unit": "edges/s", "cores": 1, "kind": "oracle",
+           "sample": sample["what"] + f", {sec:.1f} s single-threaded fp64"}
+    ncores = min(oracle.hardware_threads(), int(os.environ.get("OMP_NUM_THREADS", "1024")))
+    if ncores > 1:
+        sec_all = run(ncores)
+        out["all_cores"] = {"value": round(sample["edges"] / sec_all, 1), "unit": "edges/s", "cores": ncores,
+                            "seconds": round(sec_all, 2),
+                            "what": "the same oracle loops with a parallel-for over rows (aggregation and layer "
+                                    "loops); timing leg only"}
+    return out
 
 
 def canonical(name, s):
@@ -188,9 +208,33 @@ def main():
                     help="positive edges per step of the link tasks (default 65536; 1024 for link-sampled)")
     ap.add_argument("--fanouts", default="10,25",
                     help="link-sampled: neighbours kept per node, first layer first (the layer next to the batch last)")
+    ap.add_argument("--config", type=int, choices=(0, 1, 2, 3, 4), default=1,
+                    help="which of the configured workloads: 1 = the headline (default); 0 = the tiny case; 2 = SuperTMA at "
+                         "full size; 3 = one trainer's share at billion-edge scale; 4 = 8 trainers on 8 streams with "
+                         "parameter averaging every 50 local steps")
+    ap.add_argument("--ld", type=int, default=0,
+                    help="config 2: row pitch of the 100-wide bf16 feature matrix in elements (100 = dense, 128 = padded)")
+    ap.add_argument("--scale", type=float, default=1.0,
+                    help="configs 3 and 4: fraction of the configured graph size (1.0 = as configured)")
+    ap.add_argument("--summarize-traffic", nargs=4, metavar=("KEY", "FETCH_DIR", "WRITE_DIR", "BENCH_JSON"),
+                    help="no GPU work: write profiles/hbm_traffic.json and profiles/bench_<KEY>_hbm_traffic.txt from two "
+                         "rocprofv3 --pmc runs (FETCH_SIZE, WRITE_SIZE) of this script and the JSON line one of them printed; "
+                         "KEY = configs1, configs2_ld100, ...")
+    ap.add_argument("--calibration-dirs", nargs=2, metavar=("COPY_FETCH_DIR", "COPY_WRITE_DIR"), default=None,
+                    help="with --summarize-traffic: counter runs of `bench.py --calibrate-copy` to take the scale factors from")
+    ap.add_argument("--profiled-command", default=None,
+                    help="with --summarize-traffic: the bench.py command line that the counter runs profiled")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="only run a plain 1 GiB device copy (reference for scaling rocprofv3 FETCH_SIZE/WRITE_SIZE)")
     args = ap.parse_args()
+    if args.summarize_traffic:
+        from paper_2305_09887_amd import benchlib
+        key, fd, wd, bj = args.summarize_traffic
+        cal = args.calibration_dirs or (None, None)
+        got = benchlib.summarize_traffic(key, fd, wd, bj, args.profiled_command or "bench.py --headline-only --steps 5 --warmup 2 --no-cpu-baseline",
+                                         cal[0], cal[1])
+        print(json.dumps({k: v["bytes"] for k, v in got["kernels"].items()}))
+        return
     if args.batch is None:
         args.batch = 1024 if args.task == "link-sampled" else 65536
     if args.gpus != 1:
@@ -199,7 +243,7 @@ def main():
 
     import numpy as np
     import torch
-    from paper_2305_09887_amd import binding as B, synth
+    from paper_2305_09887_amd import benchlib, binding as B, synth
     from paper_2305_09887_amd.trainer import LocalTrainer, SampledLinkTrainer, SubgraphPrefetcher
 
     if not torch.cuda.is_available():
@@ -214,7 +258,17 @@ def main():
         print(json.dumps({"calibrate_copy_bytes_read": src.numel() * 4, "calibrate_copy_bytes_written": src.numel() * 4,
                           "copies": 5}))
         return
-    w = WORKLOAD
+    if args.config >= 2:
+        if args.task != "node" or args.encoder != "sage" or args.norm_act or args.prefetch or args.dtype != "f32":
+            sys.exit("bench.py: --config 2, 3 and 4 run the SAGE node task in the configuration's own dtype")
+        if args.config == 4 and args.steps == 50:
+            args.steps = 200                      # 4 rounds of 50 local steps
+        out, sample = {2: benchlib.run_supertma, 3: benchlib.run_share, 4: benchlib.run_aggregation}[args.config](args)
+        if not args.no_cpu_baseline:
+            out["cpu_baseline"] = cpu_baseline_leg(sample)
+        print(json.dumps(out), flush=True)
+        return
+    w = TINY if args.config == 0 else WORKLOAD
     N, K, p = w["n_nodes"], w["K"], w["part"]
     dims = [w["F"], w["hidden"], w["classes"]]
     dec_dims = None
@@ -225,7 +279,10 @@ def main():
     sd = w["seeds"]
 
     t0 = time.time()
-    rowptr, colidx = synth.chung_lu_graph(N, w["avg_degree"], w["gamma"], seed=sd["graph"])
+    if args.config == 0:
+        rowptr, colidx = synth.uniform_graph(N, w["n_edges"], seed=sd["graph"])
+    else:
+        rowptr, colidx = synth.chung_lu_graph(N, w["avg_degree"], w["gamma"], seed=sd["graph"])
     X = synth.features(N, dims[0], seed=sd["feat"])
     y = synth.labels(N, dims[-1], seed=sd["label"])
     params = synth.sage_params(dims, seed=sd["weights"])
@@ -322,6 +379,12 @@ def main():
     per_step = {k: v[1] / 3.0 for k, v in prof.items()}
     dominant = max(per_step, key=per_step.get)
 
+    B.tma_profile_begin(None)       # the launch order of one step (matched against a profiler's dispatch list)
+    step()
+    torch.cuda.synchronize()
+    B.tma_profile_end()
+    kernel_sequence = B.tma_profile_sequence()
+
     # timed region; the dominant kernel alone carries events
     B.tma_profile_begin(dominant)
     torch.cuda.synchronize()
@@ -382,6 +445,10 @@ def main():
             return None, 0.0     # shapes of the link task that the tables do not cover
         return kernel_work(k, n_loc, nnz_loc, dims, s=sb, **kw)
 
+    # HBM bytes per launch as rocprofv3's counters measured them for this workload (profiles/hbm_traffic.json,
+    # written by `bench.py --summarize-traffic` from the counter runs named there)
+    traffic_table = benchlib.load_traffic("configs1") if (args.config == 1 and args.task == "node" and args.encoder == "sage"
+                                                           and args.dtype == "f32" and not args.norm_act) else {}
     bound, work = work_of(dominant)
     avg_ms = dom[1] / max(dom[0], 1)
     if bound == "mfma":
@@ -390,7 +457,7 @@ def main():
         bound = "hbm"
         achieved, peak, unit = work / (avg_ms * 1e-3) / 1e9, PEAK_HBM_GBS, "GB/s"
     roofline = dict(bound=bound, kernel=dominant, achieved=round(achieved, 3), peak=peak, unit=unit,
-                    frac=round(achieved / peak, 4), traffic=MEASURED_TRAFFIC_BYTES.get(dominant.replace("_generic", "")),
+                    frac=round(achieved / peak, 4), traffic=traffic_table.get(dominant.replace("_generic", "")),
                     avg_launch_ms=round(avg_ms, 5), launches=dom[0],
                     algorithmic_work_per_launch=work)
 
@@ -403,7 +470,7 @@ def main():
         if b is None or ms <= 0:
             continue
         per_launch_s = ms * 1e-3 / launches
-        traffic = MEASURED_TRAFFIC_BYTES.get(k.replace("_generic", ""))
+        traffic = traffic_table.get(k.replace("_generic", ""))
         if b == "mfma":
             kernel_rooflines[k] = {"bound": b, "achieved": round(wk / per_launch_s / 1e12, 2), "peak": peak_mfma,
                                    "unit": "TFLOP/s", "frac": round(wk / per_launch_s / 1e12 / peak_mfma, 4), "traffic": traffic,
@@ -434,7 +501,11 @@ def main():
         "value": round(value, 1), "unit": "edges/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": args.dtype, "data": "synthetic",
-        "config": {"workload": "configs[1]: Chung-Lu power-law graph (gamma 2.1), 1M nodes, avg degree 20, 128-d " + ("fp32 " if args.dtype == "f32" else "bf16 (second measurement; the configuration names fp32) ") +
+        "config": {"workload": ("configs[0] Tiny: uniform random graph, 20,000 nodes, 100,000 undirected edges, 64-d fp32 features, "
+                                "16 labels; K=4 random node partitions; whole path per step = partition + induced-subgraph "
+                                "extraction of part 0 + row gather + 2-layer mean-SAGE (hidden 64) full-batch fwd+bwd+SGD + "
+                                "4-way parameter averaging") if args.config == 0 else
+                               "configs[1]: Chung-Lu power-law graph (gamma 2.1), 1M nodes, avg degree 20, 128-d " + ("fp32 " if args.dtype == "f32" else "bf16 (second measurement; the configuration names fp32) ") +
                                "features, 47 classes; K=8 random node partitions; whole path per step = partition + "
                                "induced-subgraph extraction of part 0 + row gather + 2-layer mean-SAGE (hidden 256) "
                                "full-batch fwd+bwd+SGD + 8-way parameter averaging",
@@ -447,6 +518,7 @@ def main():
         "train_only_edges_per_s": round(L * nnz_loc / (train_ms * 1e-3), 1) if train_ms > 0 else None,
         "final_loss": loss,
         "streams": 2 if args.prefetch else 1,
+        "kernel_sequence": kernel_sequence,
     }
     if per_layer is not None:
         out["per_layer_fwd_bwd"] = per_layer      # edges_per_s = nnz_loc / (fwd + bwd) of that layer alone
@@ -457,20 +529,15 @@ def main():
                                      "second stream (bench.py --prefetch times that loop as the headline)"}
 
     if not args.no_cpu_baseline and args.task == "node" and args.dtype == "f32":
-        import oracle
-        from oracle import model as omodel
-        t_cpu = time.perf_counter()
-        part_o = oracle.partition(N, K, seed=sd["part"])
-        sub_o = oracle.induced_subgraph(rowptr, colidx, part_o, p)
-        Xo, yo = X[sub_o["l2g"]], y[sub_o["l2g"]]
-        p_o = [tuple(np.asarray(t, dtype=np.float64) for t in l) for l in params]
-        _, p_new = omodel.train_step(sub_o["rowptr"], sub_o["colidx"], Xo, yo, p_o, w["lr"], encoder=args.encoder)
-        omodel.aggregate([p_new] + [p_o] * (K - 1))
-        t_cpu = time.perf_counter() - t_cpu
-        out["cpu_baseline"] = {"value": round(L * len(sub_o["colidx"]) / t_cpu, 1), "unit": "edges/s", "cores": 1,
-                               "kind": "oracle",
-                               "sample": f"one full step of the same workload at full size (n_loc={len(sub_o['l2g'])}, "
-                                         f"nnz_loc={len(sub_o['colidx'])}), {t_cpu:.1f} s single-threaded fp64"}
+        def full(oracle, omodel, p_o):       # one full step of the same workload at full size
+            part_o = oracle.partition(N, K, seed=sd["part"])
+            sub_o = oracle.induced_subgraph(rowptr, colidx, part_o, p)
+            Xo, yo = X[sub_o["l2g"]], y[sub_o["l2g"]]
+            _, p_new = omodel.train_step(sub_o["rowptr"], sub_o["colidx"], Xo, yo, p_o, w["lr"], encoder=args.encoder)
+            omodel.aggregate([p_new] + [p_o] * (K - 1))
+        out["cpu_baseline"] = cpu_baseline_leg(dict(
+            params=params, full=full, edges=L * nnz_loc,
+            what=f"one full step of the same workload at full size (n_loc={n_loc}, nnz_loc={nnz_loc})"))
     print(json.dumps(out), flush=True)
 
 

@@ -135,7 +135,10 @@ int tma_induced_subgraph_fill(int64_t n_nodes, const int32_t *colidx,
  *     M_v = inv_deg[v] * sum_{u in N'(v)} H_u        (0 for an isolated node)
  * H, M_out: [n, F] of `dtype`, leading dimensions ldh / ldm.  fp32 accumulation
  * in neighbour order.  Also exported on its own because it is the HBM-bound
- * kernel of the path.
+ * kernel of the path.  With 16-byte aligned pointers and pitches a row is
+ * handled in 16-byte pieces; if F is no multiple of such a piece and both
+ * pitches leave room for the last whole piece, the padding elements of M_out
+ * inside that piece are overwritten.
  * ---------------------------------------------------------------------- */
 int tma_mean_aggregate(int64_t n, const int32_t *rowptr, const int32_t *colidx,
                        const float *inv_deg, const void *H, int64_t ldh, int32_t F,
@@ -149,7 +152,7 @@ int tma_mean_aggregate(int64_t n, const int32_t *rowptr, const int32_t *colidx,
  * neighbour mean excludes the node itself).
  *   H       [n, F_in]  dtype, ld = ldh
  *   W_self, W_neigh [F_in, F_out] fp32 row-major, dense;  bias [F_out] fp32
- *   M_out   [n, F_in]  dtype, dense (ld = F_in), 16-byte aligned: the layer's saved state.  It holds
+ *   M_out   [n, F_in]  dtype, leading dimension ldm >= F_in, 16-byte aligned: the layer's saved state.  It holds
  *           M = Abar H when the layer aggregates first (tma_sage_layer_aggregates_first() = 1).  When
  *           F_out is at most about half of F_in the layer transforms first -- Y = H [W_self | W_neigh],
  *           H' = act(Y_self + Abar Y_neigh + b), the same function by linearity with a much narrower
@@ -158,8 +161,12 @@ int tma_mean_aggregate(int64_t n, const int32_t *rowptr, const int32_t *colidx,
  *           columns are either left alone or set to zero.  With TMA_ACT_RELU the sign pattern of
  *           H' equals that of Z, so H' is all that backward needs.
  * The 16-byte vector paths need 16-byte aligned pointers and leading
- * dimensions that are multiples of 4 elements (pad rows for widths such as
- * 47); anything else takes a slower element-wise path with the same result.
+ * dimensions that are multiples of 16 bytes (pad rows for widths such as
+ * 47, or 100 in bf16); anything else takes a slower element-wise path with
+ * the same result.  A row width that is no multiple of 16 bytes still takes
+ * the vector path of the aggregation when ldh and ldm leave room for the last
+ * whole 16-byte piece (100 bf16 elements with ld >= 104): the padding elements
+ * of M_out up to that piece are then overwritten (with sums of H's padding).
  * No workspace.
  * ---------------------------------------------------------------------- */
 /* 1 if a layer of these widths aggregates first (M_out = Abar H), 0 if it transforms first. */
@@ -170,7 +177,7 @@ int tma_sage_layer_fwd(int64_t n, const int32_t *rowptr, const int32_t *colidx,
                        const void *H, int64_t ldh, int32_t F_in,
                        const float *W_self, const float *W_neigh, const float *bias,
                        int32_t F_out, int32_t act, int32_t dtype,
-                       void *M_out, void *Hnext_out, int64_t ld_next, tma_stream_t stream);
+                       void *M_out, int64_t ldm, void *Hnext_out, int64_t ld_next, tma_stream_t stream);
 
 /* ------------------------------------------------------------------------
  * Backward of the layer (chain rule as in the proof of Thm. 1, which writes
@@ -178,7 +185,7 @@ int tma_sage_layer_fwd(int64_t n, const int32_t *rowptr, const int32_t *colidx,
  *     dZ = dHnext (.) act'(Z)                  (act' from the sign of Hnext)
  *     dW_self = H^T dZ,  dW_neigh = M^T dZ,  dbias = column sums of dZ
  *     dH = dZ W_self^T + Abar^T (dZ W_neigh^T)
- *   H, M     as in forward;  Hnext [n, F_out] the forward output (read only
+ *   H, M, ldm as in forward;  Hnext [n, F_out] the forward output (read only
  *            when act = TMA_ACT_RELU);  dHnext [n, F_out] dtype; both with
  *            leading dimension ld_next (padding columns are ignored)
  *   rowptr_T/colidx_T : CSR of the TRANSPOSED local graph.  For a symmetric
@@ -196,7 +203,7 @@ size_t tma_sage_layer_bwd_workspace_bytes(int64_t n, int32_t F_in, int32_t F_out
 
 int tma_sage_layer_bwd(int64_t n, const int32_t *rowptr_T, const int32_t *colidx_T,
                        const float *inv_deg,
-                       const void *H, int64_t ldh, const void *M, const void *Hnext,
+                       const void *H, int64_t ldh, const void *M, int64_t ldm, const void *Hnext,
                        const void *dHnext, int64_t ld_next,
                        const float *W_self, const float *W_neigh,
                        int32_t F_in, int32_t F_out, int32_t act, int32_t dtype,
@@ -535,6 +542,10 @@ int tma_profile_begin(const char *kernel_filter);
 int tma_profile_end(void);
 int tma_profile_count(void);
 int tma_profile_entry(int index, const char **name_out, int64_t *launches_out, double *total_ms_out);
+/* The timed launches of the window that the last _end closed, in launch order (the same names; a profiler's
+ * dispatch list of the same run can be matched against it one to one). */
+int tma_profile_sequence_count(void);
+int tma_profile_sequence_entry(int index, const char **name_out);
 
 #ifdef __cplusplus
 }

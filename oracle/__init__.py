@@ -23,7 +23,7 @@ def build(force: bool = False) -> str:
     """Compile the C oracle with gcc (host only)."""
     if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
         subprocess.check_call(
-            ["gcc", "-O2", "-std=c11", "-Wall", "-Wextra", "-shared", "-fPIC",
+            ["gcc", "-O2", "-std=c11", "-fopenmp", "-Wall", "-Wextra", "-shared", "-fPIC",
              "-o", _LIB, _SRC, "-lm"])
     return _LIB
 
@@ -93,6 +93,16 @@ def induced_subgraph(rowptr, colidx, part, p: int):
     lib().orc_induced_fill(C.c_int64(n), _p(rowptr), _p(colidx), _p(part), C.c_int32(p),
                            _p(g2l), _p(l2g), _p(rp), _p(ci), _p(inv))
     return dict(g2l=g2l, l2g=l2g, rowptr=rp, colidx=ci, inv_deg=inv)
+
+
+# --------------------------------------------- the benchmark's all-cores timing leg
+def set_threads(n: int) -> None:
+    """Row loops of the aggregation and of the SAGE layer on n threads (timing only; tests keep the default 1)."""
+    lib().orc_set_threads(C.c_int(int(n)))
+
+
+def hardware_threads() -> int:
+    return int(lib().orc_hardware_threads())
 
 
 # ------------------------------------------------------- storage formats

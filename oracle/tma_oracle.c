@@ -9,6 +9,11 @@
  * Everything floating point is fp64, single-threaded, written as the
  * definition reads: adjacency scanned entry by entry, matrix products as
  * triple loops, no blocking, no fusion.
+ * For the benchmark's all-cores timing leg only, orc_set_threads(n > 1) lets
+ * the row loops of the aggregation and of the SAGE layer (the ones whose
+ * iterations are independent, or plain sums over rows) run under an OpenMP
+ * parallel-for: the same loops, split over rows.  Every test runs with the
+ * default of one thread, where those pragmas are inactive.
  *
  * Passages of the paper each function follows are named in its comment
  * (Preliminaries = the paragraph defining alpha, alpha^-1 and the node-induced
@@ -33,9 +38,15 @@
  * reverse-mode derivatives, finite differences through encoder + decoder.
  */
 #include <math.h>
+#include <omp.h>
 #include <stddef.h>
 #include <stdint.h>
 #include <string.h>
+
+static int orc_nthreads = 1;
+void orc_set_threads(int n) { orc_nthreads = n < 1 ? 1 : n; }
+int orc_hardware_threads(void) { return omp_get_num_procs(); }
+#define ORC_ROWS _Pragma("omp parallel for schedule(static) num_threads(orc_nthreads) if(orc_nthreads > 1)")
 
 /* ------------------------------------------------------------------------
  * Random assignment (Sec. 3.2.2): every node, or every super-node, goes
@@ -128,6 +139,7 @@ void orc_induced_fill(int64_t n_nodes, const int64_t *rowptr, const int32_t *col
 void orc_mean_aggregate(int64_t n, const int32_t *rowptr, const int32_t *colidx,
                         const double *H, int64_t F, double *M)
 {
+    ORC_ROWS
     for (int64_t v = 0; v < n; ++v) {
         double *m = M + v * F;
         for (int64_t f = 0; f < F; ++f) m[f] = 0.0;
@@ -172,6 +184,7 @@ void orc_sage_layer_fwd(int64_t n, const int32_t *rowptr, const int32_t *colidx,
                         double *M, double *Z, double *Hnext)
 {
     orc_mean_aggregate(n, rowptr, colidx, H, F_in, M);
+    ORC_ROWS
     for (int64_t v = 0; v < n; ++v) {
         double *z = Z + v * F_out;
         for (int64_t o = 0; o < F_out; ++o) z[o] = bias[o];
@@ -205,6 +218,9 @@ void orc_sage_layer_bwd(int64_t n, const int32_t *rowptr, const int32_t *colidx,
 
     for (int64_t i = 0; i < F_in * F_out; ++i) dW_self[i] = dW_neigh[i] = 0.0;
     for (int64_t o = 0; o < F_out; ++o) dbias[o] = 0.0;
+    const int64_t nW = F_in * F_out;
+#pragma omp parallel for schedule(static) num_threads(orc_nthreads) if(orc_nthreads > 1) \
+    reduction(+ : dW_self[:nW], dW_neigh[:nW], dbias[:F_out])
     for (int64_t v = 0; v < n; ++v) {       /* sums over nodes, one node at a time */
         const double *g = dZ + v * F_out;
         for (int64_t k = 0; k < F_in; ++k) {
@@ -219,6 +235,7 @@ void orc_sage_layer_bwd(int64_t n, const int32_t *rowptr, const int32_t *colidx,
     if (!dH) return;
 
     double *dM = scratch_dM;
+    ORC_ROWS
     for (int64_t v = 0; v < n; ++v)
         for (int64_t k = 0; k < F_in; ++k) {
             double s = 0.0, t = 0.0;

@@ -36,6 +36,7 @@ EXPORTS = (
     "tma_block_inv_deg", "tma_sage_block_fwd", "tma_sage_block_bwd_workspace_bytes", "tma_sage_block_bwd",
     "tma_loss_workspace_bytes", "tma_softmax_ce", "tma_sigmoid_l2", "tma_sgd_step", "tma_adam_step", "tma_average",
     "tma_gather_rows", "tma_profile_begin", "tma_profile_end", "tma_profile_count", "tma_profile_entry",
+    "tma_profile_sequence_count", "tma_profile_sequence_entry",
 )
 
 
@@ -230,17 +231,18 @@ def tma_sage_layer_fwd(rowptr, colidx, inv_deg, H, W_self, W_neigh, bias, act: i
     if rowptr.numel() != n + 1 or inv_deg.numel() != n:
         raise TmaError("tma_sage_layer_fwd: graph and feature row counts differ")
     if M_out is None:
-        M_out = torch.empty((n, F_in), dtype=H.dtype, device=H.device)
+        M_out = _padded(n, F_in, H.dtype, H.device)
     if Hnext_out is None:
         Hnext_out = _padded(n, F_out, H.dtype, H.device)
-    if tuple(M_out.shape) != (n, F_in) or tuple(Hnext_out.shape) != (n, F_out):
+    if tuple(M_out.shape) != (n, F_in) or tuple(Hnext_out.shape) != (n, F_out) or M_out.dtype != H.dtype:
         raise TmaError("tma_sage_layer_fwd: output shapes")
     _, _, ld_next = _rows_ld(Hnext_out, "Hnext_out")
+    _, _, ldm = _rows_ld(M_out, "M_out")
     _check(lib().tma_sage_layer_fwd(
         C.c_int64(n), _ptr(rowptr, torch.int32), _ptr(colidx, torch.int32), _ptr(inv_deg, torch.float32),
         C.c_void_p(H.data_ptr()), C.c_int64(ldh), C.c_int32(F_in), _ptr(W_self, torch.float32, "W_self"),
         _ptr(W_neigh, torch.float32, "W_neigh"), _ptr(bias, torch.float32, "bias"), C.c_int32(F_out),
-        C.c_int32(act), C.c_int32(_feat_dtype(H)), _ptr(M_out, H.dtype, "M_out"),
+        C.c_int32(act), C.c_int32(_feat_dtype(H)), C.c_void_p(M_out.data_ptr()), C.c_int64(ldm),
         C.c_void_p(Hnext_out.data_ptr()), C.c_int64(ld_next), _stream(stream)))
     return M_out, Hnext_out
 
@@ -256,8 +258,9 @@ def tma_sage_layer_bwd(rowptr_T, colidx_T, inv_deg, H, M, Hnext, dHnext, W_self,
     n, F_in, ldh = _rows_ld(H, "H")
     F_out = W_self.shape[1]
     dev = H.device
-    if tuple(M.shape) != (n, F_in) or tuple(dHnext.shape) != (n, F_out):
+    if tuple(M.shape) != (n, F_in) or tuple(dHnext.shape) != (n, F_out) or M.dtype != H.dtype:
         raise TmaError("tma_sage_layer_bwd: M / dHnext shapes")
+    _, _, ldm = _rows_ld(M, "M")
     if act == TMA_ACT_RELU and (Hnext is None or tuple(Hnext.shape) != (n, F_out)):
         raise TmaError("tma_sage_layer_bwd: Hnext is required with ReLU")
     if need_dH and (rowptr_T.numel() != n + 1 or inv_deg.numel() != n):
@@ -284,7 +287,7 @@ def tma_sage_layer_bwd(rowptr_T, colidx_T, inv_deg, H, M, Hnext, dHnext, W_self,
         ws = _workspace(need, dev, stream)
     _check(lib().tma_sage_layer_bwd(
         C.c_int64(n), _ptr(rowptr_T, torch.int32), _ptr(colidx_T, torch.int32), _ptr(inv_deg, torch.float32),
-        C.c_void_p(H.data_ptr()), C.c_int64(ldh), _ptr(M, H.dtype, "M"),
+        C.c_void_p(H.data_ptr()), C.c_int64(ldh), C.c_void_p(M.data_ptr()), C.c_int64(ldm),
         C.c_void_p(Hnext.data_ptr() if Hnext is not None else 0), C.c_void_p(dHnext.data_ptr()), C.c_int64(ld_next),
         _ptr(W_self, torch.float32), _ptr(W_neigh, torch.float32),
         C.c_int32(F_in), C.c_int32(F_out), C.c_int32(act), C.c_int32(dt),
@@ -865,16 +868,32 @@ def tma_gather_rows(l2g, src, out=None, stream=None):
         shape = (n_loc, cols)
     if out is None:
         out = torch.empty(shape, dtype=src.dtype, device=src.device)
-    if tuple(out.shape) != shape or out.dtype != src.dtype or not out.is_contiguous():
-        raise TmaError("tma_gather_rows: out must be a contiguous tensor of the gathered shape")
+    if tuple(out.shape) != shape or out.dtype != src.dtype:
+        raise TmaError("tma_gather_rows: out must have the gathered shape and the table's dtype")
+    dst_ld = row_bytes
+    if not out.is_contiguous():      # rows with a pitch of their own (a padded layout)
+        if out.dim() != 2 or out.stride(1) != 1 or out.stride(0) < shape[1]:
+            raise TmaError("tma_gather_rows: out must be row-major (contiguous, or rows with a larger pitch)")
+        dst_ld = out.stride(0) * out.element_size()
     _check(lib().tma_gather_rows(C.c_int64(n_loc), _ptr(l2g, torch.int32, "l2g"), C.c_void_p(src.data_ptr()),
                                  C.c_int64(src_ld), C.c_int64(row_bytes), C.c_void_p(out.data_ptr()),
-                                 C.c_int64(row_bytes), _stream(stream)))
+                                 C.c_int64(dst_ld), _stream(stream)))
     return out
 
 
 def tma_profile_begin(kernel_filter: str | None = None):
     _check(lib().tma_profile_begin(None if not kernel_filter else kernel_filter.encode()))
+
+
+def tma_profile_sequence() -> list:
+    """Names of the timed launches of the window that the last tma_profile_end closed, in launch order."""
+    L = lib()
+    out = []
+    for i in range(L.tma_profile_sequence_count()):
+        name = C.c_char_p()
+        _check(L.tma_profile_sequence_entry(C.c_int(i), C.byref(name)))
+        out.append(name.value.decode())
+    return out
 
 
 def tma_profile_end() -> dict:

@@ -38,6 +38,7 @@ bool g_on = false;
 std::string g_filter;
 std::vector<Sample> g_samples;
 std::vector<Entry> g_entries;
+std::vector<std::string> g_sequence;   // names of the timed launches of the last window, in launch order
 }  // namespace
 
 KernelTimer::KernelTimer(const char *name, hipStream_t stream) : slot_(-1), stream_(stream)
@@ -88,8 +89,10 @@ extern "C" int tma_profile_end(void)
     std::lock_guard<std::mutex> lk(g_mu);
     g_on = false;
     g_entries.clear();
+    g_sequence.clear();
     int rc = TMA_OK;
     for (auto &s : g_samples) {
+        g_sequence.push_back(s.name);
         float ms = 0.0f;
         hipError_t e = hipEventSynchronize(s.stop);
         if (e == hipSuccess) e = hipEventElapsedTime(&ms, s.start, s.stop);
@@ -107,6 +110,22 @@ extern "C" int tma_profile_end(void)
     }
     g_samples.clear();
     return rc;
+}
+
+extern "C" int tma_profile_sequence_count(void)
+{
+    std::lock_guard<std::mutex> lk(tma::g_mu);
+    return int(tma::g_sequence.size());
+}
+
+extern "C" int tma_profile_sequence_entry(int index, const char **name_out)
+{
+    using namespace tma;
+    std::lock_guard<std::mutex> lk(g_mu);
+    TMA_REQUIRE(index >= 0 && index < int(g_sequence.size()) && name_out, TMA_ERR_INVALID_ARG,
+                "tma_profile_sequence_entry: index %d", index);
+    *name_out = g_sequence[index].c_str();
+    return TMA_OK;
 }
 
 extern "C" int tma_profile_count(void)

@@ -49,7 +49,7 @@ static int dense_fwd_typed(int64_t n, const T *X, int64_t ldx, int32_t F_in, con
                                 "gemm_dense_fwd_bf16_generic", va);
 #define TMA_DENSE_FWD(VA_, VB_)                                                               \
     do {                                                                                      \
-        CatRows<T, VA_> a{X, ldx, X, F_in, n, F_in};                                          \
+        CatRows<T, VA_> a{X, ldx, X, ldx, F_in, n, F_in};                                          \
         SideWeights<VB_> b{W, W, F_in, F_out, pad8(F_out)};                                   \
         launch_by_width<T, 32, false>(name, a, b, e, n, N_out, K, kps, 1, nullptr, s);        \
     } while (0)
@@ -166,11 +166,11 @@ static int dense_bwd_weight_typed(int64_t n, const T *X, int64_t ldx, const T *g
     const char *name = kname<T>("gemm_dense_bwd_weight", "gemm_dense_bwd_weight_generic", "gemm_dense_bwd_weight_bf16",
                                 "gemm_dense_bwd_weight_bf16_generic", v);
     if (v) {
-        CatRowsT<T, true> a{X, ldx, X, F_in, n};
+        CatRowsT<T, true> a{X, ldx, X, ldx, F_in, n};
         MaskedGrad<false, T, true, kRelu> b{g, h, F_out, ld, n};
         launch_by_width<T, 32, true>(name, a, b, e, int64_t(F_in), F_out, n, w.k_per_split, w.n_splits, colsum, s);
     } else {
-        CatRowsT<T, false> a{X, ldx, X, F_in, n};
+        CatRowsT<T, false> a{X, ldx, X, ldx, F_in, n};
         MaskedGrad<false, T, false, kRelu> b{g, h, F_out, ld, n};
         launch_by_width<T, 32, true>(name, a, b, e, int64_t(F_in), F_out, n, w.k_per_split, w.n_splits, colsum, s);
     }

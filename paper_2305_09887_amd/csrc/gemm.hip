@@ -129,10 +129,10 @@ int launch_reduce_splits(const float *partial, const float *colsum_partial, int 
 
 // ---- forward ----------------------------------------------------------------
 template <typename T, bool VA, bool VB>
-static void fwd_dispatch(int64_t n, const T *H, int64_t ldh, const T *M, int F_in, const float *W_self,
+static void fwd_dispatch(int64_t n, const T *H, int64_t ldh, const T *M, int64_t ldm, int F_in, const float *W_self,
                          const float *W_neigh, const FwdEpilogue<T> &e, int F_out, hipStream_t s)
 {
-    CatRows<T, VA> a{H, ldh, M, F_in, n, 2 * F_in};
+    CatRows<T, VA> a{H, ldh, M, ldm, F_in, n, 2 * F_in};
     CatWeights<VB> b{W_self, W_neigh, F_in, F_out};
     const int64_t K = 2 * int64_t(F_in);
     const int64_t kps = int64_t(round_up(size_t(K), 32));
@@ -145,30 +145,30 @@ static void fwd_dispatch(int64_t n, const T *H, int64_t ldh, const T *M, int F_i
 }
 
 template <typename T>
-static int fwd_typed(int64_t n, const T *H, int64_t ldh, const T *M, int32_t F_in, const float *W_self,
+static int fwd_typed(int64_t n, const T *H, int64_t ldh, const T *M, int64_t ldm, int32_t F_in, const float *W_self,
                      const float *W_neigh, const float *bias, int32_t F_out, int32_t act, T *Hnext, int64_t ld_next,
                      hipStream_t stream)
 {
     FwdEpilogue<T> e{Hnext, ld_next, bias, act == TMA_ACT_RELU};
-    const bool va = vec4_ok(H, ldh) && vec4_ok(M, F_in);
+    const bool va = vec4_ok(H, ldh) && vec4_ok(M, ldm) && F_in % 4 == 0;
     const bool vb = vec4_ok(W_self, F_out) && vec4_ok(W_neigh, F_out);
-    if (va && vb) fwd_dispatch<T, true, true>(n, H, ldh, M, F_in, W_self, W_neigh, e, F_out, stream);
-    else if (va) fwd_dispatch<T, true, false>(n, H, ldh, M, F_in, W_self, W_neigh, e, F_out, stream);
-    else if (vb) fwd_dispatch<T, false, true>(n, H, ldh, M, F_in, W_self, W_neigh, e, F_out, stream);
-    else fwd_dispatch<T, false, false>(n, H, ldh, M, F_in, W_self, W_neigh, e, F_out, stream);
+    if (va && vb) fwd_dispatch<T, true, true>(n, H, ldh, M, ldm, F_in, W_self, W_neigh, e, F_out, stream);
+    else if (va) fwd_dispatch<T, true, false>(n, H, ldh, M, ldm, F_in, W_self, W_neigh, e, F_out, stream);
+    else if (vb) fwd_dispatch<T, false, true>(n, H, ldh, M, ldm, F_in, W_self, W_neigh, e, F_out, stream);
+    else fwd_dispatch<T, false, false>(n, H, ldh, M, ldm, F_in, W_self, W_neigh, e, F_out, stream);
     return check_launch("sage gemm fwd");
 }
 
-int launch_sage_gemm_fwd(int64_t n, const void *H, int64_t ldh, const void *M, int32_t F_in, const float *W_self,
+int launch_sage_gemm_fwd(int64_t n, const void *H, int64_t ldh, const void *M, int64_t ldm, int32_t F_in, const float *W_self,
                          const float *W_neigh, const float *bias, int32_t F_out, int32_t act, int32_t dtype,
                          void *Hnext, int64_t ld_next, hipStream_t stream)
 {
     if (n == 0 || F_out == 0) return TMA_OK;
     if (dtype == TMA_F32)
-        return fwd_typed<float>(n, static_cast<const float *>(H), ldh, static_cast<const float *>(M), F_in, W_self,
+        return fwd_typed<float>(n, static_cast<const float *>(H), ldh, static_cast<const float *>(M), ldm, F_in, W_self,
                                 W_neigh, bias, F_out, act, static_cast<float *>(Hnext), ld_next, stream);
     if (dtype == TMA_BF16)
-        return fwd_typed<uint16_t>(n, static_cast<const uint16_t *>(H), ldh, static_cast<const uint16_t *>(M), F_in,
+        return fwd_typed<uint16_t>(n, static_cast<const uint16_t *>(H), ldh, static_cast<const uint16_t *>(M), ldm, F_in,
                                    W_self, W_neigh, bias, F_out, act, static_cast<uint16_t *>(Hnext), ld_next, stream);
     return fail(TMA_ERR_UNSUPPORTED_DTYPE, "sage gemm fwd: dtype %d", dtype);
 }
@@ -256,12 +256,12 @@ size_t sage_gemm_bwd_weight_workspace_bytes(int64_t n, int32_t F_in, int32_t F_o
 }
 
 template <typename T, bool VA, bool VB, bool kRelu>
-static void bwd_weight_dispatch(int64_t n, const T *H, int64_t ldh, const T *M, const T *g, const T *h,
+static void bwd_weight_dispatch(int64_t n, const T *H, int64_t ldh, const T *M, int64_t ldm, const T *g, const T *h,
                                 int64_t ld_next, int F_in, int F_out, const WeightSplit &w, const SplitEpilogue &e,
                                 float *colsum, hipStream_t s)
 {
     constexpr bool V = VA && VB;
-    CatRowsT<T, VA> a{H, ldh, M, F_in, n};
+    CatRowsT<T, VA> a{H, ldh, M, ldm, F_in, n};
     MaskedGrad<false, T, VB, kRelu> b{g, h, F_out, ld_next, n};
     const int64_t Mtot = 2 * int64_t(F_in);
     if (F_out <= 64)
@@ -273,16 +273,16 @@ static void bwd_weight_dispatch(int64_t n, const T *H, int64_t ldh, const T *M, 
 }
 
 template <typename T>
-static int bwd_weight_typed(int64_t n, const T *H, int64_t ldh, const T *M, const T *g, const T *h, int64_t ld_next,
+static int bwd_weight_typed(int64_t n, const T *H, int64_t ldh, const T *M, int64_t ldm, const T *g, const T *h, int64_t ld_next,
                             int32_t F_in, int32_t F_out, int32_t act, const WeightSplit &w, const SplitEpilogue &e,
                             float *colsum, hipStream_t stream)
 {
     const bool relu = act == TMA_ACT_RELU;
-    const bool va = vec4_ok(H, ldh) && vec4_ok(M, F_in);
+    const bool va = vec4_ok(H, ldh) && vec4_ok(M, ldm) && F_in % 4 == 0;
     const bool vb = vec4_ok(g, ld_next) && (!relu || vec4_ok(h, ld_next));
 #define TMA_BWD_WEIGHT(VA_, VB_)                                                                                           \
-    (relu ? bwd_weight_dispatch<T, VA_, VB_, true>(n, H, ldh, M, g, h, ld_next, F_in, F_out, w, e, colsum, stream)         \
-          : bwd_weight_dispatch<T, VA_, VB_, false>(n, H, ldh, M, g, h, ld_next, F_in, F_out, w, e, colsum, stream))
+    (relu ? bwd_weight_dispatch<T, VA_, VB_, true>(n, H, ldh, M, ldm, g, h, ld_next, F_in, F_out, w, e, colsum, stream)         \
+          : bwd_weight_dispatch<T, VA_, VB_, false>(n, H, ldh, M, ldm, g, h, ld_next, F_in, F_out, w, e, colsum, stream))
     if (va && vb) TMA_BWD_WEIGHT(true, true);
     else if (va) TMA_BWD_WEIGHT(true, false);
     else if (vb) TMA_BWD_WEIGHT(false, true);
@@ -291,7 +291,7 @@ static int bwd_weight_typed(int64_t n, const T *H, int64_t ldh, const T *M, cons
     return check_launch("sage gemm bwd weight");
 }
 
-int launch_sage_gemm_bwd_weight(int64_t n, const void *H, int64_t ldh, const void *M, const void *dHnext,
+int launch_sage_gemm_bwd_weight(int64_t n, const void *H, int64_t ldh, const void *M, int64_t ldm, const void *dHnext,
                                 const void *Hnext, int64_t ld_next, int32_t F_in, int32_t F_out, int32_t act,
                                 int32_t dtype, float *dW_self, float *dW_neigh, float *dbias, void *ws, size_t ws_bytes,
                                 hipStream_t stream)
@@ -312,11 +312,11 @@ int launch_sage_gemm_bwd_weight(int64_t n, const void *H, int64_t ldh, const voi
     if (have_rows) {
         int rc;
         if (dtype == TMA_F32)
-            rc = bwd_weight_typed<float>(n, static_cast<const float *>(H), ldh, static_cast<const float *>(M),
+            rc = bwd_weight_typed<float>(n, static_cast<const float *>(H), ldh, static_cast<const float *>(M), ldm,
                                          static_cast<const float *>(dHnext), static_cast<const float *>(Hnext), ld_next,
                                          F_in, F_out, act, w, e, colsum, stream);
         else
-            rc = bwd_weight_typed<uint16_t>(n, static_cast<const uint16_t *>(H), ldh, static_cast<const uint16_t *>(M),
+            rc = bwd_weight_typed<uint16_t>(n, static_cast<const uint16_t *>(H), ldh, static_cast<const uint16_t *>(M), ldm,
                                             static_cast<const uint16_t *>(dHnext),
                                             static_cast<const uint16_t *>(Hnext), ld_next, F_in, F_out, act, w, e,
                                             colsum, stream);
@@ -342,7 +342,7 @@ static int tf_fwd_typed(int64_t n, const T *H, int64_t ldh, int32_t F_in, const 
     const char *name = kname<T>("gemm_tf_fwd", "gemm_tf_fwd_generic", "gemm_tf_fwd_bf16", "gemm_tf_fwd_bf16_generic", va);
 #define TMA_TF_FWD(VA_, VB_)                                                                      \
     do {                                                                                          \
-        CatRows<T, VA_> a{H, ldh, H, F_in, n, F_in};                                                   \
+        CatRows<T, VA_> a{H, ldh, H, ldh, F_in, n, F_in};                                                   \
         SideWeights<VB_> b{W_self, W_neigh, F_in, F_out, Fp};                                     \
         launch_by_width<T, 32, false>(name, a, b, e, n, 2 * Fp, K, kps, 1, nullptr, s);              \
     } while (0)
@@ -406,7 +406,7 @@ static int tf_bwd_weight_typed(int64_t n, const T *H, int64_t ldh, const T *g, c
                                 "gemm_tf_bwd_weight_bf16_generic", va && vb);
 #define TMA_TF_BW(VA_, VB_, R_)                                                                                       \
     do {                                                                                                              \
-        CatRowsT<T, VA_> a{H, ldh, H, F_in, n};                                                                       \
+        CatRowsT<T, VA_> a{H, ldh, H, ldh, F_in, n};                                                                       \
         SideGrad<false, T, VB_, R_> b{g, h, dYn, F_out, Fp, ld_next, ldy, n};                                         \
         launch_by_width<T, (sizeof(T) == 2 ? 32 : 16), true>(name, a, b, e, int64_t(F_in), 2 * Fp, n, w.k_per_split, w.n_splits, colsum, s);     \
     } while (0)

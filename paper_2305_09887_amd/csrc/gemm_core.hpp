@@ -131,6 +131,7 @@ struct CatRows {  // A[m][k] = k < F ? H[m][k] : M[m][k-F]  for k < Kv, zero bey
     const T *H;
     int64_t ldh;
     const T *Mx;
+    int64_t ldm;
     int F;
     int64_t rows;
     int Kv;  // extent of k: 2F for the concatenation, F when only the first part is used (Mx is then never read)
@@ -138,7 +139,7 @@ struct CatRows {  // A[m][k] = k < F ? H[m][k] : M[m][k-F]  for k < Kv, zero bey
     __device__ __forceinline__ Lane prepare(int64_t m) const
     {
         const int64_t mm = m < rows ? m : 0;
-        return Lane{H + mm * ldh, Mx + mm * int64_t(F) - F, m < rows};
+        return Lane{H + mm * ldh, Mx + mm * ldm - F, m < rows};
     }
     __device__ __forceinline__ float at(const Lane &l, int k) const
     {
@@ -185,6 +186,7 @@ struct CatRowsT {  // A[m][k] = (m < F ? H[k][m] : M[k][m-F])          (contiguo
     const T *H;
     int64_t ldh;
     const T *Mx;
+    int64_t ldm;
     int F;
     int64_t rows;
     static __device__ __forceinline__ float4 resolve(const Raw &r) { return r.get(); }
@@ -192,12 +194,12 @@ struct CatRowsT {  // A[m][k] = (m < F ? H[k][m] : M[k][m-F])          (contiguo
     {
         const int m = int(m64);
         if (m < F) return Lane{H + m, ldh, m, true};
-        return Lane{Mx + (m < 2 * F ? m - F : 0), int64_t(F), m, m < 2 * F};
+        return Lane{Mx + (m < 2 * F ? m - F : 0), ldm, m, m < 2 * F};
     }
     __device__ __forceinline__ float at(int64_t node, int m) const
     {
         if (m < F) return widen1(H + node * ldh + m);
-        if (m < 2 * F) return widen1(Mx + node * int64_t(F) + (m - F));
+        if (m < 2 * F) return widen1(Mx + node * ldm + (m - F));
         return 0.0f;
     }
     __device__ __forceinline__ Raw load(const Lane &l, int64_t node) const

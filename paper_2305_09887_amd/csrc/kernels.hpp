@@ -25,8 +25,8 @@ int launch_scale_mask_rows(int64_t n, int32_t F, int32_t F_pad, const void *g, c
                            const float *inv_deg, bool relu, int32_t dtype, void *dst, int64_t ld_dst,
                            hipStream_t stream);
 
-// Z = [H | M] [W_self ; W_neigh] + b ;  Hnext = act(Z)
-int launch_sage_gemm_fwd(int64_t n, const void *H, int64_t ldh, const void *M, int32_t F_in, const float *W_self,
+// Z = [H | M] [W_self ; W_neigh] + b ;  Hnext = act(Z)      (M: [n, F_in] with leading dimension ldm)
+int launch_sage_gemm_fwd(int64_t n, const void *H, int64_t ldh, const void *M, int64_t ldm, int32_t F_in, const float *W_self,
                          const float *W_neigh, const float *bias, int32_t F_out, int32_t act, int32_t dtype,
                          void *Hnext, int64_t ld_next, hipStream_t stream);
 
@@ -38,7 +38,7 @@ int launch_sage_gemm_bwd_data(int64_t n, const void *dHnext, const void *Hnext, 
 
 // [dW_self ; dW_neigh] = [H | M]^T dZ,  dbias = 1^T dZ   (split over nodes, two-stage fixed-order reduction)
 size_t sage_gemm_bwd_weight_workspace_bytes(int64_t n, int32_t F_in, int32_t F_out);
-int launch_sage_gemm_bwd_weight(int64_t n, const void *H, int64_t ldh, const void *M, const void *dHnext,
+int launch_sage_gemm_bwd_weight(int64_t n, const void *H, int64_t ldh, const void *M, int64_t ldm, const void *dHnext,
                                 const void *Hnext, int64_t ld_next, int32_t F_in, int32_t F_out, int32_t act,
                                 int32_t dtype,
                                 float *dW_self, float *dW_neigh, float *dbias, void *ws, size_t ws_bytes,

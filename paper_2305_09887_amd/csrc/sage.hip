@@ -39,7 +39,7 @@ static BwdWorkspace plan_bwd(int64_t n, int32_t F_in, int32_t F_out, int32_t dty
 extern "C" int tma_sage_layer_fwd(int64_t n, const int32_t *rowptr, const int32_t *colidx, const float *inv_deg,
                                   const void *H, int64_t ldh, int32_t F_in, const float *W_self,
                                   const float *W_neigh, const float *bias, int32_t F_out, int32_t act, int32_t dtype,
-                                  void *M_out, void *Hnext_out, int64_t ld_next, tma_stream_t stream)
+                                  void *M_out, int64_t ldm, void *Hnext_out, int64_t ld_next, tma_stream_t stream)
 {
     using namespace tma;
     const char *fn = "tma_sage_layer_fwd";
@@ -51,11 +51,12 @@ extern "C" int tma_sage_layer_fwd(int64_t n, const int32_t *rowptr, const int32_
     if (n == 0) return TMA_OK;
     TMA_REQUIRE(rowptr && inv_deg && H && W_self && W_neigh && bias && M_out && Hnext_out, TMA_ERR_INVALID_ARG,
                 "%s: NULL argument", fn);
-    TMA_REQUIRE(ldh >= F_in && ld_next >= F_out, TMA_ERR_BAD_SHAPE, "%s: ldh < F_in or ld_next < F_out", fn);
+    TMA_REQUIRE(ldh >= F_in && ldm >= F_in && ld_next >= F_out, TMA_ERR_BAD_SHAPE,
+                "%s: ldh < F_in, ldm < F_in or ld_next < F_out", fn);
     hipStream_t s = as_stream(stream);
     if (aggregates_first(F_in, F_out, dtype)) {
-        if (int rc = launch_spmm(n, rowptr, colidx, inv_deg, H, ldh, F_in, dtype, M_out, F_in, false, s)) return rc;
-        return launch_sage_gemm_fwd(n, H, ldh, M_out, F_in, W_self, W_neigh, bias, F_out, act, dtype, Hnext_out,
+        if (int rc = launch_spmm(n, rowptr, colidx, inv_deg, H, ldh, F_in, dtype, M_out, ldm, false, s)) return rc;
+        return launch_sage_gemm_fwd(n, H, ldh, M_out, ldm, F_in, W_self, W_neigh, bias, F_out, act, dtype, Hnext_out,
                                     ld_next, s);
     }
     // transform first: [Y_self | Y_neigh] = H [W_self | W_neigh] into the M_out buffer, then
@@ -86,8 +87,8 @@ extern "C" size_t tma_sage_layer_bwd_workspace_bytes(int64_t n, int32_t F_in, in
 }
 
 extern "C" int tma_sage_layer_bwd(int64_t n, const int32_t *rowptr_T, const int32_t *colidx_T, const float *inv_deg,
-                                  const void *H, int64_t ldh, const void *M, const void *Hnext, const void *dHnext,
-                                  int64_t ld_next, const float *W_self, const float *W_neigh, int32_t F_in, int32_t F_out, int32_t act,
+                                  const void *H, int64_t ldh, const void *M, int64_t ldm, const void *Hnext,
+                                  const void *dHnext, int64_t ld_next, const float *W_self, const float *W_neigh, int32_t F_in, int32_t F_out, int32_t act,
                                   int32_t dtype, float *dW_self, float *dW_neigh, float *dbias, void *dH_out, void *ws,
                                   size_t ws_bytes, tma_stream_t stream)
 {
@@ -109,7 +110,8 @@ extern "C" int tma_sage_layer_bwd(int64_t n, const int32_t *rowptr_T, const int3
         TMA_REQUIRE(H && (M || !agg_first) && dHnext && W_self && W_neigh, TMA_ERR_INVALID_ARG, "%s: NULL argument", fn);
         TMA_REQUIRE(act == TMA_ACT_NONE || Hnext, TMA_ERR_INVALID_ARG, "%s: Hnext is required with ReLU", fn);
         TMA_REQUIRE(!need_dH || (rowptr_T && inv_deg), TMA_ERR_INVALID_ARG, "%s: graph is NULL", fn);
-        TMA_REQUIRE(ldh >= F_in && ld_next >= F_out, TMA_ERR_BAD_SHAPE, "%s: ldh < F_in or ld_next < F_out", fn);
+        TMA_REQUIRE(ldh >= F_in && ld_next >= F_out && (!agg_first || ldm >= F_in), TMA_ERR_BAD_SHAPE,
+                    "%s: ldh < F_in, ldm < F_in or ld_next < F_out", fn);
     }
     hipStream_t s = as_stream(stream);
     char *base = static_cast<char *>(ws);
@@ -134,7 +136,7 @@ extern "C" int tma_sage_layer_bwd(int64_t n, const int32_t *rowptr_T, const int3
         return launch_sage_tf_gemm_bwd_data(n, dHnext, Hnext, ld_next, dYn, Fp, W_self, W_neigh, F_in, F_out, act,
                                             dtype, dH_out, ldh, s);
     }
-    if (int rc = launch_sage_gemm_bwd_weight(n, H, ldh, M, dHnext, Hnext, ld_next, F_in, F_out, act, dtype, dW_self,
+    if (int rc = launch_sage_gemm_bwd_weight(n, H, ldh, M, ldm, dHnext, Hnext, ld_next, F_in, F_out, act, dtype, dW_self,
                                              dW_neigh, dbias, wws, w.weight_bytes, s))
         return rc;
     if (!need_dH || n == 0) return TMA_OK;

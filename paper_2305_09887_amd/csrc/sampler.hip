@@ -448,7 +448,7 @@ extern "C" int tma_sage_block_fwd(int64_t n_dst, int64_t n_src, const int32_t *b
     hipStream_t s = as_stream(stream);
     if (int rc = launch_spmm(n_dst, blk_rowptr, blk_col, inv_deg, H, ldh, F_in, dtype, M_out, F_in, false, s, n_src))
         return rc;
-    return launch_sage_gemm_fwd(n_dst, H, ldh, M_out, F_in, W_self, W_neigh, bias, F_out, act, dtype, Hnext_out, ld_next, s);
+    return launch_sage_gemm_fwd(n_dst, H, ldh, M_out, F_in, F_in, W_self, W_neigh, bias, F_out, act, dtype, Hnext_out, ld_next, s);
 }
 
 extern "C" size_t tma_sage_block_bwd_workspace_bytes(int64_t n_dst, int64_t n_src, int64_t max_entries, int32_t F_in,
@@ -496,7 +496,7 @@ extern "C" int tma_sage_block_bwd(int64_t n_dst, int64_t n_src, int64_t max_entr
     void *scan_ws = base + w.dm_bytes + w.deg_bytes + w.rowptr_bytes + 2 * w.list_bytes;
     void *wws = base + w.dm_bytes + w.deg_bytes + w.rowptr_bytes + 2 * w.list_bytes + w.scan_bytes;
 
-    if (int rc = launch_sage_gemm_bwd_weight(n_dst, H, ldh, M, dHnext, Hnext, ld_next, F_in, F_out, act, dtype, dW_self,
+    if (int rc = launch_sage_gemm_bwd_weight(n_dst, H, ldh, M, F_in, dHnext, Hnext, ld_next, F_in, F_out, act, dtype, dW_self,
                                              dW_neigh, dbias, wws, w.weight_bytes, s))
         return rc;
     if (!need_dH || n_src == 0) return TMA_OK;

@@ -574,10 +574,15 @@ template <typename T>
 static int launch_typed(int64_t n, const int32_t *rowptr, const int32_t *colidx, const T *in, int64_t ld_in, int32_t F,
                         const SpmmOut<T> &o, hipStream_t s)
 {
-    const size_t row_bytes = size_t(F) * sizeof(T);
-    const bool vec_ok = row_bytes % 16 == 0 && (size_t(ld_in) * sizeof(T)) % 16 == 0 &&
-                        (size_t(o.ld_out) * sizeof(T)) % 16 == 0 && aligned(in, 16) && aligned(o.out, 16) &&
-                        (!o.self || ((size_t(o.ld_self) * sizeof(T)) % 16 == 0 && aligned(o.self, 16))) &&
+    // A row is walked in whole 16-byte pieces.  A width that is no multiple of 16 bytes (100 bf16 elements) still
+    // takes this path when every pitch leaves room for the last piece: the piece's tail then reads and writes
+    // padding elements inside the rows (never memory outside them).
+    const size_t row_bytes = round_up(size_t(F) * sizeof(T), 16);
+    const bool vec_ok = (size_t(ld_in) * sizeof(T)) % 16 == 0 && size_t(ld_in) * sizeof(T) >= row_bytes &&
+                        (size_t(o.ld_out) * sizeof(T)) % 16 == 0 && size_t(o.ld_out) * sizeof(T) >= row_bytes &&
+                        aligned(in, 16) && aligned(o.out, 16) &&
+                        (!o.self || ((size_t(o.ld_self) * sizeof(T)) % 16 == 0 && aligned(o.self, 16) &&
+                                     size_t(o.ld_self) * sizeof(T) >= row_bytes)) &&
                         row_bytes / 16 <= 256 && !(o.self && o.accumulate);
     // the streaming kernel's weighted form takes the self weight from the row scale it already holds
     const bool edge_stream = o.edge_scale && o.self && o.inv_deg == o.edge_scale;

@@ -83,7 +83,9 @@ class LocalTrainer:
         # activations and their gradients share one row pitch per layer, padded to 16 bytes so that a
         # width such as 47 still takes the library's vector paths
         self.H = [X] + [B._padded(self.n, f, self.dtype, dev) for f in dims[1:]]
-        self.M = ([torch.empty((n, f), dtype=self.dtype, device=dev)[: self.n] for f in dims[:-1]]
+        # the saved aggregate of a SAGE layer may have padded rows (16-byte pieces for any width); GCN's is dense
+        self.M = ([(B._padded(n, f, self.dtype, dev) if encoder == "sage" else
+                    torch.empty((n, f), dtype=self.dtype, device=dev))[: self.n] for f in dims[:-1]]
                   if encoder != "mlp" else None)
         # gradient w.r.t. H[l] for l = 1..L (index l); dH[L] is d(loss)/d(logits)
         self.dH = [None] + [B._padded(self.n, f, self.dtype, dev) for f in dims[1:]]

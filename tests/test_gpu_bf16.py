@@ -61,6 +61,60 @@ def test_mean_aggregate_bf16(B, F):
     close(host(got), oracle.mean_aggregate(sub["rowptr"], sub["colidx"], H), f"M F={F}")
 
 
+@pytest.mark.parametrize("F,ld,bf16", [(100, 128, True), (100, 104, True), (47, 48, False), (5, 8, False), (33, 40, True)])
+def test_mean_aggregate_of_a_ragged_width_in_padded_rows(B, F, ld, bf16):
+    """A row width that is no multiple of 16 bytes (the SuperTMA configuration's 100 bf16 features) in rows padded to
+    whole 16-byte pieces: the vector path walks the last piece too, so it may overwrite the padding elements of the
+    output up to that piece -- and nothing beyond it, and the valid columns are the oracle's."""
+    sub = _sub(6000, 30_000, F + ld)
+    n = len(sub["l2g"])
+    H = synth.features(n, F, seed=1)
+    H = synth.round_bf16(H) if bf16 else H
+    dt = torch.bfloat16 if bf16 else torch.float32
+    per16 = 8 if bf16 else 4
+    piece_end = (F + per16 - 1) // per16 * per16
+    Hd = torch.full((n, ld), 3.0, dtype=dt, device="cuda")            # finite padding, as a caller's zero-fill would be
+    Hd[:, :F] = dev_bf16(H) if bf16 else dev(H)
+    out = torch.full((n, ld), -7.0, dtype=dt, device="cuda")
+    got = B.tma_mean_aggregate(dev(sub["rowptr"]), dev(sub["colidx"]), dev(sub["inv_deg"], torch.float32), Hd[:, :F],
+                               out=out[:, :F])
+    close(host(got), oracle.mean_aggregate(sub["rowptr"], sub["colidx"], H), f"M F={F} ld={ld}", tol=TOL if bf16 else 1e-4)
+    assert torch.all(out[:, piece_end:] == -7.0)                       # nothing past the last whole piece is touched
+    if B.lib() is not None and ld * (2 if bf16 else 4) % 16 == 0:
+        # the name of the kernel that ran: the streaming kernel, not the element-wise fallback
+        B.tma_profile_begin(None)
+        B.tma_mean_aggregate(dev(sub["rowptr"]), dev(sub["colidx"]), dev(sub["inv_deg"], torch.float32), Hd[:, :F],
+                             out=out[:, :F])
+        assert all("generic" not in k for k in B.tma_profile_end())
+
+
+def test_sage_layer_bf16_with_100_features_in_padded_rows(B):
+    """The first layer of the SuperTMA configuration (100 -> 256, bf16) with H and the saved aggregate M in rows of
+    128 elements: forward and backward against the oracle, M's valid columns included."""
+    sub = _sub(5000, 40_000, 77)
+    rp, ci, inv = sub["rowptr"], sub["colidx"], sub["inv_deg"]
+    n, F_in, F_out, ld = len(sub["l2g"]), 100, 256, 128
+    H = synth.round_bf16(synth.features(n, F_in, seed=1))
+    (Ws, Wn, b), = synth.sage_params([F_in, F_out], seed=2)
+    M_o, Z_o, Hn_o = oracle.sage_layer_fwd(rp, ci, H, Ws, Wn, b, oracle.ACT_RELU)
+    d_rp, d_ci, d_inv = dev(rp), dev(ci), dev(inv, torch.float32)
+    Hd = torch.zeros((n, ld), dtype=torch.bfloat16, device="cuda")
+    Hd[:, :F_in] = dev_bf16(H)
+    Md = torch.zeros((n, ld), dtype=torch.bfloat16, device="cuda")
+    M_g, Hn_g = B.tma_sage_layer_fwd(d_rp, d_ci, d_inv, Hd[:, :F_in], dev(Ws), dev(Wn), dev(b), oracle.ACT_RELU,
+                                     M_out=Md[:, :F_in])
+    close(host(M_g), M_o, "M")
+    close(host(Hn_g), Hn_o, "Hnext")
+    dHn = synth.round_bf16(np.random.default_rng(3).standard_normal((n, F_out)).astype(np.float32))
+    Mb, Hnb = synth.round_bf16(M_o.astype(np.float32)), synth.round_bf16(Hn_o.astype(np.float32))
+    Md[:, :F_in] = dev_bf16(Mb)
+    want = oracle.sage_layer_bwd(rp, ci, H, Mb, Hnb, dHn, Ws, Wn, oracle.ACT_RELU, need_dH=False)
+    got = B.tma_sage_layer_bwd(d_rp, d_ci, d_inv, Hd[:, :F_in], Md[:, :F_in], dev_bf16(Hnb), dev_bf16(dHn), dev(Ws),
+                               dev(Wn), oracle.ACT_RELU, need_dH=False)
+    for g, w, name in zip(got[:3], want[:3], ("dW_self", "dW_neigh", "dbias")):
+        close(host(g), w, name)
+
+
 @pytest.mark.parametrize("n_glob,m,F_in,F_out,act", [(4000, 20_000, 100, 256, "relu"), (3000, 12_000, 256, 47, "none"),
                                                      (1200, 5000, 30, 10, "relu")])
 def test_sage_layer_bf16(B, n_glob, m, F_in, F_out, act):
