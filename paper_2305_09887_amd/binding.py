@@ -13,7 +13,7 @@ import os
 import torch
 
 _PKG = os.path.dirname(os.path.abspath(__file__))
-_LIB_PATH = os.path.join(_PKG, "libtma.so")
+_LIB_PATH = os.environ.get("TMA_LIBRARY_PATH") or os.path.join(_PKG, "libtma.so")   # (a build elsewhere: set TMA_LIBRARY_PATH)
 
 TMA_F32, TMA_BF16 = 0, 1
 TMA_ACT_NONE, TMA_ACT_RELU = 0, 1

@@ -25,6 +25,16 @@ namespace tma {
 
 typedef float floatx16 __attribute__((ext_vector_type(16)));
 
+// Which products keep two slabs in flight in registers (and then run two blocks per compute unit, 256 registers):
+// the ones bound by streaming their operands -- bf16 storage, and the weight gradient whose k runs over the nodes.
+// Measured at n = 125,237 / 2,000,000 rows: bf16 forward 97 -> 79 us / 1.34 -> 1.06 ms, bf16 narrow input gradient
+// 66 -> 48 us, fp32 weight gradient 188 -> 180 us / 2.76 -> 2.53 ms; the fp32 forward and input-gradient products,
+// whose matrix work per slab is four times longer, lose 5 % with it and keep one slab and three blocks.
+template <typename CT, bool kColSum>
+struct DeepPrefetch {
+    static constexpr bool value = sizeof(CT) == 2 || kColSum;
+};
+
 constexpr int kPad = 4;   // LDS row padding in words: keeps 16-byte alignment, spreads banks
 constexpr int kXcds = 8;  // MI355X: 8 accelerator dies, workgroups are dealt round-robin to them
 
@@ -851,12 +861,13 @@ struct TileMath<uint16_t> {
 // gives the compiler a fixed number of stores to count its waits against.
 // ---------------------------------------------------------------------------
 template <typename CT, int BM, int BN, int BK, int WM, int WN, bool kColSum, class AL, class BL, class Epi>
-__global__ __launch_bounds__(WM *WN * 64, (BK * sizeof(CT) <= 64 && !Epi::kRowAux ? 3 : 2)) void gemm_f32_kernel(AL a, BL b, Epi epi, int64_t M, int N, int64_t K,
+__global__ __launch_bounds__(WM *WN * 64, (BK * sizeof(CT) <= 64 && !Epi::kRowAux && !DeepPrefetch<CT, kColSum>::value ? 3 : 2)) void gemm_f32_kernel(AL a, BL b, Epi epi, int64_t M, int N, int64_t K,
                                                                  int64_t k_per_split, int n_tiles,
                                                                  int64_t tiles_per_split, int64_t total_work,
                                                                  float *__restrict__ colsum_partial)
 {
     constexpr int NT = WM * WN * 64;
+    constexpr bool kPrefetch2 = DeepPrefetch<CT, kColSum>::value;
     constexpr int TM = BM / WM / 32;
     constexpr int TN = BN / WN / 32;
     constexpr int A_Q = BM * BK / 4, B_Q = BN * BK / 4;   // 16-byte pieces of a slab
@@ -992,57 +1003,87 @@ __global__ __launch_bounds__(WM *WN * 64, (BK * sizeof(CT) <= 64 && !Epi::kRowAu
         stage(0, afirst, bfirst);
         __syncthreads();
 
-        auto main_loop = [&](auto plain_tag) {
-            constexpr bool kPlain = decltype(plain_tag)::value;
-            typename AL::Raw areg[A_V];
-            typename BL::Raw breg[B_V];
-            int buf = 0;
-            for (int64_t kt = t.k_begin; kt < t.k_end; kt += BK) {
-                const bool more = kt + BK < t.k_end;
-                if (more) {  // in flight while this slab is multiplied
-                    if constexpr (kPlain) fetch_plain(kt + BK, areg, breg);
-                    else fetch(kt + BK, areg, breg);
+        // one slab from LDS buffer `buf`: fragment reads one group ahead of the MFMAs that use them
+        auto multiply = [&](int buf) {
+#if defined(TMA_GEMM_IGLP)
+            __builtin_amdgcn_iglp_opt(TMA_GEMM_IGLP);
+#endif
+            Frag fa[2][TM], fb[2][TN];
+#pragma unroll
+            for (int i = 0; i < TM; ++i) fa[0][i] = frag_a(buf, 0, i);
+#pragma unroll
+            for (int j = 0; j < TN; ++j) fb[0][j] = frag_b(buf, 0, j);
+#pragma unroll
+            for (int g = 0; g < KG; ++g) {
+                const int cur = g & 1, nxt = cur ^ 1;
+                if (g + 1 < KG) {  // next group's fragments are in flight while this group's MFMAs run
+#pragma unroll
+                    for (int i = 0; i < TM; ++i) fa[nxt][i] = frag_a(buf, g + 1, i);
+#pragma unroll
+                    for (int j = 0; j < TN; ++j) fb[nxt][j] = frag_b(buf, g + 1, j);
                 }
-
-                Frag fa[2][TM], fb[2][TN];
+                if constexpr (sizeof(CT) == 4) {   // fp32: the four k-pairs in turn, round-robin over the output tiles
 #pragma unroll
-                for (int i = 0; i < TM; ++i) fa[0][i] = frag_a(buf, 0, i);
-#pragma unroll
-                for (int j = 0; j < TN; ++j) fb[0][j] = frag_b(buf, 0, j);
-#pragma unroll
-                for (int g = 0; g < KG; ++g) {
-                    const int cur = g & 1, nxt = cur ^ 1;
-                    if (g + 1 < KG) {  // next group's fragments are in flight while this group's MFMAs run
-#pragma unroll
-                        for (int i = 0; i < TM; ++i) fa[nxt][i] = frag_a(buf, g + 1, i);
-#pragma unroll
-                        for (int j = 0; j < TN; ++j) fb[nxt][j] = frag_b(buf, g + 1, j);
-                    }
-                    if constexpr (sizeof(CT) == 4) {   // fp32: the four k-pairs in turn, round-robin over the output tiles
-#pragma unroll
-                        for (int q = 0; q < 4; ++q)
-#pragma unroll
-                            for (int i = 0; i < TM; ++i)
-#pragma unroll
-                                for (int j = 0; j < TN; ++j) {
-                                    const float av = q == 0 ? fa[cur][i].x : q == 1 ? fa[cur][i].y : q == 2 ? fa[cur][i].z : fa[cur][i].w;
-                                    const float bv = q == 0 ? fb[cur][j].x : q == 1 ? fb[cur][j].y : q == 2 ? fb[cur][j].z : fb[cur][j].w;
-                                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(av, bv, acc[i][j], 0, 0, 0);
-                                }
-                    } else {
+                    for (int q = 0; q < 4; ++q)
 #pragma unroll
                         for (int i = 0; i < TM; ++i)
 #pragma unroll
-                            for (int j = 0; j < TN; ++j) Math::mma(fa[cur][i], fb[cur][j], acc[i][j]);
-                    }
-                }
-                if (kColSum && t.m0 == 0 && tid < BN) {
+                            for (int j = 0; j < TN; ++j) {
+                                const float av = q == 0 ? fa[cur][i].x : q == 1 ? fa[cur][i].y : q == 2 ? fa[cur][i].z : fa[cur][i].w;
+                                const float bv = q == 0 ? fb[cur][j].x : q == 1 ? fb[cur][j].y : q == 2 ? fb[cur][j].z : fb[cur][j].w;
+                                acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(av, bv, acc[i][j], 0, 0, 0);
+                            }
+                } else {
 #pragma unroll
-                    for (int k = 0; k < BK; ++k) colsum += Math::value(&Bs[buf][k * B_LD + tid]);
+                    for (int i = 0; i < TM; ++i)
+#pragma unroll
+                        for (int j = 0; j < TN; ++j) Math::mma(fa[cur][i], fb[cur][j], acc[i][j]);
                 }
-                if (more) stage(buf ^ 1, areg, breg);  // the other buffer was last read before the previous barrier
-                __syncthreads();
-                buf ^= 1;
+            }
+            if (kColSum && t.m0 == 0 && tid < BN) {
+#pragma unroll
+                for (int k = 0; k < BK; ++k) colsum += Math::value(&Bs[buf][k * B_LD + tid]);
+            }
+        };
+        auto main_loop = [&](auto plain_tag) {
+            constexpr bool kPlain = decltype(plain_tag)::value;
+            if constexpr (kPlain && kPrefetch2) {
+                // Two slabs in flight in registers beside the two in LDS: a slab's loads are issued two iterations
+                // before it is staged.  One iteration's matrix work is far shorter than a memory round trip under
+                // load, so with a single slab in flight every iteration ends up waiting for one.
+                typename AL::Raw areg[2][A_V];
+                typename BL::Raw breg[2][B_V];
+                const int64_t n_slabs = (t.k_end - t.k_begin) / BK;
+                if (n_slabs > 1) fetch_plain(t.k_begin + BK, areg[0], breg[0]);
+                if (n_slabs > 2) fetch_plain(t.k_begin + 2 * BK, areg[1], breg[1]);
+                int buf = 0;
+                auto step = [&](int64_t sl, auto r_tag) {
+                    constexpr int R = decltype(r_tag)::value;
+                    multiply(buf);
+                    if (sl + 1 < n_slabs) stage(buf ^ 1, areg[R], breg[R]);
+                    if (sl + 3 < n_slabs) fetch_plain(t.k_begin + (sl + 3) * BK, areg[R], breg[R]);
+                    __syncthreads();
+                    buf ^= 1;
+                };
+                for (int64_t sl = 0; sl < n_slabs; sl += 2) {
+                    step(sl, std::integral_constant<int, 0>{});
+                    if (sl + 1 < n_slabs) step(sl + 1, std::integral_constant<int, 1>{});
+                }
+            } else {
+                typename AL::Raw areg[A_V];
+                typename BL::Raw breg[B_V];
+                int buf = 0;
+                for (int64_t kt = t.k_begin; kt < t.k_end; kt += BK) {
+                    const bool more = kt + BK < t.k_end;
+                    if (more) {  // in flight while this slab is multiplied
+                        if constexpr (kPlain) fetch_plain(kt + BK, areg, breg);
+                        else fetch(kt + BK, areg, breg);
+                    }
+                    multiply(buf);
+                    if (more) stage(buf ^ 1, areg, breg);  // the other buffer was last read before the previous barrier
+                    __syncthreads();
+                    buf ^= 1;
+                }
             }
         };
         if (views_plain && (t.k_end - t.k_begin) % BK == 0) main_loop(std::true_type{});
@@ -1115,7 +1156,7 @@ static void launch_gemm(const char *name, const AL &a, const BL &b, const Epi &e
     // resident blocks per compute unit follow from the kernel's LDS footprint (160 KB per unit) and its
     // register budget (launch bounds); 256 units in 8 dies
     constexpr int kLdsBytes = 2 * int(sizeof(CT)) * ((AL::kContigK ? BM * (BK + kPad) : BK * (BM + kPad)) + (BL::kContigK ? BN * (BK + kPad) : BK * (BN + kPad)));
-    constexpr int kPerCu = (BK * sizeof(CT) <= 64 && !Epi::kRowAux && kLdsBytes <= 53 * 1024) ? 3 : 2;
+    constexpr int kPerCu = (BK * sizeof(CT) <= 64 && !Epi::kRowAux && kLdsBytes <= 53 * 1024 && !DeepPrefetch<CT, kColSum>::value) ? 3 : 2;
     int64_t blocks_per_die = ceil_div(total, kXcds);
     if (blocks_per_die > 32 * kPerCu) blocks_per_die = 32 * kPerCu;
     TMA_TIMED(name, s);

@@ -558,8 +558,17 @@ static void launch_stream(int64_t n, const int32_t *rowptr, const int32_t *colid
     // rows per group: long enough a stream for the pipeline to pay, short enough to leave the chip
     // several workgroups per compute unit
     const int NG = (kSpmmThreads / kWave) * (kWave / G);
-    int64_t rpg = ceil_div(n, int64_t(NG) * 256 * 6);
-    rpg = rpg < 4 ? 4 : (rpg > 8 ? 8 : rpg);
+#ifndef TMA_SPMM_RPG_MAX
+#define TMA_SPMM_RPG_MAX 16
+#endif
+#ifndef TMA_SPMM_SLOTS
+#define TMA_SPMM_SLOTS (256 * 5)
+#endif
+    // A group's life is (rows + 2) pipeline steps of about one memory latency each, so the launch takes
+    // (rounds of resident blocks) x (rows per group + 2) latencies: as few rounds as possible (one, when the rows
+    // fit), and many rows per group to amortise the pipeline's fill and drain.
+    int64_t rpg = ceil_div(n, int64_t(NG) * TMA_SPMM_SLOTS);
+    rpg = rpg < 4 ? 4 : (rpg > TMA_SPMM_RPG_MAX ? TMA_SPMM_RPG_MAX : rpg);
     if (rpg * NG > kMaxRowsPerBlock) rpg = kMaxRowsPerBlock / NG;
     char name[48];
     snprintf(name, sizeof(name), "%s_%s_g%dx1",
