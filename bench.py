@@ -220,6 +220,9 @@ def main():
                     help="no GPU work: write profiles/hbm_traffic.json and profiles/bench_<KEY>_hbm_traffic.txt from two "
                          "rocprofv3 --pmc runs (FETCH_SIZE, WRITE_SIZE) of this script and the JSON line one of them printed; "
                          "KEY = configs1, configs2_ld100, ...")
+    ap.add_argument("--summarize-kernel-stats", nargs=3, metavar=("KEY", "STATS_DIR", "BENCH_JSON"),
+                    help="no GPU work: write profiles/bench_<KEY>_kernel_stats.txt from a `rocprofv3 --kernel-trace --stats "
+                         "--output-format csv` run of this script and the JSON line it printed")
     ap.add_argument("--calibration-dirs", nargs=2, metavar=("COPY_FETCH_DIR", "COPY_WRITE_DIR"), default=None,
                     help="with --summarize-traffic: counter runs of `bench.py --calibrate-copy` to take the scale factors from")
     ap.add_argument("--profiled-command", default=None,
@@ -227,6 +230,11 @@ def main():
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="only run a plain 1 GiB device copy (reference for scaling rocprofv3 FETCH_SIZE/WRITE_SIZE)")
     args = ap.parse_args()
+    if args.summarize_kernel_stats:
+        from paper_2305_09887_amd import benchlib
+        key, sd, bj = args.summarize_kernel_stats
+        print(benchlib.summarize_kernel_stats(key, sd, bj, args.profiled_command or "bench.py --headline-only --steps 10 --warmup 3 --no-cpu-baseline"))
+        return
     if args.summarize_traffic:
         from paper_2305_09887_amd import benchlib
         key, fd, wd, bj = args.summarize_traffic

@@ -599,3 +599,48 @@ def summarize_traffic(config_key, fetch_dir, write_dir, bench_json, command, cal
                 name, k["fetch_kib"], k["write_kib"], k["bytes"] / 1e6, ("%.1f" % (alg / 1e6)) if alg else "-",
                 ("%.2f" % (k["bytes"] / alg)) if alg else "-", k["symbol"][:110]))
     return table[config_key]
+
+
+def summarize_kernel_stats(config_key, stats_dir, bench_json, command):
+    """Writes profiles/bench_<config_key>_kernel_stats.txt from a `rocprofv3 --kernel-trace --stats --output-format csv`
+    run of bench.py and the JSON line that run printed."""
+    import csv
+    import glob
+    files = glob.glob(os.path.join(stats_dir, "**", "*kernel_stats.csv"), recursive=True)
+    if not files:
+        raise SystemExit(f"no *kernel_stats.csv under {stats_dir}")
+    with open(bench_json) as f:
+        bench = json.loads([l for l in f.read().splitlines() if l.startswith("{")][-1])
+    rows = []
+    with open(files[0]) as f:
+        for r in csv.DictReader(f):
+            rows.append((r["Name"], int(r["Calls"]), float(r["TotalDurationNs"]) / 1e3, float(r["AverageNs"]) / 1e3,
+                         float(r["Percentage"])))
+    rows.sort(key=lambda r: -r[2])
+    dom = bench["roofline"]
+    out = os.path.join(ROOT, "profiles", f"bench_{config_key}_kernel_stats.txt")
+    with open(out, "w") as f:
+        f.write(f"Kernel time per launch, {bench['config']['workload'][:220]}...\n\n")
+        f.write("command (MI355X box, repo root, after `cd /tmp && export TMPDIR=/tmp`):\n")
+        f.write(f"  rocprofv3 --kernel-trace --stats --output-format csv -d <dir> -o b -- python3 {command}\n")
+        f.write(f"  python3 bench.py --summarize-kernel-stats {config_key} <dir> <json line of that command>\n")
+        f.write(f"(the run: {bench['warmup']} warm-up steps, 3 + 2 + 1 steps of the event-profile passes, {bench['steps']} timed steps)\n\n")
+        f.write("%-8s %-12s %-10s %-7s kernel\n" % ("calls", "total_us", "avg_us", "pct"))
+        for name, calls, total, avg, pct in rows:
+            if pct < 0.05:
+                continue
+            f.write("%-8d %-12.1f %-10.2f %-7.2f %s\n" % (calls, total, avg, pct, name.replace("void ", "")[:150]))
+        f.write(f"\nbench.py (the same run, under the profiler): {bench['ms_per_step'] * 1e3:.1f} us per step, value {bench['value']:.4g} {bench['unit']}\n")
+        f.write(f"dominant kernel {dom['kernel']}: bench.py's HIP events give {dom['avg_launch_ms'] * 1e3:.1f} us per launch -> "
+                f"{dom['achieved']} {dom['unit']} = {dom['frac'] * 100:.1f} % of {dom['peak']} ({dom['bound']} bound)\n\n")
+        f.write("per-kernel rates from the event-timed pass of the same run (algorithmic work / time):\n")
+        for k, v in bench["kernel_ms_per_step"].items():
+            r = bench["kernel_rooflines"].get(k)
+            if r:
+                f.write("  %-34s %9.1f us/step  %9.1f %s  (%.1f %% of %s)\n" % (k, v * 1e3, r["achieved"], r["unit"], r["frac"] * 100, r["peak"]))
+            else:
+                f.write("  %-34s %9.1f us/step\n" % (k, v * 1e3))
+        for extra in ("aggregation", "cpu_baseline", "per_layer_fwd_bwd", "two_stream"):
+            if bench.get(extra):
+                f.write(f"\n{extra}: {json.dumps(bench[extra])}\n")
+    return out

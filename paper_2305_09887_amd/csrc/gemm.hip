@@ -127,6 +127,11 @@ int launch_reduce_splits(const float *partial, const float *colsum_partial, int 
     return check_launch("split reduce");
 }
 
+#ifndef TMA_GEMM_WIDE_BF16
+#define TMA_GEMM_WIDE_BF16 1
+#endif
+constexpr bool kWideBf16 = TMA_GEMM_WIDE_BF16 != 0;
+
 // ---- forward ----------------------------------------------------------------
 template <typename T, bool VA, bool VB>
 static void fwd_dispatch(int64_t n, const T *H, int64_t ldh, const T *M, int64_t ldm, int F_in, const float *W_self,
@@ -139,7 +144,13 @@ static void fwd_dispatch(int64_t n, const T *H, int64_t ldh, const T *M, int64_t
     if (F_out <= 64)
         launch_gemm<128, 64, 32, 4, 1, false, T>(kname<T>("gemm_fwd_128x64", "gemm_fwd_128x64_generic", "gemm_fwd_128x64_bf16", "gemm_fwd_128x64_bf16_generic", VA),
                                               a, b, e, n, F_out, K, kps, 1, nullptr, s);
-    else
+    else if constexpr (kWideBf16 && sizeof(T) == 2 && VA) {
+        // bf16 storage: the product is bound by streaming [H | M]; a tile as wide as the output reads it once
+        if (F_out > 128 && F_out <= 256)
+            launch_gemm<128, 256, 32, 2, 4, false, T>("gemm_fwd_128x256_bf16", a, b, e, n, F_out, K, kps, 1, nullptr, s);
+        else
+            launch_gemm<128, 128, 32, 2, 2, false, T>("gemm_fwd_128x128_bf16", a, b, e, n, F_out, K, kps, 1, nullptr, s);
+    } else
         launch_gemm<128, 128, (sizeof(T) == 2 ? 32 : 16), 2, 2, false, T>(kname<T>("gemm_fwd_128x128", "gemm_fwd_128x128_generic", "gemm_fwd_128x128_bf16", "gemm_fwd_128x128_bf16_generic", VA),
                                                a, b, e, n, F_out, K, kps, 1, nullptr, s);
 }
@@ -233,13 +244,27 @@ int launch_sage_gemm_bwd_data(int64_t n, const void *dHnext, const void *Hnext, 
 
 // ---- backward: weights ------------------------------------------------------
 
-static WeightSplit plan_weight_split(int64_t n, int32_t F_in, int32_t F_out)
+// wide: 256 x 256 tiles (bf16 storage with F_out > 128: the product is bound by streaming its two operands, which
+// 128 x 128 tiles read two and four times: 54 GB instead of 16 GB per launch on a 12.5 M-row part); fewer tiles then
+// need more splits to fill the chip, capped so that the partial results stay under a quarter of the operands'
+// bytes.  Below some 4e5 rows that cap leaves too few work items and the narrow tiles are faster (95 vs 109 us at
+// 125 k rows), above it the wide ones are (2 M rows: 1.17 -> 0.73 ms for 128 -> 256, 2.47 -> 1.42 ms for 256 -> 256).
+static bool wide_weight_tiles(int64_t n, int32_t F_in, int32_t F_out, int elem_bytes)
 {
-    const int bn = F_out <= 64 ? 64 : 128;
-    const int64_t tiles = ceil_div(2 * int64_t(F_in), 128) * ceil_div(F_out, bn);
+    return kWideBf16 && elem_bytes == 2 && F_out > 128 && F_out <= 256 && F_in >= 128 && n >= 400000;
+}
+
+static WeightSplit plan_weight_split(int64_t n, int32_t F_in, int32_t F_out, bool wide = false)
+{
+    const int bn = wide ? 256 : (F_out <= 64 ? 64 : 128);
+    const int64_t tiles = ceil_div(2 * int64_t(F_in), wide ? 256 : 128) * ceil_div(F_out, bn);
     int64_t want = ceil_div(512, tiles > 0 ? tiles : 1);
     const int64_t max_useful = ceil_div(n > 0 ? n : 1, 128);
     if (want > max_useful) want = max_useful;
+    if (wide) {
+        const int64_t cap = (n > 0 ? n : 1) * (2 * int64_t(F_in) + F_out) * 2 / 4 / (2 * int64_t(F_in) * F_out * 4);
+        if (want > cap) want = cap;
+    }
     if (want < 1) want = 1;
     WeightSplit w;
     w.k_per_split = int64_t(round_up(size_t(ceil_div(n > 0 ? n : 1, want)), 32));
@@ -252,7 +277,12 @@ static WeightSplit plan_weight_split(int64_t n, int32_t F_in, int32_t F_out)
 size_t sage_gemm_bwd_weight_workspace_bytes(int64_t n, int32_t F_in, int32_t F_out)
 {
     const WeightSplit w = plan_weight_split(n, F_in, F_out);
-    return w.partial_bytes + w.colsum_bytes;
+    size_t bytes = w.partial_bytes + w.colsum_bytes;
+    if (wide_weight_tiles(n, F_in, F_out, 2)) {   // the query does not know the storage type: room for either plan
+        const WeightSplit v = plan_weight_split(n, F_in, F_out, true);
+        if (v.partial_bytes + v.colsum_bytes > bytes) bytes = v.partial_bytes + v.colsum_bytes;
+    }
+    return bytes;
 }
 
 template <typename T, bool VA, bool VB, bool kRelu>
@@ -267,7 +297,14 @@ static void bwd_weight_dispatch(int64_t n, const T *H, int64_t ldh, const T *M, 
     if (F_out <= 64)
         launch_gemm<128, 64, 32, 4, 1, true, T>(kname<T>("gemm_bwd_weight_128x64", "gemm_bwd_weight_128x64_generic", "gemm_bwd_weight_128x64_bf16", "gemm_bwd_weight_128x64_bf16_generic", V),
                                              a, b, e, Mtot, F_out, n, w.k_per_split, w.n_splits, colsum, s);
-    else
+    else if constexpr (kWideBf16 && sizeof(T) == 2 && V) {
+        if (wide_weight_tiles(n, F_in, F_out, 2))
+            launch_gemm<256, 256, 32, 4, 2, true, T>("gemm_bwd_weight_256x256_bf16", a, b, e, Mtot, F_out, n, w.k_per_split,
+                                                     w.n_splits, colsum, s);
+        else
+            launch_gemm<128, 128, 32, 2, 2, true, T>("gemm_bwd_weight_128x128_bf16", a, b, e, Mtot, F_out, n, w.k_per_split,
+                                                     w.n_splits, colsum, s);
+    } else
         launch_gemm<128, 128, (sizeof(T) == 2 ? 32 : 16), 2, 2, true, T>(kname<T>("gemm_bwd_weight_128x128", "gemm_bwd_weight_128x128_generic", "gemm_bwd_weight_128x128_bf16", "gemm_bwd_weight_128x128_bf16_generic", V),
                                               a, b, e, Mtot, F_out, n, w.k_per_split, w.n_splits, colsum, s);
 }
@@ -298,7 +335,12 @@ int launch_sage_gemm_bwd_weight(int64_t n, const void *H, int64_t ldh, const voi
 {
     if (dtype != TMA_F32 && dtype != TMA_BF16) return fail(TMA_ERR_UNSUPPORTED_DTYPE, "sage gemm bwd: dtype %d", dtype);
     if (F_out == 0) return TMA_OK;
-    const WeightSplit w = plan_weight_split(n, F_in, F_out);
+    const bool relu_ = act == TMA_ACT_RELU;
+    const bool all_vec = dtype == TMA_BF16 && vec4_ok(static_cast<const uint16_t *>(H), ldh) &&
+                         vec4_ok(static_cast<const uint16_t *>(M), ldm) && F_in % 4 == 0 &&
+                         vec4_ok(static_cast<const uint16_t *>(dHnext), ld_next) &&
+                         (!relu_ || vec4_ok(static_cast<const uint16_t *>(Hnext), ld_next));
+    const WeightSplit w = plan_weight_split(n, F_in, F_out, all_vec && wide_weight_tiles(n, F_in, F_out, 2));
     if (ws_bytes < w.partial_bytes + w.colsum_bytes)
         return fail(TMA_ERR_WORKSPACE_TOO_SMALL, "sage gemm bwd weight: workspace %zu < %zu", ws_bytes,
                     w.partial_bytes + w.colsum_bytes);

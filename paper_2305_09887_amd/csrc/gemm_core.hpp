@@ -29,10 +29,11 @@ typedef float floatx16 __attribute__((ext_vector_type(16)));
 // the ones bound by streaming their operands -- bf16 storage, and the weight gradient whose k runs over the nodes.
 // Measured at n = 125,237 / 2,000,000 rows: bf16 forward 97 -> 79 us / 1.34 -> 1.06 ms, bf16 narrow input gradient
 // 66 -> 48 us, fp32 weight gradient 188 -> 180 us / 2.76 -> 2.53 ms; the fp32 forward and input-gradient products,
-// whose matrix work per slab is four times longer, lose 5 % with it and keep one slab and three blocks.
-template <typename CT, bool kColSum>
+// whose matrix work per slab is four times longer, lose 5 % with it and keep one slab and three blocks; so does the
+// bf16 input-gradient product of the aggregate-first form (169 -> 190 us), which already runs two blocks per unit.
+template <typename CT, bool kColSum, bool kRowAux = false>
 struct DeepPrefetch {
-    static constexpr bool value = sizeof(CT) == 2 || kColSum;
+    static constexpr bool value = (sizeof(CT) == 2 && !kRowAux) || kColSum;
 };
 
 constexpr int kPad = 4;   // LDS row padding in words: keeps 16-byte alignment, spreads banks
@@ -861,13 +862,13 @@ struct TileMath<uint16_t> {
 // gives the compiler a fixed number of stores to count its waits against.
 // ---------------------------------------------------------------------------
 template <typename CT, int BM, int BN, int BK, int WM, int WN, bool kColSum, class AL, class BL, class Epi>
-__global__ __launch_bounds__(WM *WN * 64, (BK * sizeof(CT) <= 64 && !Epi::kRowAux && !DeepPrefetch<CT, kColSum>::value ? 3 : 2)) void gemm_f32_kernel(AL a, BL b, Epi epi, int64_t M, int N, int64_t K,
+__global__ __launch_bounds__(WM *WN * 64, (BK * sizeof(CT) <= 64 && !Epi::kRowAux && !DeepPrefetch<CT, kColSum, Epi::kRowAux>::value ? 3 : 2)) void gemm_f32_kernel(AL a, BL b, Epi epi, int64_t M, int N, int64_t K,
                                                                  int64_t k_per_split, int n_tiles,
                                                                  int64_t tiles_per_split, int64_t total_work,
                                                                  float *__restrict__ colsum_partial)
 {
     constexpr int NT = WM * WN * 64;
-    constexpr bool kPrefetch2 = DeepPrefetch<CT, kColSum>::value;
+    constexpr bool kPrefetch2 = DeepPrefetch<CT, kColSum, Epi::kRowAux>::value && (BM / WM / 32) * (BN / WN / 32) <= 4;   // (8 accumulator tiles leave no registers for it)
     constexpr int TM = BM / WM / 32;
     constexpr int TN = BN / WN / 32;
     constexpr int A_Q = BM * BK / 4, B_Q = BN * BK / 4;   // 16-byte pieces of a slab
@@ -1156,7 +1157,12 @@ static void launch_gemm(const char *name, const AL &a, const BL &b, const Epi &e
     // resident blocks per compute unit follow from the kernel's LDS footprint (160 KB per unit) and its
     // register budget (launch bounds); 256 units in 8 dies
     constexpr int kLdsBytes = 2 * int(sizeof(CT)) * ((AL::kContigK ? BM * (BK + kPad) : BK * (BM + kPad)) + (BL::kContigK ? BN * (BK + kPad) : BK * (BN + kPad)));
-    constexpr int kPerCu = (BK * sizeof(CT) <= 64 && !Epi::kRowAux && kLdsBytes <= 53 * 1024 && !DeepPrefetch<CT, kColSum>::value) ? 3 : 2;
+    // the launch bound's second number is waves per SIMD: 3 or 2, i.e. that many blocks of four wavefronts per compute
+    // unit, half as many (at least one) of eight
+    constexpr int kWavesPerSimd = (BK * sizeof(CT) <= 64 && !Epi::kRowAux && kLdsBytes <= 53 * 1024 && !DeepPrefetch<CT, kColSum, Epi::kRowAux>::value) ? 3 : 2;
+    constexpr int kByWaves = kWavesPerSimd * 4 / (WM * WN) > 0 ? kWavesPerSimd * 4 / (WM * WN) : 1;
+    constexpr int kByLds = 160 * 1024 / kLdsBytes > 0 ? 160 * 1024 / kLdsBytes : 1;
+    constexpr int kPerCu = kByWaves < kByLds ? kByWaves : kByLds;
     int64_t blocks_per_die = ceil_div(total, kXcds);
     if (blocks_per_die > 32 * kPerCu) blocks_per_die = 32 * kPerCu;
     TMA_TIMED(name, s);
