@@ -208,6 +208,13 @@ def main():
                     help="positive edges per step of the link tasks (default 65536; 1024 for link-sampled)")
     ap.add_argument("--fanouts", default="10,25",
                     help="link-sampled: neighbours kept per node, first layer first (the layer next to the batch last)")
+    ap.add_argument("--extract", choices=("async", "sync"), default="async",
+                    help="async (default): the step enqueues the extraction over capacity-sized buffers and never waits for "
+                         "the GPU (the sizes, known from the set-up pass, are checked on the device values after the timed "
+                         "region); sync: the two-pass extraction that returns the sizes to the host in every step")
+    ap.add_argument("--graph", action="store_true",
+                    help="beside the headline: capture one whole step (assignment, extraction, row gathers, training pass, "
+                         "averaging) as a HIP graph and time its replays (node task, SGD)")
     ap.add_argument("--config", type=int, choices=(0, 1, 2, 3, 4), default=1,
                     help="which of the configured workloads: 1 = the headline (default); 0 = the tiny case; 2 = SuperTMA at "
                          "full size; 3 = one trainer's share at billion-edge scale; 4 = 8 trainers on 8 streams with "
@@ -348,10 +355,17 @@ def main():
     two_stream = SubgraphPrefetcher(d_rowptr, d_colidx, N, K, p, cap, cap_nnz, tables=(d_X,) if sampled else (d_X, d_y))
     state = {"next": None, "trained": None}
 
+    held = B.tma_induced_subgraph_async(d_rowptr, d_colidx, part, p, cap, cap_nnz) if args.extract == "async" else None
+
     def step(prefetch=two_stream if args.prefetch else None):
         if prefetch is None:
             B.tma_partition(N, K, sd["part"], out=part)
-            s = B.tma_induced_subgraph(d_rowptr, d_colidx, part, p, cap_n_loc=cap, cap_nnz_loc=cap_nnz)
+            if held is not None:      # same buffers every step; views at the sizes the set-up pass reported
+                B.tma_induced_subgraph_async(d_rowptr, d_colidx, part, p, cap, cap_nnz, out=held)
+                s = dict(l2g=held["l2g"][:n_loc], rowptr=held["rowptr"][:n_loc + 1], colidx=held["colidx"][:nnz_loc],
+                         inv_deg=held["inv_deg"][:n_loc], nnz_loc=nnz_loc)
+            else:
+                s = B.tma_induced_subgraph(d_rowptr, d_colidx, part, p, cap_n_loc=cap, cap_nnz_loc=cap_nnz)
         else:
             if state["next"] is None:
                 state["next"] = prefetch.start(sd["part"])
@@ -404,6 +418,32 @@ def main():
     dom = B.tma_profile_end().get(dominant, (0, 0.0))
     ms_per_step = elapsed * 1e3 / args.steps
     loss = float(tr.loss.item())
+    if held is not None and held["sizes"].cpu().tolist() != [n_loc, nnz_loc]:
+        sys.exit(f"bench.py: the extraction reported sizes {held['sizes'].cpu().tolist()}, expected {[n_loc, nnz_loc]}")
+
+    # beside the headline: the same step captured once as a HIP graph and replayed (no launch gaps, no host work)
+    graph_leg = None
+    if args.graph:
+        if args.task != "node" or held is None or args.prefetch:
+            sys.exit("bench.py: --graph captures the node task's step with --extract async and without --prefetch")
+        gs = torch.cuda.Stream()
+        gs.wait_stream(torch.cuda.current_stream())
+        tr.stream = gs
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph, stream=gs):
+            step()
+        for _ in range(max(args.warmup, 2)):
+            graph.replay()
+        torch.cuda.synchronize()
+        t_start = time.perf_counter()
+        for _ in range(args.steps):
+            graph.replay()
+        torch.cuda.synchronize()
+        graph_ms = (time.perf_counter() - t_start) * 1e3 / args.steps
+        tr.stream = torch.cuda.current_stream()
+        graph_leg = {"ms_per_step": round(graph_ms, 4), "eager_ms_per_step": round(ms_per_step, 4),
+                     "saved_ms_per_step": round(ms_per_step - graph_ms, 4), "steps": args.steps,
+                     "loss_after": float(tr.loss.item())}
 
     # beside the headline: every encoder layer's forward and backward bracketed by events, median over 20 more steps
     per_layer = None
@@ -530,6 +570,9 @@ def main():
     }
     if per_layer is not None:
         out["per_layer_fwd_bwd"] = per_layer      # edges_per_s = nnz_loc / (fwd + bwd) of that layer alone
+    out["config"]["extract"] = args.extract
+    if graph_leg is not None:
+        out["hip_graph"] = graph_leg
     if two_stream_ms is not None:
         out["two_stream"] = {"ms_per_step": round(two_stream_ms, 4), "value": round(value * ms_per_step / two_stream_ms, 1),
                              "unit": "edges/s", "steps": args.steps, "attempts_ms": two_stream_tries,

@@ -124,6 +124,26 @@ int tma_induced_subgraph(int64_t n_nodes, const int64_t *rowptr, const int32_t *
                          int64_t *h_n_loc, int64_t *h_nnz_loc,
                          void *ws, size_t ws_bytes, tma_stream_t stream);
 
+/* The same extraction with no host wait, for callers that keep the sizes on
+ * the device (a step replayed as a HIP graph, a loop that never blocks): both
+ * passes are enqueued over as many rows as the capacity allows and the second
+ * pass reads the node count from device memory.  d_sizes_out [2] int64
+ * (device) receives |V^(p)| and the kept entries of the first
+ * min(|V^(p)|, cap_n_loc) rows; the caller reads it when it wants to (e.g. an
+ * asynchronous copy) and must check both against its capacities: rows past
+ * cap_n_loc are dropped, and a row whose entries would end past cap_nnz_loc
+ * gets its inv_deg but no entries -- nothing is ever written out of bounds.
+ * Within the capacities all five outputs equal those of
+ * tma_induced_subgraph bit for bit; elements past the actual sizes are left
+ * untouched.  Same workspace as above.  Nothing here clears memory with a
+ * memset, so the call may be captured into a graph. */
+int tma_induced_subgraph_async(int64_t n_nodes, const int64_t *rowptr, const int32_t *colidx,
+                               const int32_t *part, int32_t p,
+                               int32_t *g2l_out, int32_t *l2g_out, int32_t *rowptr_loc_out,
+                               int32_t *colidx_loc_out, float *inv_deg_out,
+                               int64_t cap_n_loc, int64_t cap_nnz_loc, int64_t *d_sizes_out,
+                               void *ws, size_t ws_bytes, tma_stream_t stream);
+
 int tma_induced_subgraph_fill(int64_t n_nodes, const int32_t *colidx,
                               const int32_t *g2l, int64_t n_loc, const int32_t *rowptr_loc,
                               int32_t *colidx_loc_out, float *inv_deg_out,

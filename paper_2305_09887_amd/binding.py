@@ -21,7 +21,7 @@ TMA_ACT_NONE, TMA_ACT_RELU = 0, 1
 EXPORTS = (
     "tma_version", "tma_last_error", "tma_partition", "tma_mix64",
     "tma_induced_subgraph_workspace_bytes", "tma_induced_subgraph_count", "tma_induced_subgraph_fill",
-    "tma_induced_subgraph",
+    "tma_induced_subgraph", "tma_induced_subgraph_async",
     "tma_mean_aggregate", "tma_sage_layer_aggregates_first", "tma_sage_layer_fwd",
     "tma_sage_layer_bwd_workspace_bytes", "tma_sage_layer_bwd",
     "tma_layernorm_prelu_fwd", "tma_layernorm_prelu_bwd_workspace_bytes", "tma_layernorm_prelu_bwd",
@@ -198,6 +198,37 @@ def tma_induced_subgraph(rowptr, colidx, part, p: int, cap_n_loc: int | None = N
             _ptr(ws), C.c_size_t(ws.numel()), _stream(stream)))
     return dict(g2l=g2l[:n], l2g=l2g[:n_loc], rowptr=rp[:n_loc + 1], colidx=ci[:nnz_loc], inv_deg=inv[:n_loc],
                 n_loc=n_loc, nnz_loc=nnz_loc)
+
+
+def tma_induced_subgraph_async(rowptr, colidx, part, p: int, cap_n_loc: int, cap_nnz_loc: int, out=None, stream=None):
+    """The extraction without a host wait.  Returns dict(g2l, l2g, rowptr, colidx, inv_deg, sizes, ws): the buffers
+    at their capacities and sizes = device int64 [|V^(p)|, kept entries].  Pass a previous result as `out` to
+    write into the same buffers again (fixed addresses, as a captured graph needs)."""
+    n = rowptr.numel() - 1
+    if part.numel() != n:
+        raise TmaError("tma_induced_subgraph_async: part must have one entry per node")
+    dev = rowptr.device
+    if colidx.numel() == 0:
+        colidx = torch.zeros(1, dtype=torch.int32, device=dev)
+    cap, cap_nnz = min(int(cap_n_loc), n), int(cap_nnz_loc)
+    L = lib()
+    ws_bytes = L.tma_induced_subgraph_workspace_bytes(C.c_int64(n), C.c_int64(cap))
+    if out is None:
+        i32 = lambda k: torch.empty(max(k, 1), dtype=torch.int32, device=dev)
+        out = dict(g2l=i32(n), l2g=i32(cap), rowptr=i32(cap + 1), colidx=i32(cap_nnz),
+                   inv_deg=torch.empty(max(cap, 1), dtype=torch.float32, device=dev),
+                   sizes=torch.zeros(2, dtype=torch.int64, device=dev),
+                   ws=torch.empty(max(ws_bytes, 256), dtype=torch.uint8, device=dev))
+    if (out["g2l"].numel() < n or out["l2g"].numel() < cap or out["rowptr"].numel() < cap + 1
+            or out["colidx"].numel() < cap_nnz or out["inv_deg"].numel() < cap or out["ws"].numel() < ws_bytes):
+        raise TmaError("tma_induced_subgraph_async: `out` holds buffers below the capacities")
+    _check(L.tma_induced_subgraph_async(
+        C.c_int64(n), _ptr(rowptr, torch.int64, "rowptr"), _ptr(colidx, torch.int32, "colidx"),
+        _ptr(part, torch.int32, "part"), C.c_int32(p), _ptr(out["g2l"], torch.int32), _ptr(out["l2g"], torch.int32),
+        _ptr(out["rowptr"], torch.int32), _ptr(out["colidx"], torch.int32), _ptr(out["inv_deg"], torch.float32),
+        C.c_int64(cap), C.c_int64(cap_nnz), _ptr(out["sizes"], torch.int64), _ptr(out["ws"]),
+        C.c_size_t(out["ws"].numel()), _stream(stream)))
+    return out
 
 
 def tma_mean_aggregate(rowptr, colidx, inv_deg, H, out=None, stream=None):

@@ -314,7 +314,10 @@ __global__ __launch_bounds__(256) void row_count_kernel(const int64_t *d_n_loc, 
 }
 
 // Order-preserving compaction of each local row into colidx_loc, relabelled.
-__global__ __launch_bounds__(256) void row_fill_kernel(int64_t n_loc, const int64_t *__restrict__ row_beg,
+// n_loc rows at most; with d_n_loc the actual count is read from the device (a launch sized by capacity).  A row
+// whose entries would end past cap_nnz is skipped: the caller's buffer is then too small and the sizes say so.
+__global__ __launch_bounds__(256) void row_fill_kernel(int64_t n_loc, const int64_t *__restrict__ d_n_loc,
+                                                       int64_t cap_nnz, const int64_t *__restrict__ row_beg,
                                                        const int32_t *__restrict__ row_len,
                                                        const int32_t *__restrict__ colidx,
                                                        const uint32_t *__restrict__ member,
@@ -329,6 +332,10 @@ __global__ __launch_bounds__(256) void row_fill_kernel(int64_t n_loc, const int6
     if (threadIdx.x == 0) hub_count = 0;
     __syncthreads();
 
+    if (d_n_loc) {
+        const int64_t actual = *d_n_loc;
+        n_loc = actual < n_loc ? actual : n_loc;
+    }
     const int sub = threadIdx.x % kRowLanes;
     const int group_shift = ((threadIdx.x % kWave) / kRowLanes) * kRowLanes;
     const int64_t row0 = int64_t(blockIdx.x) * kRowsPerBlock;
@@ -340,10 +347,12 @@ __global__ __launch_bounds__(256) void row_fill_kernel(int64_t n_loc, const int6
         beg = row_beg[i];
         len = row_len[i];
         out = rowptr_loc[i];
+        const int32_t end = rowptr_loc[i + 1];
         if (sub == 0) {
-            const int32_t d = rowptr_loc[i + 1] - out;
+            const int32_t d = end - out;
             inv_deg[i] = d > 0 ? 1.0f / float(d) : 0.0f;
         }
+        if (int64_t(end) > cap_nnz) len = 0;
         if (len > kHubRow) {  // left to the whole workgroup below
             if (sub == 0) hub_rows[atomicAdd(&hub_count, 1)] = int32_t(i - row0);
             len = 0;
@@ -503,18 +512,18 @@ extern "C" size_t tma_induced_subgraph_workspace_bytes(int64_t n_nodes, int64_t 
     return tma::carve(nullptr, n_nodes, cap_n_loc).bytes;
 }
 
-extern "C" int tma_induced_subgraph_count(int64_t n_nodes, const int64_t *rowptr, const int32_t *colidx,
-                                          const int32_t *part, int32_t p, int32_t *g2l_out, int32_t *l2g_out,
-                                          int32_t *rowptr_loc_out, int64_t cap_n_loc, int64_t *h_n_loc,
-                                          int64_t *h_nnz_loc, void *ws, size_t ws_bytes, tma_stream_t stream)
+namespace tma {
+
+// The counting pass, enqueued on the stream: flags, node ranks, kept degrees, rowptr_loc.  The two totals
+// (|V^(p)|, kept entries) end up in sizes[0..1] (device memory); nothing here waits for the GPU.
+static int enqueue_count(const char *fn, int64_t n_nodes, const int64_t *rowptr, const int32_t *colidx,
+                         const int32_t *part, int32_t p, int32_t *g2l_out, int32_t *l2g_out, int32_t *rowptr_loc_out,
+                         int64_t cap_n_loc, int64_t *sizes, void *ws, size_t ws_bytes, hipStream_t s)
 {
-    using namespace tma;
-    const char *fn = "tma_induced_subgraph_count";
     TMA_REQUIRE(n_nodes >= 0 && n_nodes <= INT32_MAX, TMA_ERR_INVALID_ARG, "%s: n_nodes outside [0, 2^31)", fn);
     TMA_REQUIRE(cap_n_loc >= 0 && cap_n_loc <= n_nodes, TMA_ERR_INVALID_ARG,
                 "%s: cap_n_loc must lie in [0, n_nodes]", fn);
-    TMA_REQUIRE(h_n_loc && h_nnz_loc && rowptr_loc_out, TMA_ERR_INVALID_ARG,
-                "%s: h_n_loc / h_nnz_loc / rowptr_loc_out is NULL", fn);
+    TMA_REQUIRE(rowptr_loc_out, TMA_ERR_INVALID_ARG, "%s: rowptr_loc_out is NULL", fn);
     TMA_REQUIRE(n_nodes == 0 || (rowptr && part && g2l_out), TMA_ERR_INVALID_ARG,
                 "%s: rowptr / part / g2l_out is NULL", fn);
     TMA_REQUIRE(cap_n_loc == 0 || l2g_out, TMA_ERR_INVALID_ARG, "%s: l2g_out is NULL", fn);
@@ -522,7 +531,7 @@ extern "C" int tma_induced_subgraph_count(int64_t n_nodes, const int64_t *rowptr
     CountWorkspace w = carve(ws, n_nodes, cap_n_loc);
     TMA_REQUIRE(ws_bytes >= w.bytes, TMA_ERR_WORKSPACE_TOO_SMALL, "%s: workspace %zu < %zu bytes", fn, ws_bytes,
                 w.bytes);
-    hipStream_t s = as_stream(stream);
+    if (!sizes) sizes = w.sizes;
 
     const unsigned nb_nodes = unsigned(ceil_div(n_nodes > 0 ? n_nodes : 1, kScanTile));
     const unsigned nb_rows = unsigned(ceil_div(cap_n_loc > 0 ? cap_n_loc : 1, kScanTile));
@@ -537,7 +546,7 @@ extern "C" int tma_induced_subgraph_count(int64_t n_nodes, const int64_t *rowptr
     {
         TMA_TIMED("scan_sums", s);
         hipLaunchKernelGGL(scan_sums_kernel, dim3(1), dim3(1024), 0, s, int64_t(nb_nodes), w.node_block_sums,
-                           w.sizes + 0, rowptr_loc_out);
+                           sizes + 0, rowptr_loc_out);
     }
     {
         TMA_TIMED("scan_apply_flags", s);
@@ -548,27 +557,44 @@ extern "C" int tma_induced_subgraph_count(int64_t n_nodes, const int64_t *rowptr
     if (cap_n_loc > 0) {
         const unsigned row_blocks = unsigned(ceil_div(cap_n_loc, kRowsPerBlock));
         TMA_TIMED("row_count", s);
-        hipLaunchKernelGGL(row_count_kernel, dim3(row_blocks), dim3(256), 0, s, w.sizes + 0, cap_n_loc, w.row_beg,
+        hipLaunchKernelGGL(row_count_kernel, dim3(row_blocks), dim3(256), 0, s, sizes + 0, cap_n_loc, w.row_beg,
                            w.row_len, colidx, w.member, w.deg);
     }
     DegIn din{w.deg};
     DegOut dout{rowptr_loc_out};
     {
         TMA_TIMED("scan_reduce_deg", s);
-        hipLaunchKernelGGL(scan_reduce_kernel<DegIn>, dim3(nb_rows), dim3(kScanThreads), 0, s, w.sizes + 0,
+        hipLaunchKernelGGL(scan_reduce_kernel<DegIn>, dim3(nb_rows), dim3(kScanThreads), 0, s, sizes + 0,
                            cap_n_loc, din, w.row_block_sums);
     }
     {
         TMA_TIMED("scan_sums", s);
         hipLaunchKernelGGL(scan_sums_kernel, dim3(1), dim3(1024), 0, s, int64_t(nb_rows), w.row_block_sums,
-                           w.sizes + 1, static_cast<int32_t *>(nullptr));
+                           sizes + 1, static_cast<int32_t *>(nullptr));
     }
     {
         TMA_TIMED("scan_apply_deg", s);
-        hipLaunchKernelGGL((scan_apply_kernel<DegIn, DegOut>), dim3(nb_rows), dim3(kScanThreads), 0, s, w.sizes + 0,
+        hipLaunchKernelGGL((scan_apply_kernel<DegIn, DegOut>), dim3(nb_rows), dim3(kScanThreads), 0, s, sizes + 0,
                            cap_n_loc, din, dout, w.row_block_sums);
     }
-    if (int rc = check_launch(fn)) return rc;
+    return check_launch(fn);
+}
+
+}  // namespace tma
+
+extern "C" int tma_induced_subgraph_count(int64_t n_nodes, const int64_t *rowptr, const int32_t *colidx,
+                                          const int32_t *part, int32_t p, int32_t *g2l_out, int32_t *l2g_out,
+                                          int32_t *rowptr_loc_out, int64_t cap_n_loc, int64_t *h_n_loc,
+                                          int64_t *h_nnz_loc, void *ws, size_t ws_bytes, tma_stream_t stream)
+{
+    using namespace tma;
+    const char *fn = "tma_induced_subgraph_count";
+    TMA_REQUIRE(h_n_loc && h_nnz_loc, TMA_ERR_INVALID_ARG, "%s: h_n_loc / h_nnz_loc is NULL", fn);
+    hipStream_t s = as_stream(stream);
+    if (int rc = enqueue_count(fn, n_nodes, rowptr, colidx, part, p, g2l_out, l2g_out, rowptr_loc_out, cap_n_loc,
+                               nullptr, ws, ws_bytes, s))
+        return rc;
+    const CountWorkspace w = carve(ws, n_nodes, cap_n_loc);
 
     int64_t h_sizes[2] = {0, 0};
     // copy in stream order and wait for it (one call: measurably shorter than an asynchronous copy
@@ -603,7 +629,8 @@ extern "C" int tma_induced_subgraph_fill(int64_t n_nodes, const int32_t *colidx,
     TMA_REQUIRE(colidx && colidx_loc_out, TMA_ERR_INVALID_ARG, "%s: colidx / colidx_loc_out is NULL", fn);
     const unsigned blocks = unsigned(ceil_div(n_loc, kRowsPerBlock));
     TMA_TIMED("row_fill", as_stream(stream));
-    hipLaunchKernelGGL(row_fill_kernel, dim3(blocks), dim3(256), 0, as_stream(stream), n_loc, w.row_beg, w.row_len,
+    hipLaunchKernelGGL(row_fill_kernel, dim3(blocks), dim3(256), 0, as_stream(stream), n_loc,
+                       static_cast<const int64_t *>(nullptr), int64_t(INT64_MAX), w.row_beg, w.row_len,
                        colidx, w.member, g2l, rowptr_loc, colidx_loc_out, inv_deg_out);
     return check_launch(fn);
 }
@@ -625,4 +652,31 @@ extern "C" int tma_induced_subgraph(int64_t n_nodes, const int64_t *rowptr, cons
                 (long long)cap_nnz_loc);
     return tma_induced_subgraph_fill(n_nodes, colidx, g2l_out, *h_n_loc, rowptr_loc_out, colidx_loc_out, inv_deg_out,
                                      cap_n_loc, ws, ws_bytes, stream);
+}
+
+extern "C" int tma_induced_subgraph_async(int64_t n_nodes, const int64_t *rowptr, const int32_t *colidx,
+                                          const int32_t *part, int32_t p, int32_t *g2l_out, int32_t *l2g_out,
+                                          int32_t *rowptr_loc_out, int32_t *colidx_loc_out, float *inv_deg_out,
+                                          int64_t cap_n_loc, int64_t cap_nnz_loc, int64_t *d_sizes_out, void *ws,
+                                          size_t ws_bytes, tma_stream_t stream)
+{
+    using namespace tma;
+    const char *fn = "tma_induced_subgraph_async";
+    TMA_REQUIRE(cap_nnz_loc >= 0 && cap_nnz_loc <= INT32_MAX, TMA_ERR_INVALID_ARG, "%s: cap_nnz_loc outside [0, 2^31)", fn);
+    TMA_REQUIRE(d_sizes_out, TMA_ERR_INVALID_ARG, "%s: d_sizes_out is NULL", fn);
+    TMA_REQUIRE(cap_n_loc == 0 || (colidx && colidx_loc_out && inv_deg_out), TMA_ERR_INVALID_ARG,
+                "%s: colidx / colidx_loc_out / inv_deg_out is NULL", fn);
+    hipStream_t s = as_stream(stream);
+    if (int rc = enqueue_count(fn, n_nodes, rowptr, colidx, part, p, g2l_out, l2g_out, rowptr_loc_out, cap_n_loc,
+                               d_sizes_out, ws, ws_bytes, s))
+        return rc;
+    if (cap_n_loc == 0) return TMA_OK;
+    const CountWorkspace w = carve(ws, n_nodes, cap_n_loc);
+    // the second pass over as many rows as the capacity allows; the kernel reads the actual count
+    const unsigned blocks = unsigned(ceil_div(cap_n_loc, kRowsPerBlock));
+    TMA_TIMED("row_fill", s);
+    hipLaunchKernelGGL(row_fill_kernel, dim3(blocks), dim3(256), 0, s, cap_n_loc,
+                       static_cast<const int64_t *>(d_sizes_out), cap_nnz_loc, w.row_beg, w.row_len, colidx, w.member,
+                       g2l_out, rowptr_loc_out, colidx_loc_out, inv_deg_out);
+    return check_launch(fn);
 }

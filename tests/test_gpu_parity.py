@@ -170,6 +170,65 @@ def test_subgraph_single_call_with_capacities(B):
     torch.cuda.synchronize()
 
 
+def test_subgraph_without_host_wait(B):
+    """The extraction that keeps its sizes on the device: bit-exact against the oracle within the capacities
+    (hub rows, exact and generous capacities, the same buffers written twice, an empty part), elements past the
+    actual sizes untouched; beyond the capacities the sizes still arrive and nothing is written out of bounds."""
+    rowptr, colidx = synth.chung_lu_graph(150_000, 20, 2.1, seed=11)
+    part = oracle.partition(150_000, 8, seed=14)
+    d = dev(rowptr), dev(colidx), dev(part)
+    sizes_of = {p: (int((part == p).sum()), None) for p in (0, 3, 5)}
+    generous = (max(v[0] for v in sizes_of.values()) + 5000, int(rowptr[-1]) // 32)
+    out = None
+    for p, reuse in ((3, False), (0, False), (5, True)):
+        want = oracle.induced_subgraph(rowptr, colidx, part, p)
+        n_loc, nnz_loc = len(want["l2g"]), len(want["colidx"])
+        cap_n, cap_e = (n_loc, nnz_loc) if p == 3 else generous
+        assert n_loc <= cap_n and nnz_loc <= cap_e
+        if reuse:   # the buffers of the call before, marked
+            for k in ("l2g", "rowptr", "colidx"):
+                out[k].fill_(-7)
+            out["inv_deg"].fill_(-7.0)
+        out = B.tma_induced_subgraph_async(*d, p, cap_n, cap_e, out=out if reuse else None)
+        assert out["sizes"].cpu().tolist() == [n_loc, nnz_loc]
+        assert np.array_equal(out["g2l"][:150_000].cpu().numpy(), want["g2l"])
+        assert np.array_equal(out["l2g"][:n_loc].cpu().numpy(), want["l2g"])
+        assert np.array_equal(out["rowptr"][:n_loc + 1].cpu().numpy(), want["rowptr"])
+        assert np.array_equal(out["colidx"][:nnz_loc].cpu().numpy(), want["colidx"])
+        assert np.array_equal(out["inv_deg"][:n_loc].cpu().numpy(), want["inv_deg"].astype(np.float32))
+        if reuse:   # the tails keep the marker
+            assert bool((out["colidx"][nnz_loc:] == -7).all()) and bool((out["inv_deg"][n_loc:] == -7.0).all())
+            assert bool((out["l2g"][n_loc:] == -7).all()) and bool((out["rowptr"][n_loc + 1:] == -7).all())
+
+    # capacities too small: sizes reported, the rows that fit are exact, guard elements past the buffers intact
+    want = oracle.induced_subgraph(rowptr, colidx, part, 3)
+    n_loc, nnz_loc = len(want["l2g"]), len(want["colidx"])
+    cap_n, cap_e = n_loc - 1000, nnz_loc // 2
+    guard = 4096
+    i32 = lambda k: torch.full((k + guard,), -7, dtype=torch.int32, device="cuda")
+    ws_bytes = B.lib().tma_induced_subgraph_workspace_bytes(150_000, cap_n)
+    big = dict(g2l=i32(150_000), l2g=i32(cap_n), rowptr=i32(cap_n + 1), colidx=i32(cap_e),
+               inv_deg=torch.full((cap_n + guard,), -7.0, device="cuda"),
+               sizes=torch.zeros(2, dtype=torch.int64, device="cuda"),
+               ws=torch.empty(ws_bytes + 256, dtype=torch.uint8, device="cuda"))
+    B.tma_induced_subgraph_async(*d, 3, cap_n, cap_e, out=big)
+    sizes = big["sizes"].cpu().tolist()
+    assert sizes[0] == n_loc and sizes[1] == int(want["rowptr"][cap_n])
+    assert bool((big["l2g"][cap_n:] == -7).all()) and bool((big["rowptr"][cap_n + 1:] == -7).all())
+    assert bool((big["colidx"][cap_e:] == -7).all()) and bool((big["inv_deg"][cap_n:] == -7.0).all())
+    assert np.array_equal(big["l2g"][:cap_n].cpu().numpy(), want["l2g"][:cap_n])
+    assert np.array_equal(big["rowptr"][:cap_n + 1].cpu().numpy(), want["rowptr"][:cap_n + 1])
+    fit = int(np.searchsorted(want["rowptr"][:cap_n + 1], cap_e, side="right")) - 1   # rows that end within cap_e
+    got_ci = big["colidx"][:cap_e].cpu().numpy()
+    assert np.array_equal(got_ci[:want["rowptr"][fit]], want["colidx"][:want["rowptr"][fit]])
+
+    # empty part
+    rp, ci = synth.uniform_graph(3000, 9000, seed=5)
+    out = B.tma_induced_subgraph_async(dev(rp), dev(ci), dev(np.zeros(3000, dtype=np.int32)), 1, 100, 100)
+    assert out["sizes"].cpu().tolist() == [0, 0] and int(out["rowptr"][0]) == 0
+    torch.cuda.synchronize()
+
+
 # ------------------------------------------------------------------ aggregation
 def _local_graph(n, m, seed, K=2, kind="uniform"):
     if kind == "uniform":
