@@ -3,9 +3,8 @@
 //
 // Integer-only, HBM-scan bound.  Two prefix scans (local-node flags, kept
 // degrees) done as reduce -> scan-of-block-sums -> apply, which needs no
-// inter-block waiting, and a per-row order-preserving compaction that uses
-// wavefront ballots.  Sixteen lanes share one global row (global average
-// degree of the workloads is about 20), four rows per wavefront.
+// inter-block waiting, and an order-preserving compaction that uses wavefront
+// ballots over the concatenated entries of sixteen consecutive local rows.
 //
 // The flag scan also leaves, for the two passes over the local rows, a
 // membership bitmap (one bit per global node: 1/32 of the bytes of the id map,
@@ -19,8 +18,8 @@ namespace tma {
 constexpr int kScanThreads = 256;
 constexpr int kScanItems = 8;                           // consecutive items per thread
 constexpr int kScanTile = kScanThreads * kScanItems;    // items per block
-constexpr int kRowLanes = 16;                           // lanes per CSR row
-constexpr int kRowsPerBlock = 256 / kRowLanes;
+constexpr int kWaveRows = 16;                           // consecutive local rows per wavefront
+constexpr int kRowsPerBlock = (256 / kWave) * kWaveRows;
 
 // ---- value sources / sinks of the two scans -------------------------------
 struct FlagIn {  // 1 where the node belongs to partition p
@@ -210,10 +209,53 @@ __global__ __launch_bounds__(1024) void scan_sums_kernel(int64_t nb, int64_t *__
     if (threadIdx.x == 0) *total_out = carry_s;
 }
 
+// Sum over the workgroup of one 64-bit value per thread, returned to every thread.
+__device__ __forceinline__ int64_t block_sum_i64(int64_t v)
+{
+    __shared__ int64_t wave_sums64[kScanThreads / kWave];
+#pragma unroll
+    for (int d = kWave / 2; d >= 1; d >>= 1) v += __shfl_xor(v, d, kWave);
+    if ((threadIdx.x & (kWave - 1)) == 0) wave_sums64[threadIdx.x / kWave] = v;
+    __syncthreads();
+    int64_t total = 0;
+#pragma unroll
+    for (int w = 0; w < kScanThreads / kWave; ++w) total += wave_sums64[w];
+    __syncthreads();
+    return total;
+}
+
+// Up to this many tiles the apply kernel adds up the tile sums before its own tile by itself (a few loads per
+// thread) and no kernel scans them; above it scan_sums_kernel turns them into offsets first.
+constexpr int64_t kInlineTiles = 1024;
+
+// block_sums: per-tile sums (total_out != nullptr: this kernel derives its offset from them, and its first
+// workgroup stores the grand total to total_out and 0 to first_out, if given) or per-tile exclusive offsets
+// (total_out == nullptr).  zero_out[0 .. zero_n) is cleared, one element per workgroup, for a later kernel.
 template <class In, class Out>
 __global__ __launch_bounds__(kScanThreads) void scan_apply_kernel(const int64_t *d_n, int64_t cap, In in, Out out,
-                                                                  const int64_t *__restrict__ block_offsets)
+                                                                  const int64_t *__restrict__ block_sums,
+                                                                  int64_t *__restrict__ total_out,
+                                                                  int32_t *__restrict__ first_out,
+                                                                  int64_t *__restrict__ zero_out, int64_t zero_n)
 {
+    if (zero_out && threadIdx.x == 0 && int64_t(blockIdx.x) < zero_n) zero_out[blockIdx.x] = 0;
+    int64_t tile_offset;
+    if (total_out) {
+        int64_t before = 0, all = 0;
+        for (int64_t b = threadIdx.x; b < int64_t(gridDim.x); b += kScanThreads) {
+            const int64_t v = block_sums[b];
+            all += v;
+            if (b < int64_t(blockIdx.x)) before += v;
+        }
+        tile_offset = block_sum_i64(before);
+        all = block_sum_i64(all);
+        if (blockIdx.x == 0 && threadIdx.x == 0) {
+            *total_out = all;
+            if (first_out) *first_out = 0;
+        }
+    } else {
+        tile_offset = block_sums[blockIdx.x];
+    }
     const int64_t n = effective_n(d_n, cap);
     const int64_t base = int64_t(blockIdx.x) * kScanTile + int64_t(threadIdx.x) * kScanItems;
     static_assert(kScanItems == 8, "one thread's flags are one byte of the bitmap");
@@ -232,7 +274,7 @@ __global__ __launch_bounds__(kScanThreads) void scan_apply_kernel(const int64_t 
     }
     out.store_flags(base, bits, n);
     int32_t total;
-    int64_t prefix = block_offsets[blockIdx.x] + block_exclusive_scan(c, total);
+    int64_t prefix = tile_offset + block_exclusive_scan(c, total);
     // the last item also closes the output (DegOut writes the total after it): left to the item-wise path
     if (whole && base + kScanItems < n && out.store8(base, prefix, v)) return;
 #pragma unroll
@@ -247,9 +289,59 @@ __device__ __forceinline__ int member_bit(const uint32_t *__restrict__ member, i
     return int((member[uint32_t(u) >> 5] >> (uint32_t(u) & 31u)) & 1u);
 }
 
-// Global rows longer than this are scanned by the whole workgroup instead of 16 lanes
-// (power-law graphs: a few rows hold thousands of entries and would otherwise set the kernel's tail).
-constexpr int kHubRow = 128;
+// The two passes over the local rows walk the entries of kWaveRows consecutive rows as ONE stream per wavefront:
+// lane j < kWaveRows holds row j's bounds, a prefix sum over the row lengths gives every stream position its row,
+// and the 64 lanes take 64 consecutive stream positions per chunk, kStreamChunks chunks in flight.  All lanes
+// carry entries whatever the degree distribution (rows of 2 entries next to rows of 900), every lane has
+// several independent index -> bit (-> id) chains in flight, and there is no workgroup barrier on this path.
+// Rows longer than kGiantRow are left out of the stream and scanned by the whole workgroup afterwards
+// (power-law graphs: a handful of rows hold thousands of entries and would otherwise set the kernel's tail).
+constexpr int kGiantRow = 512;
+constexpr int kStreamChunks = 4;
+
+struct RowStream {
+    int32_t start[kWaveRows];  // wave-uniform: stream position of row j's first entry
+    int32_t total;             // wave-uniform: entries in the stream
+    int64_t adjust;            // lane j: row_beg[j] - start[j]  (global CSR position = adjust[row] + stream position)
+    int32_t first, last;       // lane j: the stream positions [first, last) of row j
+
+    // len: lane j's row length as it enters the stream (0 for lanes >= kWaveRows and for rows left out)
+    __device__ __forceinline__ void build(int64_t beg, int32_t len)
+    {
+        const int lane = threadIdx.x & (kWave - 1);
+        int32_t incl = len;
+#pragma unroll
+        for (int d = 1; d < kWaveRows; d <<= 1) {
+            const int32_t t = __shfl_up(incl, d, kWave);
+            if (lane >= d) incl += t;
+        }
+        first = incl - len;
+        last = incl;
+        adjust = beg - first;
+#pragma unroll
+        for (int j = 0; j < kWaveRows; ++j) start[j] = __builtin_amdgcn_readlane(first, j);
+        total = __builtin_amdgcn_readlane(incl, kWaveRows - 1);
+    }
+    // row of stream position t < total: the last row that starts at or before t (rows without entries
+    // share their start with the row after them and are passed over)
+    __device__ __forceinline__ int row_of(int32_t t) const
+    {
+        int r = 0;
+#pragma unroll
+        for (int j = 1; j < kWaveRows; ++j) r += t >= start[j] ? 1 : 0;
+        return r;
+    }
+    // bits of a 64-position chunk starting at stream position c that belong to this lane's row
+    __device__ __forceinline__ uint64_t own_bits(int32_t c) const
+    {
+        int32_t lo = first - c, hi = last - c;
+        lo = lo < 0 ? 0 : (lo > kWave ? kWave : lo);
+        hi = hi < 0 ? 0 : (hi > kWave ? kWave : hi);
+        const uint64_t below_hi = hi >= kWave ? ~0ull : ((1ull << hi) - 1ull);
+        const uint64_t below_lo = lo >= kWave ? ~0ull : ((1ull << lo) - 1ull);
+        return below_hi & ~below_lo;
+    }
+};
 
 // Kept degree of every local row: entries whose column is local too.
 __global__ __launch_bounds__(256) void row_count_kernel(const int64_t *d_n_loc, int64_t cap,
@@ -257,43 +349,69 @@ __global__ __launch_bounds__(256) void row_count_kernel(const int64_t *d_n_loc, 
                                                         const int32_t *__restrict__ row_len,
                                                         const int32_t *__restrict__ colidx,
                                                         const uint32_t *__restrict__ member,
-                                                        int32_t *__restrict__ deg)
+                                                        int32_t *__restrict__ deg,
+                                                        int64_t *__restrict__ tile_sums)
 {
-    __shared__ int32_t hub_rows[kRowsPerBlock];
-    __shared__ int32_t hub_count;
+    // tile_sums (may be NULL): tile_sums[t] (zero on entry) receives the kept degrees of the scan tile t that this workgroup's rows lie in:
+    // the first stage of the scan that turns deg into rowptr_loc (integer atomics: the sum has one value)
+    static_assert(kScanTile % kRowsPerBlock == 0, "the rows of a workgroup lie within one scan tile");
+    __shared__ int32_t giant_rows[kRowsPerBlock];
+    __shared__ int32_t giant_count;
+    __shared__ int32_t block_kept;
     __shared__ int32_t wave_part[256 / kWave];
-    if (threadIdx.x == 0) hub_count = 0;
+    if (threadIdx.x == 0) {
+        giant_count = 0;
+        block_kept = 0;
+    }
     __syncthreads();
 
     const int64_t n_loc = effective_n(d_n_loc, cap);
-    const int sub = threadIdx.x % kRowLanes;
+    const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
     const int64_t row0 = int64_t(blockIdx.x) * kRowsPerBlock;
-    const int64_t i = row0 + threadIdx.x / kRowLanes;
-    int32_t c = 0;
-    bool light = false;
-    if (i < n_loc) {
-        const int64_t beg = row_beg[i];
-        const int32_t len = row_len[i];
-        if (len > kHubRow) {
-            if (sub == 0) hub_rows[atomicAdd(&hub_count, 1)] = int32_t(i - row0);
-        } else {
-            light = true;
-            int32_t off = sub;
-            for (; off + kRowLanes < len; off += 2 * kRowLanes) {   // two index -> bit chains in flight
-                const int32_t u0 = colidx[beg + off], u1 = colidx[beg + off + kRowLanes];
-                c += member_bit(member, u0) + member_bit(member, u1);
-            }
-            if (off < len) c += member_bit(member, colidx[beg + off]);
+    const int64_t i = row0 + wave * kWaveRows + lane;      // this lane's row (lanes < kWaveRows)
+    const bool has_row = lane < kWaveRows && i < n_loc;
+    int64_t beg = 0;
+    int32_t len = 0;
+    if (has_row) {
+        beg = row_beg[i];
+        len = row_len[i];
+        if (len > kGiantRow) {
+            giant_rows[atomicAdd(&giant_count, 1)] = int32_t(i - row0);
+            len = -1;
         }
     }
+    const bool in_stream = has_row && len >= 0;
+    RowStream st;
+    st.build(beg, len > 0 ? len : 0);
+    int32_t c = 0;
+    for (int32_t c0 = 0; c0 < st.total; c0 += kStreamChunks * kWave) {
+        int32_t u[kStreamChunks];
 #pragma unroll
-    for (int d = kRowLanes / 2; d >= 1; d >>= 1) c += __shfl_xor(c, d, kWave);
-    if (light && sub == 0) deg[i] = c;
+        for (int q = 0; q < kStreamChunks; ++q) {
+            u[q] = -1;
+            if (c0 + q * kWave >= st.total) continue;     // wave-uniform: the chunk lies past the end
+            const int32_t t = c0 + q * kWave + lane;
+            // every lane takes part in the shuffle (positions past the end ask for row_of(0), a valid lane)
+            const int64_t base = __shfl(st.adjust, st.row_of(t < st.total ? t : 0), kWave);
+            if (t < st.total) u[q] = colidx[base + t];
+        }
+#pragma unroll
+        for (int q = 0; q < kStreamChunks; ++q) {
+            if (c0 + q * kWave >= st.total) continue;
+            const bool keep = u[q] >= 0 && member_bit(member, u[q]) != 0;
+            c += __popcll(__ballot(keep) & st.own_bits(c0 + q * kWave));
+        }
+    }
+    if (in_stream) deg[i] = c;
+    int32_t wave_kept = c;       // lanes past the rows of the wavefront hold 0
+#pragma unroll
+    for (int d = kWaveRows / 2; d >= 1; d >>= 1) wave_kept += __shfl_xor(wave_kept, d, kWave);
+    if (lane == 0 && wave_kept) atomicAdd(&block_kept, wave_kept);
     __syncthreads();
 
-    const int n_hubs = hub_count;
-    for (int h = 0; h < n_hubs; ++h) {
-        const int64_t ih = row0 + hub_rows[h];
+    const int n_giants = giant_count;
+    for (int h = 0; h < n_giants; ++h) {
+        const int64_t ih = row0 + giant_rows[h];
         const int64_t end = row_beg[ih] + row_len[ih];
         int32_t ch = 0;
         for (int64_t e = row_beg[ih] + threadIdx.x; e < end; e += 4 * 256) {  // up to four index -> bit chains in flight
@@ -308,14 +426,24 @@ __global__ __launch_bounds__(256) void row_count_kernel(const int64_t *d_n_loc, 
         for (int d = kWave / 2; d >= 1; d >>= 1) ch += __shfl_xor(ch, d, kWave);
         if ((threadIdx.x & (kWave - 1)) == 0) wave_part[threadIdx.x / kWave] = ch;
         __syncthreads();
-        if (threadIdx.x == 0) deg[ih] = wave_part[0] + wave_part[1] + wave_part[2] + wave_part[3];
+        if (threadIdx.x == 0) {
+            const int32_t kept = wave_part[0] + wave_part[1] + wave_part[2] + wave_part[3];
+            deg[ih] = kept;
+            block_kept += kept;
+        }
         __syncthreads();
     }
+    if (tile_sums && threadIdx.x == 0 && block_kept)
+        atomicAdd(reinterpret_cast<unsigned long long *>(tile_sums + row0 / kScanTile),
+                  static_cast<unsigned long long>(block_kept));
 }
 
 // Order-preserving compaction of each local row into colidx_loc, relabelled.
 // n_loc rows at most; with d_n_loc the actual count is read from the device (a launch sized by capacity).  A row
 // whose entries would end past cap_nnz is skipped: the caller's buffer is then too small and the sizes say so.
+// The rows of a wavefront are consecutive, so are their ranges in colidx_loc: the kept entries of the stream go
+// to consecutive positions from the first row's offset on, shifted by the kept entries of the giant rows left
+// out of the stream before them.
 __global__ __launch_bounds__(256) void row_fill_kernel(int64_t n_loc, const int64_t *__restrict__ d_n_loc,
                                                        int64_t cap_nnz, const int64_t *__restrict__ row_beg,
                                                        const int32_t *__restrict__ row_len,
@@ -326,75 +454,81 @@ __global__ __launch_bounds__(256) void row_fill_kernel(int64_t n_loc, const int6
                                                        int32_t *__restrict__ colidx_loc,
                                                        float *__restrict__ inv_deg)
 {
-    __shared__ int32_t hub_rows[kRowsPerBlock];
-    __shared__ int32_t hub_count;
+    __shared__ int32_t giant_rows[kRowsPerBlock];
+    __shared__ int32_t giant_count;
     __shared__ int32_t wave_part[256 / kWave];
-    if (threadIdx.x == 0) hub_count = 0;
+    if (threadIdx.x == 0) giant_count = 0;
     __syncthreads();
 
     if (d_n_loc) {
         const int64_t actual = *d_n_loc;
         n_loc = actual < n_loc ? actual : n_loc;
     }
-    const int sub = threadIdx.x % kRowLanes;
-    const int group_shift = ((threadIdx.x % kWave) / kRowLanes) * kRowLanes;
+    const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
     const int64_t row0 = int64_t(blockIdx.x) * kRowsPerBlock;
-    const int64_t i = row0 + threadIdx.x / kRowLanes;
+    const int64_t i = row0 + wave * kWaveRows + lane;
     int64_t beg = 0;
-    int32_t len = 0;
-    int32_t out = 0;
-    if (i < n_loc) {
+    int32_t len = 0, out = 0, left_out = 0;
+    if (lane < kWaveRows && i < n_loc) {
         beg = row_beg[i];
         len = row_len[i];
         out = rowptr_loc[i];
         const int32_t end = rowptr_loc[i + 1];
-        if (sub == 0) {
-            const int32_t d = end - out;
-            inv_deg[i] = d > 0 ? 1.0f / float(d) : 0.0f;
-        }
-        if (int64_t(end) > cap_nnz) len = 0;
-        if (len > kHubRow) {  // left to the whole workgroup below
-            if (sub == 0) hub_rows[atomicAdd(&hub_count, 1)] = int32_t(i - row0);
+        inv_deg[i] = end > out ? 1.0f / float(end - out) : 0.0f;
+        // nothing to write: a row without kept entries (most rows of a sparse part) never touches colidx again
+        if (int64_t(end) > cap_nnz || end == out) len = 0;
+        if (len > kGiantRow) {  // left to the whole workgroup below
+            giant_rows[atomicAdd(&giant_count, 1)] = int32_t(i - row0);
+            left_out = end - out;
             len = 0;
         }
     }
-    // Every lane of the wavefront runs the same number of rounds so that the
-    // ballot below is executed by all of them.
-    int32_t rounds = len;
+    RowStream st;
+    st.build(beg, len);
+    // kept entries of the giant rows before this lane's row, among the rows of the wavefront
+    int32_t shift = left_out;
 #pragma unroll
-    for (int d = kRowLanes; d < kWave; d <<= 1) {
-        int32_t o = __shfl_xor(rounds, d, kWave);
-        rounds = o > rounds ? o : rounds;
+    for (int d = 1; d < kWaveRows; d <<= 1) {
+        const int32_t t = __shfl_up(shift, d, kWave);
+        if (lane >= d) shift += t;
     }
-    // two runs of kRowLanes entries per round: both index -> bit -> id chains are in flight together
-    for (int32_t off = 0; off < rounds; off += 2 * kRowLanes) {
-        int32_t u0 = -1, u1 = -1;
-        if (off + sub < len) u0 = colidx[beg + off + sub];
-        if (off + kRowLanes + sub < len) u1 = colidx[beg + off + kRowLanes + sub];
-        const bool keep0 = u0 >= 0 && member_bit(member, u0) != 0;
-        const bool keep1 = u1 >= 0 && member_bit(member, u1) != 0;
-        int32_t lid0 = 0, lid1 = 0;
-        if (keep0) lid0 = g2l[u0];
-        if (keep1) lid1 = g2l[u1];
-        const uint64_t ballot0 = __ballot(keep0);
-        const uint64_t ballot1 = __ballot(keep1);
-        const uint32_t mine0 = uint32_t(ballot0 >> group_shift) & ((1u << kRowLanes) - 1u);
-        const uint32_t mine1 = uint32_t(ballot1 >> group_shift) & ((1u << kRowLanes) - 1u);
-        if (keep0) colidx_loc[out + __popc(mine0 & ((1u << sub) - 1u))] = lid0;
-        out += __popc(mine0);
-        if (keep1) colidx_loc[out + __popc(mine1 & ((1u << sub) - 1u))] = lid1;
-        out += __popc(mine1);
+    shift -= left_out;
+    int32_t pos = __builtin_amdgcn_readlane(out, 0);     // next free position of the stream's output
+    for (int32_t c0 = 0; c0 < st.total; c0 += kStreamChunks * kWave) {
+        int32_t u[kStreamChunks], lid[kStreamChunks], extra[kStreamChunks];
+        bool keep[kStreamChunks];
+#pragma unroll
+        for (int q = 0; q < kStreamChunks; ++q) {
+            u[q] = -1;
+            extra[q] = 0;
+            if (c0 + q * kWave >= st.total) continue;          // wave-uniform: the chunk lies past the end
+            const int32_t t = c0 + q * kWave + lane;
+            const int r = st.row_of(t < st.total ? t : 0);     // every lane takes part in the shuffles
+            const int64_t base = __shfl(st.adjust, r, kWave);
+            extra[q] = __shfl(shift, r, kWave);
+            if (t < st.total) u[q] = colidx[base + t];
+        }
+#pragma unroll
+        for (int q = 0; q < kStreamChunks; ++q) keep[q] = u[q] >= 0 && member_bit(member, u[q]) != 0;
+#pragma unroll
+        for (int q = 0; q < kStreamChunks; ++q) lid[q] = keep[q] ? g2l[u[q]] : 0;
+#pragma unroll
+        for (int q = 0; q < kStreamChunks; ++q) {
+            if (c0 + q * kWave >= st.total) continue;
+            const uint64_t ballot = __ballot(keep[q]);
+            if (keep[q]) colidx_loc[pos + extra[q] + __popcll(ballot & ((1ull << lane) - 1ull))] = lid[q];
+            pos += __popcll(ballot);
+        }
     }
     __syncthreads();
 
-    // Hub rows: the whole workgroup, 4 consecutive entries per thread and round (1024 per round, order kept: a
+    // Giant rows: the whole workgroup, 4 consecutive entries per thread and round (1024 per round, order kept: a
     // thread's entries follow those of all lower threads).  The longest row of a power-law graph sets the tail of
     // this kernel, so a round carries as many independent index -> bit -> id chains as the registers allow.
-    const int n_hubs = hub_count;
-    const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
+    const int n_hubs = giant_count;
     constexpr int kPerThread = 4;
     for (int h = 0; h < n_hubs; ++h) {
-        const int64_t ih = row0 + hub_rows[h];
+        const int64_t ih = row0 + giant_rows[h];
         const int64_t hbeg = row_beg[ih], hend = hbeg + row_len[ih];
         int32_t hout = rowptr_loc[ih];
         int32_t u_next[kPerThread];
@@ -497,10 +631,13 @@ int launch_exclusive_scan_i32(int64_t n, const int32_t *values, int32_t *prefix_
     if (nb > 0)
         hipLaunchKernelGGL(scan_reduce_kernel<DegIn>, dim3(unsigned(nb)), dim3(kScanThreads), 0, s,
                            static_cast<const int64_t *>(nullptr), n, in, block_sums);
-    hipLaunchKernelGGL(scan_sums_kernel, dim3(1), dim3(1024), 0, s, nb, block_sums, total, prefix_out);
+    const bool inline_sums = nb > 0 && nb <= kInlineTiles;
+    if (!inline_sums) hipLaunchKernelGGL(scan_sums_kernel, dim3(1), dim3(1024), 0, s, nb, block_sums, total, prefix_out);
     if (nb > 0)
         hipLaunchKernelGGL((scan_apply_kernel<DegIn, DegOut>), dim3(unsigned(nb)), dim3(kScanThreads), 0, s,
-                           static_cast<const int64_t *>(nullptr), n, in, out, block_sums);
+                           static_cast<const int64_t *>(nullptr), n, in, out, block_sums,
+                           inline_sums ? total : nullptr, inline_sums ? prefix_out : nullptr,
+                           static_cast<int64_t *>(nullptr), int64_t(0));
     return check_launch("exclusive scan");
 }
 
@@ -537,37 +674,39 @@ static int enqueue_count(const char *fn, int64_t n_nodes, const int64_t *rowptr,
     const unsigned nb_rows = unsigned(ceil_div(cap_n_loc > 0 ? cap_n_loc : 1, kScanTile));
     FlagIn fin{part, p};
     FlagOut fout{g2l_out, l2g_out, cap_n_loc, rowptr, w.row_beg, w.row_len, reinterpret_cast<uint8_t *>(w.member)};
-    // 1. rank local nodes
+    // 1. rank local nodes.  Few tiles: the apply kernel adds up the tile sums itself; many: a scan kernel first.
+    const bool inline_nodes = nb_nodes <= kInlineTiles, inline_rows = nb_rows <= kInlineTiles;
     {
         TMA_TIMED("scan_reduce_flags", s);
         hipLaunchKernelGGL(scan_reduce_kernel<FlagIn>, dim3(nb_nodes), dim3(kScanThreads), 0, s, nullptr, n_nodes,
                            fin, w.node_block_sums);
     }
-    {
+    if (!inline_nodes) {
         TMA_TIMED("scan_sums", s);
         hipLaunchKernelGGL(scan_sums_kernel, dim3(1), dim3(1024), 0, s, int64_t(nb_nodes), w.node_block_sums,
                            sizes + 0, rowptr_loc_out);
     }
-    {
+    {   // also clears the tile sums that the kept-degree pass adds to (nb_rows <= nb_nodes)
         TMA_TIMED("scan_apply_flags", s);
         hipLaunchKernelGGL((scan_apply_kernel<FlagIn, FlagOut>), dim3(nb_nodes), dim3(kScanThreads), 0, s, nullptr,
-                           n_nodes, fin, fout, w.node_block_sums);
+                           n_nodes, fin, fout, w.node_block_sums, inline_nodes ? sizes + 0 : nullptr,
+                           inline_nodes ? rowptr_loc_out : nullptr, w.row_block_sums, int64_t(nb_rows));
     }
-    // 2. kept degree per local row, then rowptr_loc by a second scan
+    // 2. kept degree per local row and per scan tile, then rowptr_loc by the second scan
     if (cap_n_loc > 0) {
         const unsigned row_blocks = unsigned(ceil_div(cap_n_loc, kRowsPerBlock));
         TMA_TIMED("row_count", s);
         hipLaunchKernelGGL(row_count_kernel, dim3(row_blocks), dim3(256), 0, s, sizes + 0, cap_n_loc, w.row_beg,
-                           w.row_len, colidx, w.member, w.deg);
+                           w.row_len, colidx, w.member, w.deg, inline_rows ? w.row_block_sums : nullptr);
     }
     DegIn din{w.deg};
     DegOut dout{rowptr_loc_out};
-    {
-        TMA_TIMED("scan_reduce_deg", s);
-        hipLaunchKernelGGL(scan_reduce_kernel<DegIn>, dim3(nb_rows), dim3(kScanThreads), 0, s, sizes + 0,
-                           cap_n_loc, din, w.row_block_sums);
-    }
-    {
+    if (!inline_rows) {   // many tiles: their sums by a pass of its own (one atomic per workgroup would queue up)
+        {
+            TMA_TIMED("scan_reduce_deg", s);
+            hipLaunchKernelGGL(scan_reduce_kernel<DegIn>, dim3(nb_rows), dim3(kScanThreads), 0, s, sizes + 0,
+                               cap_n_loc, din, w.row_block_sums);
+        }
         TMA_TIMED("scan_sums", s);
         hipLaunchKernelGGL(scan_sums_kernel, dim3(1), dim3(1024), 0, s, int64_t(nb_rows), w.row_block_sums,
                            sizes + 1, static_cast<int32_t *>(nullptr));
@@ -575,7 +714,8 @@ static int enqueue_count(const char *fn, int64_t n_nodes, const int64_t *rowptr,
     {
         TMA_TIMED("scan_apply_deg", s);
         hipLaunchKernelGGL((scan_apply_kernel<DegIn, DegOut>), dim3(nb_rows), dim3(kScanThreads), 0, s, sizes + 0,
-                           cap_n_loc, din, dout, w.row_block_sums);
+                           cap_n_loc, din, dout, w.row_block_sums, inline_rows ? sizes + 1 : nullptr,
+                           static_cast<int32_t *>(nullptr), static_cast<int64_t *>(nullptr), int64_t(0));
     }
     return check_launch(fn);
 }
