@@ -254,6 +254,57 @@ def gcn_layer_bwd(rowptr, colidx, M, Z, dHnext, W, act: int, need_dH=True):
     return dW, db, dH
 
 
+def gcn_block_aggregate(rowptr, colidx, H, transpose: bool = False, n_src: int | None = None) -> np.ndarray:
+    """Row-normalised aggregation with the self-loop on a bipartite block: M = Dt^-1 (A_S + I) H over the block's
+    rows (H has a row per source node, the first rows being the block's own nodes); with ``transpose`` the
+    adjoint, from one row per block row to n_src rows."""
+    rowptr, colidx, H = _i32(rowptr), _i32(colidx), _f64(H)
+    n_dst, F = rowptr.shape[0] - 1, H.shape[1]
+    if transpose:
+        assert H.shape[0] == n_dst and n_src is not None and n_src >= n_dst
+        out = np.empty((n_src, F))
+        lib().orc_gcn_block_aggregate_T(C.c_int64(n_dst), C.c_int64(n_src), _p(rowptr), _p(colidx), _p(H),
+                                        C.c_int64(F), _p(out))
+        return out
+    assert n_dst <= H.shape[0]
+    M = np.empty((n_dst, F))
+    lib().orc_gcn_block_aggregate(C.c_int64(n_dst), _p(rowptr), _p(colidx), _p(H), C.c_int64(F), _p(M))
+    return M
+
+
+def gcn_block_layer_fwd(rowptr, colidx, H, W, bias, act: int):
+    """Returns (M, Z, Hnext) of one GCN layer on a bipartite block: M = Dt^-1 (A_S + I) H, Z = M W + b."""
+    rowptr, colidx = _i32(rowptr), _i32(colidx)
+    H, W, bias = _f64(H), _f64(W), _f64(bias)
+    n_dst, F_in = rowptr.shape[0] - 1, H.shape[1]
+    F_out = W.shape[1]
+    assert W.shape == (F_in, F_out) and bias.shape == (F_out,) and n_dst <= H.shape[0]
+    M = np.empty((n_dst, F_in))
+    Z = np.empty((n_dst, F_out))
+    Hn = np.empty((n_dst, F_out))
+    lib().orc_gcn_block_layer_fwd(C.c_int64(n_dst), _p(rowptr), _p(colidx), _p(H), C.c_int64(F_in), _p(W), _p(bias),
+                                  C.c_int64(F_out), C.c_int(act), _p(M), _p(Z), _p(Hn))
+    return M, Z, Hn
+
+
+def gcn_block_layer_bwd(rowptr, colidx, n_src: int, M, Z, dHnext, W, act: int, need_dH=True):
+    """Returns (dW, dbias, dH [n_src, F_in] or None)."""
+    rowptr, colidx = _i32(rowptr), _i32(colidx)
+    M, Z, dHnext, W = _f64(M), _f64(Z), _f64(dHnext), _f64(W)
+    n_dst, F_in = M.shape
+    F_out = W.shape[1]
+    assert n_dst == rowptr.shape[0] - 1 and n_src >= n_dst
+    dW = np.empty((F_in, F_out))
+    db = np.empty(F_out)
+    dH = np.empty((n_src, F_in)) if need_dH else None
+    sM = np.empty((n_dst, F_in))
+    sZ = np.empty((n_dst, F_out))
+    lib().orc_gcn_block_layer_bwd(C.c_int64(n_dst), C.c_int64(n_src), _p(rowptr), _p(colidx), _p(M), _p(Z),
+                                  _p(dHnext), _p(W), C.c_int64(F_in), C.c_int64(F_out), C.c_int(act), _p(dW), _p(db),
+                                  _p(dH), _p(sM), _p(sZ))
+    return dW, db, dH
+
+
 # ------------------------------------------------------ normalisation + activation
 LN_EPS = 1e-5
 

@@ -9,19 +9,23 @@ from __future__ import annotations
 
 import numpy as np
 
-from . import (ACT_NONE, ACT_RELU, adam_step, average, bce_logits, dense_bwd, dense_fwd, gcn_aggregate, gcn_layer_bwd,
-               gcn_layer_fwd, gcn_norm, layernorm_prelu_bwd, layernorm_prelu_fwd, mean_aggregate, mfg_relabel, mix64,
-               neighbor_sample, pair_product_bwd, pair_product_fwd, prelu_bwd, prelu_fwd, round_bf16, sage_layer_bwd,
-               sage_layer_fwd, sgd_step, softmax_ce)
+from . import (ACT_NONE, ACT_RELU, adam_step, average, bce_logits, dense_bwd, dense_fwd, gcn_aggregate,
+               gcn_block_aggregate, gcn_block_layer_bwd, gcn_block_layer_fwd, gcn_layer_bwd,
+               gcn_layer_fwd, gcn_norm, layernorm_prelu_bwd, layernorm_prelu_fwd, mean_aggregate,
+               mfg_relabel, mix64, neighbor_sample, pair_product_bwd, pair_product_fwd, prelu_bwd,
+               prelu_fwd, round_bf16, sage_layer_bwd, sage_layer_fwd, sgd_step, softmax_ce)
 
 ACT_LN_PRELU = "ln_prelu"   # a layer whose parameter tuple ends with (gamma, beta, slope)
 
 
-def _layer_fwd(encoder, rowptr, colidx, H, lin, act):
+def _layer_fwd(encoder, rowptr, colidx, H, lin, act, block=False):
     """(M, Z, Hnext) of one layer of the chosen encoder (Sec. 4.1): "sage" (W_self, W_neigh, b),
-    "gcn" (W, b) or the graph-agnostic "mlp" (W, b), whose M is its input."""
+    "gcn" (W, b) or the graph-agnostic "mlp" (W, b), whose M is its input.  ``block``: the graph is one bipartite
+    block of a sampled message-flow graph (GCN then takes its row-normalised form)."""
     if encoder == "sage":
         return sage_layer_fwd(rowptr, colidx, H, lin[0], lin[1], lin[2], act)
+    if encoder == "gcn" and block:
+        return gcn_block_layer_fwd(rowptr, colidx, H, lin[0], lin[1], act)
     if encoder == "gcn":
         return gcn_layer_fwd(rowptr, colidx, H, lin[0], lin[1], act)
     if encoder == "mlp":
@@ -30,11 +34,14 @@ def _layer_fwd(encoder, rowptr, colidx, H, lin, act):
     raise ValueError(encoder)
 
 
-def _layer_bwd(encoder, rowptr, colidx, H, M, Z, d, lin, act, need_dH):
+def _layer_bwd(encoder, rowptr, colidx, H, M, Z, d, lin, act, need_dH, block=False):
     """(gradients of the linear parameters, dH)."""
     if encoder == "sage":
         dWs, dWn, db, dH = sage_layer_bwd(rowptr, colidx, H, M, Z, d, lin[0], lin[1], act, need_dH=need_dH)
         return (dWs, dWn, db), dH
+    if encoder == "gcn" and block:
+        dW, db, dH = gcn_block_layer_bwd(rowptr, colidx, H.shape[0], M, Z, d, lin[0], act, need_dH=need_dH)
+        return (dW, db), dH
     if encoder == "gcn":
         dW, db, dH = gcn_layer_bwd(rowptr, colidx, M, Z, d, lin[0], act, need_dH=need_dH)
         return (dW, db), dH
@@ -60,12 +67,12 @@ def forward(rowptr, colidx, X, params, encoder="sage"):
         rowptr, colidx = (graphs[0][l], graphs[1][l]) if per_layer else graphs
         lin = layer[:nl]
         if len(layer) == nl + 3:
-            M, Z, _ = _layer_fwd(encoder, rowptr, colidx, H, lin, ACT_NONE)
+            M, Z, _ = _layer_fwd(encoder, rowptr, colidx, H, lin, ACT_NONE, per_layer)
             Hn = layernorm_prelu_fwd(Z, layer[nl], layer[nl + 1], float(np.asarray(layer[nl + 2]).ravel()[0]))
             saved.append((H, M, Z, ACT_LN_PRELU))
         else:
             act = ACT_RELU if l < L - 1 else ACT_NONE
-            M, Z, Hn = _layer_fwd(encoder, rowptr, colidx, H, lin, act)
+            M, Z, Hn = _layer_fwd(encoder, rowptr, colidx, H, lin, act, per_layer)
             saved.append((H, M, Z, act))
         H = Hn
     return H, saved
@@ -113,6 +120,10 @@ def forward_as_stored(rowptr, colidx, X, params, encoder="sage", storage="bf16",
         elif encoder == "sage":
             M = _store(mean_aggregate(rp, ci, H), storage)
             Z, _ = dense_fwd(np.concatenate([H[:n_dst], M], axis=1), np.concatenate(W, axis=0), b, ACT_NONE)
+        elif encoder == "gcn" and per_layer:
+            if tf:
+                raise ValueError("the GCN layer on a block is evaluated aggregate-first only")
+            Z, _ = dense_fwd(_store(gcn_block_aggregate(rp, ci, H), storage), W[0], b, ACT_NONE)
         elif encoder == "gcn" and tf:
             s_norm = gcn_norm(rp)[:, None]
             Y = _store(s_norm * dense_fwd(H, W[0], None, ACT_NONE)[0], storage)
@@ -175,12 +186,12 @@ def backward(rowptr, colidx, params, saved, d, relu_open=None, encoder="sage", n
             gamma, beta = params[l][nl], params[l][nl + 1]
             slope = float(np.asarray(params[l][nl + 2]).ravel()[0])
             dZ, dg, dbeta, ds = layernorm_prelu_bwd(Z, d, gamma, beta, slope, open_mask=forced)
-            glin, dH = _layer_bwd(encoder, rowptr, colidx, H, M, Z, dZ, lin, ACT_NONE, need_dH)
+            glin, dH = _layer_bwd(encoder, rowptr, colidx, H, M, Z, dZ, lin, ACT_NONE, need_dH, per_layer)
             grads[l] = glin + (dg, dbeta, np.array([ds]))
         else:
             if forced is not None and act == ACT_RELU:
                 Z = np.where(np.asarray(forced), 1.0, -1.0)   # only the sign of Z is used by the backward pass
-            glin, dH = _layer_bwd(encoder, rowptr, colidx, H, M, Z, d, lin, act, need_dH)
+            glin, dH = _layer_bwd(encoder, rowptr, colidx, H, M, Z, d, lin, act, need_dH, per_layer)
             grads[l] = glin
         d = dH
     return grads, d
@@ -319,16 +330,16 @@ def sample_mfg(rowptr, colidx, seeds, fanouts, seed: int, step: int):
 
 
 def sampled_link_loss_and_grads(rowptr, colidx, X, batch, enc_params, dec_params, fanouts, seed, step,
-                                relu_open=None, dec_open=None, decisions=None, trace=None):
-    """The link-prediction step on the sampled message-flow graph of its batch (SAGE encoder): the encoder runs on
-    the bipartite blocks only, from the features of the sampled input nodes up to the embeddings of the batch's
-    nodes.  Returns (loss, enc_grads, dec_grads, logits, (rps, cis, input_nodes, seeds))."""
+                                relu_open=None, dec_open=None, decisions=None, trace=None, encoder="sage"):
+    """The link-prediction step on the sampled message-flow graph of its batch (SAGE or GCN encoder): the encoder
+    runs on the bipartite blocks only, from the features of the sampled input nodes up to the embeddings of the
+    batch's nodes.  Returns (loss, enc_grads, dec_grads, logits, (rps, cis, input_nodes, seeds))."""
     u, v, vneg = batch
     seeds = np.unique(np.concatenate([u, v, vneg])).astype(np.int32)
     rps, cis, inputs = sample_mfg(rowptr, colidx, seeds, fanouts, seed, step)
     pos = tuple(np.searchsorted(seeds, a).astype(np.int32) for a in (u, v, vneg))
     loss, enc_grads, dec_grads, z = _link_tail((rps, cis), np.asarray(X)[inputs], pos, enc_params, dec_params,
-                                               "sage", relu_open, dec_open, decisions, trace)
+                                               encoder, relu_open, dec_open, decisions, trace)
     return loss, enc_grads, dec_grads, z, (rps, cis, inputs, seeds)
 
 

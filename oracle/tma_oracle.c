@@ -534,6 +534,69 @@ void orc_gcn_layer_bwd(int64_t n, const int32_t *rowptr, const int32_t *colidx,
 }
 
 /* ------------------------------------------------------------------------
+ * GCN layer on one bipartite block of a sampled message-flow graph (Sec. 4.1:
+ * the GCN encoder is trained with the neighbour sampler on the larger
+ * datasets).  A block has n_dst rows over n_src >= n_dst source nodes, the
+ * destination nodes being the first n_dst sources.  The symmetric
+ * normalisation of the full-graph layer needs a degree for the source side,
+ * which a sampled block does not define (how often a source was drawn depends
+ * on which destinations were asked).  Reading taken here: the row-normalised
+ * form with the self-loop,
+ *     m_v = ( h_v + sum_{u in S(v)} h_u ) / ( |S(v)| + 1 ),   Z = M W + 1 b^T,
+ * i.e. Dt^-1 (A_S + I): the mean over the sampled neighbourhood and the node
+ * itself, which is how the cited neighbour-sampling method writes its GCN
+ * variant.  With S(v) = N(v) it is the random-walk normalisation of A + I.
+ * ---------------------------------------------------------------------- */
+void orc_gcn_block_aggregate(int64_t n_dst, const int32_t *rowptr, const int32_t *colidx,
+                             const double *H, int64_t F, double *M)
+{
+    for (int64_t v = 0; v < n_dst; ++v) {
+        const double c = 1.0 / ((double)(rowptr[v + 1] - rowptr[v]) + 1.0);
+        double *m = M + v * F;
+        for (int64_t f = 0; f < F; ++f) m[f] = H[v * F + f];
+        for (int32_t e = rowptr[v]; e < rowptr[v + 1]; ++e) {
+            const double *h = H + (int64_t)colidx[e] * F;
+            for (int64_t f = 0; f < F; ++f) m[f] += h[f];
+        }
+        for (int64_t f = 0; f < F; ++f) m[f] *= c;
+    }
+}
+
+/* out [n_src, F] = (Dt^-1 (A_S + I))^T G, G [n_dst, F]: a scatter over the block. */
+void orc_gcn_block_aggregate_T(int64_t n_dst, int64_t n_src, const int32_t *rowptr, const int32_t *colidx,
+                               const double *G, int64_t F, double *out)
+{
+    memset(out, 0, (size_t)(n_src * F) * sizeof(double));
+    for (int64_t v = 0; v < n_dst; ++v) {
+        const double c = 1.0 / ((double)(rowptr[v + 1] - rowptr[v]) + 1.0);
+        for (int64_t f = 0; f < F; ++f) out[v * F + f] += c * G[v * F + f];
+        for (int32_t e = rowptr[v]; e < rowptr[v + 1]; ++e) {
+            double *o = out + (int64_t)colidx[e] * F;
+            for (int64_t f = 0; f < F; ++f) o[f] += c * G[v * F + f];
+        }
+    }
+}
+
+void orc_gcn_block_layer_fwd(int64_t n_dst, const int32_t *rowptr, const int32_t *colidx,
+                             const double *H, int64_t F_in, const double *W, const double *bias,
+                             int64_t F_out, int act, double *M, double *Z, double *Hnext)
+{
+    orc_gcn_block_aggregate(n_dst, rowptr, colidx, H, F_in, M);
+    orc_dense_fwd(n_dst, M, F_in, W, bias, F_out, act, Z, Hnext);
+}
+
+/* dW = M^T dZ, db = 1^T dZ, dH [n_src, F_in] = (Dt^-1 (A_S + I))^T (dZ W^T)   (dH skipped when NULL).
+ * scratch_dM: n_dst*F_in doubles, scratch_dZ: n_dst*F_out doubles. */
+void orc_gcn_block_layer_bwd(int64_t n_dst, int64_t n_src, const int32_t *rowptr, const int32_t *colidx,
+                             const double *M, const double *Z, const double *dHnext, const double *W,
+                             int64_t F_in, int64_t F_out, int act, double *dW, double *dbias, double *dH,
+                             double *scratch_dM, double *scratch_dZ)
+{
+    orc_dense_bwd(n_dst, M, Z, dHnext, W, F_in, F_out, act, dW, dbias, dH ? scratch_dM : NULL, scratch_dZ);
+    if (dH) orc_gcn_block_aggregate_T(n_dst, n_src, rowptr, colidx, scratch_dM, F_in, dH);
+}
+
+/* ------------------------------------------------------------------------
  * Link-prediction head (Sec. 4.1, paragraphs on the link prediction decoder
  * and on mini-batch and negative sampling; App., formulation of the MLP
  * decoder).
