@@ -328,10 +328,11 @@ def main():
     sampled = args.task == "link-sampled"
     fanouts = [int(f) for f in args.fanouts.split(",")] if sampled else None
     if sampled:
-        if args.encoder != "sage" or args.norm_act or len(fanouts) != L:
-            sys.exit("bench.py: link-sampled runs the SAGE encoder with ReLU and needs one fan-out per layer")
+        if args.encoder == "mlp" or args.norm_act or len(fanouts) != L:
+            sys.exit("bench.py: link-sampled runs the SAGE or GCN encoder with ReLU and needs one fan-out per layer")
         tr = SampledLinkTrainer(sub["rowptr"], sub["colidx"], nnz_loc, Xl, dims, dec_dims, fanouts, args.batch,
-                                batch_seed=sd["part"] + 1, params=params, nnz_cap=nnz_loc + nnz_loc // 4 + 4096)
+                                batch_seed=sd["part"] + 1, params=params, nnz_cap=nnz_loc + nnz_loc // 4 + 4096,
+                                encoder=args.encoder)
     else:
         tr = LocalTrainer(sub["rowptr"], sub["colidx"], sub["inv_deg"], Xl, yl, dims, params=params,
                           norm_act=args.norm_act, encoder=args.encoder, **link)

@@ -489,6 +489,45 @@ int tma_sage_block_bwd(int64_t n_dst, int64_t n_src, int64_t max_entries,
                        void *ws, size_t ws_bytes, tma_stream_t stream);
 
 /* ------------------------------------------------------------------------
+ * GCN layer on a bipartite block of a sampled message-flow graph (Sec. 4.1:
+ * the GCN encoder trained with the neighbour sampler).  The symmetric
+ * normalisation of tma_gcn_layer_* needs a degree for the source side, which
+ * a sampled block does not define; on a block the layer is taken in its
+ * row-normalised form with the self-loop,
+ *     m_v = ( h_v + sum_{u in S(v)} h_u ) / ( |S(v)| + 1 ),  Z = M W + 1 b^T,
+ *     H' = act(Z),
+ * the mean over the sampled neighbourhood and the node itself.  Blocks, node
+ * order (the n_dst destination nodes are the first sources) and buffers as
+ * for tma_sage_block_*.
+ *   tma_gcn_block_norm: c_out [n_dst] fp32 = 1 / (|S(v)| + 1).
+ *   tma_gcn_block_fwd:  M_out [n_dst, F_in] dense (16-byte aligned, kept for
+ *     the backward pass), Hnext_out [n_dst, F_out] with leading dimension
+ *     ld_next; W [F_in, F_out] and bias fp32.
+ *   tma_gcn_block_bwd:  dW = M^T dZ, dbias = 1^T dZ with dZ = dHnext (.)
+ *     act'(Hnext); dH_out [n_src, F_in] (leading dimension ldh; NULL = not
+ *     wanted) = (A_S + I)^T diag(c) dZ W^T.  blk_row [max_entries]: the dst row
+ *     of every block entry, as tma_neighbor_sample wrote it.
+ * Workspace of the backward pass: tma_gcn_block_bwd_workspace_bytes(n_dst,
+ * n_src, max_entries, F_in, F_out, dtype, dH_out != NULL), 256-byte aligned.
+ * ---------------------------------------------------------------------- */
+int tma_gcn_block_norm(int64_t n_dst, const int32_t *blk_rowptr, float *c_out, tma_stream_t stream);
+
+int tma_gcn_block_fwd(int64_t n_dst, int64_t n_src, const int32_t *blk_rowptr, const int32_t *blk_col,
+                      const float *c_norm, const void *H, int64_t ldh, int32_t F_in,
+                      const float *W, const float *bias, int32_t F_out, int32_t act, int32_t dtype,
+                      void *M_out, void *Hnext_out, int64_t ld_next, tma_stream_t stream);
+
+size_t tma_gcn_block_bwd_workspace_bytes(int64_t n_dst, int64_t n_src, int64_t max_entries,
+                                         int32_t F_in, int32_t F_out, int32_t dtype, int32_t need_dH);
+
+int tma_gcn_block_bwd(int64_t n_dst, int64_t n_src, int64_t max_entries,
+                      const int32_t *blk_rowptr, const int32_t *blk_col, const int32_t *blk_row,
+                      const float *c_norm, const void *M, const void *Hnext, const void *dHnext,
+                      int64_t ld_next, const float *W, int32_t F_in, int32_t F_out,
+                      int32_t act, int32_t dtype, float *dW, float *dbias,
+                      void *dH_out, int64_t ldh, void *ws, size_t ws_bytes, tma_stream_t stream);
+
+/* ------------------------------------------------------------------------
  * Losses on the last layer's output.
  * tma_softmax_ce: mean softmax cross-entropy over the n local nodes (reading
  *   taken for workloads with class labels); loss_out[0] fp32 (device),

@@ -34,6 +34,7 @@ EXPORTS = (
     "tma_bce_logits",
     "tma_neighbor_sample_workspace_bytes", "tma_neighbor_sample", "tma_mfg_relabel_workspace_bytes", "tma_mfg_relabel",
     "tma_block_inv_deg", "tma_sage_block_fwd", "tma_sage_block_bwd_workspace_bytes", "tma_sage_block_bwd",
+    "tma_gcn_block_norm", "tma_gcn_block_fwd", "tma_gcn_block_bwd_workspace_bytes", "tma_gcn_block_bwd",
     "tma_loss_workspace_bytes", "tma_softmax_ce", "tma_sigmoid_l2", "tma_sgd_step", "tma_adam_step", "tma_average",
     "tma_gather_rows", "tma_profile_begin", "tma_profile_end", "tma_profile_count", "tma_profile_entry",
     "tma_profile_sequence_count", "tma_profile_sequence_entry",
@@ -61,7 +62,8 @@ def lib() -> C.CDLL:
                      "tma_dense_bwd_workspace_bytes", "tma_gcn_layer_bwd_workspace_bytes",
                      "tma_pair_product_bwd_workspace_bytes", "tma_prelu_bwd_workspace_bytes",
                      "tma_bce_logits_workspace_bytes", "tma_neighbor_sample_workspace_bytes",
-                     "tma_mfg_relabel_workspace_bytes", "tma_sage_block_bwd_workspace_bytes"):
+                     "tma_mfg_relabel_workspace_bytes", "tma_sage_block_bwd_workspace_bytes",
+                     "tma_gcn_block_bwd_workspace_bytes"):
             getattr(L, name).restype = C.c_size_t
         L.tma_mix64.restype = C.c_uint64
         L.tma_mix64.argtypes = [C.c_uint64, C.c_uint64]
@@ -714,6 +716,74 @@ def tma_sage_block_bwd(n_dst: int, n_src: int, max_entries: int, blk_rowptr, blk
         C.c_int32(F_in), C.c_int32(F_out), C.c_int32(act), C.c_int32(dt), _ptr(dW_self, torch.float32, "dW_self"),
         _ptr(dW_neigh, torch.float32, "dW_neigh"), _ptr(dbias, torch.float32, "dbias"),
         C.c_void_p(dH_out.data_ptr() if dH_out is not None else 0), _ptr(ws), C.c_size_t(ws.numel()), _stream(stream)))
+    return dH_out
+
+
+def tma_gcn_block_norm(blk_rowptr, n_dst: int, out=None, stream=None):
+    """c_v = 1 / (|S(v)| + 1) for the block's first n_dst rows."""
+    if out is None:
+        out = torch.empty(max(n_dst, 1), dtype=torch.float32, device=blk_rowptr.device)
+    if out.numel() < n_dst or blk_rowptr.numel() < n_dst + 1:
+        raise TmaError("tma_gcn_block_norm: a buffer has too few elements")
+    _check(lib().tma_gcn_block_norm(C.c_int64(n_dst), _ptr(blk_rowptr, torch.int32), _ptr(out, torch.float32),
+                                    _stream(stream)))
+    return out
+
+
+def tma_gcn_block_fwd(n_dst: int, n_src: int, blk_rowptr, blk_col, c_norm, H, W, bias, act: int, M_out, Hnext_out,
+                      stream=None):
+    """GCN layer on a bipartite block; H, M_out, Hnext_out are buffers with at least n_src / n_dst / n_dst rows."""
+    _, F_in, ldh = _rows_ld(H, "H")
+    F_out = W.shape[1]
+    if H.shape[0] < n_src or M_out.shape[0] < n_dst or Hnext_out.shape[0] < n_dst:
+        raise TmaError("tma_gcn_block_fwd: a buffer has too few rows")
+    if tuple(W.shape) != (F_in, F_out) or bias.numel() != F_out:
+        raise TmaError("tma_gcn_block_fwd: weight shapes do not match H")
+    if M_out.shape[1] != F_in or Hnext_out.shape[1] != F_out or not M_out.is_contiguous():
+        raise TmaError("tma_gcn_block_fwd: M_out must be a dense [rows, F_in] buffer, Hnext_out [rows, F_out]")
+    _, _, ld_next = _rows_ld(Hnext_out, "Hnext_out")
+    _check(lib().tma_gcn_block_fwd(
+        C.c_int64(n_dst), C.c_int64(n_src), _ptr(blk_rowptr, torch.int32), _ptr(blk_col, torch.int32),
+        _ptr(c_norm, torch.float32), C.c_void_p(H.data_ptr()), C.c_int64(ldh), C.c_int32(F_in),
+        _ptr(W, torch.float32, "W"), _ptr(bias, torch.float32, "bias"), C.c_int32(F_out), C.c_int32(act),
+        C.c_int32(_feat_dtype(H)), C.c_void_p(M_out.data_ptr()), C.c_void_p(Hnext_out.data_ptr()), C.c_int64(ld_next),
+        _stream(stream)))
+    return M_out, Hnext_out
+
+
+def tma_gcn_block_bwd_workspace_bytes(n_dst: int, n_src: int, max_entries: int, F_in: int, F_out: int, dtype: int,
+                                      need_dH: bool) -> int:
+    return int(lib().tma_gcn_block_bwd_workspace_bytes(C.c_int64(n_dst), C.c_int64(n_src), C.c_int64(max_entries),
+                                                       C.c_int32(F_in), C.c_int32(F_out), C.c_int32(dtype),
+                                                       C.c_int32(1 if need_dH else 0)))
+
+
+def tma_gcn_block_bwd(n_dst: int, n_src: int, max_entries: int, blk_rowptr, blk_col, blk_row, c_norm, M, Hnext, dHnext,
+                      W, act: int, dW, dbias, dH_out=None, ws=None, stream=None):
+    """Backward of the GCN layer on a bipartite block; dH_out (buffer with at least n_src rows of F_in) or None."""
+    F_in, F_out = W.shape
+    _, _, ld_next = _rows_ld(dHnext, "dHnext")
+    if act == TMA_ACT_RELU:
+        _same_ld(Hnext, dHnext, "tma_gcn_block_bwd: Hnext / dHnext")
+    if M.shape[0] < n_dst or M.shape[1] != F_in or not M.is_contiguous():
+        raise TmaError("tma_gcn_block_bwd: M must be the dense [rows, F_in] buffer of the forward pass")
+    ldh = 0
+    if dH_out is not None:
+        rows, Fh, ldh = _rows_ld(dH_out, "dH_out")
+        if rows < n_src or Fh != F_in or dH_out.dtype != M.dtype:
+            raise TmaError("tma_gcn_block_bwd: dH_out needs n_src rows of F_in elements in the features' dtype")
+    dt = _feat_dtype(M)
+    if ws is None:
+        ws = _workspace(tma_gcn_block_bwd_workspace_bytes(n_dst, n_src, max_entries, F_in, F_out, dt, dH_out is not None),
+                        M.device, stream)
+    _check(lib().tma_gcn_block_bwd(
+        C.c_int64(n_dst), C.c_int64(n_src), C.c_int64(max_entries), _ptr(blk_rowptr, torch.int32),
+        _ptr(blk_col, torch.int32), _ptr(blk_row, torch.int32), _ptr(c_norm, torch.float32), C.c_void_p(M.data_ptr()),
+        C.c_void_p(Hnext.data_ptr() if Hnext is not None else 0), C.c_void_p(dHnext.data_ptr()), C.c_int64(ld_next),
+        _ptr(W, torch.float32, "W"), C.c_int32(F_in), C.c_int32(F_out), C.c_int32(act), C.c_int32(dt),
+        _ptr(dW, torch.float32, "dW"), _ptr(dbias, torch.float32, "dbias"),
+        C.c_void_p(dH_out.data_ptr() if dH_out is not None else 0), C.c_int64(ldh), _ptr(ws), C.c_size_t(ws.numel()),
+        _stream(stream)))
     return dH_out
 
 

@@ -308,6 +308,48 @@ static BlockBwdWorkspace plan_block_bwd(int64_t n_dst, int64_t n_src, int64_t ma
     return w;
 }
 
+// Transpose of a block: for every source node the dst rows that sampled it, in ascending order (rowptr_T [n_src + 1],
+// sorted [entries]); blk_row = the dst row of every entry of the block.  deg: 2 * n_src + 1 int32 of
+// scratch, unsorted: max_entries int32 of scratch.
+static int transpose_block(const char *fn, int64_t n_dst, int64_t n_src, int64_t max_entries, const int32_t *blk_rowptr,
+                           const int32_t *blk_col, const int32_t *blk_row, int32_t *deg, int32_t *rowptr_T, int32_t *unsorted,
+                           int32_t *sorted, void *scan_ws, hipStream_t s)
+{
+    const int32_t *d_items = blk_rowptr ? blk_rowptr + n_dst : nullptr;
+    int32_t *cursor = deg + n_src;
+    {
+        TMA_TIMED("transpose_count", s);
+        hipLaunchKernelGGL(fill_i32_kernel, dim3(capped_blocks(2 * n_src + 1)), dim3(256), 0, s, 2 * n_src + 1, deg, 0);
+        if (max_entries > 0 && n_dst > 0)
+            hipLaunchKernelGGL(transpose_count_kernel, dim3(blocks_for(max_entries)), dim3(256), 0, s, max_entries, d_items,
+                               blk_col, deg);
+    }
+    if (int rc = check_launch(fn)) return rc;
+    if (int rc = launch_exclusive_scan_i32(n_src, deg, rowptr_T, scan_ws, s)) return rc;
+    if (max_entries > 0 && n_dst > 0) {
+        {
+            TMA_TIMED("transpose_fill", s);
+            hipLaunchKernelGGL(transpose_fill_kernel, dim3(blocks_for(max_entries)), dim3(256), 0, s, max_entries, d_items,
+                               blk_col, rowptr_T, cursor, unsorted);
+        }
+        if (int rc = launch_sort_lists(n_src, rowptr_T, unsorted, sorted, deg, deg + 2 * n_src, s)) return rc;
+        TMA_TIMED("transpose_rows", s);
+        hipLaunchKernelGGL(entries_to_rows_kernel, dim3(blocks_for(max_entries)), dim3(256), 0, s, max_entries, d_items,
+                           sorted, blk_row);
+        if (int rc = check_launch(fn)) return rc;
+    }
+    return TMA_OK;
+}
+
+// The same workspace layout with the weight-gradient scratch of the one-matrix (GCN) layer.
+static BlockBwdWorkspace plan_gcn_block_bwd(int64_t n_dst, int64_t n_src, int64_t max_entries, int32_t F_in, int32_t F_out,
+                                            int32_t dtype, bool need_dH)
+{
+    BlockBwdWorkspace w = plan_block_bwd(n_dst, n_src, max_entries, F_in, F_out, dtype, need_dH);
+    w.weight_bytes = dense_gemm_bwd_weight_workspace_bytes(n_dst, F_in, F_out);
+    return w;
+}
+
 }  // namespace tma
 
 extern "C" size_t tma_neighbor_sample_workspace_bytes(int64_t n_dst)
@@ -504,30 +546,9 @@ extern "C" int tma_sage_block_bwd(int64_t n_dst, int64_t n_src, int64_t max_entr
     if (int rc = launch_sage_gemm_bwd_data(n_dst, dHnext, Hnext, ld_next, inv_deg, W_self, W_neigh, F_in, F_out, act, dtype,
                                            dH_out, ldh, dMs, s))
         return rc;
-    // transpose of the block: source node -> the dst rows that sampled it, in ascending order
-    const int32_t *d_items = blk_rowptr ? blk_rowptr + n_dst : nullptr;
-    int32_t *cursor = deg + n_src;
-    {
-        TMA_TIMED("transpose_count", s);
-        hipLaunchKernelGGL(fill_i32_kernel, dim3(capped_blocks(2 * n_src + 1)), dim3(256), 0, s, 2 * n_src + 1, deg, 0);
-        if (max_entries > 0 && n_dst > 0)
-            hipLaunchKernelGGL(transpose_count_kernel, dim3(blocks_for(max_entries)), dim3(256), 0, s, max_entries, d_items,
-                               blk_col, deg);
-    }
-    if (int rc = check_launch(fn)) return rc;
-    if (int rc = launch_exclusive_scan_i32(n_src, deg, rowptr_T, scan_ws, s)) return rc;
-    if (max_entries > 0 && n_dst > 0) {
-        {
-            TMA_TIMED("transpose_fill", s);
-            hipLaunchKernelGGL(transpose_fill_kernel, dim3(blocks_for(max_entries)), dim3(256), 0, s, max_entries, d_items,
-                               blk_col, rowptr_T, cursor, unsorted);
-        }
-        if (int rc = launch_sort_lists(n_src, rowptr_T, unsorted, sorted, deg, deg + 2 * n_src, s)) return rc;
-        TMA_TIMED("transpose_rows", s);
-        hipLaunchKernelGGL(entries_to_rows_kernel, dim3(blocks_for(max_entries)), dim3(256), 0, s, max_entries, d_items,
-                           sorted, blk_row);
-        if (int rc = check_launch(fn)) return rc;
-    }
+    if (int rc = transpose_block(fn, n_dst, n_src, max_entries, blk_rowptr, blk_col, blk_row, deg, rowptr_T, unsorted, sorted,
+                                 scan_ws, s))
+        return rc;
     // dH += A^T (D^-1 dM): on top of the product for the dst rows, plain for the rows that are sources only
     const int64_t n_rows_dm = n_dst > 0 ? n_dst : 1;
     if (int rc = launch_spmm(n_dst, rowptr_T, sorted, nullptr, dMs, F_in, F_in, dtype, dH_out, ldh, true, s, n_rows_dm))
@@ -535,4 +556,112 @@ extern "C" int tma_sage_block_bwd(int64_t n_dst, int64_t n_src, int64_t max_entr
     char *tail = static_cast<char *>(dH_out) + size_t(n_dst) * size_t(ldh) * elem_size(dtype);
     return launch_spmm(n_src - n_dst, rowptr_T + n_dst, sorted, nullptr, dMs, F_in, F_in, dtype, tail, ldh, false, s,
                        n_rows_dm);
+}
+
+// ---- GCN layer on a block: m_v = (h_v + sum over the sampled neighbours) / (|S(v)| + 1) ---------------------------
+__global__ __launch_bounds__(256) void gcn_block_norm_kernel(int64_t n_dst, const int32_t *__restrict__ blk_rowptr,
+                                                             float *__restrict__ out)
+{
+    const int64_t v = int64_t(blockIdx.x) * 256 + threadIdx.x;
+    if (v < n_dst) out[v] = 1.0f / float(blk_rowptr[v + 1] - blk_rowptr[v] + 1);
+}
+
+extern "C" int tma_gcn_block_norm(int64_t n_dst, const int32_t *blk_rowptr, float *c_out, tma_stream_t stream)
+{
+    using namespace tma;
+    const char *fn = "tma_gcn_block_norm";
+    TMA_REQUIRE(n_dst >= 0 && n_dst <= INT32_MAX, TMA_ERR_INVALID_ARG, "%s: n_dst", fn);
+    if (n_dst == 0) return TMA_OK;
+    TMA_REQUIRE(blk_rowptr && c_out, TMA_ERR_INVALID_ARG, "%s: NULL argument", fn);
+    hipStream_t s = as_stream(stream);
+    TMA_TIMED("gcn_block_norm", s);
+    hipLaunchKernelGGL(gcn_block_norm_kernel, dim3(blocks_for(n_dst)), dim3(256), 0, s, n_dst, blk_rowptr, c_out);
+    return check_launch(fn);
+}
+
+extern "C" int tma_gcn_block_fwd(int64_t n_dst, int64_t n_src, const int32_t *blk_rowptr, const int32_t *blk_col,
+                                 const float *c_norm, const void *H, int64_t ldh, int32_t F_in, const float *W,
+                                 const float *bias, int32_t F_out, int32_t act, int32_t dtype, void *M_out, void *Hnext_out,
+                                 int64_t ld_next, tma_stream_t stream)
+{
+    using namespace tma;
+    const char *fn = "tma_gcn_block_fwd";
+    TMA_REQUIRE(n_dst >= 0 && n_dst <= n_src && n_src <= INT32_MAX, TMA_ERR_INVALID_ARG, "%s: need 0 <= n_dst <= n_src", fn);
+    TMA_REQUIRE(F_in >= 1 && F_out >= 1 && F_in <= (1 << 20) && F_out <= (1 << 20), TMA_ERR_BAD_SHAPE,
+                "%s: F_in=%d F_out=%d", fn, F_in, F_out);
+    TMA_REQUIRE(act == TMA_ACT_NONE || act == TMA_ACT_RELU, TMA_ERR_INVALID_ARG, "%s: act %d", fn, act);
+    TMA_REQUIRE(dtype == TMA_F32 || dtype == TMA_BF16, TMA_ERR_UNSUPPORTED_DTYPE, "%s: dtype %d", fn, dtype);
+    if (n_dst == 0) return TMA_OK;
+    TMA_REQUIRE(blk_rowptr && c_norm && H && W && bias && M_out && Hnext_out, TMA_ERR_INVALID_ARG, "%s: NULL argument", fn);
+    TMA_REQUIRE(ldh >= F_in && ld_next >= F_out && H != M_out, TMA_ERR_BAD_SHAPE, "%s: leading dimensions / aliasing", fn);
+    TMA_REQUIRE(aligned(M_out, 16), TMA_ERR_INVALID_ARG, "%s: M_out must be 16-byte aligned", fn);
+    hipStream_t s = as_stream(stream);
+    // one pass over the sampled rows: neighbours and the own row summed, the sum scaled by 1 / (|S(v)| + 1)
+    if (int rc = launch_spmm_combine(n_dst, blk_rowptr, blk_col, c_norm, H, ldh, F_in, dtype, M_out, F_in, false, H, ldh,
+                                     nullptr, F_in, false, true, nullptr, s, n_src))
+        return rc;
+    return launch_dense_gemm_fwd(n_dst, M_out, F_in, F_in, W, bias, nullptr, F_out, F_out, act, dtype, Hnext_out, ld_next, s);
+}
+
+extern "C" size_t tma_gcn_block_bwd_workspace_bytes(int64_t n_dst, int64_t n_src, int64_t max_entries, int32_t F_in,
+                                                    int32_t F_out, int32_t dtype, int32_t need_dH)
+{
+    if (n_dst < 0 || n_src < n_dst || max_entries < 0 || F_in < 1 || F_out < 1) return 0;
+    return tma::plan_gcn_block_bwd(n_dst, n_src, max_entries, F_in, F_out, dtype, need_dH != 0).total();
+}
+
+extern "C" int tma_gcn_block_bwd(int64_t n_dst, int64_t n_src, int64_t max_entries, const int32_t *blk_rowptr,
+                                 const int32_t *blk_col, const int32_t *blk_row, const float *c_norm, const void *M,
+                                 const void *Hnext, const void *dHnext, int64_t ld_next, const float *W, int32_t F_in,
+                                 int32_t F_out, int32_t act, int32_t dtype, float *dW, float *dbias, void *dH_out,
+                                 int64_t ldh, void *ws, size_t ws_bytes, tma_stream_t stream)
+{
+    using namespace tma;
+    const char *fn = "tma_gcn_block_bwd";
+    TMA_REQUIRE(n_dst >= 0 && n_dst <= n_src && n_src <= INT32_MAX && max_entries >= 0 && max_entries <= INT32_MAX,
+                TMA_ERR_INVALID_ARG, "%s: need 0 <= n_dst <= n_src", fn);
+    TMA_REQUIRE(F_in >= 1 && F_out >= 1 && F_in <= (1 << 20) && F_out <= (1 << 20), TMA_ERR_BAD_SHAPE,
+                "%s: F_in=%d F_out=%d", fn, F_in, F_out);
+    TMA_REQUIRE(act == TMA_ACT_NONE || act == TMA_ACT_RELU, TMA_ERR_INVALID_ARG, "%s: act %d", fn, act);
+    TMA_REQUIRE(dtype == TMA_F32 || dtype == TMA_BF16, TMA_ERR_UNSUPPORTED_DTYPE, "%s: dtype %d", fn, dtype);
+    TMA_REQUIRE(dW && dbias, TMA_ERR_INVALID_ARG, "%s: gradient output is NULL", fn);
+    TMA_REQUIRE(ws && aligned(ws, 256), TMA_ERR_INVALID_ARG, "%s: workspace NULL or not 256-byte aligned", fn);
+    const bool need_dH = dH_out != nullptr;
+    const BlockBwdWorkspace w = plan_gcn_block_bwd(n_dst, n_src, max_entries, F_in, F_out, dtype, need_dH);
+    TMA_REQUIRE(ws_bytes >= w.total(), TMA_ERR_WORKSPACE_TOO_SMALL, "%s: workspace %zu < %zu bytes", fn, ws_bytes,
+                w.total());
+    if (n_dst > 0) {
+        TMA_REQUIRE(M && dHnext && W, TMA_ERR_INVALID_ARG, "%s: NULL argument", fn);
+        TMA_REQUIRE(act == TMA_ACT_NONE || Hnext, TMA_ERR_INVALID_ARG, "%s: Hnext is required with ReLU", fn);
+        TMA_REQUIRE(!need_dH || (blk_rowptr && c_norm && (max_entries == 0 || (blk_col && blk_row))), TMA_ERR_INVALID_ARG,
+                    "%s: block is NULL", fn);
+        TMA_REQUIRE(ld_next >= F_out && (!need_dH || ldh >= F_in), TMA_ERR_BAD_SHAPE, "%s: ldh < F_in or ld_next < F_out", fn);
+    }
+    hipStream_t s = as_stream(stream);
+    char *base = static_cast<char *>(ws);
+    void *P = base;      // c_v (dZ W^T)_v, one row per dst node
+    int32_t *deg = reinterpret_cast<int32_t *>(base + w.dm_bytes);
+    int32_t *rowptr_T = reinterpret_cast<int32_t *>(base + w.dm_bytes + w.deg_bytes);
+    int32_t *unsorted = reinterpret_cast<int32_t *>(base + w.dm_bytes + w.deg_bytes + w.rowptr_bytes);
+    int32_t *sorted = reinterpret_cast<int32_t *>(base + w.dm_bytes + w.deg_bytes + w.rowptr_bytes + w.list_bytes);
+    void *scan_ws = base + w.dm_bytes + w.deg_bytes + w.rowptr_bytes + 2 * w.list_bytes;
+    void *wws = base + w.dm_bytes + w.deg_bytes + w.rowptr_bytes + 2 * w.list_bytes + w.scan_bytes;
+
+    // dW = M^T dZ, db = 1^T dZ
+    if (int rc = launch_dense_gemm_bwd_weight(n_dst, M, F_in, dHnext, Hnext, ld_next, F_in, F_out, act, dtype, dW, dbias,
+                                              wws, w.weight_bytes, s))
+        return rc;
+    if (!need_dH || n_src == 0) return TMA_OK;
+    if (int rc = launch_dense_gemm_bwd_data(n_dst, dHnext, Hnext, ld_next, W, F_in, F_out, act, dtype, c_norm, P, F_in, s))
+        return rc;
+    if (int rc = transpose_block(fn, n_dst, n_src, max_entries, blk_rowptr, blk_col, blk_row, deg, rowptr_T, unsorted, sorted,
+                                 scan_ws, s))
+        return rc;
+    // dH = (A_S + I)^T P: the dst rows take their own row of P on top of the gathered ones, the others gather only
+    const int64_t n_rows_p = n_dst > 0 ? n_dst : 1;
+    if (int rc = launch_spmm_combine(n_dst, rowptr_T, sorted, nullptr, P, F_in, F_in, dtype, dH_out, ldh, false, P, F_in,
+                                     nullptr, F_in, false, false, nullptr, s, n_rows_p))
+        return rc;
+    char *tail = static_cast<char *>(dH_out) + size_t(n_dst) * size_t(ldh) * elem_size(dtype);
+    return launch_spmm(n_src - n_dst, rowptr_T + n_dst, sorted, nullptr, P, F_in, F_in, dtype, tail, ldh, false, s, n_rows_p);
 }

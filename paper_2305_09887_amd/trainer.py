@@ -319,16 +319,19 @@ class SampledLinkTrainer(LocalTrainer):
     normalisation followed by PReLU.  All buffers are sized once for the largest possible level
     (3 * batch_size nodes at the top, times 1 + fanout per layer, capped by the local node count); the level sizes
     of a step come back from the device, one wait per level.  The neighbour sampler's seed for step t and layer l is
-    SplitMix64(batch_seed, 64 t + l).
+    SplitMix64(batch_seed, 64 t + l).  ``encoder``: "sage" (W_self, W_neigh, b per layer) or "gcn" (W, b per layer;
+    on a block the layer averages over the sampled neighbours and the node itself).
     """
 
     def __init__(self, rowptr, colidx, nnz, X, dims, decoder_dims, fanouts, batch_size, batch_seed=0, params=None,
-                 decoder_params=None, stream=None, optimizer="sgd", norm_act=False, nnz_cap=None):
+                 decoder_params=None, stream=None, optimizer="sgd", norm_act=False, nnz_cap=None, encoder="sage"):
         if len(fanouts) != len(dims) - 1:
             raise B.TmaError("SampledLinkTrainer: one fan-out per layer")
         if colidx.numel() < nnz or (nnz_cap is not None and nnz_cap < nnz):
             raise B.TmaError("SampledLinkTrainer: nnz entries must be there in colidx, and nnz_cap >= nnz")
-        self.norm_act, self.encoder, self.n_lin = bool(norm_act), "sage", 3
+        if encoder not in ("sage", "gcn"):
+            raise B.TmaError("SampledLinkTrainer: encoder must be 'sage' or 'gcn'")
+        self.norm_act, self.encoder, self.n_lin = bool(norm_act), encoder, 3 if encoder == "sage" else 2
         if optimizer not in ("sgd", "adam"):
             raise B.TmaError("SampledLinkTrainer: optimizer must be 'sgd' or 'adam'")
         self.optimizer = optimizer
@@ -346,7 +349,7 @@ class SampledLinkTrainer(LocalTrainer):
         if X.shape[1] != dims[0] or not X.is_contiguous():
             raise B.TmaError("SampledLinkTrainer: X must be a dense [n, dims[0]] table")
 
-        self.n_params = sum(2 * fi * fo + fo for fi, fo in zip(dims[:-1], dims[1:]))
+        self.n_params = sum((self.n_lin - 1) * fi * fo + fo for fi, fo in zip(dims[:-1], dims[1:]))
         if self.norm_act:
             self.n_params += sum(2 * fo + 1 for fo in dims[1:-1])
         self.n_params += sum(a * b for a, b in zip(self.dec_dims[:-1], self.dec_dims[1:])) + len(self.dec_dims) - 2
@@ -388,8 +391,8 @@ class SampledLinkTrainer(LocalTrainer):
         ws_bytes = max(
             max(B.tma_neighbor_sample_workspace_bytes(cap[l + 1]) for l in range(L)),
             B.tma_mfg_relabel_workspace_bytes(self.n),
-            max(B.tma_sage_block_bwd_workspace_bytes(cap[l + 1], cap[l], self.ecap[l], dims[l], dims[l + 1], dt, l > 0)
-                for l in range(L)),
+            max((B.tma_sage_block_bwd_workspace_bytes if encoder == "sage" else B.tma_gcn_block_bwd_workspace_bytes)(
+                cap[l + 1], cap[l], self.ecap[l], dims[l], dims[l + 1], dt, l > 0) for l in range(L)),
             B.tma_pair_product_bwd_workspace_bytes(cap[L], Bn, dd[0], dt), B.tma_prelu_bwd_workspace_bytes(),
             B.tma_bce_logits_workspace_bytes(),
             max(B.tma_dense_bwd_workspace_bytes(2 * Bn, a, b) for a, b in zip(dd[:-1], dd[1:])))
@@ -426,44 +429,55 @@ class SampledLinkTrainer(LocalTrainer):
             _, self.count[l] = B.tma_mfg_relabel(self.n, self.nodes[l + 1], n_dst, self.blk_col[l], self.ecap[l],
                                                  d_items=self.blk_rowptr[l][n_dst:n_dst + 1], src_out=self.nodes[l],
                                                  ws=self.ws, stream=st)
-            B.tma_block_inv_deg(self.blk_rowptr[l], n_dst, out=self.blk_inv_deg[l], stream=st)
+            if self.encoder == "sage":
+                B.tma_block_inv_deg(self.blk_rowptr[l], n_dst, out=self.blk_inv_deg[l], stream=st)
+            else:
+                B.tma_gcn_block_norm(self.blk_rowptr[l], n_dst, out=self.blk_inv_deg[l], stream=st)
         B.tma_gather_rows(self.nodes[0][:self.count[0]], self.X, out=self.H[0][:self.count[0]], stream=st)
+
+    def _block_fwd(self, l, act, out):
+        block_fwd = B.tma_sage_block_fwd if self.encoder == "sage" else B.tma_gcn_block_fwd
+        block_fwd(self.count[l + 1], self.count[l], self.blk_rowptr[l], self.blk_col[l], self.blk_inv_deg[l], self.H[l],
+                  *self.layers[l][:self.n_lin], act, self.M[l], out, stream=self.stream)
 
     def forward(self):
         for l in range(self.L):
-            ws_, wn, b = self.layers[l][:3]
             n_dst = self.count[l + 1]
             if self.norm_act and l < self.L - 1:
-                gamma, beta, slope = self.layers[l][3:]
-                B.tma_sage_block_fwd(n_dst, self.count[l], self.blk_rowptr[l], self.blk_col[l], self.blk_inv_deg[l], self.H[l],
-                                     ws_, wn, b, B.TMA_ACT_NONE, self.M[l], self.Z[l + 1], stream=self.stream)
+                gamma, beta, slope = self.layers[l][self.n_lin:]
+                self._block_fwd(l, B.TMA_ACT_NONE, self.Z[l + 1])
                 B.tma_layernorm_prelu_fwd(self.Z[l + 1][:n_dst], gamma, beta, slope, out=self.H[l + 1][:n_dst],
                                           stream=self.stream)
                 continue
-            act = B.TMA_ACT_RELU if l < self.L - 1 else B.TMA_ACT_NONE
-            B.tma_sage_block_fwd(n_dst, self.count[l], self.blk_rowptr[l], self.blk_col[l], self.blk_inv_deg[l], self.H[l],
-                                 ws_, wn, b, act, self.M[l], self.H[l + 1], stream=self.stream)
+            self._block_fwd(l, B.TMA_ACT_RELU if l < self.L - 1 else B.TMA_ACT_NONE, self.H[l + 1])
         return self.H[self.L][:self.count[self.L]]
 
     def backward(self):
         n_top = self.count[self.L]
         self._decoder_backward(self.H[self.L][:n_top], self.dH[self.L][:n_top])
         for l in range(self.L - 1, -1, -1):
-            ws_, wn = self.layers[l][:2]
-            dws, dwn, db = self.grads[l][:3]
             act = B.TMA_ACT_RELU if l < self.L - 1 else B.TMA_ACT_NONE
             out_act, n_dst = self.H[l + 1], self.count[l + 1]
             if self.norm_act and l < self.L - 1:
-                gamma, beta, slope = self.layers[l][3:]
-                dgamma, dbeta, dslope = self.grads[l][3:]
+                gamma, beta, slope = self.layers[l][self.n_lin:]
+                dgamma, dbeta, dslope = self.grads[l][self.n_lin:]
                 # dL/dZ replaces dL/dH' in place; the layer below then runs without an activation of its own
                 B.tma_layernorm_prelu_bwd(self.Z[l + 1][:n_dst], self.dH[l + 1][:n_dst], gamma, beta, slope,
                                           dZ_out=self.dH[l + 1][:n_dst], dgamma=dgamma, dbeta=dbeta, dslope=dslope,
                                           ws=self.ws, stream=self.stream)
                 act, out_act = B.TMA_ACT_NONE, self.Z[l + 1]
-            B.tma_sage_block_bwd(n_dst, self.count[l], self.ecap[l], self.blk_rowptr[l], self.blk_col[l], self.blk_row[l],
-                                 self.blk_inv_deg[l], self.H[l], self.M[l], out_act, self.dH[l + 1], ws_, wn, act, dws, dwn,
-                                 db, dH_out=self.dH[l] if l > 0 else None, ws=self.ws, stream=self.stream)
+            block = (n_dst, self.count[l], self.ecap[l], self.blk_rowptr[l], self.blk_col[l], self.blk_row[l],
+                     self.blk_inv_deg[l])
+            dH_out = self.dH[l] if l > 0 else None
+            if self.encoder == "sage":
+                ws_, wn = self.layers[l][:2]
+                dws, dwn, db = self.grads[l][:3]
+                B.tma_sage_block_bwd(*block, self.H[l], self.M[l], out_act, self.dH[l + 1], ws_, wn, act, dws, dwn, db,
+                                     dH_out=dH_out, ws=self.ws, stream=self.stream)
+            else:
+                dw, db = self.grads[l][:2]
+                B.tma_gcn_block_bwd(*block, self.M[l], out_act, self.dH[l + 1], self.layers[l][0], act, dw, db,
+                                    dH_out=dH_out, ws=self.ws, stream=self.stream)
 
     def step(self, lr: float):
         """One iteration of Alg. 2's loop body on the sampled neighbourhood of one mini-batch."""

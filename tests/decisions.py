@@ -137,6 +137,13 @@ def encoder_bounds(encoder, rowptr, colidx, params, saved, ups, D, q_top=None):
                     nq[int(v)] += x * ws
                     for u in ci[rp[v]:rp[v + 1]]:
                         nq[int(u)] += x * wn / deg[v]
+            elif encoder == "gcn" and per_layer:      # on a block: the mean over the sampled neighbours and the node
+                w = _spec(params[l][0])
+                for v, x in zip(rows, rv):
+                    c = x * w / (deg[v] + 1.0)
+                    nq[int(v)] += c
+                    for u in ci[rp[v]:rp[v + 1]]:
+                        nq[int(u)] += c
             elif encoder == "gcn":
                 w = _spec(params[l][0])
                 s = 1.0 / np.sqrt(deg + 1.0)

@@ -146,10 +146,12 @@ def test_sage_layer_on_a_sampled_block(B, F_in, F_out, fanout, bf16, act):
     dWs, dWn, db = (torch.empty((F_in, F_out), device="cuda"), torch.empty((F_in, F_out), device="cuda"),
                     torch.empty(F_out, device="cuda"))
     dH = torch.full_like(Hd, float("nan"))
+    # the backward pass is given the oracle's layer output (rounded to the storage format: signs survive), so both
+    # sides take the ReLU decisions of the oracle's own Z
+    Hn[:n_dst] = put(want)
     B.tma_sage_block_bwd(n_dst, n_src, len(cols) + 17, rpd, cid, rows, inv, Hd, Md, Hn, gd, dev(Ws), dev(Wn), act, dWs, dWn,
                          db, dH_out=dH)
-    Zs = np.where(host(Hn[:n_dst]) > 0, 1.0, -1.0) if act == 1 else Z
-    wWs, wWn, wb, wH = oracle.sage_layer_bwd(brp, cols, H, M, Zs, g, Ws, Wn, act)
+    wWs, wWn, wb, wH = oracle.sage_layer_bwd(brp, cols, H, M, Z, g, Ws, Wn, act)
     close(host(dWs), wWs, tol, "dW_self")
     close(host(dWn), wWn, tol, "dW_neigh")
     close(host(db), wb, tol, "dbias")
@@ -164,12 +166,84 @@ def test_sage_layer_on_a_sampled_block(B, F_in, F_out, fanout, bf16, act):
     close(host(dWs), wWs, tol, "dW_self without dH")
 
 
-@pytest.mark.parametrize("fanouts,Bn,norm_act", [([5, 5], 512, False), ([10, 25], 300, False), ([10**6, 10**6], 200, False),
-                                                 ([1, 2], 1000, False), ([5, 10], 400, True)])
-def test_sampled_link_prediction_training_steps(B, fanouts, Bn, norm_act):
-    """Three steps of link prediction on sampled message-flow graphs (2-layer SAGE 64-96-32, decoder 32-48-1) on the
-    tiny configuration's part 0: batch, node lists and blocks bit for bit; loss, logits, every gradient and the
-    weights after each SGD step against the oracle."""
+@pytest.mark.parametrize("F_in,F_out,fanout,bf16", [(64, 96, 5, False), (128, 256, 10, False), (256, 47, 3, False),
+                                                    (100, 64, 25, False), (128, 128, 10, True)])
+@pytest.mark.parametrize("act", [0, 1])
+def test_gcn_layer_on_a_sampled_block(B, F_in, F_out, fanout, bf16, act):
+    """The GCN layer in its block form (mean over the sampled neighbours and the node itself): aggregate, output,
+    and every gradient against the oracle; rows of the buffers past the block stay untouched."""
+    brp, cols, n_dst, n_src, H, W, _, b, g = _block_case(F_in, F_out, fanout, seed=F_in + F_out + 1)
+    tol = 2e-2 if bf16 else 1e-4
+    if bf16:
+        H, g = synth.round_bf16(H), synth.round_bf16(g)
+    dt = torch.bfloat16 if bf16 else torch.float32
+    put = (lambda a: dev_bf16(a)) if bf16 else (lambda a: dev(a))
+    Hd = B._padded(n_src + 5, F_in, dt, "cuda")
+    Hd[:n_src] = put(H)
+    gd = B._padded(n_dst + 5, F_out, dt, "cuda")
+    gd[:n_dst] = put(g)
+    Md = torch.empty((n_dst + 5, F_in), dtype=dt, device="cuda")
+    Hn = B._padded(n_dst + 5, F_out, dt, "cuda")
+    rpd, cid = dev(brp), dev(cols)
+    rows = dev(np.repeat(np.arange(n_dst, dtype=np.int32), np.diff(brp)))
+    c = B.tma_gcn_block_norm(rpd, n_dst)
+    np.testing.assert_array_equal(c.cpu().numpy()[:n_dst], (1.0 / (np.diff(brp) + 1.0)).astype(np.float32))
+    B.tma_gcn_block_fwd(n_dst, n_src, rpd, cid, c, Hd, dev(W), dev(b), act, Md, Hn)
+    M, Z, want = oracle.gcn_block_layer_fwd(brp, cols, H, W, b, act)
+    close(host(Md[:n_dst]), M, tol, "M")
+    close(host(Hn[:n_dst]), want, tol, "Hnext")
+    dW, db = torch.empty((F_in, F_out), device="cuda"), torch.empty(F_out, device="cuda")
+    dH = torch.full((n_src + 5, F_in), float("nan"), dtype=dt, device="cuda")
+    # the saved aggregate and the layer output that the backward pass reads are the oracle's, in the storage format:
+    # both sides then differentiate the same function at the same point, with the oracle's ReLU decisions
+    Md[:n_dst] = put(M)
+    Hn[:n_dst] = put(want)
+    Ms = synth.round_bf16(M.astype(np.float32)) if bf16 else M
+    B.tma_gcn_block_bwd(n_dst, n_src, len(cols) + 17, rpd, cid, rows, c, Md, Hn, gd, dev(W), act, dW, db, dH_out=dH)
+    wW, wb, wH = oracle.gcn_block_layer_bwd(brp, cols, n_src, Ms, Z, g, W, act)
+    close(host(dW), wW, tol, "dW")
+    close(host(db), wb, tol, "dbias")
+    close(host(dH[:n_src]), wH, tol, "dH over all source rows")
+    assert torch.isnan(dH[n_src:]).all()
+    dH2 = torch.empty_like(dH)
+    B.tma_gcn_block_bwd(n_dst, n_src, len(cols) + 17, rpd, cid, rows, c, Md, Hn, gd, dev(W), act, dW, db, dH_out=dH2)
+    assert torch.equal(dH2[:n_src], dH[:n_src])             # fixed summation order: the same bits
+    B.tma_gcn_block_bwd(n_dst, n_src, len(cols), rpd, cid, rows, c, Md, Hn, gd, dev(W), act, dW, db, dH_out=None)
+    close(host(dW), wW, tol, "dW without dH")
+
+
+def test_gcn_block_degenerate_shapes(B):
+    """No destination rows; a block without any entry (every row keeps its own features)."""
+    F_in, F_out = 24, 8
+    rng = np.random.default_rng(3)
+    W, b = dev(synth.glorot(F_in, F_out, rng).astype(np.float32)), dev(np.zeros(F_out, np.float32))
+    H = rng.standard_normal((7, F_in)).astype(np.float32)
+    Hd, Md, Hn = dev(H), torch.empty((7, F_in), device="cuda"), torch.empty((7, F_out), device="cuda")
+    rp0 = dev(np.zeros(8, dtype=np.int32))
+    none = torch.zeros(1, dtype=torch.int32, device="cuda")
+    B.tma_gcn_block_fwd(0, 7, rp0, none, torch.ones(1, device="cuda"), Hd, W, b, 0, Md, Hn)     # nothing to do
+    c = B.tma_gcn_block_norm(rp0, 7)
+    assert bool((c == 1.0).all())
+    B.tma_gcn_block_fwd(7, 7, rp0, none, c, Hd, W, b, 0, Md, Hn)
+    assert torch.equal(Md, Hd)
+    close(host(Hn), H.astype(np.float64) @ host(W), 1e-4, "a block without entries is the dense layer")
+    dW, db, dH = torch.empty((F_in, F_out), device="cuda"), torch.empty(F_out, device="cuda"), torch.empty((7, F_in), device="cuda")
+    g = rng.standard_normal((7, F_out)).astype(np.float32)
+    B.tma_gcn_block_bwd(7, 7, 0, rp0, none, none, c, Md, Hn, dev(g), W, 0, dW, db, dH_out=dH)
+    close(host(dH), g.astype(np.float64) @ host(W).T, 1e-4, "dH")
+    close(host(dW), H.astype(np.float64).T @ g, 1e-4, "dW")
+    torch.cuda.synchronize()
+
+
+@pytest.mark.parametrize("fanouts,Bn,norm_act,encoder", [([5, 5], 512, False, "sage"), ([10, 25], 300, False, "sage"),
+                                                         ([10**6, 10**6], 200, False, "sage"), ([1, 2], 1000, False, "sage"),
+                                                         ([5, 10], 400, True, "sage"), ([5, 5], 512, False, "gcn"),
+                                                         ([10, 25], 300, False, "gcn"), ([10**6, 10**6], 200, False, "gcn"),
+                                                         ([5, 10], 400, True, "gcn")])
+def test_sampled_link_prediction_training_steps(B, fanouts, Bn, norm_act, encoder):
+    """Three steps of link prediction on sampled message-flow graphs (2-layer SAGE or GCN 64-96-32, decoder 32-48-1)
+    on the tiny configuration's part 0: batch, node lists and blocks bit for bit; loss, logits, every gradient and
+    the weights after each SGD step against the oracle."""
     from oracle import model as omodel
     from paper_2305_09887_amd.trainer import SampledLinkTrainer
     N, K, dims, dec_dims = 20_000, 4, [64, 96, 32], [32, 48, 1]
@@ -178,7 +252,7 @@ def test_sampled_link_prediction_training_steps(B, fanouts, Bn, norm_act):
     rng = np.random.default_rng(7)
     enc = []
     for l, layer in enumerate(synth.sage_params(dims, seed=5)):
-        layer = list(layer)
+        layer = list(layer) if encoder == "sage" else [layer[0], layer[2]]
         if norm_act and l < len(dims) - 2:      # the paper's encoder variant: layer normalisation + PReLU
             layer += [rng.normal(1.0, 0.1, dims[l + 1]).astype(np.float32),
                       rng.normal(0.0, 0.1, dims[l + 1]).astype(np.float32), np.array([0.25], dtype=np.float32)]
@@ -189,7 +263,7 @@ def test_sampled_link_prediction_training_steps(B, fanouts, Bn, norm_act):
     rp, ci = sub["rowptr"], sub["colidx"]
     Xo = X[sub["l2g"]]
     tr = SampledLinkTrainer(dev(rp), dev(ci), int(rp[-1]), dev(Xo), dims, dec_dims, fanouts, Bn, batch_seed=99,
-                            params=enc, decoder_params=dec, norm_act=norm_act)
+                            params=enc, decoder_params=dec, norm_act=norm_act, encoder=encoder)
     e_o = [tuple(np.asarray(t, dtype=np.float64) for t in l) for l in enc]
     d_o = [tuple(np.asarray(t, dtype=np.float64) for t in l) for l in dec]
     assert tr.n_params == omodel.flatten(e_o + d_o).size
@@ -199,7 +273,7 @@ def test_sampled_link_prediction_training_steps(B, fanouts, Bn, norm_act):
         batch = oracle.edge_batch(rp, ci, 99, step * Bn, Bn)
         t = {}
         loss_o, ge, gd, z, (rps, cis, inputs, seeds) = omodel.sampled_link_loss_and_grads(
-            rp, ci, Xo, batch, e_o, d_o, fanouts, 99, step, trace=t)
+            rp, ci, Xo, batch, e_o, d_o, fanouts, 99, step, trace=t, encoder=encoder)
         assert tr.count[2] == len(seeds) and np.array_equal(tr.nodes[2].cpu().numpy()[:len(seeds)], seeds)
         for got, want in zip(tr.batch, batch):
             assert np.array_equal(got.cpu().numpy(), np.searchsorted(seeds, want))
@@ -212,7 +286,7 @@ def test_sampled_link_prediction_training_steps(B, fanouts, Bn, norm_act):
         D = decisions.differing(t["pre"], [host(tr.H[1]), None], f"step {step} encoder")
         Dd = decisions.differing(t["dec_pre"], [host(tr.E[1]), None], f"step {step} decoder")
         db, q_top = decisions.decoder_bounds(d_o, t["dsaved"], t["dec_ups"], Dd, t["R"], t["batch_pos"])
-        eb = decisions.encoder_bounds("sage", rps, cis, e_o, t["saved"], t["ups"], D, q_top)
+        eb = decisions.encoder_bounds(encoder, rps, cis, e_o, t["saved"], t["ups"], D, q_top)
         assert abs(loss_g - loss_o) <= 1e-4 * abs(loss_o), f"loss at step {step}"
         close(host(tr.Zd[2]).ravel(), z, 1e-4, f"logits at step {step}")
         for l in range(2):
