@@ -215,6 +215,13 @@ def main():
     ap.add_argument("--graph", action="store_true",
                     help="beside the headline: capture one whole step (assignment, extraction, row gathers, training pass, "
                          "averaging) as a HIP graph and time its replays (node task, SGD)")
+    ap.add_argument("--extraction", type=int, default=0, metavar="NODES",
+                    help="time the assignment + induced-subgraph extraction alone on a Chung-Lu graph of NODES nodes "
+                         "(e.g. 1000000, 100000000) instead of a configured workload")
+    ap.add_argument("--avg-degree", type=float, default=20.0, help="with --extraction: average degree of that graph")
+    ap.add_argument("--fused-assignment", action="store_true",
+                    help="with --extraction: RandomTMA's assignment recomputed inside the extraction "
+                         "(tma_random_subgraph_async) instead of tma_partition + tma_induced_subgraph_async")
     ap.add_argument("--config", type=int, choices=(0, 1, 2, 3, 4), default=1,
                     help="which of the configured workloads: 1 = the headline (default); 0 = the tiny case; 2 = SuperTMA at "
                          "full size; 3 = one trainer's share at billion-edge scale; 4 = 8 trainers on 8 streams with "
@@ -272,6 +279,10 @@ def main():
         torch.cuda.synchronize()
         print(json.dumps({"calibrate_copy_bytes_read": src.numel() * 4, "calibrate_copy_bytes_written": src.numel() * 4,
                           "copies": 5}))
+        return
+    if args.extraction:
+        out, _ = benchlib.run_extraction(args)
+        print(json.dumps(out), flush=True)
         return
     if args.config >= 2:
         if args.task != "node" or args.encoder != "sage" or args.norm_act or args.prefetch or args.dtype != "f32":

@@ -144,6 +144,23 @@ int tma_induced_subgraph_async(int64_t n_nodes, const int64_t *rowptr, const int
                                int64_t cap_n_loc, int64_t cap_nnz_loc, int64_t *d_sizes_out,
                                void *ws, size_t ws_bytes, tma_stream_t stream);
 
+/* RandomTMA's assignment (Sec. 3.2.2) fused into the extraction: the outputs of
+ * tma_partition(n_nodes, NULL, 0, K, seed, part) followed by
+ * tma_induced_subgraph_async(..., part, p, ...), bit for bit, without a part
+ * array.  Node v belongs to the part iff floor(SplitMix64(seed, v) * K / 2^64)
+ * = p, so membership of a neighbour is recomputed (a few integer multiplies)
+ * where the general form looks it up; on graphs whose membership bitmap
+ * outgrows the L2 those look-ups, not the entries, bound the extraction.
+ * Arguments, capacities, workspace and error behaviour as for
+ * tma_induced_subgraph_async; 1 <= K <= 2^30, 0 <= p < K.  (Super-node
+ * assignments go through tma_partition and the general form.) */
+int tma_random_subgraph_async(int64_t n_nodes, const int64_t *rowptr, const int32_t *colidx,
+                              int32_t K, uint64_t seed, int32_t p,
+                              int32_t *g2l_out, int32_t *l2g_out, int32_t *rowptr_loc_out,
+                              int32_t *colidx_loc_out, float *inv_deg_out,
+                              int64_t cap_n_loc, int64_t cap_nnz_loc, int64_t *d_sizes_out,
+                              void *ws, size_t ws_bytes, tma_stream_t stream);
+
 int tma_induced_subgraph_fill(int64_t n_nodes, const int32_t *colidx,
                               const int32_t *g2l, int64_t n_loc, const int32_t *rowptr_loc,
                               int32_t *colidx_loc_out, float *inv_deg_out,

@@ -257,12 +257,14 @@ def run_supertma(args):
     W_global = torch.empty_like(tr.W)
     cap, cap_nnz = n_loc + n_loc // 8 + 1024, nnz_loc + nnz_loc // 4 + 4096
 
-    def step():
+    held = B.tma_induced_subgraph_async(rowptr, colidx, part, p, cap, cap_nnz)
+
+    def step():     # nothing in it waits for the GPU: the extraction leaves its sizes on the device (checked below)
         B.tma_partition(N, K, 24, cluster=block, n_clusters=nb, out=part)
-        sg = B.tma_induced_subgraph(rowptr, colidx, part, p, cap_n_loc=cap, cap_nnz_loc=cap_nnz)
-        B.tma_gather_rows(sg["l2g"], X, out=Xl)
-        B.tma_gather_rows(sg["l2g"], y, out=yl)
-        tr.set_graph(sg["rowptr"], sg["colidx"], sg["inv_deg"], nnz=sg["nnz_loc"])
+        B.tma_induced_subgraph_async(rowptr, colidx, part, p, cap, cap_nnz, out=held)
+        B.tma_gather_rows(held["l2g"][:n_loc], X, out=Xl)
+        B.tma_gather_rows(held["l2g"][:n_loc], y, out=yl)
+        tr.set_graph(held["rowptr"][:n_loc + 1], held["colidx"][:nnz_loc], held["inv_deg"][:n_loc], nnz=nnz_loc)
         tr.step(lr)
         B.tma_average(W_all, W_global_out=W_global, ptr_table=ptrs)
 
@@ -276,6 +278,8 @@ def run_supertma(args):
                                                          K=K, n_params=int(tr.W.numel()))
 
     r = _timed_loop(step, args.steps, args.warmup, PEAK_MFMA_BF16_TFLOPS, factory, traffic)
+    if held["sizes"].cpu().tolist() != [n_loc, nnz_loc]:
+        sys.exit(f"bench.py: the extraction reported sizes {held['sizes'].cpu().tolist()}, expected {[n_loc, nnz_loc]}")
     deg = (sub["rowptr"][1:] - sub["rowptr"][:-1]).float()
     out = _result(args, r, L * nnz_loc, "bf16", {
         "workload": f"configs[2] SuperTMA: stochastic-block graph, 2.4M nodes in 2,400 planted communities of 1,000, "
@@ -305,6 +309,67 @@ def _result(args, r, edges_per_step, dtype, config, tr):
         "final_loss": float(tr.loss.item()) if tr is not None else None, "streams": 1,
         "kernel_sequence": r["sequence"],
     }
+
+
+# ------------------------------------------------------------------------------- the extraction on its own
+def run_extraction(args):
+    """Assignment + node-induced subgraph extraction alone (Sec. 3.2.2; Preliminaries), at a global graph size of the
+    caller's choice: a Chung-Lu power-law graph (gamma 2.1) of --extraction nodes with --avg-degree, drawn on the
+    GPU; K = 8, part 0; the extraction that leaves its sizes on the device.  Step = tma_partition +
+    tma_induced_subgraph_async.  Reports microseconds per step and every kernel against its algorithmic bytes."""
+    from . import synth_torch as st
+    dev = torch.device("cuda:0")
+    N, K, p = int(args.extraction), 8, 0
+    t0 = time.time()
+    rowptr, colidx = st.chung_lu_graph(N, args.avg_degree, 2.1, seed=41, device=dev)
+    torch.cuda.synchronize()
+    nnz_glob = int(rowptr[-1])
+    _log(f"graph drawn on the GPU in {time.time() - t0:.1f}s: N={N} nnz={nnz_glob}")
+    part = torch.empty(N, dtype=torch.int32, device=dev)
+    B.tma_partition(N, K, 44, out=part)
+    first = B.tma_induced_subgraph(rowptr, colidx, part, p)
+    n_loc, nnz_loc = first["n_loc"], first["nnz_loc"]
+    rows_glob = int((rowptr[1:] - rowptr[:-1])[first["l2g"].long()].sum())     # global entries of the part's rows
+    max_row = int((rowptr[1:] - rowptr[:-1]).max())
+    cap, cap_nnz = n_loc + n_loc // 8 + 1024, nnz_loc + nnz_loc // 4 + 4096
+    fused = bool(args.fused_assignment)
+    if fused:    # the assignment recomputed inside the extraction: no part array, no assignment kernel
+        held = B.tma_random_subgraph_async(rowptr, colidx, K, 44, p, cap, cap_nnz)
+    else:
+        held = B.tma_induced_subgraph_async(rowptr, colidx, part, p, cap, cap_nnz)
+    same = all(torch.equal(held[k][:m], first[k][:m]) for k, m in
+               (("g2l", N), ("l2g", n_loc), ("rowptr", n_loc + 1), ("colidx", nnz_loc), ("inv_deg", n_loc)))
+    if not same or held["sizes"].cpu().tolist() != [n_loc, nnz_loc]:
+        sys.exit("bench.py: the two forms of the extraction disagree")
+    del first
+
+    def step():
+        if fused:
+            B.tma_random_subgraph_async(rowptr, colidx, K, 44, p, cap, cap_nnz, out=held)
+        else:
+            B.tma_partition(N, K, 44, out=part)
+            B.tma_induced_subgraph_async(rowptr, colidx, part, p, cap, cap_nnz, out=held)
+
+    def factory():
+        return lambda k: other_kernel_work(k, n_loc, nnz_loc, 0, 0, 0, N=N, rows_glob=rows_glob, K=K)
+
+    r = _timed_loop(step, args.steps, args.warmup, PEAK_MFMA_BF16_TFLOPS, factory, {})
+    out = _result(args, r, N, "int32", {
+        "workload": f"extraction alone: Chung-Lu power-law graph (gamma 2.1), {N} nodes, {nnz_glob} CSR entries "
+                    f"(longest row {max_row}), K=8 random node assignment, part 0; step = "
+                    + ("node-induced subgraph extraction with the assignment recomputed inside it (no part array)"
+                       if fused else "assignment of all ids + node-induced subgraph extraction")
+                    + ", sizes left on the device (no host wait)",
+        "n_nodes": N, "nnz_global": nnz_glob, "K": K, "n_loc": n_loc, "nnz_loc": nnz_loc,
+        "entries_of_the_parts_rows": rows_glob, "fused_assignment": fused}, None)
+    out["metric"], out["unit"] = "global nodes assigned and extracted per second", "nodes/s"
+    algorithmic = sum(other_kernel_work(k, n_loc, nnz_loc, 0, 0, 0, N=N, rows_glob=rows_glob, K=K)[1] * c
+                      for k, c in (("partition", 0 if fused else 1), ("scan_reduce_flags", 1), ("scan_apply_flags", 1), ("row_count", 1),
+                                   ("scan_apply_deg", 1), ("row_fill", 1)))
+    out["extraction"] = {"us_per_step": round(r["ms_per_step"] * 1e3, 1), "algorithmic_bytes_per_step": algorithmic,
+                         "algorithmic_GBs": round(algorithmic / (r["ms_per_step"] * 1e-3) / 1e9, 1),
+                         "frac_of_hbm_peak": round(algorithmic / (r["ms_per_step"] * 1e-3) / 1e9 / PEAK_HBM_GBS, 4)}
+    return out, None
 
 
 # ----------------------------------------------------------------------------------------------- configs[3]

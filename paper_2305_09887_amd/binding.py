@@ -21,7 +21,7 @@ TMA_ACT_NONE, TMA_ACT_RELU = 0, 1
 EXPORTS = (
     "tma_version", "tma_last_error", "tma_partition", "tma_mix64",
     "tma_induced_subgraph_workspace_bytes", "tma_induced_subgraph_count", "tma_induced_subgraph_fill",
-    "tma_induced_subgraph", "tma_induced_subgraph_async",
+    "tma_induced_subgraph", "tma_induced_subgraph_async", "tma_random_subgraph_async",
     "tma_mean_aggregate", "tma_sage_layer_aggregates_first", "tma_sage_layer_fwd",
     "tma_sage_layer_bwd_workspace_bytes", "tma_sage_layer_bwd",
     "tma_layernorm_prelu_fwd", "tma_layernorm_prelu_bwd_workspace_bytes", "tma_layernorm_prelu_bwd",
@@ -202,12 +202,16 @@ def tma_induced_subgraph(rowptr, colidx, part, p: int, cap_n_loc: int | None = N
                 n_loc=n_loc, nnz_loc=nnz_loc)
 
 
-def tma_induced_subgraph_async(rowptr, colidx, part, p: int, cap_n_loc: int, cap_nnz_loc: int, out=None, stream=None):
+def tma_induced_subgraph_async(rowptr, colidx, part, p: int, cap_n_loc: int, cap_nnz_loc: int, out=None, stream=None,
+                               rule=None):
     """The extraction without a host wait.  Returns dict(g2l, l2g, rowptr, colidx, inv_deg, sizes, ws): the buffers
     at their capacities and sizes = device int64 [|V^(p)|, kept entries].  Pass a previous result as `out` to
-    write into the same buffers again (fixed addresses, as a captured graph needs)."""
+    write into the same buffers again (fixed addresses, as a captured graph needs).  rule = (K, seed) with part
+    None: RandomTMA's assignment is recomputed inside the extraction (tma_random_subgraph_async)."""
     n = rowptr.numel() - 1
-    if part.numel() != n:
+    if (part is None) == (rule is None):
+        raise TmaError("tma_induced_subgraph_async: give either part or rule=(K, seed)")
+    if part is not None and part.numel() != n:
         raise TmaError("tma_induced_subgraph_async: part must have one entry per node")
     dev = rowptr.device
     if colidx.numel() == 0:
@@ -224,13 +228,23 @@ def tma_induced_subgraph_async(rowptr, colidx, part, p: int, cap_n_loc: int, cap
     if (out["g2l"].numel() < n or out["l2g"].numel() < cap or out["rowptr"].numel() < cap + 1
             or out["colidx"].numel() < cap_nnz or out["inv_deg"].numel() < cap or out["ws"].numel() < ws_bytes):
         raise TmaError("tma_induced_subgraph_async: `out` holds buffers below the capacities")
-    _check(L.tma_induced_subgraph_async(
-        C.c_int64(n), _ptr(rowptr, torch.int64, "rowptr"), _ptr(colidx, torch.int32, "colidx"),
-        _ptr(part, torch.int32, "part"), C.c_int32(p), _ptr(out["g2l"], torch.int32), _ptr(out["l2g"], torch.int32),
-        _ptr(out["rowptr"], torch.int32), _ptr(out["colidx"], torch.int32), _ptr(out["inv_deg"], torch.float32),
-        C.c_int64(cap), C.c_int64(cap_nnz), _ptr(out["sizes"], torch.int64), _ptr(out["ws"]),
-        C.c_size_t(out["ws"].numel()), _stream(stream)))
+    tail = (_ptr(out["g2l"], torch.int32), _ptr(out["l2g"], torch.int32), _ptr(out["rowptr"], torch.int32),
+            _ptr(out["colidx"], torch.int32), _ptr(out["inv_deg"], torch.float32), C.c_int64(cap), C.c_int64(cap_nnz),
+            _ptr(out["sizes"], torch.int64), _ptr(out["ws"]), C.c_size_t(out["ws"].numel()), _stream(stream))
+    head = (C.c_int64(n), _ptr(rowptr, torch.int64, "rowptr"), _ptr(colidx, torch.int32, "colidx"))
+    if rule is None:
+        _check(L.tma_induced_subgraph_async(*head, _ptr(part, torch.int32, "part"), C.c_int32(p), *tail))
+    else:
+        _check(L.tma_random_subgraph_async(*head, C.c_int32(int(rule[0])), C.c_uint64(int(rule[1]) & ((1 << 64) - 1)),
+                                           C.c_int32(p), *tail))
     return out
+
+
+def tma_random_subgraph_async(rowptr, colidx, K: int, seed: int, p: int, cap_n_loc: int, cap_nnz_loc: int, out=None,
+                              stream=None):
+    """RandomTMA's assignment fused into the extraction: tma_induced_subgraph_async without a part array."""
+    return tma_induced_subgraph_async(rowptr, colidx, None, p, cap_n_loc, cap_nnz_loc, out=out, stream=stream,
+                                      rule=(K, seed))
 
 
 def tma_mean_aggregate(rowptr, colidx, inv_deg, H, out=None, stream=None):

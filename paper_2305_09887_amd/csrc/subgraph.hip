@@ -13,6 +13,8 @@
 // rowptr).  Only entries that are kept go on to the id map.
 #include "common.hpp"
 
+#include <type_traits>
+
 namespace tma {
 
 constexpr int kScanThreads = 256;
@@ -37,6 +39,22 @@ struct FlagIn {  // 1 where the node belongs to partition p
         return true;
     }
 };
+struct RuleIn {  // the same flag, computed: RandomTMA's assignment of node i is a pure function of (seed, i)
+    uint64_t seed;
+    uint32_t K;
+    int32_t p;
+    __device__ int32_t load(int64_t i) const
+    {
+        return int32_t(__umul64hi(splitmix64_at(seed, uint64_t(i)), uint64_t(K))) == p ? 1 : 0;
+    }
+    __device__ bool load8(int64_t first, int32_t (&v)[8]) const
+    {
+#pragma unroll
+        for (int j = 0; j < 8; ++j) v[j] = load(first + j);
+        return true;
+    }
+};
+
 struct FlagOut {  // local id = exclusive rank; inverse map, row bounds for the first `cap` local nodes; bitmap
     int32_t *g2l;
     int32_t *l2g;
@@ -284,10 +302,25 @@ __global__ __launch_bounds__(kScanThreads) void scan_apply_kernel(const int64_t 
     }
 }
 
-__device__ __forceinline__ int member_bit(const uint32_t *__restrict__ member, int32_t u)
-{
-    return int((member[uint32_t(u) >> 5] >> (uint32_t(u) & 31u)) & 1u);
-}
+// Does global node u belong to the part?  Read from the bitmap that the flag scan leaves (any assignment), or
+// recomputed from the assignment rule (RandomTMA: a few integer multiplies instead of a random memory access; on
+// graphs whose bitmap outgrows the L2 the look-ups, not the entries, bound the two row passes).
+struct BitMember {
+    const uint32_t *__restrict__ bits;
+    __device__ __forceinline__ int operator()(int32_t u) const
+    {
+        return int((bits[uint32_t(u) >> 5] >> (uint32_t(u) & 31u)) & 1u);
+    }
+};
+struct RuleMember {
+    uint64_t seed;
+    uint32_t K;
+    int32_t p;
+    __device__ __forceinline__ int operator()(int32_t u) const
+    {
+        return int32_t(__umul64hi(splitmix64_at(seed, uint64_t(uint32_t(u))), uint64_t(K))) == p ? 1 : 0;
+    }
+};
 
 // The two passes over the local rows walk the entries of kWaveRows consecutive rows as ONE stream per wavefront:
 // lane j < kWaveRows holds row j's bounds, a prefix sum over the row lengths gives every stream position its row,
@@ -344,11 +377,11 @@ struct RowStream {
 };
 
 // Kept degree of every local row: entries whose column is local too.
+template <class Member>
 __global__ __launch_bounds__(256) void row_count_kernel(const int64_t *d_n_loc, int64_t cap,
                                                         const int64_t *__restrict__ row_beg,
                                                         const int32_t *__restrict__ row_len,
-                                                        const int32_t *__restrict__ colidx,
-                                                        const uint32_t *__restrict__ member,
+                                                        const int32_t *__restrict__ colidx, Member member,
                                                         int32_t *__restrict__ deg,
                                                         int64_t *__restrict__ tile_sums)
 {
@@ -398,7 +431,7 @@ __global__ __launch_bounds__(256) void row_count_kernel(const int64_t *d_n_loc, 
 #pragma unroll
         for (int q = 0; q < kStreamChunks; ++q) {
             if (c0 + q * kWave >= st.total) continue;
-            const bool keep = u[q] >= 0 && member_bit(member, u[q]) != 0;
+            const bool keep = u[q] >= 0 && member(u[q]) != 0;
             c += __popcll(__ballot(keep) & st.own_bits(c0 + q * kWave));
         }
     }
@@ -420,7 +453,7 @@ __global__ __launch_bounds__(256) void row_count_kernel(const int64_t *d_n_loc, 
             for (int j = 0; j < 4; ++j) u[j] = e + j * 256 < end ? colidx[e + j * 256] : -1;
 #pragma unroll
             for (int j = 0; j < 4; ++j)
-                if (u[j] >= 0) ch += member_bit(member, u[j]);
+                if (u[j] >= 0) ch += member(u[j]);
         }
 #pragma unroll
         for (int d = kWave / 2; d >= 1; d >>= 1) ch += __shfl_xor(ch, d, kWave);
@@ -444,11 +477,11 @@ __global__ __launch_bounds__(256) void row_count_kernel(const int64_t *d_n_loc, 
 // The rows of a wavefront are consecutive, so are their ranges in colidx_loc: the kept entries of the stream go
 // to consecutive positions from the first row's offset on, shifted by the kept entries of the giant rows left
 // out of the stream before them.
+template <class Member>
 __global__ __launch_bounds__(256) void row_fill_kernel(int64_t n_loc, const int64_t *__restrict__ d_n_loc,
                                                        int64_t cap_nnz, const int64_t *__restrict__ row_beg,
                                                        const int32_t *__restrict__ row_len,
-                                                       const int32_t *__restrict__ colidx,
-                                                       const uint32_t *__restrict__ member,
+                                                       const int32_t *__restrict__ colidx, Member member,
                                                        const int32_t *__restrict__ g2l,
                                                        const int32_t *__restrict__ rowptr_loc,
                                                        int32_t *__restrict__ colidx_loc,
@@ -509,7 +542,7 @@ __global__ __launch_bounds__(256) void row_fill_kernel(int64_t n_loc, const int6
             if (t < st.total) u[q] = colidx[base + t];
         }
 #pragma unroll
-        for (int q = 0; q < kStreamChunks; ++q) keep[q] = u[q] >= 0 && member_bit(member, u[q]) != 0;
+        for (int q = 0; q < kStreamChunks; ++q) keep[q] = u[q] >= 0 && member(u[q]) != 0;
 #pragma unroll
         for (int q = 0; q < kStreamChunks; ++q) lid[q] = keep[q] ? g2l[u[q]] : 0;
 #pragma unroll
@@ -549,7 +582,7 @@ __global__ __launch_bounds__(256) void row_fill_kernel(int64_t n_loc, const int6
                 u_next[j] = e < hend ? colidx[e] : -1;
             }
 #pragma unroll
-            for (int j = 0; j < kPerThread; ++j) keep[j] = u[j] >= 0 && member_bit(member, u[j]) != 0;
+            for (int j = 0; j < kPerThread; ++j) keep[j] = u[j] >= 0 && member(u[j]) != 0;
 #pragma unroll
             for (int j = 0; j < kPerThread; ++j) lid[j] = keep[j] ? g2l[u[j]] : 0;
             int32_t wave_kept = 0, below = 0;
@@ -653,15 +686,20 @@ namespace tma {
 
 // The counting pass, enqueued on the stream: flags, node ranks, kept degrees, rowptr_loc.  The two totals
 // (|V^(p)|, kept entries) end up in sizes[0..1] (device memory); nothing here waits for the GPU.
+// kRule: membership comes from RandomTMA's assignment rule (seed, K) instead of a part array.
+template <bool kRule>
 static int enqueue_count(const char *fn, int64_t n_nodes, const int64_t *rowptr, const int32_t *colidx,
-                         const int32_t *part, int32_t p, int32_t *g2l_out, int32_t *l2g_out, int32_t *rowptr_loc_out,
-                         int64_t cap_n_loc, int64_t *sizes, void *ws, size_t ws_bytes, hipStream_t s)
+                         const int32_t *part, int32_t p, int32_t K, uint64_t seed, int32_t *g2l_out, int32_t *l2g_out,
+                         int32_t *rowptr_loc_out, int64_t cap_n_loc, int64_t *sizes, void *ws, size_t ws_bytes,
+                         hipStream_t s)
 {
+    using In = std::conditional_t<kRule, RuleIn, FlagIn>;
+    using Member = std::conditional_t<kRule, RuleMember, BitMember>;
     TMA_REQUIRE(n_nodes >= 0 && n_nodes <= INT32_MAX, TMA_ERR_INVALID_ARG, "%s: n_nodes outside [0, 2^31)", fn);
     TMA_REQUIRE(cap_n_loc >= 0 && cap_n_loc <= n_nodes, TMA_ERR_INVALID_ARG,
                 "%s: cap_n_loc must lie in [0, n_nodes]", fn);
     TMA_REQUIRE(rowptr_loc_out, TMA_ERR_INVALID_ARG, "%s: rowptr_loc_out is NULL", fn);
-    TMA_REQUIRE(n_nodes == 0 || (rowptr && part && g2l_out), TMA_ERR_INVALID_ARG,
+    TMA_REQUIRE(n_nodes == 0 || (rowptr && (kRule || part) && g2l_out), TMA_ERR_INVALID_ARG,
                 "%s: rowptr / part / g2l_out is NULL", fn);
     TMA_REQUIRE(cap_n_loc == 0 || l2g_out, TMA_ERR_INVALID_ARG, "%s: l2g_out is NULL", fn);
     TMA_REQUIRE(ws && aligned(ws, 256), TMA_ERR_INVALID_ARG, "%s: workspace NULL or not 256-byte aligned", fn);
@@ -672,13 +710,21 @@ static int enqueue_count(const char *fn, int64_t n_nodes, const int64_t *rowptr,
 
     const unsigned nb_nodes = unsigned(ceil_div(n_nodes > 0 ? n_nodes : 1, kScanTile));
     const unsigned nb_rows = unsigned(ceil_div(cap_n_loc > 0 ? cap_n_loc : 1, kScanTile));
-    FlagIn fin{part, p};
+    In fin;
+    Member mem;
+    if constexpr (kRule) {
+        fin = RuleIn{seed, uint32_t(K), p};
+        mem = RuleMember{seed, uint32_t(K), p};
+    } else {
+        fin = FlagIn{part, p};
+        mem = BitMember{w.member};
+    }
     FlagOut fout{g2l_out, l2g_out, cap_n_loc, rowptr, w.row_beg, w.row_len, reinterpret_cast<uint8_t *>(w.member)};
     // 1. rank local nodes.  Few tiles: the apply kernel adds up the tile sums itself; many: a scan kernel first.
     const bool inline_nodes = nb_nodes <= kInlineTiles, inline_rows = nb_rows <= kInlineTiles;
     {
         TMA_TIMED("scan_reduce_flags", s);
-        hipLaunchKernelGGL(scan_reduce_kernel<FlagIn>, dim3(nb_nodes), dim3(kScanThreads), 0, s, nullptr, n_nodes,
+        hipLaunchKernelGGL(scan_reduce_kernel<In>, dim3(nb_nodes), dim3(kScanThreads), 0, s, nullptr, n_nodes,
                            fin, w.node_block_sums);
     }
     if (!inline_nodes) {
@@ -688,7 +734,7 @@ static int enqueue_count(const char *fn, int64_t n_nodes, const int64_t *rowptr,
     }
     {   // also clears the tile sums that the kept-degree pass adds to (nb_rows <= nb_nodes)
         TMA_TIMED("scan_apply_flags", s);
-        hipLaunchKernelGGL((scan_apply_kernel<FlagIn, FlagOut>), dim3(nb_nodes), dim3(kScanThreads), 0, s, nullptr,
+        hipLaunchKernelGGL((scan_apply_kernel<In, FlagOut>), dim3(nb_nodes), dim3(kScanThreads), 0, s, nullptr,
                            n_nodes, fin, fout, w.node_block_sums, inline_nodes ? sizes + 0 : nullptr,
                            inline_nodes ? rowptr_loc_out : nullptr, w.row_block_sums, int64_t(nb_rows));
     }
@@ -696,8 +742,8 @@ static int enqueue_count(const char *fn, int64_t n_nodes, const int64_t *rowptr,
     if (cap_n_loc > 0) {
         const unsigned row_blocks = unsigned(ceil_div(cap_n_loc, kRowsPerBlock));
         TMA_TIMED("row_count", s);
-        hipLaunchKernelGGL(row_count_kernel, dim3(row_blocks), dim3(256), 0, s, sizes + 0, cap_n_loc, w.row_beg,
-                           w.row_len, colidx, w.member, w.deg, inline_rows ? w.row_block_sums : nullptr);
+        hipLaunchKernelGGL(row_count_kernel<Member>, dim3(row_blocks), dim3(256), 0, s, sizes + 0, cap_n_loc, w.row_beg,
+                           w.row_len, colidx, mem, w.deg, inline_rows ? w.row_block_sums : nullptr);
     }
     DegIn din{w.deg};
     DegOut dout{rowptr_loc_out};
@@ -731,8 +777,8 @@ extern "C" int tma_induced_subgraph_count(int64_t n_nodes, const int64_t *rowptr
     const char *fn = "tma_induced_subgraph_count";
     TMA_REQUIRE(h_n_loc && h_nnz_loc, TMA_ERR_INVALID_ARG, "%s: h_n_loc / h_nnz_loc is NULL", fn);
     hipStream_t s = as_stream(stream);
-    if (int rc = enqueue_count(fn, n_nodes, rowptr, colidx, part, p, g2l_out, l2g_out, rowptr_loc_out, cap_n_loc,
-                               nullptr, ws, ws_bytes, s))
+    if (int rc = enqueue_count<false>(fn, n_nodes, rowptr, colidx, part, p, 0, 0, g2l_out, l2g_out, rowptr_loc_out,
+                                      cap_n_loc, nullptr, ws, ws_bytes, s))
         return rc;
     const CountWorkspace w = carve(ws, n_nodes, cap_n_loc);
 
@@ -769,9 +815,9 @@ extern "C" int tma_induced_subgraph_fill(int64_t n_nodes, const int32_t *colidx,
     TMA_REQUIRE(colidx && colidx_loc_out, TMA_ERR_INVALID_ARG, "%s: colidx / colidx_loc_out is NULL", fn);
     const unsigned blocks = unsigned(ceil_div(n_loc, kRowsPerBlock));
     TMA_TIMED("row_fill", as_stream(stream));
-    hipLaunchKernelGGL(row_fill_kernel, dim3(blocks), dim3(256), 0, as_stream(stream), n_loc,
+    hipLaunchKernelGGL(row_fill_kernel<BitMember>, dim3(blocks), dim3(256), 0, as_stream(stream), n_loc,
                        static_cast<const int64_t *>(nullptr), int64_t(INT64_MAX), w.row_beg, w.row_len,
-                       colidx, w.member, g2l, rowptr_loc, colidx_loc_out, inv_deg_out);
+                       colidx, BitMember{w.member}, g2l, rowptr_loc, colidx_loc_out, inv_deg_out);
     return check_launch(fn);
 }
 
@@ -794,29 +840,61 @@ extern "C" int tma_induced_subgraph(int64_t n_nodes, const int64_t *rowptr, cons
                                      cap_n_loc, ws, ws_bytes, stream);
 }
 
+namespace tma {
+
+template <bool kRule>
+static int subgraph_async(const char *fn, int64_t n_nodes, const int64_t *rowptr, const int32_t *colidx,
+                          const int32_t *part, int32_t p, int32_t K, uint64_t seed, int32_t *g2l_out, int32_t *l2g_out,
+                          int32_t *rowptr_loc_out, int32_t *colidx_loc_out, float *inv_deg_out, int64_t cap_n_loc,
+                          int64_t cap_nnz_loc, int64_t *d_sizes_out, void *ws, size_t ws_bytes, tma_stream_t stream)
+{
+    using Member = std::conditional_t<kRule, RuleMember, BitMember>;
+    TMA_REQUIRE(cap_nnz_loc >= 0 && cap_nnz_loc <= INT32_MAX, TMA_ERR_INVALID_ARG, "%s: cap_nnz_loc outside [0, 2^31)", fn);
+    TMA_REQUIRE(d_sizes_out, TMA_ERR_INVALID_ARG, "%s: d_sizes_out is NULL", fn);
+    TMA_REQUIRE(cap_n_loc == 0 || (colidx && colidx_loc_out && inv_deg_out), TMA_ERR_INVALID_ARG,
+                "%s: colidx / colidx_loc_out / inv_deg_out is NULL", fn);
+    hipStream_t s = as_stream(stream);
+    if (int rc = enqueue_count<kRule>(fn, n_nodes, rowptr, colidx, part, p, K, seed, g2l_out, l2g_out, rowptr_loc_out,
+                                      cap_n_loc, d_sizes_out, ws, ws_bytes, s))
+        return rc;
+    if (cap_n_loc == 0) return TMA_OK;
+    const CountWorkspace w = carve(ws, n_nodes, cap_n_loc);
+    Member mem;
+    if constexpr (kRule)
+        mem = RuleMember{seed, uint32_t(K), p};
+    else
+        mem = BitMember{w.member};
+    // the second pass over as many rows as the capacity allows; the kernel reads the actual count
+    const unsigned blocks = unsigned(ceil_div(cap_n_loc, kRowsPerBlock));
+    TMA_TIMED("row_fill", s);
+    hipLaunchKernelGGL(row_fill_kernel<Member>, dim3(blocks), dim3(256), 0, s, cap_n_loc,
+                       static_cast<const int64_t *>(d_sizes_out), cap_nnz_loc, w.row_beg, w.row_len, colidx, mem, g2l_out,
+                       rowptr_loc_out, colidx_loc_out, inv_deg_out);
+    return check_launch(fn);
+}
+
+}  // namespace tma
+
 extern "C" int tma_induced_subgraph_async(int64_t n_nodes, const int64_t *rowptr, const int32_t *colidx,
                                           const int32_t *part, int32_t p, int32_t *g2l_out, int32_t *l2g_out,
                                           int32_t *rowptr_loc_out, int32_t *colidx_loc_out, float *inv_deg_out,
                                           int64_t cap_n_loc, int64_t cap_nnz_loc, int64_t *d_sizes_out, void *ws,
                                           size_t ws_bytes, tma_stream_t stream)
 {
-    using namespace tma;
-    const char *fn = "tma_induced_subgraph_async";
-    TMA_REQUIRE(cap_nnz_loc >= 0 && cap_nnz_loc <= INT32_MAX, TMA_ERR_INVALID_ARG, "%s: cap_nnz_loc outside [0, 2^31)", fn);
-    TMA_REQUIRE(d_sizes_out, TMA_ERR_INVALID_ARG, "%s: d_sizes_out is NULL", fn);
-    TMA_REQUIRE(cap_n_loc == 0 || (colidx && colidx_loc_out && inv_deg_out), TMA_ERR_INVALID_ARG,
-                "%s: colidx / colidx_loc_out / inv_deg_out is NULL", fn);
-    hipStream_t s = as_stream(stream);
-    if (int rc = enqueue_count(fn, n_nodes, rowptr, colidx, part, p, g2l_out, l2g_out, rowptr_loc_out, cap_n_loc,
-                               d_sizes_out, ws, ws_bytes, s))
-        return rc;
-    if (cap_n_loc == 0) return TMA_OK;
-    const CountWorkspace w = carve(ws, n_nodes, cap_n_loc);
-    // the second pass over as many rows as the capacity allows; the kernel reads the actual count
-    const unsigned blocks = unsigned(ceil_div(cap_n_loc, kRowsPerBlock));
-    TMA_TIMED("row_fill", s);
-    hipLaunchKernelGGL(row_fill_kernel, dim3(blocks), dim3(256), 0, s, cap_n_loc,
-                       static_cast<const int64_t *>(d_sizes_out), cap_nnz_loc, w.row_beg, w.row_len, colidx, w.member,
-                       g2l_out, rowptr_loc_out, colidx_loc_out, inv_deg_out);
-    return check_launch(fn);
+    return tma::subgraph_async<false>("tma_induced_subgraph_async", n_nodes, rowptr, colidx, part, p, 0, 0, g2l_out,
+                                      l2g_out, rowptr_loc_out, colidx_loc_out, inv_deg_out, cap_n_loc, cap_nnz_loc,
+                                      d_sizes_out, ws, ws_bytes, stream);
+}
+
+extern "C" int tma_random_subgraph_async(int64_t n_nodes, const int64_t *rowptr, const int32_t *colidx, int32_t K,
+                                         uint64_t seed, int32_t p, int32_t *g2l_out, int32_t *l2g_out,
+                                         int32_t *rowptr_loc_out, int32_t *colidx_loc_out, float *inv_deg_out,
+                                         int64_t cap_n_loc, int64_t cap_nnz_loc, int64_t *d_sizes_out, void *ws,
+                                         size_t ws_bytes, tma_stream_t stream)
+{
+    const char *fn = "tma_random_subgraph_async";
+    TMA_REQUIRE(K >= 1 && K <= (1 << 30), TMA_ERR_INVALID_ARG, "%s: K outside [1, 2^30]", fn);
+    TMA_REQUIRE(p >= 0 && p < K, TMA_ERR_INVALID_ARG, "%s: p outside [0, K)", fn);
+    return tma::subgraph_async<true>(fn, n_nodes, rowptr, colidx, nullptr, p, K, seed, g2l_out, l2g_out, rowptr_loc_out,
+                                     colidx_loc_out, inv_deg_out, cap_n_loc, cap_nnz_loc, d_sizes_out, ws, ws_bytes, stream);
 }

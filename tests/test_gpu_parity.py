@@ -229,6 +229,27 @@ def test_subgraph_without_host_wait(B):
     torch.cuda.synchronize()
 
 
+@pytest.mark.parametrize("K,p,seed", [(8, 3, 14), (1, 0, 5), (23, 22, 77), (4, 0, 2**63 + 11)])
+def test_subgraph_with_the_assignment_recomputed_inside(B, K, p, seed):
+    """RandomTMA's assignment fused into the extraction (no part array): every output equals the oracle's
+    partition followed by the oracle's extraction, bit for bit; hubs, scan-tile edges, K = 1."""
+    for n, avg in ((150_000, 20), (2049, 6)):
+        rowptr, colidx = synth.chung_lu_graph(n, avg, 2.1, seed=11 + n)
+        part = oracle.partition(n, K, seed=seed)
+        want = oracle.induced_subgraph(rowptr, colidx, part, p)
+        n_loc, nnz_loc = len(want["l2g"]), len(want["colidx"])
+        out = B.tma_random_subgraph_async(dev(rowptr), dev(colidx), K, seed, p, n_loc + 100, nnz_loc + 1000)
+        assert out["sizes"].cpu().tolist() == [n_loc, nnz_loc]
+        assert np.array_equal(out["g2l"][:n].cpu().numpy(), want["g2l"])
+        assert np.array_equal(out["l2g"][:n_loc].cpu().numpy(), want["l2g"])
+        assert np.array_equal(out["rowptr"][:n_loc + 1].cpu().numpy(), want["rowptr"])
+        assert np.array_equal(out["colidx"][:nnz_loc].cpu().numpy(), want["colidx"])
+        assert np.array_equal(out["inv_deg"][:n_loc].cpu().numpy(), want["inv_deg"].astype(np.float32))
+    with pytest.raises(B.TmaError, match="p outside"):
+        B.tma_random_subgraph_async(dev(rowptr), dev(colidx), 4, 1, 4, 10, 10)
+    torch.cuda.synchronize()
+
+
 # ------------------------------------------------------------------ aggregation
 def _local_graph(n, m, seed, K=2, kind="uniform"):
     if kind == "uniform":
