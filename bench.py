@@ -237,6 +237,10 @@ def main():
     ap.add_argument("--summarize-kernel-stats", nargs=3, metavar=("KEY", "STATS_DIR", "BENCH_JSON"),
                     help="no GPU work: write profiles/bench_<KEY>_kernel_stats.txt from a `rocprofv3 --kernel-trace --stats "
                          "--output-format csv` run of this script and the JSON line it printed")
+    ap.add_argument("--summarize-counters", nargs=2, metavar=("KEY", "PMC_DIR"),
+                    help="no GPU work: write profiles/bench_<KEY>.txt, the per-kernel means of the counters of one "
+                         "rocprofv3 --pmc run of this script (give its command with --profiled-command, a heading with --title)")
+    ap.add_argument("--title", default="Hardware counters per kernel launch")
     ap.add_argument("--calibration-dirs", nargs=2, metavar=("COPY_FETCH_DIR", "COPY_WRITE_DIR"), default=None,
                     help="with --summarize-traffic: counter runs of `bench.py --calibrate-copy` to take the scale factors from")
     ap.add_argument("--profiled-command", default=None,
@@ -244,6 +248,12 @@ def main():
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="only run a plain 1 GiB device copy (reference for scaling rocprofv3 FETCH_SIZE/WRITE_SIZE)")
     args = ap.parse_args()
+    if args.summarize_counters:
+        from paper_2305_09887_amd import benchlib
+        print(benchlib.summarize_counters(args.summarize_counters[0], args.summarize_counters[1],
+                                          args.profiled_command or "bench.py --headline-only --steps 5 --warmup 2 --no-cpu-baseline",
+                                          args.title))
+        return
     if args.summarize_kernel_stats:
         from paper_2305_09887_amd import benchlib
         key, sd, bj = args.summarize_kernel_stats

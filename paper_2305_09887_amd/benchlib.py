@@ -716,3 +716,51 @@ def summarize_kernel_stats(config_key, stats_dir, bench_json, command):
             if bench.get(extra):
                 f.write(f"\n{extra}: {json.dumps(bench[extra])}\n")
     return out
+
+
+def summarize_counters(key, directory, command, title):
+    """Writes profiles/bench_<key>.txt: the mean over the launches of every library kernel of each counter that a
+    `rocprofv3 --pmc ... --kernel-trace --output-format csv` run of bench.py collected, with a few derived ratios
+    where their counters are there."""
+    import csv
+    import glob
+    files = glob.glob(os.path.join(directory, "**", "*counter_collection.csv"), recursive=True)
+    if not files:
+        raise SystemExit(f"no *counter_collection.csv under {directory}")
+    acc, counters = {}, []
+    with open(files[0]) as f:
+        for r in csv.DictReader(f):
+            if "tma::" not in r["Kernel_Name"]:
+                continue
+            c = r["Counter_Name"]
+            if c not in counters:
+                counters.append(c)
+            a = acc.setdefault(r["Kernel_Name"], {}).setdefault(c, [0.0, 0])
+            a[0] += float(r["Counter_Value"])
+            a[1] += 1
+    mean = {k: {c: v[0] / v[1] for c, v in d.items()} for k, d in acc.items()}
+    launches = {k: max(v[1] for v in d.values()) for k, d in acc.items()}
+    derived = []
+    if {"SQ_INSTS_VALU", "SQ_INSTS_MFMA"} <= set(counters):
+        derived.append(("valu/mfma", lambda m: (m["SQ_INSTS_VALU"] - m["SQ_INSTS_MFMA"]) / m["SQ_INSTS_MFMA"] if m.get("SQ_INSTS_MFMA") else None))
+    if {"SQ_INSTS_LDS", "SQ_INSTS_MFMA"} <= set(counters):
+        derived.append(("lds/mfma", lambda m: m["SQ_INSTS_LDS"] / m["SQ_INSTS_MFMA"] if m.get("SQ_INSTS_MFMA") else None))
+    if {"TCP_TCC_READ_REQ_LATENCY_sum", "TCP_TCC_READ_REQ_sum"} <= set(counters):
+        derived.append(("read_latency_cycles", lambda m: m["TCP_TCC_READ_REQ_LATENCY_sum"] / m["TCP_TCC_READ_REQ_sum"] if m.get("TCP_TCC_READ_REQ_sum") else None))
+    if {"TCC_HIT_sum", "TCC_MISS_sum"} <= set(counters):
+        derived.append(("L2_hit_share", lambda m: m["TCC_HIT_sum"] / (m["TCC_HIT_sum"] + m["TCC_MISS_sum"]) if m.get("TCC_HIT_sum", 0) + m.get("TCC_MISS_sum", 0) else None))
+    order = sorted(mean, key=lambda k: -mean[k].get(counters[0], 0.0))
+    out = os.path.join(ROOT, "profiles", f"bench_{key}.txt")
+    with open(out, "w") as f:
+        f.write(title + "\n\ncommand (MI355X box, repo root, after `cd /tmp && export TMPDIR=/tmp`):\n")
+        f.write(f"  rocprofv3 --pmc {' '.join(counters)} --kernel-trace --output-format csv -d <dir> -o b -- python3 {command}\n")
+        f.write(f"  python3 bench.py --summarize-counters {key} <dir>\n")
+        f.write("Means over the launches of each library kernel (a name launched with several shapes is averaged over them).\n\n")
+        cols = counters + [d[0] for d in derived]
+        f.write("launches " + " ".join("%-14s" % c[:14] for c in cols) + " kernel\n")
+        for k in order:
+            m = mean[k]
+            vals = [m.get(c) for c in counters] + [fn(m) for _, fn in derived]
+            f.write("%-8d " % launches[k] + " ".join("%-14s" % ("-" if v is None else ("%.4g" % v)) for v in vals)
+                    + " " + k.replace("void ", "")[:140] + "\n")
+    return out
