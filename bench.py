@@ -125,6 +125,9 @@ def kernel_work(name, n, nnz, dims, N=0, nnz_glob=0, K=1, n_params=0, encoder="s
     F0, F1, C = dims
     Cp = (C * s + 15) // 16 * 16 // s        # padded width of the transform-first blocks (rows of whole 16-byte pieces)
     name = canonical(name, s)
+    # the tile shape of a product and the lanes per row of a gather follow from the widths: not part of the key
+    name = re.sub(r"^(gemm_(?:fwd|bwd_weight|bwd_data))_\d+x\d+$", r"\1", name)
+    name = re.sub(r"^(spmm_(?:mean|combine|sum|weighted))_f32_g\d+x1$", r"\1", name)
     if encoder != "sage":
         both = (2.0 * n * F0 * F1 + 2.0 * n * F1 * C) / 2
         other = {
@@ -132,17 +135,17 @@ def kernel_work(name, n, nnz, dims, N=0, nnz_glob=0, K=1, n_params=0, encoder="s
             "gemm_dense_bwd_weight": ("mfma", both),               # dW = X^T G, both layers
             "gemm_dense_bwd_data": ("mfma", 2.0 * n * F1 * C),     # dH1 = G W^T, layer 1 only
             # layer 0 aggregates first: M = S (A + I) S H0, rows of H0 once + ids + rowptr, s + output
-            "spmm_weighted_f32_g32x1": ("hbm", 2.0 * n * F0 * s + nnz * 4 + n * 8),
+            "spmm_weighted": ("hbm", 2.0 * n * F0 * s + nnz * 4 + n * 8),
             # layer 1 transforms first: H2 = S (A + I) Y + b forward and G = S (A + I)^T Q backward
-            "spmm_combine_f32_g12x1": ("hbm", 2.0 * n * Cp * s + nnz * 4 + n * 8),
+            "spmm_combine": ("hbm", 2.0 * n * Cp * s + nnz * 4 + n * 8),
             # Q = S dZ of layer 1: dH2 read, Q written, s read
             "scale_mask_colsum": ("hbm", n * (C + Cp) * s + n * 4.0),
         }
         if name in other:
             return other[name]
     gemm = {
-        "gemm_fwd_128x128": 2.0 * n * (2 * F0) * F1,          # Z1 = [H0 | M0] [Ws; Wn]
-        "gemm_bwd_weight_128x128": 2.0 * n * (2 * F0) * F1,   # [dWs; dWn] = [H0 | M0]^T dZ1
+        "gemm_fwd": 2.0 * n * (2 * F0) * F1,          # Z1 = [H0 | M0] [Ws; Wn]
+        "gemm_bwd_weight": 2.0 * n * (2 * F0) * F1,   # [dWs; dWn] = [H0 | M0]^T dZ1
         "gemm_tf_fwd": 2.0 * n * F1 * (2 * C),                # [Ys | Yn] = H1 [Ws | Wn]
         "gemm_tf_bwd_weight": 2.0 * n * F1 * (2 * C),         # [dWs | dWn] = H1^T [dZ | dYn]
         "gemm_tf_bwd_data": 2.0 * n * (2 * C) * F1,           # dH1 = [dZ | dYn] [Ws | Wn]^T
@@ -152,11 +155,11 @@ def kernel_work(name, n, nnz, dims, N=0, nnz_glob=0, K=1, n_params=0, encoder="s
     rows_glob = nnz_glob / max(K, 1)     # global entries of the local rows
     hbm = {
         # mean aggregation of H0: rows of H0 once + ids + rowptr/inv_deg + output
-        "spmm_mean_f32_g32x1": n * F0 * s + nnz * 4 + n * 8 + n * F0 * s,
+        "spmm_mean": n * F0 * s + nnz * 4 + n * 8 + n * F0 * s,
         # layer-1 output: gathered Yn rows once + Ys + ids + rowptr/inv_deg + bias + H2
-        "spmm_combine_f32_g12x1": 2 * n * Cp * s + nnz * 4 + n * 8 + n * Cp * s,
+        "spmm_combine": 2 * n * Cp * s + nnz * 4 + n * 8 + n * Cp * s,
         # dYn = A^T (D^-1 dZ): scaled rows once + ids + rowptr + output
-        "spmm_sum_f32_g12x1": n * Cp * s + nnz * 4 + n * 4 + n * Cp * s,
+        "spmm_sum": n * Cp * s + nnz * 4 + n * 4 + n * Cp * s,
         "scale_mask_rows": n * C * s + n * 4 + n * Cp * s,
         "softmax_ce": 2 * n * C * s + n * 4,
         "ln_prelu_fwd_f32": 2 * n * F1 * s,                   # Z read, H' written

@@ -290,7 +290,7 @@ def run_supertma(args):
         "n_nodes": N, "nnz_global": nnz_glob, "K": K, "n_loc": n_loc, "nnz_loc": nnz_loc, "layers": L, "dims": dims,
         "feature_row_pitch": ld, "mean_local_degree": round(float(deg.mean()), 2), "max_local_degree": int(deg.max()),
         "edge_definition": "directed local CSR entry; value = layers*nnz_loc/step time"}, tr)
-    m = min(2000, n_loc)
+    m = min(60_000, n_loc)            # about 10 s of single-threaded oracle work
     sample = oracle_sample(sub["rowptr"], sub["colidx"], Xl, yl, params, lr, m, None,
                            f"one full 3-layer step on the first {m} local nodes and the entries among them "
                            f"(of n_loc={n_loc}, nnz_loc={nnz_loc})")
@@ -435,7 +435,7 @@ def run_share(args):
         "n_nodes": N, "K": K, "n_loc": n_loc, "nnz_loc": nnz_loc, "layers": L, "dims": dims,
         "max_local_degree": max_deg, "isolated_share": round(iso, 3),
         "edge_definition": "directed local CSR entry; value = layers*nnz_loc/step time"}, tr)
-    m = min(4000, n_loc)
+    m = min(100_000, n_loc)           # about 12 s of single-threaded oracle work
     # the step's cost is dominated by the rows (dense products), so the oracle's rate is extrapolated per row
     sample = oracle_sample(rowptr, colidx, X, y, params, lr, m, L * nnz_loc * (m / n_loc),
                            f"extrapolated: one full 3-layer step on the first {m} of {n_loc} local rows, counted as "
@@ -561,7 +561,7 @@ def run_aggregation(args):
                                        "steps_at_each_round": hist}},
         "final_loss": float(trainers[0].loss.item()), "streams": K,
     }
-    m = min(8000, sizes[0][0])
+    m = min(300_000, sizes[0][0])       # about 11 s of single-threaded oracle work
     sample = oracle_sample(tr0.rowptr, tr0.colidx, tr0.X, tr0.labels, params, lr, m, L * sizes[0][1] * (m / sizes[0][0]),
                            f"extrapolated: one trainer's full step on the first {m} of its {sizes[0][0]} local rows, "
                            "counted as that share of its entries")

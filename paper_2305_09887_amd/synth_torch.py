@@ -65,6 +65,14 @@ def _shift_for_cap(n: int, total: float, expo: float, device) -> tuple[float, fl
     return hi, raw_sum(hi)
 
 
+def _cdf(weights: torch.Tensor) -> torch.Tensor:
+    """Running sum of the weights, taken on the host in one fixed order and sent back: a floating-point prefix sum
+    on the GPU may associate differently from run to run, and a cdf that differs in its last bits sends a few of
+    the draws to a neighbouring node, so that one seed would no longer name one graph."""
+    import numpy as np
+    return torch.from_numpy(np.cumsum(weights.cpu().numpy(), dtype=np.float64)).to(weights.device)
+
+
 def _draw(cdf: torch.Tensor, m: int, g: torch.Generator, chunk: int = 1 << 26) -> torch.Tensor:
     """m indices drawn with probabilities proportional to the increments of cdf."""
     out = torch.empty(m, dtype=torch.int64, device=cdf.device)
@@ -84,7 +92,7 @@ def chung_lu_graph(n: int, avg_degree: float, gamma: float, seed: int, device="c
     total = float(n) * avg_degree
     expo = 1.0 / (gamma - 1.0)
     i0, _ = _shift_for_cap(n, total, expo, device)
-    cdf = torch.cumsum((torch.arange(n, dtype=torch.float64, device=device) + i0) ** (-expo), 0)
+    cdf = _cdf((torch.arange(n, dtype=torch.float64, device=device) + i0) ** (-expo))
     perm = torch.randperm(n, generator=g, device=device)
     m = int(round(total / 2))
     u = perm[_draw(cdf, m, g)]
@@ -109,7 +117,7 @@ def chung_lu_share(n_global: int, total_global: float, gamma: float, n_local: in
     del ranks
     share = float(w.sum()) / total_global
     m = int(round(total_global / 2 * share * share))
-    cdf = torch.cumsum(w, 0)
+    cdf = _cdf(w)
     del w
     u, v = _draw(cdf, m, g), _draw(cdf, m, g)
     del cdf
