@@ -382,6 +382,20 @@ def main():
 
     held = B.tma_induced_subgraph_async(d_rowptr, d_colidx, part, p, cap, cap_nnz) if args.extract == "async" else None
 
+    def prepare_sampled(prefetch, after):
+        """Sampled task: the next step's assignment, extraction, row gather AND batch sampling on the extraction
+        stream (the batch depends on the subgraph, the feature rows and the seeds only), driven by the trainer's
+        worker thread while this thread enqueues the training pass."""
+        if tr._side is not prefetch.stream:
+            tr.enable_prefetch(stream=prefetch.stream, auto=False, background=True)
+
+        def prepare():
+            s, rows, ready = prefetch.start(sd["part"], after=after)
+            tr.set_graph(s["rowptr"], s["colidx"], s["nnz_loc"], ready=ready)
+            tr.set_data(rows[0])
+
+        tr.prefetch_sample(prepare)
+
     def step(prefetch=two_stream if args.prefetch else None):
         if prefetch is None:
             B.tma_partition(N, K, sd["part"], out=part)
@@ -391,6 +405,9 @@ def main():
                          inv_deg=held["inv_deg"][:n_loc], nnz_loc=nnz_loc)
             else:
                 s = B.tma_induced_subgraph(d_rowptr, d_colidx, part, p, cap_n_loc=cap, cap_nnz_loc=cap_nnz)
+        elif sampled:
+            if tr._pending is None or tr._side is not prefetch.stream:
+                prepare_sampled(prefetch, None)
         else:
             if state["next"] is None:
                 state["next"] = prefetch.start(sd["part"])
@@ -400,9 +417,9 @@ def main():
         if prefetch is None:
             B.tma_gather_rows(s["l2g"], d_X, out=Xl)
             B.tma_gather_rows(s["l2g"], d_y, out=yl)
-        if sampled:
+        if sampled and prefetch is None:
             tr.set_graph(s["rowptr"], s["colidx"], s["nnz_loc"])
-        else:
+        elif not sampled:
             tr.set_graph(s["rowptr"], s["colidx"], s["inv_deg"], nnz=s["nnz_loc"])
         tr.step(w["lr"])
         B.tma_average(W_all, W_global_out=W_global, ptr_table=ptrs)
@@ -410,7 +427,10 @@ def main():
             trained = torch.cuda.Event()
             trained.record()
             # the allocator may hand the next extraction the buffers that the step before this one read
-            state["next"] = prefetch.start(sd["part"], after=state["trained"])
+            if sampled:
+                prepare_sampled(prefetch, state["trained"])
+            else:
+                state["next"] = prefetch.start(sd["part"], after=state["trained"])
             state["trained"] = trained
 
     for _ in range(args.warmup):
@@ -506,6 +526,8 @@ def main():
             if two_stream_tries[-1] < ms_per_step:
                 break
         two_stream_ms = min(two_stream_tries)
+        if sampled:
+            tr.disable_prefetch()
         tr.set_data(Xl, yl) if not sampled else tr.set_data(Xl)
 
     kw = dict(N=N, nnz_glob=int(rowptr[-1]), K=K, n_params=int(tr.W.numel()), encoder=args.encoder)

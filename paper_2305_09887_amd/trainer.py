@@ -308,6 +308,31 @@ class LocalTrainer:
         return self.loss
 
 
+class _Mfg:
+    """Buffers of one mini-batch's message-flow graph: the batch, the node list of every level, the blocks, the
+    gathered input features, and the sampler's own workspace (so that a batch can be sampled on one stream while
+    another one trains).  ``ready``: recorded when all of it has been written; ``released``: recorded on the
+    training stream after the last pass that read it."""
+
+    def __init__(self, cap, ecap, Bn, F0, n, dtype, dev):
+        L = len(cap) - 1
+        i32 = lambda k: torch.empty(k, dtype=torch.int32, device=dev)
+        self.nodes = [i32(c) for c in cap]
+        self.count = [0] * (L + 1)
+        self.blk_rowptr = [i32(cap[l + 1] + 1) for l in range(L)]
+        self.blk_col = [i32(ecap[l]) for l in range(L)]
+        self.blk_row = [i32(ecap[l]) for l in range(L)]
+        self.blk_inv_deg = [torch.empty(cap[l + 1], dtype=torch.float32, device=dev) for l in range(L)]
+        self.H0 = torch.empty((cap[0], F0), dtype=dtype, device=dev)
+        self.bcat = i32(3 * Bn)                       # u | v | v': node ids when drawn, then positions in level L
+        self.batch = (self.bcat[:Bn], self.bcat[Bn:2 * Bn], self.bcat[2 * Bn:])
+        ws_bytes = max(max(B.tma_neighbor_sample_workspace_bytes(cap[l + 1]) for l in range(L)),
+                       B.tma_mfg_relabel_workspace_bytes(n))
+        self.ws = torch.empty(max(ws_bytes, 256), dtype=torch.uint8, device=dev)
+        self.step = -1
+        self.ready = self.released = None
+
+
 class SampledLinkTrainer(LocalTrainer):
     """Link prediction on the sampled message-flow graph of each mini-batch (Sec. 4.1: random positive edges, one
     random-tail negative each, a GraphSAGE-style sampler that caps the neighbours per node and layer, MLP decoder).
@@ -321,6 +346,12 @@ class SampledLinkTrainer(LocalTrainer):
     of a step come back from the device, one wait per level.  The neighbour sampler's seed for step t and layer l is
     SplitMix64(batch_seed, 64 t + l).  ``encoder``: "sage" (W_self, W_neigh, b per layer) or "gcn" (W, b per layer;
     on a block the layer averages over the sampled neighbours and the node itself).
+
+    A batch and its message-flow graph depend on the graph, the seeds and the step number only, never on the
+    model: after ``enable_prefetch()`` every ``step`` trains on the batch that was sampled while the step before
+    it trained (a second stream, a second set of buffers), and then starts the sampling of the next one, so the
+    sampler's kernels and its waits for the level sizes fall beside the training kernels.  Same batches, same
+    arithmetic, same bits as without it.
     """
 
     def __init__(self, rowptr, colidx, nnz, X, dims, decoder_dims, fanouts, batch_size, batch_seed=0, params=None,
@@ -368,29 +399,21 @@ class SampledLinkTrainer(LocalTrainer):
             cap[l] = max(min(self.n, cap[l + 1] * (1 + self.fanouts[l])), 1)
         self.cap = cap
         self.ecap = [max(min(cap[l + 1] * self.fanouts[l], self.nnz_cap), 1) for l in range(L)]
-        i32 = lambda k: torch.empty(k, dtype=torch.int32, device=dev)
-        self.nodes = [i32(c) for c in cap]
-        self.count = [0] * (L + 1)
-        self.blk_rowptr = [i32(cap[l + 1] + 1) for l in range(L)]
-        self.blk_col = [i32(self.ecap[l]) for l in range(L)]
-        self.blk_row = [i32(self.ecap[l]) for l in range(L)]
-        self.blk_inv_deg = [torch.empty(cap[l + 1], dtype=torch.float32, device=dev) for l in range(L)]
-        self.H = [torch.empty((cap[0], dims[0]), dtype=self.dtype, device=dev)]
-        self.H += [B._padded(cap[l], dims[l], self.dtype, dev) for l in range(1, L + 1)]
+        self._mfgs = [_Mfg(cap, self.ecap, Bn, dims[0], self.n, self.dtype, dev)]
+        self._side = self._pending = self._inputs_ready = self._worker = None
+        self._auto = True
+        self.H = [None] + [B._padded(cap[l], dims[l], self.dtype, dev) for l in range(1, L + 1)]
+        self._bind(self._mfgs[0])
         self.M = [torch.empty((cap[l + 1], dims[l]), dtype=self.dtype, device=dev) for l in range(L)]
         self.dH = [None] + [B._padded(cap[l], dims[l], self.dtype, dev) for l in range(1, L + 1)]
         # pre-activations of the normalised hidden layers (index l + 1 = output of layer l), kept for the backward
         self.Z = [None] + [B._padded(cap[l], dims[l], self.dtype, dev) if self.norm_act and l < L else None
                            for l in range(1, L + 1)]
-        self.bcat = i32(3 * Bn)                       # u | v | v': node ids when drawn, then positions in level L
-        self.batch = (self.bcat[:Bn], self.bcat[Bn:2 * Bn], self.bcat[2 * Bn:])
         dd, dt = self.dec_dims, B._feat_dtype(X)
         self.E = [B._padded(2 * Bn, f, self.dtype, dev) for f in dd[:-1]]
         self.Zd = [None] + [B._padded(2 * Bn, f, self.dtype, dev) for f in dd[1:]]
         self.dE = [B._padded(2 * Bn, f, self.dtype, dev) for f in dd]
-        ws_bytes = max(
-            max(B.tma_neighbor_sample_workspace_bytes(cap[l + 1]) for l in range(L)),
-            B.tma_mfg_relabel_workspace_bytes(self.n),
+        ws_bytes = max(          # the training pass's workspace (the sampler's is part of each batch's buffers)
             max((B.tma_sage_block_bwd_workspace_bytes if encoder == "sage" else B.tma_gcn_block_bwd_workspace_bytes)(
                 cap[l + 1], cap[l], self.ecap[l], dims[l], dims[l + 1], dt, l > 0) for l in range(L)),
             B.tma_pair_product_bwd_workspace_bytes(cap[L], Bn, dd[0], dt), B.tma_prelu_bwd_workspace_bytes(),
@@ -402,12 +425,20 @@ class SampledLinkTrainer(LocalTrainer):
         self.loss = torch.zeros(1, dtype=torch.float32, device=dev)
         self.steps_done = 0
 
-    def set_graph(self, rowptr, colidx, nnz):
+    def _bind(self, mfg):
+        """The batch the training pass works on."""
+        self._cur = mfg
+        self.nodes, self.count, self.blk_rowptr, self.blk_col = mfg.nodes, mfg.count, mfg.blk_rowptr, mfg.blk_col
+        self.blk_row, self.blk_inv_deg, self.bcat, self.batch = mfg.blk_row, mfg.blk_inv_deg, mfg.bcat, mfg.batch
+        self.H[0] = mfg.H0
+
+    def set_graph(self, rowptr, colidx, nnz, ready=None):
         """Point the trainer at another local graph over the same nodes, with at most the entry count given at
-        construction."""
+        construction.  ``ready``: an event after which its arrays may be read (for sampling on the second stream)."""
         if rowptr.numel() != self.n + 1 or nnz > self.nnz_cap:
             raise B.TmaError("SampledLinkTrainer.set_graph: node count or entry count beyond the allocated buffers")
         self.rowptr, self.colidx, self.nnz = rowptr, colidx, int(nnz)
+        self._inputs_ready = ready
 
     def set_data(self, X, labels=None):
         """Point the trainer at another feature table over the same nodes."""
@@ -415,25 +446,89 @@ class SampledLinkTrainer(LocalTrainer):
             raise B.TmaError("SampledLinkTrainer.set_data: X differs in shape or dtype from the one it replaces")
         self.X = X
 
-    def sample(self):
-        """The batch of this step and its message-flow graph: node lists, blocks, input features."""
-        L, Bn, st = self.L, self.batch_size, self.stream
-        self._draw_batch()
-        _, self.count[L] = B.tma_mfg_relabel(self.n, None, 0, self.bcat, 3 * Bn, src_out=self.nodes[L], ws=self.ws,
-                                             stream=st)
+    def sample(self, mfg=None, step=None, stream=None):
+        """The batch of step ``step`` (default: the next one) and its message-flow graph: node lists, blocks, input
+        features, written to ``mfg`` (default: the buffers the training pass reads) on ``stream``."""
+        mfg = self._cur if mfg is None else mfg
+        t = self.steps_done if step is None else int(step)
+        L, Bn, st = self.L, self.batch_size, self.stream if stream is None else stream
+        u, v, vneg = mfg.batch
+        B.tma_edge_batch(self.rowptr, self.colidx, self.nnz, self.batch_seed, t * Bn, Bn, u_out=u, v_out=v, vneg_out=vneg,
+                         stream=st)
+        _, mfg.count[L] = B.tma_mfg_relabel(self.n, None, 0, mfg.bcat, 3 * Bn, src_out=mfg.nodes[L], ws=mfg.ws, stream=st)
         for l in range(L - 1, -1, -1):
-            n_dst = self.count[l + 1]
-            B.tma_neighbor_sample(self.nodes[l + 1], n_dst, self.nnz, self.rowptr, self.colidx, self.fanouts[l],
-                                  B.tma_mix64(self.batch_seed, 64 * self.steps_done + l), blk_rowptr_out=self.blk_rowptr[l],
-                                  blk_col_out=self.blk_col[l], blk_row_out=self.blk_row[l], ws=self.ws, stream=st)
-            _, self.count[l] = B.tma_mfg_relabel(self.n, self.nodes[l + 1], n_dst, self.blk_col[l], self.ecap[l],
-                                                 d_items=self.blk_rowptr[l][n_dst:n_dst + 1], src_out=self.nodes[l],
-                                                 ws=self.ws, stream=st)
+            n_dst = mfg.count[l + 1]
+            B.tma_neighbor_sample(mfg.nodes[l + 1], n_dst, self.nnz, self.rowptr, self.colidx, self.fanouts[l],
+                                  B.tma_mix64(self.batch_seed, 64 * t + l), blk_rowptr_out=mfg.blk_rowptr[l],
+                                  blk_col_out=mfg.blk_col[l], blk_row_out=mfg.blk_row[l], ws=mfg.ws, stream=st)
+            _, mfg.count[l] = B.tma_mfg_relabel(self.n, mfg.nodes[l + 1], n_dst, mfg.blk_col[l], self.ecap[l],
+                                                d_items=mfg.blk_rowptr[l][n_dst:n_dst + 1], src_out=mfg.nodes[l],
+                                                ws=mfg.ws, stream=st)
             if self.encoder == "sage":
-                B.tma_block_inv_deg(self.blk_rowptr[l], n_dst, out=self.blk_inv_deg[l], stream=st)
+                B.tma_block_inv_deg(mfg.blk_rowptr[l], n_dst, out=mfg.blk_inv_deg[l], stream=st)
             else:
-                B.tma_gcn_block_norm(self.blk_rowptr[l], n_dst, out=self.blk_inv_deg[l], stream=st)
-        B.tma_gather_rows(self.nodes[0][:self.count[0]], self.X, out=self.H[0][:self.count[0]], stream=st)
+                B.tma_gcn_block_norm(mfg.blk_rowptr[l], n_dst, out=mfg.blk_inv_deg[l], stream=st)
+        B.tma_gather_rows(mfg.nodes[0][:mfg.count[0]], self.X, out=mfg.H0[:mfg.count[0]], stream=st)
+        mfg.step = t
+
+    def enable_prefetch(self, stream=None, auto=True, background=False):
+        """From now on ``step`` trains on a batch sampled ahead on a second stream (``stream``, or a new one of
+        default priority) into a second set of buffers; see the class description.  ``auto``: every step starts
+        the sampling of the next one itself; otherwise the caller does, with prefetch_sample(), once the graph and
+        features of the next step are known (set_graph / set_data).  ``background``: the sampling calls, with
+        their waits for the level sizes, are made by a worker thread, so that the calling thread goes straight on
+        to enqueue the next training pass (the library's calls release the interpreter lock)."""
+        self._drain()
+        self._side = stream if stream is not None else torch.cuda.Stream(device=self.W.device)
+        self._auto, self._pending = bool(auto), None
+        if background and self._worker is None:
+            from concurrent.futures import ThreadPoolExecutor
+            self._worker = ThreadPoolExecutor(max_workers=1, thread_name_prefix="tma-sampler")
+        elif not background and self._worker is not None:
+            self._worker.shutdown(wait=True)
+            self._worker = None
+        if len(self._mfgs) < 2:
+            self._mfgs.append(_Mfg(self.cap, self.ecap, self.batch_size, self.dims[0], self.n, self.dtype, self.W.device))
+
+    def _drain(self):
+        """Wait for a sampling that a worker thread is still making."""
+        if self._pending is not None and hasattr(self._pending, "result"):
+            self._pending = self._pending.result()
+
+    def disable_prefetch(self):
+        """Back to sampling inside ``step`` on the training stream (waits for a sampling that is under way)."""
+        self._drain()
+        if self._side is not None:
+            self._side.synchronize()
+        if self._worker is not None:
+            self._worker.shutdown(wait=True)
+        self._side = self._pending = self._worker = None
+
+    def prefetch_sample(self, prepare=None):
+        """Start sampling the next step's batch on the second stream, from the graph and feature table the trainer
+        points at (after the event given with set_graph, if any).  The level sizes are waited for here, or by the
+        worker thread, while the training stream works through what has been enqueued.  ``prepare``: called first,
+        in the thread that samples (e.g. the next step's extraction followed by set_graph / set_data)."""
+        if self._side is None:
+            raise B.TmaError("SampledLinkTrainer.prefetch_sample: call enable_prefetch() first")
+        self._drain()
+        t = self.steps_done
+        mfg, side = self._mfgs[t % 2], self._side
+
+        def work():
+            if prepare is not None:
+                prepare()
+            with torch.cuda.stream(side):
+                if mfg.released is not None:        # the training pass that last read these buffers
+                    side.wait_event(mfg.released)
+                if self._inputs_ready is not None:
+                    side.wait_event(self._inputs_ready)
+                self.sample(mfg, t, side)
+                mfg.ready = torch.cuda.Event()
+                mfg.ready.record(side)
+            return mfg
+
+        self._pending = self._worker.submit(work) if self._worker is not None else work()
 
     def _block_fwd(self, l, act, out):
         block_fwd = B.tma_sage_block_fwd if self.encoder == "sage" else B.tma_gcn_block_fwd
@@ -481,11 +576,25 @@ class SampledLinkTrainer(LocalTrainer):
 
     def step(self, lr: float):
         """One iteration of Alg. 2's loop body on the sampled neighbourhood of one mini-batch."""
-        self.sample()
+        if self._side is None:
+            self.sample()
+        else:
+            self._drain()
+            if self._pending is None or self._pending.step != self.steps_done:
+                self.prefetch_sample()             # nothing sampled ahead (first step, or the step count was set)
+                self._drain()
+            mfg, self._pending = self._pending, None
+            self.stream.wait_event(mfg.ready)
+            self._bind(mfg)
         R = self.forward()
         self._decoder_forward(R)
         self.backward()
         self._optimizer_step(lr)
+        if self._side is not None:
+            self._cur.released = torch.cuda.Event()
+            self._cur.released.record(self.stream)
+            if self._auto:
+                self.prefetch_sample()
         return self.loss
 
 

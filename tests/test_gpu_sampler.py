@@ -306,6 +306,56 @@ def test_sampled_link_prediction_training_steps(B, fanouts, Bn, norm_act, encode
     assert np.isfinite(losses).all()      # (every step sees another batch: the loss need not fall step by step)
 
 
+@pytest.mark.parametrize("encoder", ["sage", "gcn"])
+def test_sampling_one_step_ahead_on_a_second_stream_changes_nothing(B, encoder):
+    """With enable_prefetch() every step trains on the batch that was sampled, on a second stream and into a second
+    set of buffers, while the step before it trained: the same batches, blocks and bits as sampling inside the step.
+    Also when the caller drives the sampling itself and swaps the feature table between steps."""
+    from paper_2305_09887_amd.trainer import SampledLinkTrainer
+    N, K, dims, dec_dims, fanouts, Bn = 20_000, 4, [64, 96, 32], [32, 48, 1], [5, 10], 400
+    rowptr, colidx = synth.chung_lu_graph(N, 12, 2.1, seed=1)
+    X = synth.features(N, dims[0], seed=2)
+    rng = np.random.default_rng(7)
+    enc = [tuple(l) if encoder == "sage" else (l[0], l[2]) for l in synth.sage_params(dims, seed=5)]
+    dec = [(synth.glorot(32, 48, rng).astype(np.float32), np.array([0.25], np.float32)),
+           (synth.glorot(48, 1, rng).astype(np.float32),)]
+    sub = oracle.induced_subgraph(rowptr, colidx, oracle.partition(N, K, seed=4), 0)
+    rp, ci, Xd = dev(sub["rowptr"]), dev(sub["colidx"]), dev(X[sub["l2g"]])
+    X2 = Xd.clone()                                       # a second table with the same values at another address
+
+    def make():
+        return SampledLinkTrainer(rp, ci, int(sub["rowptr"][-1]), Xd, dims, dec_dims, fanouts, Bn, batch_seed=99,
+                                  params=enc, decoder_params=dec, encoder=encoder)
+
+    plain, ahead, driven = make(), make(), make()
+    ahead.enable_prefetch(background=True)                # a worker thread makes the sampling calls
+    driven.enable_prefetch(auto=False)
+    for step in range(5):
+        lp = plain.step(0.5).item()
+        la = ahead.step(0.5).item()
+        if step == 0:
+            driven.prefetch_sample()
+        ld = driven.step(0.5).item()
+        driven.set_data(X2 if step % 2 == 0 else Xd)      # the next batch reads the other table
+        driven.prefetch_sample()
+        for other, l in ((ahead, la), (driven, ld)):
+            assert l == lp, f"loss at step {step}"
+            assert other.count == plain.count
+            for a, b in zip(other.batch, plain.batch):
+                assert torch.equal(a, b)
+            for l_ in range(3):
+                assert torch.equal(other.nodes[l_][:plain.count[l_]], plain.nodes[l_][:plain.count[l_]])
+            for l_ in range(2):
+                n_dst = plain.count[l_ + 1]
+                e = int(plain.blk_rowptr[l_][n_dst])
+                assert torch.equal(other.blk_rowptr[l_][:n_dst + 1], plain.blk_rowptr[l_][:n_dst + 1])
+                assert torch.equal(other.blk_col[l_][:e], plain.blk_col[l_][:e])
+            assert torch.equal(other.W, plain.W), f"weights after step {step}"
+    ahead.disable_prefetch()
+    assert ahead.step(0.5).item() == plain.step(0.5).item() and torch.equal(ahead.W, plain.W)
+    torch.cuda.synchronize()
+
+
 def test_sampled_link_prediction_bf16_storage(B):
     """The sampled link-prediction step with bf16 feature / activation storage (bf16 MFMA products, fp32
     accumulation and parameters): one step against the oracle at the bf16 tolerance; structure bit for bit."""
