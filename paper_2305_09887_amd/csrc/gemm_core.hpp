@@ -1006,9 +1006,6 @@ __global__ __launch_bounds__(WM *WN * 64, (BK * sizeof(CT) <= 64 && !Epi::kRowAu
 
         // one slab from LDS buffer `buf`: fragment reads one group ahead of the MFMAs that use them
         auto multiply = [&](int buf) {
-#if defined(TMA_GEMM_IGLP)
-            __builtin_amdgcn_iglp_opt(TMA_GEMM_IGLP);
-#endif
             Frag fa[2][TM], fb[2][TN];
 #pragma unroll
             for (int i = 0; i < TM; ++i) fa[0][i] = frag_a(buf, 0, i);
