@@ -211,10 +211,12 @@ def main():
                     help="positive edges per step of the link tasks (default 65536; 1024 for link-sampled)")
     ap.add_argument("--fanouts", default="10,25",
                     help="link-sampled: neighbours kept per node, first layer first (the layer next to the batch last)")
-    ap.add_argument("--extract", choices=("async", "sync"), default="async",
+    ap.add_argument("--extract", choices=("async", "sync", "fused"), default="async",
                     help="async (default): the step enqueues the extraction over capacity-sized buffers and never waits for "
                          "the GPU (the sizes, known from the set-up pass, are checked on the device values after the timed "
-                         "region); sync: the two-pass extraction that returns the sizes to the host in every step")
+                         "region); sync: the two-pass extraction that returns the sizes to the host in every step; fused: "
+                         "as async, with RandomTMA's assignment recomputed inside the extraction instead of a separate "
+                         "assignment kernel and part array (tma_random_subgraph_async)")
     ap.add_argument("--graph", action="store_true",
                     help="beside the headline: capture one whole step (assignment, extraction, row gathers, training pass, "
                          "averaging) as a HIP graph and time its replays (node task, SGD)")
@@ -380,7 +382,11 @@ def main():
     two_stream = SubgraphPrefetcher(d_rowptr, d_colidx, N, K, p, cap, cap_nnz, tables=(d_X,) if sampled else (d_X, d_y))
     state = {"next": None, "trained": None}
 
-    held = B.tma_induced_subgraph_async(d_rowptr, d_colidx, part, p, cap, cap_nnz) if args.extract == "async" else None
+    held = None
+    if args.extract == "async":
+        held = B.tma_induced_subgraph_async(d_rowptr, d_colidx, part, p, cap, cap_nnz)
+    elif args.extract == "fused":
+        held = B.tma_random_subgraph_async(d_rowptr, d_colidx, K, sd["part"], p, cap, cap_nnz)
 
     def prepare_sampled(prefetch, after):
         """Sampled task: the next step's assignment, extraction, row gather AND batch sampling on the extraction
@@ -398,9 +404,13 @@ def main():
 
     def step(prefetch=two_stream if args.prefetch else None):
         if prefetch is None:
-            B.tma_partition(N, K, sd["part"], out=part)
+            if args.extract != "fused":
+                B.tma_partition(N, K, sd["part"], out=part)
             if held is not None:      # same buffers every step; views at the sizes the set-up pass reported
-                B.tma_induced_subgraph_async(d_rowptr, d_colidx, part, p, cap, cap_nnz, out=held)
+                if args.extract == "fused":
+                    B.tma_random_subgraph_async(d_rowptr, d_colidx, K, sd["part"], p, cap, cap_nnz, out=held)
+                else:
+                    B.tma_induced_subgraph_async(d_rowptr, d_colidx, part, p, cap, cap_nnz, out=held)
                 s = dict(l2g=held["l2g"][:n_loc], rowptr=held["rowptr"][:n_loc + 1], colidx=held["colidx"][:nnz_loc],
                          inv_deg=held["inv_deg"][:n_loc], nnz_loc=nnz_loc)
             else:

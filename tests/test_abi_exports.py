@@ -54,6 +54,32 @@ def test_host_side_argument_validation_needs_no_gpu(lib):
     assert large >= small + 1000 * 64 * 4
 
 
+def test_extraction_entry_points_reject_bad_arguments_before_touching_a_device(lib):
+    """The no-wait and fused forms of the extraction: every refusal below happens in host code."""
+    lib.tma_last_error.restype = ctypes.c_char_p
+    i64, i32, u64, sz = ctypes.c_int64, ctypes.c_int32, ctypes.c_uint64, ctypes.c_size_t
+    fake = ctypes.c_void_p(4096)            # a non-NULL, 256-byte aligned address that is never dereferenced
+
+    def fused(n, K, p, cap_n, cap_e, sizes=fake, ws=fake, ws_bytes=1 << 40):
+        return lib.tma_random_subgraph_async(i64(n), fake, fake, i32(K), u64(7), i32(p), fake, fake, fake, fake, fake,
+                                             i64(cap_n), i64(cap_e), sizes, ws, sz(ws_bytes), None)
+
+    assert fused(100, 0, 0, 10, 10) < 0 and b"K outside" in lib.tma_last_error()
+    assert fused(100, 4, 4, 10, 10) < 0 and b"p outside" in lib.tma_last_error()
+    assert fused(100, 4, 1, 10, -1) < 0 and b"cap_nnz_loc" in lib.tma_last_error()
+    assert fused(100, 4, 1, 10, 10, sizes=None) < 0 and b"d_sizes_out" in lib.tma_last_error()
+    assert fused(100, 4, 1, 101, 10) < 0 and b"cap_n_loc" in lib.tma_last_error()
+    assert fused(-1, 4, 1, 0, 0) < 0 and b"n_nodes" in lib.tma_last_error()
+    assert fused(100, 4, 1, 10, 10, ws=ctypes.c_void_p(4100)) < 0 and b"aligned" in lib.tma_last_error()
+    assert fused(100, 4, 1, 10, 10, ws_bytes=16) < 0 and b"workspace" in lib.tma_last_error()
+    rc = lib.tma_induced_subgraph_async(i64(100), fake, fake, None, i32(0), fake, fake, fake, fake, fake, i64(10), i64(10),
+                                        fake, fake, sz(1 << 40), None)
+    assert rc < 0 and b"part" in lib.tma_last_error()
+    lib.tma_gcn_block_bwd_workspace_bytes.restype = sz
+    assert lib.tma_gcn_block_bwd_workspace_bytes(i64(10), i64(5), i64(0), 8, 8, 0, 1) == 0      # n_src < n_dst
+    assert lib.tma_gcn_block_bwd_workspace_bytes(i64(10), i64(50), i64(200), 8, 8, 0, 1) % 256 == 0
+
+
 def test_host_generator_reproduces_the_published_vector(lib):
     """tma_mix64 is host code: the library's generator against the published SplitMix64 outputs for seed 1234567
     (the same fixture that pins the oracle's), no GPU needed."""
