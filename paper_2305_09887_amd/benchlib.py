@@ -38,28 +38,33 @@ def padded_width(F: int, s: int) -> int:
 
 
 def sage_layer_work(n: int, nnz: int, dims, s: int, dt: int):
-    """{(phase, layer, family): (bound, algorithmic work of that launch)} for an L-layer model on one graph.
+    """{(phase, layer, family): (bound, algorithmic work of that launch[, bytes of a product])} for an L-layer
+    model on one graph.
 
     Bytes count every array the kernel must touch once (each distinct input row once however often it is gathered,
-    outputs once: the B_min of a gather); flops count the products of the layer's definition, no padding."""
+    outputs once: the B_min of a gather); flops count the products of the layer's definition, no padding.  A
+    product also carries the bytes of its streamed operands and results (weights left out), because with bf16
+    storage its honest ceiling is the smaller of the matrix peak and intensity x HBM bandwidth."""
     out = {}
+    L = len(dims) - 1
     for l, (Fi, Fo) in enumerate(zip(dims[:-1], dims[1:])):
         Fp = padded_width(Fo, s)
+        g = (2.0 if l < L - 1 else 1.0) * n * Fo * s     # the upstream gradient, and the layer output as ReLU mask
         if B.tma_sage_layer_aggregates_first(Fi, Fo, dt):
             out[("fwd", l, "spmm_mean")] = ("hbm", 2.0 * n * Fi * s + nnz * 4 + n * 8)
-            out[("fwd", l, "gemm_fwd")] = ("mfma", 2.0 * n * 2 * Fi * Fo)
-            out[("bwd", l, "gemm_bwd_weight")] = ("mfma", 2.0 * n * 2 * Fi * Fo)
+            out[("fwd", l, "gemm_fwd")] = ("mfma", 2.0 * n * 2 * Fi * Fo, n * 2.0 * Fi * s + n * Fo * s)
+            out[("bwd", l, "gemm_bwd_weight")] = ("mfma", 2.0 * n * 2 * Fi * Fo, n * 2.0 * Fi * s + g)
             if l > 0:
-                out[("bwd", l, "gemm_bwd_data")] = ("mfma", 2.0 * n * Fo * 2 * Fi)
+                out[("bwd", l, "gemm_bwd_data")] = ("mfma", 2.0 * n * Fo * 2 * Fi, g + n * 2.0 * Fi * s)
                 out[("bwd", l, "spmm_sum")] = ("hbm", 3.0 * n * Fi * s + nnz * 4 + n * 4)    # dM rows once; dH read + written
         else:
-            out[("fwd", l, "gemm_tf_fwd")] = ("mfma", 2.0 * n * Fi * 2 * Fo)
+            out[("fwd", l, "gemm_tf_fwd")] = ("mfma", 2.0 * n * Fi * 2 * Fo, n * Fi * s + n * 2.0 * Fp * s)
             out[("fwd", l, "spmm_combine")] = ("hbm", 3.0 * n * Fp * s + nnz * 4 + n * 8)    # Yn rows once, Ys, output
             out[("bwd", l, "scale_mask_rows")] = ("hbm", float(n * Fo * s + n * 4 + n * Fp * s))
             out[("bwd", l, "spmm_sum")] = ("hbm", 2.0 * n * Fp * s + nnz * 4 + n * 4)
-            out[("bwd", l, "gemm_tf_bwd_weight")] = ("mfma", 2.0 * n * Fi * 2 * Fo)
+            out[("bwd", l, "gemm_tf_bwd_weight")] = ("mfma", 2.0 * n * Fi * 2 * Fo, n * Fi * s + g + n * Fp * s)
             if l > 0:
-                out[("bwd", l, "gemm_tf_bwd_data")] = ("mfma", 2.0 * n * 2 * Fo * Fi)
+                out[("bwd", l, "gemm_tf_bwd_data")] = ("mfma", 2.0 * n * 2 * Fo * Fi, g + n * Fp * s + n * Fi * s)
     return out
 
 
@@ -116,7 +121,7 @@ class LayerWindows:
 def work_by_name(windows, layer_work):
     """Mean algorithmic work per launch of every kernel NAME that the layers launch: a name that several layers
     use with different shapes gets the mean over its launches of a step."""
-    tot, cnt, bound = {}, {}, {}
+    tot, cnt, bound, byt = {}, {}, {}, {}
     for (phase, l, name), (launches, _) in windows.items():
         fam = family(name)
         hit = layer_work.get((phase, l, fam))
@@ -125,7 +130,10 @@ def work_by_name(windows, layer_work):
         tot[name] = tot.get(name, 0.0) + hit[1]
         cnt[name] = cnt.get(name, 0.0) + launches
         bound[name] = hit[0]
-    return {k: (bound[k], tot[k] / max(cnt[k], 1.0)) for k in tot}
+        if len(hit) > 2:
+            byt[name] = byt.get(name, 0.0) + hit[2]
+    return {k: (bound[k], tot[k] / max(cnt[k], 1.0)) + ((byt[k] / max(cnt[k], 1.0),) if k in byt else ())
+            for k in tot}
 
 
 def load_traffic(config_key: str):
@@ -140,7 +148,7 @@ def load_traffic(config_key: str):
 def rooflines(per_step, prof, repeats, work_of, peak_mfma, traffic):
     out = {}
     for k, ms in per_step.items():
-        b, wk = work_of(k)
+        b, wk, *streamed = work_of(k)
         launches = prof[k][0] / float(repeats)
         if b is None or ms <= 0 or launches <= 0:
             continue
@@ -153,20 +161,28 @@ def rooflines(per_step, prof, repeats, work_of, peak_mfma, traffic):
         out[k] = {"bound": b, "achieved": round(a, 2), "peak": peak, "unit": unit, "frac": round(a / peak, 4),
                   "us_per_launch": round(sec * 1e6, 2), "traffic": tr,
                   "traffic_GBs": round(tr / sec / 1e9, 1) if tr else None}
+        if streamed:      # a product against its other ceiling: streamed operands and results per time
+            out[k]["streamed_GBs"] = round(streamed[0] / sec / 1e9, 1)
+            out[k]["hbm_frac"] = round(streamed[0] / sec / 1e9 / PEAK_HBM_GBS, 4)
     return out
 
 
 def dominant_roofline(name, dom, work_of, peak_mfma, traffic):
-    bound, work = work_of(name)
+    bound, work, *streamed = work_of(name)
     avg_ms = dom[1] / max(dom[0], 1)
     if bound == "mfma":
         achieved, peak, unit = work / (avg_ms * 1e-3) / 1e12, peak_mfma, "TFLOP/s"
     else:
         bound = "hbm"
         achieved, peak, unit = work / (avg_ms * 1e-3) / 1e9, PEAK_HBM_GBS, "GB/s"
-    return dict(bound=bound, kernel=name, achieved=round(achieved, 3), peak=peak, unit=unit,
-                frac=round(achieved / peak, 4), traffic=traffic.get(name), avg_launch_ms=round(avg_ms, 5),
-                launches=dom[0], algorithmic_work_per_launch=work)
+    out = dict(bound=bound, kernel=name, achieved=round(achieved, 3), peak=peak, unit=unit,
+               frac=round(achieved / peak, 4), traffic=traffic.get(name), avg_launch_ms=round(avg_ms, 5),
+               launches=dom[0], algorithmic_work_per_launch=work)
+    if streamed:
+        out["streamed_bytes_per_launch"] = streamed[0]
+        out["streamed_GBs"] = round(streamed[0] / (avg_ms * 1e-3) / 1e9, 1)
+        out["hbm_frac"] = round(streamed[0] / (avg_ms * 1e-3) / 1e9 / PEAK_HBM_GBS, 4)
+    return out
 
 
 def _log(msg):
@@ -709,7 +725,9 @@ def summarize_kernel_stats(config_key, stats_dir, bench_json, command):
         for k, v in bench["kernel_ms_per_step"].items():
             r = bench["kernel_rooflines"].get(k)
             if r:
-                f.write("  %-34s %9.1f us/step  %9.1f %s  (%.1f %% of %s)\n" % (k, v * 1e3, r["achieved"], r["unit"], r["frac"] * 100, r["peak"]))
+                also = ("; operands + results %.0f GB/s = %.1f %% of the HBM peak" % (r["streamed_GBs"], r["hbm_frac"] * 100)
+                        if "hbm_frac" in r else "")
+                f.write("  %-34s %9.1f us/step  %9.1f %s  (%.1f %% of %s%s)\n" % (k, v * 1e3, r["achieved"], r["unit"], r["frac"] * 100, r["peak"], also))
             else:
                 f.write("  %-34s %9.1f us/step\n" % (k, v * 1e3))
         for extra in ("aggregation", "cpu_baseline", "per_layer_fwd_bwd", "two_stream"):
