@@ -29,6 +29,9 @@ struct DenseEpilogue {  // out = act(acc + b)  or  row_scale[row] * acc
         return v;
     }
     __device__ __forceinline__ void store(int64_t row, int col, float v, int) const { narrow1(out + row * ld + col, v); }
+    static constexpr bool kPairs = sizeof(T) == 2;
+    __device__ __forceinline__ bool pairs_ok() const { return ld % 2 == 0 && word_aligned(out); }
+    __device__ __forceinline__ T *at(int64_t row, int col) const { return out + row * ld + col; }
 };
 
 static int pad8(int32_t F) { return int(round_up(size_t(F), 8)); }

@@ -697,6 +697,28 @@ struct SideGrad {
 // Epilogues.  col_aux / row_aux are fetched once per tile column / row with a
 // clamped (always valid) index; value() is pure arithmetic on registers.
 // ---------------------------------------------------------------------------
+// Two-byte results: an epilogue that can name the address of an element (at) and vouches that columns 2c and 2c + 1
+// of a row are one aligned 4-byte word (pairs_ok) lets neighbouring lanes trade every other value, so that each
+// lane stores two columns of one row in one instruction instead of one column of two rows in two.
+template <class E, class = void>
+struct StoresPairs : std::false_type {};
+template <class E>
+struct StoresPairs<E, std::void_t<decltype(&E::pairs_ok)>> : std::bool_constant<E::kPairs> {};
+
+__device__ __forceinline__ bool word_aligned(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 3) == 0; }
+
+template <class E>
+__device__ __forceinline__ bool pairs_ok_of(const E &e)
+{
+    if constexpr (StoresPairs<E>::value) return e.pairs_ok();
+    else return false;
+}
+template <class E>
+__device__ __forceinline__ void store_pair(const E &e, int64_t row, int col, uint32_t word)
+{
+    if constexpr (StoresPairs<E>::value) *reinterpret_cast<uint32_t *>(e.at(row, col)) = word;
+}
+
 template <typename T>
 struct FwdEpilogue {  // H' = act(acc + b)
     static constexpr bool kColAux = true, kRowAux = false;
@@ -713,6 +735,9 @@ struct FwdEpilogue {  // H' = act(acc + b)
         return v;
     }
     __device__ __forceinline__ void store(int64_t row, int col, float v, int) const { narrow1(out + row * ld + col, v); }
+    static constexpr bool kPairs = sizeof(T) == 2;
+    __device__ __forceinline__ bool pairs_ok() const { return ld % 2 == 0 && word_aligned(out); }
+    __device__ __forceinline__ T *at(int64_t row, int col) const { return out + row * ld + col; }
 };
 
 template <typename T>
@@ -731,6 +756,15 @@ struct BwdDataEpilogue {  // columns [0,F): dH_self (leading dimension ldh) ; [F
         if (col < F) narrow1(dH + row * ldh + col, v);
         else narrow1(dMs + row * F + (col - F), v);
     }
+    static constexpr bool kPairs = sizeof(T) == 2;
+    __device__ __forceinline__ bool pairs_ok() const
+    {
+        return ldh % 2 == 0 && F % 2 == 0 && word_aligned(dH) && word_aligned(dMs);
+    }
+    __device__ __forceinline__ T *at(int64_t row, int col) const
+    {
+        return col < F ? dH + row * ldh + col : dMs + row * F + (col - F);
+    }
 };
 
 template <typename T>
@@ -748,6 +782,15 @@ struct HalvesEpilogue {  // columns [0,Fp): Y_self ; [Fp,2Fp): Y_neigh ; both [r
         if (col < Fp) narrow1(Ys + row * ldy + col, v);
         else narrow1(Yn + row * ldy + (col - Fp), v);
     }
+    static constexpr bool kPairs = sizeof(T) == 2;
+    __device__ __forceinline__ bool pairs_ok() const
+    {
+        return ldy % 2 == 0 && Fp % 2 == 0 && word_aligned(Ys) && word_aligned(Yn);
+    }
+    __device__ __forceinline__ T *at(int64_t row, int col) const
+    {
+        return col < Fp ? Ys + row * ldy + col : Yn + row * ldy + (col - Fp);
+    }
 };
 
 template <typename T>
@@ -759,6 +802,9 @@ struct RowsEpilogue {  // plain [rows, ld] output
     __device__ __forceinline__ float row_aux(int64_t) const { return 0.0f; }
     __device__ __forceinline__ float value(float v, float, float, int) const { return v; }
     __device__ __forceinline__ void store(int64_t row, int col, float v, int) const { narrow1(out + row * ld + col, v); }
+    static constexpr bool kPairs = sizeof(T) == 2;
+    __device__ __forceinline__ bool pairs_ok() const { return ld % 2 == 0 && word_aligned(out); }
+    __device__ __forceinline__ T *at(int64_t row, int col) const { return out + row * ld + col; }
 };
 
 struct SplitEpilogue {  // partial products, one slab per split
@@ -1113,6 +1159,8 @@ __global__ __launch_bounds__(WM *WN * 64, (BK * sizeof(CT) <= 64 && !Epi::kRowAu
         for (int j = 0; j < TN; ++j) caux[j] = Epi::kColAux ? a_aux[wn0 + j * 32 + l31] : 0.0f;
         auto write_out = [&](auto inside_tag) {
             constexpr bool kInside = decltype(inside_tag)::value;   // the whole tile lies inside the result
+            bool pairs = false;
+            if constexpr (kInside && StoresPairs<Epi>::value) pairs = pairs_ok_of(epi);   // the same for every lane
 #pragma unroll
             for (int i = 0; i < TM; ++i) {
                 float raux[16];
@@ -1122,6 +1170,24 @@ __global__ __launch_bounds__(WM *WN * 64, (BK * sizeof(CT) <= 64 && !Epi::kRowAu
 #pragma unroll
                 for (int j = 0; j < TN; ++j) {
                     const int col = done.n0 + wn0 + j * 32 + l31;
+                    if constexpr (kInside && StoresPairs<Epi>::value) {
+                        if (pairs) {
+                            // registers r and r + 1 are rows R and R + 1 of this lane's column: an odd lane gives its
+                            // row-R value to the even lane on its left and gets that lane's row-R+1 value, so the
+                            // even lane holds (col, col + 1) of row R and the odd one (col - 1, col) of row R + 1
+                            const int odd = l31 & 1;
+#pragma unroll
+                            for (int r = 0; r < 16; r += 2) {
+                                const int64_t row = done.m0 + wm0 + i * 32 + 8 * (r / 4) + 4 * hi + (r % 4);
+                                const float v0 = epi.value(acc[i][j][r], caux[j], raux[r], col);
+                                const float v1 = epi.value(acc[i][j][r + 1], caux[j], raux[r + 1], col);
+                                const float got = __shfl_xor(odd ? v0 : v1, 1, kWave);
+                                const uint32_t word = odd ? pack_bf16(got, v1) : pack_bf16(v0, got);
+                                store_pair(epi, row + odd, col - odd, word);
+                            }
+                            continue;
+                        }
+                    }
 #pragma unroll
                     for (int r = 0; r < 16; ++r) {
                         const int64_t row = done.m0 + wm0 + i * 32 + 8 * (r / 4) + 4 * hi + (r % 4);
