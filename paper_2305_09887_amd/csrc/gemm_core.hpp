@@ -41,6 +41,16 @@ constexpr int kXcds = 8;  // MI355X: 8 accelerator dies, workgroups are dealt ro
 
 __device__ __forceinline__ float4 zero4() { return make_float4(0.0f, 0.0f, 0.0f, 0.0f); }
 
+// f(integral_constant<int, 0>), ..., f(integral_constant<int, N - 1>): a loop whose index is a constant in the body
+template <int N, class F>
+__device__ __forceinline__ void static_for(F &&f)
+{
+    if constexpr (N > 0) {
+        static_for<N - 1>(f);
+        f(std::integral_constant<int, N - 1>{});
+    }
+}
+
 // ---------------------------------------------------------------------------
 // Storage types.  T = float (fp32 storage) or uint16_t (bf16 storage).  The
 // views hand every operand over as fp32 quads (bf16 widened exactly); TileMath
@@ -915,6 +925,7 @@ __global__ __launch_bounds__(WM *WN * 64, (BK * sizeof(CT) <= 64 && !Epi::kRowAu
 {
     constexpr int NT = WM * WN * 64;
     constexpr bool kPrefetch2 = DeepPrefetch<CT, kColSum, Epi::kRowAux>::value && (BM / WM / 32) * (BN / WN / 32) <= 4;   // (8 accumulator tiles leave no registers for it)
+    constexpr int kDepth = 2;   // slabs in flight in registers (3 and 4 measured: no faster for any product, the wide forward one slower)
     constexpr int TM = BM / WM / 32;
     constexpr int TN = BN / WN / 32;
     constexpr int A_Q = BM * BK / 4, B_Q = BN * BK / 4;   // 16-byte pieces of a slab
@@ -1095,23 +1106,27 @@ __global__ __launch_bounds__(WM *WN * 64, (BK * sizeof(CT) <= 64 && !Epi::kRowAu
                 // Two slabs in flight in registers beside the two in LDS: a slab's loads are issued two iterations
                 // before it is staged.  One iteration's matrix work is far shorter than a memory round trip under
                 // load, so with a single slab in flight every iteration ends up waiting for one.
-                typename AL::Raw areg[2][A_V];
-                typename BL::Raw breg[2][B_V];
+                // (kDepth register sets: slab s >= 1 waits in set (s - 1) % kDepth)
+                typename AL::Raw areg[kDepth][A_V];
+                typename BL::Raw breg[kDepth][B_V];
                 const int64_t n_slabs = (t.k_end - t.k_begin) / BK;
-                if (n_slabs > 1) fetch_plain(t.k_begin + BK, areg[0], breg[0]);
-                if (n_slabs > 2) fetch_plain(t.k_begin + 2 * BK, areg[1], breg[1]);
+                static_for<kDepth>([&](auto d_tag) {
+                    constexpr int D = decltype(d_tag)::value;
+                    if (n_slabs > D + 1) fetch_plain(t.k_begin + (D + 1) * BK, areg[D], breg[D]);
+                });
                 int buf = 0;
-                auto step = [&](int64_t sl, auto r_tag) {
-                    constexpr int R = decltype(r_tag)::value;
-                    multiply(buf);
-                    if (sl + 1 < n_slabs) stage(buf ^ 1, areg[R], breg[R]);
-                    if (sl + 3 < n_slabs) fetch_plain(t.k_begin + (sl + 3) * BK, areg[R], breg[R]);
-                    __syncthreads();
-                    buf ^= 1;
-                };
-                for (int64_t sl = 0; sl < n_slabs; sl += 2) {
-                    step(sl, std::integral_constant<int, 0>{});
-                    if (sl + 1 < n_slabs) step(sl + 1, std::integral_constant<int, 1>{});
+                for (int64_t sl0 = 0; sl0 < n_slabs; sl0 += kDepth) {
+                    static_for<kDepth>([&](auto r_tag) {
+                        constexpr int R = decltype(r_tag)::value;
+                        const int64_t sl = sl0 + R;
+                        if (sl < n_slabs) {      // the same for every thread
+                            multiply(buf);
+                            if (sl + 1 < n_slabs) stage(buf ^ 1, areg[R], breg[R]);
+                            if (sl + 1 + kDepth < n_slabs) fetch_plain(t.k_begin + (sl + 1 + kDepth) * BK, areg[R], breg[R]);
+                            __syncthreads();
+                            buf ^= 1;
+                        }
+                    });
                 }
             } else {
                 typename AL::Raw areg[A_V];
