@@ -227,6 +227,9 @@ def main():
     ap.add_argument("--fused-assignment", action="store_true",
                     help="with --extraction: RandomTMA's assignment recomputed inside the extraction "
                          "(tma_random_subgraph_async) instead of tma_partition + tma_induced_subgraph_async")
+    ap.add_argument("--library-reference", action="store_true",
+                    help="no step of the path: time the layers' dense products as PLAIN products through the vendor "
+                         "library behind torch.matmul, at the same shapes, as a yardstick for the hand-written ones")
     ap.add_argument("--config", type=int, choices=(0, 1, 2, 3, 4), default=1,
                     help="which of the configured workloads: 1 = the headline (default); 0 = the tiny case; 2 = SuperTMA at "
                          "full size; 3 = one trainer's share at billion-edge scale; 4 = 8 trainers on 8 streams with "
@@ -294,6 +297,9 @@ def main():
         torch.cuda.synchronize()
         print(json.dumps({"calibrate_copy_bytes_read": src.numel() * 4, "calibrate_copy_bytes_written": src.numel() * 4,
                           "copies": 5}))
+        return
+    if args.library_reference:
+        print(json.dumps(benchlib.run_library_reference(args)), flush=True)
         return
     if args.extraction:
         out, _ = benchlib.run_extraction(args)

@@ -388,6 +388,60 @@ def run_extraction(args):
     return out, None
 
 
+# --------------------------------------------------------------- the vendor library's plain products, for scale
+def run_library_reference(args):
+    """NOT part of the path: the dense products of the configured layers as PLAIN matrix products through the
+    vendor library that torch.matmul calls (no concatenated operands, no bias / ReLU / mask / scale epilogues, no
+    split reduction), timed with events at the same shapes, so that the hand-written products can be read against
+    what the chip's own library reaches at these shapes.  Returns one JSON-able dict."""
+    dev = torch.device("cuda:0")
+    torch.backends.cuda.matmul.allow_tf32 = False
+
+    def timed(fn, reps):
+        for _ in range(3):
+            fn()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(reps):
+            fn()
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / reps * 1e-3
+
+    rows = []
+
+    def product(what, n, k, m, dt, reduce_rows=False, reps=20):
+        if reduce_rows:      # weight-gradient shape: [k, n] x [n, m], the long dimension reduced
+            a = torch.randn(n, k, device=dev, dtype=dt)
+            b = torch.randn(n, m, device=dev, dtype=dt)
+            sec = timed(lambda: torch.matmul(a.t(), b), reps)
+        else:
+            a = torch.randn(n, k, device=dev, dtype=dt)
+            b = torch.randn(k, m, device=dev, dtype=dt)
+            c = torch.empty(n, m, device=dev, dtype=dt)
+            sec = timed(lambda: torch.matmul(a, b, out=c), reps)
+        streamed = (n * k + n * m) * a.element_size()
+        rows.append({"what": what, "dtype": str(dt).replace("torch.", ""), "n": n, "k": k, "m": m,
+                     "us": round(sec * 1e6, 1), "TFLOPs": round(2.0 * n * k * m / sec / 1e12, 1),
+                     "streamed_GBs": round(streamed / sec / 1e9, 1)})
+        del a, b
+
+    n1 = 125_237
+    product("configs[1] layer 0 forward, [H|M] x [Ws;Wn]", n1, 256, 256, torch.float32)
+    product("configs[1] layer 0 weight gradient, [H|M]^T x dZ", n1, 256, 256, torch.float32, reduce_rows=True)
+    product("configs[1] layer 1 forward (transform first), H x [Ws|Wn]", n1, 256, 96, torch.float32)
+    product("configs[1] layer 1 weight gradient, H^T x [dZ|dYn]", n1, 256, 96, torch.float32, reduce_rows=True)
+    product("configs[1] layer 1 data gradient, [dZ|dYn] x [Ws|Wn]^T", n1, 96, 256, torch.float32)
+    product("fp32, large reduction (the library's ceiling)", 16_384, 8192, 8192, torch.float32, reps=3)
+    n3 = int(12_496_872 * args.scale)
+    product("configs[3] 256-wide layer forward", n3, 512, 256, torch.bfloat16, reps=5)
+    product("configs[3] 256-wide layer data gradient", n3, 256, 512, torch.bfloat16, reps=5)
+    product("configs[3] 256-wide layer weight gradient", n3, 512, 256, torch.bfloat16, reduce_rows=True, reps=5)
+    return {"library_reference": rows, "note": "plain products through torch.matmul (the vendor library), event-timed; "
+            "a yardstick for the hand-written fused products, not a step of the path"}
+
+
 # ----------------------------------------------------------------------------------------------- configs[3]
 def run_share(args):
     """configs[3]: one trainer's share at billion-edge scale.  The Chung-Lu graph of 100 M nodes / 1.3 B edges is not
