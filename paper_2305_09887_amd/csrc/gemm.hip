@@ -141,7 +141,7 @@ static void fwd_dispatch(int64_t n, const T *H, int64_t ldh, const T *M, int64_t
     CatWeights<VB> b{W_self, W_neigh, F_in, F_out};
     const int64_t K = 2 * int64_t(F_in);
     const int64_t kps = int64_t(round_up(size_t(K), 32));
-    if (F_out <= 64)
+    if (F_out <= 64 || few_tiles(n, F_out))
         launch_gemm<128, 64, 32, 4, 1, false, T>(kname<T>("gemm_fwd_128x64", "gemm_fwd_128x64_generic", "gemm_fwd_128x64_bf16", "gemm_fwd_128x64_bf16_generic", VA),
                                               a, b, e, n, F_out, K, kps, 1, nullptr, s);
     else if constexpr (kWideBf16 && sizeof(T) == 2 && VA) {
@@ -195,7 +195,11 @@ static void bwd_data_dispatch(int64_t n, const T *g, const T *h, int64_t ld_next
     const int64_t K = F_out;
     const char *name = kname<T>("gemm_bwd_data_128x128", "gemm_bwd_data_128x128_generic", "gemm_bwd_data_128x128_bf16",
                                 "gemm_bwd_data_128x128_bf16_generic", VA);
-    if (K <= 48) {  // short reduction: 16-wide slabs waste less of the last one
+    if (few_tiles(n, N)) {
+        const char *narrow = kname<T>("gemm_bwd_data_128x64", "gemm_bwd_data_128x64_generic", "gemm_bwd_data_128x64_bf16",
+                                      "gemm_bwd_data_128x64_bf16_generic", VA);
+        launch_gemm<128, 64, 32, 4, 1, false, T>(narrow, a, b, e, n, N, K, int64_t(round_up(size_t(K), 32)), 1, nullptr, s);
+    } else if (K <= 48) {  // short reduction: 16-wide slabs waste less of the last one
         const int64_t kps = int64_t(round_up(size_t(K), 16));
         launch_gemm<128, 128, 16, 2, 2, false, T>(name, a, b, e, n, N, K, kps, 1, nullptr, s);
     } else {

@@ -1258,11 +1258,23 @@ static const char *kname(const char *f32_vec, const char *f32_gen, const char *b
     return vec ? bf16_vec : bf16_gen;
 }
 
+// A product with few 128x128 output tiles (a sampled block, a small part) would leave compute units without a
+// workgroup or with a single one: below this many tiles (256 compute units) the narrower tile is taken, for twice
+// as many workgroups.
+#ifndef TMA_GEMM_FEW_TILES
+#define TMA_GEMM_FEW_TILES 384
+#endif
+constexpr int64_t kFewTiles = TMA_GEMM_FEW_TILES;
+static inline bool few_tiles(int64_t M, int64_t N, int n_splits = 1)
+{
+    return ceil_div(M, int64_t(128)) * ceil_div(N, int64_t(128)) * n_splits < kFewTiles;
+}
+
 template <typename CT, int BK, bool kColSum, class AL, class BL, class Epi>
 static void launch_by_width(const char *name, const AL &a, const BL &b, const Epi &e, int64_t M, int N, int64_t K,
                             int64_t kps, int n_splits, float *colsum, hipStream_t s)
 {
-    if (N <= 64) launch_gemm<128, 64, BK, 4, 1, kColSum, CT>(name, a, b, e, M, N, K, kps, n_splits, colsum, s);
+    if (N <= 64 || few_tiles(M, N, n_splits)) launch_gemm<128, 64, BK, 4, 1, kColSum, CT>(name, a, b, e, M, N, K, kps, n_splits, colsum, s);
     else if (N <= 96) launch_gemm<128, 96, BK, 4, 1, kColSum, CT>(name, a, b, e, M, N, K, kps, n_splits, colsum, s);
     else launch_gemm<128, 128, BK, 2, 2, kColSum, CT>(name, a, b, e, M, N, K, kps, n_splits, colsum, s);
 }

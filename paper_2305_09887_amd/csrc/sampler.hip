@@ -71,18 +71,17 @@ __global__ __launch_bounds__(256) void sample_fill_short_kernel(int64_t n_dst, c
     }
 }
 
-// The fanout-th smallest key of a row whose keys fit NC registers per lane (chunk c of the row: entry
-// c * 64 + lane), found bit by bit from the top: per bit one count over the row (ballots), no sorting.  On return
+// The fanout-th smallest of `count` keys (key_at(j), j < count) that fit NC registers per lane (chunk c: key
+// c * 64 + lane), found bit by bit from the top: per bit one count over the keys (ballots), no sorting.  On return
 // T is that key and `remaining` says how many of the keys equal to T are still needed after all keys below T.
-// Lanes past the row hold the all-ones key, which never counts as having a zero bit.
-template <int NC>
-__device__ __forceinline__ void threshold_in_registers(uint64_t seed, int32_t beg, int32_t d, int lane, int32_t fanout,
-                                                       uint64_t &T, int32_t &remaining)
+// Lanes past the end hold the all-ones key, which never counts as having a zero bit.
+template <int NC, class KeyAt>
+__device__ __forceinline__ void threshold_in_registers(int32_t count, int lane, int32_t fanout, KeyAt key_at, uint64_t &T,
+                                                       int32_t &remaining)
 {
     uint64_t kreg[NC];
 #pragma unroll
-    for (int c = 0; c < NC; ++c)
-        kreg[c] = (c * kWave + lane < d) ? splitmix64_at(seed, uint64_t(beg + c * kWave + lane)) : ~uint64_t(0);
+    for (int c = 0; c < NC; ++c) kreg[c] = (c * kWave + lane < count) ? key_at(c * kWave + lane) : ~uint64_t(0);
     T = 0;
     remaining = fanout;
     for (int bit = 63; bit >= 0; --bit) {
@@ -100,9 +99,48 @@ __device__ __forceinline__ void threshold_in_registers(uint64_t seed, int32_t be
     }
 }
 
+// The same for any count: up to 16 registers per lane hold the keys, beyond that key_at is asked again for every bit.
+template <class KeyAt>
+__device__ __forceinline__ void threshold_of(int32_t count, int lane, int32_t fanout, KeyAt key_at, uint64_t &T,
+                                             int32_t &remaining)
+{
+    if (count <= kWave) return threshold_in_registers<1>(count, lane, fanout, key_at, T, remaining);
+    if (count <= 2 * kWave) return threshold_in_registers<2>(count, lane, fanout, key_at, T, remaining);
+    if (count <= 4 * kWave) return threshold_in_registers<4>(count, lane, fanout, key_at, T, remaining);
+    if (count <= 8 * kWave) return threshold_in_registers<8>(count, lane, fanout, key_at, T, remaining);
+    if (count <= 16 * kWave) return threshold_in_registers<16>(count, lane, fanout, key_at, T, remaining);
+    T = 0;                 // bits of the threshold decided so far (the undecided low bits are 0)
+    remaining = fanout;    // the threshold is the remaining-th smallest of the keys that match T's decided bits
+    for (int bit = 63; bit >= 0; --bit) {
+        const uint64_t above = bit == 63 ? uint64_t(0) : (~uint64_t(0) << (bit + 1));
+        int32_t zeros = 0;         // matching keys whose bit `bit` is 0
+        for (int32_t base = 0; base < count; base += kWave) {
+            const int32_t k = base + lane;
+            bool hit = false;
+            if (k < count) {
+                const uint64_t key = key_at(k);
+                hit = ((key ^ T) & above) == 0 && ((key >> bit) & 1) == 0;
+            }
+            zeros += int32_t(__popcll(__ballot(hit)));
+        }
+        if (zeros < remaining) {
+            remaining -= zeros;
+            T |= uint64_t(1) << bit;
+        }
+    }
+}
+
 // A wavefront per queued row.  A row longer than the fan-out keeps the `fanout` entries with the smallest
 // (key, entry index), key(e) = SplitMix64(seed, e), in row order: kept are the keys below the fanout-th smallest
 // key T and, of the keys equal to T, the first ones in row order that are still needed.
+//
+// T of a long row is looked for among few keys: the keys are uniform on the 64-bit range, so the fanout-th
+// smallest of d lies near fanout / d of the range, and one pass over the row first collects the keys below a
+// bound U = (2 fanout + 32) / d of the range (about 2 fanout + 32 of them, in the wavefront's LDS segment).  If at
+// least `fanout` and no more than the segment holds were collected, every key up to T is among them and the T and
+// `remaining` of the collected keys are those of the row; otherwise (a chance far below one in a million for
+// fan-outs up to a few hundred, and always when the fan-out is a large share of the row) all keys of the row are
+// ranked as for a short row.  Either way the result is exact.
 __global__ __launch_bounds__(256) void sample_fill_long_kernel(const int32_t *__restrict__ dst,
                                                                const int32_t *__restrict__ rowptr,
                                                                const int32_t *__restrict__ colidx, int32_t fanout,
@@ -113,6 +151,7 @@ __global__ __launch_bounds__(256) void sample_fill_long_kernel(const int32_t *__
 {
     __shared__ uint64_t keys[256 / kWave][kKeyLds];
     const int lane = threadIdx.x % kWave, wave = threadIdx.x / kWave;
+    const uint64_t lower_lanes = (uint64_t(1) << lane) - 1;
     const int count = *n_queued;
     const int waves = gridDim.x * (256 / kWave);
     for (int q = blockIdx.x * (256 / kWave) + wave; q < count; q += waves) {
@@ -127,39 +166,51 @@ __global__ __launch_bounds__(256) void sample_fill_long_kernel(const int32_t *__
             }
             continue;
         }
-        // short rows keep their keys in registers; longer ones in LDS; beyond that they are recomputed
-        const bool in_regs = d <= 16 * kWave;
-        const bool in_lds = !in_regs && d <= kKeyLds;
-        if (in_lds)
-            for (int32_t k = lane; k < d; k += kWave) keys[wave][k] = splitmix64_at(seed, uint64_t(beg + k));
-        // a wavefront's LDS accesses complete in program order: its own writes above are visible to the reads below
-        __builtin_amdgcn_wave_barrier();
-        auto key_of = [&](int32_t k) { return in_lds ? keys[wave][k] : splitmix64_at(seed, uint64_t(beg + k)); };
+        auto fresh_key = [&](int32_t k) { return splitmix64_at(seed, uint64_t(beg + k)); };
+        auto held_key = [&](int32_t k) { return keys[wave][k]; };
+        // a wavefront's LDS accesses complete in program order: its own writes are visible to its later reads; the
+        // wave barriers only keep the compiler from moving the accesses across them
 
-        uint64_t T = 0;                // bits of the threshold decided so far (the undecided low bits are 0)
-        int32_t remaining = fanout;    // the threshold is the remaining-th smallest of the keys that match T's decided bits
-        if (d <= kWave) threshold_in_registers<1>(seed, beg, d, lane, fanout, T, remaining);
-        else if (d <= 2 * kWave) threshold_in_registers<2>(seed, beg, d, lane, fanout, T, remaining);
-        else if (d <= 4 * kWave) threshold_in_registers<4>(seed, beg, d, lane, fanout, T, remaining);
-        else if (d <= 8 * kWave) threshold_in_registers<8>(seed, beg, d, lane, fanout, T, remaining);
-        else if (in_regs) threshold_in_registers<16>(seed, beg, d, lane, fanout, T, remaining);
-        else {
-            for (int bit = 63; bit >= 0; --bit) {
-                const uint64_t above = bit == 63 ? uint64_t(0) : (~uint64_t(0) << (bit + 1));
-                int32_t zeros = 0;         // matching keys whose bit `bit` is 0
-                for (int32_t base = 0; base < d; base += kWave) {
-                    const int32_t k = base + lane;
-                    bool hit = false;
-                    if (k < d) {
-                        const uint64_t key = key_of(k);
-                        hit = ((key ^ T) & above) == 0 && ((key >> bit) & 1) == 0;
-                    }
-                    zeros += int32_t(__popcll(__ballot(hit)));
+        uint64_t T = 0;
+        int32_t remaining = fanout;
+        bool found = false;
+        const int64_t want = 2 * int64_t(fanout) + 32;
+        if (d > 2 * kWave && want < d) {
+            const uint64_t U = (~uint64_t(0) / uint64_t(d)) * uint64_t(want);
+            int32_t held = 0;
+            for (int32_t base = 0; base < d; base += kWave) {
+                const int32_t k = base + lane;
+                uint64_t key = 0;
+                bool low = false;
+                if (k < d) {
+                    key = fresh_key(k);
+                    low = key < U;
                 }
-                if (zeros < remaining) {
-                    remaining -= zeros;
-                    T |= uint64_t(1) << bit;
+                const uint64_t lows = __ballot(low);
+                if (low) {
+                    const int32_t p = held + int32_t(__popcll(lows & lower_lanes));
+                    if (p < kKeyLds) keys[wave][p] = key;
                 }
+                held += int32_t(__popcll(lows));
+            }
+            __builtin_amdgcn_wave_barrier();
+            if (held >= fanout && held <= kKeyLds) {
+                threshold_of(held, lane, fanout, held_key, T, remaining);
+                found = true;
+            }
+            __builtin_amdgcn_wave_barrier();   // before the segment is written again
+        }
+        bool row_in_lds = false;
+        if (!found) {
+            // rows up to 16 keys per lane are ranked from registers, longer ones from LDS; beyond that the keys are
+            // recomputed for every bit
+            if (d > 16 * kWave && d <= kKeyLds) {
+                for (int32_t k = lane; k < d; k += kWave) keys[wave][k] = fresh_key(k);
+                __builtin_amdgcn_wave_barrier();
+                row_in_lds = true;
+                threshold_of(d, lane, fanout, held_key, T, remaining);
+            } else {
+                threshold_of(d, lane, fanout, fresh_key, T, remaining);
             }
         }
         // keys below T: fanout - remaining of them; of the keys equal to T the first `remaining` in row order
@@ -168,11 +219,10 @@ __global__ __launch_bounds__(256) void sample_fill_long_kernel(const int32_t *__
             const int32_t k = base + lane;
             bool below = false, equal = false;
             if (k < d) {
-                const uint64_t key = key_of(k);
+                const uint64_t key = row_in_lds ? held_key(k) : fresh_key(k);
                 below = key < T;
                 equal = key == T;
             }
-            const uint64_t lower_lanes = (uint64_t(1) << lane) - 1;
             const uint64_t equals = __ballot(equal);
             const bool keep = below || (equal && equal_before + int32_t(__popcll(equals & lower_lanes)) < remaining);
             const uint64_t kept = __ballot(keep);

@@ -78,10 +78,12 @@ def test_neighbor_sample_rows_beyond_the_lds_segment(B):
     rp, ci = synth.csr_from_pairs(m + 1, np.zeros(m, dtype=np.int64), np.arange(1, m + 1))
     rp, ci = rp.astype(np.int32), ci.astype(np.int32)
     dst = np.array([7, 0, 4000], dtype=np.int32)
-    for fanout in (10, 4999, 5000):
-        brp, bcol, _ = B.tma_neighbor_sample(dev(dst), 3, int(rp[-1]), dev(rp), dev(ci), fanout, seed=5)
-        wrp, wcol = oracle.neighbor_sample(dst, rp, ci, fanout, 5)
-        assert np.array_equal(brp.cpu().numpy(), wrp) and np.array_equal(bcol.cpu().numpy()[:wrp[-1]], wcol)
+    # fan-outs for which the kernel's first cut of the keys (about 2 * fanout + 32 of them) holds the wanted ones,
+    # lands near the 2048 keys the LDS segment holds (either side of it over the seeds), or is not tried at all
+    for fanout, seed in [(10, 5), (300, 6)] + [(f, s) for f in (1000, 1008, 1016) for s in (7, 8, 9)] + [(4999, 5), (5000, 5)]:
+        brp, bcol, _ = B.tma_neighbor_sample(dev(dst), 3, int(rp[-1]), dev(rp), dev(ci), fanout, seed=seed)
+        wrp, wcol = oracle.neighbor_sample(dst, rp, ci, fanout, seed)
+        assert np.array_equal(brp.cpu().numpy(), wrp) and np.array_equal(bcol.cpu().numpy()[:wrp[-1]], wcol), (fanout, seed)
 
 
 @pytest.mark.parametrize("n_dst,n_items", [(300, 5000), (0, 9000), (1, 1), (2000, 0), (50, 40_000)])
