@@ -131,16 +131,16 @@ int launch_reduce_splits(const float *partial, const float *colsum_partial, int 
 #define TMA_GEMM_WIDE_BF16 1
 #endif
 constexpr bool kWideBf16 = TMA_GEMM_WIDE_BF16 != 0;
+#ifndef TMA_GEMM_WIDE_BWD_DATA
+#define TMA_GEMM_WIDE_BWD_DATA 1
+#endif
+constexpr bool kWideBwdData = TMA_GEMM_WIDE_BWD_DATA != 0;
 
 // ---- forward ----------------------------------------------------------------
-template <typename T, bool VA, bool VB>
-static void fwd_dispatch(int64_t n, const T *H, int64_t ldh, const T *M, int64_t ldm, int F_in, const float *W_self,
-                         const float *W_neigh, const FwdEpilogue<T> &e, int F_out, hipStream_t s)
+template <typename T, bool VA, class AL, class BL>
+static void fwd_launch(const AL &a, const BL &b, const FwdEpilogue<T> &e, int64_t n, int F_out, int64_t K, int64_t kps,
+                       hipStream_t s)
 {
-    CatRows<T, VA> a{H, ldh, M, ldm, F_in, n, 2 * F_in};
-    CatWeights<VB> b{W_self, W_neigh, F_in, F_out};
-    const int64_t K = 2 * int64_t(F_in);
-    const int64_t kps = int64_t(round_up(size_t(K), 32));
     if (F_out <= 64 || few_tiles(n, F_out))
         launch_gemm<128, 64, 32, 4, 1, false, T>(kname<T>("gemm_fwd_128x64", "gemm_fwd_128x64_generic", "gemm_fwd_128x64_bf16", "gemm_fwd_128x64_bf16_generic", VA),
                                               a, b, e, n, F_out, K, kps, 1, nullptr, s);
@@ -153,6 +153,17 @@ static void fwd_dispatch(int64_t n, const T *H, int64_t ldh, const T *M, int64_t
     } else
         launch_gemm<128, 128, (sizeof(T) == 2 ? 32 : 16), 2, 2, false, T>(kname<T>("gemm_fwd_128x128", "gemm_fwd_128x128_generic", "gemm_fwd_128x128_bf16", "gemm_fwd_128x128_bf16_generic", VA),
                                                a, b, e, n, F_out, K, kps, 1, nullptr, s);
+}
+
+template <typename T, bool VA, bool VB>
+static void fwd_dispatch(int64_t n, const T *H, int64_t ldh, const T *M, int64_t ldm, int F_in, const float *W_self,
+                         const float *W_neigh, const FwdEpilogue<T> &e, int F_out, hipStream_t s)
+{
+    CatRows<T, VA> a{H, ldh, M, ldm, F_in, n, 2 * F_in};
+    const int64_t K = 2 * int64_t(F_in);
+    const int64_t kps = int64_t(round_up(size_t(K), 32));
+    CatWeights<VB> b{W_self, W_neigh, F_in, F_out};
+    fwd_launch<T, VA>(a, b, e, n, F_out, K, kps, s);
 }
 
 template <typename T>
@@ -199,6 +210,10 @@ static void bwd_data_dispatch(int64_t n, const T *g, const T *h, int64_t ld_next
         const char *narrow = kname<T>("gemm_bwd_data_128x64", "gemm_bwd_data_128x64_generic", "gemm_bwd_data_128x64_bf16",
                                       "gemm_bwd_data_128x64_bf16_generic", VA);
         launch_gemm<128, 64, 32, 4, 1, false, T>(narrow, a, b, e, n, N, K, int64_t(round_up(size_t(K), 32)), 1, nullptr, s);
+    } else if (kWideBwdData && sizeof(T) == 2 && VA && N >= 256 && K > 48) {
+        if constexpr (kWideBwdData && sizeof(T) == 2 && VA)   // bf16 storage: half as many passes over the gradient rows
+            launch_gemm<128, 256, 32, 2, 4, false, T>("gemm_bwd_data_128x256_bf16", a, b, e, n, N, K,
+                                                      int64_t(round_up(size_t(K), 32)), 1, nullptr, s);
     } else if (K <= 48) {  // short reduction: 16-wide slabs waste less of the last one
         const int64_t kps = int64_t(round_up(size_t(K), 16));
         launch_gemm<128, 128, 16, 2, 2, false, T>(name, a, b, e, n, N, K, kps, 1, nullptr, s);

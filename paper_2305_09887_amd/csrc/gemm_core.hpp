@@ -51,6 +51,14 @@ __device__ __forceinline__ void static_for(F &&f)
     }
 }
 
+// An optional member of an operand view: kPacksBf16 + packed(raw) say that the view's Raw already holds four bf16
+// values the way a bf16 tile keeps them in LDS (bits unchanged), so a bf16 product stores them as they are instead
+// of widening and rounding them again (the same bits either way).
+template <class View, class = void>
+struct PacksBf16 : std::false_type {};
+template <class View>
+struct PacksBf16<View, std::void_t<decltype(View::kPacksBf16)>> : std::integral_constant<bool, View::kPacksBf16> {};
+
 // ---------------------------------------------------------------------------
 // Storage types.  T = float (fp32 storage) or uint16_t (bf16 storage).  The
 // views hand every operand over as fp32 quads (bf16 widened exactly); TileMath
@@ -157,6 +165,12 @@ struct CatRows {  // A[m][k] = k < F ? H[m][k] : M[m][k-F]  for k < Kv, zero bey
     int64_t rows;
     int Kv;  // extent of k: 2F for the concatenation, F when only the first part is used (Mx is then never read)
     static __device__ __forceinline__ float4 resolve(const Raw &r) { return r.get(); }
+    static constexpr bool kPacksBf16 = V && sizeof(T) == 2;
+    static __device__ __forceinline__ uint2 packed(const Raw &r)
+    {
+        if constexpr (kPacksBf16) return make_uint2(r.ok ? r.v.x : 0u, r.ok ? r.v.y : 0u);
+        else return make_uint2(0u, 0u);
+    }
     __device__ __forceinline__ Lane prepare(int64_t m) const
     {
         const int64_t mm = m < rows ? m : 0;
@@ -882,6 +896,7 @@ struct TileMath<uint16_t> {
     {
         *reinterpret_cast<uint2 *>(dst) = make_uint2(pack_bf16(v.x, v.y), pack_bf16(v.z, v.w));
     }
+    static __device__ __forceinline__ void put_bits(uint16_t *dst, const uint2 &w) { *reinterpret_cast<uint2 *>(dst) = w; }
     static __device__ __forceinline__ Frag along(const uint16_t *p)
     {
         const uint2 w = *reinterpret_cast<const uint2 *>(p);
@@ -1023,9 +1038,15 @@ __global__ __launch_bounds__(WM *WN * 64, (BK * sizeof(CT) <= 64 && !Epi::kRowAu
     };
     auto stage = [&](int buf, const typename AL::Raw(&ar)[A_V], const typename BL::Raw(&br)[B_V]) {
 #pragma unroll
-        for (int i = 0; i < A_V; ++i) Math::put(&As[buf][a_lds[i]], AL::resolve(ar[i]));
+        for (int i = 0; i < A_V; ++i) {
+            if constexpr (sizeof(CT) == 2 && PacksBf16<AL>::value) Math::put_bits(&As[buf][a_lds[i]], AL::packed(ar[i]));
+            else Math::put(&As[buf][a_lds[i]], AL::resolve(ar[i]));
+        }
 #pragma unroll
-        for (int i = 0; i < B_V; ++i) Math::put(&Bs[buf][b_lds[i]], BL::resolve(br[i]));
+        for (int i = 0; i < B_V; ++i) {
+            if constexpr (sizeof(CT) == 2 && PacksBf16<BL>::value) Math::put_bits(&Bs[buf][b_lds[i]], BL::packed(br[i]));
+            else Math::put(&Bs[buf][b_lds[i]], BL::resolve(br[i]));
+        }
     };
     // The four k-values (4*hi + 0..3 of group g) of this lane's row/column, for the 4 MFMAs of the group.
     auto frag_a = [&](int buf, int g, int i) -> Frag {
