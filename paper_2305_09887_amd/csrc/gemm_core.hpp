@@ -4,17 +4,17 @@
 // One kernel template serves every product: operands are described by small "view" structs that present
 // concatenations ([H | M], [W_self ; W_neigh]), the ReLU mask and transposes as plain A[m][k], B[k][n], and by
 // an epilogue struct.  Arithmetic: fp32 storage multiplies with v_mfma_f32_32x32x2_f32 (fp32 in, fp32
-// accumulate), bf16 storage with v_mfma_f32_32x32x8_bf16 (see TileMath).
+// accumulate), bf16 storage with v_mfma_f32_32x32x16_bf16 (see TileMath).
 //
 // Tiling.  128 x BN block tile, 4 wavefronts, each owning a (BM/WM) x (BN/WN) patch of 32x32 MFMA tiles; k is
 // consumed in slabs of BK through two LDS buffers (one barrier per slab) while the next slab's global loads are
 // in flight in registers.  Every operand keeps in LDS the orientation it has in HBM, so all global->LDS
 // traffic is 16-byte loads and 16-byte LDS writes:
-//   k-contiguous operand : LDS [mn][BK+4]; a lane fetches 4 k-values of its row with one ds_read_b128 and
-//                          feeds 4 MFMAs (or one bf16 MFMA) from it;
-//   mn-contiguous operand: LDS [BK][MN+4]; a lane reads one word per k-value.
-// Within a group of 8 k-values the lanes of the upper half take k = 4 .. 7, those of the lower half 0 .. 3,
-// from both operands (any bijection of k is allowed as long as A and B agree).  Blocks are persistent and
+//   k-contiguous operand : LDS [mn][BK+4]; a lane fetches the k-values of its row with one 16-byte read (4 fp32
+//                          values for 4 MFMAs, 8 bf16 values for one);
+//   mn-contiguous operand: LDS [BK][MN+4]; a lane reads one element per k-value.
+// Within a group of k-values (8 for fp32, 16 for bf16) the lanes of the upper half take the upper half of the
+// group, from both operands (any bijection of k is allowed as long as A and B agree).  Blocks are persistent and
 // numbered so that the tiles sharing operand rows land on the same die (XCD) and hit its L2.
 #pragma once
 #include "kernels.hpp"
@@ -849,14 +849,14 @@ struct SplitEpilogue {  // partial products, one slab per split
 // Arithmetic of the tile product.  CT = float: operands sit in LDS as fp32 and a
 // group of 8 k-values is four v_mfma_f32_32x32x2_f32.  CT = uint16_t: operands sit
 // in LDS as bf16 (activations stored in bf16 pass through unchanged, fp32 weights
-// are rounded to nearest even on their way in) and the same group is ONE
-// v_mfma_f32_32x32x8_bf16_1k, whose operand layout -- lane l holds row l%32 and the
-// four k-values 4*(l/32) .. +3 -- is exactly the fragment the fp32 path reads, so
+// are rounded to nearest even on their way in) and a group of 16 k-values is ONE
+// v_mfma_f32_32x32x16_bf16, whose operand layout -- lane l holds row l%32 and the
+// eight k-values 8*(l/32) .. +7 -- is the fp32 fragment's with twice the k-values, so
 // tile layouts, loaders and epilogues are shared.  Accumulation is fp32 in both.
 // ---------------------------------------------------------------------------
-typedef short shortx4 __attribute__((ext_vector_type(4)));
 typedef float floatx2 __attribute__((ext_vector_type(2)));
 typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 
 // two fp32 values to a pair of bf16, round to nearest even (one v_cvt_pk_bf16_f32)
 __device__ __forceinline__ uint32_t pack_bf16(float lo, float hi)
@@ -872,6 +872,7 @@ struct TileMath;
 
 template <>
 struct TileMath<float> {
+    static constexpr int kGroupK = 8;   // k-values per fragment: four MFMAs of two
     typedef float4 Frag;
     static __device__ __forceinline__ void put(float *dst, const float4 &v) { *reinterpret_cast<float4 *>(dst) = v; }
     static __device__ __forceinline__ Frag along(const float *p) { return *reinterpret_cast<const float4 *>(p); }
@@ -891,29 +892,33 @@ struct TileMath<float> {
 
 template <>
 struct TileMath<uint16_t> {
-    typedef shortx4 Frag;
+    // one v_mfma_f32_32x32x16_bf16 per group of 16 k-values: lane l holds row l%32 and the eight k-values
+    // 8*(l/32) .. +7 (the instruction this chip adds; the 32x32x8 one runs at half its rate)
+    static constexpr int kGroupK = 16;
+    typedef bf16x8 Frag;
     static __device__ __forceinline__ void put(uint16_t *dst, const float4 &v)
     {
         *reinterpret_cast<uint2 *>(dst) = make_uint2(pack_bf16(v.x, v.y), pack_bf16(v.z, v.w));
     }
     static __device__ __forceinline__ void put_bits(uint16_t *dst, const uint2 &w) { *reinterpret_cast<uint2 *>(dst) = w; }
-    static __device__ __forceinline__ Frag along(const uint16_t *p)
+    static __device__ __forceinline__ Frag along(const uint16_t *p)   // (tile rows are 8-byte aligned, not 16)
     {
-        const uint2 w = *reinterpret_cast<const uint2 *>(p);
-        Frag f;
-        f[0] = short(w.x & 0xFFFFu); f[1] = short(w.x >> 16); f[2] = short(w.y & 0xFFFFu); f[3] = short(w.y >> 16);
-        return f;
+        const uint2 lo = *reinterpret_cast<const uint2 *>(p), hi = *reinterpret_cast<const uint2 *>(p + 4);
+        return __builtin_bit_cast(Frag, make_uint4(lo.x, lo.y, hi.x, hi.y));
     }
     static __device__ __forceinline__ Frag strided(const uint16_t *p, int ld)
     {
-        Frag f;
-        f[0] = short(p[0]); f[1] = short(p[ld]); f[2] = short(p[2 * ld]); f[3] = short(p[3 * ld]);
-        return f;
+        uint4 w;
+        w.x = uint32_t(p[0]) | (uint32_t(p[ld]) << 16);
+        w.y = uint32_t(p[2 * ld]) | (uint32_t(p[3 * ld]) << 16);
+        w.z = uint32_t(p[4 * ld]) | (uint32_t(p[5 * ld]) << 16);
+        w.w = uint32_t(p[6 * ld]) | (uint32_t(p[7 * ld]) << 16);
+        return __builtin_bit_cast(Frag, w);
     }
     static __device__ __forceinline__ float value(const uint16_t *p) { return bf16_to_f32(*p); }
     static __device__ __forceinline__ void mma(const Frag &a, const Frag &b, floatx16 &acc)
     {
-        acc = __builtin_amdgcn_mfma_f32_32x32x8bf16_1k(a, b, acc, 0, 0, 0);
+        acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, acc, 0, 0, 0);
     }
 };
 
@@ -948,12 +953,13 @@ __global__ __launch_bounds__(WM *WN * 64, (BK * sizeof(CT) <= 64 && !Epi::kRowAu
     constexpr int B_V = (B_Q + NT - 1) / NT;              // evenly the last slots repeat the last piece (same value)
     using Math = TileMath<CT>;
     typedef typename Math::Frag Frag;
-    constexpr int KG = BK / 8;  // groups of 8 k-values = 4 fp32 MFMAs or one bf16 MFMA
+    constexpr int GK = Math::kGroupK;   // k-values per fragment: 8 = 4 fp32 MFMAs, 16 = one bf16 MFMA
+    constexpr int KG = BK / GK;
     constexpr int A_LD = AL::kContigK ? BK + kPad : BM + kPad;
     constexpr int B_LD = BL::kContigK ? BK + kPad : BN + kPad;
     constexpr int A_WORDS = AL::kContigK ? BM * A_LD : BK * A_LD;
     constexpr int B_WORDS = BL::kContigK ? BN * B_LD : BK * B_LD;
-    static_assert(BM % (WM * 32) == 0 && BN % (WN * 32) == 0 && BK % 8 == 0, "tile shape");
+    static_assert(BM % (WM * 32) == 0 && BN % (WN * 32) == 0 && BK % GK == 0, "tile shape");
     static_assert(!kColSum || !BL::kContigK, "column sums are taken from a [k][n] tile");
     static_assert(A_WORDS * sizeof(CT) >= BN * sizeof(float) && B_WORDS * sizeof(CT) >= BM * sizeof(float),
                   "epilogue staging fits");
@@ -1048,16 +1054,17 @@ __global__ __launch_bounds__(WM *WN * 64, (BK * sizeof(CT) <= 64 && !Epi::kRowAu
             else Math::put(&Bs[buf][b_lds[i]], BL::resolve(br[i]));
         }
     };
-    // The four k-values (4*hi + 0..3 of group g) of this lane's row/column, for the 4 MFMAs of the group.
+    // This lane's k-values of group g (the upper half of the wavefront holds the upper half of the group) of its
+    // row/column.
     auto frag_a = [&](int buf, int g, int i) -> Frag {
         const int mn = wm0 + i * 32 + l31;
-        const int k = g * 8 + 4 * hi;
+        const int k = g * GK + (GK / 2) * hi;
         if (AL::kContigK) return Math::along(&As[buf][mn * A_LD + k]);
         return Math::strided(&As[buf][k * A_LD + mn], A_LD);
     };
     auto frag_b = [&](int buf, int g, int j) -> Frag {
         const int mn = wn0 + j * 32 + l31;
-        const int k = g * 8 + 4 * hi;
+        const int k = g * GK + (GK / 2) * hi;
         if (BL::kContigK) return Math::along(&Bs[buf][mn * B_LD + k]);
         return Math::strided(&Bs[buf][k * B_LD + mn], B_LD);
     };
