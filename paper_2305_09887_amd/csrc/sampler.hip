@@ -23,11 +23,13 @@ __device__ __forceinline__ int32_t item_count(const int32_t *d_items, int64_t ma
 }
 
 // ---- neighbour sampling -----------------------------------------------------------------------
+// (also clears the counter of the queue that the fill kernels build)
 __global__ __launch_bounds__(256) void sample_count_kernel(int64_t n_dst, const int32_t *__restrict__ dst,
                                                            const int32_t *__restrict__ rowptr, int32_t fanout,
-                                                           int32_t *__restrict__ deg)
+                                                           int32_t *__restrict__ deg, int32_t *__restrict__ n_queued)
 {
     const int64_t i = int64_t(blockIdx.x) * 256 + threadIdx.x;
+    if (i == 0) *n_queued = 0;
     if (i >= n_dst) return;
     const int32_t w = dst[i];
     const int32_t d = rowptr[w + 1] - rowptr[w];
@@ -247,6 +249,16 @@ __global__ __launch_bounds__(256) void fill_i32_kernel(int64_t count, int32_t *_
     for (int64_t i = int64_t(blockIdx.x) * 256 + threadIdx.x; i < count; i += stride) p[i] = value;
 }
 
+__global__ __launch_bounds__(256) void fill2_i32_kernel(int64_t count, int32_t *__restrict__ p, int32_t value,
+                                                        int32_t *__restrict__ q, int32_t q_value)
+{
+    const int64_t stride = int64_t(gridDim.x) * 256;
+    for (int64_t i = int64_t(blockIdx.x) * 256 + threadIdx.x; i < count; i += stride) {
+        p[i] = value;
+        q[i] = q_value;
+    }
+}
+
 __global__ __launch_bounds__(256) void mark_dst_kernel(int64_t n_dst, const int32_t *__restrict__ dst,
                                                        int32_t *__restrict__ pos, int32_t *__restrict__ src)
 {
@@ -432,8 +444,8 @@ extern "C" int tma_neighbor_sample(int64_t n_dst, const int32_t *dst, int64_t nn
         TMA_REQUIRE(dst && rowptr && (nnz == 0 || (colidx && blk_col_out && blk_row_out)), TMA_ERR_INVALID_ARG,
                     "%s: NULL argument", fn);
         TMA_TIMED("sample_count", s);
-        hipLaunchKernelGGL(sample_count_kernel, dim3(blocks_for(n_dst)), dim3(256), 0, s, n_dst, dst, rowptr, fanout, deg);
-        hipLaunchKernelGGL(fill_i32_kernel, dim3(1), dim3(256), 0, s, int64_t(1), n_queued, 0);
+        hipLaunchKernelGGL(sample_count_kernel, dim3(blocks_for(n_dst)), dim3(256), 0, s, n_dst, dst, rowptr, fanout, deg,
+                           n_queued);
     }
     if (int rc = check_launch(fn)) return rc;
     if (int rc = launch_exclusive_scan_i32(n_dst, deg, blk_rowptr_out, scan_ws, s)) return rc;
@@ -483,8 +495,7 @@ extern "C" int tma_mfg_relabel(int64_t n, int64_t n_dst, const int32_t *dst, int
     void *scan_ws = base + 2 * round_up(rows * 4, 256) + round_up((rows + 1) * 4, 256);
     {
         TMA_TIMED("mfg_mark", s);
-        hipLaunchKernelGGL(fill_i32_kernel, dim3(capped_blocks(n)), dim3(256), 0, s, n, pos, -1);
-        hipLaunchKernelGGL(fill_i32_kernel, dim3(capped_blocks(n)), dim3(256), 0, s, n, isnew, 0);
+        hipLaunchKernelGGL(fill2_i32_kernel, dim3(capped_blocks(n)), dim3(256), 0, s, n, pos, -1, isnew, 0);
         if (n_dst > 0)
             hipLaunchKernelGGL(mark_dst_kernel, dim3(blocks_for(n_dst)), dim3(256), 0, s, n_dst, dst, pos, src_out);
         if (max_items > 0)
