@@ -209,6 +209,12 @@ def main():
                          "measurements")
     ap.add_argument("--batch", type=int, default=None,
                     help="positive edges per step of the link tasks (default 65536; 1024 for link-sampled)")
+    ap.add_argument("--level-sizes", choices=("device", "host"), default="device",
+                    help="link-sampled: leave the level sizes of a batch on the device while it is sampled and wait "
+                         "for them once (default), or fetch each level's size as soon as it exists (one wait per level)")
+    ap.add_argument("--inline-sampling", action="store_true",
+                    help="link-sampled with --prefetch: the next batch's extraction and sampling calls are made by the "
+                         "thread that trains instead of a worker thread")
     ap.add_argument("--fanouts", default="10,25",
                     help="link-sampled: neighbours kept per node, first layer first (the layer next to the batch last)")
     ap.add_argument("--extract", choices=("async", "sync", "fused"), default="async",
@@ -364,7 +370,7 @@ def main():
             sys.exit("bench.py: link-sampled runs the SAGE or GCN encoder with ReLU and needs one fan-out per layer")
         tr = SampledLinkTrainer(sub["rowptr"], sub["colidx"], nnz_loc, Xl, dims, dec_dims, fanouts, args.batch,
                                 batch_seed=sd["part"] + 1, params=params, nnz_cap=nnz_loc + nnz_loc // 4 + 4096,
-                                encoder=args.encoder)
+                                encoder=args.encoder, device_counts=args.level_sizes == "device")
     else:
         tr = LocalTrainer(sub["rowptr"], sub["colidx"], sub["inv_deg"], Xl, yl, dims, params=params,
                           norm_act=args.norm_act, encoder=args.encoder, **link)
@@ -399,7 +405,7 @@ def main():
         stream (the batch depends on the subgraph, the feature rows and the seeds only), driven by the trainer's
         worker thread while this thread enqueues the training pass."""
         if tr._side is not prefetch.stream:
-            tr.enable_prefetch(stream=prefetch.stream, auto=False, background=True)
+            tr.enable_prefetch(stream=prefetch.stream, auto=False, background=not args.inline_sampling)
 
         def prepare():
             s, rows, ready = prefetch.start(sd["part"], after=after)
@@ -449,22 +455,28 @@ def main():
                 state["next"] = prefetch.start(sd["part"], after=state["trained"])
             state["trained"] = trained
 
+    def settle():
+        """Everything enqueued has run, including what a sampler's worker thread is still enqueueing."""
+        if sampled:
+            tr._drain()
+        torch.cuda.synchronize()
+
     for _ in range(args.warmup):
         step()
-    torch.cuda.synchronize()
+    settle()
 
     # which kernel dominates: every kernel timed with events over three untimed steps
     B.tma_profile_begin(None)
     for _ in range(3):
         step()
-    torch.cuda.synchronize()
+    settle()
     prof = B.tma_profile_end()
     per_step = {k: v[1] / 3.0 for k, v in prof.items()}
     dominant = max(per_step, key=per_step.get)
 
     B.tma_profile_begin(None)       # the launch order of one step (matched against a profiler's dispatch list)
     step()
-    torch.cuda.synchronize()
+    settle()
     B.tma_profile_end()
     kernel_sequence = B.tma_profile_sequence()
 
@@ -474,7 +486,7 @@ def main():
     t_start = time.perf_counter()
     for _ in range(args.steps):
         step()
-    torch.cuda.synchronize()
+    settle()
     elapsed = time.perf_counter() - t_start
     dom = B.tma_profile_end().get(dominant, (0, 0.0))
     ms_per_step = elapsed * 1e3 / args.steps
@@ -533,11 +545,11 @@ def main():
                 state["next"], state["trained"] = None, None
             for _ in range(max(args.warmup, 2)):
                 step(two_stream)
-            torch.cuda.synchronize()
+            settle()
             t_start = time.perf_counter()
             for _ in range(args.steps):
                 step(two_stream)
-            torch.cuda.synchronize()
+            settle()
             two_stream_tries.append(round((time.perf_counter() - t_start) * 1e3 / args.steps, 4))
             if two_stream_tries[-1] < ms_per_step:
                 break

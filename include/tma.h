@@ -459,6 +459,20 @@ int tma_bce_logits(int64_t count, int64_t n_pos, const void *z, int64_t ldz, int
  * n_dst = 0 this is "sorted unique ids + positions" (the nodes of a batch).
  * Workspace: tma_mfg_relabel_workspace_bytes(n), 256-byte aligned.
  *
+ * tma_neighbor_sample_dev / tma_mfg_relabel_dev: the same two steps for a caller
+ * that lets the level sizes stay on the device while it samples (no wait for
+ * the stream between the levels of a batch; the sizes are read back once, after
+ * the last level).  cap_dst is the capacity the launches are sized for and
+ * *d_n_dst (device, <= cap_dst) the number of dst nodes.  The sampler gives the
+ * rows from *d_n_dst up to cap_dst no entries: blk_rowptr_out has cap_dst + 1
+ * elements, its elements [*d_n_dst .. cap_dst] all hold the number of kept
+ * entries (so &blk_rowptr_out[cap_dst] serves as d_items of the relabelling),
+ * workspace and cap_entries are those of cap_dst rows.  The relabelling writes
+ * the length of src_out to *d_n_src_out (device) and returns without waiting;
+ * cap_src >= min(n, cap_dst + max_items); with cap_dst = 0, d_n_dst may be NULL.
+ * The first *d_n_dst rows / *d_n_src_out nodes and all entries are, bit for
+ * bit, what the host-count forms produce.
+ *
  * tma_block_inv_deg: inv_deg_out[i] = 1 / (entries of block row i), 0 for an
  * empty row.
  *
@@ -484,6 +498,15 @@ size_t tma_mfg_relabel_workspace_bytes(int64_t n);
 int tma_mfg_relabel(int64_t n, int64_t n_dst, const int32_t *dst, int64_t max_items,
                     const int32_t *d_items, int32_t *cols_inout, int32_t *src_out, int64_t cap_src,
                     int64_t *h_n_src, void *ws, size_t ws_bytes, tma_stream_t stream);
+
+int tma_neighbor_sample_dev(int64_t cap_dst, const int32_t *d_n_dst, const int32_t *dst, int64_t nnz,
+                            const int32_t *rowptr, const int32_t *colidx, int32_t fanout, uint64_t seed,
+                            int32_t *blk_rowptr_out, int32_t *blk_col_out, int32_t *blk_row_out,
+                            int64_t cap_entries, void *ws, size_t ws_bytes, tma_stream_t stream);
+
+int tma_mfg_relabel_dev(int64_t n, int64_t cap_dst, const int32_t *d_n_dst, const int32_t *dst,
+                        int64_t max_items, const int32_t *d_items, int32_t *cols_inout, int32_t *src_out,
+                        int64_t cap_src, int32_t *d_n_src_out, void *ws, size_t ws_bytes, tma_stream_t stream);
 
 int tma_block_inv_deg(int64_t n_dst, const int32_t *blk_rowptr, float *inv_deg_out, tma_stream_t stream);
 
@@ -605,6 +628,12 @@ int tma_average(float *const *W_ptrs, int32_t n_trainers, uint64_t active_mask,
  * ---------------------------------------------------------------------- */
 int tma_gather_rows(int64_t n_loc, const int32_t *l2g, const void *src, int64_t src_ld_bytes,
                     int64_t row_bytes, void *dst, int64_t dst_ld_bytes, tma_stream_t stream);
+
+/* The same with the row count on the device: rows [0, min(*d_n_rows, cap_rows)) are copied, the launch is sized for
+ * cap_rows and nothing else is written (for the input rows of a sampled batch whose size has not come back yet). */
+int tma_gather_rows_dev(int64_t cap_rows, const int32_t *d_n_rows, const int32_t *l2g, const void *src,
+                        int64_t src_ld_bytes, int64_t row_bytes, void *dst, int64_t dst_ld_bytes,
+                        tma_stream_t stream);
 
 /* ------------------------------------------------------------------------
  * Measurement aid (not part of the method): per-kernel durations from HIP

@@ -33,6 +33,7 @@ EXPORTS = (
     "tma_prelu_fwd", "tma_prelu_bwd_workspace_bytes", "tma_prelu_bwd", "tma_bce_logits_workspace_bytes",
     "tma_bce_logits",
     "tma_neighbor_sample_workspace_bytes", "tma_neighbor_sample", "tma_mfg_relabel_workspace_bytes", "tma_mfg_relabel",
+    "tma_neighbor_sample_dev", "tma_mfg_relabel_dev", "tma_gather_rows_dev",
     "tma_block_inv_deg", "tma_sage_block_fwd", "tma_sage_block_bwd_workspace_bytes", "tma_sage_block_bwd",
     "tma_gcn_block_norm", "tma_gcn_block_fwd", "tma_gcn_block_bwd_workspace_bytes", "tma_gcn_block_bwd",
     "tma_loss_workspace_bytes", "tma_softmax_ce", "tma_sigmoid_l2", "tma_sgd_step", "tma_adam_step", "tma_average",
@@ -672,6 +673,51 @@ def tma_mfg_relabel(n: int, dst, n_dst: int, cols, max_items: int, d_items=None,
     return src_out, int(n_src.value)
 
 
+def tma_neighbor_sample_dev(dst, cap_dst: int, d_n_dst, nnz: int, rowptr, colidx, fanout: int, seed: int,
+                            blk_rowptr_out=None, blk_col_out=None, blk_row_out=None, ws=None, stream=None):
+    """tma_neighbor_sample with the number of dst nodes in d_n_dst (1-element int32 device tensor or view); launches
+    and buffers are those of cap_dst rows.  blk_rowptr[*d_n_dst .. cap_dst] all hold the number of kept entries."""
+    dev = rowptr.device
+    cap = max(min(cap_dst * fanout, nnz), 1)
+    if blk_rowptr_out is None:
+        blk_rowptr_out = torch.empty(cap_dst + 1, dtype=torch.int32, device=dev)
+    if blk_col_out is None:
+        blk_col_out = torch.empty(cap, dtype=torch.int32, device=dev)
+    if blk_row_out is None:
+        blk_row_out = torch.empty(cap, dtype=torch.int32, device=dev)
+    if blk_rowptr_out.numel() < cap_dst + 1 or dst.numel() < cap_dst or colidx.numel() < nnz or d_n_dst.numel() < 1:
+        raise TmaError("tma_neighbor_sample_dev: dst / blk_rowptr_out / colidx / d_n_dst too short")
+    if ws is None:
+        ws = _workspace(tma_neighbor_sample_workspace_bytes(cap_dst), dev, stream)
+    _check(lib().tma_neighbor_sample_dev(
+        C.c_int64(cap_dst), _ptr(d_n_dst, torch.int32, "d_n_dst"), _ptr(dst, torch.int32, "dst"), C.c_int64(nnz),
+        _ptr(rowptr, torch.int32, "rowptr"), _ptr(colidx, torch.int32, "colidx"), C.c_int32(fanout), C.c_uint64(seed),
+        _ptr(blk_rowptr_out, torch.int32), _ptr(blk_col_out, torch.int32), _ptr(blk_row_out, torch.int32),
+        C.c_int64(min(blk_col_out.numel(), blk_row_out.numel())), _ptr(ws), C.c_size_t(ws.numel()), _stream(stream)))
+    return blk_rowptr_out, blk_col_out, blk_row_out
+
+
+def tma_mfg_relabel_dev(n: int, dst, cap_dst: int, d_n_dst, cols, max_items: int, d_items=None, src_out=None,
+                        n_src_out=None, ws=None, stream=None):
+    """tma_mfg_relabel without the wait: the number of dst nodes is read from d_n_dst (None with cap_dst = 0) and the
+    length of the node list is written to n_src_out (1-element int32 device tensors or views).  Returns
+    (src, n_src_out)."""
+    dev = cols.device
+    if src_out is None:
+        src_out = torch.empty(max(min(n, cap_dst + max_items), 1), dtype=torch.int32, device=dev)
+    if n_src_out is None:
+        n_src_out = torch.empty(1, dtype=torch.int32, device=dev)
+    if ws is None:
+        ws = _workspace(tma_mfg_relabel_workspace_bytes(n), dev, stream)
+    _check(lib().tma_mfg_relabel_dev(
+        C.c_int64(n), C.c_int64(cap_dst), _ptr(d_n_dst, torch.int32, "d_n_dst") if cap_dst > 0 else C.c_void_p(0),
+        _ptr(dst, torch.int32, "dst") if cap_dst > 0 else C.c_void_p(0), C.c_int64(max_items),
+        C.c_void_p(d_items.data_ptr() if d_items is not None else 0), _ptr(cols, torch.int32, "cols"),
+        _ptr(src_out, torch.int32, "src_out"), C.c_int64(src_out.numel()), _ptr(n_src_out, torch.int32, "n_src_out"),
+        _ptr(ws), C.c_size_t(ws.numel()), _stream(stream)))
+    return src_out, n_src_out
+
+
 def tma_block_inv_deg(blk_rowptr, n_dst: int, out=None, stream=None):
     if out is None:
         out = torch.empty(max(n_dst, 1), dtype=torch.float32, device=blk_rowptr.device)
@@ -993,6 +1039,21 @@ def tma_gather_rows(l2g, src, out=None, stream=None):
     _check(lib().tma_gather_rows(C.c_int64(n_loc), _ptr(l2g, torch.int32, "l2g"), C.c_void_p(src.data_ptr()),
                                  C.c_int64(src_ld), C.c_int64(row_bytes), C.c_void_p(out.data_ptr()),
                                  C.c_int64(dst_ld), _stream(stream)))
+    return out
+
+
+def tma_gather_rows_dev(l2g, d_n_rows, src, out, stream=None):
+    """out[i] = src[l2g[i]] for i < min(*d_n_rows, rows of out): the row count is read on the device (1-element
+    int32 tensor or view); the launch is sized for all rows of ``out`` (a 2-D row-major buffer)."""
+    cap = out.shape[0]
+    _, cols, ld = _rows_ld(src, "src")
+    row_bytes, src_ld = cols * src.element_size(), ld * src.element_size()
+    if out.dim() != 2 or out.shape[1] != cols or out.dtype != src.dtype or out.stride(1) != 1 or l2g.numel() < cap:
+        raise TmaError("tma_gather_rows_dev: out must be a row-major [cap, cols] buffer of the table's dtype, l2g as long")
+    _check(lib().tma_gather_rows_dev(C.c_int64(cap), _ptr(d_n_rows, torch.int32, "d_n_rows"), _ptr(l2g, torch.int32, "l2g"),
+                                     C.c_void_p(src.data_ptr()), C.c_int64(src_ld), C.c_int64(row_bytes),
+                                     C.c_void_p(out.data_ptr()), C.c_int64(out.stride(0) * out.element_size()),
+                                     _stream(stream)))
     return out
 
 

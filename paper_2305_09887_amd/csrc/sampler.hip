@@ -23,14 +23,21 @@ __device__ __forceinline__ int32_t item_count(const int32_t *d_items, int64_t ma
 }
 
 // ---- neighbour sampling -----------------------------------------------------------------------
+// d_n_dst (may be NULL): the number of dst rows when it is only known on the device; n_dst is then the capacity the
+// launch is sized for, and the rows from the count up to the capacity are given no entries.
 // (also clears the counter of the queue that the fill kernels build)
-__global__ __launch_bounds__(256) void sample_count_kernel(int64_t n_dst, const int32_t *__restrict__ dst,
+__global__ __launch_bounds__(256) void sample_count_kernel(int64_t n_dst, const int32_t *__restrict__ d_n_dst,
+                                                           const int32_t *__restrict__ dst,
                                                            const int32_t *__restrict__ rowptr, int32_t fanout,
                                                            int32_t *__restrict__ deg, int32_t *__restrict__ n_queued)
 {
     const int64_t i = int64_t(blockIdx.x) * 256 + threadIdx.x;
     if (i == 0) *n_queued = 0;
     if (i >= n_dst) return;
+    if (i >= item_count(d_n_dst, n_dst)) {
+        deg[i] = 0;
+        return;
+    }
     const int32_t w = dst[i];
     const int32_t d = rowptr[w + 1] - rowptr[w];
     deg[i] = d < fanout ? d : fanout;
@@ -38,7 +45,8 @@ __global__ __launch_bounds__(256) void sample_count_kernel(int64_t n_dst, const 
 
 // Rows that are kept whole and short are copied by their thread; the others are queued for a wavefront each
 // (one queue reservation per wavefront).
-__global__ __launch_bounds__(256) void sample_fill_short_kernel(int64_t n_dst, const int32_t *__restrict__ dst,
+__global__ __launch_bounds__(256) void sample_fill_short_kernel(int64_t n_dst, const int32_t *__restrict__ d_n_dst,
+                                                                const int32_t *__restrict__ dst,
                                                                 const int32_t *__restrict__ rowptr,
                                                                 const int32_t *__restrict__ colidx, int32_t fanout,
                                                                 const int32_t *__restrict__ blk_rowptr,
@@ -49,7 +57,7 @@ __global__ __launch_bounds__(256) void sample_fill_short_kernel(int64_t n_dst, c
     const int64_t i = int64_t(blockIdx.x) * 256 + threadIdx.x;
     const int lane = threadIdx.x % kWave;
     int32_t beg = 0, d = 0;
-    if (i < n_dst) {
+    if (i < item_count(d_n_dst, n_dst)) {
         const int32_t w = dst[i];
         beg = rowptr[w];
         d = rowptr[w + 1] - beg;
@@ -259,11 +267,12 @@ __global__ __launch_bounds__(256) void fill2_i32_kernel(int64_t count, int32_t *
     }
 }
 
-__global__ __launch_bounds__(256) void mark_dst_kernel(int64_t n_dst, const int32_t *__restrict__ dst,
-                                                       int32_t *__restrict__ pos, int32_t *__restrict__ src)
+__global__ __launch_bounds__(256) void mark_dst_kernel(int64_t n_dst, const int32_t *__restrict__ d_n_dst,
+                                                       const int32_t *__restrict__ dst, int32_t *__restrict__ pos,
+                                                       int32_t *__restrict__ src)
 {
     const int64_t i = int64_t(blockIdx.x) * 256 + threadIdx.x;
-    if (i >= n_dst) return;
+    if (i >= item_count(d_n_dst, n_dst)) return;
     pos[dst[i]] = int32_t(i);
     src[i] = dst[i];
 }
@@ -278,13 +287,17 @@ __global__ __launch_bounds__(256) void flag_new_kernel(int64_t max_items, const 
     if (pos[c] < 0) isnew[c] = 1;     // several writers, one value
 }
 
-__global__ __launch_bounds__(256) void assign_new_kernel(int64_t n, int64_t n_dst, const int32_t *__restrict__ isnew,
+// (rank[n] is the number of new nodes; n_src_out, if given, receives the length of the node list)
+__global__ __launch_bounds__(256) void assign_new_kernel(int64_t n, int64_t n_dst_cap, const int32_t *__restrict__ d_n_dst,
+                                                         const int32_t *__restrict__ isnew,
                                                          const int32_t *__restrict__ rank, int32_t *__restrict__ pos,
-                                                         int32_t *__restrict__ src)
+                                                         int32_t *__restrict__ src, int32_t *__restrict__ n_src_out)
 {
     const int64_t c = int64_t(blockIdx.x) * 256 + threadIdx.x;
+    const int32_t n_dst = item_count(d_n_dst, n_dst_cap);
+    if (c == 0 && n_src_out) *n_src_out = n_dst + rank[n];
     if (c >= n || !isnew[c]) return;
-    const int32_t p = int32_t(n_dst) + rank[c];
+    const int32_t p = n_dst + rank[c];
     pos[c] = p;
     src[p] = int32_t(c);
 }
@@ -421,13 +434,14 @@ extern "C" size_t tma_neighbor_sample_workspace_bytes(int64_t n_dst)
     return tma::round_up((2 * rows + 1) * 4, 256) + tma::exclusive_scan_i32_workspace_bytes(n_dst);
 }
 
-extern "C" int tma_neighbor_sample(int64_t n_dst, const int32_t *dst, int64_t nnz, const int32_t *rowptr,
-                                   const int32_t *colidx, int32_t fanout, uint64_t seed, int32_t *blk_rowptr_out,
-                                   int32_t *blk_col_out, int32_t *blk_row_out, int64_t cap_entries, void *ws,
-                                   size_t ws_bytes, tma_stream_t stream)
+namespace tma {
+
+// d_n_dst == NULL: n_dst rows.  Otherwise n_dst is a capacity and the row count is read on the device.
+static int neighbor_sample(const char *fn, int64_t n_dst, const int32_t *d_n_dst, const int32_t *dst, int64_t nnz,
+                           const int32_t *rowptr, const int32_t *colidx, int32_t fanout, uint64_t seed,
+                           int32_t *blk_rowptr_out, int32_t *blk_col_out, int32_t *blk_row_out, int64_t cap_entries,
+                           void *ws, size_t ws_bytes, tma_stream_t stream)
 {
-    using namespace tma;
-    const char *fn = "tma_neighbor_sample";
     TMA_REQUIRE(n_dst >= 0 && n_dst <= INT32_MAX && nnz >= 0 && nnz <= INT32_MAX && fanout >= 1, TMA_ERR_INVALID_ARG,
                 "%s: n_dst, nnz or fanout", fn);
     TMA_REQUIRE(blk_rowptr_out && ws && aligned(ws, 256) && ws_bytes >= tma_neighbor_sample_workspace_bytes(n_dst),
@@ -444,8 +458,8 @@ extern "C" int tma_neighbor_sample(int64_t n_dst, const int32_t *dst, int64_t nn
         TMA_REQUIRE(dst && rowptr && (nnz == 0 || (colidx && blk_col_out && blk_row_out)), TMA_ERR_INVALID_ARG,
                     "%s: NULL argument", fn);
         TMA_TIMED("sample_count", s);
-        hipLaunchKernelGGL(sample_count_kernel, dim3(blocks_for(n_dst)), dim3(256), 0, s, n_dst, dst, rowptr, fanout, deg,
-                           n_queued);
+        hipLaunchKernelGGL(sample_count_kernel, dim3(blocks_for(n_dst)), dim3(256), 0, s, n_dst, d_n_dst, dst, rowptr, fanout,
+                           deg, n_queued);
     }
     if (int rc = check_launch(fn)) return rc;
     if (int rc = launch_exclusive_scan_i32(n_dst, deg, blk_rowptr_out, scan_ws, s)) return rc;
@@ -453,13 +467,35 @@ extern "C" int tma_neighbor_sample(int64_t n_dst, const int32_t *dst, int64_t nn
     int32_t *queue = deg + rows;
     {
         TMA_TIMED("sample_fill_short", s);
-        hipLaunchKernelGGL(sample_fill_short_kernel, dim3(blocks_for(n_dst)), dim3(256), 0, s, n_dst, dst, rowptr, colidx,
-                           fanout, blk_rowptr_out, blk_col_out, blk_row_out, cap_entries, queue, n_queued);
+        hipLaunchKernelGGL(sample_fill_short_kernel, dim3(blocks_for(n_dst)), dim3(256), 0, s, n_dst, d_n_dst, dst, rowptr,
+                           colidx, fanout, blk_rowptr_out, blk_col_out, blk_row_out, cap_entries, queue, n_queued);
     }
     TMA_TIMED("sample_fill_long", s);
     hipLaunchKernelGGL(sample_fill_long_kernel, dim3(1024), dim3(256), 0, s, dst, rowptr, colidx, fanout, seed,
                        blk_rowptr_out, blk_col_out, blk_row_out, cap_entries, queue, n_queued);
     return check_launch(fn);
+}
+
+}  // namespace tma
+
+extern "C" int tma_neighbor_sample(int64_t n_dst, const int32_t *dst, int64_t nnz, const int32_t *rowptr,
+                                   const int32_t *colidx, int32_t fanout, uint64_t seed, int32_t *blk_rowptr_out,
+                                   int32_t *blk_col_out, int32_t *blk_row_out, int64_t cap_entries, void *ws,
+                                   size_t ws_bytes, tma_stream_t stream)
+{
+    return tma::neighbor_sample("tma_neighbor_sample", n_dst, nullptr, dst, nnz, rowptr, colidx, fanout, seed,
+                                blk_rowptr_out, blk_col_out, blk_row_out, cap_entries, ws, ws_bytes, stream);
+}
+
+extern "C" int tma_neighbor_sample_dev(int64_t cap_dst, const int32_t *d_n_dst, const int32_t *dst, int64_t nnz,
+                                       const int32_t *rowptr, const int32_t *colidx, int32_t fanout, uint64_t seed,
+                                       int32_t *blk_rowptr_out, int32_t *blk_col_out, int32_t *blk_row_out,
+                                       int64_t cap_entries, void *ws, size_t ws_bytes, tma_stream_t stream)
+{
+    const char *fn = "tma_neighbor_sample_dev";
+    TMA_REQUIRE(d_n_dst, TMA_ERR_INVALID_ARG, "%s: d_n_dst is NULL", fn);
+    return tma::neighbor_sample(fn, cap_dst, d_n_dst, dst, nnz, rowptr, colidx, fanout, seed, blk_rowptr_out,
+                                blk_col_out, blk_row_out, cap_entries, ws, ws_bytes, stream);
 }
 
 extern "C" size_t tma_mfg_relabel_workspace_bytes(int64_t n)
@@ -469,24 +505,33 @@ extern "C" size_t tma_mfg_relabel_workspace_bytes(int64_t n)
     return 2 * tma::round_up(rows * 4, 256) + tma::round_up((rows + 1) * 4, 256) + tma::exclusive_scan_i32_workspace_bytes(n);
 }
 
-extern "C" int tma_mfg_relabel(int64_t n, int64_t n_dst, const int32_t *dst, int64_t max_items, const int32_t *d_items,
-                               int32_t *cols_inout, int32_t *src_out, int64_t cap_src, int64_t *h_n_src, void *ws,
-                               size_t ws_bytes, tma_stream_t stream)
+namespace tma {
+
+// d_n_dst == NULL: n_dst dst nodes.  Otherwise n_dst is a capacity and the count is read on the device.
+// h_n_src != NULL: the length of the node list is copied to the host (one wait); d_n_src_out != NULL: it is left
+// on the device.
+static int mfg_relabel(const char *fn, int64_t n, int64_t n_dst, const int32_t *d_n_dst, const int32_t *dst,
+                       int64_t max_items, const int32_t *d_items, int32_t *cols_inout, int32_t *src_out, int64_t cap_src,
+                       int64_t *h_n_src, int32_t *d_n_src_out, void *ws, size_t ws_bytes, tma_stream_t stream)
 {
-    using namespace tma;
-    const char *fn = "tma_mfg_relabel";
     TMA_REQUIRE(n >= 0 && n <= INT32_MAX && n_dst >= 0 && n_dst <= n && max_items >= 0 && max_items <= INT32_MAX,
                 TMA_ERR_INVALID_ARG, "%s: n, n_dst or max_items", fn);
-    TMA_REQUIRE(h_n_src && ws && aligned(ws, 256) && ws_bytes >= tma_mfg_relabel_workspace_bytes(n), TMA_ERR_INVALID_ARG,
-                "%s: h_n_src / workspace", fn);
+    TMA_REQUIRE((h_n_src || d_n_src_out) && ws && aligned(ws, 256) && ws_bytes >= tma_mfg_relabel_workspace_bytes(n),
+                TMA_ERR_INVALID_ARG, "%s: no place for the node count / workspace", fn);
     const int64_t bound = n_dst + max_items < n ? n_dst + max_items : n;
     TMA_REQUIRE(cap_src >= bound, TMA_ERR_WORKSPACE_TOO_SMALL, "%s: room for %lld source nodes, up to %lld possible", fn,
                 (long long)cap_src, (long long)bound);
-    *h_n_src = n_dst;
-    if (n == 0) return TMA_OK;
+    if (h_n_src) *h_n_src = n_dst;
+    hipStream_t s = as_stream(stream);
+    if (n == 0) {
+        if (d_n_src_out) {   // (a fill kernel, not a memset: callers may capture this into a graph)
+            hipLaunchKernelGGL(fill_i32_kernel, dim3(1), dim3(256), 0, s, int64_t(1), d_n_src_out, 0);
+            return check_launch(fn);
+        }
+        return TMA_OK;
+    }
     TMA_REQUIRE((n_dst == 0 || dst) && (max_items == 0 || cols_inout) && (bound == 0 || src_out), TMA_ERR_INVALID_ARG,
                 "%s: NULL argument", fn);
-    hipStream_t s = as_stream(stream);
     const size_t rows = size_t(n);
     char *base = static_cast<char *>(ws);
     int32_t *pos = reinterpret_cast<int32_t *>(base);
@@ -497,7 +542,7 @@ extern "C" int tma_mfg_relabel(int64_t n, int64_t n_dst, const int32_t *dst, int
         TMA_TIMED("mfg_mark", s);
         hipLaunchKernelGGL(fill2_i32_kernel, dim3(capped_blocks(n)), dim3(256), 0, s, n, pos, -1, isnew, 0);
         if (n_dst > 0)
-            hipLaunchKernelGGL(mark_dst_kernel, dim3(blocks_for(n_dst)), dim3(256), 0, s, n_dst, dst, pos, src_out);
+            hipLaunchKernelGGL(mark_dst_kernel, dim3(blocks_for(n_dst)), dim3(256), 0, s, n_dst, d_n_dst, dst, pos, src_out);
         if (max_items > 0)
             hipLaunchKernelGGL(flag_new_kernel, dim3(blocks_for(max_items)), dim3(256), 0, s, max_items, d_items,
                                cols_inout, pos, isnew);
@@ -506,17 +551,42 @@ extern "C" int tma_mfg_relabel(int64_t n, int64_t n_dst, const int32_t *dst, int
     if (int rc = launch_exclusive_scan_i32(n, isnew, rank, scan_ws, s)) return rc;
     {
         TMA_TIMED("mfg_relabel", s);
-        hipLaunchKernelGGL(assign_new_kernel, dim3(blocks_for(n)), dim3(256), 0, s, n, n_dst, isnew, rank, pos, src_out);
+        hipLaunchKernelGGL(assign_new_kernel, dim3(blocks_for(n)), dim3(256), 0, s, n, n_dst, d_n_dst, isnew, rank, pos,
+                           src_out, d_n_src_out);
         if (max_items > 0)
             hipLaunchKernelGGL(relabel_kernel, dim3(blocks_for(max_items)), dim3(256), 0, s, max_items, d_items, cols_inout,
                                pos);
     }
     if (int rc = check_launch(fn)) return rc;
-    int32_t n_new = 0;
-    // copy in stream order and wait for it: the caller sizes the next launches with the count
-    TMA_HIP_TRY(hipMemcpyWithStream(&n_new, rank + n, sizeof(n_new), hipMemcpyDeviceToHost, s), fn);
-    *h_n_src = n_dst + n_new;
+    if (h_n_src) {
+        int32_t n_new = 0;
+        // copy in stream order and wait for it: the caller sizes the next launches with the count
+        TMA_HIP_TRY(hipMemcpyWithStream(&n_new, rank + n, sizeof(n_new), hipMemcpyDeviceToHost, s), fn);
+        *h_n_src = n_dst + n_new;
+    }
     return TMA_OK;
+}
+
+}  // namespace tma
+
+extern "C" int tma_mfg_relabel(int64_t n, int64_t n_dst, const int32_t *dst, int64_t max_items, const int32_t *d_items,
+                               int32_t *cols_inout, int32_t *src_out, int64_t cap_src, int64_t *h_n_src, void *ws,
+                               size_t ws_bytes, tma_stream_t stream)
+{
+    const char *fn = "tma_mfg_relabel";
+    TMA_REQUIRE(h_n_src, TMA_ERR_INVALID_ARG, "%s: h_n_src is NULL", fn);
+    return tma::mfg_relabel(fn, n, n_dst, nullptr, dst, max_items, d_items, cols_inout, src_out, cap_src, h_n_src, nullptr,
+                            ws, ws_bytes, stream);
+}
+
+extern "C" int tma_mfg_relabel_dev(int64_t n, int64_t cap_dst, const int32_t *d_n_dst, const int32_t *dst,
+                                   int64_t max_items, const int32_t *d_items, int32_t *cols_inout, int32_t *src_out,
+                                   int64_t cap_src, int32_t *d_n_src_out, void *ws, size_t ws_bytes, tma_stream_t stream)
+{
+    const char *fn = "tma_mfg_relabel_dev";
+    TMA_REQUIRE(d_n_src_out && (cap_dst == 0 || d_n_dst), TMA_ERR_INVALID_ARG, "%s: d_n_src_out / d_n_dst is NULL", fn);
+    return tma::mfg_relabel(fn, n, cap_dst, cap_dst > 0 ? d_n_dst : nullptr, dst, max_items, d_items, cols_inout, src_out,
+                            cap_src, nullptr, d_n_src_out, ws, ws_bytes, stream);
 }
 
 extern "C" int tma_block_inv_deg(int64_t n_dst, const int32_t *blk_rowptr, float *inv_deg_out, tma_stream_t stream)

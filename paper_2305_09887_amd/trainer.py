@@ -329,8 +329,19 @@ class _Mfg:
         ws_bytes = max(max(B.tma_neighbor_sample_workspace_bytes(cap[l + 1]) for l in range(L)),
                        B.tma_mfg_relabel_workspace_bytes(n))
         self.ws = torch.empty(max(ws_bytes, 256), dtype=torch.uint8, device=dev)
+        # level sizes as the sampler leaves them on the device, and where they are copied for the host
+        self.d_count = i32(L + 1)
+        self.h_count = torch.empty(L + 1, dtype=torch.int32, pin_memory=True)
+        self.counted = None          # recorded after that copy; None once the sizes are in `count`
         self.step = -1
         self.ready = self.released = None
+
+    def resolve(self):
+        """Wait (the only wait of a batch) until the level sizes have arrived on the host."""
+        if self.counted is not None:
+            self.counted.synchronize()
+            self.count[:] = self.h_count.tolist()
+            self.counted = None
 
 
 class SampledLinkTrainer(LocalTrainer):
@@ -342,8 +353,10 @@ class SampledLinkTrainer(LocalTrainer):
     level; run the mean-aggregation SAGE layers on the bipartite blocks, the decoder and the loss; go back the same
     way.  Only the sampled neighbourhood is touched.  Hidden layers use ReLU, or with ``norm_act`` layer
     normalisation followed by PReLU.  All buffers are sized once for the largest possible level
-    (3 * batch_size nodes at the top, times 1 + fanout per layer, capped by the local node count); the level sizes
-    of a step come back from the device, one wait per level.  The neighbour sampler's seed for step t and layer l is
+    (3 * batch_size nodes at the top, times 1 + fanout per layer, capped by the local node count).  The level sizes
+    of a batch stay on the device while it is sampled (launches sized for the capacities) and come back with one
+    copy, waited for once before the training pass is enqueued; ``device_counts=False`` fetches each level's size as
+    soon as it exists instead (one wait per level, launches of the exact sizes).  The neighbour sampler's seed for step t and layer l is
     SplitMix64(batch_seed, 64 t + l).  ``encoder``: "sage" (W_self, W_neigh, b per layer) or "gcn" (W, b per layer;
     on a block the layer averages over the sampled neighbours and the node itself).
 
@@ -355,7 +368,9 @@ class SampledLinkTrainer(LocalTrainer):
     """
 
     def __init__(self, rowptr, colidx, nnz, X, dims, decoder_dims, fanouts, batch_size, batch_seed=0, params=None,
-                 decoder_params=None, stream=None, optimizer="sgd", norm_act=False, nnz_cap=None, encoder="sage"):
+                 decoder_params=None, stream=None, optimizer="sgd", norm_act=False, nnz_cap=None, encoder="sage",
+                 device_counts=True):
+        self.device_counts = bool(device_counts)
         if len(fanouts) != len(dims) - 1:
             raise B.TmaError("SampledLinkTrainer: one fan-out per layer")
         if colidx.numel() < nnz or (nnz_cap is not None and nnz_cap < nnz):
@@ -455,6 +470,8 @@ class SampledLinkTrainer(LocalTrainer):
         u, v, vneg = mfg.batch
         B.tma_edge_batch(self.rowptr, self.colidx, self.nnz, self.batch_seed, t * Bn, Bn, u_out=u, v_out=v, vneg_out=vneg,
                          stream=st)
+        if self.device_counts:
+            return self._sample_levels_on_device(mfg, t, st)
         _, mfg.count[L] = B.tma_mfg_relabel(self.n, None, 0, mfg.bcat, 3 * Bn, src_out=mfg.nodes[L], ws=mfg.ws, stream=st)
         for l in range(L - 1, -1, -1):
             n_dst = mfg.count[l + 1]
@@ -469,6 +486,32 @@ class SampledLinkTrainer(LocalTrainer):
             else:
                 B.tma_gcn_block_norm(mfg.blk_rowptr[l], n_dst, out=mfg.blk_inv_deg[l], stream=st)
         B.tma_gather_rows(mfg.nodes[0][:mfg.count[0]], self.X, out=mfg.H0[:mfg.count[0]], stream=st)
+        mfg.step = t
+
+    def _sample_levels_on_device(self, mfg, t, st):
+        """The levels of batch t with their sizes left on the device: nothing here waits for the GPU."""
+        L, Bn, dc = self.L, self.batch_size, mfg.d_count
+        B.tma_mfg_relabel_dev(self.n, None, 0, None, mfg.bcat, 3 * Bn, src_out=mfg.nodes[L], n_src_out=dc[L:L + 1],
+                              ws=mfg.ws, stream=st)
+        for l in range(L - 1, -1, -1):
+            cap_dst, d_n_dst = self.cap[l + 1], dc[l + 1:l + 2]
+            B.tma_neighbor_sample_dev(mfg.nodes[l + 1], cap_dst, d_n_dst, self.nnz, self.rowptr, self.colidx,
+                                      self.fanouts[l], B.tma_mix64(self.batch_seed, 64 * t + l),
+                                      blk_rowptr_out=mfg.blk_rowptr[l], blk_col_out=mfg.blk_col[l],
+                                      blk_row_out=mfg.blk_row[l], ws=mfg.ws, stream=st)
+            # (the rows past the level's size have no entries: the element at the capacity holds the entry count)
+            B.tma_mfg_relabel_dev(self.n, mfg.nodes[l + 1], cap_dst, d_n_dst, mfg.blk_col[l], self.ecap[l],
+                                  d_items=mfg.blk_rowptr[l][cap_dst:cap_dst + 1], src_out=mfg.nodes[l],
+                                  n_src_out=dc[l:l + 1], ws=mfg.ws, stream=st)
+            if self.encoder == "sage":
+                B.tma_block_inv_deg(mfg.blk_rowptr[l], cap_dst, out=mfg.blk_inv_deg[l], stream=st)
+            else:
+                B.tma_gcn_block_norm(mfg.blk_rowptr[l], cap_dst, out=mfg.blk_inv_deg[l], stream=st)
+        B.tma_gather_rows_dev(mfg.nodes[0], dc[0:1], self.X, mfg.H0, stream=st)
+        with torch.cuda.stream(st):
+            mfg.h_count.copy_(dc, non_blocking=True)
+            mfg.counted = torch.cuda.Event()
+            mfg.counted.record(st)
         mfg.step = t
 
     def enable_prefetch(self, stream=None, auto=True, background=False):
@@ -578,12 +621,14 @@ class SampledLinkTrainer(LocalTrainer):
         """One iteration of Alg. 2's loop body on the sampled neighbourhood of one mini-batch."""
         if self._side is None:
             self.sample()
+            self._cur.resolve()
         else:
             self._drain()
             if self._pending is None or self._pending.step != self.steps_done:
                 self.prefetch_sample()             # nothing sampled ahead (first step, or the step count was set)
                 self._drain()
             mfg, self._pending = self._pending, None
+            mfg.resolve()
             self.stream.wait_event(mfg.ready)
             self._bind(mfg)
         R = self.forward()

@@ -80,6 +80,35 @@ def test_extraction_entry_points_reject_bad_arguments_before_touching_a_device(l
     assert lib.tma_gcn_block_bwd_workspace_bytes(i64(10), i64(50), i64(200), 8, 8, 0, 1) % 256 == 0
 
 
+def test_device_count_forms_of_the_sampler_reject_bad_arguments_in_host_code(lib):
+    lib.tma_last_error.restype = ctypes.c_char_p
+    i64, i32, u64, sz = ctypes.c_int64, ctypes.c_int32, ctypes.c_uint64, ctypes.c_size_t
+    fake = ctypes.c_void_p(4096)            # non-NULL, 256-byte aligned, never dereferenced
+
+    def sample(cap_dst, d_n=fake, cap_entries=1000, ws_bytes=1 << 40, fanout=5):
+        return lib.tma_neighbor_sample_dev(i64(cap_dst), d_n, fake, i64(5000), fake, fake, i32(fanout), u64(1), fake, fake,
+                                           fake, i64(cap_entries), fake, sz(ws_bytes), None)
+
+    assert sample(100, d_n=None) < 0 and b"d_n_dst" in lib.tma_last_error()
+    assert sample(100, fanout=0) < 0 and b"fanout" in lib.tma_last_error()
+    assert sample(100, cap_entries=499) < 0 and b"room for 499 entries" in lib.tma_last_error()     # capacity rows count
+    assert sample(100, ws_bytes=64) < 0 and b"workspace" in lib.tma_last_error()
+
+    def relabel(n, cap_dst, max_items, cap_src, d_n=fake, out=fake, ws_bytes=1 << 40):
+        return lib.tma_mfg_relabel_dev(i64(n), i64(cap_dst), d_n, fake, i64(max_items), None, fake, fake, i64(cap_src), out,
+                                       fake, sz(ws_bytes), None)
+
+    assert relabel(1000, 10, 50, 60, out=None) < 0 and b"d_n_src_out" in lib.tma_last_error()
+    assert relabel(1000, 10, 50, 60, d_n=None) < 0 and b"d_n_dst" in lib.tma_last_error()
+    assert relabel(1000, 10, 50, 59) < 0 and b"room for 59 source nodes" in lib.tma_last_error()
+    assert relabel(1000, 1001, 0, 1001) < 0 and b"n_dst" in lib.tma_last_error()
+    assert relabel(1000, 10, 50, 60, ws_bytes=64) < 0 and b"workspace" in lib.tma_last_error()
+    rc = lib.tma_gather_rows_dev(i64(10), None, fake, fake, i64(64), i64(64), fake, i64(64), None)
+    assert rc < 0 and b"d_n_rows" in lib.tma_last_error()
+    rc = lib.tma_gather_rows_dev(i64(10), fake, fake, fake, i64(32), i64(64), fake, i64(64), None)
+    assert rc < 0 and b"pitch" in lib.tma_last_error()
+
+
 def test_host_generator_reproduces_the_published_vector(lib):
     """tma_mix64 is host code: the library's generator against the published SplitMix64 outputs for seed 1234567
     (the same fixture that pins the oracle's), no GPU needed."""

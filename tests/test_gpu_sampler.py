@@ -86,6 +86,53 @@ def test_neighbor_sample_rows_beyond_the_lds_segment(B):
         assert np.array_equal(brp.cpu().numpy(), wrp) and np.array_equal(bcol.cpu().numpy()[:wrp[-1]], wcol), (fanout, seed)
 
 
+@pytest.mark.parametrize("n_dst,cap_dst,fanout", [(700, 2000, 5), (0, 300, 3), (1500, 1500, 10**6), (1, 4000, 1)])
+def test_sampling_a_level_with_its_size_on_the_device(B, n_dst, cap_dst, fanout):
+    """tma_neighbor_sample_dev + tma_mfg_relabel_dev + tma_gather_rows_dev: the launches are sized for cap_dst rows,
+    the row count is read on the device; against the oracle, with the buffers' contents past the counts checked."""
+    rp, ci = local_graph(40_000, 400_000, 9)
+    n = len(rp) - 1
+    rng = np.random.default_rng(n_dst + fanout % 7)
+    perm = rng.permutation(n).astype(np.int32)
+    if n_dst > 10:                                               # the hubs are asked for
+        hubs = np.argsort(-np.diff(rp))[:3].astype(np.int32)
+        perm = np.concatenate([hubs, perm[~np.isin(perm, hubs)]])
+    dst = perm[:cap_dst].copy()                                  # (the entries past n_dst are stale ids)
+    d_n = dev(np.array([n_dst, 77], np.int32))
+    nnz = int(rp[-1])
+    brp, bcol, brow = B.tma_neighbor_sample_dev(dev(dst), cap_dst, d_n[0:1], nnz, dev(rp), dev(ci), fanout, seed=4321)
+    wrp, wcol = oracle.neighbor_sample(dst[:n_dst], rp, ci, fanout, 4321)
+    total = int(wrp[-1])
+    got = brp.cpu().numpy()
+    assert got.shape == (cap_dst + 1,) and np.array_equal(got[:n_dst + 1], wrp) and (got[n_dst:] == total).all()
+    assert np.array_equal(bcol.cpu().numpy()[:total], wcol)
+    assert np.array_equal(brow.cpu().numpy()[:total], np.repeat(np.arange(n_dst, dtype=np.int32), np.diff(wrp)))
+    # node list and positions
+    max_items = bcol.numel()
+    cols = bcol.clone()
+    cols[total:] = -7
+    src = torch.full((min(n, cap_dst + max_items),), -5, dtype=torch.int32, device="cuda")
+    n_src = torch.full((1,), -1, dtype=torch.int32, device="cuda")
+    B.tma_mfg_relabel_dev(n, dev(dst), cap_dst, d_n[0:1], cols, max_items, d_items=brp[cap_dst:cap_dst + 1], src_out=src,
+                          n_src_out=n_src)
+    wsrc, wcols = oracle.mfg_relabel(dst[:n_dst], wcol)
+    assert int(n_src) == len(wsrc)
+    assert np.array_equal(src.cpu().numpy()[:len(wsrc)], wsrc) and (src.cpu().numpy()[len(wsrc):] == -5).all()
+    assert np.array_equal(cols.cpu().numpy()[:total], wcols) and (cols.cpu().numpy()[total:] == -7).all()
+    # the rows of the node list, gathered with the count on the device
+    X = torch.randn(n, 24, device="cuda")
+    out = torch.full((src.numel(), 24), 3.0, device="cuda")
+    B.tma_gather_rows_dev(src, n_src, X, out)
+    assert torch.equal(out[:len(wsrc)], X[torch.as_tensor(wsrc, device="cuda").long()]) and (out[len(wsrc):] == 3.0).all()
+    # a batch's distinct nodes: no dst nodes at all
+    ids = rng.integers(0, n, 500).astype(np.int32)
+    cbuf = dev(ids)
+    usrc, un = B.tma_mfg_relabel_dev(n, None, 0, None, cbuf, 500)
+    wsrc0, wcols0 = oracle.mfg_relabel(np.zeros(0, np.int32), ids)
+    assert int(un) == len(wsrc0) and np.array_equal(usrc.cpu().numpy()[:len(wsrc0)], wsrc0)
+    assert np.array_equal(cbuf.cpu().numpy(), wcols0)
+
+
 @pytest.mark.parametrize("n_dst,n_items", [(300, 5000), (0, 9000), (1, 1), (2000, 0), (50, 40_000)])
 def test_mfg_relabel_bit_exact(B, n_dst, n_items):
     n = 20_000
@@ -325,11 +372,13 @@ def test_sampling_one_step_ahead_on_a_second_stream_changes_nothing(B, encoder):
     rp, ci, Xd = dev(sub["rowptr"]), dev(sub["colidx"]), dev(X[sub["l2g"]])
     X2 = Xd.clone()                                       # a second table with the same values at another address
 
-    def make():
+    def make(**kw):
         return SampledLinkTrainer(rp, ci, int(sub["rowptr"][-1]), Xd, dims, dec_dims, fanouts, Bn, batch_seed=99,
-                                  params=enc, decoder_params=dec, encoder=encoder)
+                                  params=enc, decoder_params=dec, encoder=encoder, **kw)
 
-    plain, ahead, driven = make(), make(), make()
+    # the plain one fetches every level's size as soon as it exists; the others leave the sizes on the device while
+    # they sample (capacity-sized launches) and wait once
+    plain, ahead, driven = make(device_counts=False), make(), make()
     ahead.enable_prefetch(background=True)                # a worker thread makes the sampling calls
     driven.enable_prefetch(auto=False)
     for step in range(5):
