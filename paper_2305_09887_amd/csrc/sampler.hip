@@ -13,7 +13,8 @@
 namespace tma {
 
 constexpr int kThreadCopy = 32;     // rows kept whole and no longer than this are copied by their thread
-constexpr int kKeyLds = 2048;       // keys of a row that fit a wavefront's LDS segment
+constexpr int kKeyLds = 512;        // keys a wavefront keeps in its LDS segment (4 KB: 2048 measured 15 % slower, fewer wavefronts fit)
+constexpr int kLongRowBlocks = 1024;   // workgroups (of four wavefronts) that share the queue of long rows (256: 20 % slower; 4096: no faster)
 
 __device__ __forceinline__ int32_t item_count(const int32_t *d_items, int64_t max_items)
 {
@@ -149,8 +150,9 @@ __device__ __forceinline__ void threshold_of(int32_t count, int lane, int32_t fa
 // bound U = (2 fanout + 32) / d of the range (about 2 fanout + 32 of them, in the wavefront's LDS segment).  If at
 // least `fanout` and no more than the segment holds were collected, every key up to T is among them and the T and
 // `remaining` of the collected keys are those of the row; otherwise (a chance far below one in a million for
-// fan-outs up to a few hundred, and always when the fan-out is a large share of the row) all keys of the row are
-// ranked as for a short row.  Either way the result is exact.
+// fan-outs up to about 150, and always when the fan-out is a large share of the row) all keys of the row are
+// ranked as for a short row, recomputed for every bit once they no longer fit the registers.  Either way the
+// result is exact.
 __global__ __launch_bounds__(256) void sample_fill_long_kernel(const int32_t *__restrict__ dst,
                                                                const int32_t *__restrict__ rowptr,
                                                                const int32_t *__restrict__ colidx, int32_t fanout,
@@ -210,26 +212,14 @@ __global__ __launch_bounds__(256) void sample_fill_long_kernel(const int32_t *__
             }
             __builtin_amdgcn_wave_barrier();   // before the segment is written again
         }
-        bool row_in_lds = false;
-        if (!found) {
-            // rows up to 16 keys per lane are ranked from registers, longer ones from LDS; beyond that the keys are
-            // recomputed for every bit
-            if (d > 16 * kWave && d <= kKeyLds) {
-                for (int32_t k = lane; k < d; k += kWave) keys[wave][k] = fresh_key(k);
-                __builtin_amdgcn_wave_barrier();
-                row_in_lds = true;
-                threshold_of(d, lane, fanout, held_key, T, remaining);
-            } else {
-                threshold_of(d, lane, fanout, fresh_key, T, remaining);
-            }
-        }
+        if (!found) threshold_of(d, lane, fanout, fresh_key, T, remaining);
         // keys below T: fanout - remaining of them; of the keys equal to T the first `remaining` in row order
         int32_t kept_before = 0, equal_before = 0;
         for (int32_t base = 0; base < d; base += kWave) {
             const int32_t k = base + lane;
             bool below = false, equal = false;
             if (k < d) {
-                const uint64_t key = row_in_lds ? held_key(k) : fresh_key(k);
+                const uint64_t key = fresh_key(k);
                 below = key < T;
                 equal = key == T;
             }
@@ -471,7 +461,7 @@ static int neighbor_sample(const char *fn, int64_t n_dst, const int32_t *d_n_dst
                            colidx, fanout, blk_rowptr_out, blk_col_out, blk_row_out, cap_entries, queue, n_queued);
     }
     TMA_TIMED("sample_fill_long", s);
-    hipLaunchKernelGGL(sample_fill_long_kernel, dim3(1024), dim3(256), 0, s, dst, rowptr, colidx, fanout, seed,
+    hipLaunchKernelGGL(sample_fill_long_kernel, dim3(kLongRowBlocks), dim3(256), 0, s, dst, rowptr, colidx, fanout, seed,
                        blk_rowptr_out, blk_col_out, blk_row_out, cap_entries, queue, n_queued);
     return check_launch(fn);
 }

@@ -73,14 +73,16 @@ def test_neighbor_sample_bit_exact(B, kind, fanout, n_dst):
 
 
 def test_neighbor_sample_rows_beyond_the_lds_segment(B):
-    # a star: the centre has 5000 neighbours, more than the keys a wavefront keeps in LDS
+    # a star: the centre has 5000 neighbours, far more than the keys a wavefront keeps in LDS
     m = 5000
     rp, ci = synth.csr_from_pairs(m + 1, np.zeros(m, dtype=np.int64), np.arange(1, m + 1))
     rp, ci = rp.astype(np.int32), ci.astype(np.int32)
     dst = np.array([7, 0, 4000], dtype=np.int32)
     # fan-outs for which the kernel's first cut of the keys (about 2 * fanout + 32 of them) holds the wanted ones,
-    # lands near the 2048 keys the LDS segment holds (either side of it over the seeds), or is not tried at all
-    for fanout, seed in [(10, 5), (300, 6)] + [(f, s) for f in (1000, 1008, 1016) for s in (7, 8, 9)] + [(4999, 5), (5000, 5)]:
+    # lands near the 512 keys the LDS segment holds (either side of it over the seeds), is far above it, or is not
+    # tried at all
+    for fanout, seed in ([(10, 5), (100, 6)] + [(f, s) for f in (232, 240, 248) for s in (7, 8, 9)]
+                         + [(1000, 7), (4999, 5), (5000, 5)]):
         brp, bcol, _ = B.tma_neighbor_sample(dev(dst), 3, int(rp[-1]), dev(rp), dev(ci), fanout, seed=seed)
         wrp, wcol = oracle.neighbor_sample(dst, rp, ci, fanout, seed)
         assert np.array_equal(brp.cpu().numpy(), wrp) and np.array_equal(bcol.cpu().numpy()[:wrp[-1]], wcol), (fanout, seed)
