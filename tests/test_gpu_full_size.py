@@ -151,10 +151,11 @@ def test_configs1_link_prediction_step_against_oracle(configs1_part0):
             _close(g.cpu().numpy().ravel(), np.asarray(w).ravel(), f"decoder layer {l} {name}", extra=bd)
 
 
-def test_configs1_sampled_link_prediction_step_against_oracle(configs1_part0):
+@pytest.mark.parametrize("encoder,device_counts", [("sage", True), ("sage", False), ("gcn", True)])
+def test_configs1_sampled_link_prediction_step_against_oracle(configs1_part0, encoder, device_counts):
     """Link prediction on sampled message-flow graphs at the size and launch configuration of
-    `bench.py --task link-sampled`: 1,024 positives, fan-outs 10 / 25, SAGE 128-256-256, decoder 256-256-1; node lists
-    and blocks bit for bit, logits, loss and every gradient."""
+    `bench.py --task link-sampled [--encoder gcn] [--level-sizes host]`: 1,024 positives, fan-outs 10 / 25, encoder
+    128-256-256, decoder 256-256-1; node lists and blocks bit for bit, logits, loss and every gradient."""
     if not torch.cuda.is_available():
         pytest.skip("no GPU")
     from paper_2305_09887_amd.trainer import SampledLinkTrainer
@@ -162,20 +163,21 @@ def test_configs1_sampled_link_prediction_step_against_oracle(configs1_part0):
     rp, ci = sub_o["rowptr"], sub_o["colidx"]
     nnz = int(rp[-1])
     dims, dec_dims, fanouts, Bn = [128, 256, 256], [256, 256, 1], [10, 25], 1024
-    enc = [tuple(l) for l in synth.sage_params(dims, seed=15)]
+    enc = [tuple(l) if encoder == "sage" else (l[0], l[2]) for l in synth.sage_params(dims, seed=15)]
     rng = np.random.default_rng(16)
     dec = [(synth.glorot(256, 256, rng).astype(np.float32), np.array([0.25], np.float32)),
            (synth.glorot(256, 1, rng).astype(np.float32),)]
     d = lambda a: torch.as_tensor(a).cuda()
     tr = SampledLinkTrainer(d(rp), d(ci), nnz, d(Xo), dims, dec_dims, fanouts, Bn, batch_seed=15, params=enc,
-                            decoder_params=dec, nnz_cap=nnz + nnz // 4 + 4096)
+                            decoder_params=dec, nnz_cap=nnz + nnz // 4 + 4096, encoder=encoder,
+                            device_counts=device_counts)
     loss_g = tr.step(1e-3).item()
     batch = oracle.edge_batch(rp, ci, 15, 0, Bn)
     e_o = [tuple(np.asarray(t, dtype=np.float64) for t in l) for l in enc]
     d_o = [tuple(np.asarray(t, dtype=np.float64) for t in l) for l in dec]
     t = {}
     loss_o, ge, gd, z, (rps, cis, inputs, seeds) = omodel.sampled_link_loss_and_grads(
-        rp, ci, Xo, batch, e_o, d_o, fanouts, 15, 0, trace=t)
+        rp, ci, Xo, batch, e_o, d_o, fanouts, 15, 0, trace=t, encoder=encoder)
     assert tr.count == [len(inputs), len(rps[0]) - 1, len(seeds)]
     assert len(inputs) > 20_000 and np.diff(rps[0]).max() == 10 and np.diff(rps[1]).max() == 25   # the fan-outs bind
     assert np.array_equal(tr.nodes[0].cpu().numpy()[:len(inputs)], inputs)
@@ -187,7 +189,7 @@ def test_configs1_sampled_link_prediction_step_against_oracle(configs1_part0):
     D = decisions.differing(t["pre"], [tr.H[1].cpu().numpy(), None], "encoder")
     Dd = decisions.differing(t["dec_pre"], [tr.E[1].cpu().numpy(), None], "decoder")
     db, q_top = decisions.decoder_bounds(d_o, t["dsaved"], t["dec_ups"], Dd, t["R"], t["batch_pos"])
-    eb = decisions.encoder_bounds("sage", rps, cis, e_o, t["saved"], t["ups"], D, q_top)
+    eb = decisions.encoder_bounds(encoder, rps, cis, e_o, t["saved"], t["ups"], D, q_top)
     assert abs(loss_g - loss_o) <= TOL * abs(loss_o)
     _close(tr.Zd[2].cpu().numpy().ravel(), z, "logits")
     for l in range(2):
