@@ -216,6 +216,27 @@ int tma_sage_layer_fwd(int64_t n, const int32_t *rowptr, const int32_t *colidx,
                        int32_t F_out, int32_t act, int32_t dtype,
                        void *M_out, int64_t ldm, void *Hnext_out, int64_t ld_next, tma_stream_t stream);
 
+/* The same layer (Thm. 1: Abar X W; Sec. 4.1: GraphSAGE) for bf16 storage with the weight operand prepared once
+ * instead of narrowed from fp32 inside every tile of the product.
+ * tma_sage_prepare_weights_bf16 writes Wt_out[o * 2 F_in + k] = bf16(k < F_in ? W_self[k][o] : W_neigh[k - F_in][o])
+ * (round to nearest even, the rounding the product applies itself), tma_sage_weights_bf16_bytes(F_in, F_out) bytes,
+ * 16-byte aligned, caller-owned; call it again whenever the weights have changed.
+ * tma_sage_layer_fwd_prepared takes the arguments of tma_sage_layer_fwd plus that array (dtype must be TMA_BF16)
+ * and returns the same bits; a layer that transforms first, or operands without 8-byte aligned groups of four,
+ * run as in tma_sage_layer_fwd (W_self / W_neigh must therefore be valid too). */
+size_t tma_sage_weights_bf16_bytes(int32_t F_in, int32_t F_out);
+
+int tma_sage_prepare_weights_bf16(const float *W_self, const float *W_neigh, int32_t F_in, int32_t F_out,
+                                  void *Wt_out, tma_stream_t stream);
+
+int tma_sage_layer_fwd_prepared(int64_t n, const int32_t *rowptr, const int32_t *colidx,
+                                const float *inv_deg,
+                                const void *H, int64_t ldh, int32_t F_in,
+                                const float *W_self, const float *W_neigh, const float *bias,
+                                int32_t F_out, int32_t act, int32_t dtype,
+                                void *M_out, int64_t ldm, void *Hnext_out, int64_t ld_next,
+                                const void *Wt_bf16, tma_stream_t stream);
+
 /* ------------------------------------------------------------------------
  * Backward of the layer (chain rule as in the proof of Thm. 1, which writes
  * the one-layer case dL/dw = dL/dz * dz/dg * dg/dw):

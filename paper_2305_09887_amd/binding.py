@@ -34,6 +34,7 @@ EXPORTS = (
     "tma_bce_logits",
     "tma_neighbor_sample_workspace_bytes", "tma_neighbor_sample", "tma_mfg_relabel_workspace_bytes", "tma_mfg_relabel",
     "tma_neighbor_sample_dev", "tma_mfg_relabel_dev", "tma_gather_rows_dev",
+    "tma_sage_weights_bf16_bytes", "tma_sage_prepare_weights_bf16", "tma_sage_layer_fwd_prepared",
     "tma_block_inv_deg", "tma_sage_block_fwd", "tma_sage_block_bwd_workspace_bytes", "tma_sage_block_bwd",
     "tma_gcn_block_norm", "tma_gcn_block_fwd", "tma_gcn_block_bwd_workspace_bytes", "tma_gcn_block_bwd",
     "tma_loss_workspace_bytes", "tma_softmax_ce", "tma_sigmoid_l2", "tma_sgd_step", "tma_adam_step", "tma_average",
@@ -64,7 +65,7 @@ def lib() -> C.CDLL:
                      "tma_pair_product_bwd_workspace_bytes", "tma_prelu_bwd_workspace_bytes",
                      "tma_bce_logits_workspace_bytes", "tma_neighbor_sample_workspace_bytes",
                      "tma_mfg_relabel_workspace_bytes", "tma_sage_block_bwd_workspace_bytes",
-                     "tma_gcn_block_bwd_workspace_bytes"):
+                     "tma_gcn_block_bwd_workspace_bytes", "tma_sage_weights_bf16_bytes"):
             getattr(L, name).restype = C.c_size_t
         L.tma_mix64.restype = C.c_uint64
         L.tma_mix64.argtypes = [C.c_uint64, C.c_uint64]
@@ -269,9 +270,29 @@ def tma_sage_layer_aggregates_first(F_in: int, F_out: int, dtype: int) -> bool:
     return bool(lib().tma_sage_layer_aggregates_first(C.c_int32(F_in), C.c_int32(F_out), C.c_int32(dtype)))
 
 
+def tma_sage_weights_bf16_bytes(F_in: int, F_out: int) -> int:
+    return int(lib().tma_sage_weights_bf16_bytes(C.c_int32(F_in), C.c_int32(F_out)))
+
+
+def tma_sage_prepare_weights_bf16(W_self, W_neigh, out=None, stream=None):
+    """The layer's weights narrowed to bf16 with the output feature as the row ([F_out, 2 F_in], int16 bits), for
+    tma_sage_layer_fwd(..., Wt=...); to be called again whenever the weights have changed."""
+    F_in, F_out = W_self.shape
+    if tuple(W_neigh.shape) != (F_in, F_out):
+        raise TmaError("tma_sage_prepare_weights_bf16: weight shapes differ")
+    if out is None:
+        out = torch.empty(tma_sage_weights_bf16_bytes(F_in, F_out) // 2, dtype=torch.int16, device=W_self.device)
+    if out.numel() * out.element_size() < 2 * F_in * F_out * 2:
+        raise TmaError("tma_sage_prepare_weights_bf16: out too small")
+    _check(lib().tma_sage_prepare_weights_bf16(_ptr(W_self, torch.float32, "W_self"), _ptr(W_neigh, torch.float32, "W_neigh"),
+                                               C.c_int32(F_in), C.c_int32(F_out), _ptr(out), _stream(stream)))
+    return out
+
+
 def tma_sage_layer_fwd(rowptr, colidx, inv_deg, H, W_self, W_neigh, bias, act: int, M_out=None, Hnext_out=None,
-                       stream=None):
-    """Returns (M, Hnext)."""
+                       stream=None, Wt=None):
+    """Returns (M, Hnext).  Wt: the weights as tma_sage_prepare_weights_bf16 leaves them (bf16 storage only; the
+    call then goes through tma_sage_layer_fwd_prepared and returns the same bits)."""
     n, F_in, ldh = _rows_ld(H, "H")
     F_out = W_self.shape[1]
     if tuple(W_self.shape) != (F_in, F_out) or tuple(W_neigh.shape) != (F_in, F_out) or bias.numel() != F_out:
@@ -286,12 +307,17 @@ def tma_sage_layer_fwd(rowptr, colidx, inv_deg, H, W_self, W_neigh, bias, act: i
         raise TmaError("tma_sage_layer_fwd: output shapes")
     _, _, ld_next = _rows_ld(Hnext_out, "Hnext_out")
     _, _, ldm = _rows_ld(M_out, "M_out")
-    _check(lib().tma_sage_layer_fwd(
-        C.c_int64(n), _ptr(rowptr, torch.int32), _ptr(colidx, torch.int32), _ptr(inv_deg, torch.float32),
-        C.c_void_p(H.data_ptr()), C.c_int64(ldh), C.c_int32(F_in), _ptr(W_self, torch.float32, "W_self"),
-        _ptr(W_neigh, torch.float32, "W_neigh"), _ptr(bias, torch.float32, "bias"), C.c_int32(F_out),
-        C.c_int32(act), C.c_int32(_feat_dtype(H)), C.c_void_p(M_out.data_ptr()), C.c_int64(ldm),
-        C.c_void_p(Hnext_out.data_ptr()), C.c_int64(ld_next), _stream(stream)))
+    args = (C.c_int64(n), _ptr(rowptr, torch.int32), _ptr(colidx, torch.int32), _ptr(inv_deg, torch.float32),
+            C.c_void_p(H.data_ptr()), C.c_int64(ldh), C.c_int32(F_in), _ptr(W_self, torch.float32, "W_self"),
+            _ptr(W_neigh, torch.float32, "W_neigh"), _ptr(bias, torch.float32, "bias"), C.c_int32(F_out),
+            C.c_int32(act), C.c_int32(_feat_dtype(H)), C.c_void_p(M_out.data_ptr()), C.c_int64(ldm),
+            C.c_void_p(Hnext_out.data_ptr()), C.c_int64(ld_next))
+    if Wt is not None:
+        if Wt.numel() * Wt.element_size() < 2 * F_in * F_out * 2:
+            raise TmaError("tma_sage_layer_fwd: Wt too small for these widths")
+        _check(lib().tma_sage_layer_fwd_prepared(*args, _ptr(Wt), _stream(stream)))
+    else:
+        _check(lib().tma_sage_layer_fwd(*args, _stream(stream)))
     return M_out, Hnext_out
 
 

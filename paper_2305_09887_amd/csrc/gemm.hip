@@ -166,6 +166,43 @@ static void fwd_dispatch(int64_t n, const T *H, int64_t ldh, const T *M, int64_t
     fwd_launch<T, VA>(a, b, e, n, F_out, K, kps, s);
 }
 
+// bf16 storage with the weights prepared as Wt[o][k] (bf16): both operands are rows of packed bf16, contiguous
+// along k, and go into LDS as loaded -- no conversion, no 2-byte fragment reads of a [k][n] weight tile.
+static void fwd_prepared(int64_t n, const uint16_t *H, int64_t ldh, const uint16_t *M, int64_t ldm, int F_in,
+                         const uint16_t *Wt, const FwdEpilogue<uint16_t> &e, int F_out, hipStream_t s)
+{
+    CatRows<uint16_t, true> a{H, ldh, M, ldm, F_in, n, 2 * F_in};
+    CatRows<uint16_t, true> b{Wt, 2 * int64_t(F_in), Wt, 2 * int64_t(F_in), 2 * F_in, F_out, 2 * F_in};
+    const int64_t K = 2 * int64_t(F_in);
+    fwd_launch<uint16_t, true>(a, b, e, n, F_out, K, int64_t(round_up(size_t(K), 32)), s);
+}
+
+__global__ __launch_bounds__(256) void narrow_transpose_weights_kernel(const float *__restrict__ Ws,
+                                                                       const float *__restrict__ Wn, int F, int N,
+                                                                       uint16_t *__restrict__ Wt)
+{
+    const int64_t idx = int64_t(blockIdx.x) * 256 + threadIdx.x;   // over [2F][N]: coalesced reads
+    if (idx >= 2 * int64_t(F) * N) return;
+    const int k = int(idx / N), o = int(idx - int64_t(k) * N);
+    const float v = k < F ? Ws[int64_t(k) * N + o] : Wn[int64_t(k - F) * N + o];
+    Wt[int64_t(o) * 2 * F + k] = f32_to_bf16(v);
+}
+
+size_t sage_weights_bf16_bytes(int32_t F_in, int32_t F_out)
+{
+    return round_up(2 * size_t(F_in) * size_t(F_out) * sizeof(uint16_t), 256);
+}
+
+int launch_sage_prepare_weights_bf16(const float *W_self, const float *W_neigh, int32_t F_in, int32_t F_out, void *Wt_out,
+                                     hipStream_t stream)
+{
+    const int64_t total = 2 * int64_t(F_in) * F_out;
+    TMA_TIMED("prepare_weights_bf16", stream);
+    hipLaunchKernelGGL(narrow_transpose_weights_kernel, dim3(unsigned(ceil_div(total, 256))), dim3(256), 0, stream, W_self,
+                       W_neigh, F_in, F_out, static_cast<uint16_t *>(Wt_out));
+    return check_launch("prepare weights");
+}
+
 template <typename T>
 static int fwd_typed(int64_t n, const T *H, int64_t ldh, const T *M, int64_t ldm, int32_t F_in, const float *W_self,
                      const float *W_neigh, const float *bias, int32_t F_out, int32_t act, T *Hnext, int64_t ld_next,
@@ -183,9 +220,18 @@ static int fwd_typed(int64_t n, const T *H, int64_t ldh, const T *M, int64_t ldm
 
 int launch_sage_gemm_fwd(int64_t n, const void *H, int64_t ldh, const void *M, int64_t ldm, int32_t F_in, const float *W_self,
                          const float *W_neigh, const float *bias, int32_t F_out, int32_t act, int32_t dtype,
-                         void *Hnext, int64_t ld_next, hipStream_t stream)
+                         void *Hnext, int64_t ld_next, hipStream_t stream, const void *Wt_bf16)
 {
     if (n == 0 || F_out == 0) return TMA_OK;
+    if (Wt_bf16 && dtype == TMA_BF16) {
+        const uint16_t *h = static_cast<const uint16_t *>(H), *m = static_cast<const uint16_t *>(M);
+        // the packed path needs groups of four bf16 at 8-byte aligned addresses in both operands
+        if (vec4_ok(h, ldh) && vec4_ok(m, ldm) && F_in % 4 == 0 && aligned(Wt_bf16, 8)) {
+            FwdEpilogue<uint16_t> e{static_cast<uint16_t *>(Hnext), ld_next, bias, act == TMA_ACT_RELU};
+            fwd_prepared(n, h, ldh, m, ldm, F_in, static_cast<const uint16_t *>(Wt_bf16), e, F_out, stream);
+            return check_launch("sage gemm fwd");
+        }
+    }
     if (dtype == TMA_F32)
         return fwd_typed<float>(n, static_cast<const float *>(H), ldh, static_cast<const float *>(M), ldm, F_in, W_self,
                                 W_neigh, bias, F_out, act, static_cast<float *>(Hnext), ld_next, stream);

@@ -28,7 +28,11 @@ int launch_scale_mask_rows(int64_t n, int32_t F, int32_t F_pad, const void *g, c
 // Z = [H | M] [W_self ; W_neigh] + b ;  Hnext = act(Z)      (M: [n, F_in] with leading dimension ldm)
 int launch_sage_gemm_fwd(int64_t n, const void *H, int64_t ldh, const void *M, int64_t ldm, int32_t F_in, const float *W_self,
                          const float *W_neigh, const float *bias, int32_t F_out, int32_t act, int32_t dtype,
-                         void *Hnext, int64_t ld_next, hipStream_t stream);
+                         void *Hnext, int64_t ld_next, hipStream_t stream, const void *Wt_bf16 = nullptr);
+// bf16 copy of [W_self ; W_neigh] with the output feature as the row: Wt[o][k], k < 2 F_in (row pitch 2 F_in)
+size_t sage_weights_bf16_bytes(int32_t F_in, int32_t F_out);
+int launch_sage_prepare_weights_bf16(const float *W_self, const float *W_neigh, int32_t F_in, int32_t F_out, void *Wt_out,
+                                     hipStream_t stream);
 
 // [dH_self | inv_deg * dM] = dZ [W_self^T | W_neigh^T],  dZ = dHnext (.) act'(Hnext)
 int launch_sage_gemm_bwd_data(int64_t n, const void *dHnext, const void *Hnext, int64_t ld_next,

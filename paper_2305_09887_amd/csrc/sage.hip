@@ -34,15 +34,12 @@ static BwdWorkspace plan_bwd(int64_t n, int32_t F_in, int32_t F_out, int32_t dty
     return w;
 }
 
-}  // namespace tma
-
-extern "C" int tma_sage_layer_fwd(int64_t n, const int32_t *rowptr, const int32_t *colidx, const float *inv_deg,
-                                  const void *H, int64_t ldh, int32_t F_in, const float *W_self,
-                                  const float *W_neigh, const float *bias, int32_t F_out, int32_t act, int32_t dtype,
-                                  void *M_out, int64_t ldm, void *Hnext_out, int64_t ld_next, tma_stream_t stream)
+// Wt_bf16 (may be NULL): the weights as tma_sage_prepare_weights_bf16 leaves them, for the bf16 aggregate-first form
+static int sage_layer_fwd(const char *fn, int64_t n, const int32_t *rowptr, const int32_t *colidx, const float *inv_deg,
+                          const void *H, int64_t ldh, int32_t F_in, const float *W_self, const float *W_neigh,
+                          const float *bias, int32_t F_out, int32_t act, int32_t dtype, void *M_out, int64_t ldm,
+                          void *Hnext_out, int64_t ld_next, const void *Wt_bf16, tma_stream_t stream)
 {
-    using namespace tma;
-    const char *fn = "tma_sage_layer_fwd";
     TMA_REQUIRE(n >= 0 && n <= INT32_MAX, TMA_ERR_INVALID_ARG, "%s: n outside [0, 2^31)", fn);
     TMA_REQUIRE(F_in >= 1 && F_out >= 1 && F_in <= (1 << 20) && F_out <= (1 << 20), TMA_ERR_BAD_SHAPE,
                 "%s: F_in=%d F_out=%d", fn, F_in, F_out);
@@ -57,7 +54,7 @@ extern "C" int tma_sage_layer_fwd(int64_t n, const int32_t *rowptr, const int32_
     if (aggregates_first(F_in, F_out, dtype)) {
         if (int rc = launch_spmm(n, rowptr, colidx, inv_deg, H, ldh, F_in, dtype, M_out, ldm, false, s)) return rc;
         return launch_sage_gemm_fwd(n, H, ldh, M_out, ldm, F_in, W_self, W_neigh, bias, F_out, act, dtype, Hnext_out,
-                                    ld_next, s);
+                                    ld_next, s, Wt_bf16);
     }
     // transform first: [Y_self | Y_neigh] = H [W_self | W_neigh] into the M_out buffer, then
     // Hnext = act(Y_self + Abar Y_neigh + b) by the gather kernel.  Needs ld_next >= the padded width.
@@ -72,6 +69,49 @@ extern "C" int tma_sage_layer_fwd(int64_t n, const int32_t *rowptr, const int32_
                                    bias, F_out, act == TMA_ACT_RELU, false, nullptr, s);
     return launch_spmm_combine(n, rowptr, colidx, inv_deg, Yn, Fp, F_out, dtype, Hnext_out, ld_next, false, Ys, Fp,
                                bias, F_out, act == TMA_ACT_RELU, false, nullptr, s);
+}
+
+}  // namespace tma
+
+extern "C" int tma_sage_layer_fwd(int64_t n, const int32_t *rowptr, const int32_t *colidx, const float *inv_deg,
+                                  const void *H, int64_t ldh, int32_t F_in, const float *W_self,
+                                  const float *W_neigh, const float *bias, int32_t F_out, int32_t act, int32_t dtype,
+                                  void *M_out, int64_t ldm, void *Hnext_out, int64_t ld_next, tma_stream_t stream)
+{
+    return tma::sage_layer_fwd("tma_sage_layer_fwd", n, rowptr, colidx, inv_deg, H, ldh, F_in, W_self, W_neigh, bias, F_out,
+                               act, dtype, M_out, ldm, Hnext_out, ld_next, nullptr, stream);
+}
+
+extern "C" size_t tma_sage_weights_bf16_bytes(int32_t F_in, int32_t F_out)
+{
+    if (F_in < 1 || F_out < 1) return 0;
+    return tma::sage_weights_bf16_bytes(F_in, F_out);
+}
+
+extern "C" int tma_sage_prepare_weights_bf16(const float *W_self, const float *W_neigh, int32_t F_in, int32_t F_out,
+                                             void *Wt_out, tma_stream_t stream)
+{
+    using namespace tma;
+    const char *fn = "tma_sage_prepare_weights_bf16";
+    TMA_REQUIRE(F_in >= 1 && F_out >= 1 && F_in <= (1 << 20) && F_out <= (1 << 20), TMA_ERR_BAD_SHAPE,
+                "%s: F_in=%d F_out=%d", fn, F_in, F_out);
+    TMA_REQUIRE(W_self && W_neigh && Wt_out && aligned(Wt_out, 16), TMA_ERR_INVALID_ARG,
+                "%s: NULL argument, or Wt_out not 16-byte aligned", fn);
+    return launch_sage_prepare_weights_bf16(W_self, W_neigh, F_in, F_out, Wt_out, as_stream(stream));
+}
+
+extern "C" int tma_sage_layer_fwd_prepared(int64_t n, const int32_t *rowptr, const int32_t *colidx, const float *inv_deg,
+                                           const void *H, int64_t ldh, int32_t F_in, const float *W_self,
+                                           const float *W_neigh, const float *bias, int32_t F_out, int32_t act,
+                                           int32_t dtype, void *M_out, int64_t ldm, void *Hnext_out, int64_t ld_next,
+                                           const void *Wt_bf16, tma_stream_t stream)
+{
+    const char *fn = "tma_sage_layer_fwd_prepared";
+    TMA_REQUIRE(dtype == TMA_BF16, TMA_ERR_UNSUPPORTED_DTYPE, "%s: prepared weights belong to bf16 storage (dtype %d)", fn,
+                dtype);
+    TMA_REQUIRE(Wt_bf16 && tma::aligned(Wt_bf16, 16), TMA_ERR_INVALID_ARG, "%s: Wt_bf16 is NULL or not 16-byte aligned", fn);
+    return tma::sage_layer_fwd(fn, n, rowptr, colidx, inv_deg, H, ldh, F_in, W_self, W_neigh, bias, F_out, act, dtype,
+                               M_out, ldm, Hnext_out, ld_next, Wt_bf16, stream);
 }
 
 extern "C" int tma_sage_layer_aggregates_first(int32_t F_in, int32_t F_out, int32_t dtype)

@@ -184,8 +184,21 @@ class LocalTrainer:
     def _layer_fwd(self, l, act, out):
         lin = self.layers[l][:self.n_lin]
         if self.encoder == "sage":
+            Wt = None
+            F_in, F_out = lin[0].shape
+            if (self.dtype == torch.bfloat16 and F_in % 4 == 0
+                    and B.tma_sage_layer_aggregates_first(F_in, F_out, B.TMA_BF16)):
+                # bf16 storage: the product takes its weight operand narrowed once per pass, not once per tile
+                # (prepared anew every pass: the optimizer, an averaging or a caller may have changed the weights)
+                held = getattr(self, "_Wt", None)
+                if held is None:
+                    held = self._Wt = {}
+                if l not in held:
+                    held[l] = torch.empty(B.tma_sage_weights_bf16_bytes(F_in, F_out) // 2, dtype=torch.int16,
+                                          device=lin[0].device)
+                Wt = B.tma_sage_prepare_weights_bf16(lin[0], lin[1], out=held[l], stream=self.stream)
             B.tma_sage_layer_fwd(self.rowptr, self.colidx, self.inv_deg, self.H[l], lin[0], lin[1], lin[2], act,
-                                 M_out=self.M[l], Hnext_out=out, stream=self.stream)
+                                 M_out=self.M[l], Hnext_out=out, stream=self.stream, Wt=Wt)
         elif self.encoder == "gcn":
             B.tma_gcn_layer_fwd(self.rowptr, self.colidx, self.s_norm, self.H[l], lin[0], lin[1], act,
                                 M_out=self.M[l], Hnext_out=out, stream=self.stream)

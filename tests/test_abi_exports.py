@@ -109,6 +109,25 @@ def test_device_count_forms_of_the_sampler_reject_bad_arguments_in_host_code(lib
     assert rc < 0 and b"pitch" in lib.tma_last_error()
 
 
+def test_prepared_weight_entry_points_reject_bad_arguments_in_host_code(lib):
+    lib.tma_last_error.restype = ctypes.c_char_p
+    i64, i32, sz = ctypes.c_int64, ctypes.c_int32, ctypes.c_size_t
+    fake = ctypes.c_void_p(4096)
+    lib.tma_sage_weights_bf16_bytes.restype = sz
+    assert lib.tma_sage_weights_bf16_bytes(i32(128), i32(256)) == 2 * 128 * 256 * 2
+    assert lib.tma_sage_weights_bf16_bytes(i32(3), i32(5)) == 256 and lib.tma_sage_weights_bf16_bytes(i32(0), i32(5)) == 0
+    assert lib.tma_sage_prepare_weights_bf16(fake, fake, i32(8), i32(8), None, None) < 0 and b"NULL" in lib.tma_last_error()
+    assert lib.tma_sage_prepare_weights_bf16(fake, fake, i32(0), i32(8), fake, None) < 0 and b"F_in=0" in lib.tma_last_error()
+
+    def fwd(dtype, wt):
+        return lib.tma_sage_layer_fwd_prepared(i64(10), fake, fake, fake, fake, i64(8), i32(8), fake, fake, fake, i32(8), i32(0),
+                                               i32(dtype), fake, i64(8), fake, i64(8), wt, None)
+
+    assert fwd(0, fake) < 0 and b"bf16 storage" in lib.tma_last_error()
+    assert fwd(1, None) < 0 and b"Wt_bf16" in lib.tma_last_error()
+    assert fwd(1, ctypes.c_void_p(4100)) < 0 and b"16-byte aligned" in lib.tma_last_error()
+
+
 def test_host_generator_reproduces_the_published_vector(lib):
     """tma_mix64 is host code: the library's generator against the published SplitMix64 outputs for seed 1234567
     (the same fixture that pins the oracle's), no GPU needed."""

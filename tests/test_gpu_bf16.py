@@ -143,6 +143,37 @@ def test_sage_layer_bf16(B, n_glob, m, F_in, F_out, act):
         close(host(g), w, name)
 
 
+@pytest.mark.parametrize("n_glob,m,F_in,F_out,act", [(9000, 40_000, 128, 256, "relu"), (4000, 20_000, 100, 256, "relu"),
+                                                     (5000, 20_000, 64, 48, "none"), (70_000, 300_000, 32, 320, "relu"),
+                                                     (3000, 12_000, 256, 47, "none"), (1200, 5000, 30, 10, "relu")])
+def test_sage_layer_bf16_with_prepared_weights(B, n_glob, m, F_in, F_out, act):
+    """tma_sage_prepare_weights_bf16 + tma_sage_layer_fwd_prepared: the weight operand narrowed once instead of in
+    every tile.  The prepared array against the definition (bf16 round-to-nearest-even of the transposed, stacked
+    weights, taken on the host), the layer against the oracle and bit for bit against tma_sage_layer_fwd; widths for
+    every tile shape, one layer that transforms first and one whose rows have no groups of four (both run as
+    without the array)."""
+    sub = _sub(n_glob, m, F_in + F_out)
+    rp, ci, inv = sub["rowptr"], sub["colidx"], sub["inv_deg"]
+    n = len(sub["l2g"])
+    H = synth.round_bf16(synth.features(n, F_in, seed=1))
+    (Ws, Wn, b), = synth.sage_params([F_in, F_out], seed=2)
+    a = oracle.ACT_RELU if act == "relu" else oracle.ACT_NONE
+    d_rp, d_ci, d_inv, d_H = dev(rp), dev(ci), dev(inv, torch.float32), dev_bf16(H)
+    d_Ws, d_Wn, d_b = dev(Ws), dev(Wn), dev(b)
+    Wt = B.tma_sage_prepare_weights_bf16(d_Ws, d_Wn)
+    assert Wt.numel() * 2 == B.tma_sage_weights_bf16_bytes(F_in, F_out) and Wt.numel() * 2 % 256 == 0
+    want_bits = synth.to_bf16_bits(np.ascontiguousarray(np.concatenate([Ws, Wn], axis=0).T.astype(np.float32)))
+    assert np.array_equal(Wt.cpu().numpy()[:2 * F_in * F_out].view(np.uint16), want_bits.ravel())
+    M_p, Hn_p = B.tma_sage_layer_fwd(d_rp, d_ci, d_inv, d_H, d_Ws, d_Wn, d_b, a, Wt=Wt)
+    M_g, Hn_g = B.tma_sage_layer_fwd(d_rp, d_ci, d_inv, d_H, d_Ws, d_Wn, d_b, a)
+    assert torch.equal(Hn_p.view(torch.int16), Hn_g.view(torch.int16))
+    M_o, _, Hn_o = oracle.sage_layer_fwd(rp, ci, H, Ws, Wn, b, a)
+    if B.tma_sage_layer_aggregates_first(F_in, F_out, B.TMA_BF16):
+        assert torch.equal(M_p.view(torch.int16), M_g.view(torch.int16))
+        close(host(M_p), M_o, "M")
+    close(host(Hn_p), Hn_o, "Hnext")
+
+
 def test_losses_and_gather_bf16(B):
     rng = np.random.default_rng(5)
     z = synth.round_bf16((3 * rng.standard_normal((3000, 47))).astype(np.float32))
