@@ -409,7 +409,8 @@ def test_sampling_one_step_ahead_on_a_second_stream_changes_nothing(B, encoder):
     torch.cuda.synchronize()
 
 
-def test_sampled_link_prediction_bf16_storage(B):
+@pytest.mark.parametrize("encoder", ["sage", "gcn"])
+def test_sampled_link_prediction_bf16_storage(B, encoder):
     """The sampled link-prediction step with bf16 feature / activation storage (bf16 MFMA products, fp32
     accumulation and parameters): one step against the oracle at the bf16 tolerance; structure bit for bit."""
     from oracle import model as omodel
@@ -418,28 +419,28 @@ def test_sampled_link_prediction_bf16_storage(B):
     rowptr, colidx = synth.chung_lu_graph(N, 12, 2.1, seed=1)
     X = synth.round_bf16(synth.features(N, dims[0], seed=2))
     rng = np.random.default_rng(7)
-    enc = [tuple(l) for l in synth.sage_params(dims, seed=5)]
+    enc = [tuple(l) if encoder == "sage" else (l[0], l[2]) for l in synth.sage_params(dims, seed=5)]
     dec = [(synth.glorot(32, 48, rng).astype(np.float32), np.array([0.25], np.float32)),
            (synth.glorot(48, 1, rng).astype(np.float32),)]
     sub = oracle.induced_subgraph(rowptr, colidx, oracle.partition(N, K, seed=4), 0)
     rp, ci = sub["rowptr"], sub["colidx"]
     Xo = X[sub["l2g"]]
     tr = SampledLinkTrainer(dev(rp), dev(ci), int(rp[-1]), dev_bf16(Xo).contiguous(), dims, dec_dims, fanouts, Bn,
-                            batch_seed=3, params=enc, decoder_params=dec)
+                            batch_seed=3, params=enc, decoder_params=dec, encoder=encoder)
     loss_g = tr.step(0.1).item()
     e_o = [tuple(np.asarray(t, dtype=np.float64) for t in l) for l in enc]
     d_o = [tuple(np.asarray(t, dtype=np.float64) for t in l) for l in dec]
     batch = oracle.edge_batch(rp, ci, 3, 0, Bn)
     t = {}
     loss_o, ge, gd, z, (rps, cis, inputs, seeds) = omodel.sampled_link_loss_and_grads(
-        rp, ci, Xo, batch, e_o, d_o, fanouts, 3, 0, decisions="bf16", trace=t)    # decisions of the as-stored pass
+        rp, ci, Xo, batch, e_o, d_o, fanouts, 3, 0, decisions="bf16", trace=t, encoder=encoder)    # decisions of the as-stored pass
     assert tr.count == [len(inputs), len(rps[0]) - 1, len(seeds)]
     assert np.array_equal(tr.nodes[0].cpu().numpy()[:len(inputs)], inputs)
     kw = decisions.STORED
     D = decisions.differing(t["pre"], [host(tr.H[1]), None], "encoder", **kw)
     Dd = decisions.differing(t["dec_pre"], [host(tr.E[1]), None], "decoder", **kw)
     db, q_top = decisions.decoder_bounds(d_o, t["dsaved"], t["dec_ups"], Dd, t["R"], t["batch_pos"])
-    eb = decisions.encoder_bounds("sage", rps, cis, e_o, t["saved"], t["ups"], D, q_top)
+    eb = decisions.encoder_bounds(encoder, rps, cis, e_o, t["saved"], t["ups"], D, q_top)
     print(f"differing decisions: encoder {int(D[0].sum())} of {D[0].size}, decoder {int(Dd[0].sum())} of {Dd[0].size}")
     assert abs(loss_g - loss_o) <= 2e-2 * abs(loss_o)
     close(host(tr.Zd[2]).ravel(), z, 2e-2, "logits")
