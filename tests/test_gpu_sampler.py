@@ -334,7 +334,7 @@ def test_sampled_link_prediction_training_steps(B, fanouts, Bn, norm_act, encode
             assert np.array_equal(tr.blk_rowptr[l].cpu().numpy()[:n_dst + 1], rps[l])
             assert np.array_equal(tr.blk_col[l].cpu().numpy()[:rps[l][-1]], cis[l])
         assert tr.count[0] == len(inputs) and np.array_equal(tr.nodes[0].cpu().numpy()[:len(inputs)], inputs)
-        D = decisions.differing(t["pre"], [host(tr.H[1]), None], f"step {step} encoder")
+        D = decisions.differing(t["pre"], [host(tr.H[1][:tr.count[1]]), None], f"step {step} encoder")
         Dd = decisions.differing(t["dec_pre"], [host(tr.E[1]), None], f"step {step} decoder")
         db, q_top = decisions.decoder_bounds(d_o, t["dsaved"], t["dec_ups"], Dd, t["R"], t["batch_pos"])
         eb = decisions.encoder_bounds(encoder, rps, cis, e_o, t["saved"], t["ups"], D, q_top)
@@ -437,7 +437,7 @@ def test_sampled_link_prediction_bf16_storage(B, encoder):
     assert tr.count == [len(inputs), len(rps[0]) - 1, len(seeds)]
     assert np.array_equal(tr.nodes[0].cpu().numpy()[:len(inputs)], inputs)
     kw = decisions.STORED
-    D = decisions.differing(t["pre"], [host(tr.H[1]), None], "encoder", **kw)
+    D = decisions.differing(t["pre"], [host(tr.H[1][:tr.count[1]]), None], "encoder", **kw)
     Dd = decisions.differing(t["dec_pre"], [host(tr.E[1]), None], "decoder", **kw)
     db, q_top = decisions.decoder_bounds(d_o, t["dsaved"], t["dec_ups"], Dd, t["R"], t["batch_pos"])
     eb = decisions.encoder_bounds(encoder, rps, cis, e_o, t["saved"], t["ups"], D, q_top)
